@@ -1,0 +1,264 @@
+"""Float64 CPU oracle for Beagle's block-masked cross-attention.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, dense, obviously-correct
+definition that the GPU path is compared against.  It is imported by the
+tests, by the smoke check and by the CPU-baseline leg of the benchmark, and
+by nothing else; it shares no code with the HIP path and never calls it.
+
+What it computes (paper section 4.1, Eq. 2, with the early-stage mask of
+section 4.2):
+
+    Q = Xq Wq,  K = Xkv Wk,  V = Xkv Wv            per-head column slices
+    s = softmax_j( <Q_i, K_j> / sqrt(d_h) )        over the VISIBLE keys only
+    o_i = sum_j Mask_ij s_ij V_j
+    y_i = [o^(1); ...; o^(H)] Wo
+
+Everything is float64 NumPy on an explicit dense boolean mask.  No tiling, no
+online softmax, no recomputation: the backward pass is the chain rule written
+on the stored dense probability matrix.
+
+Readings of the paper taken here (the paper is silent or ambiguous):
+  * The mask is applied BEFORE normalisation (masked scores are -inf), so that
+    visible weights sum to one and masked weights are exactly zero.  Eq. 2
+    read literally multiplies the mask after the softmax.
+  * One mask for every head and batch entry.
+  * Windows tile the whole sequence: starts are eps + w*k for every integer w
+    whose window touches the sequence, including the partial leading window
+    when eps > 0.
+  * A query that sees no key gets a zero output row, LSE = -inf, and
+    contributes no gradient.  PARITY UNPINNED by the paper: this is a
+    convention (the paper never discusses the empty softmax).
+  * GQA: query head h reads KV head h // (H // G).
+  * Weights are stored [in, out]; scale defaults to 1/sqrt(d_h) (Eq. 2).
+  * LSE is the natural-log log-sum-exp of the scaled visible scores.
+
+Indices are 0-based here; the paper is 1-based.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# Mask (section 4.1 "diagonal scores are also masked"; section 4.2 windows)
+# --------------------------------------------------------------------------
+def _window_starts(seq_q: int, k: int, eps: int):
+    """Window starts eps + w*k (section 4.2) for every window that overlaps
+    queries 0 .. seq_q-1, the partial leading one (start eps-k < 0) included."""
+    if k < 1 or not (0 <= eps < k):
+        raise ValueError("need k >= 1 and 0 <= eps < k")
+    n = eps - k if eps > 0 else 0
+    starts = []
+    while n < seq_q:
+        starts.append(n)
+        n += k
+    return starts
+
+
+def dense_mask_loops(seq_q: int, seq_kv: int, k: int, eps: int = 0) -> np.ndarray:
+    """Boolean [seq_q, seq_kv]; True where query p may attend key j.
+
+    Element-by-element from the two prose rules (small sizes only):
+      (1) strict causality: key j is hidden from query p when j >= p
+          (section 4.1: the diagonal is masked too);
+      (2) a window that starts at n (0-based) holds queries n .. n+k-1 and
+          hides keys n .. n+k-1 from each of them (section 4.2).
+    """
+    m = np.ones((seq_q, seq_kv), dtype=bool)
+    for p in range(seq_q):                       # rule (1)
+        for j in range(seq_kv):
+            if j >= p:
+                m[p, j] = False
+    for n in _window_starts(seq_q, k, eps):      # rule (2)
+        for p in range(max(n, 0), min(n + k, seq_q)):
+            for j in range(max(n, 0), min(n + k, seq_kv)):
+                m[p, j] = False
+    return m
+
+
+def dense_mask(seq_q: int, seq_kv: int, k: int, eps: int = 0) -> np.ndarray:
+    """Same mask as dense_mask_loops, with each rule applied as one array
+    operation (rule 1: strictly-lower triangle; rule 2: one square block per
+    window) so that full-size masks are affordable."""
+    m = np.tri(seq_q, seq_kv, -1, dtype=bool)    # rule (1): j < p
+    for n in _window_starts(seq_q, k, eps):      # rule (2)
+        m[max(n, 0):min(n + k, seq_q), max(n, 0):min(n + k, seq_kv)] = False
+    return m
+
+
+def visible_counts(mask: np.ndarray) -> np.ndarray:
+    """Number of visible keys per query row (int64 [seq_q])."""
+    return mask.sum(axis=1).astype(np.int64)
+
+
+# --------------------------------------------------------------------------
+# Forward (Eq. 2)
+# --------------------------------------------------------------------------
+def _check_heads(H: int, G: int) -> int:
+    if H < 1 or G < 1 or H % G:
+        raise ValueError("n_kv_heads must divide n_q_heads")
+    return H // G
+
+
+def masked_softmax(scores: np.ndarray, mask: np.ndarray):
+    """Row-wise softmax over visible entries.  Returns (P, LSE).
+
+    Masked entries of P are exactly 0.0.  A row with no visible entry is all
+    zero with LSE = -inf.
+    """
+    s = np.where(mask, scores, -np.inf)
+    mx = s.max(axis=-1, keepdims=True)
+    mx_safe = np.where(np.isfinite(mx), mx, 0.0)
+    e = np.where(mask, np.exp(s - mx_safe), 0.0)
+    l = e.sum(axis=-1, keepdims=True)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        P = np.where(l > 0, e / np.where(l > 0, l, 1.0), 0.0)
+        lse = np.where(l > 0, mx_safe + np.log(np.where(l > 0, l, 1.0)), -np.inf)
+    return P, lse[..., 0]
+
+
+def xattn_forward(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
+                  scale=None, keep_probs=False):
+    """Forward pass of Eq. 2 under an explicit dense mask.
+
+    xq  [B, Sq, D]      draft-side query states e(t_i)
+    xkv [B, L, D]       target hidden states h_j
+    wq  [D, H*d]  wk, wv [D, G*d]  wo [H*d, D]
+    mask bool [Sq, L]   shared by batch and heads
+    Returns dict: y [B,Sq,D], lse [B,H,Sq], q [B,Sq,H,d], k,v [B,L,G,d],
+                  o [B,Sq,H,d] and, if keep_probs, p [B,H,Sq,L].
+    """
+    xq, xkv = np.asarray(xq, F64), np.asarray(xkv, F64)
+    wq, wk, wv, wo = (np.asarray(w, F64) for w in (wq, wk, wv, wo))
+    H, G = n_q_heads, n_kv_heads
+    rep = _check_heads(H, G)
+    B, Sq, D = xq.shape
+    L = xkv.shape[1]
+    d = wq.shape[1] // H
+    if scale is None or scale == 0:
+        scale = 1.0 / math.sqrt(d)
+    mask = np.asarray(mask, bool)
+    assert mask.shape == (Sq, L)
+
+    q = (xq @ wq).reshape(B, Sq, H, d)
+    k = (xkv @ wk).reshape(B, L, G, d)
+    v = (xkv @ wv).reshape(B, L, G, d)
+    o = np.zeros((B, Sq, H, d), F64)
+    lse = np.zeros((B, H, Sq), F64)
+    probs = np.zeros((B, H, Sq, L), F64) if keep_probs else None
+    for b in range(B):
+        for h in range(H):
+            g = h // rep
+            s = (q[b, :, h, :] @ k[b, :, g, :].T) * scale
+            P, lse[b, h] = masked_softmax(s, mask)
+            o[b, :, h, :] = P @ v[b, :, g, :]
+            if keep_probs:
+                probs[b, h] = P
+    y = o.reshape(B, Sq, H * d) @ wo
+    out = dict(y=y, lse=lse, q=q, k=k, v=v, o=o, scale=scale)
+    if keep_probs:
+        out["p"] = probs
+    return out
+
+
+# --------------------------------------------------------------------------
+# Backward (chain rule of Eq. 2 on the dense probabilities)
+# --------------------------------------------------------------------------
+def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
+                   scale=None):
+    """Gradients of sum(dy * y) with respect to every input of xattn_forward.
+
+    Returns dict with dxq, dxkv, dwq, dwk, dwv, dwo and the intermediates
+    dq [B,Sq,H,d], dk, dv [B,L,G,d], do [B,Sq,H,d], delta [B,H,Sq].
+    """
+    dy = np.asarray(dy, F64)
+    xq, xkv = np.asarray(xq, F64), np.asarray(xkv, F64)
+    wq, wk, wv, wo = (np.asarray(w, F64) for w in (wq, wk, wv, wo))
+    H, G = n_q_heads, n_kv_heads
+    rep = _check_heads(H, G)
+    fw = xattn_forward(xq, xkv, wq, wk, wv, wo, n_q_heads=H, n_kv_heads=G,
+                       mask=mask, scale=scale, keep_probs=False)
+    q, k, v, o, scale = fw["q"], fw["k"], fw["v"], fw["o"], fw["scale"]
+    B, Sq, D = xq.shape
+    L = xkv.shape[1]
+    d = q.shape[-1]
+    mask = np.asarray(mask, bool)
+
+    o2 = o.reshape(B * Sq, H * d)
+    dy2 = dy.reshape(B * Sq, D)
+    dwo = o2.T @ dy2
+    do = (dy2 @ wo.T).reshape(B, Sq, H, d)
+
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    delta = np.zeros((B, H, Sq), F64)
+    for b in range(B):
+        for h in range(H):
+            g = h // rep
+            s = (q[b, :, h, :] @ k[b, :, g, :].T) * scale
+            P, _ = masked_softmax(s, mask)
+            dO = do[b, :, h, :]
+            dv[b, :, g, :] += P.T @ dO
+            dP = dO @ v[b, :, g, :].T
+            # softmax Jacobian: dS = P * (dP - sum_j P dP); the row sum equals
+            # sum_c dO_c O_c because O = P V.
+            dlt = (dO * o[b, :, h, :]).sum(axis=-1)
+            delta[b, h] = dlt
+            dS = P * (dP - dlt[:, None])
+            dq[b, :, h, :] = (dS @ k[b, :, g, :]) * scale
+            dk[b, :, g, :] += (dS.T @ q[b, :, h, :]) * scale
+
+    dq2 = dq.reshape(B * Sq, H * d)
+    dk2 = dk.reshape(B * L, G * d)
+    dv2 = dv.reshape(B * L, G * d)
+    xq2 = xq.reshape(B * Sq, D)
+    xkv2 = xkv.reshape(B * L, D)
+    return dict(
+        dxq=(dq2 @ wq.T).reshape(B, Sq, D),
+        dxkv=(dk2 @ wk.T + dv2 @ wv.T).reshape(B, L, D),
+        dwq=xq2.T @ dq2, dwk=xkv2.T @ dk2, dwv=xkv2.T @ dv2, dwo=dwo,
+        dq=dq, dk=dk, dv=dv, do=do, delta=delta,
+        y=fw["y"], lse=fw["lse"], o=o, q=q, k=k, v=v)
+
+
+# --------------------------------------------------------------------------
+# Decode-time draft step (section 4.1, KV-cache paragraph)
+# --------------------------------------------------------------------------
+def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None):
+    """M draft queries against a cache of L already-projected K/V rows.
+
+    x [M, D]; k_cache, v_cache [L, G, d]; every query sees every cache row
+    (drafted states are not concatenated).  Returns y [M, D], lse [H, M].
+    """
+    x = np.asarray(x, F64)
+    kc, vc = np.asarray(k_cache, F64), np.asarray(v_cache, F64)
+    wq, wo = np.asarray(wq, F64), np.asarray(wo, F64)
+    H, G = n_q_heads, n_kv_heads
+    rep = _check_heads(H, G)
+    M, D = x.shape
+    L, _, d = kc.shape
+    if scale is None or scale == 0:
+        scale = 1.0 / math.sqrt(d)
+    q = (x @ wq).reshape(M, H, d)
+    o = np.zeros((M, H, d), F64)
+    lse = np.zeros((H, M), F64)
+    allvis = np.ones((M, L), bool)
+    for h in range(H):
+        g = h // rep
+        s = (q[:, h, :] @ kc[:, g, :].T) * scale
+        P, lse[h] = masked_softmax(s, allvis)
+        o[:, h, :] = P @ vc[:, g, :]
+    y = o.reshape(M, H * d) @ wo
+    return dict(y=y, lse=lse, q=q, o=o)
+
+
+# --------------------------------------------------------------------------
+# Accounting helpers used by the tests and the benchmark's CPU leg
+# --------------------------------------------------------------------------
+def visible_pairs(mask: np.ndarray) -> int:
+    return int(np.asarray(mask, bool).sum())
