@@ -1,0 +1,178 @@
+/*
+ * beagle_xattn.h -- C ABI of the block-masked cross-attention of Beagle's
+ * single-layer draft decoder (paper section 4.1, Eq. 2; training mask of
+ * section 4.2; KV-cache decode protocol at the end of section 4.1), for
+ * AMD MI355X (gfx950).
+ *
+ * Notation (0-based; the paper is 1-based)
+ *   B batch, S query length, L key length, D model width ("hidden"),
+ *   H query heads, G key/value heads (G divides H), d head width,
+ *   k window ("block") size, eps window offset in [0, k).
+ *   ws(p) = max(0, eps + k * floor((p - eps) / k)) is the start of the window
+ *   that holds query p.  Query p may attend key j  iff  j < ws(p).
+ *   This is the strict rule "key j is hidden when j >= i" of section 4.1
+ *   together with the early-stage rule of section 4.2 that a window hides its
+ *   own keys from its own queries; k = 1 is the strict-causal cross mask.
+ *   The mask is never materialised on the device (constant space).
+ *
+ * General conventions
+ *   - Every tensor argument is a DEVICE pointer to a contiguous row-major
+ *     array (last index fastest), 16-byte aligned, allocated and owned by the
+ *     caller.  The library neither allocates, frees nor keeps them.  The two
+ *     exceptions are the descriptor (host memory) and the outputs of the
+ *     beagle_xattn_mask_* helpers (host memory).
+ *   - Element type of activations and weights is desc->io_dtype (float or
+ *     bfloat16); sums are always accumulated in float.  lse is always float.
+ *   - Weights are stored [in, out] so that Q = Xq * Wq; head h of a projected
+ *     tensor occupies columns [h*d, (h+1)*d).  Query head h reads KV head
+ *     h / (H / G).
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  Calls return without synchronising.
+ *   - Arguments are validated on the host before anything is enqueued: a
+ *     status other than BEAGLE_OK / BEAGLE_ERR_HIP means nothing ran.
+ *     Nothing throws across this boundary.
+ *   - A query with no visible key (ws(p) == 0) gets a zero output row, lse =
+ *     -infinity and contributes no gradient.
+ *   - Results are run-to-run bitwise reproducible (no floating-point atomics).
+ *
+ * Supported shapes
+ *   BEAGLE_F32 : any d <= 128 with d % 4 == 0; D, H*d, G*d multiples of 4.
+ *   BEAGLE_BF16: d == 128; D a multiple of 64.
+ *   B, S, L >= 1 arbitrary (ragged tiles are handled); anything else returns
+ *   BEAGLE_ERR_UNSUPPORTED -- there is no fallback path.
+ */
+#ifndef BEAGLE_XATTN_H
+#define BEAGLE_XATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BEAGLE_OK = 0,
+  BEAGLE_ERR_NULL = 1,        /* a required pointer is NULL                     */
+  BEAGLE_ERR_SHAPE = 2,       /* a size is non-positive or inconsistent         */
+  BEAGLE_ERR_UNSUPPORTED = 3, /* valid problem that this build has no kernel for*/
+  BEAGLE_ERR_WORKSPACE = 4,   /* workspace missing or smaller than required     */
+  BEAGLE_ERR_ALIGN = 5,       /* a device pointer is not 16-byte aligned        */
+  BEAGLE_ERR_HIP = 6          /* the HIP runtime reported an error at launch    */
+} beagle_status;
+
+typedef enum { BEAGLE_F32 = 0, BEAGLE_BF16 = 1 } beagle_dtype;
+
+enum {
+  BEAGLE_FLAG_NEED_DXKV = 1u << 0, /* bwd also produces dxkv                    */
+  BEAGLE_FLAG_WGRAD_F32 = 1u << 1  /* bwd writes dwq/dwk/dwv/dwo as float even
+                                      when io_dtype is bf16                     */
+};
+
+enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2 };
+
+typedef struct {
+  int32_t struct_size;   /* sizeof(beagle_xattn_desc); checked                  */
+  int32_t batch;         /* B                                                   */
+  int32_t seq_q;         /* S  (draft step: M, the number of draft queries)     */
+  int32_t seq_kv;        /* L  (training: usually == S)                         */
+  int32_t hidden;        /* D                                                   */
+  int32_t n_q_heads;     /* H                                                   */
+  int32_t n_kv_heads;    /* G, divides H                                        */
+  int32_t head_dim;      /* d                                                   */
+  int32_t block_size;    /* k >= 1 (section 4.2 window size)                    */
+  int32_t block_offset;  /* eps in [0, k) (section 4.2 random offset)           */
+  int32_t io_dtype;      /* beagle_dtype                                        */
+  float   softmax_scale; /* 0 selects 1/sqrt(d) as in Eq. 2                     */
+  uint32_t flags;        /* BEAGLE_FLAG_*; unknown bits are rejected            */
+} beagle_xattn_desc;
+
+/* Bytes of device workspace that the given entry point needs for `desc`
+ * (`which` is BEAGLE_WS_*).  Returns 0 for an invalid descriptor. */
+size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which);
+
+/*
+ * Forward pass (Eq. 2): Q = Xq Wq, K = Xkv Wk, V = Xkv Wv, masked softmax over
+ * the visible keys with scale 1/sqrt(d), O = P V, Y = O Wo.
+ *   in : xq [B,S,D], xkv [B,L,D], wq [D,H*d], wk [D,G*d], wv [D,G*d], wo [H*d,D]
+ *   out: y [B,S,D]; lse [B,H,S] float, natural-log log-sum-exp of the scaled
+ *        visible scores; q_save [B,S,H,d], k_save [B,L,G,d], v_save [B,L,G,d],
+ *        o_save [B,S,H,d] in io_dtype -- the tensors the backward pass reuses
+ *        (k_save / v_save are also exactly the KV-cache rows of the decode
+ *        step).  All eight outputs are required.
+ */
+beagle_status beagle_xattn_fwd(const beagle_xattn_desc* desc,
+    const void* xq, const void* xkv, const void* wq, const void* wk,
+    const void* wv, const void* wo,
+    void* y, float* lse, void* q_save, void* k_save, void* v_save, void* o_save,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward pass of the same operation (used by the training-time simulation
+ * of section 4.2), by recomputing the probabilities from q_save, k_save, lse:
+ *   dO = dY Wo^T, dWo = O^T dY, delta = rowsum(dO * O), P = exp(s - lse),
+ *   dV = P^T dO, dS = P * (dO V^T - delta), dQ = dS K * scale,
+ *   dK = dS^T Q * scale (summed over the H/G query heads of a KV head),
+ *   dXq = dQ Wq^T, dWq = Xq^T dQ, dWk = Xkv^T dK, dWv = Xkv^T dV,
+ *   dXkv = dK Wk^T + dV Wv^T (only with BEAGLE_FLAG_NEED_DXKV).
+ *   in : dy [B,S,D] and the forward's inputs and saved tensors
+ *   out: dxq [B,S,D]; dxkv [B,L,D] (NULL allowed unless NEED_DXKV is set);
+ *        dwq [D,H*d], dwk, dwv [D,G*d], dwo [H*d,D] in io_dtype, or float with
+ *        BEAGLE_FLAG_WGRAD_F32.  Outputs are overwritten, not accumulated.
+ */
+beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
+    const void* dy, const void* xq, const void* xkv, const void* wq,
+    const void* wk, const void* wv, const void* wo,
+    const void* q_save, const void* k_save, const void* v_save,
+    const void* o_save, const float* lse,
+    void* dxq, void* dxkv, void* dwq, void* dwk, void* dwv, void* dwo,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Decode-time draft step (section 4.1, KV-cache paragraph): M = desc->seq_q
+ * draft query states attend to a cache of L = desc->seq_kv already projected
+ * key/value rows; every query sees every cache row (drafted states are not
+ * concatenated), so block_size / block_offset are ignored.  desc->batch must
+ * be 1.
+ *   in : x_draft [M,D], k_cache [L,G,d], v_cache [L,G,d], wq [D,H*d], wo [H*d,D]
+ *   out: y [M,D] = softmax(q K^T * scale) V Wo with q = x_draft Wq;
+ *        lse [H,M] float.
+ */
+beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache,
+    const void* wq, const void* wo, void* y, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- mask / index inspection (HOST memory, integers only, no GPU needed) --
+ * These run the same index code that the kernels use, so that it can be
+ * compared bit for bit with a mask built independently from the paper. */
+
+/* ws_out[p] = min(ws(p), L) for p in [0,S): the number of keys query p sees. */
+beagle_status beagle_xattn_mask_row_limit(const beagle_xattn_desc* desc, int32_t* ws_out);
+/* mask_out[p*L + j] = 1 if query p may attend key j, else 0. */
+beagle_status beagle_xattn_mask_dense(const beagle_xattn_desc* desc, uint8_t* mask_out);
+/* Class of every (query tile, key tile) pair for tiles of tq x tk:
+ * cls_out[a * ceil(L/tk) + c] = 0 skip (nothing visible), 1 partial (needs the
+ * per-element predicate), 2 full (everything visible).  Section 4.2's block
+ * structure is what makes whole-tile skipping possible. */
+beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, int32_t tk, uint8_t* cls_out);
+
+/* ---- per-kernel timing (measurement aid) ---------------------------------
+ * Between profile_begin and profile_end every kernel launch of the three
+ * entry points is bracketed by HIP events on the launch stream.  profile_end
+ * synchronises those events and returns the number of distinct kernel names;
+ * profile_get then yields, for index i, the name (static string), the launch
+ * count and the summed duration in milliseconds.  Not thread-safe; capacity
+ * is 4096 launches per begin/end pair (further launches are not timed). */
+beagle_status beagle_xattn_profile_begin(void);
+int32_t       beagle_xattn_profile_end(void);
+beagle_status beagle_xattn_profile_get(int32_t i, const char** name, int32_t* launches, double* total_ms);
+
+const char* beagle_xattn_status_string(beagle_status s);
+/* "major.minor" of this ABI. */
+const char* beagle_xattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BEAGLE_XATTN_H */

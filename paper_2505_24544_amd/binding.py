@@ -1,0 +1,200 @@
+"""ctypes binding over libbeagle_xattn.so: argument marshalling only.
+
+Function names mirror include/beagle_xattn.h.  Tensor arguments may be torch
+tensors (their data_ptr() is passed; they must be contiguous) or raw integer
+device addresses.  PyTorch is used for device allocations and streams only;
+every step of the computation runs inside the library's kernels.  There is no
+fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbeagle_xattn.so")
+
+BEAGLE_OK = 0
+BEAGLE_F32, BEAGLE_BF16 = 0, 1
+BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32 = 1, 2
+BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT = 0, 1, 2
+STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
+                4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
+
+EXPORTS = (
+    "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
+    "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
+    "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
+    "beagle_xattn_status_string", "beagle_xattn_version",
+)
+
+
+class BeagleError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, STATUS_NAMES.get(status, "?"), status))
+
+
+class beagle_xattn_desc(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_int32), ("batch", C.c_int32), ("seq_q", C.c_int32), ("seq_kv", C.c_int32),
+        ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("block_size", C.c_int32), ("block_offset", C.c_int32), ("io_dtype", C.c_int32),
+        ("softmax_scale", C.c_float), ("flags", C.c_uint32),
+    ]
+
+
+def make_desc(*, batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads, head_dim, block_size=1,
+              block_offset=0, io_dtype=BEAGLE_BF16, softmax_scale=0.0, flags=0) -> beagle_xattn_desc:
+    return beagle_xattn_desc(C.sizeof(beagle_xattn_desc), batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads,
+                             head_dim, block_size, block_offset, io_dtype, softmax_scale, flags)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Open the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s not found: build it with `python -m paper_2505_24544_amd.build` "
+                           "(there is no fallback path)" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, dp = C.c_void_p, C.POINTER(beagle_xattn_desc)
+    L.beagle_xattn_workspace_bytes.restype = C.c_size_t
+    L.beagle_xattn_workspace_bytes.argtypes = [dp, C.c_int]
+    L.beagle_xattn_fwd.restype = C.c_int
+    L.beagle_xattn_fwd.argtypes = [dp] + [vp] * 12 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_bwd.restype = C.c_int
+    L.beagle_xattn_bwd.argtypes = [dp] + [vp] * 18 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_draft_step.restype = C.c_int
+    L.beagle_xattn_draft_step.argtypes = [dp] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_mask_row_limit.restype = C.c_int
+    L.beagle_xattn_mask_row_limit.argtypes = [dp, vp]
+    L.beagle_xattn_mask_dense.restype = C.c_int
+    L.beagle_xattn_mask_dense.argtypes = [dp, vp]
+    L.beagle_xattn_tile_map.restype = C.c_int
+    L.beagle_xattn_tile_map.argtypes = [dp, C.c_int32, C.c_int32, vp]
+    L.beagle_xattn_profile_begin.restype = C.c_int
+    L.beagle_xattn_profile_begin.argtypes = []
+    L.beagle_xattn_profile_end.restype = C.c_int32
+    L.beagle_xattn_profile_end.argtypes = []
+    L.beagle_xattn_profile_get.restype = C.c_int
+    L.beagle_xattn_profile_get.argtypes = [C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int32),
+                                           C.POINTER(C.c_double)]
+    L.beagle_xattn_status_string.restype = C.c_char_p
+    L.beagle_xattn_status_string.argtypes = [C.c_int]
+    L.beagle_xattn_version.restype = C.c_char_p
+    L.beagle_xattn_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor arguments must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _nbytes(ws):
+    if ws is None:
+        return 0
+    return ws.numel() * ws.element_size()
+
+
+def _check(st, where, check):
+    if check and st != BEAGLE_OK:
+        raise BeagleError(st, where)
+    return st
+
+
+def beagle_xattn_workspace_bytes(desc, which) -> int:
+    return int(lib().beagle_xattn_workspace_bytes(C.byref(desc), which))
+
+
+def beagle_xattn_fwd(desc, xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save,
+                     workspace=None, stream=None, *, workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_fwd(
+        C.byref(desc), *(_ptr(t) for t in (xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save)),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_fwd", check)
+
+
+def beagle_xattn_bwd(desc, dy, xq, xkv, wq, wk, wv, wo, q_save, k_save, v_save, o_save, lse,
+                     dxq, dxkv, dwq, dwk, dwv, dwo, workspace, stream=None, *, workspace_bytes=None,
+                     check=True) -> int:
+    st = lib().beagle_xattn_bwd(
+        C.byref(desc), *(_ptr(t) for t in (dy, xq, xkv, wq, wk, wv, wo, q_save, k_save, v_save, o_save, lse,
+                                           dxq, dxkv, dwq, dwk, dwv, dwo)),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_bwd", check)
+
+
+def beagle_xattn_draft_step(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, workspace, stream=None, *,
+                            workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_draft_step(
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo, y, lse)),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_draft_step", check)
+
+
+def beagle_xattn_mask_row_limit(desc) -> np.ndarray:
+    out = np.empty(max(desc.seq_q, 0), np.int32)
+    _check(lib().beagle_xattn_mask_row_limit(C.byref(desc), out.ctypes.data), "beagle_xattn_mask_row_limit", True)
+    return out
+
+
+def beagle_xattn_mask_dense(desc) -> np.ndarray:
+    out = np.empty((max(desc.seq_q, 0), max(desc.seq_kv, 0)), np.uint8)
+    _check(lib().beagle_xattn_mask_dense(C.byref(desc), out.ctypes.data), "beagle_xattn_mask_dense", True)
+    return out
+
+
+def beagle_xattn_tile_map(desc, tq, tk) -> np.ndarray:
+    if tq < 1 or tk < 1:
+        raise BeagleError(2, "beagle_xattn_tile_map")
+    nq, nk = -(-desc.seq_q // tq), -(-desc.seq_kv // tk)
+    out = np.empty((max(nq, 0), max(nk, 0)), np.uint8)
+    _check(lib().beagle_xattn_tile_map(C.byref(desc), tq, tk, out.ctypes.data), "beagle_xattn_tile_map", True)
+    return out
+
+
+def beagle_xattn_profile_begin() -> None:
+    _check(lib().beagle_xattn_profile_begin(), "beagle_xattn_profile_begin", True)
+
+
+def beagle_xattn_profile_end() -> dict:
+    """Returns {kernel name: (launches, total_ms)} for the launches since begin."""
+    n = lib().beagle_xattn_profile_end()
+    if n < 0:
+        raise BeagleError(6, "beagle_xattn_profile_end")
+    out = {}
+    for i in range(n):
+        name, cnt, ms = C.c_char_p(), C.c_int32(), C.c_double()
+        _check(lib().beagle_xattn_profile_get(i, C.byref(name), C.byref(cnt), C.byref(ms)),
+               "beagle_xattn_profile_get", True)
+        out[name.value.decode()] = (cnt.value, ms.value)
+    return out
+
+
+def beagle_xattn_status_string(status: int) -> str:
+    return lib().beagle_xattn_status_string(status).decode()
+
+
+def beagle_xattn_version() -> str:
+    return lib().beagle_xattn_version().decode()

@@ -1,0 +1,374 @@
+// C-ABI entry points: argument validation, workspace carving, and the order in
+// which the kernels of the hot path are enqueued.  No arithmetic lives here.
+#include "../../include/beagle_xattn.h"
+#include "common.h"
+
+#include <math.h>
+#include <string.h>
+
+using namespace beagle;
+
+namespace {
+
+constexpr uint32_t KNOWN_FLAGS = BEAGLE_FLAG_NEED_DXKV | BEAGLE_FLAG_WGRAD_F32;
+constexpr size_t WS_ALIGN = 256;
+
+size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+struct Dims {
+  int64_t B, S, L, D, H, G, d, HD, GD;
+  size_t esz;
+  bool bf16;
+  float scale;
+  MaskParams mask;
+};
+
+beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
+  if (!c) return BEAGLE_ERR_NULL;
+  if (c->struct_size != (int32_t)sizeof(beagle_xattn_desc)) return BEAGLE_ERR_SHAPE;
+  if (c->batch < 1 || c->seq_q < 1 || c->seq_kv < 1 || c->hidden < 1 || c->n_q_heads < 1 ||
+      c->n_kv_heads < 1 || c->head_dim < 1)
+    return BEAGLE_ERR_SHAPE;
+  if (c->n_q_heads % c->n_kv_heads) return BEAGLE_ERR_SHAPE;
+  if (!draft && (c->block_size < 1 || c->block_offset < 0 || c->block_offset >= c->block_size))
+    return BEAGLE_ERR_SHAPE;
+  if (draft && c->batch != 1) return BEAGLE_ERR_SHAPE;
+  if (c->flags & ~KNOWN_FLAGS) return BEAGLE_ERR_UNSUPPORTED;
+  if (c->io_dtype != BEAGLE_F32 && c->io_dtype != BEAGLE_BF16) return BEAGLE_ERR_UNSUPPORTED;
+  if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BEAGLE_ERR_SHAPE;
+  Dims d;
+  d.B = c->batch; d.S = c->seq_q; d.L = c->seq_kv; d.D = c->hidden;
+  d.H = c->n_q_heads; d.G = c->n_kv_heads; d.d = c->head_dim;
+  d.HD = d.H * d.d; d.GD = d.G * d.d;
+  d.bf16 = c->io_dtype == BEAGLE_BF16;
+  d.esz = d.bf16 ? 2 : 4;
+  // grid dimensions and 32-bit row counts used by the kernels
+  if (d.B > 65535 || d.H > 65535) return BEAGLE_ERR_UNSUPPORTED;
+  if (d.B * d.S > INT32_MAX / 2 || d.B * d.L > INT32_MAX / 2 || d.HD > INT32_MAX / 2 || d.D > INT32_MAX / 2)
+    return BEAGLE_ERR_UNSUPPORTED;
+  if (d.bf16) {
+    if (d.d != 128 || d.D % 64) return BEAGLE_ERR_UNSUPPORTED;
+  } else {
+    if (d.d > 128 || d.d % 4 || d.D % 4) return BEAGLE_ERR_UNSUPPORTED;
+  }
+  d.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)d.d));
+  d.mask.k = draft ? 1 : c->block_size;
+  d.mask.eps = draft ? 0 : c->block_offset;
+  d.mask.seq_kv = (int32_t)d.L;
+  d.mask.all_visible = draft ? 1 : 0;
+  *out = d;
+  return BEAGLE_OK;
+}
+
+struct BwdWs { size_t dO, dQ, dK, dV, delta, attn, total; };
+BwdWs bwd_layout(const Dims& d) {
+  BwdWs w; size_t o = 0;
+  w.dO = o; o += align_up((size_t)(d.B * d.S * d.HD) * d.esz);
+  w.dQ = o; o += align_up((size_t)(d.B * d.S * d.HD) * d.esz);
+  w.dK = o; o += align_up((size_t)(d.B * d.L * d.GD) * d.esz);
+  w.dV = o; o += align_up((size_t)(d.B * d.L * d.GD) * d.esz);
+  w.delta = o; o += align_up((size_t)(d.B * d.H * d.S) * sizeof(float));
+  w.attn = o;
+  w.total = o;
+  return w;
+}
+
+AttnArgs attn_args(const Dims& d) {
+  AttnArgs a; memset(&a, 0, sizeof(a));
+  a.B = (int32_t)d.B; a.S = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G;
+  a.d = (int32_t)d.d; a.scale = d.scale; a.mask = d.mask;
+  return a;
+}
+
+// C[M,N] = A[M,K] * B  with B stored [K,N] (weights [in,out])
+GemmArgs gemm_nn(const void* A, const void* W, void* C, int64_t M, int64_t N, int64_t K) {
+  GemmArgs g; memset(&g, 0, sizeof(g));
+  g.A = A; g.B = W; g.C = C; g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K;
+  g.lda = K; g.ldb = N; g.ldc = N; g.a_kmajor = 1; g.b_kmajor = 0;
+  return g;
+}
+// C[M,N] = A[M,K] * W^T  with W stored [N,K]
+GemmArgs gemm_nt(const void* A, const void* W, void* C, int64_t M, int64_t N, int64_t K) {
+  GemmArgs g = gemm_nn(A, W, C, M, N, K);
+  g.ldb = K; g.b_kmajor = 1;
+  return g;
+}
+// C[M,N] = X^T * Y  with X stored [K,M], Y stored [K,N]
+GemmArgs gemm_tn(const void* X, const void* Y, void* C, int64_t M, int64_t N, int64_t K, bool c_f32) {
+  GemmArgs g = gemm_nn(X, Y, C, M, N, K);
+  g.lda = M; g.a_kmajor = 0; g.c_is_f32 = c_f32 ? 1 : 0;
+  return g;
+}
+
+GemmGroup group1(const GemmArgs& a) { GemmGroup g; memset(&g, 0, sizeof(g)); g.count = 1; g.p[0] = a; return g; }
+
+void run_gemm(const Dims& d, const GemmGroup& g, hipStream_t s, const char* name) {
+  if (d.bf16) launch_gemm_bf16(g, s, name); else launch_gemm_f32(g, s, name);
+}
+
+beagle_status hip_status() { return hipGetLastError() == hipSuccess ? BEAGLE_OK : BEAGLE_ERR_HIP; }
+
+}  // namespace
+
+// ------------------------------------------------------------------ profiler
+namespace beagle {
+namespace {
+constexpr int PROF_CAP = 4096;
+struct ProfState {
+  bool on = false;
+  int n = 0;
+  hipEvent_t ev0[PROF_CAP], ev1[PROF_CAP];
+  const char* name[PROF_CAP];
+  int have_events = 0;
+  // aggregated results
+  int n_names = 0;
+  const char* agg_name[64];
+  int agg_count[64];
+  double agg_ms[64];
+} g_prof;
+}  // namespace
+
+void prof_before(const char* name, hipStream_t s) {
+  if (!g_prof.on || g_prof.n >= g_prof.have_events) return;
+  g_prof.name[g_prof.n] = name;
+  (void)hipEventRecord(g_prof.ev0[g_prof.n], s);
+}
+void prof_after(hipStream_t s) {
+  if (!g_prof.on || g_prof.n >= g_prof.have_events) return;
+  (void)hipEventRecord(g_prof.ev1[g_prof.n], s);
+  ++g_prof.n;
+}
+}  // namespace beagle
+
+extern "C" {
+
+beagle_status beagle_xattn_profile_begin(void) {
+  while (g_prof.have_events < PROF_CAP) {
+    int i = g_prof.have_events;
+    if (hipEventCreate(&g_prof.ev0[i]) != hipSuccess) return BEAGLE_ERR_HIP;
+    if (hipEventCreate(&g_prof.ev1[i]) != hipSuccess) { (void)hipEventDestroy(g_prof.ev0[i]); return BEAGLE_ERR_HIP; }
+    ++g_prof.have_events;
+  }
+  g_prof.n = 0; g_prof.n_names = 0; g_prof.on = true;
+  return BEAGLE_OK;
+}
+
+int32_t beagle_xattn_profile_end(void) {
+  g_prof.on = false;
+  g_prof.n_names = 0;
+  for (int i = 0; i < g_prof.n; ++i) {
+    if (hipEventSynchronize(g_prof.ev1[i]) != hipSuccess) return -1;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.ev0[i], g_prof.ev1[i]) != hipSuccess) return -1;
+    int k = 0;
+    for (; k < g_prof.n_names; ++k) if (!strcmp(g_prof.agg_name[k], g_prof.name[i])) break;
+    if (k == g_prof.n_names) {
+      if (k == 64) continue;
+      g_prof.agg_name[k] = g_prof.name[i]; g_prof.agg_count[k] = 0; g_prof.agg_ms[k] = 0.0; ++g_prof.n_names;
+    }
+    g_prof.agg_count[k] += 1; g_prof.agg_ms[k] += ms;
+  }
+  g_prof.n = 0;
+  return g_prof.n_names;
+}
+
+beagle_status beagle_xattn_profile_get(int32_t i, const char** name, int32_t* launches, double* total_ms) {
+  if (!name || !launches || !total_ms) return BEAGLE_ERR_NULL;
+  if (i < 0 || i >= g_prof.n_names) return BEAGLE_ERR_SHAPE;
+  *name = g_prof.agg_name[i]; *launches = g_prof.agg_count[i]; *total_ms = g_prof.agg_ms[i];
+  return BEAGLE_OK;
+}
+
+const char* beagle_xattn_status_string(beagle_status s) {
+  switch (s) {
+    case BEAGLE_OK: return "ok";
+    case BEAGLE_ERR_NULL: return "required pointer is NULL";
+    case BEAGLE_ERR_SHAPE: return "invalid or inconsistent size";
+    case BEAGLE_ERR_UNSUPPORTED: return "unsupported configuration";
+    case BEAGLE_ERR_WORKSPACE: return "workspace missing or too small";
+    case BEAGLE_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case BEAGLE_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* beagle_xattn_version(void) { return "1.0"; }
+
+// ------------------------------------------------------------- mask helpers
+beagle_status beagle_xattn_mask_row_limit(const beagle_xattn_desc* desc, int32_t* ws_out) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!ws_out) return BEAGLE_ERR_NULL;
+  for (int32_t p = 0; p < d.S; ++p) ws_out[p] = row_limit(p, d.mask);
+  return BEAGLE_OK;
+}
+
+beagle_status beagle_xattn_mask_dense(const beagle_xattn_desc* desc, uint8_t* mask_out) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!mask_out) return BEAGLE_ERR_NULL;
+  for (int64_t p = 0; p < d.S; ++p) {
+    int32_t lim = row_limit((int32_t)p, d.mask);
+    for (int64_t j = 0; j < d.L; ++j) mask_out[p * d.L + j] = j < lim ? 1 : 0;
+  }
+  return BEAGLE_OK;
+}
+
+beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, int32_t tk, uint8_t* cls_out) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!cls_out) return BEAGLE_ERR_NULL;
+  if (tq < 1 || tk < 1) return BEAGLE_ERR_SHAPE;
+  const int64_t nq = (d.S + tq - 1) / tq, nk = (d.L + tk - 1) / tk;
+  for (int64_t a = 0; a < nq; ++a)
+    for (int64_t c = 0; c < nk; ++c) {
+      int32_t q0 = (int32_t)(a * tq), q1 = (int32_t)((a + 1) * tq < d.S ? (a + 1) * tq : d.S);
+      int32_t j0 = (int32_t)(c * tk), j1 = (int32_t)((c + 1) * tk < d.L ? (c + 1) * tk : d.L);
+      cls_out[a * nk + c] = (uint8_t)tile_class(q0, q1, j0, j1, d.mask);
+    }
+  return BEAGLE_OK;
+}
+
+// ---------------------------------------------------------------- workspace
+size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
+  Dims d;
+  if (check_desc(desc, which == BEAGLE_WS_DRAFT, &d) != BEAGLE_OK) return 0;
+  switch (which) {
+    case BEAGLE_WS_FWD: return WS_ALIGN;   // nothing beyond the saved tensors
+    case BEAGLE_WS_BWD: {
+      BwdWs w = bwd_layout(d);
+      size_t extra = 0;
+      if (d.bf16) { AttnArgs a = attn_args(d); extra = attn_bwd_bf16_ws_bytes(a); }
+      return w.total + align_up(extra);
+    }
+    case BEAGLE_WS_DRAFT:
+      if (d.bf16) return align_up(decode_bf16_ws_bytes((int32_t)d.S, (int32_t)d.L, (int32_t)d.H, (int32_t)d.d, (int32_t)d.D));
+      return align_up((size_t)(2 * d.S * d.HD) * d.esz);
+    default: return 0;
+  }
+}
+
+// ------------------------------------------------------------------ forward
+beagle_status beagle_xattn_fwd(const beagle_xattn_desc* desc,
+    const void* xq, const void* xkv, const void* wq, const void* wk, const void* wv, const void* wo,
+    void* y, float* lse, void* q_save, void* k_save, void* v_save, void* o_save,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  const void* ptrs[] = {xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  (void)workspace; (void)workspace_bytes;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+
+  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
+  qkv.count = 3;
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
+  run_gemm(d, qkv, s, "proj_qkv");
+
+  AttnArgs a = attn_args(d);
+  a.q = q_save; a.k = k_save; a.v = v_save; a.o = o_save; a.lse = lse;
+  if (d.bf16) launch_attn_fwd_bf16(a, s); else launch_attn_fwd_f32(a, s);
+
+  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD)), s, "proj_out");
+  return hip_status();
+}
+
+// ----------------------------------------------------------------- backward
+beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
+    const void* dy, const void* xq, const void* xkv, const void* wq, const void* wk, const void* wv,
+    const void* wo, const void* q_save, const void* k_save, const void* v_save, const void* o_save,
+    const float* lse, void* dxq, void* dxkv, void* dwq, void* dwk, void* dwv, void* dwo,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  const bool need_dxkv = desc->flags & BEAGLE_FLAG_NEED_DXKV;
+  const void* ptrs[] = {dy, xq, xkv, wq, wk, wv, wo, q_save, k_save, v_save, o_save, lse,
+                        dxq, dwq, dwk, dwv, dwo, workspace};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  if (need_dxkv && !dxkv) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (dxkv && !aligned16(dxkv)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD)) return BEAGLE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+
+  const BwdWs w = bwd_layout(d);
+  char* base = (char*)workspace;
+  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
+  float* delta = (float*)(base + w.delta);
+  const bool wf32 = d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32);
+  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
+
+  // dO = dY Wo^T ; dWo = O^T dY
+  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
+  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
+
+  AttnArgs a = attn_args(d);
+  a.q = q_save; a.k = k_save; a.v = v_save; a.o = (void*)o_save; a.lse = (float*)lse;
+  a.dout = dO; a.dq = dQ; a.dk = dK; a.dv = dV; a.delta = delta;
+  if (d.bf16) launch_attn_bwd_bf16(a, base + w.attn, s); else launch_attn_bwd_f32(a, s);
+
+  // input gradients
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 1;
+    g.p[0] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
+    if (need_dxkv) {
+      g.count = 2;
+      g.p[1] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
+      g.p[1].A2 = dV; g.p[1].B2 = wv; g.p[1].K2 = (int32_t)d.GD; g.p[1].lda2 = d.GD; g.p[1].ldb2 = d.GD;
+    }
+    run_gemm(d, g, s, "bwd_dx");
+  }
+  // weight gradients
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 3;
+    g.p[0] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
+    g.p[1] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);
+    g.p[2] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
+    run_gemm(d, g, s, "bwd_dw");
+  }
+  return hip_status();
+}
+
+// --------------------------------------------------------------- draft step
+beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
+    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  const void* ptrs[] = {x_draft, k_cache, v_cache, wq, wo, y, lse, workspace};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT)) return BEAGLE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+
+  if (d.bf16) {
+    DecodeArgs a; memset(&a, 0, sizeof(a));
+    a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
+    a.D = (int32_t)d.D; a.scale = d.scale;
+    a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.wq = wq; a.wo = wo; a.y = y; a.lse = lse; a.ws = workspace;
+    launch_decode_bf16(a, s);
+    return hip_status();
+  }
+  char* base = (char*)workspace;
+  void* q = base;
+  void* o = base + (size_t)(d.S * d.HD) * d.esz;
+  launch_gemm_f32(group1(gemm_nn(x_draft, wq, q, d.S, d.HD, d.D)), s, "draft_proj_q");
+  AttnArgs a = attn_args(d);
+  a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
+  launch_attn_fwd_f32(a, s);
+  launch_gemm_f32(group1(gemm_nn(o, wo, y, d.S, d.D, d.HD)), s, "draft_proj_out");
+  return hip_status();
+}
+
+}  // extern "C"

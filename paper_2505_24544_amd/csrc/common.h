@@ -1,0 +1,91 @@
+// Shared declarations of the HIP sources: bf16 storage helpers, the launch
+// profiler hooks, and the internal launcher prototypes.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mask_index.h"
+
+namespace beagle {
+
+typedef uint16_t bf16_t;   // storage type: raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+  return __uint_as_float(((uint32_t)v) << 16);
+}
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// ---- launch profiler (see beagle_xattn_profile_* in the public header) ----
+void prof_before(const char* name, hipStream_t s);
+void prof_after(hipStream_t s);
+struct ProfScope {
+  hipStream_t s;
+  ProfScope(const char* name, hipStream_t st) : s(st) { prof_before(name, st); }
+  ~ProfScope() { prof_after(s); }
+};
+
+// ---- GEMM:  C[M,N] (+)= op(A) * op(B), float accumulation -----------------
+// a_kmajor: A is stored [M,K] (k fastest, leading dim lda) else [K,M].
+// b_kmajor: B is stored [N,K] (k fastest, leading dim ldb) else [K,N].
+// C is row-major [M,N] with leading dim ldc.  accumulate: C += instead of C =.
+// An optional second k-segment (A2, B2, K2; same storage orders and leading
+// dims lda2/ldb2) is contracted into the same C:  C = A*B + A2*B2.
+struct GemmArgs {
+  const void* A; const void* B; void* C;
+  int32_t M, N, K;
+  int64_t lda, ldb, ldc;
+  int32_t a_kmajor, b_kmajor;
+  int32_t c_is_f32;      // bf16 inputs only: write float instead of bf16
+  const void* A2; const void* B2;
+  int32_t K2;
+  int64_t lda2, ldb2;
+};
+// Up to 4 independent GEMMs in one launch (they share one grid).
+struct GemmGroup {
+  int32_t count;
+  GemmArgs p[4];
+};
+void launch_gemm_f32(const GemmGroup& g, hipStream_t s, const char* name);
+void launch_gemm_bf16_scalar(const GemmGroup& g, hipStream_t s, const char* name);
+void launch_gemm_bf16(const GemmGroup& g, hipStream_t s, const char* name);
+
+// ---- attention -------------------------------------------------------------
+struct AttnArgs {
+  int32_t B, S, L, H, G, d;
+  float scale;
+  MaskParams mask;
+  const void* q; const void* k; const void* v;   // [B,S,H,d], [B,L,G,d] x2
+  void* o; float* lse;                            // [B,S,H,d], [B,H,S]
+  // backward only
+  const void* dout;                               // dO [B,S,H,d]
+  void* dq; void* dk; void* dv;                   // [B,S,H,d], [B,L,G,d] x2
+  float* delta;                                   // [B,H,S]
+};
+void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s);
+void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s);
+void launch_attn_fwd_bf16_scalar(const AttnArgs& a, hipStream_t s);
+void launch_attn_bwd_bf16_scalar(const AttnArgs& a, hipStream_t s);
+void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
+void launch_attn_bwd_bf16(const AttnArgs& a, void* ws, hipStream_t s);
+size_t attn_bwd_bf16_ws_bytes(const AttnArgs& a);
+
+// ---- decode (bf16): split-KV attention of M queries over L cache rows ------
+struct DecodeArgs {
+  int32_t M, L, H, G, d, D;
+  float scale;
+  const void* x; const void* kc; const void* vc; const void* wq; const void* wo;
+  void* y; float* lse;
+  void* ws;
+};
+size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
+void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
+
+}  // namespace beagle

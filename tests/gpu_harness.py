@@ -1,0 +1,122 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, call the
+C-ABI through the binding, bring results back as float64, and error metrics.
+No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+
+DEV = "cuda:0"
+
+
+def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0):
+    return bx.make_desc(batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
+                        n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                        block_size=cfg.block_size, block_offset=cfg.block_offset,
+                        io_dtype=bx.BEAGLE_BF16 if cfg.dtype == "bf16" else bx.BEAGLE_F32,
+                        softmax_scale=scale, flags=flags)
+
+
+def tdtype(cfg):
+    return torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+
+
+def to_dev(a: np.ndarray, cfg) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, np.float32))
+    if cfg.dtype == "bf16":
+        t = t.to(torch.bfloat16)      # exact: the values are bf16-representable
+    return t.to(DEV).contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def workspace(desc, which):
+    n = bx.beagle_xattn_workspace_bytes(desc, which)
+    assert n > 0
+    return torch.empty(n, dtype=torch.uint8, device=DEV)
+
+
+def run_fwd(cfg, inp, flags=0, scale=0.0, poison=True):
+    """Returns (device tensors dict, host float64 dict)."""
+    d = desc_of(cfg, flags, scale)
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo")}
+
+    def out(*shape, dtype=dt):
+        t = torch.empty(*shape, dtype=dtype, device=DEV)
+        if poison:
+            t.fill_(float("nan"))
+        return t
+    dev.update(y=out(B, S, D), lse=out(B, H, S, dtype=torch.float32), q=out(B, S, H, hd), k=out(B, L, G, hd),
+               v=out(B, L, G, hd), o=out(B, S, H, hd))
+    ws = workspace(d, bx.BEAGLE_WS_FWD)
+    bx.beagle_xattn_fwd(d, dev["xq"], dev["xkv"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], dev["y"], dev["lse"],
+                        dev["q"], dev["k"], dev["v"], dev["o"], ws)
+    torch.cuda.synchronize()
+    host = {n: to_host(dev[n]) for n in ("y", "lse", "q", "k", "v", "o")}
+    return dev, host
+
+
+def run_bwd(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poison=True):
+    d = desc_of(cfg, flags, scale)
+    dt = tdtype(cfg)
+    wdt = torch.float32 if (flags & bx.BEAGLE_FLAG_WGRAD_F32) else dt
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dy = to_dev(inp["dy"], cfg)
+
+    def out(*shape, dtype=dt):
+        t = torch.empty(*shape, dtype=dtype, device=DEV)
+        if poison:
+            t.fill_(float("nan"))
+        return t
+    g = dict(dxq=out(B, S, D), dxkv=out(B, L, D) if (flags & bx.BEAGLE_FLAG_NEED_DXKV) else None,
+             dwq=out(D, H * hd, dtype=wdt), dwk=out(D, G * hd, dtype=wdt), dwv=out(D, G * hd, dtype=wdt),
+             dwo=out(H * hd, D, dtype=wdt))
+    ws = workspace(d, bx.BEAGLE_WS_BWD)
+    bx.beagle_xattn_bwd(d, dy, dev["xq"], dev["xkv"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], dev["q"], dev["k"],
+                        dev["v"], dev["o"], dev["lse"], g["dxq"], g["dxkv"], g["dwq"], g["dwk"], g["dwv"], g["dwo"], ws)
+    torch.cuda.synchronize()
+    return g, {n: to_host(t) for n, t in g.items() if t is not None}
+
+
+def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
+    """x [M,D], kc/vc [L,G,d], float32 arrays of stored values."""
+    d = desc_of(cfg, 0, scale)
+    M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
+    t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
+    y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
+    lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(d, bx.BEAGLE_WS_DRAFT)
+    bx.beagle_xattn_draft_step(d, t["x"], t["kc"], t["vc"], t["wq"], t["wo"], y, lse, ws)
+    torch.cuda.synchronize()
+    return to_host(y), to_host(lse)
+
+
+# ------------------------------------------------------------------ metrics
+def max_abs(a, b):
+    return float(np.max(np.abs(a - b))) if a.size else 0.0
+
+
+def rel_max(a, ref):
+    """max |a - ref| / max |ref|."""
+    den = float(np.max(np.abs(ref))) if ref.size else 0.0
+    return max_abs(a, ref) / den if den > 0 else max_abs(a, ref)
+
+
+def rel_fro(a, ref):
+    den = float(np.linalg.norm(ref.ravel()))
+    num = float(np.linalg.norm((a - ref).ravel()))
+    return num / den if den > 0 else num
+
+
+def lse_err(got, ref):
+    """Max abs error over finite entries; the -inf pattern must agree exactly."""
+    fin = np.isfinite(ref)
+    assert np.array_equal(np.isneginf(got), ~fin), "empty-row pattern differs"
+    return max_abs(got[fin], ref[fin]) if fin.any() else 0.0

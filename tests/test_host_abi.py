@@ -1,0 +1,130 @@
+"""Host-side checks of the C-ABI library (CPU only, no compute calls): it
+loads, exports every declared symbol, its integer mask/index code agrees bit
+for bit with the mask the oracle builds from the paper's prose, and invalid
+arguments are rejected before anything would be launched."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import beagle_oracle as orc
+from paper_2505_24544_amd import binding as bx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _desc(S=16, L=None, k=4, eps=0, **kw):
+    base = dict(batch=1, seq_q=S, seq_kv=S if L is None else L, hidden=256, n_q_heads=4, n_kv_heads=4,
+                head_dim=64, block_size=k, block_offset=eps, io_dtype=bx.BEAGLE_F32)
+    base.update(kw)
+    return bx.make_desc(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "beagle_xattn.h")).read()
+    declared = set(re.findall(r"\b(beagle_xattn_[a-z_]+)\s*\(", hdr))
+    declared.discard("beagle_xattn_desc")
+    assert declared == set(bx.EXPORTS)
+    L = bx.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert bx.beagle_xattn_version() == "1.0"
+    assert bx.beagle_xattn_status_string(0) == "ok"
+    for s in range(1, 7):
+        assert bx.beagle_xattn_status_string(s) not in ("ok", "unknown status")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 8, 16])
+def test_mask_and_row_limit_bit_exact_vs_oracle(k):
+    for eps in sorted({0, 1, k // 2, k - 1} & set(range(k))):
+        for S, L in ((1, 1), (7, 7), (64, 64), (130, 130), (257, 100), (100, 257)):
+            d = _desc(S, L, k, eps)
+            want = orc.dense_mask(S, L, k, eps)
+            got = bx.beagle_xattn_mask_dense(d)
+            assert got.dtype == np.uint8 and np.array_equal(got.astype(bool), want), (k, eps, S, L)
+            lim = bx.beagle_xattn_mask_row_limit(d)
+            assert np.array_equal(lim, want.sum(1).astype(np.int32))
+
+
+@pytest.mark.parametrize("S,k,count", [(2048, 4, 2093056), (4096, 8, 8372224), (8192, 8, 33521664)])
+def test_row_limits_at_full_size(S, k, count):
+    lim = bx.beagle_xattn_mask_row_limit(_desc(S, S, k, 0))
+    assert int(lim.astype(np.int64).sum()) == count
+    assert np.array_equal(lim, orc.dense_mask(S, S, k, 0).sum(1).astype(np.int32))
+
+
+@pytest.mark.parametrize("tq,tk", [(128, 64), (64, 64), (32, 16), (128, 128), (48, 20)])
+def test_tile_classes_vs_oracle_mask(tq, tk):
+    for (S, L, k, eps) in ((300, 300, 4, 0), (512, 512, 8, 3), (257, 190, 5, 2), (130, 400, 1, 0), (64, 64, 3, 1)):
+        cls = bx.beagle_xattn_tile_map(_desc(S, L, k, eps), tq, tk)
+        m = orc.dense_mask(S, L, k, eps)
+        assert cls.shape == (-(-S // tq), -(-L // tk))
+        for a in range(cls.shape[0]):
+            for c in range(cls.shape[1]):
+                blk = m[a * tq:(a + 1) * tq, c * tk:(c + 1) * tk]
+                want = 0 if not blk.any() else (2 if blk.all() else 1)
+                assert cls[a, c] == want, (S, L, k, eps, a, c)
+
+
+def test_skipped_tile_fraction_matches_block_structure():
+    # 128x128 tiles on the 7B-shaped config: 120 full, 16 partial, 120 skipped
+    cls = bx.beagle_xattn_tile_map(_desc(2048, 2048, 4, 0), 128, 128)
+    assert [(cls == v).sum() for v in (2, 1, 0)] == [120, 16, 120]
+
+
+def test_invalid_descriptors_are_rejected_on_the_host():
+    E = bx.BeagleError
+    bad = [dict(k=0), dict(k=4, eps=4), dict(eps=-1), dict(S=0), dict(n_kv_heads=3), dict(head_dim=0),
+           dict(io_dtype=7), dict(flags=1 << 9), dict(softmax_scale=-1.0), dict(batch=0)]
+    for kw in bad:
+        with pytest.raises(E):
+            bx.beagle_xattn_mask_row_limit(_desc(**kw))
+        assert bx.beagle_xattn_workspace_bytes(_desc(**kw), bx.BEAGLE_WS_BWD) == 0
+    d = _desc()
+    d.struct_size = 8
+    with pytest.raises(E) as ei:
+        bx.beagle_xattn_mask_row_limit(d)
+    assert ei.value.status == 2
+    # unsupported shapes: bf16 needs d == 128 and D % 64 == 0; f32 needs d <= 128
+    for kw in (dict(io_dtype=bx.BEAGLE_BF16, head_dim=64), dict(io_dtype=bx.BEAGLE_BF16, head_dim=128, hidden=200),
+               dict(head_dim=256), dict(head_dim=6)):
+        with pytest.raises(E) as ei:
+            bx.beagle_xattn_mask_row_limit(_desc(**kw))
+        assert ei.value.status == 3
+    with pytest.raises(E):
+        bx.beagle_xattn_tile_map(_desc(), 0, 4)
+
+
+def test_entry_points_validate_before_launching():
+    """NULL / misaligned / short-workspace arguments return a status without
+    touching the GPU (this test runs where there is none)."""
+    d = _desc()
+    a = 4096  # fake, aligned, never dereferenced: validation fails first
+    st = bx.beagle_xattn_fwd(d, a, a, a, a, a, a, a, a, a, a, a, None, None, stream=0, check=False)
+    assert st == 1
+    st = bx.beagle_xattn_fwd(d, a, a, a, a + 4, a, a, a, a, a, a, a, a, None, stream=0, check=False)
+    assert st == 5
+    args = [a] * 18
+    st = bx.beagle_xattn_bwd(d, *args, None, stream=0, check=False)
+    assert st == 1
+    st = bx.beagle_xattn_bwd(d, *args, a, stream=0, workspace_bytes=16, check=False)
+    assert st == 4
+    d2 = _desc(flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    args[13] = None
+    assert bx.beagle_xattn_bwd(d2, *args, a, stream=0, workspace_bytes=1 << 30, check=False) == 1
+    assert bx.beagle_xattn_draft_step(_desc(batch=2), a, a, a, a, a, a, a, a, stream=0, workspace_bytes=1 << 30,
+                                      check=False) == 2
+    assert bx.beagle_xattn_draft_step(d, a, a, a, a, a, a, a, a, stream=0, workspace_bytes=8, check=False) == 4
+    assert bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_BWD) > 0
+    assert bx.beagle_xattn_workspace_bytes(d, 99) == 0
+
+
+def test_workspace_is_linear_in_sequence_length():
+    """Constant-space masks: no S x L buffer anywhere in the workspace."""
+    def ws(S):
+        d = bx.make_desc(batch=1, seq_q=S, seq_kv=S, hidden=4096, n_q_heads=32, n_kv_heads=32, head_dim=128,
+                         block_size=4, io_dtype=bx.BEAGLE_BF16, flags=bx.BEAGLE_FLAG_NEED_DXKV)
+        return bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_BWD)
+    a, b, c = ws(1024), ws(2048), ws(4096)
+    assert abs((c - b) - 2 * (b - a)) <= 4096 and c < 3 * b
