@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-masked cross-attention hot path on one MI355X.
+
+One "step" = beagle_xattn_fwd + beagle_xattn_bwd (all projections, masked
+attention, every gradient) on one synthetic batch of the named workload, with
+all inputs resident in HBM.  Prints ONE JSON line.
+
+  value       TFLOP/s counting only unmasked attention pairs plus the dense
+              projection FLOPs (forward + backward)
+  roofline    the kernel with the largest share of the step, its algorithmic
+              FLOPs / its average duration (HIP events on the launch stream)
+  decode      the draft step at M in {1, 8, 32, 64} against L = 4096 cache
+              rows, buffers rotated through > 1 GB so each call reads cold HBM
+  cpu_baseline the float64 oracle timed on the host cores on a bounded sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def flops_training(cfg, need_dxkv=True):
+    """Algorithmic FLOPs of one forward+backward (unmasked pairs only)."""
+    B, S, L, D = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden
+    H, G, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    import numpy as np
+    p = np.arange(S)
+    t = p - cfg.block_offset
+    ws = np.where(t < 0, 0, cfg.block_offset + (t // cfg.block_size) * cfg.block_size)
+    pairs = int(np.minimum(ws, L).sum())
+    proj = {
+        "q": 2 * B * S * D * H * d, "k": 2 * B * L * D * G * d, "v": 2 * B * L * D * G * d,
+        "o": 2 * B * S * H * d * D,
+    }
+    proj_fwd = sum(proj.values())
+    proj_bwd = 2 * proj_fwd - (0 if need_dxkv else 2 * (2 * B * L * D * G * d))
+    attn_fwd = 4 * d * pairs * B * H
+    attn_bwd = 10 * d * pairs * B * H
+    return dict(total=proj_fwd + proj_bwd + attn_fwd + attn_bwd, proj_fwd=proj_fwd, proj_bwd=proj_bwd,
+                attn_fwd=attn_fwd, attn_bwd=attn_bwd, proj=proj, pairs=pairs)
+
+
+def kernel_flops(cfg, fl, need_dxkv=True):
+    """Algorithmic FLOPs per launch of each named kernel of the training step."""
+    p = fl["proj"]
+    return {
+        "proj_qkv": p["q"] + p["k"] + p["v"], "proj_out": p["o"], "bwd_dout": p["o"], "bwd_dwo": p["o"],
+        "bwd_dx": p["q"] + ((p["k"] + p["v"]) if need_dxkv else 0), "bwd_dw": p["q"] + p["k"] + p["v"],
+        "attn_fwd_bf16": fl["attn_fwd"], "attn_bwd_bf16": fl["attn_bwd"],
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_24544_amd import binding as bx, synth
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import gpu_harness as gh
+
+    bx.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.workload]
+    flags = bx.BEAGLE_FLAG_NEED_DXKV
+    desc = gh.desc_of(cfg, flags)
+    inp = synth.make_inputs(cfg)
+    t = {n: gh.to_dev(a, cfg) for n, a in inp.items()}
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    bf = torch.bfloat16
+    E = lambda *s, dt=bf: torch.empty(*s, dtype=dt, device=dev)
+    y, lse = E(B, S, D), E(B, H, S, dt=torch.float32)
+    q, k, v, o = E(B, S, H, hd), E(B, L, G, hd), E(B, L, G, hd), E(B, S, H, hd)
+    dxq, dxkv = E(B, S, D), E(B, L, D)
+    dwq, dwk, dwv, dwo = E(D, H * hd), E(D, G * hd), E(D, G * hd), E(H * hd, D)
+    ws_f = gh.workspace(desc, bx.BEAGLE_WS_FWD)
+    ws_b = gh.workspace(desc, bx.BEAGLE_WS_BWD)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        bx.beagle_xattn_fwd(desc, t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], y, lse, q, k, v, o,
+                            ws_f, stream)
+        bx.beagle_xattn_bwd(desc, t["dy"], t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], q, k, v, o, lse,
+                            dxq, dxkv, dwq, dwk, dwv, dwo, ws_b, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        bx.beagle_xattn_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = {} if args.no_profile else bx.beagle_xattn_profile_end()
+    ms_step = dt / args.steps * 1e3
+    fl = flops_training(cfg, True)
+    tflops = fl["total"] / (ms_step * 1e-3) / 1e12
+
+    # ---- roofline of the dominant kernel
+    roofline, kernels = None, {}
+    kf = kernel_flops(cfg, fl, True)
+    for name, (cnt, ms) in prof.items():
+        avg = ms / cnt
+        per_step = cnt / args.steps
+        kernels[name] = dict(avg_ms=round(avg, 4), launches_per_step=per_step,
+                             tflops=round(kf[name] / (avg * 1e-3) / 1e12, 1) if name in kf else None)
+    if prof:
+        dom = max(prof, key=lambda n: prof[n][1])
+        avg = prof[dom][1] / prof[dom][0]
+        ach = kf.get(dom, 0) / (avg * 1e-3) / 1e12
+        roofline = dict(bound="mfma", kernel=dom, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(avg, 4),
+                        flops_per_launch=kf.get(dom))
+
+    # ---- decode: draft step, cold HBM via buffer rotation
+    decode = None
+    if not args.no_decode:
+        decode = bench_decode(torch, bx, gh, synth, k, v, t)
+
+    # ---- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, synth)
+
+    out = {
+        "metric": "masked xattn fwd+bwd TFLOP/s (% bf16 MFMA peak); draft-step us (% HBM BW)",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: B%d S%d D%d H%d/G%d d%d k%d bf16 fwd+bwd (dXkv included)" % (
+            cfg.name, B, S, D, H, G, hd, cfg.block_size)},
+        "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "tokens_per_s": round(B * S / (ms_step * 1e-3)),
+        "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
+        "roofline": roofline, "kernels": kernels, "decode": decode, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):
+    """Draft step at the decode config (L=4096, D=4096, H=32, d=128).  The
+    cache rows come from the HIP forward's own K/V projection of synthetic
+    target states; timing is value-independent."""
+    cfg = synth.CONFIGS["c4"]
+    dev = "cuda:0"
+    L, D, H, G, hd = cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    nset = 10                      # 10 x 134 MB > 1 GB: defeats the 256 MB Infinity Cache
+    g = torch.Generator(device=dev).manual_seed(4)
+    sets = []
+    for i in range(nset):
+        kc = (torch.randn(L, G, hd, device=dev, generator=g) * 1.28).to(torch.bfloat16)
+        vc = (torch.randn(L, G, hd, device=dev, generator=g) * 1.28).to(torch.bfloat16)
+        wq = (torch.randn(D, H * hd, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+        wo = (torch.randn(H * hd, D, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+        sets.append((kc, vc, wq, wo))
+    res = {}
+    stream = torch.cuda.current_stream()
+    for M in (1, 8, 32, 64):
+        c = cfg.with_(seq_q=M)
+        desc = gh.desc_of(c)
+        x = torch.randn(M, D, device=dev, generator=g)
+        x = (x / x.pow(2).mean(-1, keepdim=True).add(1e-5).sqrt()).to(torch.bfloat16)
+        y = torch.empty(M, D, dtype=torch.bfloat16, device=dev)
+        lse = torch.empty(H, M, dtype=torch.float32, device=dev)
+        ws = gh.workspace(desc, bx.BEAGLE_WS_DRAFT)
+        for i in range(nset):
+            bx.beagle_xattn_draft_step(desc, x, *sets[i], y, lse, ws, stream)
+        torch.cuda.synchronize()
+        reps = 50
+        bx.beagle_xattn_profile_begin()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            bx.beagle_xattn_draft_step(desc, x, *sets[r % nset], y, lse, ws, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        prof = bx.beagle_xattn_profile_end()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        core_bytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2
+        call_bytes = core_bytes + 2 * D * H * hd * 2
+        kern = {n: round(ms / cnt * 1e3, 2) for n, (cnt, ms) in prof.items()}
+        res["M%d" % M] = dict(us_per_call=round(us, 2), gbs=round(call_bytes / us / 1e3, 1),
+                              pct_hbm_peak=round(100 * call_bytes / us / 1e3 / PEAK_HBM_GBS, 2),
+                              draft_tokens_per_s=round(M / (us * 1e-6)), bytes=call_bytes, kernel_us=kern)
+    return res
+
+
+def cpu_baseline(cfg, synth):
+    """The float64 oracle, as it stands, on the host cores: forward+backward on
+    batch 1 x the first 256 positions of the workload (all heads, full width)."""
+    import numpy as np
+    from oracle import beagle_oracle as orc
+    S = 256
+    c = cfg.with_(batch=1, seq_q=S, seq_kv=S)
+    inp = synth.make_inputs(c)
+    mask = orc.dense_mask(S, S, c.block_size, c.block_offset)
+    t0 = time.perf_counter()
+    orc.xattn_backward(inp["dy"], inp["xq"], inp["xkv"], inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                       n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, mask=mask)
+    dt = time.perf_counter() - t0
+    fl = flops_training(c, True)["total"]
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    return dict(value=round(fl / dt / 1e12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
+                seconds=round(dt, 2), tokens_per_s=round(S / dt, 1),
+                sample="%s shape, batch 1, first %d positions, float64 NumPy, fwd+bwd incl. dXkv" % (c.name, S))
+
+
+if __name__ == "__main__":
+    main()

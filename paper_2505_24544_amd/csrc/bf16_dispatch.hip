@@ -5,10 +5,6 @@
 
 namespace beagle {
 
-#ifndef BEAGLE_HAVE_MFMA_GEMM
-void launch_gemm_bf16(const GemmGroup& g, hipStream_t s, const char* name) { launch_gemm_bf16_scalar(g, s, name); }
-#endif
-
 #ifndef BEAGLE_HAVE_MFMA_ATTN_FWD
 void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s) { launch_attn_fwd_bf16_scalar(a, s); }
 #endif
