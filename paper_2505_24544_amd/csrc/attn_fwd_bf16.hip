@@ -1,0 +1,240 @@
+// Flash-style forward of the block-masked cross-attention (Eq. 2 with the
+// window mask of section 4.2) for bf16, head width 128, on gfx950 MFMA.
+//
+// One workgroup (4 waves) owns 128 queries of one (batch, head); each wave owns
+// 32 of them.  Key/value tiles of 64 rows are staged through two LDS stages in
+// their HBM order (rows of 128 channels).
+//
+// Everything is computed transposed so that a lane owns ONE query:
+//   S^T[j][q] = sum_c K[j][c] Q[q][c]     A operand = K rows   (ds_read_b128)
+//                                          B operand = Q rows   (registers)
+//   O^T[c][q] = sum_j V[j][c] P^T[j][q]   A operand = V^T      (ds_read_b64_tr_b16)
+//                                          B operand = P^T, taken straight from
+//                                          the S^T accumulator registers
+// With the 32x32 MFMA output layout a lane holds column q = lane % 32, so the
+// row max / row sum of the online softmax are reductions over the lane's own
+// registers plus one exchange with lane ^ 32, and rescaling O is a per-lane
+// scalar multiply.  The accumulator-to-operand hand-over of P needs no LDS
+// round trip: the k index of the second MFMA is an arbitrary labelling of the
+// 16 keys of a step, so V^T is simply fetched in the order the S^T registers
+// already have.
+//
+// Mask: query p sees keys j < row_limit(p).  The loop over key tiles stops at
+// the last tile any query of the workgroup can see (whole-tile skipping); only
+// tiles that straddle a wave's limits evaluate the per-element predicate.
+#include "common.h"
+
+namespace beagle {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_t;
+typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+
+namespace fwd {
+constexpr int HD = 128;           // head width
+constexpr int BQ = 128;           // queries per workgroup
+constexpr int BJ = 64;            // keys per tile
+constexpr int KLD = HD + 8;       // K tile row stride (elements): conflict-free b128 reads
+constexpr int VLD = HD + 32;      // V tile row stride: conflict-free transpose reads
+constexpr int K_ELEMS = BJ * KLD, V_ELEMS = BJ * VLD;
+constexpr int STAGE = K_ELEMS + V_ELEMS;
+constexpr int CHUNKS = BJ * HD / 8 / 256;   // 16-byte chunks per thread per tile
+}  // namespace fwd
+
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return *(uint32_t*)&b;
+}
+
+__global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
+  using namespace fwd;
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, ql = lane & 31;
+  const int nqt = (a.S + BQ - 1) / BQ;
+  const int qt = nqt - 1 - blockIdx.x;            // heaviest (latest) query tiles first
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int g = h / (a.H / a.G);
+  const int q0 = qt * BQ;
+  const int qw0 = q0 + wave * 32;                 // first query of this wave
+  const int q = qw0 + ql;                         // this lane's query
+  const bool q_ok = q < a.S;
+  const int qc = q_ok ? q : a.S - 1;
+
+  const bf16_t* Qg = (const bf16_t*)a.q + (((int64_t)b * a.S + qc) * a.H + h) * HD;
+  const bf16_t* Kg = (const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD;
+  const bf16_t* Vg = (const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD;
+  const int64_t kvs = (int64_t)a.G * HD;
+
+  const int lim = q_ok ? row_limit(q, a.mask) : 0;                 // keys visible to this lane's query
+  const int q_last = min(q0 + BQ, a.S) - 1;
+  const int wg_lim = row_limit(q_last, a.mask);                    // limits never decrease with p
+  const int w_last = min(qw0 + 32, a.S) - 1;
+  const int wave_hi = qw0 < a.S ? row_limit(w_last, a.mask) : 0;   // largest limit in this wave
+  const int wave_lo = qw0 < a.S ? row_limit(qw0, a.mask) : 0;      // smallest
+  const int ntiles = (wg_lim + BJ - 1) / BJ;
+
+  // Q fragments: B operand, lane holds Q[q][16*s + 8*hf .. +7]
+  bf16x8_t qf[HD / 16];
+#pragma unroll
+  for (int s = 0; s < HD / 16; ++s) qf[s] = *(const bf16x8_t*)(Qg + 16 * s + 8 * hf);
+
+  f32x16_t o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
+  float m = -INFINITY, l = 0.f;
+  const float c2 = a.scale * 1.44269504088896340736f;   // scores are kept raw; exp2((s - m) * c2)
+
+  i32x4_t kr[CHUNKS], vr[CHUNKS];
+  auto load_tile = [&](int jt) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = tid + 256 * i, r = c >> 4, col = (c & 15) * 8;
+      const int j = jt * BJ + r;
+      i32x4_t z = {0, 0, 0, 0};
+      kr[i] = z; vr[i] = z;
+      if (j < a.L) {
+        kr[i] = *(const i32x4_t*)(Kg + j * kvs + col);
+        vr[i] = *(const i32x4_t*)(Vg + j * kvs + col);
+      }
+    }
+  };
+  auto store_tile = [&](int stage) {
+    bf16_t* ks = smem + stage * STAGE;
+    bf16_t* vs = ks + K_ELEMS;
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const int c = tid + 256 * i, r = c >> 4, col = (c & 15) * 8;
+      *(i32x4_t*)(ks + r * KLD + col) = kr[i];
+      *(i32x4_t*)(vs + r * VLD + col) = vr[i];
+    }
+  };
+
+  if (ntiles > 0) {
+    load_tile(0);
+    store_tile(0);
+  }
+  __syncthreads();
+
+#pragma unroll 1
+  for (int jt = 0; jt < ntiles; ++jt) {
+    const int cur = jt & 1;
+    const bool more = jt + 1 < ntiles;
+    if (more) load_tile(jt + 1);
+    const int j0 = jt * BJ;
+    if (j0 < wave_hi) {                                  // wave-uniform: this wave sees part of the tile
+      const bf16_t* ks = smem + cur * STAGE;
+      const bf16_t* vs = ks + K_ELEMS;
+      // ---- S^T = K Q^T  (two blocks of 32 keys)
+      f32x16_t st[2];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[jb][e] = 0.f;
+#pragma unroll
+        for (int s = 0; s < HD / 16; ++s) {
+          bf16x8_t kf = *(const bf16x8_t*)(ks + (jb * 32 + ql) * KLD + 16 * s + 8 * hf);
+          st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], st[jb], 0, 0, 0);
+        }
+      }
+      // ---- mask (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4)
+      if (j0 + BJ > wave_lo) {
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int j = j0 + 32 * jb + 8 * (e >> 2) + 4 * hf + (e & 3);
+            if (j >= lim) st[jb][e] = -INFINITY;
+          }
+      }
+      // ---- online softmax for this lane's query
+      float mx = st[0][0];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[jb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f((m - m_safe) * c2);
+      const float mc = m_safe * c2;
+      float rs = 0.f;
+      uint32_t pk[2][8];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(st[jb][e] * c2 - mc);
+          const float p1 = __builtin_amdgcn_exp2f(st[jb][e + 1] * c2 - mc);
+          rs += p0 + p1;
+          pk[jb][e >> 1] = cvt_pk_bf16(p0, p1);
+        }
+      rs += __shfl_xor(rs, 32, 64);
+      l = l * alpha + rs;
+      m = m_new;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+      // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7, i.e. keys
+      //      32 jb + 16 t + {4 hf + 0..3, 8 + 4 hf + 0..3}
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          union { uint32_t u[4]; bf16x8_t v; } pf;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pf.u[i] = pk[jb][4 * t + i];
+          const int gi = lane >> 4, r = lane & 15;
+          const int row = 32 * jb + 16 * t + 4 * (gi >> 1) + (r >> 2);
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) {
+            const bf16_t* p = vs + row * VLD + 32 * cb + 16 * (gi & 1) + 4 * (r & 3);
+            union { struct { s16x4_t x, y; } s; bf16x8_t v; } vf;
+            vf.s.x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+            vf.s.y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * VLD));
+            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[cb], 0, 0, 0);
+          }
+        }
+    }
+    if (more) store_tile(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- normalise and store: register e of block cb is channel 32 cb + 8 (e/4) + 4 hf + e%4
+  if (q_ok) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    bf16_t* Og = (bf16_t*)a.o + (((int64_t)b * a.S + q) * a.H + h) * HD;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        uint2 v = {cvt_pk_bf16(o[cb][4 * qd] * inv, o[cb][4 * qd + 1] * inv),
+                   cvt_pk_bf16(o[cb][4 * qd + 2] * inv, o[cb][4 * qd + 3] * inv)};
+        *(uint2*)(Og + 32 * cb + 8 * qd + 4 * hf) = v;
+      }
+    if (hf == 0)
+      a.lse[((int64_t)b * a.H + h) * a.S + q] = l > 0.f ? m * a.scale + __logf(l) : -INFINITY;
+  }
+}
+
+void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s) {
+  using namespace fwd;
+  constexpr size_t smem = 2 * (size_t)STAGE * sizeof(bf16_t);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    attr_set = true;
+  }
+  ProfScope ps("attn_fwd_bf16", s);
+  dim3 grid((a.S + BQ - 1) / BQ, a.H, a.B);
+  hipLaunchKernelGGL(attn_fwd_bf16_kernel, grid, dim3(256), smem, s, a);
+}
+
+}  // namespace beagle

@@ -5,15 +5,6 @@
 
 namespace beagle {
 
-#ifndef BEAGLE_HAVE_MFMA_ATTN_FWD
-void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s) { launch_attn_fwd_bf16_scalar(a, s); }
-#endif
-
-#ifndef BEAGLE_HAVE_MFMA_ATTN_BWD
-size_t attn_bwd_bf16_ws_bytes(const AttnArgs&) { return 0; }
-void launch_attn_bwd_bf16(const AttnArgs& a, void*, hipStream_t s) { launch_attn_bwd_bf16_scalar(a, s); }
-#endif
-
 #ifndef BEAGLE_HAVE_DECODE
 size_t decode_bf16_ws_bytes(int32_t M, int32_t, int32_t H, int32_t d, int32_t) {
   return (size_t)2 * M * H * d * sizeof(bf16_t);
