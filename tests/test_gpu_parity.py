@@ -166,7 +166,9 @@ def test_train_decode_consistency_on_gpu():
         vc = fw["v"][0, :n].astype(np.float32)
         y, lse = run_draft(dcfg, inp["xq"][0, p:p + 1], kc, vc, inp["wq"], inp["wo"])
         assert max_abs(y[0], fw["y"][0, p]) <= 2e-3
-        assert max_abs(lse[:, 0], fw["lse"][0, :, p]) <= 1e-4
+        # the training path scores with the bf16-rounded q it saves, the draft
+        # step with q at ~16 bits: the two LSEs differ by that rounding only
+        assert max_abs(lse[:, 0], fw["lse"][0, :, p]) <= 2e-3
 
 
 # ------------------------------------------------------------------ decode (bf16)
