@@ -6,18 +6,27 @@
 //   * One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C; each
 //     wave owns (32*TM) x (32*TN) of it as TM x TN accumulators of the
 //     v_mfma_f32_32x32x16_bf16 instruction.
-//   * The k loop walks BK = 64 at a time through two LDS stages: the global
-//     loads of slice t+1 are issued before the MFMAs of slice t and parked in
-//     registers, then written to the other stage; one barrier per slice.
-//   * Each operand tile sits in LDS in the order it has in HBM, so the copy is
-//     16 bytes per lane, coalesced, whatever the storage order:
-//       k-contiguous operand  -> tile [rows][BK + 8]; a fragment is one
-//                                ds_read_b128 (rows padded to 144 B: the 16
-//                                lanes of a read phase hit 64 distinct banks);
-//       row-contiguous operand-> tile [BK][rows + 32]; a fragment is two
-//                                ds_read_b64_tr_b16 (the LDS transpose read),
-//                                which hand every lane four consecutive k of
-//                                its own row.
+//   * The k loop walks BK = 64 at a time through two LDS stages.  Slices go
+//     from HBM/L2 straight into LDS (buffer_load ... lds, 16 bytes per lane):
+//     no staging registers, no ds_write, and out-of-range chunks arrive as
+//     zeros through the buffer descriptor's range check.  The loads of slice
+//     t+1 are issued before the MFMAs of slice t; one vmcnt wait + barrier per
+//     slice.  The two stages are two separate __shared__ arrays so that the
+//     compiler can tell a fragment read of one stage from an in-flight load
+//     into the other.
+//   * Each operand tile sits in LDS in the order it has in HBM (a lane's 16
+//     bytes land at wave_base + 16 * lane), with an XOR swizzle chosen on the
+//     GLOBAL side (which chunk a lane fetches) so that reads are conflict free:
+//       k-contiguous operand  -> rows of 128 B; chunk c of row r is stored at
+//                                chunk c ^ ((r >> 1) & 7); a fragment is one
+//                                ds_read_b128;
+//       row-contiguous operand-> k-rows of ROWS*2 B; chunk c of k-row k is
+//                                stored at chunk c ^ ((k & 3) << 2); a fragment
+//                                is two ds_read_b64_tr_b16 (the LDS transpose
+//                                read), which hand every lane four consecutive
+//                                k of its own row.
+//   * Fragments are double-buffered in registers: those of k step s+1 are read
+//     from LDS before the MFMAs of step s are issued.
 //   * The MFMA is issued "transposed" (A operand = W rows, B operand = X rows)
 //     so that a lane ends up with 4 consecutive n of one C row in 4 consecutive
 //     accumulator registers: the epilogue stores 8 (bf16) or 16 (float) bytes
@@ -35,76 +44,63 @@ namespace beagle {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
-typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_t;
+typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 constexpr int BK = 64;
-constexpr int KPAD = 8;     // k-contiguous tiles: row stride BK + 8 elements
-constexpr int RPAD = 32;    // row-contiguous tiles: k-row stride rows + 32 elements
 constexpr int GROUP_M = 4;
 constexpr int NUM_XCD = 8;
 
-template <int ROWS, bool KMAJOR>
-struct TileGeom {
-  static constexpr int LD = KMAJOR ? (BK + KPAD) : (ROWS + RPAD);
-  static constexpr int ELEMS = KMAJOR ? ROWS * LD : BK * LD;
-  static constexpr int CHUNKS = ROWS * BK / 8;          // 16-byte chunks per slice
-  static constexpr int PER_THREAD = CHUNKS / 256;
-};
-
-// Global -> registers for one BK slice of one operand.
-//   KMAJOR : element (row r, k) at base[r * ld + k]
-//   !KMAJOR: element (row r, k) at base[k * ld + r]
-// rows beyond `rows_valid` and k beyond `k_valid` read as zero.
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void load_slice(i32x4_t* __restrict__ reg,
-                                           const bf16_t* __restrict__ base, int64_t ld, int row0, int k0,
-                                           int rows_valid, int k_valid, int tid) {
-  using G = TileGeom<ROWS, KMAJOR>;
-#pragma unroll
-  for (int i = 0; i < G::PER_THREAD; ++i) {
-    const int c = tid + 256 * i;
-    int r, k;
-    if (KMAJOR) { r = c / (BK / 8); k = (c % (BK / 8)) * 8; }
-    else        { k = c / (ROWS / 8); r = (c % (ROWS / 8)) * 8; }
-    const int gr = row0 + r, gk = k0 + k;
-    i32x4_t v = {0, 0, 0, 0};
-    if (gr < rows_valid && gk < k_valid) {
-      const bf16_t* p = KMAJOR ? base + (int64_t)gr * ld + gk : base + (int64_t)gk * ld + gr;
-      v = *(const i32x4_t*)p;
-    }
-    reg[i] = v;
-  }
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, int64_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
 }
 
+// One BK slice of one operand, HBM -> LDS.  Chunk q = tid + 256 i of the tile
+// (16 bytes) lands at tile + 16 q; which global chunk it is follows from the
+// swizzle.
+//   KMAJOR : element (row r, k) at base[r * ld + k]   (buffer = rows * ld elements)
+//   !KMAJOR: element (row r, k) at base[k * ld + r]   (buffer = K * ld elements)
+// k beyond K must read as zero: for !KMAJOR that is past the end of the buffer;
+// for KMAJOR the launcher requires K % BK == 0.  Rows beyond the matrix only
+// feed output rows/columns that are never stored, so whatever they read (zero
+// past the end, or a neighbouring row) is harmless.
 template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void store_slice(const i32x4_t* __restrict__ reg,
-                                            bf16_t* __restrict__ tile, int tid) {
-  using G = TileGeom<ROWS, KMAJOR>;
+__device__ __forceinline__ void load_slice(bf16_t* tile, __amdgpu_buffer_rsrc_t rsrc, int64_t ld, int row0, int k0,
+                                           int tid) {
+  constexpr int PER_THREAD = ROWS * BK / 8 / 256;
+  const int wave = tid >> 6;
 #pragma unroll
-  for (int i = 0; i < G::PER_THREAD; ++i) {
-    const int c = tid + 256 * i;
-    int r, k;
-    if (KMAJOR) { r = c / (BK / 8); k = (c % (BK / 8)) * 8; *(i32x4_t*)(tile + r * G::LD + k) = reg[i]; }
-    else        { k = c / (ROWS / 8); r = (c % (ROWS / 8)) * 8; *(i32x4_t*)(tile + k * G::LD + r) = reg[i]; }
+  for (int i = 0; i < PER_THREAD; ++i) {
+    const int q = tid + 256 * i;
+    int off;
+    if (KMAJOR) {
+      const int r = q >> 3, c = (q & 7) ^ ((r >> 1) & 7);
+      off = (int)(((int64_t)(row0 + r) * ld + k0 + 8 * c) * 2);
+    } else {
+      constexpr int CPR = ROWS / 8;
+      const int k = q / CPR, c = (q % CPR) ^ ((k & 3) << 2);
+      off = (int)(((int64_t)(k0 + k) * ld + row0 + 8 * c) * 2);
+    }
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * 4 + wave) * 512), 16, off, 0, 0, 0);
   }
 }
 
 // MFMA operand fragment: lane l gets row (r0 + l % 32), k = kk + 8 * (l / 32) .. + 7.
 template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ bf16x8_t read_frag(const bf16_t* __restrict__ tile, int r0, int kk, int lane) {
-  using G = TileGeom<ROWS, KMAJOR>;
+__device__ __forceinline__ bf16x8_t read_frag(const bf16_t* tile, int r0, int kk, int lane) {
   if (KMAJOR) {
-    return *(const bf16x8_t*)(tile + (r0 + (lane & 31)) * G::LD + kk + 8 * (lane >> 5));
+    const int r = r0 + (lane & 31), c = (kk >> 3) + (lane >> 5);
+    return *(const bf16x8_t*)(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3));
   } else {
     // transpose read: the 16 lanes of a group pass the addresses of 4 k-rows x
-    // 4 chunks of 4 rows; lane l of the group receives k-rows 0..3 of row l.
-    const int gi = lane >> 4, r = lane & 15;
-    const bf16_t* p = tile + (kk + 8 * (gi >> 1) + (r >> 2)) * G::LD + r0 + 16 * (gi & 1) + 4 * (r & 3);
-    typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
-    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)p);
-    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * G::LD));
+    // 4 pieces of 4 rows; lane l of the group receives k-rows 0..3 of row l.
+    const int gi = lane >> 4, r16 = lane & 15;
+    const int kr = kk + 8 * (gi >> 1) + (r16 >> 2);          // kr & 3 == (kr + 4) & 3
+    const int col = r0 + 16 * (gi & 1) + 4 * (r16 & 3);
+    const bf16_t* p = tile + kr * ROWS + ((((col >> 3) ^ ((kr & 3) << 2)) << 3) | (col & 7));
     union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
-    u.s.a = lo; u.s.b = hi;
+    u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+    u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ROWS));
     return u.v;
   }
 }
@@ -116,12 +112,11 @@ __device__ __forceinline__ int remap_xcd(int pid, int total) {
 }
 
 template <int TM, int TN, bool XK, bool WK, bool F32OUT>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmGroup grp, int total_tiles) {
+__global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(GemmGroup grp, int total_tiles) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
-  using GX = TileGeom<BM, XK>;
-  using GW = TileGeom<BN, WK>;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  constexpr int STAGE = GX::ELEMS + GW::ELEMS;   // stage s: X tile at s*STAGE, W tile after it
+  constexpr int XE = BM * BK, WE = BN * BK;      // elements per operand tile
+  __shared__ __attribute__((aligned(1024))) bf16_t stage0[XE + WE];
+  __shared__ __attribute__((aligned(1024))) bf16_t stage1[XE + WE];
 
   // ---- which tile of which problem
   int pid = remap_xcd(blockIdx.x, total_tiles);
@@ -152,8 +147,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmGroup grp, int to
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  i32x4_t xr[GX::PER_THREAD], wr[GW::PER_THREAD];
-
 #pragma unroll 1
   for (int seg = 0; seg < 2; ++seg) {
     const bf16_t* X = (const bf16_t*)(seg ? g.A2 : g.A);
@@ -162,43 +155,51 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmGroup grp, int to
     const int64_t ldx = seg ? g.lda2 : g.lda, ldw = seg ? g.ldb2 : g.ldb;
     if (X == nullptr || K <= 0) continue;
     const int nk = (K + BK - 1) / BK;
+    const __amdgpu_buffer_rsrc_t xrs = make_rsrc(X, (int64_t)(XK ? g.M : K) * ldx * 2);
+    const __amdgpu_buffer_rsrc_t wrs = make_rsrc(W, (int64_t)(WK ? g.N : K) * ldw * 2);
 
-    load_slice<BM, XK>(xr, X, ldx, m0, 0, g.M, K, tid);
-    load_slice<BN, WK>(wr, W, ldw, n0, 0, g.N, K, tid);
-    __syncthreads();                       // previous segment's readers are done
-    store_slice<BM, XK>(xr, smem, tid);
-    store_slice<BN, WK>(wr, smem + GX::ELEMS, tid);
-    __syncthreads();
-
-#pragma unroll 1
-    for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      const bool more = kt + 1 < nk;
-      if (more) {
-        load_slice<BM, XK>(xr, X, ldx, m0, (kt + 1) * BK, g.M, K, tid);
-        load_slice<BN, WK>(wr, W, ldw, n0, (kt + 1) * BK, g.N, K, tid);
-      }
-      const bf16_t* xt = smem + cur * STAGE;
-      const bf16_t* wt = xt + GX::ELEMS;
+    bf16x8_t xf[2][TM], wf[2][TN];
+    auto fetch = [&](bf16_t* st, int k0) {
+      load_slice<BM, XK>(st, xrs, ldx, m0, k0, tid);
+      load_slice<BN, WK>(st + XE, wrs, ldw, n0, k0, tid);
+    };
+    auto frags = [&](const bf16_t* st, int fb, int kk) {
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 16) {
-        bf16x8_t xf[TM], wf[TN];
+      for (int i = 0; i < TM; ++i) xf[fb][i] = read_frag<BM, XK>(st, wm + 32 * i, kk, lane);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) xf[i] = read_frag<BM, XK>(xt, wm + 32 * i, kk, lane);
+      for (int j = 0; j < TN; ++j) wf[fb][j] = read_frag<BN, WK>(st + XE, wn + 32 * j, kk, lane);
+    };
+    // one k slice: loads of the next slice fly into `nxt` while `cur` is consumed
+    auto slice = [&](const bf16_t* cur, bf16_t* nxt, int kt) {
+      fetch(nxt, (kt + 1) * BK);      // past the last slice this fetches zeros / unused rows: harmless
+      __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the MFMAs that hide their latency
 #pragma unroll
-        for (int j = 0; j < TN; ++j) wf[j] = read_frag<BN, WK>(wt, wn + 32 * j, kk, lane);
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        const int fb = ks & 1;
+        if (ks + 1 < BK / 16) frags(cur, fb ^ 1, 16 * (ks + 1));
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb][j], xf[fb][i], acc[i][j], 0, 0, 0);
       }
-      if (more) {
-        store_slice<BM, XK>(xr, smem + (cur ^ 1) * STAGE, tid);
-        store_slice<BN, WK>(wr, smem + (cur ^ 1) * STAGE + GX::ELEMS, tid);
-      }
-      __syncthreads();
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's chunks of the next slice are in LDS
+      __syncthreads();                      // everyone's are, and everyone is done reading `cur`
+      frags(nxt, 0, 0);
+    };
+
+    __syncthreads();                        // previous segment: all reads done, both stages free
+    fetch(stage0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    frags(stage0, 0, 0);
+    int kt = 0;
+#pragma unroll 1
+    for (; kt + 2 <= nk; kt += 2) {
+      slice(stage0, stage1, kt);
+      slice(stage1, stage0, kt + 1);
     }
+    if (kt < nk) slice(stage0, stage1, kt);
   }
 
   // ---- epilogue: lane holds C row m = .. + lane % 32; register e of tile (i, j)
@@ -229,15 +230,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmGroup grp, int to
 
 template <int TM, int TN, bool XK, bool WK, bool F32OUT>
 static void launch_variant(const GemmGroup& grp, int total, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<TM, TN, XK, WK, F32OUT>;
-  constexpr size_t smem =
-      2 * (size_t)(TileGeom<64 * TM, XK>::ELEMS + TileGeom<64 * TN, WK>::ELEMS) * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3(total), dim3(256), smem, s, grp, total);
+  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, XK, WK, F32OUT>), dim3(total), dim3(256), 0, s, grp, total);
 }
 
 template <int TM, int TN>
@@ -248,6 +241,15 @@ static void launch_tiles(const GemmGroup& grp, hipStream_t s) {
     total += ((grp.p[i].M + BM - 1) / BM) * ((grp.p[i].N + BN - 1) / BN);
   if (total == 0) return;
   const bool xk = grp.p[0].a_kmajor, wk = grp.p[0].b_kmajor, f32 = grp.p[0].c_is_f32;
+  bool fits = true;      // k-contiguous operands: K a multiple of BK; byte offsets must fit 31 bits
+  for (int i = 0; i < grp.count; ++i) {
+    const GemmArgs& q = grp.p[i];
+    const int64_t lim = (int64_t)1 << 31;
+    if ((xk || wk) && (q.K % BK || (q.A2 && q.K2 % BK))) fits = false;
+    if ((int64_t)(xk ? q.M : q.K) * q.lda * 2 >= lim || (int64_t)(wk ? q.N : q.K) * q.ldb * 2 >= lim) fits = false;
+    if (q.A2 && ((int64_t)(xk ? q.M : q.K2) * q.lda2 * 2 >= lim || (int64_t)(wk ? q.N : q.K2) * q.ldb2 * 2 >= lim)) fits = false;
+  }
+  if (!fits) { launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar"); return; }
   if (xk && !wk && !f32) launch_variant<TM, TN, true, false, false>(grp, total, s);
   else if (xk && wk && !f32) launch_variant<TM, TN, true, true, false>(grp, total, s);
   else if (!xk && !wk && !f32) launch_variant<TM, TN, false, false, false>(grp, total, s);

@@ -43,6 +43,13 @@ def workspace(desc, which):
 
 def run_fwd(cfg, inp, flags=0, scale=0.0, poison=True):
     """Returns (device tensors dict, host float64 dict)."""
+    dev, _ = run_fwd_device(cfg, inp, flags, scale, poison)
+    host = {n: to_host(dev[n]) for n in ("y", "lse", "q", "k", "v", "o")}
+    return dev, host
+
+
+def run_fwd_device(cfg, inp, flags=0, scale=0.0, poison=True):
+    """Forward through the C ABI; results stay on the device."""
     d = desc_of(cfg, flags, scale)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -59,11 +66,15 @@ def run_fwd(cfg, inp, flags=0, scale=0.0, poison=True):
     bx.beagle_xattn_fwd(d, dev["xq"], dev["xkv"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], dev["y"], dev["lse"],
                         dev["q"], dev["k"], dev["v"], dev["o"], ws)
     torch.cuda.synchronize()
-    host = {n: to_host(dev[n]) for n in ("y", "lse", "q", "k", "v", "o")}
-    return dev, host
+    return dev, None
 
 
 def run_bwd(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poison=True):
+    g = run_bwd_device(cfg, inp, dev, flags, scale, poison)
+    return g, {n: to_host(t) for n, t in g.items() if t is not None}
+
+
+def run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poison=True):
     d = desc_of(cfg, flags, scale)
     dt = tdtype(cfg)
     wdt = torch.float32 if (flags & bx.BEAGLE_FLAG_WGRAD_F32) else dt
@@ -82,7 +93,7 @@ def run_bwd(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poison=Tru
     bx.beagle_xattn_bwd(d, dy, dev["xq"], dev["xkv"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], dev["q"], dev["k"],
                         dev["v"], dev["o"], dev["lse"], g["dxq"], g["dxkv"], g["dwq"], g["dwk"], g["dwv"], g["dwo"], ws)
     torch.cuda.synchronize()
-    return g, {n: to_host(t) for n, t in g.items() if t is not None}
+    return g
 
 
 def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):

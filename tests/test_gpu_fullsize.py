@@ -1,0 +1,87 @@
+"""GPU parity at the FULL sizes of the training configs, in the launch
+configuration that bench.py times (bf16, dXkv requested), on sampled outputs.
+
+The expected values are float64 oracle outputs at sampled positions, written
+once by tests/golden/make_fullsize_golden.py (which calls only the oracle and
+the input generators) into tests/golden/fullsize_*.npz."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+OUT_ABS, OUT_FRO, LSE_TOL, GRAD_FRO = 2e-2, 1e-2, 1e-3, 3e-2
+
+
+def _gather(t: torch.Tensor, idx: np.ndarray) -> np.ndarray:
+    i = torch.from_numpy(idx).to(t.device)
+    return t.reshape(-1)[i].to(torch.float64).cpu().numpy()
+
+
+@pytest.mark.parametrize("name", ["c2", "c2_peaked", "c3", "c5"])
+def test_fullsize_sampled_parity(name):
+    path = os.path.join(GOLD, "fullsize_%s.npz" % name)
+    if not os.path.exists(path):
+        pytest.skip("golden file %s not generated" % path)
+    gold = np.load(path)
+    cname = name.split("_")[0]
+    cfg = synth.CONFIGS[cname]
+    peaked = bool(gold["meta"][2])
+    inp = synth.make_inputs(cfg, peaked_queries=peaked)
+    dev, _ = gh.run_fwd_device(cfg, inp)
+    grads = gh.run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    tensors = {**{n: dev[n] for n in ("y", "lse", "q", "k", "v", "o")}, **grads}
+    tensors["o_group"], tensors["lse_group"] = dev["o"], dev["lse"]
+    checked = 0
+    for key in gold.files:
+        if not key.startswith("idx_"):
+            continue
+        tname = key[4:]
+        t = tensors[tname]
+        assert tuple(gold["shape_" + tname]) == tuple(t.shape), tname
+        got, ref = _gather(t, gold[key]), gold["val_" + tname]
+        checked += 1
+        if tname.startswith("lse"):
+            fin = np.isfinite(ref)
+            assert np.array_equal(np.isneginf(got), ~fin), tname
+            tol = 4e-3 if peaked else LSE_TOL
+            assert gh.max_abs(got[fin], ref[fin]) <= tol, (tname, gh.max_abs(got[fin], ref[fin]))
+        elif tname.startswith("d"):
+            assert np.isfinite(got).all(), tname
+            assert gh.rel_fro(got, ref) <= GRAD_FRO, (tname, gh.rel_fro(got, ref))
+        else:
+            assert np.isfinite(got).all(), tname
+            assert gh.max_abs(got, ref) <= OUT_ABS, (tname, gh.max_abs(got, ref))
+            assert gh.rel_fro(got, ref) <= OUT_FRO, (tname, gh.rel_fro(got, ref))
+    assert checked >= 8
+
+
+def test_fullsize_structure_properties_c5():
+    """Properties that hold at any size, checked on the largest config: rows
+    that see no key are exactly zero with LSE = -inf, keys that no query sees
+    get exactly zero gradient, nothing is NaN, and a second run is bitwise equal."""
+    cfg = synth.CONFIGS["c5"]
+    inp = synth.make_inputs(cfg)
+    dev, _ = gh.run_fwd_device(cfg, inp)
+    g1 = gh.run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    k = cfg.block_size
+    assert bool((dev["y"][:, :k] == 0).all()) and bool(torch.isneginf(dev["lse"][:, :, :k]).all())
+    assert bool(torch.isfinite(dev["lse"][:, :, k:]).all())
+    assert bool((g1["dxq"][:, :k] == 0).all())
+    assert bool((g1["dxkv"][:, cfg.seq_kv - k:] == 0).all())        # the last window's keys are seen by nobody
+    for t in list(g1.values()) + [dev["y"], dev["o"]]:
+        assert bool(torch.isfinite(t.float()).all())
+    snap = {n: t.clone() for n, t in g1.items()}
+    y1 = dev["y"].clone()
+    dev2, _ = gh.run_fwd_device(cfg, inp)
+    g2 = gh.run_bwd_device(cfg, inp, dev2, flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    assert torch.equal(y1, dev2["y"])
+    for n in snap:
+        assert torch.equal(snap[n], g2[n]), n
