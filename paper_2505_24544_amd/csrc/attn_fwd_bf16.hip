@@ -2,8 +2,8 @@
 // window mask of section 4.2) for bf16, head width 128, on gfx950 MFMA.
 //
 // One workgroup (4 waves) owns 128 queries of one (batch, head); each wave owns
-// 32 of them.  Key/value tiles of 64 rows are staged through two LDS stages in
-// their HBM order (rows of 128 channels).
+// 32 of them.  Key/value tiles of 64 rows go from HBM/L2 straight into one of
+// two LDS stages (see attn_tiles.h) while the other stage is consumed.
 //
 // Everything is computed transposed so that a lane owns ONE query:
 //   S^T[j][q] = sum_c K[j][c] Q[q][c]     A operand = K rows   (ds_read_b128)
@@ -22,42 +22,27 @@
 // Mask: query p sees keys j < row_limit(p).  The loop over key tiles stops at
 // the last tile any query of the workgroup can see (whole-tile skipping); only
 // tiles that straddle a wave's limits evaluate the per-element predicate.
-#include "common.h"
+#include "attn_tiles.h"
 
 namespace beagle {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
-typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4_t;
-typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+using namespace tiles;
 
 namespace fwd {
-constexpr int HD = 128;           // head width
 constexpr int BQ = 128;           // queries per workgroup
 constexpr int BJ = 64;            // keys per tile
-constexpr int KLD = HD + 8;       // K tile row stride (elements): conflict-free b128 reads
-constexpr int VLD = HD + 32;      // V tile row stride: conflict-free transpose reads
-constexpr int K_ELEMS = BJ * KLD, V_ELEMS = BJ * VLD;
-constexpr int STAGE = K_ELEMS + V_ELEMS;
-constexpr int CHUNKS = BJ * HD / 8 / 256;   // 16-byte chunks per thread per tile
+constexpr int TILE = BJ * HD;     // elements of one K or V tile
 }  // namespace fwd
-
-__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
-  f32x2_t f = {lo, hi};
-  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
-  return *(uint32_t*)&b;
-}
 
 __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   using namespace fwd;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
+  __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, ql = lane & 31;
   const int nqt = (a.S + BQ - 1) / BQ;
-  const int qt = nqt - 1 - blockIdx.x;            // heaviest (latest) query tiles first
-  const int h = blockIdx.y, b = blockIdx.z;
+  int row, tpos;
+  map_block(blockIdx.x, a.H * a.B, row, tpos);
+  const int qt = nqt - 1 - tpos;                  // heaviest (latest) query tiles first
+  const int h = row % a.H, b = row / a.H;
   const int g = h / (a.H / a.G);
   const int q0 = qt * BQ;
   const int qw0 = q0 + wave * 32;                 // first query of this wave
@@ -66,9 +51,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   const int qc = q_ok ? q : a.S - 1;
 
   const bf16_t* Qg = (const bf16_t*)a.q + (((int64_t)b * a.S + qc) * a.H + h) * HD;
-  const bf16_t* Kg = (const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD;
-  const bf16_t* Vg = (const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD;
   const int64_t kvs = (int64_t)a.G * HD;
+  const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
+  const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
 
   const int lim = q_ok ? row_limit(q, a.mask) : 0;                 // keys visible to this lane's query
   const int q_last = min(q0 + BQ, a.S) - 1;
@@ -89,48 +74,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
   float m = -INFINITY, l = 0.f;
-  const float c2 = a.scale * 1.44269504088896340736f;   // scores are kept raw; exp2((s - m) * c2)
+  const float c2 = a.scale * LOG2E;               // scores are kept raw; exp2((s - m) * c2)
+  const FragOffs fo = make_frag_offs(lane);
 
-  i32x4_t kr[CHUNKS], vr[CHUNKS];
-  auto load_tile = [&](int jt) {
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int c = tid + 256 * i, r = c >> 4, col = (c & 15) * 8;
-      const int j = jt * BJ + r;
-      i32x4_t z = {0, 0, 0, 0};
-      kr[i] = z; vr[i] = z;
-      if (j < a.L) {
-        kr[i] = *(const i32x4_t*)(Kg + j * kvs + col);
-        vr[i] = *(const i32x4_t*)(Vg + j * kvs + col);
-      }
-    }
-  };
-  auto store_tile = [&](int stage) {
-    bf16_t* ks = smem + stage * STAGE;
-    bf16_t* vs = ks + K_ELEMS;
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-      const int c = tid + 256 * i, r = c >> 4, col = (c & 15) * 8;
-      *(i32x4_t*)(ks + r * KLD + col) = kr[i];
-      *(i32x4_t*)(vs + r * VLD + col) = vr[i];
-    }
+  auto fetch = [&](bf16_t* st, int jt) {
+    load_rows<BJ>(st, krs, kvs, jt * BJ, tid);
+    load_rows<BJ>(st + TILE, vrs, kvs, jt * BJ, tid);
   };
 
-  if (ntiles > 0) {
-    load_tile(0);
-    store_tile(0);
-  }
-  __syncthreads();
-
-#pragma unroll 1
-  for (int jt = 0; jt < ntiles; ++jt) {
-    const int cur = jt & 1;
-    const bool more = jt + 1 < ntiles;
-    if (more) load_tile(jt + 1);
+  auto tile_step = [&](const bf16_t* cur, bf16_t* nxt, int jt) {
+    fetch(nxt, jt + 1);                           // past the last tile: zeros / unused, harmless
+    __builtin_amdgcn_sched_barrier(0);
     const int j0 = jt * BJ;
-    if (j0 < wave_hi) {                                  // wave-uniform: this wave sees part of the tile
-      const bf16_t* ks = smem + cur * STAGE;
-      const bf16_t* vs = ks + K_ELEMS;
+    if (j0 < wave_hi) {                           // wave-uniform: this wave sees part of the tile
+      const bf16_t* ks = cur;
+      const bf16_t* vs = cur + TILE;
       // ---- S^T = K Q^T  (two blocks of 32 keys)
       f32x16_t st[2];
 #pragma unroll
@@ -138,10 +96,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) st[jb][e] = 0.f;
 #pragma unroll
-        for (int s = 0; s < HD / 16; ++s) {
-          bf16x8_t kf = *(const bf16x8_t*)(ks + (jb * 32 + ql) * KLD + 16 * s + 8 * hf);
-          st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], st[jb], 0, 0, 0);
-        }
+        for (int s = 0; s < HD / 16; ++s)
+          st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(ks, fo, jb, s), qf[s], st[jb], 0, 0, 0);
       }
       // ---- mask (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4)
       if (j0 + BJ > wave_lo) {
@@ -173,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
           const float p0 = __builtin_amdgcn_exp2f(st[jb][e] * c2 - mc);
           const float p1 = __builtin_amdgcn_exp2f(st[jb][e + 1] * c2 - mc);
           rs += p0 + p1;
-          pk[jb][e >> 1] = cvt_pk_bf16(p0, p1);
+          pk[jb][e >> 1] = cvt_pk(p0, p1);
         }
       rs += __shfl_xor(rs, 32, 64);
       l = l * alpha + rs;
@@ -182,8 +138,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
-      // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7, i.e. keys
-      //      32 jb + 16 t + {4 hf + 0..3, 8 + 4 hf + 0..3}
+      // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
@@ -191,21 +146,27 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
 #pragma unroll
           for (int i = 0; i < 4; ++i) pf.u[i] = pk[jb][4 * t + i];
-          const int gi = lane >> 4, r = lane & 15;
-          const int row = 32 * jb + 16 * t + 4 * (gi >> 1) + (r >> 2);
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            const bf16_t* p = vs + row * VLD + 32 * cb + 16 * (gi & 1) + 4 * (r & 3);
-            union { struct { s16x4_t x, y; } s; bf16x8_t v; } vf;
-            vf.s.x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
-            vf.s.y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * VLD));
-            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf.v, o[cb], 0, 0, 0);
-          }
+          for (int cb = 0; cb < 4; ++cb)
+            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(vs, fo, 32 * jb + 16 * t, cb), pf.v, o[cb], 0, 0, 0);
         }
     }
-    if (more) store_tile(cur ^ 1);
+    wait_vmem();
     __syncthreads();
+  };
+
+  if (ntiles > 0) {
+    fetch(stage0, 0);
+    wait_vmem();
   }
+  __syncthreads();
+  int jt = 0;
+#pragma unroll 1
+  for (; jt + 2 <= ntiles; jt += 2) {
+    tile_step(stage0, stage1, jt);
+    tile_step(stage1, stage0, jt + 1);
+  }
+  if (jt < ntiles) tile_step(stage0, stage1, jt);
 
   // ---- normalise and store: register e of block cb is channel 32 cb + 8 (e/4) + 4 hf + e%4
   if (q_ok) {
@@ -215,8 +176,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
-        uint2 v = {cvt_pk_bf16(o[cb][4 * qd] * inv, o[cb][4 * qd + 1] * inv),
-                   cvt_pk_bf16(o[cb][4 * qd + 2] * inv, o[cb][4 * qd + 3] * inv)};
+        uint2 v = {cvt_pk(o[cb][4 * qd] * inv, o[cb][4 * qd + 1] * inv),
+                   cvt_pk(o[cb][4 * qd + 2] * inv, o[cb][4 * qd + 3] * inv)};
         *(uint2*)(Og + 32 * cb + 8 * qd + 4 * hf) = v;
       }
     if (hf == 0)
@@ -225,16 +186,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
 }
 
 void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s) {
-  using namespace fwd;
-  constexpr size_t smem = 2 * (size_t)STAGE * sizeof(bf16_t);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)attn_fwd_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    attr_set = true;
-  }
   ProfScope ps("attn_fwd_bf16", s);
-  dim3 grid((a.S + BQ - 1) / BQ, a.H, a.B);
-  hipLaunchKernelGGL(attn_fwd_bf16_kernel, grid, dim3(256), smem, s, a);
+  dim3 grid(((a.S + fwd::BQ - 1) / fwd::BQ) * a.H * a.B);
+  hipLaunchKernelGGL(attn_fwd_bf16_kernel, grid, dim3(256), 0, s, a);
 }
 
 }  // namespace beagle

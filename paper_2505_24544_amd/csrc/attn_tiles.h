@@ -1,0 +1,116 @@
+// LDS tile helpers shared by the bf16 attention kernels (head width 128).
+//
+// A tile holds rows of 128 channels (256 B, 16 chunks of 16 B) in HBM order.
+// Chunk c of row r is stored at chunk position c ^ swz(r), swz(r) =
+// ((r & 3) << 2) | ((r >> 2) & 3).  With that, both access patterns are free of
+// bank conflicts on the same tile:
+//   row_frag : MFMA operand whose k index is the channel  (one ds_read_b128)
+//   tr_frag  : MFMA operand whose k index is the row      (two ds_read_b64_tr_b16)
+// Tiles are filled straight from HBM/L2 (buffer_load ... lds): a lane's 16 bytes
+// land at wave_base + 16 * lane, so the swizzle is applied by choosing WHICH
+// global chunk each lane fetches.  Rows past the end of the buffer descriptor
+// arrive as zeros.
+#pragma once
+#include "common.h"
+
+namespace beagle {
+namespace tiles {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+constexpr int HD = 128;                 // head width = elements per tile row
+constexpr float LOG2E = 1.44269504088896340736f;
+
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// Buffer descriptor over `rows` rows of 128 channels that are `stride` elements apart.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_rsrc(const bf16_t* base, int rows, int64_t stride) {
+  const int64_t bytes = rows > 0 ? ((int64_t)(rows - 1) * stride + HD) * 2 : 0;
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+// Fill a tile of R rows (R * 16 chunks, 256 threads) with global rows row0 .. row0 + R - 1.
+template <int R>
+__device__ __forceinline__ void load_rows(bf16_t* tile, __amdgpu_buffer_rsrc_t rsrc, int64_t stride, int row0, int tid) {
+  const int wave = tid >> 6;
+#pragma unroll
+  for (int i = 0; i < R * 16 / 256; ++i) {
+    const int q = tid + 256 * i, r = q >> 4, c = (q & 15) ^ swz(r);
+    const int off = (int)(((int64_t)(row0 + r) * stride + 8 * c) * 2);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (i * 4 + wave) * 512), 16, off, 0, 0, 0);
+  }
+}
+
+// Per-lane element offsets of the two fragment kinds, computed once.  Tile
+// bases, 32-row blocks and 16-row steps then add compile-time constants (they
+// do not change swz), so that the reads use immediate offsets instead of one
+// address register per fragment.
+struct FragOffs {
+  int row[8];      // row_frag: (lane % 32) * 128 + swizzled chunk of k step s
+  int tr[4][2];    // tr_frag : channel block cb, rows {4 hf + 0..3} and {8 + 4 hf + 0..3}
+};
+
+__device__ __forceinline__ FragOffs make_frag_offs(int lane) {
+  FragOffs f;
+  const int ql = lane & 31, hf = lane >> 5;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) f.row[s] = ql * HD + (((2 * s + hf) ^ swz(ql)) << 3);
+  const int gi = lane >> 4, r = lane & 15;
+  const int row = 4 * (gi >> 1) + (r >> 2);
+  const int sub = 4 * (r & 1);
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) {
+    const int chunk = 4 * cb + 2 * (gi & 1) + ((r & 3) >> 1);
+    f.tr[cb][0] = row * HD + ((chunk ^ swz(row)) << 3) + sub;
+    f.tr[cb][1] = (row + 8) * HD + ((chunk ^ swz(row + 8)) << 3) + sub;
+  }
+  return f;
+}
+
+// whole-row fragment: row 32 * blk + lane % 32, channels 16 s + 8 hf .. + 7  (k index = channel)
+__device__ __forceinline__ bf16x8_t row_frag(const bf16_t* tile, const FragOffs& f, int blk, int s) {
+  return *(const bf16x8_t*)(tile + blk * 32 * HD + f.row[s]);
+}
+
+// transpose fragment: lane gets rows rowbase + {4 hf + 0..3, 8 + 4 hf + 0..3} of channel 32 cb + lane % 32
+// (k index = row).  With rowbase = 32 * blk + 16 * t (a multiple of 16) this is exactly the key/query order
+// of accumulator registers 8t .. 8t+7 of a 32x32 MFMA output block.
+__device__ __forceinline__ bf16x8_t tr_frag(const bf16_t* tile, const FragOffs& f, int rowbase, int cb) {
+  union { struct { s16x4_t x, y; } s; bf16x8_t v; } u;
+  u.s.x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + rowbase * HD + f.tr[cb][0]));
+  u.s.y = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + rowbase * HD + f.tr[cb][1]));
+  return u.v;
+}
+
+__device__ __forceinline__ uint32_t cvt_pk(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return *(uint32_t*)&b;
+}
+
+// Workgroup id -> (row, tile position) for a staircase-shaped workload: `rows`
+// independent (batch, head) rows, each with tiles of decreasing cost along the
+// tile position.  Ids are dealt round-robin to the 8 XCDs, so: every XCD gets
+// the same mix of tile positions (balanced), positions are visited heavy-first
+// chip-wide, and all tiles of one row land on one XCD (its K/V stay in that L2).
+__device__ __forceinline__ void map_block(int n, int rows, int& row, int& tpos) {
+  if (rows % 8 == 0) {
+    const int c = n & 7, i = n >> 3, r8 = rows >> 3;
+    row = (i % r8) * 8 + c;
+    tpos = i / r8;
+  } else {
+    row = n % rows;
+    tpos = n / rows;
+  }
+}
+
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+}  // namespace tiles
+}  // namespace beagle

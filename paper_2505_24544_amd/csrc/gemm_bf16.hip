@@ -85,19 +85,41 @@ __device__ __forceinline__ void load_slice(bf16_t* tile, __amdgpu_buffer_rsrc_t 
   }
 }
 
-// MFMA operand fragment: lane l gets row (r0 + l % 32), k = kk + 8 * (l / 32) .. + 7.
-template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ bf16x8_t read_frag(const bf16_t* tile, int r0, int kk, int lane) {
+// Per-lane element offsets of an operand's fragments inside its tile, computed
+// once per kernel.  Everything that varies inside the k loop (the 32-row block
+// for k-contiguous tiles, the k step for both) is then a compile-time constant
+// added to one of these, i.e. an immediate offset of the LDS read.
+//   KMAJOR : o[ks]  = row (l % 32), swizzled chunk of k step ks       (+ 32-row block * BK)
+//   !KMAJOR: o[blk] = k-row (8 (l/32) + (l%16)/4), swizzled column of block blk   (+ k step * 16 * ROWS)
+template <int ROWS, bool KMAJOR, int NBLK>
+struct FragOffs {
+  int o[KMAJOR ? BK / 16 : NBLK];
+  __device__ __forceinline__ void init(int lane, int r0) {
+    if (KMAJOR) {
+      const int ql = lane & 31, hf = lane >> 5;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) o[ks] = (r0 + ql) * BK + (((2 * ks + hf) ^ ((ql >> 1) & 7)) << 3);
+    } else {
+      const int gi = lane >> 4, r16 = lane & 15;
+      const int kr = 8 * (gi >> 1) + (r16 >> 2);
+#pragma unroll
+      for (int b = 0; b < NBLK; ++b) {
+        const int col = r0 + 32 * b + 16 * (gi & 1) + 4 * (r16 & 3);
+        o[b] = kr * ROWS + ((((col >> 3) ^ ((kr & 3) << 2)) << 3) | (col & 7));
+      }
+    }
+  }
+};
+
+// MFMA operand fragment: lane l gets row (r0 + 32 blk + l % 32), k = 16 ks + 8 * (l / 32) .. + 7.
+template <int ROWS, bool KMAJOR, int NBLK>
+__device__ __forceinline__ bf16x8_t read_frag(const bf16_t* tile, const FragOffs<ROWS, KMAJOR, NBLK>& f, int blk, int ks) {
   if (KMAJOR) {
-    const int r = r0 + (lane & 31), c = (kk >> 3) + (lane >> 5);
-    return *(const bf16x8_t*)(tile + r * BK + ((c ^ ((r >> 1) & 7)) << 3));
+    return *(const bf16x8_t*)(tile + blk * 32 * BK + f.o[ks]);
   } else {
     // transpose read: the 16 lanes of a group pass the addresses of 4 k-rows x
     // 4 pieces of 4 rows; lane l of the group receives k-rows 0..3 of row l.
-    const int gi = lane >> 4, r16 = lane & 15;
-    const int kr = kk + 8 * (gi >> 1) + (r16 >> 2);          // kr & 3 == (kr + 4) & 3
-    const int col = r0 + 16 * (gi & 1) + 4 * (r16 & 3);
-    const bf16_t* p = tile + kr * ROWS + ((((col >> 3) ^ ((kr & 3) << 2)) << 3) | (col & 7));
+    const bf16_t* p = tile + ks * 16 * ROWS + f.o[blk];
     union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
     u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
     u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * ROWS));
@@ -139,6 +161,11 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * (32 * TM), wn = (wave & 1) * (32 * TN);
 
+  FragOffs<BM, XK, TM> xo;
+  FragOffs<BN, WK, TN> wo;
+  xo.init(lane, wm);
+  wo.init(lane, wn);
+
   f32x16_t acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -163,11 +190,11 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
       load_slice<BM, XK>(st, xrs, ldx, m0, k0, tid);
       load_slice<BN, WK>(st + XE, wrs, ldw, n0, k0, tid);
     };
-    auto frags = [&](const bf16_t* st, int fb, int kk) {
+    auto frags = [&](const bf16_t* st, int fb, int ks) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) xf[fb][i] = read_frag<BM, XK>(st, wm + 32 * i, kk, lane);
+      for (int i = 0; i < TM; ++i) xf[fb][i] = read_frag<BM, XK, TM>(st, xo, i, ks);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) wf[fb][j] = read_frag<BN, WK>(st + XE, wn + 32 * j, kk, lane);
+      for (int j = 0; j < TN; ++j) wf[fb][j] = read_frag<BN, WK, TN>(st + XE, wo, j, ks);
     };
     // one k slice: loads of the next slice fly into `nxt` while `cur` is consumed
     auto slice = [&](const bf16_t* cur, bf16_t* nxt, int kt) {
@@ -176,12 +203,25 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
         const int fb = ks & 1;
-        if (ks + 1 < BK / 16) frags(cur, fb ^ 1, 16 * (ks + 1));
+        if (ks + 1 < BK / 16) frags(cur, fb ^ 1, ks + 1);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb][j], xf[fb][i], acc[i][j], 0, 0, 0);
+        // issue order: the LDS reads of the next step go out right behind the first MFMAs of
+        // this one, so their latency is covered by the rest of the step
+        if (ks + 1 < BK / 16) {
+          constexpr int NREADS = (XK ? TM : 2 * TM) + (WK ? TN : 2 * TN);
+#pragma unroll
+          for (int t = 0; t < NREADS / 2; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NREADS / 2, 0);
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        }
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's chunks of the next slice are in LDS
       __syncthreads();                      // everyone's are, and everyone is done reading `cur`
