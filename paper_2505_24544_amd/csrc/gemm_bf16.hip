@@ -196,36 +196,54 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
 #pragma unroll
       for (int j = 0; j < TN; ++j) wf[fb][j] = read_frag<BN, WK, TN>(st + XE, wo, j, ks);
     };
-    // one k slice: loads of the next slice fly into `nxt` while `cur` is consumed
+    auto mfmas = [&](int fb) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb][j], xf[fb][i], acc[i][j], 0, 0, 0);
+    };
+    constexpr int NSTEP = BK / 16;                                      // k steps per slice (4)
+    constexpr int NREADS = (XK ? TM : 2 * TM) + (WK ? TN : 2 * TN);     // LDS reads per k step
+    constexpr int NLOADS = (BM + BN) * BK / 8 / 256;                    // HBM->LDS loads per thread per slice
+    static_assert(NSTEP == 4 && NLOADS % 2 == 0 && NREADS % 2 == 0, "issue pattern below assumes this");
+    // One k slice.  Issue order (enforced with sched_group_barrier so that the
+    // in-order wave never sits on a queue while the MFMA pipe is idle):
+    //   steps 0,1 : MFMAs interleaved with the LDS reads of the next step and
+    //               with half of the next slice's HBM->LDS loads each
+    //   step 2    : MFMAs + LDS reads of step 3
+    //   wait for this thread's loads, barrier (next slice visible, `cur` free)
+    //   step 3    : MFMAs from registers, while the first fragments of the next
+    //               slice are already being read
     auto slice = [&](const bf16_t* cur, bf16_t* nxt, int kt) {
       fetch(nxt, (kt + 1) * BK);      // past the last slice this fetches zeros / unused rows: harmless
-      __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the MFMAs that hide their latency
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
+      for (int ks = 0; ks < NSTEP - 1; ++ks) {
         const int fb = ks & 1;
-        if (ks + 1 < BK / 16) frags(cur, fb ^ 1, ks + 1);
+        frags(cur, fb ^ 1, ks + 1);
+        mfmas(fb);
+        constexpr int HALF = NLOADS / 2;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fb][j], xf[fb][i], acc[i][j], 0, 0, 0);
-        // issue order: the LDS reads of the next step go out right behind the first MFMAs of
-        // this one, so their latency is covered by the rest of the step
-        if (ks + 1 < BK / 16) {
-          constexpr int NREADS = (XK ? TM : 2 * TM) + (WK ? TN : 2 * TN);
-#pragma unroll
-          for (int t = 0; t < NREADS / 2; ++t) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-          }
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NREADS / 2, 0);
-        } else {
-          __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        for (int t = 0; t < NREADS / 2; ++t) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          if (ks < 2 && t < HALF) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
+        if (ks < 2) {
+#pragma unroll
+          for (int t = NREADS / 2; t < HALF; ++t) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          }
+        }
+        constexpr int USED = (NREADS / 2 > HALF ? NREADS / 2 : HALF);
+        if (ks < 2) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - USED, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NREADS / 2, 0);
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's chunks of the next slice are in LDS
       __syncthreads();                      // everyone's are, and everyone is done reading `cur`
       frags(nxt, 0, 0);
+      mfmas((NSTEP - 1) & 1);
     };
 
     __syncthreads();                        // previous segment: all reads done, both stages free
