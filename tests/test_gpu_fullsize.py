@@ -18,6 +18,10 @@ pytestmark = pytest.mark.gpu
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 OUT_ABS, OUT_FRO, LSE_TOL, GRAD_FRO = 2e-2, 1e-2, 1e-3, 3e-2
+# Peaked-query variant (not one of the five configs): scores have std ~1.6, and the saved Q/K are rounded to
+# bf16 (unit roundoff 2^-9), which moves a score by ~2.6e-3 rms.  A row with few visible keys inherits that
+# directly in its LSE; 1.5e-2 is ~6 sigma (derivation in the design doc).
+LSE_TOL_PEAKED = 1.5e-2
 
 
 def _gather(t: torch.Tensor, idx: np.ndarray) -> np.ndarray:
@@ -51,7 +55,7 @@ def test_fullsize_sampled_parity(name):
         if tname.startswith("lse"):
             fin = np.isfinite(ref)
             assert np.array_equal(np.isneginf(got), ~fin), tname
-            tol = 4e-3 if peaked else LSE_TOL
+            tol = LSE_TOL_PEAKED if peaked else LSE_TOL
             assert gh.max_abs(got[fin], ref[fin]) <= tol, (tname, gh.max_abs(got[fin], ref[fin]))
         elif tname.startswith("d"):
             assert np.isfinite(got).all(), tname
