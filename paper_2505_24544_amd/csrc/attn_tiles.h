@@ -110,7 +110,14 @@ __device__ __forceinline__ void map_block(int n, int rows, int& row, int& tpos) 
   }
 }
 
-__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).  Memory loads complete in
+// order, so vmcnt(N) means "all but the N youngest loads have landed".
+template <int N>
+__device__ __forceinline__ void wait_vmem_n() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_vmem() { wait_vmem_n<0>(); }
 
 }  // namespace tiles
 }  // namespace beagle
