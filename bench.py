@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -105,6 +107,12 @@ def main():
         bx.beagle_xattn_bwd(desc, t["dy"], t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], q, k, v, o, lse,
                             dxq, dxkv, dwq, dwk, dwv, dwo, ws_b, stream)
 
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
