@@ -27,6 +27,14 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# HBM-side bytes per launch (fetched + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+# scaled by a plain 1 GiB copy in the same run (profiles/hbm_traffic_c2_c4.md).  Counters cannot be read
+# from inside this process, so the figures are carried here for the workload they were measured on.
+MEASURED_TRAFFIC_BYTES = {
+    "c2": {"proj_qkv": 1216e6 + 201e6, "proj_out": 405e6 + 67e6, "bwd_dout": 410e6 + 67e6, "bwd_dwo": 403e6 + 34e6,
+           "bwd_dx": 1229e6 + 134e6, "bwd_dw": 1208e6 + 101e6},
+}
+
 
 def flops_training(cfg, need_dxkv=True):
     """Algorithmic FLOPs of one forward+backward (unmasked pairs only)."""
@@ -141,7 +149,8 @@ def main():
         avg = prof[dom][1] / prof[dom][0]
         ach = kf.get(dom, 0) / (avg * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom, achieved=round(ach, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None, avg_ms=round(avg, 4),
+                        frac=round(ach / PEAK_BF16_TFLOPS, 4),
+                        traffic=MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom), avg_ms=round(avg, 4),
                         flops_per_launch=kf.get(dom))
 
     # ---- decode: draft step, cold HBM via buffer rotation
