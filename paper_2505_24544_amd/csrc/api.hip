@@ -320,9 +320,11 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
     g.count = 1;
     g.p[0] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
     if (need_dxkv) {
+      // deeper problem first: dXkv contracts over the K and the V columns
       g.count = 2;
-      g.p[1] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
-      g.p[1].A2 = dV; g.p[1].B2 = wv; g.p[1].K2 = (int32_t)d.GD; g.p[1].lda2 = d.GD; g.p[1].ldb2 = d.GD;
+      g.p[1] = g.p[0];
+      g.p[0] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
+      g.p[0].A2 = dV; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
     }
     run_gemm(d, g, s, "bwd_dx");
   }

@@ -127,10 +127,25 @@ __device__ __forceinline__ bf16x8_t read_frag(const bf16_t* tile, const FragOffs
   }
 }
 
-__device__ __forceinline__ int remap_xcd(int pid, int total) {
-  const int base = total / NUM_XCD, rem = total % NUM_XCD;
-  const int xcd = pid % NUM_XCD, idx = pid / NUM_XCD;
-  return xcd * base + (xcd < rem ? xcd : rem) + idx;
+// Workgroup id -> (problem, tile index inside the problem).  Ids are dealt
+// round-robin to the 8 XCDs; every problem's tiles are split evenly over the
+// XCDs (contiguous runs, so neighbouring tiles share an L2), and an XCD walks
+// the problems in order.  Remainder tiles of successive problems go to
+// successive XCDs, which keeps the per-XCD totals equal to what the hardware
+// deals out.  Problems of different depth (dXkv has twice the k of dXq) are thus
+// balanced across XCDs instead of being concentrated on some of them.
+__device__ __forceinline__ void map_tile(int pid, const int* tiles, int count, int& prob, int& local) {
+  const int c = pid % NUM_XCD;
+  int idx = pid / NUM_XCD, off = 0;
+  prob = count - 1; local = 0;
+  for (int p = 0; p < count; ++p) {
+    const int base = tiles[p] / NUM_XCD, rem = tiles[p] % NUM_XCD;
+    const int r = (c - off + NUM_XCD) % NUM_XCD;
+    const int cnt = base + (r < rem ? 1 : 0);
+    if (idx < cnt || p + 1 == count) { prob = p; local = r * base + (r < rem ? r : rem) + idx; return; }
+    idx -= cnt;
+    off = (off + rem) % NUM_XCD;
+  }
 }
 
 template <int TM, int TN, bool XK, bool WK, bool F32OUT>
@@ -141,16 +156,15 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[XE + WE];
 
   // ---- which tile of which problem
-  int pid = remap_xcd(blockIdx.x, total_tiles);
-  int pi = 0, tiles_m = 0, tiles_n = 0;
-  for (;; ++pi) {
-    tiles_m = (grp.p[pi].M + BM - 1) / BM;
-    tiles_n = (grp.p[pi].N + BN - 1) / BN;
-    const int t = tiles_m * tiles_n;
-    if (pid < t || pi + 1 == grp.count) break;
-    pid -= t;
-  }
+  int ntile[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    ntile[i] = i < grp.count ? ((grp.p[i].M + BM - 1) / BM) * ((grp.p[i].N + BN - 1) / BN) : 0;
+  int pi, pid;
+  map_tile(blockIdx.x, ntile, grp.count, pi, pid);
   const GemmArgs& g = grp.p[pi];
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  (void)total_tiles;
   const int per_group = GROUP_M * tiles_n;
   const int first_m = (pid / per_group) * GROUP_M;
   const int gsz = min(tiles_m - first_m, GROUP_M);
