@@ -122,6 +122,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
           dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(vs, fo, jb, s), dof[s], dp[jb], 0, 0, 0);
         }
       }
+      pipeline_reads_mfma<32, 1>();
+      __builtin_amdgcn_sched_barrier(0);
       const bool partial = j0 + BJ > wave_lo;
       uint32_t pk[2][8];
 #pragma unroll
@@ -138,6 +140,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
           }
           pk[jb][e >> 1] = cvt_pk(ds[0], ds[1]);
         }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
@@ -149,6 +152,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
           for (int cb = 0; cb < 4; ++cb)
             dq[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(ks, fo, 32 * jb + 16 * t, cb), sf.v, dq[cb], 0, 0, 0);
         }
+      pipeline_reads_mfma<16, 2>();
+      __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmem();
     __syncthreads();
@@ -265,6 +270,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
           dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(dsm, fo, qb, s), vf[s], dp[qb], 0, 0, 0);
         }
       }
+      pipeline_reads_mfma<32, 1>();
+      __builtin_amdgcn_sched_barrier(0);
       // register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key
       const bool partial = q0 < wave_all;
       uint32_t pp[2][8], pd[2][8];
@@ -289,6 +296,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
           pp[qb][2 * e4] = cvt_pk(pv[0], pv[1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[2], pv[3]);
           pd[qb][2 * e4] = cvt_pk(dsv[0], dsv[1]); pd[qb][2 * e4 + 1] = cvt_pk(dsv[2], dsv[3]);
         }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
@@ -302,6 +310,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
             dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qsm, fo, 32 * qb + 16 * t, cb), sf.v, dk[cb], 0, 0, 0);
           }
         }
+      pipeline_reads_mfma<32, 2>();
+      __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmem();
     __syncthreads();

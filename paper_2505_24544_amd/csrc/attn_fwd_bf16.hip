@@ -99,6 +99,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
         for (int s = 0; s < HD / 16; ++s)
           st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(ks, fo, jb, s), qf[s], st[jb], 0, 0, 0);
       }
+      pipeline_reads_mfma<16, 1>();
+      __builtin_amdgcn_sched_barrier(0);
       // ---- mask (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4)
       if (j0 + BJ > wave_lo) {
 #pragma unroll
@@ -139,6 +141,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
       // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
@@ -150,6 +153,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
           for (int cb = 0; cb < 4; ++cb)
             o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(vs, fo, 32 * jb + 16 * t, cb), pf.v, o[cb], 0, 0, 0);
         }
+      pipeline_reads_mfma<16, 2>();
+      __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmem();
     __syncthreads();

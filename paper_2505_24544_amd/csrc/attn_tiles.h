@@ -110,6 +110,21 @@ __device__ __forceinline__ void map_block(int n, int rows, int& row, int& tpos) 
   }
 }
 
+// Issue-order hints for a run of N MFMAs that each consume RPM LDS reads (1 for
+// a whole-row fragment, 2 for a transpose fragment): keep four fragments in
+// flight ahead of the MFMA that uses them instead of read-wait-MFMA per step.
+// The caller fences the run with __builtin_amdgcn_sched_barrier(0) on both sides.
+template <int N, int RPM>
+__device__ __forceinline__ void pipeline_reads_mfma() {
+  __builtin_amdgcn_sched_group_barrier(0x100, 4 * RPM, 0);
+#pragma unroll
+  for (int i = 0; i < N - 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+}
+
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).  Memory loads complete in
 // order, so vmcnt(N) means "all but the N youngest loads have landed".
