@@ -200,10 +200,8 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
     const __amdgpu_buffer_rsrc_t wrs = make_rsrc(W, (int64_t)(WK ? g.N : K) * ldw * 2);
 
     bf16x8_t xf[2][TM], wf[2][TN];
-    auto fetch = [&](bf16_t* st, int k0) {
-      load_slice<BM, XK>(st, xrs, ldx, m0, k0, tid);
-      load_slice<BN, WK>(st + XE, wrs, ldw, n0, k0, tid);
-    };
+    auto fetch_x = [&](bf16_t* st, int k0) { load_slice<BM, XK>(st, xrs, ldx, m0, k0, tid); };
+    auto fetch_w = [&](bf16_t* st, int k0) { load_slice<BN, WK>(st + XE, wrs, ldw, n0, k0, tid); };
     auto frags = [&](const bf16_t* st, int fb, int ks) {
 #pragma unroll
       for (int i = 0; i < TM; ++i) xf[fb][i] = read_frag<BM, XK, TM>(st, xo, i, ks);
@@ -219,52 +217,52 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
     };
     constexpr int NSTEP = BK / 16;                                      // k steps per slice (4)
     constexpr int NREADS = (XK ? TM : 2 * TM) + (WK ? TN : 2 * TN);     // LDS reads per k step
-    constexpr int NLOADS = (BM + BN) * BK / 8 / 256;                    // HBM->LDS loads per thread per slice
-    static_assert(NSTEP == 4 && NLOADS % 2 == 0 && NREADS % 2 == 0, "issue pattern below assumes this");
-    // One k slice.  Issue order (enforced with sched_group_barrier so that the
-    // in-order wave never sits on a queue while the MFMA pipe is idle):
-    //   steps 0,1 : MFMAs interleaved with the LDS reads of the next step and
-    //               with half of the next slice's HBM->LDS loads each
-    //   step 2    : MFMAs + LDS reads of step 3
-    //   wait for this thread's loads, barrier (next slice visible, `cur` free)
-    //   step 3    : MFMAs from registers, while the first fragments of the next
-    //               slice are already being read
-    auto slice = [&](const bf16_t* cur, bf16_t* nxt, int kt) {
-      fetch(nxt, (kt + 1) * BK);      // past the last slice this fetches zeros / unused rows: harmless
+    constexpr int XLOADS = BM * BK / 8 / 256, WLOADS = BN * BK / 8 / 256;   // HBM->LDS loads per thread per slice
+    static_assert(NSTEP == 4 && NREADS % 2 == 0 && NREADS / 2 <= TM * TN, "issue pattern below assumes this");
+    static_assert(XLOADS <= TM * TN && WLOADS <= TM * TN, "one load per MFMA at most");
+    // One k slice.  On entry: slice kt is visible in `cur` and its step-0 fragments are in
+    // registers; the X half of slice kt+1 is already on its way into `nxt`.
+    //   step 0    : MFMAs + LDS reads of step 1 + the W half of slice kt+1 (one load per MFMA)
+    //   steps 1,2 : MFMAs + LDS reads of the next step
+    //   wait for this thread's loads, barrier: slice kt+1 visible, nobody reads `cur` any more
+    //   step 3    : MFMAs from registers + first fragment reads of slice kt+1 + the X half of
+    //               slice kt+2 into `cur`
+    // so every HBM->LDS load is issued at least two k steps (>= 1000 cycles) before it is
+    // waited for, and the in-order wave never waits on a queue while the MFMA pipe is idle.
+    auto slice = [&](bf16_t* cur, bf16_t* nxt, int kt) {
+      fetch_w(nxt, (kt + 1) * BK);    // past the last slice these fetch zeros / unused rows: harmless
 #pragma unroll
       for (int ks = 0; ks < NSTEP - 1; ++ks) {
         const int fb = ks & 1;
         frags(cur, fb ^ 1, ks + 1);
         mfmas(fb);
-        constexpr int HALF = NLOADS / 2;
 #pragma unroll
-        for (int t = 0; t < NREADS / 2; ++t) {
+        for (int t = 0; t < TM * TN; ++t) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-          if (ks < 2 && t < HALF) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          if (t < NREADS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          if (ks == 0 && t < WLOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        if (ks < 2) {
-#pragma unroll
-          for (int t = NREADS / 2; t < HALF; ++t) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-          }
-        }
-        constexpr int USED = (NREADS / 2 > HALF ? NREADS / 2 : HALF);
-        if (ks < 2) __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - USED, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - NREADS / 2, 0);
       }
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this thread's chunks of the next slice are in LDS
       __syncthreads();                      // everyone's are, and everyone is done reading `cur`
       frags(nxt, 0, 0);
+      fetch_x(cur, (kt + 2) * BK);
       mfmas((NSTEP - 1) & 1);
+#pragma unroll
+      for (int t = 0; t < TM * TN; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (t < NREADS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        if (t < XLOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
     };
 
     __syncthreads();                        // previous segment: all reads done, both stages free
-    fetch(stage0, 0);
+    fetch_x(stage0, 0);
+    fetch_w(stage0, 0);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     frags(stage0, 0, 0);
+    fetch_x(stage1, BK);
     int kt = 0;
 #pragma unroll 1
     for (; kt + 2 <= nk; kt += 2) {
@@ -272,6 +270,7 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
       slice(stage1, stage0, kt + 1);
     }
     if (kt < nk) slice(stage0, stage1, kt);
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // drain the look-ahead loads before the stages are reused
   }
 
   // ---- epilogue: lane holds C row m = .. + lane % 32; register e of tile (i, j)
