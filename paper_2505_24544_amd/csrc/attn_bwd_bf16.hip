@@ -27,6 +27,7 @@
 // Mask: query p sees key j iff j < row_limit(p) iff p >= first_query_seeing(j).
 // Key tiles beyond a workgroup's last limit / query tiles before a key tile's
 // first viewer are never visited (whole-tile skipping).
+#include <type_traits>
 #include "attn_tiles.h"
 
 namespace beagle {
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   using namespace dqk;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, ql = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int nqt = (a.S + BQ - 1) / BQ;
   int row, tpos;
   map_block(blockIdx.x, a.H * a.B, row, tpos);
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
   __shared__ __attribute__((aligned(256))) float stat0[2 * BQ];    // [lse 64 | delta 64] of the stage's queries
   __shared__ __attribute__((aligned(256))) float stat1[2 * BQ];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, jl = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, jl = lane & 31;
   int row, jt;                                    // key tile 0 is seen by the most queries: heaviest first
   map_block(blockIdx.x, a.G * a.B, row, jt);
   const int g = row % a.G, b = row / a.G;
@@ -236,26 +237,32 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
 
   // Q / dO rows and the LSE / delta entries of tile `it`; rows and entries past
   // the sequence end arrive as zeros (zero Q and dO rows contribute nothing).
-  auto fetch = [&](bf16_t* st, float* stat, int it) {
-    const int hh = per_head > 0 ? it / per_head : 0;
-    const int h = g * rep + (hh < rep ? hh : rep - 1);
-    const int q0 = (qt0 + (per_head > 0 ? it % per_head : 0)) * BQ;
-    const int rows = it < iters ? a.S : 0;          // past the last pair: fetch zeros
-    const __amdgpu_buffer_rsrc_t qrs = rows_rsrc((const bf16_t*)a.q + ((int64_t)b * a.S * a.H + h) * HD, rows, qs);
-    const __amdgpu_buffer_rsrc_t drs = rows_rsrc((const bf16_t*)a.dout + ((int64_t)b * a.S * a.H + h) * HD, rows, qs);
-    load_rows<BQ>(st, qrs, qs, q0, tid);
-    load_rows<BQ>(st + TILE, drs, qs, q0, tid);
+  int f_hh = 0, f_qt = qt0;                         // fetch cursor: head within the group, query tile
+  int c_qt = qt0;                                   // compute cursor: query tile
+  const int64_t head0 = (int64_t)b * a.S * a.H + g * rep;
+  const bf16_t* f_q = (const bf16_t*)a.q + head0 * HD;           // row 0 of the fetch cursor's head
+  const bf16_t* f_do = (const bf16_t*)a.dout + head0 * HD;
+  const float* f_stat = (wave == 0 ? a.lse : a.delta) + ((int64_t)b * a.H + g * rep) * a.S;
+  auto fetch = [&](bf16_t* st, float* stat) {
+    const int q0 = f_qt * BQ;
+    const int rows = f_hh < rep ? a.S : 0;          // past the last pair: fetch zeros
+    load_rows<BQ>(st, rows_rsrc(f_q, rows, qs), qs, q0, tid);
+    load_rows<BQ>(st + TILE, rows_rsrc(f_do, rows, qs), qs, q0, tid);
     if (wave < 2) {
-      const float* src = (wave == 0 ? a.lse : a.delta) + ((int64_t)b * a.H + h) * a.S;
-      const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void*)src, 0, rows * 4, 0x00020000);
+      const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void*)f_stat, 0, rows * 4, 0x00020000);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(srs, (lds_void_ptr)(stat + wave * BQ), 4, (q0 + lane) * 4, 0, 0, 0);
+    }
+    if (++f_qt == nqt) {
+      f_qt = qt0;
+      if (++f_hh < rep) { f_q += HD; f_do += HD; f_stat += a.S; }
     }
   };
 
-  auto tile_step = [&](const bf16_t* cur, const float* sl, bf16_t* nxt, float* nstat, int it) {
-    fetch(nxt, nstat, it + 1);
+  auto tile_step = [&](const bf16_t* cur, const float* sl, bf16_t* nxt, float* nstat) {
+    fetch(nxt, nstat);
     __builtin_amdgcn_sched_barrier(0);
-    const int q0 = (qt0 + it % per_head) * BQ;
+    const int q0 = c_qt * BQ;
+    if (++c_qt == nqt) c_qt = qt0;
     if (q0 + BQ > wave_first) {                       // some query of the tile sees some key of the wave
       const bf16_t* qsm = cur;
       const bf16_t* dsm = cur + TILE;
@@ -273,29 +280,32 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       pipeline_reads_mfma<32, 1>();
       __builtin_amdgcn_sched_barrier(0);
       // register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key
-      const bool partial = q0 < wave_all;
       uint32_t pp[2][8], pd[2][8];
+      auto probs = [&](auto masked) {
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int r = 32 * qb + 8 * e4 + 4 * hf;
-          const float4 l4 = *(const float4*)(sl + r);
-          const float4 d4 = *(const float4*)(sl + BQ + r);
-          const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
-          const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
-          float pv[4], dsv[4];
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const int r = 32 * qb + 8 * e4 + 4 * hf;
+            const float4 l4 = *(const float4*)(sl + r);
+            const float4 d4 = *(const float4*)(sl + BQ + r);
+            const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
+            const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+            float pv[4], dsv[4];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int e = 4 * e4 + u;
-            float p = __builtin_amdgcn_exp2f(s2[qb][e] * c2 - ls[u] * LOG2E);
-            if (partial && q0 + r + u < fq) p = 0.f;     // also kills the +inf of blind queries (LSE = -inf)
-            pv[u] = p;
-            dsv[u] = p * (dp[qb][e] - dl[u]);
+            for (int u = 0; u < 4; ++u) {
+              const int e = 4 * e4 + u;
+              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][e], c2, -LOG2E * ls[u]));
+              if (decltype(masked)::value && q0 + r + u < fq) p = 0.f;   // also kills the +inf of blind queries (LSE = -inf)
+              pv[u] = p;
+              dsv[u] = p * (dp[qb][e] - dl[u]);
+            }
+            pp[qb][2 * e4] = cvt_pk(pv[0], pv[1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[2], pv[3]);
+            pd[qb][2 * e4] = cvt_pk(dsv[0], dsv[1]); pd[qb][2 * e4 + 1] = cvt_pk(dsv[2], dsv[3]);
           }
-          pp[qb][2 * e4] = cvt_pk(pv[0], pv[1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[2], pv[3]);
-          pd[qb][2 * e4] = cvt_pk(dsv[0], dsv[1]); pd[qb][2 * e4 + 1] = cvt_pk(dsv[2], dsv[3]);
-        }
+      };
+      // a blind query (LSE = -inf) is below fq for every key, so its tiles always take the masked form
+      if (q0 < wave_all) probs(std::true_type{}); else probs(std::false_type{});
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb)
@@ -317,15 +327,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     __syncthreads();
   };
 
-  if (iters > 0) { fetch(stage0, stat0, 0); wait_vmem(); }
+  if (iters > 0) { fetch(stage0, stat0); wait_vmem(); }
   __syncthreads();
   int it = 0;
 #pragma unroll 1
   for (; it + 2 <= iters; it += 2) {
-    tile_step(stage0, stat0, stage1, stat1, it);
-    tile_step(stage1, stat1, stage0, stat0, it + 1);
+    tile_step(stage0, stat0, stage1, stat1);
+    tile_step(stage1, stat1, stage0, stat0);
   }
-  if (it < iters) tile_step(stage0, stat0, stage1, stat1, it);
+  if (it < iters) tile_step(stage0, stat0, stage1, stat1);
 
   if (j_ok) {
     bf16_t* dKg = (bf16_t*)a.dk + kvrow;

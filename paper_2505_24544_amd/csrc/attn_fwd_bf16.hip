@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   using namespace fwd;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, ql = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int nqt = (a.S + BQ - 1) / BQ;
   int row, tpos;
   map_block(blockIdx.x, a.H * a.B, row, tpos);

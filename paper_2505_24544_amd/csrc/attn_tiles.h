@@ -38,7 +38,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_rsrc(const bf16_t* base, 
 // Fill a tile of R rows (R * 16 chunks, 256 threads) with global rows row0 .. row0 + R - 1.
 template <int R>
 __device__ __forceinline__ void load_rows(bf16_t* tile, __amdgpu_buffer_rsrc_t rsrc, int64_t stride, int row0, int tid) {
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
   for (int i = 0; i < R * 16 / 256; ++i) {
     const int q = tid + 256 * i, r = q >> 4, c = (q & 15) ^ swz(r);

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
                                                              float* __restrict__ part, int M, int N, int K) {
   using namespace dec;
   __shared__ __attribute__((aligned(1024))) bf16_t wt[SG_K * SG_N];     // 64 KB
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
   const int n0 = blockIdx.x * SG_N, ks = blockIdx.y, k0 = ks * SG_K;
   const int mblocks = (M + 31) / 32;
 
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];    // K step tile, V step tile: 64 KB
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
   __shared__ float s_ml[4][2][MAXM];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, ql = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int h = blockIdx.x, r = blockIdx.y;
   const int g = h / (a.H / a.G);
   const int HDt = a.H * HD;

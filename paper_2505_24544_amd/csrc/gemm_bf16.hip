@@ -68,7 +68,7 @@ template <int ROWS, bool KMAJOR>
 __device__ __forceinline__ void load_slice(bf16_t* tile, __amdgpu_buffer_rsrc_t rsrc, int64_t ld, int row0, int k0,
                                            int tid) {
   constexpr int PER_THREAD = ROWS * BK / 8 / 256;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
   for (int i = 0; i < PER_THREAD; ++i) {
     const int q = tid + 256 * i;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
   const int tn = (pid % per_group) / gsz;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 1) * (32 * TM), wn = (wave & 1) * (32 * TN);
 
   FragOffs<BM, XK, TM> xo;
