@@ -125,7 +125,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
       }
       pipeline_reads_mfma<32, 1>();
       __builtin_amdgcn_sched_barrier(0);
-      const bool partial = j0 + BJ > wave_lo;
+      // key offsets inside the tile are compile-time constants; tiles below every limit of the wave never mask
+      const int rel = j0 + BJ > wave_lo ? lim - j0 - 4 * hf : BJ;
       uint32_t pk[2][8];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
@@ -134,10 +135,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
           float ds[2];
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
-            const int j = j0 + 32 * jb + 8 * ((e + u) >> 2) + 4 * hf + ((e + u) & 3);
+            const int jo = 32 * jb + 8 * ((e + u) >> 2) + ((e + u) & 3);
             const float p = __builtin_amdgcn_exp2f(st[jb][e + u] * c2 - lse2);
             const float v = p * (dp[jb][e + u] - delta);
-            ds[u] = (partial && j >= lim) ? 0.f : v;
+            ds[u] = jo >= rel ? 0.f : v;
           }
           pk[jb][e >> 1] = cvt_pk(ds[0], ds[1]);
         }
@@ -281,6 +282,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       __builtin_amdgcn_sched_barrier(0);
       // register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key
       uint32_t pp[2][8], pd[2][8];
+      const int relq = fq - q0 - 4 * hf;    // query offsets inside the tile are compile-time constants
       auto probs = [&](auto masked) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
             for (int u = 0; u < 4; ++u) {
               const int e = 4 * e4 + u;
               float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][e], c2, -LOG2E * ls[u]));
-              if (decltype(masked)::value && q0 + r + u < fq) p = 0.f;   // also kills the +inf of blind queries (LSE = -inf)
+              if (decltype(masked)::value && 32 * qb + 8 * e4 + u < relq) p = 0.f;   // also kills the +inf of blind queries (LSE = -inf)
               pv[u] = p;
               dsv[u] = p * (dp[qb][e] - dl[u]);
             }

@@ -22,6 +22,7 @@
 // Mask: query p sees keys j < row_limit(p).  The loop over key tiles stops at
 // the last tile any query of the workgroup can see (whole-tile skipping); only
 // tiles that straddle a wave's limits evaluate the per-element predicate.
+#include <type_traits>
 #include "attn_tiles.h"
 
 namespace beagle {
@@ -31,6 +32,7 @@ namespace fwd {
 constexpr int BQ = 128;           // queries per workgroup
 constexpr int BJ = 64;            // keys per tile
 constexpr int TILE = BJ * HD;     // elements of one K or V tile
+constexpr float RESCALE_LOG2 = 8.f;
 }  // namespace fwd
 
 __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
@@ -101,45 +103,56 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
       }
       pipeline_reads_mfma<16, 1>();
       __builtin_amdgcn_sched_barrier(0);
-      // ---- mask (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4)
-      if (j0 + BJ > wave_lo) {
+      // ---- mask + tile maximum (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4).
+      // Only tiles that straddle a limit of this wave evaluate the per-element predicate.
+      float mx;
+      const int rel = lim - j0 - 4 * hf;    // key offsets inside the tile are compile-time constants
+      auto tile_max = [&](auto masked) {
+        if (decltype(masked)::value) {
+#pragma unroll
+          for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              if (32 * jb + 8 * (e >> 2) + (e & 3) >= rel) st[jb][e] = -INFINITY;
+            }
+        }
+        mx = st[0][0];
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int j = j0 + 32 * jb + 8 * (e >> 2) + 4 * hf + (e & 3);
-            if (j >= lim) st[jb][e] = -INFINITY;
-          }
-      }
-      // ---- online softmax for this lane's query
-      float mx = st[0][0];
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[jb][e]);
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[jb][e]);
+      };
+      if (j0 + BJ > wave_lo) tile_max(std::true_type{}); else tile_max(std::false_type{});
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f((m - m_safe) * c2);
-      const float mc = m_safe * c2;
+      // ---- online softmax for this lane's query.  The running reference m only moves when the
+      // tile maximum exceeds it by more than 2^RESCALE_LOG2 in the exponent, so that most tiles
+      // skip the rescaling of O; p then ranges up to 2^RESCALE_LOG2 instead of 1, which float
+      // sums and bf16 probabilities (same relative precision) take without loss.
+      const bool grow = (mx - m) * c2 > RESCALE_LOG2;      // also true for the first visible key (m = -inf)
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {         // wave-uniform
+        const float m_new = grow ? mx : m;
+        const float alpha = grow ? __builtin_amdgcn_exp2f((m - m_new) * c2) : 1.f;   // m = -inf: 0 (and O, l are 0)
+        l *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+      }
+      const float mc = (m == -INFINITY ? 0.f : m) * c2;
       float rs = 0.f;
       uint32_t pk[2][8];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(st[jb][e] * c2 - mc);
-          const float p1 = __builtin_amdgcn_exp2f(st[jb][e + 1] * c2 - mc);
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][e], c2, -mc));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(st[jb][e + 1], c2, -mc));
           rs += p0 + p1;
           pk[jb][e >> 1] = cvt_pk(p0, p1);
         }
       rs += __shfl_xor(rs, 32, 64);
-      l = l * alpha + rs;
-      m = m_new;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+      l += rs;
       // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
