@@ -134,5 +134,15 @@ __device__ __forceinline__ void wait_vmem_n() {
 }
 __device__ __forceinline__ void wait_vmem() { wait_vmem_n<0>(); }
 
+// Workgroup barrier that orders LDS traffic only: this wave's LDS instructions have completed,
+// then all waves meet.  Unlike __syncthreads() it carries no fence, so the compiler does not add
+// a wait for every HBM -> LDS request that is still in flight; the caller waits for the requests
+// it needs with wait_vmem_n first.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 }  // namespace tiles
 }  // namespace beagle

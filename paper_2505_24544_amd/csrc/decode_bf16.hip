@@ -24,6 +24,7 @@
 // device-scope fence inside a kernel writes back a whole L2 (the XCDs' L2s are
 // not coherent with each other), which costs far more than a launch.  All sums
 // run in a fixed order, so results are bitwise reproducible.
+#include <type_traits>
 #include "attn_tiles.h"
 
 namespace beagle {
@@ -178,23 +179,71 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     load_rows<KSTEP>(st, krs, kvs, j_begin + step * KSTEP, tid);
     load_rows<KSTEP>(st + TILE, vrs, kvs, j_begin + step * KSTEP, tid);
   };
-  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums it once into LDS (stage1 is
-  // not in use yet; float4 slot c4 of row m sits at (c4 + 2 m) % 32 to spread the fragment reads over the
-  // banks), then every lane picks up its B-operand fragments, split into bf16 hi + lo.
-  {
-    float* qs = (float*)stage1;
-    for (int idx = tid; idx < MB * 32 * 32; idx += 256) {
-      const int m = idx >> 5, c4 = idx & 31;
-      float4 acc = {0.f, 0.f, 0.f, 0.f};
+  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums it once into LDS (float4
+  // slot c4 of row m sits at (c4 + 2 m) % 32 to spread the fragment reads over the banks), then every lane
+  // picks up its B-operand fragments, split into bf16 hi + lo.
+  //
+  // With one query block the sum has an LDS buffer of its own, and the first two K/V steps are requested
+  // while the q slices are still on their way: the load counter of a wave retires in order, so the roles
+  // are split by wave.  Up to 8 queries are summed by wave 0 alone (more by all four): a summing wave
+  // loads, adds, stores to LDS and only then requests its share of K/V rows; the other waves request
+  // theirs at once.  The fragments are then read from LDS with explicit ds_read instructions: the
+  // compiler cannot tell these reads from the K/V requests in flight and would wait for all of them.
+  // With two query blocks LDS is full and stage1 serves as the buffer before any K/V request.
+  constexpr bool EARLY_KV = MB == 1;
+  __shared__ __attribute__((aligned(16))) float qbuf[EARLY_KV ? 32 * HD : 4];
+  float* qs = EARLY_KV ? qbuf : (float*)stage1;
+  const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
+  if (EARLY_KV) {
+    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+    const int qwaves = a.M <= 8 ? 1 : 4;
+    if (wave < qwaves) {
+      // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
+      const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
+      const __amdgpu_buffer_rsrc_t qrs =
+          __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
+      const int oob = 0x7fffff00;
+      u32x4_t t[4][8];                          // the launcher takes this form only for KSq <= 8
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int off = (int)((((int64_t)k * a.M + m) * HDt + h * HD + 4 * c4) * 4);
+          t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < a.M && k < a.KSq) ? off : oob, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+        float4 acc = zero4;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          acc.x += __uint_as_float(t[i][k][0]); acc.y += __uint_as_float(t[i][k][1]);
+          acc.z += __uint_as_float(t[i][k][2]); acc.w += __uint_as_float(t[i][k][3]);
+        }
+        *(float4*)(qs + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc;
+      }
+    } else {
+      // rows 8 .. 31 of the block have no query here (only reached with qwaves == 1): zeros
+      for (int idx = 256 + (tid - 64); idx < 32 * 32; idx += 192) *(float4*)(qs + 4 * idx) = zero4;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (nsteps > 0) fetch(stage0, 0);
+    if (nsteps > 1) fetch(stage1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+  } else {
+    // queries m = idx / 32 and float4 column c4 = idx % 32; a thread owns idx = tid + 256 i
+#pragma unroll
+    for (int i = 0; i < MB * 4; ++i) {
+      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
+      float4 acc = zero4;
       if (m < a.M) {
         const float* p = a.qpart + (int64_t)m * HDt + h * HD + 4 * c4;
         for (int k0 = 0; k0 < a.KSq; k0 += 8) {
           float4 t[8];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const float4 z = {0.f, 0.f, 0.f, 0.f};
-            t[k] = (k0 + k < a.KSq) ? *(const float4*)(p + (int64_t)(k0 + k) * a.M * HDt) : z;
-          }
+          for (int k = 0; k < 8; ++k) t[k] = (k0 + k < a.KSq) ? *(const float4*)(p + (int64_t)(k0 + k) * a.M * HDt) : zero4;
 #pragma unroll
           for (int k = 0; k < 8; ++k) { acc.x += t[k].x; acc.y += t[k].y; acc.z += t[k].z; acc.w += t[k].w; }
         }
@@ -202,18 +251,36 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       *(float4*)(qs + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc;
     }
   }
-  __syncthreads();
   bf16x8_t qh[MB][8], qlo[MB][8];
-  {
-    const float* qs = (const float*)stage1;
+  // B-operand fragments of q from the LDS buffer.  ASM_READS: explicit ds_read + wait, for reads that
+  // happen while K/V requests are in flight (the compiler would wait for all of those first).
+  auto build_q_frags = [&](auto asm_reads) {
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) float* lds_float_ptr;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const int m = 32 * mb + ql;
+      f32x4_t t0[8], t1[8];
+      if (decltype(asm_reads)::value) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          asm volatile("ds_read_b128 %0, %1" : "=v"(t0[s]) : "v"((lds_float_ptr)(qs + m * HD + 4 * ((4 * s + 2 * hf + 2 * m) & 31))));
+          asm volatile("ds_read_b128 %0, %1" : "=v"(t1[s]) : "v"((lds_float_ptr)(qs + m * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * m) & 31))));
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // tie the values to the wait: nothing that uses them may be scheduled above it
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(t0[s]), "+v"(t1[s]));
+      } else {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          t0[s] = *(const f32x4_t*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 2 * m) & 31));
+          t1[s] = *(const f32x4_t*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * m) & 31));
+        }
+      }
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        const float4 t0 = *(const float4*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 2 * m) & 31));
-        const float4 t1 = *(const float4*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * m) & 31));
-        const float v[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+        const float v[8] = {t0[s][0], t0[s][1], t0[s][2], t0[s][3], t1[s][0], t1[s][1], t1[s][2], t1[s][3]};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const __bf16 hi = (__bf16)v[i];
@@ -222,10 +289,14 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         }
       }
     }
+  };
+  if (!EARLY_KV) {
+    __syncthreads();
+    build_q_frags(std::false_type{});
+    __syncthreads();                                         // stage1 is free again
+    if (nsteps > 0) fetch(stage0, 0);
+    if (nsteps > 1) fetch(stage1, 1);
   }
-  __syncthreads();                                           // stage1 is free again
-  if (nsteps > 0) fetch(stage0, 0);
-  if (nsteps > 1) fetch(stage1, 1);
   const float c2 = a.scale * LOG2E;
   const FragOffs fo = make_frag_offs(lane);
 
@@ -309,8 +380,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   if (nsteps > 0) {
     // the first step's loads are the oldest 16 of (up to) 32 in flight
     if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
-    __syncthreads();
   }
+  lds_barrier();                                             // first K/V step landed; q sum visible
+  if (EARLY_KV) build_q_frags(std::true_type{});
 #pragma unroll 1
   for (int step = 0; step < nsteps; step += 2) {
     step_compute(stage0, step);
