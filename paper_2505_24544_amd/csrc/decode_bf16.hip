@@ -327,14 +327,17 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         for (int cb = 0; cb < 4; ++cb) vf[t][cb] = tr_frag(vs, fo, 32 * wave + 16 * t, cb);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        f32x16_t st;
+        // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
+        f32x16_t st, st2;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) st[e] = 0.f;
+        for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
           st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[mb][s], st, 0, 0, 0);
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[mb][s], st, 0, 0, 0);
+          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[mb][s], st2, 0, 0, 0);
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[e] += st2[e];
         if (jw + 32 > j_end) {
 #pragma unroll
           for (int e = 0; e < 16; ++e)
@@ -344,9 +347,21 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(mrun[mb], mx);             // finite: the block holds at least one real key
-        const float alpha = __builtin_amdgcn_exp2f((mrun[mb] - m_new) * c2);
-        const float mc = m_new * c2;
+        // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
+        // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
+        // steps skip the rescaling of O
+        const bool grow = (mx - mrun[mb]) * c2 > 8.f;        // also true at the first step (reference -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {        // wave-uniform
+          const float m_new = grow ? mx : mrun[mb];          // finite: the block holds at least one real key
+          const float alpha = grow ? __builtin_amdgcn_exp2f((mrun[mb] - m_new) * c2) : 1.f;
+          lrun[mb] *= alpha;
+          mrun[mb] = m_new;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[mb][i][e] *= alpha;
+        }
+        const float mc = mrun[mb] * c2;
         float rs = 0.f;
         uint32_t pk[8];
 #pragma unroll
@@ -357,12 +372,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
           pk[e >> 1] = cvt_pk(p0, p1);
         }
         rs += __shfl_xor(rs, 32, 64);
-        lrun[mb] = lrun[mb] * alpha + rs;
-        mrun[mb] = m_new;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) o[mb][i][e] *= alpha;
+        lrun[mb] += rs;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
@@ -421,7 +431,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       }
     if (hf == 0) { s_ml[wave][0][32 * mb + ql] = mrun[mb]; s_ml[wave][1][32 * mb + ql] = lrun[mb]; }
     __syncthreads();
-    for (int i = tid; i < 32 * HD; i += 256) {
+    const int rows = min(32, a.M - 32 * mb);                 // padding rows of the block are never read
+    for (int i = tid; i < rows * HD; i += 256) {
       const int c = i & (HD - 1), q = i >> 7, m = 32 * mb + q;
       float mm = -INFINITY;
 #pragma unroll
