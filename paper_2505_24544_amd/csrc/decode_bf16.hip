@@ -45,10 +45,25 @@ constexpr int TILE = KSTEP * HD;       // one K or V step tile
 // sits at chunk c ^ (((k >> 1) & 1) << 2), which makes the transpose reads
 // (4 consecutive k-rows x 64 B) hit four different bank quarters.
 // ---------------------------------------------------------------------------
+//
+// COMBINE: x is not read from memory.  It is the attention output of the M <= 8 draft queries, merged here
+// from the split-KV partials of (B) while the W tile is on its way: the workgroup's 512 k are the channels
+// of 4 heads, each the (max, sum)-weighted mean of R key ranges; the result is rounded to bf16 as the
+// stand-alone merge (C) does.  Workgroups of the first column block also write the LSE of their heads.
+struct CombineArgs {
+  const float* opart; const float* mlpart;   // [H][R][Mpad][128], [H][R][Mpad][2]
+  float* lse; int lse_stride;                // [H][lse_stride]
+  int Mpad, R;
+  float scale;
+};
+constexpr int COMB_MAXM = 8, COMB_MAXR = 8;
+
+template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
-                                                             float* __restrict__ part, int M, int N, int K) {
+                                                             float* __restrict__ part, int M, int N, int K, CombineArgs cb) {
   using namespace dec;
   __shared__ __attribute__((aligned(1024))) bf16_t wt[SG_K * SG_N];     // 64 KB
+  __shared__ __attribute__((aligned(16))) bf16_t xs[COMBINE ? COMB_MAXM * SG_K : 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
   const int n0 = blockIdx.x * SG_N, ks = blockIdx.y, k0 = ks * SG_K;
   const int mblocks = (M + 31) / 32;
@@ -64,15 +79,49 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
 
   // x fragments (B operand): lane holds x[m][k0 + 128 wave + 16 st + 8 hf .. +7]
   bf16x8_t xf[2][8];
+  if (!COMBINE) {
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      const int m = 32 * mb + (lane & 31), k = k0 + wave * 128 + st * 16 + 8 * hf;
-      bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
-      xf[mb][st] = z;
-      if (mb < mblocks && m < M && k < K) xf[mb][st] = *(const bf16x8_t*)(x + (int64_t)m * K + k);
+      for (int st = 0; st < 8; ++st) {
+        const int m = 32 * mb + (lane & 31), k = k0 + wave * 128 + st * 16 + 8 * hf;
+        bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+        xf[mb][st] = z;
+        if (mb < mblocks && m < M && k < K) xf[mb][st] = *(const bf16x8_t*)(x + (int64_t)m * K + k);
+      }
+  } else {
+    // item = (query m, head hh of the 4, float4 column c4): all R ranges are loaded before any is used
+    const float c2 = cb.scale * LOG2E;
+    for (int idx = tid; idx < M * 4 * 32; idx += 256) {
+      const int c4 = idx & 31, hh = (idx >> 5) & 3, m = idx >> 7;
+      const int h = k0 / HD + hh;
+      float mr[COMB_MAXR], lr[COMB_MAXR];
+      float4 ov[COMB_MAXR];
+#pragma unroll
+      for (int r = 0; r < COMB_MAXR; ++r) {
+        const int64_t pb = ((int64_t)h * cb.R + (r < cb.R ? r : 0)) * cb.Mpad + m;
+        const float2 ml = *(const float2*)(cb.mlpart + pb * 2);
+        mr[r] = r < cb.R ? ml.x : -INFINITY;
+        lr[r] = ml.y;
+        ov[r] = *(const float4*)(cb.opart + pb * HD + 4 * c4);
+      }
+      float mm = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < COMB_MAXR; ++r) mm = fmaxf(mm, mr[r]);
+      float4 acc = {0.f, 0.f, 0.f, 0.f};
+      float lt = 0.f;
+#pragma unroll
+      for (int r = 0; r < COMB_MAXR; ++r) {                  // fixed order
+        const float sc = mr[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mr[r] - mm) * c2);
+        acc.x += ov[r].x * sc; acc.y += ov[r].y * sc; acc.z += ov[r].z * sc; acc.w += ov[r].w * sc;
+        lt += lr[r] * sc;
+      }
+      const float inv = lt > 0.f ? 1.f / lt : 0.f;
+      uint2 v = {cvt_pk(acc.x * inv, acc.y * inv), cvt_pk(acc.z * inv, acc.w * inv)};
+      *(uint2*)(xs + m * SG_K + hh * HD + 4 * c4) = v;
+      if (blockIdx.x == 0 && c4 == 0) cb.lse[(int64_t)h * cb.lse_stride + m] = lt > 0.f ? mm * cb.scale + logf(lt) : -INFINITY;
     }
+  }
 
   f32x16_t acc[2][2];
 #pragma unroll
@@ -84,6 +133,15 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
 
   wait_vmem();
   __syncthreads();
+  if (COMBINE) {
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const int m = lane & 31;
+      bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+      xf[0][st] = m < M ? *(const bf16x8_t*)(xs + m * SG_K + wave * 128 + st * 16 + 8 * hf) : z;
+      xf[1][st] = z;
+    }
+  }
 
   const int gi = lane >> 4, r16 = lane & 15;
 #pragma unroll
@@ -525,8 +583,8 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
     const bf16_t* x = (const bf16_t*)a.x + (int64_t)m0 * a.D;
     {
       ProfScope ps("draft_proj_q", s);
-      hipLaunchKernelGGL(skinny_gemm_kernel, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
-                         Mp, HDt, a.D);
+      hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
+                         Mp, HDt, a.D, CombineArgs{});
     }
     {
       DecAttnArgs t;
@@ -538,15 +596,23 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       if (Mp <= 32) hipLaunchKernelGGL(decode_attn_kernel<1>, dim3(a.H, w.R), dim3(256), 0, s, t);
       else hipLaunchKernelGGL(decode_attn_kernel<2>, dim3(a.H, w.R), dim3(256), 0, s, t);
     }
-    {
-      ProfScope ps("draft_combine", s);
-      hipLaunchKernelGGL(decode_combine_kernel, dim3(Mp, a.H), dim3(128), 0, s, opart, mlpart, o, a.lse + m0, a.M,
-                         w.Mpad, a.H, w.R, a.scale);
-    }
-    {
+    if (Mp <= COMB_MAXM && w.R <= COMB_MAXR && HDt % SG_K == 0) {
+      // few queries: the merge of the key ranges rides in the projection's prologue
+      CombineArgs cb;
+      cb.opart = opart; cb.mlpart = mlpart; cb.lse = a.lse + m0; cb.lse_stride = a.M; cb.Mpad = w.Mpad; cb.R = w.R;
+      cb.scale = a.scale;
       ProfScope ps("draft_proj_out", s);
-      hipLaunchKernelGGL(skinny_gemm_kernel, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)o,
-                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt);
+      hipLaunchKernelGGL(skinny_gemm_kernel<true>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)nullptr,
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, cb);
+    } else {
+      {
+        ProfScope ps("draft_combine", s);
+        hipLaunchKernelGGL(decode_combine_kernel, dim3(Mp, a.H), dim3(128), 0, s, opart, mlpart, o, a.lse + m0, a.M,
+                           w.Mpad, a.H, w.R, a.scale);
+      }
+      ProfScope ps("draft_proj_out", s);
+      hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)o,
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, CombineArgs{});
     }
     {
       ProfScope ps("draft_sum_out", s);
