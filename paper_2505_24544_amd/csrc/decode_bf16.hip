@@ -217,14 +217,17 @@ struct DecAttnArgs {
   float scale;
 };
 
-template <int MB>
+// One workgroup per (head, key range, block of 32 queries): grid (H, R, ceil(M / 32)).
 __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   using namespace dec;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];    // K step tile, V step tile: 64 KB
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  __shared__ float s_ml[4][2][MAXM];
+  __shared__ __attribute__((aligned(16))) float qbuf[32 * HD];          // q of the block, float
+  __shared__ float s_ml[4][2][32];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int h = blockIdx.x, r = blockIdx.y;
+  const int m0 = 32 * blockIdx.z;                            // first query of the block
+  const int mrows = min(32, a.M - m0);                       // queries in the block
   const int g = h / (a.H / a.G);
   const int HDt = a.H * HD;
   const int j_begin = r * a.range, j_end = min(j_begin + a.range, a.L);
@@ -241,133 +244,96 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   // slot c4 of row m sits at (c4 + 2 m) % 32 to spread the fragment reads over the banks), then every lane
   // picks up its B-operand fragments, split into bf16 hi + lo.
   //
-  // With one query block the sum has an LDS buffer of its own, and the first two K/V steps are requested
-  // while the q slices are still on their way: the load counter of a wave retires in order, so the roles
-  // are split by wave.  Up to 8 queries are summed by wave 0 alone (more by all four): a summing wave
-  // loads, adds, stores to LDS and only then requests its share of K/V rows; the other waves request
-  // theirs at once.  The fragments are then read from LDS with explicit ds_read instructions: the
-  // compiler cannot tell these reads from the K/V requests in flight and would wait for all of them.
-  // With two query blocks LDS is full and stage1 serves as the buffer before any K/V request.
-  constexpr bool EARLY_KV = MB == 1;
-  __shared__ __attribute__((aligned(16))) float qbuf[EARLY_KV ? 32 * HD : 4];
-  float* qs = EARLY_KV ? qbuf : (float*)stage1;
-  const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
-  if (EARLY_KV) {
+  // The first two K/V steps are requested while the q slices are still on their way: the load counter of
+  // a wave retires in order, so the roles are split by wave.  Up to 8 queries are summed by wave 0 alone
+  // (more by all four): a summing wave loads, adds, stores to LDS and only then requests its share of K/V
+  // rows; the other waves request theirs at once.  The fragments are read after the barrier that also
+  // waits for the first step, with explicit ds_read instructions: the compiler cannot tell these reads
+  // from the K/V requests in flight and would wait for all of them.
+  {
     typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-    const int qwaves = a.M <= 8 ? 1 : 4;
+    const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    const int qwaves = mrows <= 8 ? 1 : 4;
     if (wave < qwaves) {
       // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
       const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
       const __amdgpu_buffer_rsrc_t qrs =
           __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
       const int oob = 0x7fffff00;
-      u32x4_t t[4][8];                          // the launcher takes this form only for KSq <= 8
+      float4 acc[4] = {zero4, zero4, zero4, zero4};
+      for (int k0 = 0; k0 < a.KSq; k0 += 8) {                             // one pass for up to 8 slices
+        u32x4_t t[4][8];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+        for (int i = 0; i < 4; ++i) {
+          const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const int off = (int)((((int64_t)k * a.M + m) * HDt + h * HD + 4 * c4) * 4);
-          t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < a.M && k < a.KSq) ? off : oob, 0, 0);
+          for (int k = 0; k < 8; ++k) {
+            const int off = (int)((((int64_t)(k0 + k) * a.M + m0 + m) * HDt + h * HD + 4 * c4) * 4);
+            t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < mrows && k0 + k < a.KSq) ? off : oob, 0, 0);
+          }
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
+            acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
+          }
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
-        float4 acc = zero4;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          acc.x += __uint_as_float(t[i][k][0]); acc.y += __uint_as_float(t[i][k][1]);
-          acc.z += __uint_as_float(t[i][k][2]); acc.w += __uint_as_float(t[i][k][3]);
-        }
-        *(float4*)(qs + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc;
+        *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
       }
     } else {
       // rows 8 .. 31 of the block have no query here (only reached with qwaves == 1): zeros
-      for (int idx = 256 + (tid - 64); idx < 32 * 32; idx += 192) *(float4*)(qs + 4 * idx) = zero4;
+      for (int idx = 256 + (tid - 64); idx < 32 * 32; idx += 192) *(float4*)(qbuf + 4 * idx) = zero4;
     }
     __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 0) fetch(stage0, 0);
     if (nsteps > 1) fetch(stage1, 1);
     __builtin_amdgcn_sched_barrier(0);
-  } else {
-    // queries m = idx / 32 and float4 column c4 = idx % 32; a thread owns idx = tid + 256 i
-#pragma unroll
-    for (int i = 0; i < MB * 4; ++i) {
-      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
-      float4 acc = zero4;
-      if (m < a.M) {
-        const float* p = a.qpart + (int64_t)m * HDt + h * HD + 4 * c4;
-        for (int k0 = 0; k0 < a.KSq; k0 += 8) {
-          float4 t[8];
-#pragma unroll
-          for (int k = 0; k < 8; ++k) t[k] = (k0 + k < a.KSq) ? *(const float4*)(p + (int64_t)(k0 + k) * a.M * HDt) : zero4;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) { acc.x += t[k].x; acc.y += t[k].y; acc.z += t[k].z; acc.w += t[k].w; }
-        }
-      }
-      *(float4*)(qs + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc;
-    }
   }
-  bf16x8_t qh[MB][8], qlo[MB][8];
-  // B-operand fragments of q from the LDS buffer.  ASM_READS: explicit ds_read + wait, for reads that
-  // happen while K/V requests are in flight (the compiler would wait for all of those first).
-  auto build_q_frags = [&](auto asm_reads) {
+  if (nsteps > 0) {
+    // the first step's loads are the oldest 16 of (up to) 32 in flight
+    if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
+  }
+  lds_barrier();                                             // first K/V step landed; q sum visible
+
+  bf16x8_t qh[8], qlo[8];
+  {
     typedef float f32x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) float* lds_float_ptr;
+    f32x4_t t0[8], t1[8];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      const int m = 32 * mb + ql;
-      f32x4_t t0[8], t1[8];
-      if (decltype(asm_reads)::value) {
+    for (int s = 0; s < 8; ++s) {
+      asm volatile("ds_read_b128 %0, %1" : "=v"(t0[s]) : "v"((lds_float_ptr)(qbuf + ql * HD + 4 * ((4 * s + 2 * hf + 2 * ql) & 31))));
+      asm volatile("ds_read_b128 %0, %1" : "=v"(t1[s]) : "v"((lds_float_ptr)(qbuf + ql * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * ql) & 31))));
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // tie the values to the wait: nothing that uses them may be scheduled above it
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          asm volatile("ds_read_b128 %0, %1" : "=v"(t0[s]) : "v"((lds_float_ptr)(qs + m * HD + 4 * ((4 * s + 2 * hf + 2 * m) & 31))));
-          asm volatile("ds_read_b128 %0, %1" : "=v"(t1[s]) : "v"((lds_float_ptr)(qs + m * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * m) & 31))));
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        // tie the values to the wait: nothing that uses them may be scheduled above it
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(t0[s]), "+v"(t1[s]));
 #pragma unroll
-        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(t0[s]), "+v"(t1[s]));
-      } else {
+    for (int s = 0; s < 8; ++s) {
+      const float v[8] = {t0[s][0], t0[s][1], t0[s][2], t0[s][3], t1[s][0], t1[s][1], t1[s][2], t1[s][3]};
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          t0[s] = *(const f32x4_t*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 2 * m) & 31));
-          t1[s] = *(const f32x4_t*)(qs + m * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * m) & 31));
-        }
-      }
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const float v[8] = {t0[s][0], t0[s][1], t0[s][2], t0[s][3], t1[s][0], t1[s][1], t1[s][2], t1[s][3]};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const __bf16 hi = (__bf16)v[i];
-          qh[mb][s][i] = hi;
-          qlo[mb][s][i] = (__bf16)(v[i] - (float)hi);
-        }
+      for (int i = 0; i < 8; ++i) {
+        const __bf16 hi = (__bf16)v[i];
+        qh[s][i] = hi;
+        qlo[s][i] = (__bf16)(v[i] - (float)hi);
       }
     }
-  };
-  if (!EARLY_KV) {
-    __syncthreads();
-    build_q_frags(std::false_type{});
-    __syncthreads();                                         // stage1 is free again
-    if (nsteps > 0) fetch(stage0, 0);
-    if (nsteps > 1) fetch(stage1, 1);
   }
   const float c2 = a.scale * LOG2E;
   const FragOffs fo = make_frag_offs(lane);
 
-  f32x16_t o[MB][4];
-  float mrun[MB], lrun[MB];
+  f32x16_t o[4];
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    mrun[mb] = -INFINITY; lrun[mb] = 0.f;
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[mb][i][e] = 0.f;
-  }
+    for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
+  float mrun = -INFINITY, lrun = 0.f;
 
   // one 128-key step: this wave takes rows 32 wave .. 32 wave + 31 of the step tiles
   auto step_compute = [&](const bf16_t* cur, int step) {
@@ -383,74 +349,65 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) vf[t][cb] = tr_frag(vs, fo, 32 * wave + 16 * t, cb);
+      // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
+      f32x16_t st, st2;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
-        f32x16_t st, st2;
+      for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
+      for (int s = 0; s < 8; ++s) {
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[s], st, 0, 0, 0);
+        st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[s], st2, 0, 0, 0);
+      }
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[mb][s], st, 0, 0, 0);
-          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[mb][s], st2, 0, 0, 0);
-        }
+      for (int e = 0; e < 16; ++e) st[e] += st2[e];
+      if (jw + 32 > j_end) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) st[e] += st2[e];
-        if (jw + 32 > j_end) {
+        for (int e = 0; e < 16; ++e)
+          if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
+      }
+      float mx = st[0];
 #pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
-        }
-        float mx = st[0];
+      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
+      // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
+      // steps skip the rescaling of O
+      const bool grow = (mx - mrun) * c2 > 8.f;              // also true at the first step (reference -inf)
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // wave-uniform
+        const float m_new = grow ? mx : mrun;                // finite: the block holds at least one real key
+        const float alpha = grow ? __builtin_amdgcn_exp2f((mrun - m_new) * c2) : 1.f;
+        lrun *= alpha;
+        mrun = m_new;
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
-        // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
-        // steps skip the rescaling of O
-        const bool grow = (mx - mrun[mb]) * c2 > 8.f;        // also true at the first step (reference -inf)
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {        // wave-uniform
-          const float m_new = grow ? mx : mrun[mb];          // finite: the block holds at least one real key
-          const float alpha = grow ? __builtin_amdgcn_exp2f((mrun[mb] - m_new) * c2) : 1.f;
-          lrun[mb] *= alpha;
-          mrun[mb] = m_new;
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+          for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+      }
+      const float mc = mrun * c2;
+      float rs = 0.f;
+      uint32_t pk[8];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[mb][i][e] *= alpha;
-        }
-        const float mc = mrun[mb] * c2;
-        float rs = 0.f;
-        uint32_t pk[8];
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(st[e] * c2 - mc);
+        const float p1 = __builtin_amdgcn_exp2f(st[e + 1] * c2 - mc);
+        rs += p0 + p1;
+        pk[e >> 1] = cvt_pk(p0, p1);
+      }
+      rs += __shfl_xor(rs, 32, 64);
+      lrun += rs;
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(st[e] * c2 - mc);
-          const float p1 = __builtin_amdgcn_exp2f(st[e + 1] * c2 - mc);
-          rs += p0 + p1;
-          pk[e >> 1] = cvt_pk(p0, p1);
-        }
-        rs += __shfl_xor(rs, 32, 64);
-        lrun[mb] += rs;
+      for (int t = 0; t < 2; ++t) {
+        union { uint32_t u[4]; bf16x8_t v; } pf;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          union { uint32_t u[4]; bf16x8_t v; } pf;
+        for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-            o[mb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb], pf.v, o[mb][cb], 0, 0, 0);
-        }
+        for (int cb = 0; cb < 4; ++cb)
+          o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb], pf.v, o[cb], 0, 0, 0);
       }
     }
   };
 
   // two stages, both requested up front; a stage is refilled as soon as every wave is done with it
-  if (nsteps > 0) {
-    // the first step's loads are the oldest 16 of (up to) 32 in flight
-    if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
-  }
-  lds_barrier();                                             // first K/V step landed; q sum visible
-  if (EARLY_KV) build_q_frags(std::true_type{});
 #pragma unroll 1
   for (int step = 0; step < nsteps; step += 2) {
     step_compute(stage0, step);
@@ -476,39 +433,33 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   // (c + q) % 128 so that neither the per-query writes nor the per-channel reads conflict
   float* ob = (float*)stage0;
   static_assert(4 * 32 * HD * sizeof(float) <= sizeof(stage0), "merge buffer must fit in one stage");
-  const int64_t pbase = ((int64_t)h * a.R + r) * a.Mpad;
+  const int64_t pbase = ((int64_t)h * a.R + r) * a.Mpad + m0;
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    if (mb > 0) __syncthreads();                             // previous block's merge has been read
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int c = 32 * cb + 8 * (e >> 2) + 4 * hf + (e & 3);
-        ob[(wave * 32 + ql) * HD + ((c + ql) & (HD - 1))] = o[mb][cb][e];
-      }
-    if (hf == 0) { s_ml[wave][0][32 * mb + ql] = mrun[mb]; s_ml[wave][1][32 * mb + ql] = lrun[mb]; }
-    __syncthreads();
-    const int rows = min(32, a.M - 32 * mb);                 // padding rows of the block are never read
-    for (int i = tid; i < rows * HD; i += 256) {
-      const int c = i & (HD - 1), q = i >> 7, m = 32 * mb + q;
-      float mm = -INFINITY;
-#pragma unroll
-      for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, s_ml[wv][0][m]);
-      float acc = 0.f, lt = 0.f;
-      if (mm > -INFINITY) {
-#pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
-          const float sc = __builtin_amdgcn_exp2f((s_ml[wv][0][m] - mm) * c2);
-          acc += ob[(wv * 32 + q) * HD + ((c + q) & (HD - 1))] * sc;
-          lt += s_ml[wv][1][m] * sc;
-        }
-      }
-      a.opart[(pbase + m) * HD + c] = acc;
-      if (c == 0) { a.mlpart[(pbase + m) * 2] = mm; a.mlpart[(pbase + m) * 2 + 1] = lt; }
+    for (int e = 0; e < 16; ++e) {
+      const int c = 32 * cb + 8 * (e >> 2) + 4 * hf + (e & 3);
+      ob[(wave * 32 + ql) * HD + ((c + ql) & (HD - 1))] = o[cb][e];
     }
+  if (hf == 0) { s_ml[wave][0][ql] = mrun; s_ml[wave][1][ql] = lrun; }
+  __syncthreads();
+  for (int i = tid; i < mrows * HD; i += 256) {              // padding rows of the block are never read
+    const int c = i & (HD - 1), q = i >> 7;
+    float mm = -INFINITY;
+#pragma unroll
+    for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, s_ml[wv][0][q]);
+    float acc = 0.f, lt = 0.f;
+    if (mm > -INFINITY) {
+#pragma unroll
+      for (int wv = 0; wv < 4; ++wv) {
+        const float sc = __builtin_amdgcn_exp2f((s_ml[wv][0][q] - mm) * c2);
+        acc += ob[(wv * 32 + q) * HD + ((c + q) & (HD - 1))] * sc;
+        lt += s_ml[wv][1][q] * sc;
+      }
+    }
+    a.opart[(pbase + q) * HD + c] = acc;
+    if (c == 0) { a.mlpart[(pbase + q) * 2] = mm; a.mlpart[(pbase + q) * 2 + 1] = lt; }
   }
-
 }
 
 // ---- (C) merge the key ranges (fixed order): o (bf16) and LSE ------------------
@@ -593,8 +544,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       t.M = Mp; t.Mpad = w.Mpad; t.L = a.L; t.H = a.H; t.G = a.G; t.R = w.R; t.range = w.range;
       t.scale = a.scale;
       ProfScope ps("draft_attn", s);
-      if (Mp <= 32) hipLaunchKernelGGL(decode_attn_kernel<1>, dim3(a.H, w.R), dim3(256), 0, s, t);
-      else hipLaunchKernelGGL(decode_attn_kernel<2>, dim3(a.H, w.R), dim3(256), 0, s, t);
+      hipLaunchKernelGGL(decode_attn_kernel, dim3(a.H, w.R, (Mp + 31) / 32), dim3(256), 0, s, t);
     }
     if (Mp <= COMB_MAXM && w.R <= COMB_MAXR && HDt % SG_K == 0) {
       // few queries: the merge of the key ranges rides in the projection's prologue
