@@ -1,22 +1,22 @@
 // Decode-time draft step (section 4.1, KV-cache paragraph) for bf16, head
 // width 128: M <= 64 draft queries per pass against L cached K/V rows, all
 // visible.  The step is bound by HBM bandwidth (the K/V cache, Wq and Wo are
-// each read once), so the three kernels are shaped to put every CU's share of
-// those bytes in flight at once (direct HBM -> LDS loads, whole chip resident
-// in a single round); the matrix cores only keep arithmetic off the critical
-// path.
+// each read once), so the kernels are shaped to put every CU's share of those
+// bytes in flight at once (direct HBM -> LDS loads, whole chip resident in a
+// single round); the matrix cores only keep arithmetic off the critical path.
 //
 //   (A) skinny_gemm   q_part[ks] = x * Wq[k-slice ks]        grid (N/64) x (K/512),
 //                     two workgroups per CU, the whole chip resident at once
-//   (B) decode_attn   one workgroup per (head, key range); its 4 waves split
-//                     each 128-key step by rows.  A lane owns one query (as in
-//                     the training forward): online softmax per lane, P goes
-//                     from the accumulator registers straight into the second
-//                     MFMA.  q is the sum of (A)'s k-slices, split into a bf16
-//                     hi + lo pair so that scores (and the LSE) see q at ~16
-//                     bits.  Waves are merged in LDS; each range writes an
-//                     unnormalised partial.
-//   (C) combine       merges the key ranges, writes o (bf16) and the LSE
+//   (B) decode_attn   one workgroup per (head, key range, block of 32 queries);
+//                     its 4 waves split each 128-key step by rows.  A lane owns
+//                     one query (as in the training forward): online softmax per
+//                     lane, P goes from the accumulator registers straight into
+//                     the second MFMA.  q is the sum of (A)'s k-slices, split
+//                     into a bf16 hi + lo pair so that scores (and the LSE) see
+//                     q at ~16 bits.  Waves are merged in LDS; each range writes
+//                     an unnormalised partial.
+//   (C) combine       merges the key ranges, writes o (bf16) and the LSE; with up
+//                     to 8 queries this runs in the prologue of (D) instead
 //   (D) skinny_gemm   y_part[ks] = o * Wo[k-slice ks]
 //   (E) sum_slices    y = sum_ks y_part[ks]  (bf16)
 //

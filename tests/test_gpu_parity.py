@@ -48,10 +48,10 @@ def check_f32(cfg, inp, scale=0.0):
     return fw, gr
 
 
-def check_bf16(cfg, inp, flags=bx.BEAGLE_FLAG_NEED_DXKV, lse_tol=LSE_TOL):
-    ref = oracle_all(cfg, inp)
-    dev, fw = run_fwd(cfg, inp)
-    _, gr = run_bwd(cfg, inp, dev, flags=flags)
+def check_bf16(cfg, inp, flags=bx.BEAGLE_FLAG_NEED_DXKV, lse_tol=LSE_TOL, scale=0.0):
+    ref = oracle_all(cfg, inp, scale or None)
+    dev, fw = run_fwd(cfg, inp, scale=scale)
+    _, gr = run_bwd(cfg, inp, dev, flags=flags, scale=scale)
     for n in ("y", "q", "k", "v", "o"):
         assert np.isfinite(fw[n]).all(), n
         assert max_abs(fw[n], ref[n]) <= BF16_OUT_ABS, (n, max_abs(fw[n], ref[n]))
@@ -127,6 +127,17 @@ def test_bf16_reduced_configs(name, kw, peaked):
     check_bf16(cfg, inp, lse_tol=LSE_TOL if not peaked else 4e-3)
 
 
+def test_bf16_wide_score_range():
+    """Scores spread over tens of nats (peaked queries, 4x the default scale):
+    along a row the running maximum jumps by more than the kernels' lazy
+    rescaling threshold several times and by less in between, so both branches
+    of the online softmax run.  The bf16 rounding of q and k moves a score by
+    4x what it does at the default scale; the LSE bound scales with it."""
+    cfg = synth.CONFIGS["c2"].with_(batch=1, seq_q=600, seq_kv=600, **SMALL)
+    inp = synth.make_inputs(cfg, peaked_queries=True)
+    check_bf16(cfg, inp, lse_tol=1.6e-2, scale=4.0 / np.sqrt(128.0))
+
+
 def test_bf16_weight_grads_in_float_and_no_dxkv():
     cfg = synth.CONFIGS["c2"].with_(batch=1, seq_q=200, seq_kv=200, **SMALL)
     inp = synth.make_inputs(cfg, peaked_queries=True)
@@ -184,13 +195,30 @@ def _decode_problem(M, L, H, G, D, seed):
 
 @pytest.mark.parametrize("M,L,H,G,D", [(1, 1000, 4, 4, 512), (8, 1000, 4, 2, 512), (32, 777, 8, 8, 1024),
                                        (64, 1030, 4, 1, 512), (5, 1, 4, 4, 512), (17, 63, 4, 4, 512),
-                                       (64, 4096, 8, 8, 1024)])
+                                       (64, 4096, 8, 8, 1024),
+                                       (40, 600, 4, 4, 512),      # second block of 32 queries partly filled
+                                       (100, 300, 4, 2, 512),     # two passes of 64 queries
+                                       (3, 500, 2, 2, 8192)])     # 16 k-slices of q
 def test_decode_reduced(M, L, H, G, D):
     cfg, inp, kc, vc = _decode_problem(M, L, H, G, D, 400 + M)
     ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G)
     y, lse = run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"])
     assert max_abs(y, ref["y"]) <= BF16_OUT_ABS and rel_fro(y, ref["y"]) <= BF16_OUT_FRO, rel_fro(y, ref["y"])
     assert max_abs(lse, ref["lse"]) <= LSE_TOL
+
+
+@pytest.mark.parametrize("M", [4, 20])
+def test_decode_wide_score_range(M):
+    """Four 128-key steps per workgroup with scores spread over tens of nats
+    (4x the default scale): the running reference of the split-KV softmax
+    both jumps and stays within the lazy-rescaling threshold."""
+    L, H, G, D = 4096, 32, 32, 512
+    cfg, inp, kc, vc = _decode_problem(M, L, H, G, D, 430 + M)
+    scale = 4.0 / np.sqrt(128.0)
+    ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G, scale=scale)
+    y, lse = run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], scale=scale)
+    assert max_abs(y, ref["y"]) <= BF16_OUT_ABS and rel_fro(y, ref["y"]) <= BF16_OUT_FRO, rel_fro(y, ref["y"])
+    assert max_abs(lse, ref["lse"]) <= 4 * LSE_TOL
 
 
 @pytest.mark.parametrize("M", [1, 8, 32, 64])
