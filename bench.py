@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # scaled by a plain 1 GiB copy in the same run (profiles/hbm_traffic_c2_c4.md).  Counters cannot be read
 # from inside this process, so the figures are carried here for the workload they were measured on.
 MEASURED_TRAFFIC_BYTES = {
-    "c2": {"proj_qkv": 1216e6 + 201e6, "proj_out": 405e6 + 67e6, "bwd_dout": 410e6 + 67e6, "bwd_dwo": 403e6 + 34e6,
-           "bwd_dx": 1229e6 + 134e6, "bwd_dw": 1208e6 + 101e6},
+    "c2": {"proj_qkv": 1222e6 + 201e6, "proj_out": 408e6 + 67e6, "bwd_dout": 412e6 + 67e6, "bwd_dwo": 403e6 + 34e6,
+           "bwd_dx": 1235e6 + 134e6, "bwd_dw": 1210e6 + 101e6},
 }
 
 
@@ -63,7 +63,10 @@ def kernel_flops(cfg, fl, need_dxkv=True):
     return {
         "proj_qkv": p["q"] + p["k"] + p["v"], "proj_out": p["o"], "bwd_dout": p["o"], "bwd_dwo": p["o"],
         "bwd_dx": p["q"] + ((p["k"] + p["v"]) if need_dxkv else 0), "bwd_dw": p["q"] + p["k"] + p["v"],
-        "attn_fwd_bf16": fl["attn_fwd"], "attn_bwd_bf16": fl["attn_bwd"],
+        "attn_fwd_bf16": fl["attn_fwd"],
+        # the backward's five contractions (10 d flops per visible pair): S, dP, dQ are credited to the dQ
+        # kernel, dK and dV to the dK/dV kernel; the S and dP that the latter recomputes are not counted
+        "attn_bwd_dq_bf16": 0.6 * fl["attn_bwd"], "attn_bwd_dkv_bf16": 0.4 * fl["attn_bwd"],
     }
 
 
@@ -232,25 +235,30 @@ def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):
 
 def cpu_baseline(cfg, synth):
     """The float64 oracle, as it stands, on the host cores: forward+backward on
-    batch 1 x the first 256 positions of the workload (all heads, full width)."""
+    every sequence of the workload's batch, one at a time, each cut to its
+    first 2048 positions (all heads, full width).  For c2 that is the whole
+    workload: about 12 s on the GPU machine's 16 host cores."""
     import numpy as np
     from oracle import beagle_oracle as orc
-    S = 256
+    S = min(2048, cfg.seq_q)
     c = cfg.with_(batch=1, seq_q=S, seq_kv=S)
-    inp = synth.make_inputs(c)
     mask = orc.dense_mask(S, S, c.block_size, c.block_offset)
-    t0 = time.perf_counter()
-    orc.xattn_backward(inp["dy"], inp["xq"], inp["xkv"], inp["wq"], inp["wk"], inp["wv"], inp["wo"],
-                       n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, mask=mask)
-    dt = time.perf_counter() - t0
-    fl = flops_training(c, True)["total"]
+    dt = 0.0
+    for b in range(cfg.batch):
+        inp = synth.make_inputs(c.with_(seed_base=c.seed_base + 1000 * b))
+        t0 = time.perf_counter()
+        orc.xattn_backward(inp["dy"], inp["xq"], inp["xkv"], inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                           n_q_heads=c.n_q_heads, n_kv_heads=c.n_kv_heads, mask=mask)
+        dt += time.perf_counter() - t0
+    fl = flops_training(c, True)["total"] * cfg.batch
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count()
     return dict(value=round(fl / dt / 1e12, 5), unit="TFLOP/s", cores=cores, kind="oracle",
-                seconds=round(dt, 2), tokens_per_s=round(S / dt, 1),
-                sample="%s shape, batch 1, first %d positions, float64 NumPy, fwd+bwd incl. dXkv" % (c.name, S))
+                seconds=round(dt, 2), tokens_per_s=round(cfg.batch * S / dt, 1),
+                sample="%s shape, %d sequence(s) one at a time, first %d positions each, float64 NumPy, "
+                       "fwd+bwd incl. dXkv" % (c.name, cfg.batch, S))
 
 
 if __name__ == "__main__":
