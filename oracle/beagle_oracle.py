@@ -258,6 +258,104 @@ def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None
 
 
 # --------------------------------------------------------------------------
+# Decode with drafted states concatenated to the cache, under a draft tree
+# (section 4.1, KV-cache paragraph: "append new states K_i, V_i ... reset
+# KV-cache to only contain true states at the end of SD iteration"; section 6:
+# the "concate" option and the EAGLE-style dynamic drafting tree, depth 1+6,
+# top-k 10, 60 candidates)
+#
+# Readings taken here (the paper gives no formula for the tree mask):
+#   * The cache holds n_true rows of true target states followed by the rows
+#     of the states drafted so far in this iteration, in the order they were
+#     appended.  Every query sees every true row.
+#   * A query placed at draft node t sees the drafted rows of the PROPER
+#     ancestors of t only: its own state is appended after the query has run
+#     (the section 4.1 wording), and siblings / other branches never.
+#     PARITY UNPINNED by the paper beyond that wording; the entry point takes
+#     an arbitrary boolean mask, ancestor_mask() builds this reading of it.
+#   * Resetting the cache is dropping the rows past n_true: no arithmetic.
+# --------------------------------------------------------------------------
+def kv_project(x_new, wk, wv, *, n_kv_heads):
+    """K and V rows of n new states (true or drafted): x_new [n, D] -> [n, G, d] each."""
+    x = np.asarray(x_new, F64)
+    wk, wv = np.asarray(wk, F64), np.asarray(wv, F64)
+    n = x.shape[0]
+    G = n_kv_heads
+    if wk.shape[1] % G or wk.shape != wv.shape:
+        raise ValueError("K/V weight shapes")
+    d = wk.shape[1] // G
+    return (x @ wk).reshape(n, G, d), (x @ wv).reshape(n, G, d)
+
+
+def kv_append(k_cache, v_cache, pos, x_new, wk, wv, *, n_kv_heads):
+    """Copies of the caches with rows pos .. pos+n-1 replaced by the K/V rows of x_new."""
+    kc, vc = np.array(k_cache, F64, copy=True), np.array(v_cache, F64, copy=True)
+    kn, vn = kv_project(x_new, wk, wv, n_kv_heads=n_kv_heads)
+    n = kn.shape[0]
+    if pos < 0 or pos + n > kc.shape[0]:
+        raise ValueError("append range outside the cache")
+    kc[pos:pos + n] = kn
+    vc[pos:pos + n] = vn
+    return kc, vc
+
+
+def ancestor_mask(parents, query_nodes):
+    """Tree mask of the reading above.
+
+    parents[t] is the parent draft node of draft node t (appended earlier, so
+    parents[t] < t), or -1 when its parent is the last true token.  Returns a
+    boolean [len(query_nodes), len(parents)] matrix: entry (m, t) is True iff
+    node t is a proper ancestor of node query_nodes[m].
+    """
+    T = len(parents)
+    for t, p in enumerate(parents):
+        if not (-1 <= p < t):
+            raise ValueError("parents must point to earlier nodes or -1")
+    out = np.zeros((len(query_nodes), T), bool)
+    for m, node in enumerate(query_nodes):
+        if not (0 <= node < T):
+            raise ValueError("query node out of range")
+        a = parents[node]
+        while a >= 0:
+            out[m, a] = True
+            a = parents[a]
+    return out
+
+
+def draft_step_tree(x, k_cache, v_cache, wq, wo, *, n_true, tree_mask, n_q_heads, n_kv_heads, scale=None):
+    """M draft queries against n_true true rows plus T drafted rows of the cache.
+
+    x [M, D]; k_cache, v_cache [n_true + T, G, d]; tree_mask boolean [M, T]:
+    query m sees every true row, and drafted row n_true + t iff tree_mask[m, t].
+    Returns y [M, D], lse [H, M].
+    """
+    x = np.asarray(x, F64)
+    kc, vc = np.asarray(k_cache, F64), np.asarray(v_cache, F64)
+    wq, wo = np.asarray(wq, F64), np.asarray(wo, F64)
+    tm = np.asarray(tree_mask, bool)
+    H, G = n_q_heads, n_kv_heads
+    rep = _check_heads(H, G)
+    M, D = x.shape
+    L, _, d = kc.shape
+    T = L - n_true
+    if n_true < 0 or T < 0 or tm.shape != (M, T):
+        raise ValueError("tree mask must be [M, rows past n_true]")
+    if scale is None or scale == 0:
+        scale = 1.0 / math.sqrt(d)
+    vis = np.concatenate([np.ones((M, n_true), bool), tm], axis=1)
+    q = (x @ wq).reshape(M, H, d)
+    o = np.zeros((M, H, d), F64)
+    lse = np.zeros((H, M), F64)
+    for h in range(H):
+        g = h // rep
+        s = (q[:, h, :] @ kc[:, g, :].T) * scale
+        P, lse[h] = masked_softmax(s, vis)
+        o[:, h, :] = P @ vc[:, g, :]
+    y = o.reshape(M, H * d) @ wo
+    return dict(y=y, lse=lse, q=q, o=o)
+
+
+# --------------------------------------------------------------------------
 # Accounting helpers used by the tests and the benchmark's CPU leg
 # --------------------------------------------------------------------------
 def visible_pairs(mask: np.ndarray) -> int:
