@@ -230,6 +230,54 @@ def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):
         res["M%d" % M] = dict(us_per_call=round(us, 2), gbs=round(call_bytes / us / 1e3, 1),
                               pct_hbm_peak=round(100 * call_bytes / us / 1e3 / PEAK_HBM_GBS, 2),
                               draft_tokens_per_s=round(M / (us * 1e-6)), bytes=call_bytes, kernel_us=kern)
+    # ---- the same step with drafted states in the cache under a draft tree (50 drafted rows: five finished
+    # depths of top-k 10; the 10 queries of the next depth), and appending 10 drafted states to the cache
+    import numpy as np
+    M, T = 10, 50
+    rng = np.random.default_rng(5)
+    tm = np.zeros((M, 2), np.uint32)
+    for m in range(M):
+        for dpt in range(5):                       # one ancestor per finished depth
+            t = 10 * dpt + int(rng.integers(0, 10))
+            tm[m, t // 32] |= np.uint32(1) << np.uint32(t % 32)
+    tmd = torch.from_numpy(tm.view(np.int32)).to(dev)
+    c = cfg.with_(seq_q=M, seq_kv=L)
+    desc = gh.desc_of(c)
+    x = torch.randn(M, D, device=dev, generator=g).to(torch.bfloat16)
+    y = torch.empty(M, D, dtype=torch.bfloat16, device=dev)
+    lse = torch.empty(H, M, dtype=torch.float32, device=dev)
+    ws = gh.workspace(desc, bx.BEAGLE_WS_DRAFT)
+    wk = (torch.randn(D, G * hd, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+    wv = (torch.randn(D, G * hd, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+    adesc = gh.desc_of(cfg.with_(seq_q=M, seq_kv=L))
+    aws = gh.workspace(adesc, bx.BEAGLE_WS_APPEND)
+
+    def tree_call(r):
+        kc, vc, wq, wo = sets[r % nset]
+        bx.beagle_xattn_draft_step_tree(desc, x, kc, vc, wq, wo, L - T, tmd, 2, y, lse, ws, stream)
+
+    def append_call(r):
+        kc, vc, _, _ = sets[r % nset]
+        bx.beagle_xattn_kv_append(adesc, x, wk, wv, kc, vc, L - T, aws, stream)
+
+    for name, fn in (("tree_M10_T50", tree_call), ("kv_append_n10", append_call)):
+        for r in range(nset):
+            fn(r)
+        torch.cuda.synchronize()
+        reps = 50
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            fn(r)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        if name.startswith("tree"):
+            nbytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2 + 2 * D * H * hd * 2
+        else:
+            nbytes = 2 * D * G * hd * 2 + M * D * 2 + 2 * M * G * hd * 2
+        res[name] = dict(us_per_call=round(us, 2), gbs=round(nbytes / us / 1e3, 1),
+                         pct_hbm_peak=round(100 * nbytes / us / 1e3 / PEAK_HBM_GBS, 2), bytes=nbytes)
     return res
 
 

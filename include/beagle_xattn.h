@@ -69,7 +69,7 @@ enum {
                                       when io_dtype is bf16                     */
 };
 
-enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2 };
+enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3 };
 
 typedef struct {
   int32_t struct_size;   /* sizeof(beagle_xattn_desc); checked                  */
@@ -141,6 +141,47 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
 beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache,
     const void* wq, const void* wo, void* y, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Appending states to the decode cache (section 4.1, KV-cache paragraph: new
+ * K_i, V_i are appended as drafting proceeds, and the cache is reset to the
+ * true states at the end of a speculative-decoding iteration).  The
+ * n = desc->seq_q states x_new (true target states, or drafted states) are
+ * projected and written in place,
+ *   k_cache[pos + i] = x_new[i] Wk,   v_cache[pos + i] = x_new[i] Wv,   i < n,
+ * into a cache with room for desc->seq_kv rows; 0 <= pos, pos + n <= seq_kv.
+ * No other row is touched.  Resetting the cache needs no call: the caller
+ * stops counting the rows past the true states.  desc->batch must be 1;
+ * block_size / block_offset are ignored.
+ *   in    : x_new [n,D], wk [D,G*d], wv [D,G*d]
+ *   in/out: k_cache, v_cache [seq_kv,G,d]
+ * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_APPEND) (split-k
+ * partial sums of the two projections when n is small).
+ */
+beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
+    const void* x_new, const void* wk, const void* wv,
+    void* k_cache, void* v_cache, int32_t pos,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Draft step with the drafted states concatenated to the cache, under a draft
+ * tree (section 6: the "concate" option with the dynamic drafting tree).  The
+ * cache holds n_true rows of true states followed by T = desc->seq_kv - n_true
+ * rows of drafted states.  Query m sees every true row, and drafted row
+ * n_true + t iff bit (t % 32) of tree_mask[m * mask_words + t / 32] is set.
+ * 0 <= n_true <= seq_kv; mask_words >= ceil(T / 32); bits at t >= T are
+ * ignored; with T == 0 this is beagle_xattn_draft_step and tree_mask may be
+ * NULL.  A query that sees no row at all gets y = 0 and lse = -inf.
+ *   in : as beagle_xattn_draft_step, plus tree_mask: DEVICE pointer,
+ *        uint32 [M, mask_words], 4-byte aligned
+ *   out: y [M,D], lse [H,M]
+ * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT).
+ */
+beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache,
+    const void* wq, const void* wo, int32_t n_true,
+    const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---- mask / index inspection (HOST memory, integers only, no GPU needed) --

@@ -17,14 +17,17 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbeagle_xattn.so")
 
 BEAGLE_OK = 0
+(BEAGLE_ERR_NULL, BEAGLE_ERR_SHAPE, BEAGLE_ERR_UNSUPPORTED, BEAGLE_ERR_WORKSPACE, BEAGLE_ERR_ALIGN,
+ BEAGLE_ERR_HIP) = range(1, 7)
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
 BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32 = 1, 2
-BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT = 0, 1, 2
+BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND = 0, 1, 2, 3
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
                 4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
+    "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -73,6 +76,10 @@ def lib() -> C.CDLL:
     L.beagle_xattn_bwd.argtypes = [dp] + [vp] * 18 + [vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step.restype = C.c_int
     L.beagle_xattn_draft_step.argtypes = [dp] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_draft_step_tree.restype = C.c_int
+    L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+    L.beagle_xattn_kv_append.restype = C.c_int
+    L.beagle_xattn_kv_append.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_size_t, vp]
     L.beagle_xattn_mask_row_limit.restype = C.c_int
     L.beagle_xattn_mask_row_limit.argtypes = [dp, vp]
     L.beagle_xattn_mask_dense.restype = C.c_int
@@ -121,6 +128,23 @@ def _check(st, where, check):
     if check and st != BEAGLE_OK:
         raise BeagleError(st, where)
     return st
+
+
+def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true, tree_mask, mask_words, y, lse,
+                                 workspace, stream=None, *, workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_draft_step_tree(
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo)), int(n_true), _ptr(tree_mask),
+        int(mask_words), _ptr(y), _ptr(lse),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_draft_step_tree", check)
+
+
+def beagle_xattn_kv_append(desc, x_new, wk, wv, k_cache, v_cache, pos, workspace, stream=None, *,
+                           workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_kv_append(
+        C.byref(desc), *(_ptr(t) for t in (x_new, wk, wv, k_cache, v_cache)), int(pos),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_kv_append", check)
 
 
 def beagle_xattn_workspace_bytes(desc, which) -> int:

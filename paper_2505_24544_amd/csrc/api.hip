@@ -233,7 +233,7 @@ beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, i
 // ---------------------------------------------------------------- workspace
 size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
   Dims d;
-  if (check_desc(desc, which == BEAGLE_WS_DRAFT, &d) != BEAGLE_OK) return 0;
+  if (check_desc(desc, which == BEAGLE_WS_DRAFT || which == BEAGLE_WS_APPEND, &d) != BEAGLE_OK) return 0;
   switch (which) {
     case BEAGLE_WS_FWD: return WS_ALIGN;   // nothing beyond the saved tensors
     case BEAGLE_WS_BWD: {
@@ -245,6 +245,10 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
     case BEAGLE_WS_DRAFT:
       if (d.bf16) return align_up(decode_bf16_ws_bytes((int32_t)d.S, (int32_t)d.L, (int32_t)d.H, (int32_t)d.d, (int32_t)d.D));
       return align_up((size_t)(2 * d.S * d.HD) * d.esz);
+    case BEAGLE_WS_APPEND:
+      if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))
+        return WS_ALIGN + align_up(kv_append_bf16_ws_bytes((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D));
+      return WS_ALIGN;
     default: return 0;
   }
 }
@@ -341,8 +345,11 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
 }
 
 // --------------------------------------------------------------- draft step
-beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
+namespace {
+// shared by the plain and the draft-tree decode entry points
+beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
+    int32_t n_true, const uint32_t* tree, int32_t words,
     void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
@@ -351,6 +358,15 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
   if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
   if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT)) return BEAGLE_ERR_WORKSPACE;
+  if (n_true < 0 || n_true > d.L) return BEAGLE_ERR_SHAPE;
+  const int64_t T = d.L - n_true;
+  if (T > 0) {
+    if (!tree) return BEAGLE_ERR_NULL;
+    if (((uintptr_t)tree) % 4) return BEAGLE_ERR_ALIGN;
+    if (words < (T + 31) / 32) return BEAGLE_ERR_SHAPE;
+  } else {
+    tree = nullptr; words = 0;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
@@ -359,6 +375,7 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
     a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.wq = wq; a.wo = wo; a.y = y; a.lse = lse; a.ws = workspace;
+    a.tree = tree; a.n_true = n_true; a.tree_words = words;
     launch_decode_bf16(a, s);
     return hip_status();
   }
@@ -368,8 +385,55 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
   launch_gemm_f32(group1(gemm_nn(x_draft, wq, q, d.S, d.HD, d.D)), s, "draft_proj_q");
   AttnArgs a = attn_args(d);
   a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
+  a.tree = tree; a.n_true = n_true; a.tree_words = words;
   launch_attn_fwd_f32(a, s);
   launch_gemm_f32(group1(gemm_nn(o, wo, y, d.S, d.D, d.HD)), s, "draft_proj_out");
+  return hip_status();
+}
+}  // namespace
+
+beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
+    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int32_t L = desc ? desc->seq_kv : 0;
+  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo, L, nullptr, 0, y, lse, workspace, workspace_bytes,
+                         hip_stream);
+}
+
+beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
+    int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo, n_true, tree_mask, mask_words, y, lse, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
+    const void* x_new, const void* wk, const void* wv, void* k_cache, void* v_cache, int32_t pos,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  const void* ptrs[] = {x_new, wk, wv, k_cache, v_cache, workspace};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_APPEND)) return BEAGLE_ERR_WORKSPACE;
+  if (pos < 0 || (int64_t)pos + d.S > d.L) return BEAGLE_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  // rows pos .. pos + n - 1 of the caches are the output matrices (leading dimension G*d)
+  char* kdst = (char*)k_cache + (size_t)pos * d.GD * d.esz;
+  char* vdst = (char*)v_cache + (size_t)pos * d.GD * d.esz;
+  if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
+    // a handful of states: HBM-bound on Wk and Wv, so the split-k streaming projection of the draft step
+    launch_kv_append_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, workspace, s);
+    return hip_status();
+  }
+  GemmGroup g; memset(&g, 0, sizeof(g));
+  g.count = 2;
+  g.p[0] = gemm_nn(x_new, wk, kdst, d.S, d.GD, d.D);
+  g.p[1] = gemm_nn(x_new, wv, vdst, d.S, d.GD, d.D);
+  run_gemm(d, g, s, "kv_append");
   return hip_status();
 }
 

@@ -68,6 +68,8 @@ struct AttnArgs {
   const void* dout;                               // dO [B,S,H,d]
   void* dq; void* dk; void* dv;                   // [B,S,H,d], [B,L,G,d] x2
   float* delta;                                   // [B,H,S]
+  // draft-tree decode only: keys >= n_true are visible to query p iff bit (j - n_true) of row p is set
+  const uint32_t* tree; int32_t n_true, tree_words;
 };
 void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s);
@@ -84,8 +86,14 @@ struct DecodeArgs {
   const void* x; const void* kc; const void* vc; const void* wq; const void* wo;
   void* y; float* lse;
   void* ws;
+  // draft tree (tree == nullptr: every cache row is visible to every query)
+  const uint32_t* tree; int32_t n_true, tree_words;
 };
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
+size_t kv_append_bf16_ws_bytes(int32_t n, int32_t N, int32_t K);
+bool kv_append_bf16_fits(int32_t n, int32_t N, int32_t K);
+void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
+                           int32_t K, void* ws, hipStream_t s);
 
 }  // namespace beagle

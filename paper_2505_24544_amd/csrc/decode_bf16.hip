@@ -20,6 +20,12 @@
 //   (D) skinny_gemm   y_part[ks] = o * Wo[k-slice ks]
 //   (E) sum_slices    y = sum_ks y_part[ks]  (bf16)
 //
+// With drafted states concatenated to the cache (section 6, "concate" with the
+// drafting tree) the rows at and past n_true are visible to a query only where
+// its row of the tree bitmask has a bit; (B) applies it to the 32-key blocks
+// that reach past n_true.  Appending up to 64 states to the cache runs (A) on
+// Wk and Wv in one launch (z = 0, 1) and (E) into the cache rows.
+//
 // Partial results cross workgroups only at kernel boundaries: on this chip a
 // device-scope fence inside a kernel writes back a whole L2 (the XCDs' L2s are
 // not coherent with each other), which costs far more than a launch.  All sums
@@ -60,8 +66,10 @@ constexpr int COMB_MAXM = 8, COMB_MAXR = 8;
 
 template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
-                                                             float* __restrict__ part, int M, int N, int K, CombineArgs cb) {
+                                                             float* __restrict__ part, int M, int N, int K, CombineArgs cb,
+                                                             const bf16_t* __restrict__ W_z1, float* __restrict__ part_z1) {
   using namespace dec;
+  if (blockIdx.z == 1) { W = W_z1; part = part_z1; }        // second weight matrix of the launch (same x)
   __shared__ __attribute__((aligned(1024))) bf16_t wt[SG_K * SG_N];     // 64 KB
   __shared__ __attribute__((aligned(16))) bf16_t xs[COMBINE ? COMB_MAXM * SG_K : 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
@@ -194,7 +202,9 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
 
 // y[m][n] = sum_ks part[ks][m][n]  -> bf16
 __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ part, bf16_t* __restrict__ y,
-                                                         int64_t MN, int KS) {
+                                                         int64_t MN, int KS, const float* __restrict__ part_z1,
+                                                         bf16_t* __restrict__ y_z1) {
+  if (blockIdx.z == 1) { part = part_z1; y = y_z1; }
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
   float4 s = *(const float4*)(part + i);
@@ -215,6 +225,9 @@ struct DecAttnArgs {
   float* opart; float* mlpart;            // [H][R][Mpad][128], [H][R][Mpad][2]
   int M, Mpad, L, H, G, R, range;
   float scale;
+  // draft tree (nullptr: all rows visible): rows >= n_true are visible to query m iff bit (row - n_true) of
+  // tree[m * tree_words ...] is set
+  const uint32_t* tree; int n_true, tree_words;
 };
 
 // One workgroup per (head, key range, block of 32 queries): grid (H, R, ceil(M / 32)).
@@ -365,6 +378,19 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         for (int e = 0; e < 16; ++e)
           if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
       }
+      if (a.tree != nullptr && jw + 32 > a.n_true) {
+        // drafted rows: bit i of `vis` says whether this lane's query sees key jw + i (true rows: yes)
+        const int off = jw - a.n_true;                       // tree bit of key jw; negative inside the true rows
+        const int w0 = off >> 5, sh = off & 31;              // floor division: -1 for the straddling block
+        const uint32_t* row = a.tree + (int64_t)(m0 + ql) * a.tree_words;
+        const bool real = ql < mrows;
+        const uint32_t lo = w0 < 0 ? 0xffffffffu : (real && w0 < a.tree_words ? row[w0] : 0u);
+        const uint32_t hi = real && w0 + 1 < a.tree_words ? row[w0 + 1] : 0u;
+        const uint32_t vis = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (!((vis >> (8 * (e >> 2) + 4 * hf + (e & 3))) & 1u)) st[e] = -INFINITY;
+      }
       float mx = st[0];
 #pragma unroll
       for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
@@ -383,7 +409,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
       }
-      const float mc = mrun * c2;
+      const float mc = (mrun == -INFINITY ? 0.f : mrun) * c2;   // nothing visible so far: p = exp2(-inf) = 0
       float rs = 0.f;
       uint32_t pk[8];
 #pragma unroll
@@ -535,7 +561,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
     {
       ProfScope ps("draft_proj_q", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
-                         Mp, HDt, a.D, CombineArgs{});
+                         Mp, HDt, a.D, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
     }
     {
       DecAttnArgs t;
@@ -543,6 +569,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       t.opart = opart; t.mlpart = mlpart;
       t.M = Mp; t.Mpad = w.Mpad; t.L = a.L; t.H = a.H; t.G = a.G; t.R = w.R; t.range = w.range;
       t.scale = a.scale;
+      t.tree = a.tree ? a.tree + (int64_t)m0 * a.tree_words : nullptr; t.n_true = a.n_true; t.tree_words = a.tree_words;
       ProfScope ps("draft_attn", s);
       hipLaunchKernelGGL(decode_attn_kernel, dim3(a.H, w.R, (Mp + 31) / 32), dim3(256), 0, s, t);
     }
@@ -553,7 +580,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       cb.scale = a.scale;
       ProfScope ps("draft_proj_out", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<true>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)nullptr,
-                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, cb);
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, cb, (const bf16_t*)nullptr, (float*)nullptr);
     } else {
       {
         ProfScope ps("draft_combine", s);
@@ -562,14 +589,42 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       }
       ProfScope ps("draft_proj_out", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)o,
-                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, CombineArgs{});
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
     }
     {
       ProfScope ps("draft_sum_out", s);
       const int64_t MN = (int64_t)Mp * a.D;
       hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, s, ypart,
-                         (bf16_t*)a.y + (int64_t)m0 * a.D, MN, w.KSo);
+                         (bf16_t*)a.y + (int64_t)m0 * a.D, MN, w.KSo, (const float*)nullptr, (bf16_t*)nullptr);
     }
+  }
+}
+
+// ---- K and V rows of up to 64 new states, written into the cache rows at kdst / vdst ([n][N] contiguous):
+// the two projections share one split-k launch (z = 0: Wk, z = 1: Wv) and one slice sum.
+size_t kv_append_bf16_ws_bytes(int32_t n, int32_t N, int32_t K) {
+  const int KS = (K + dec::SG_K - 1) / dec::SG_K;
+  return 2 * up256((size_t)KS * n * N * 4);
+}
+bool kv_append_bf16_fits(int32_t n, int32_t N, int32_t K) {
+  return n >= 1 && n <= dec::MAXM && N % dec::SG_N == 0 && K % 8 == 0 && (int64_t)K * N * 2 < ((int64_t)1 << 31);
+}
+void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
+                           int32_t K, void* ws, hipStream_t s) {
+  using namespace dec;
+  const int KS = (K + SG_K - 1) / SG_K;
+  float* kpart = (float*)ws;
+  float* vpart = (float*)((char*)ws + up256((size_t)KS * n * N * 4));
+  {
+    ProfScope ps("kv_append_proj", s);
+    hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(N / SG_N, KS, 2), dim3(256), 0, s, (const bf16_t*)x,
+                       (const bf16_t*)wk, kpart, n, N, K, CombineArgs{}, (const bf16_t*)wv, vpart);
+  }
+  {
+    ProfScope ps("kv_append_sum", s);
+    const int64_t MN = (int64_t)n * N;
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((MN / 4 + 255) / 256), 1, 2), dim3(256), 0, s, kpart,
+                       (bf16_t*)kdst, MN, KS, (const float*)vpart, (bf16_t*)vdst);
   }
 }
 

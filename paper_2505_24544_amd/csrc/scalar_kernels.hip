@@ -153,22 +153,35 @@ __global__ __launch_bounds__(64) void attn_fwd_scalar_kernel(AttnArgs a) {
     if (lane == 0) a.lse[li] = -INFINITY;
     return;
   }
+  // draft-tree decode: keys at or past n_true are visible only where the query's tree row has a bit
+  const uint32_t* trow = a.tree ? a.tree + (int64_t)p * a.tree_words : nullptr;
+  auto visible = [&](int j) {
+    if (trow == nullptr || j < a.n_true) return true;
+    const int t = j - a.n_true;
+    return ((trow[t >> 5] >> (t & 31)) & 1u) != 0;
+  };
   // pass A: row max and sum of exponentials, online per lane, then merged
   float m = -INFINITY, l = 0.f;
   for (int j = lane; j < n; j += 64) {
+    if (!visible(j)) continue;
     float s = a.scale * dot_row(qs, K + j * kvs, d);
     float mn = fmaxf(m, s);
     l = l * expf(m - mn) + expf(s - mn);
     m = mn;
   }
   const float mw = wave_max(m);
+  if (mw == -INFINITY) {                       // the tree hides every row from this query
+    for (int c = lane; c < d; c += 64) Io<T>::st(O + c, 0.f);
+    if (lane == 0) a.lse[li] = -INFINITY;
+    return;
+  }
   l = wave_sum(m == -INFINITY ? 0.f : l * expf(m - mw));
   const float lse = mw + logf(l);
   // pass B: probabilities from the final lse, weighted sum of V
   float acc0 = 0.f, acc1 = 0.f;
   for (int j0 = 0; j0 < n; j0 += 64) {
     int j = j0 + lane;
-    pch[lane] = j < n ? expf(a.scale * dot_row(qs, K + j * kvs, d) - lse) : 0.f;
+    pch[lane] = (j < n && visible(j)) ? expf(a.scale * dot_row(qs, K + j * kvs, d) - lse) : 0.f;
     __syncthreads();
     int cnt = min(64, n - j0);
     for (int jj = 0; jj < cnt; ++jj) {

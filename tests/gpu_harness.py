@@ -109,6 +109,47 @@ def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
     return to_host(y), to_host(lse)
 
 
+def pack_tree_mask(tree_bool):
+    """bool [M, T] -> uint32 [M, max(1, ceil(T/32))] with bit (t % 32) of word t // 32."""
+    tm = np.asarray(tree_bool, bool)
+    M, T = tm.shape
+    words = max(1, (T + 31) // 32)
+    out = np.zeros((M, words), np.uint32)
+    for t in range(T):
+        out[:, t // 32] |= (tm[:, t].astype(np.uint32) << np.uint32(t % 32))
+    return out
+
+
+def run_draft_tree(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True):
+    """Like run_draft with kc/vc holding n_true true rows then the drafted rows; tree_bool [M, T]."""
+    d = desc_of(cfg, 0, scale)
+    M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
+    t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
+    packed = pack_tree_mask(tree_bool)
+    tm = torch.from_numpy(packed.view(np.int32)).to(DEV)
+    y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
+    lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(d, bx.BEAGLE_WS_DRAFT)
+    st = bx.beagle_xattn_draft_step_tree(d, t["x"], t["kc"], t["vc"], t["wq"], t["wo"], n_true, tm, packed.shape[1],
+                                         y, lse, ws, check=check)
+    torch.cuda.synchronize()
+    if not check:
+        return st
+    return to_host(y), to_host(lse)
+
+
+def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True):
+    """kc/vc: host arrays [capacity, G, d] (current cache contents).  Returns the caches after the call."""
+    d = desc_of(cfg, 0, 0.0)
+    t = {n: to_dev(a, cfg) for n, a in dict(x=x_new, wk=wk, wv=wv, kc=kc, vc=vc).items()}
+    ws = workspace(d, bx.BEAGLE_WS_APPEND)
+    st = bx.beagle_xattn_kv_append(d, t["x"], t["wk"], t["wv"], t["kc"], t["vc"], pos, ws, check=check)
+    torch.cuda.synchronize()
+    if not check:
+        return st
+    return to_host(t["kc"]), to_host(t["vc"])
+
+
 # ------------------------------------------------------------------ metrics
 def max_abs(a, b):
     return float(np.max(np.abs(a - b))) if a.size else 0.0
