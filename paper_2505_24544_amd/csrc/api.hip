@@ -49,6 +49,11 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
     return BEAGLE_ERR_UNSUPPORTED;
   if (d.bf16) {
     if (d.d != 128 || d.D % 64) return BEAGLE_ERR_UNSUPPORTED;
+    // the bf16 kernels address one batch entry's Q / K / V slab, and the decode step a whole weight matrix,
+    // through 32-bit buffer descriptors
+    const int64_t lim = (int64_t)1 << 31;
+    if (d.S * d.HD * 2 >= lim || d.L * d.GD * 2 >= lim) return BEAGLE_ERR_UNSUPPORTED;
+    if (draft && (d.D * d.HD * 2 >= lim || d.D * d.GD * 2 >= lim)) return BEAGLE_ERR_UNSUPPORTED;
   } else {
     if (d.d > 128 || d.d % 4 || d.D % 4) return BEAGLE_ERR_UNSUPPORTED;
   }

@@ -94,6 +94,27 @@ def test_invalid_descriptors_are_rejected_on_the_host():
         assert ei.value.status == 3
     with pytest.raises(E):
         bx.beagle_xattn_tile_map(_desc(), 0, 4)
+    # bf16: one batch entry's K/V slab must stay below 2 GiB (32-bit buffer descriptors)
+    big = dict(io_dtype=bx.BEAGLE_BF16, head_dim=128, hidden=4096, n_q_heads=32, n_kv_heads=32)
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=262143, **big), bx.BEAGLE_WS_FWD) > 0
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=262144, **big), bx.BEAGLE_WS_FWD) == 0
+
+
+def test_tree_and_append_entry_points_validate_before_launching():
+    d = _desc(S=4, L=100)
+    a = 4096
+    ws = 1 << 30
+    tree = lambda n_true, mask, words: bx.beagle_xattn_draft_step_tree(
+        d, a, a, a, a, a, n_true, mask, words, a, a, a, stream=0, workspace_bytes=ws, check=False)
+    assert tree(101, a, 4) == 2 and tree(-1, a, 4) == 2          # n_true outside [0, L]
+    assert tree(50, None, 2) == 1                                 # drafted rows but no mask
+    assert tree(50, a, 1) == 2                                    # 50 drafted rows need 2 words
+    assert tree(50, a + 2, 2) == 5                                # mask not 4-byte aligned
+    app = lambda pos, wsb=ws: bx.beagle_xattn_kv_append(d, a, a, a, a, a, pos, a, stream=0, workspace_bytes=wsb,
+                                                        check=False)
+    assert app(97) == 2 and app(-1) == 2                          # rows pos .. pos+3 must fit in 100
+    assert app(0, 8) == 4
+    assert bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_APPEND) > 0
 
 
 def test_entry_points_validate_before_launching():
