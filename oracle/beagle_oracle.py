@@ -227,6 +227,87 @@ def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
 
 
 # --------------------------------------------------------------------------
+# Late-stage training: simulated inference steps (section 4.2, second half, and
+# the caption of the mask figure; the figure itself is not available)
+#
+# The keys of a query come from two sources: the true target states Xkv, under
+# the early-stage mask, and a buffer Xp of states that the draft model itself
+# predicted in the earlier simulation steps of this training iteration (one
+# buffer of the sequence's size, updated in place: "constant space").  After t
+# steps the first t positions of every window hold predicted states, and a
+# query may use those of its own window that lie before it.
+#
+# Readings taken here (PARITY UNPINNED by the paper beyond the prose: the
+# figure that defines the masks is missing from the text):
+#   * step t >= 0; t = 0 is the early-stage mask (no predicted key visible);
+#   * query p, whose window starts at w0(p) = eps + k*floor((p - eps)/k) (below
+#     zero for the partial leading window), sees predicted key j iff
+#     max(w0(p), 0) <= j < min(p, w0(p) + t): positions are counted from the
+#     window's own start also in the leading partial window;
+#   * queries are not unrolled: Xq is the same in every step;
+#   * K and V of the predicted states use the same Wk, Wv as the true states.
+# --------------------------------------------------------------------------
+def sim_pred_mask_loops(seq_q: int, seq_kv: int, k: int, eps: int, t: int) -> np.ndarray:
+    """Boolean [seq_q, seq_kv]: True where query p may attend PREDICTED key j at
+    simulation step t.  Element by element from the prose: inside each window,
+    the states predicted so far are those of its first t positions, and a query
+    reaches the ones strictly before itself."""
+    if t < 0:
+        raise ValueError("simulation step must be >= 0")
+    m = np.zeros((seq_q, seq_kv), dtype=bool)
+    for n in _window_starts(seq_q, k, eps):
+        for p in range(max(n, 0), min(n + k, seq_q)):
+            for j in range(max(n, 0), min(n + k, seq_kv)):
+                if j < p and j - n < t:
+                    m[p, j] = True
+    return m
+
+
+def sim_pred_mask(seq_q: int, seq_kv: int, k: int, eps: int, t: int) -> np.ndarray:
+    """Same mask as sim_pred_mask_loops from the closed form
+    max(w0(p), 0) <= j < min(p, w0(p) + t), affordable at full size."""
+    if t < 0 or k < 1 or not (0 <= eps < k):
+        raise ValueError("need t >= 0, k >= 1 and 0 <= eps < k")
+    p = np.arange(seq_q)[:, None]
+    j = np.arange(seq_kv)[None, :]
+    w0 = eps + k * np.floor_divide(p - eps, k)
+    return (j >= np.maximum(w0, 0)) & (j < np.minimum(p, w0 + t))
+
+
+def _sim_concat(xkv, xpred, k, eps, t, seq_q):
+    xkv, xpred = np.asarray(xkv, F64), np.asarray(xpred, F64)
+    if xkv.shape != xpred.shape:
+        raise ValueError("the predicted-state buffer has the shape of the target states")
+    L = xkv.shape[1]
+    mask = np.concatenate([dense_mask(seq_q, L, k, eps), sim_pred_mask(seq_q, L, k, eps, t)], axis=1)
+    return np.concatenate([xkv, xpred], axis=1), mask, L
+
+
+def xattn_forward_sim(xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None):
+    """Forward of simulation step t: Eq. 2 over the keys [true states under the
+    early-stage mask | predicted states under sim_pred_mask].  Returns the dict
+    of xattn_forward with k, v split into k, v (true) and kp, vp (predicted)."""
+    cat, mask, L = _sim_concat(xkv, xpred, k, eps, t, np.asarray(xq).shape[1])
+    out = xattn_forward(xq, cat, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask, scale=scale)
+    out["kp"], out["vp"] = out["k"][:, L:], out["v"][:, L:]
+    out["k"], out["v"] = out["k"][:, :L], out["v"][:, :L]
+    return out
+
+
+def xattn_backward_sim(dy, xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None):
+    """Gradients of simulation step t with respect to every input, the
+    predicted-state buffer included (dxpred; zero on rows that no query sees)."""
+    cat, mask, L = _sim_concat(xkv, xpred, k, eps, t, np.asarray(xq).shape[1])
+    out = xattn_backward(dy, xq, cat, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask,
+                         scale=scale)
+    out["dxpred"] = out["dxkv"][:, L:]
+    out["dxkv"] = out["dxkv"][:, :L]
+    for n in ("k", "v", "dk", "dv"):
+        out[n + "p"], out[n] = out[n][:, L:], out[n][:, :L]
+    return out
+
+
+# --------------------------------------------------------------------------
 # Decode-time draft step (section 4.1, KV-cache paragraph)
 # --------------------------------------------------------------------------
 def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None):
