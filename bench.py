@@ -156,6 +156,37 @@ def main():
                         traffic=MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom), avg_ms=round(avg, 4),
                         flops_per_launch=kf.get(dom))
 
+    # ---- late-stage simulation step (true keys + the predicted-state band), same workload, step t = 3
+    sim = None
+    if not args.no_decode:
+        tsim = min(3, cfg.block_size - 1)
+        xp = t["xkv"].flip(1).contiguous()             # any states of the right shape: time is value-independent
+        kp, vp, dxp = E(B, L, G, hd), E(B, L, G, hd), E(B, L, D)
+        ws_s = gh.workspace(desc, bx.BEAGLE_WS_BWD_SIM)
+
+        def sim_step():
+            bx.beagle_xattn_fwd_sim(desc, t["xq"], t["xkv"], xp, t["wq"], t["wk"], t["wv"], t["wo"], tsim, y, lse,
+                                    q, k, v, kp, vp, o, ws_f, stream)
+            bx.beagle_xattn_bwd_sim(desc, t["dy"], t["xq"], t["xkv"], xp, t["wq"], t["wk"], t["wv"], t["wo"], q, k, v,
+                                    kp, vp, o, lse, tsim, dxq, dxkv, dxp, dwq, dwk, dwv, dwo, ws_s, stream)
+        for _ in range(3):
+            sim_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nsim = max(1, args.steps // 2)
+        for _ in range(nsim):
+            sim_step()
+        torch.cuda.synchronize()
+        ms_sim = (time.perf_counter() - t0) / nsim * 1e3
+        # algorithmic FLOPs: the early-stage step + the projections of the predicted states (forward K, V;
+        # backward dXpred and their share of dWk, dWv) + the band (4 d forward, 10 d backward per visible pair)
+        band_pairs = B * H * sum(min(i, tsim) for i in range(cfg.block_size)) * (S // cfg.block_size)
+        fl_sim = fl["total"] + 3 * (fl["proj"]["k"] + fl["proj"]["v"]) + 14 * hd * band_pairs
+        sim = dict(sim_step=tsim, ms_per_step=round(ms_sim, 4), tflops=round(fl_sim / (ms_sim * 1e-3) / 1e12, 1),
+                   pct_bf16_mfma_peak=round(100 * fl_sim / (ms_sim * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                   algorithmic_tflop_per_step=round(fl_sim / 1e12, 4))
+        del xp, kp, vp, dxp, ws_s
+
     # ---- decode: draft step, cold HBM via buffer rotation
     decode = None
     if not args.no_decode:
@@ -176,7 +207,7 @@ def main():
         "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "tokens_per_s": round(B * S / (ms_step * 1e-3)),
         "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
-        "roofline": roofline, "kernels": kernels, "decode": decode, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "late_stage_sim": sim, "decode": decode, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

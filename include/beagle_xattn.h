@@ -69,7 +69,7 @@ enum {
                                       when io_dtype is bf16                     */
 };
 
-enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3 };
+enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3, BEAGLE_WS_BWD_SIM = 4 };
 
 typedef struct {
   int32_t struct_size;   /* sizeof(beagle_xattn_desc); checked                  */
@@ -141,6 +141,48 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
 beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache,
     const void* wq, const void* wo, void* y, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Late-stage training: one simulated inference step (section 4.2, second
+ * half, and the caption of the mask figure).  Keys come from two sources: the
+ * true target states xkv under the early-stage mask of beagle_xattn_fwd, and
+ * the buffer xpred [B,L,D] of states that the draft model predicted in the
+ * earlier simulation steps of this iteration (updated in place by the caller
+ * between steps: constant space).  At step sim_step = t >= 0 query p, whose
+ * window starts at w0(p) = eps + k*floor((p - eps)/k), also sees predicted key
+ * j iff max(w0(p), 0) <= j < min(p, w0(p) + t): the first t positions of its
+ * own window that lie before it.  t = 0 is beagle_xattn_fwd; t >= k - 1 shows
+ * every earlier position of the window.  Queries are not unrolled (xq is the
+ * same in every step); predicted states are projected with the same Wk, Wv.
+ * Requires seq_q == seq_kv.
+ *   in : as beagle_xattn_fwd, plus xpred [B,L,D]
+ *   out: as beagle_xattn_fwd, plus kp_save, vp_save [B,L,G,d] (K, V of xpred)
+ */
+beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
+    const void* xq, const void* xkv, const void* xpred, const void* wq,
+    const void* wk, const void* wv, const void* wo, int32_t sim_step,
+    void* y, float* lse, void* q_save, void* k_save, void* v_save,
+    void* kp_save, void* vp_save, void* o_save,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of the simulated step: as beagle_xattn_bwd, with the gradient of
+ * the predicted-state buffer as an additional output, and with Wk, Wv
+ * receiving the contributions of both key sources:
+ *   dWk = Xkv^T dK + Xpred^T dKp, dWv likewise, dXpred = dKp Wk^T + dVp Wv^T
+ * (rows of xpred that no query sees get exactly zero).
+ *   in : as beagle_xattn_bwd, plus xpred, kp_save, vp_save and sim_step
+ *   out: as beagle_xattn_bwd, plus dxpred [B,L,D] (required)
+ * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM).
+ */
+beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
+    const void* dy, const void* xq, const void* xkv, const void* xpred,
+    const void* wq, const void* wk, const void* wv, const void* wo,
+    const void* q_save, const void* k_save, const void* v_save,
+    const void* kp_save, const void* vp_save, const void* o_save,
+    const float* lse, int32_t sim_step,
+    void* dxq, void* dxkv, void* dxpred, void* dwq, void* dwk, void* dwv, void* dwo,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*

@@ -21,13 +21,13 @@ BEAGLE_OK = 0
  BEAGLE_ERR_HIP) = range(1, 7)
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
 BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32 = 1, 2
-BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND = 0, 1, 2, 3
+BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
                 4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
-    "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append",
+    "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -76,6 +76,10 @@ def lib() -> C.CDLL:
     L.beagle_xattn_bwd.argtypes = [dp] + [vp] * 18 + [vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step.restype = C.c_int
     L.beagle_xattn_draft_step.argtypes = [dp] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_fwd_sim.restype = C.c_int
+    L.beagle_xattn_fwd_sim.argtypes = [dp] + [vp] * 7 + [C.c_int32] + [vp] * 8 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_bwd_sim.restype = C.c_int
+    L.beagle_xattn_bwd_sim.argtypes = [dp] + [vp] * 15 + [C.c_int32] + [vp] * 7 + [vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step_tree.restype = C.c_int
     L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
@@ -128,6 +132,27 @@ def _check(st, where, check):
     if check and st != BEAGLE_OK:
         raise BeagleError(st, where)
     return st
+
+
+def beagle_xattn_fwd_sim(desc, xq, xkv, xpred, wq, wk, wv, wo, sim_step, y, lse, q_save, k_save, v_save,
+                         kp_save, vp_save, o_save, workspace=None, stream=None, *, workspace_bytes=None,
+                         check=True) -> int:
+    st = lib().beagle_xattn_fwd_sim(
+        C.byref(desc), *(_ptr(t) for t in (xq, xkv, xpred, wq, wk, wv, wo)), int(sim_step),
+        *(_ptr(t) for t in (y, lse, q_save, k_save, v_save, kp_save, vp_save, o_save)),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_fwd_sim", check)
+
+
+def beagle_xattn_bwd_sim(desc, dy, xq, xkv, xpred, wq, wk, wv, wo, q_save, k_save, v_save, kp_save, vp_save,
+                         o_save, lse, sim_step, dxq, dxkv, dxpred, dwq, dwk, dwv, dwo, workspace, stream=None, *,
+                         workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_bwd_sim(
+        C.byref(desc), *(_ptr(t) for t in (dy, xq, xkv, xpred, wq, wk, wv, wo, q_save, k_save, v_save, kp_save,
+                                           vp_save, o_save, lse)), int(sim_step),
+        *(_ptr(t) for t in (dxq, dxkv, dxpred, dwq, dwk, dwv, dwo)),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_bwd_sim", check)
 
 
 def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true, tree_mask, mask_words, y, lse,

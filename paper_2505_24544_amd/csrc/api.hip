@@ -250,6 +250,12 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
     case BEAGLE_WS_DRAFT:
       if (d.bf16) return align_up(decode_bf16_ws_bytes((int32_t)d.S, (int32_t)d.L, (int32_t)d.H, (int32_t)d.d, (int32_t)d.D));
       return align_up((size_t)(2 * d.S * d.HD) * d.esz);
+    case BEAGLE_WS_BWD_SIM: {
+      BwdWs w = bwd_layout(d);
+      size_t extra = 0;
+      if (d.bf16) { AttnArgs a = attn_args(d); extra = attn_bwd_bf16_ws_bytes(a); }
+      return w.total + align_up(extra) + 2 * align_up((size_t)(d.B * d.L * d.GD) * d.esz);   // + dKp, dVp
+    }
     case BEAGLE_WS_APPEND:
       if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))
         return WS_ALIGN + align_up(kv_append_bf16_ws_bytes((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D));
@@ -344,6 +350,117 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
     g.p[0] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
     g.p[1] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);
     g.p[2] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
+    run_gemm(d, g, s, "bwd_dw");
+  }
+  return hip_status();
+}
+
+// ----------------------------------------------- late-stage simulation step
+beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
+    const void* xq, const void* xkv, const void* xpred, const void* wq, const void* wk, const void* wv,
+    const void* wo, int32_t sim_step, void* y, float* lse, void* q_save, void* k_save, void* v_save,
+    void* kp_save, void* vp_save, void* o_save, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  const void* ptrs[] = {xq, xkv, xpred, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, kp_save, vp_save, o_save};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  (void)workspace; (void)workspace_bytes;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+
+  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
+  qkv.count = 3;
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
+  run_gemm(d, qkv, s, "proj_qkv");
+  GemmGroup kvp; memset(&kvp, 0, sizeof(kvp));
+  kvp.count = 2;
+  kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.B * d.L, d.GD, d.D);
+  kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.B * d.L, d.GD, d.D);
+  run_gemm(d, kvp, s, "proj_kvp");
+
+  SimArgs sa; memset(&sa, 0, sizeof(sa));
+  sa.a = attn_args(d);
+  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = o_save; sa.a.lse = lse;
+  sa.kp = kp_save; sa.vp = vp_save; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
+  if (d.bf16) launch_attn_fwd_bf16(sa.a, s); else launch_attn_fwd_f32(sa.a, s);
+  if (sim_step > 0) launch_sim_band_fwd(sa, s);
+
+  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD)), s, "proj_out");
+  return hip_status();
+}
+
+beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
+    const void* dy, const void* xq, const void* xkv, const void* xpred, const void* wq, const void* wk,
+    const void* wv, const void* wo, const void* q_save, const void* k_save, const void* v_save,
+    const void* kp_save, const void* vp_save, const void* o_save, const float* lse, int32_t sim_step,
+    void* dxq, void* dxkv, void* dxpred, void* dwq, void* dwk, void* dwv, void* dwo,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  const bool need_dxkv = desc->flags & BEAGLE_FLAG_NEED_DXKV;
+  const void* ptrs[] = {dy, xq, xkv, xpred, wq, wk, wv, wo, q_save, k_save, v_save, kp_save, vp_save, o_save, lse,
+                        dxq, dxpred, dwq, dwk, dwv, dwo, workspace};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  if (need_dxkv && !dxkv) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (dxkv && !aligned16(dxkv)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM)) return BEAGLE_ERR_WORKSPACE;
+  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+
+  const BwdWs w = bwd_layout(d);
+  char* base = (char*)workspace;
+  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
+  float* delta = (float*)(base + w.delta);
+  size_t extra = 0;
+  if (d.bf16) { AttnArgs t = attn_args(d); extra = attn_bwd_bf16_ws_bytes(t); }
+  const size_t kvb = align_up((size_t)(d.B * d.L * d.GD) * d.esz);
+  void* dKp = base + w.total + align_up(extra);
+  void* dVp = (char*)dKp + kvb;
+  const bool wf32 = d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32);
+  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
+
+  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
+  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
+
+  // true-key part: the main kernels, given the merged LSE and delta = rowsum(dO * O) of the merged O
+  SimArgs sa; memset(&sa, 0, sizeof(sa));
+  sa.a = attn_args(d);
+  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = (void*)o_save; sa.a.lse = (float*)lse;
+  sa.a.dout = dO; sa.a.dq = dQ; sa.a.dk = dK; sa.a.dv = dV; sa.a.delta = delta;
+  sa.kp = kp_save; sa.vp = vp_save; sa.dkp = dKp; sa.dvp = dVp; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
+  if (d.bf16) launch_attn_bwd_bf16(sa.a, base + w.attn, s); else launch_attn_bwd_f32(sa.a, s);
+  // predicted-key band: adds to dQ, writes dKp and dVp (zeros where nothing is seen)
+  launch_sim_band_bwd(sa, s);
+
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 2;
+    g.p[0] = gemm_nt(dKp, wk, dxpred, Mk, d.D, d.GD);
+    g.p[0].A2 = dVp; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
+    g.p[1] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
+    if (need_dxkv) {
+      g.count = 3;
+      g.p[2] = g.p[1];
+      g.p[1] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
+      g.p[1].A2 = dV; g.p[1].B2 = wv; g.p[1].K2 = (int32_t)d.GD; g.p[1].lda2 = d.GD; g.p[1].ldb2 = d.GD;
+    }
+    run_gemm(d, g, s, "bwd_dx");
+  }
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 3;
+    g.p[0] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);        // two k segments: true and predicted rows
+    g.p[0].A2 = xpred; g.p[0].B2 = dKp; g.p[0].K2 = (int32_t)Mk; g.p[0].lda2 = d.D; g.p[0].ldb2 = d.GD;
+    g.p[1] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
+    g.p[1].A2 = xpred; g.p[1].B2 = dVp; g.p[1].K2 = (int32_t)Mk; g.p[1].lda2 = d.D; g.p[1].ldb2 = d.GD;
+    g.p[2] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
     run_gemm(d, g, s, "bwd_dw");
   }
   return hip_status();

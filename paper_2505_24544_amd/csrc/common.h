@@ -71,6 +71,17 @@ struct AttnArgs {
   // draft-tree decode only: keys >= n_true are visible to query p iff bit (j - n_true) of row p is set
   const uint32_t* tree; int32_t n_true, tree_words;
 };
+// Late-stage simulation: the band of predicted keys of every query, merged into / differentiated
+// against the result of the masked attention over the true keys.
+struct SimArgs {
+  AttnArgs a;                       // q, o, lse (in/out), dout, dq (in/out), delta as in the main kernels
+  const void* kp; const void* vp;   // [B,L,G,d] predicted-state keys / values
+  void* dkp; void* dvp;             // [B,L,G,d]
+  int32_t t;                        // simulation step, 0 <= t
+  int32_t is_bf16;
+};
+void launch_sim_band_fwd(const SimArgs& s, hipStream_t st);
+void launch_sim_band_bwd(const SimArgs& s, hipStream_t st);
 void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_fwd_bf16_scalar(const AttnArgs& a, hipStream_t s);

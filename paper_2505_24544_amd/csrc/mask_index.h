@@ -28,6 +28,25 @@ BEAGLE_HD int32_t window_start(int32_t p, int32_t k, int32_t eps) {
   return eps + (t / k) * k;
 }
 
+// Start of the window that holds position p, NOT clamped: below zero for the
+// partial leading window (floor division toward minus infinity).
+BEAGLE_HD int32_t window_start_raw(int32_t p, int32_t k, int32_t eps) {
+  int32_t t = p - eps;
+  int32_t w = t >= 0 ? t / k : -((-t + k - 1) / k);
+  return eps + w * k;
+}
+
+// Late-stage simulation, step t (section 4.2, second half): the predicted keys
+// that query p may attend are [lo, hi): the first t positions of p's own
+// window that lie before p.  hi <= lo: none.
+BEAGLE_HD void sim_band(int32_t p, int32_t k, int32_t eps, int32_t t, int32_t seq_kv, int32_t& lo, int32_t& hi) {
+  int32_t w0 = window_start_raw(p, k, eps);
+  lo = w0 > 0 ? w0 : 0;
+  hi = w0 + t;
+  if (hi > p) hi = p;
+  if (hi > seq_kv) hi = seq_kv;
+}
+
 // Number of keys visible to query p (they are keys 0 .. limit-1).
 BEAGLE_HD int32_t row_limit(int32_t p, const MaskParams& mp) {
   if (mp.all_visible) return mp.seq_kv;

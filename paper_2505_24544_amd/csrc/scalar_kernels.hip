@@ -319,6 +319,146 @@ static void attn_bwd_scalar(const AttnArgs& a, hipStream_t s, const char* n1, co
 }
 
 void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s) { attn_fwd_scalar<float>(a, s, "attn_fwd_f32"); }
+// --------------------------------------------------------------------------
+// Late-stage simulation (section 4.2, second half): every query also sees the
+// predicted states of at most t earlier positions of its own window.  That
+// band is a handful of keys per query, so it runs as plain FMA code, one
+// wavefront per query row (forward, dQ) or per predicted key row (dKp, dVp),
+// lanes owning head channels:
+//   forward : (O, LSE) of the masked attention over the true keys is merged
+//             with the band: LSE' = logaddexp(LSE, lse_band), O' the weighted mean;
+//   backward: the main kernels, given LSE' and delta = rowsum(dO * O'), already
+//             produce the true-key parts; the band adds its share to dQ and
+//             yields dKp, dVp (zero on rows that no query sees).
+// --------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(64) void sim_band_fwd_kernel(SimArgs s) {
+  const AttnArgs& a = s.a;
+  const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  int lo, hi;
+  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
+  if (hi <= lo) return;
+  const int d = a.d, g = h / (a.H / a.G);
+  const int64_t kvs = (int64_t)a.G * d;
+  const T* Q = (const T*)a.q + (((int64_t)b * a.S + p) * a.H + h) * d;
+  T* O = (T*)a.o + (((int64_t)b * a.S + p) * a.H + h) * d;
+  const T* Kp = (const T*)s.kp + ((int64_t)b * a.L * a.G + g) * d;
+  const T* Vp = (const T*)s.vp + ((int64_t)b * a.L * a.G + g) * d;
+  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  const bool c0 = lane < d, c1 = lane + 64 < d;
+  const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
+  float m = a.lse[li];                                   // weight of the true-key part: exp(m) * 1
+  float l = m > -INFINITY ? 1.f : 0.f;
+  float acc0 = (c0 && l > 0.f) ? Io<T>::ld(O + lane) : 0.f, acc1 = (c1 && l > 0.f) ? Io<T>::ld(O + lane + 64) : 0.f;
+  for (int j = lo; j < hi; ++j) {
+    const T* kr = Kp + j * kvs;
+    const T* vr = Vp + j * kvs;
+    const float sc = a.scale * wave_sum((c0 ? q0 * Io<T>::ld(kr + lane) : 0.f) + (c1 ? q1 * Io<T>::ld(kr + lane + 64) : 0.f));
+    const float mn = fmaxf(m, sc);
+    const float al = expf(m - mn), pj = expf(sc - mn);   // m = -inf: al = 0
+    acc0 = acc0 * al + (c0 ? pj * Io<T>::ld(vr + lane) : 0.f);
+    acc1 = acc1 * al + (c1 ? pj * Io<T>::ld(vr + lane + 64) : 0.f);
+    l = l * al + pj;
+    m = mn;
+  }
+  const float inv = 1.f / l;
+  if (c0) Io<T>::st(O + lane, acc0 * inv);
+  if (c1) Io<T>::st(O + lane + 64, acc1 * inv);
+  if (lane == 0) a.lse[li] = m + logf(l);
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void sim_band_bwd_dq_kernel(SimArgs s) {
+  const AttnArgs& a = s.a;
+  const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  int lo, hi;
+  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
+  if (hi <= lo) return;
+  const int d = a.d, g = h / (a.H / a.G);
+  const int64_t kvs = (int64_t)a.G * d;
+  const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * d;
+  const T* Q = (const T*)a.q + row;
+  const T* dO = (const T*)a.dout + row;
+  T* dQ = (T*)a.dq + row;
+  const T* Kp = (const T*)s.kp + ((int64_t)b * a.L * a.G + g) * d;
+  const T* Vp = (const T*)s.vp + ((int64_t)b * a.L * a.G + g) * d;
+  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  const bool c0 = lane < d, c1 = lane + 64 < d;
+  const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
+  const float g0 = c0 ? Io<T>::ld(dO + lane) : 0.f, g1 = c1 ? Io<T>::ld(dO + lane + 64) : 0.f;
+  const float lse = a.lse[li], delta = a.delta[li];
+  float a0 = 0.f, a1 = 0.f;
+  for (int j = lo; j < hi; ++j) {
+    const T* kr = Kp + j * kvs;
+    const T* vr = Vp + j * kvs;
+    const float k0 = c0 ? Io<T>::ld(kr + lane) : 0.f, k1 = c1 ? Io<T>::ld(kr + lane + 64) : 0.f;
+    const float v0 = c0 ? Io<T>::ld(vr + lane) : 0.f, v1 = c1 ? Io<T>::ld(vr + lane + 64) : 0.f;
+    const float pj = expf(a.scale * wave_sum(q0 * k0 + q1 * k1) - lse);
+    const float ds = pj * (wave_sum(g0 * v0 + g1 * v1) - delta);
+    a0 = fmaf(ds, k0, a0);
+    a1 = fmaf(ds, k1, a1);
+  }
+  if (c0) Io<T>::st(dQ + lane, Io<T>::ld(dQ + lane) + a0 * a.scale);
+  if (c1) Io<T>::st(dQ + lane + 64, Io<T>::ld(dQ + lane + 64) + a1 * a.scale);
+}
+
+template <typename T>
+__global__ __launch_bounds__(64) void sim_band_bwd_dkv_kernel(SimArgs s) {
+  const AttnArgs& a = s.a;
+  const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const int d = a.d, rep = a.H / a.G;
+  const int64_t kvrow = (((int64_t)b * a.L + j) * a.G + g) * d;
+  const T* kr = (const T*)s.kp + kvrow;
+  const T* vr = (const T*)s.vp + kvrow;
+  const bool c0 = lane < d, c1 = lane + 64 < d;
+  float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
+  const int w0 = window_start_raw(j, a.mask.k, a.mask.eps);
+  if (j - w0 < s.t) {                                  // this position holds a predicted state at step t
+    const float k0 = c0 ? Io<T>::ld(kr + lane) : 0.f, k1 = c1 ? Io<T>::ld(kr + lane + 64) : 0.f;
+    const float v0 = c0 ? Io<T>::ld(vr + lane) : 0.f, v1 = c1 ? Io<T>::ld(vr + lane + 64) : 0.f;
+    const int p_end = min(w0 + a.mask.k, a.S);         // the later queries of the same window see it
+    for (int p = j + 1; p < p_end; ++p)
+      for (int hh = 0; hh < rep; ++hh) {
+        const int h = g * rep + hh;
+        const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * d;
+        const T* Q = (const T*)a.q + row;
+        const T* dO = (const T*)a.dout + row;
+        const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+        const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
+        const float g0 = c0 ? Io<T>::ld(dO + lane) : 0.f, g1 = c1 ? Io<T>::ld(dO + lane + 64) : 0.f;
+        const float pj = expf(a.scale * wave_sum(q0 * k0 + q1 * k1) - a.lse[li]);
+        const float ds = pj * (wave_sum(g0 * v0 + g1 * v1) - a.delta[li]);
+        dk0 = fmaf(ds, q0, dk0); dk1 = fmaf(ds, q1, dk1);
+        dv0 = fmaf(pj, g0, dv0); dv1 = fmaf(pj, g1, dv1);
+      }
+  }
+  T* dK = (T*)s.dkp + kvrow;
+  T* dV = (T*)s.dvp + kvrow;
+  if (c0) { Io<T>::st(dK + lane, dk0 * a.scale); Io<T>::st(dV + lane, dv0); }
+  if (c1) { Io<T>::st(dK + lane + 64, dk1 * a.scale); Io<T>::st(dV + lane + 64, dv1); }
+}
+
+void launch_sim_band_fwd(const SimArgs& s, hipStream_t st) {
+  ProfScope ps("sim_band_fwd", st);
+  dim3 grid(s.a.S, s.a.H, s.a.B);
+  if (s.is_bf16) hipLaunchKernelGGL(sim_band_fwd_kernel<bf16_t>, grid, dim3(64), 0, st, s);
+  else hipLaunchKernelGGL(sim_band_fwd_kernel<float>, grid, dim3(64), 0, st, s);
+}
+void launch_sim_band_bwd(const SimArgs& s, hipStream_t st) {
+  {
+    ProfScope ps("sim_band_bwd_dq", st);
+    dim3 grid(s.a.S, s.a.H, s.a.B);
+    if (s.is_bf16) hipLaunchKernelGGL(sim_band_bwd_dq_kernel<bf16_t>, grid, dim3(64), 0, st, s);
+    else hipLaunchKernelGGL(sim_band_bwd_dq_kernel<float>, grid, dim3(64), 0, st, s);
+  }
+  {
+    ProfScope ps("sim_band_bwd_dkv", st);
+    dim3 grid(s.a.L, s.a.G, s.a.B);
+    if (s.is_bf16) hipLaunchKernelGGL(sim_band_bwd_dkv_kernel<bf16_t>, grid, dim3(64), 0, st, s);
+    else hipLaunchKernelGGL(sim_band_bwd_dkv_kernel<float>, grid, dim3(64), 0, st, s);
+  }
+}
+
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s) {
   attn_bwd_scalar<float>(a, s, "attn_bwd_dq_f32", "attn_bwd_dkv_f32");
 }

@@ -96,6 +96,32 @@ def run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poi
     return g
 
 
+def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0):
+    """Forward + backward of late-stage simulation step t through the C ABI.
+    Returns host float64 dicts (forward results, gradients)."""
+    d = desc_of(cfg, flags, scale)
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    dev["xp"] = to_dev(xpred, cfg)
+
+    def out(*shape, dtype=dt):
+        return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
+    f = dict(y=out(B, S, D), lse=out(B, H, S, dtype=torch.float32), q=out(B, S, H, hd), k=out(B, L, G, hd),
+             v=out(B, L, G, hd), kp=out(B, L, G, hd), vp=out(B, L, G, hd), o=out(B, S, H, hd))
+    bx.beagle_xattn_fwd_sim(d, dev["xq"], dev["xkv"], dev["xp"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], t,
+                            f["y"], f["lse"], f["q"], f["k"], f["v"], f["kp"], f["vp"], f["o"],
+                            workspace(d, bx.BEAGLE_WS_FWD))
+    g = dict(dxq=out(B, S, D), dxkv=out(B, L, D) if (flags & bx.BEAGLE_FLAG_NEED_DXKV) else None,
+             dxpred=out(B, L, D), dwq=out(D, H * hd), dwk=out(D, G * hd), dwv=out(D, G * hd), dwo=out(H * hd, D))
+    bx.beagle_xattn_bwd_sim(d, dev["dy"], dev["xq"], dev["xkv"], dev["xp"], dev["wq"], dev["wk"], dev["wv"], dev["wo"],
+                            f["q"], f["k"], f["v"], f["kp"], f["vp"], f["o"], f["lse"], t,
+                            g["dxq"], g["dxkv"], g["dxpred"], g["dwq"], g["dwk"], g["dwv"], g["dwo"],
+                            workspace(d, bx.BEAGLE_WS_BWD_SIM))
+    torch.cuda.synchronize()
+    return ({n: to_host(v) for n, v in f.items()}, {n: to_host(v) for n, v in g.items() if v is not None})
+
+
 def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
     """x [M,D], kc/vc [L,G,d], float32 arrays of stored values."""
     d = desc_of(cfg, 0, scale)

@@ -1,0 +1,109 @@
+"""GPU parity of the late-stage simulation step (section 4.2, second half):
+keys from the true states under the early-stage mask plus the predicted-state
+buffer's band of the query's own window, forward and backward, against the
+float64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import beagle_oracle as orc
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+from gpu_harness import run_sim, run_fwd, run_bwd, max_abs, rel_fro, rel_max
+
+pytestmark = pytest.mark.gpu
+F32_TOL = 1e-5
+BF16_OUT_ABS, BF16_OUT_FRO, LSE_TOL, BF16_GRAD_FRO = 2e-2, 1e-2, 1e-3, 3e-2
+GRADS = ("dxq", "dxkv", "dxpred", "dwq", "dwk", "dwv", "dwo")
+
+
+def _inputs(cfg, peaked=False):
+    inp = synth.make_inputs(cfg, peaked_queries=peaked)
+    # predicted states: the recipe of the target states with another seed (stored values of the io dtype)
+    xp = synth.make_inputs(cfg.with_(seed_base=cfg.seed_base + 50), with_dy=False)["xkv"]
+    return inp, xp
+
+
+def _oracle(cfg, inp, xp, t):
+    return orc.xattn_backward_sim(inp["dy"], inp["xq"], inp["xkv"], xp, inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                                  n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size,
+                                  eps=cfg.block_offset, t=t)
+
+
+@pytest.mark.parametrize("kw,t", [
+    (dict(seq_q=40, seq_kv=40, block_size=4), 1), (dict(seq_q=40, seq_kv=40, block_size=4), 3),
+    (dict(seq_q=40, seq_kv=40, block_size=4), 9),                          # more steps than the window holds
+    (dict(batch=2, seq_q=70, seq_kv=70, n_q_heads=4, n_kv_heads=2, block_size=5, block_offset=3), 2),
+    (dict(seq_q=33, seq_kv=33, block_size=8, block_offset=7), 5),
+    (dict(seq_q=20, seq_kv=20, block_size=1), 3),                          # k = 1: no band at any step
+    (dict(seq_q=6, seq_kv=6, block_size=8, block_offset=5), 4),            # true part blind everywhere: band only
+])
+def test_fp32_simulation_step(kw, t):
+    cfg = synth.CONFIGS["c1"].with_(seed_base=21, **kw)
+    inp, xp = _inputs(cfg)
+    ref = _oracle(cfg, inp, xp, t)
+    fw, gr = run_sim(cfg, inp, xp, t)
+    for n in ("y", "q", "k", "v", "kp", "vp", "o"):
+        assert rel_max(fw[n], ref[n]) <= F32_TOL, (n, rel_max(fw[n], ref[n]))
+    fin = np.isfinite(ref["lse"])
+    assert np.array_equal(np.isneginf(fw["lse"]), ~fin)
+    if fin.any():
+        assert max_abs(fw["lse"][fin], ref["lse"][fin]) <= F32_TOL * max(1.0, float(np.abs(ref["lse"][fin]).max()))
+    for n in GRADS:
+        assert rel_max(gr[n], ref[n]) <= F32_TOL, (n, rel_max(gr[n], ref[n]))
+    used = orc.sim_pred_mask(cfg.seq_q, cfg.seq_kv, cfg.block_size, cfg.block_offset, t).any(axis=0)
+    assert (gr["dxpred"][:, ~used] == 0).all()                               # unseen predicted rows: exactly zero
+
+
+SMALL = dict(hidden=512, n_q_heads=4, n_kv_heads=4)
+
+
+@pytest.mark.parametrize("name,kw,t,peaked", [
+    ("c2", dict(batch=2, seq_q=300, seq_kv=300, **SMALL), 1, False),
+    ("c2", dict(batch=1, seq_q=300, seq_kv=300, **SMALL), 3, True),
+    ("c2", dict(batch=1, seq_q=257, seq_kv=257, block_size=5, block_offset=2, **SMALL), 2, True),
+    ("c3", dict(batch=1, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2), 7, True),
+    ("c3", dict(batch=2, seq_q=260, seq_kv=260, hidden=512, n_q_heads=4, n_kv_heads=1, block_offset=5), 4, False),
+])
+def test_bf16_simulation_step(name, kw, t, peaked):
+    cfg = synth.CONFIGS[name].with_(**kw)
+    inp, xp = _inputs(cfg, peaked)
+    ref = _oracle(cfg, inp, xp, t)
+    fw, gr = run_sim(cfg, inp, xp, t)
+    for n in ("y", "q", "k", "v", "kp", "vp", "o"):
+        assert np.isfinite(fw[n]).all(), n
+        assert max_abs(fw[n], ref[n]) <= BF16_OUT_ABS, (n, max_abs(fw[n], ref[n]))
+        assert rel_fro(fw[n], ref[n]) <= BF16_OUT_FRO, (n, rel_fro(fw[n], ref[n]))
+    fin = np.isfinite(ref["lse"])
+    assert np.array_equal(np.isneginf(fw["lse"]), ~fin)
+    assert max_abs(fw["lse"][fin], ref["lse"][fin]) <= (4e-3 if peaked else LSE_TOL)
+    for n in GRADS:
+        assert np.isfinite(gr[n]).all(), n
+        assert rel_fro(gr[n], ref[n]) <= BF16_GRAD_FRO, (n, rel_fro(gr[n], ref[n]))
+    used = orc.sim_pred_mask(cfg.seq_q, cfg.seq_kv, cfg.block_size, cfg.block_offset, t).any(axis=0)
+    assert (gr["dxpred"][:, ~used] == 0).all()
+
+
+def test_step_zero_equals_the_early_stage_entry_points_bitwise():
+    cfg = synth.CONFIGS["c2"].with_(batch=1, seq_q=200, seq_kv=200, **SMALL)
+    inp, xp = _inputs(cfg)
+    fw, gr = run_sim(cfg, inp, xp, 0)
+    dev, fw0 = run_fwd(cfg, inp)
+    _, gr0 = run_bwd(cfg, inp, dev)
+    for n in ("y", "lse", "o"):
+        assert np.array_equal(fw[n], fw0[n], equal_nan=True), n
+    for n in ("dxq", "dxkv", "dwq", "dwo"):
+        assert np.array_equal(gr[n], gr0[n]), n
+    assert not gr["dxpred"].any()
+
+
+def test_simulation_argument_errors():
+    import torch
+    d = bx.make_desc(batch=1, seq_q=16, seq_kv=32, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=4,
+                     io_dtype=bx.BEAGLE_F32)
+    a = torch.zeros(1 << 16, device="cuda:0")
+    st = bx.beagle_xattn_fwd_sim(d, a, a, a, a, a, a, a, 1, a, a, a, a, a, a, a, a, None, check=False)
+    assert st == bx.BEAGLE_ERR_SHAPE                                         # seq_q != seq_kv
+    d2 = bx.make_desc(batch=1, seq_q=16, seq_kv=16, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=4,
+                      io_dtype=bx.BEAGLE_F32)
+    assert bx.beagle_xattn_fwd_sim(d2, a, a, a, a, a, a, a, -1, a, a, a, a, a, a, a, a, None, check=False) == bx.BEAGLE_ERR_SHAPE
+    assert bx.beagle_xattn_fwd_sim(d2, a, a, None, a, a, a, a, 1, a, a, a, a, a, a, a, a, None, check=False) == bx.BEAGLE_ERR_NULL
