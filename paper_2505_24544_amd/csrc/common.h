@@ -82,6 +82,9 @@ struct SimArgs {
 };
 void launch_sim_band_fwd(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd(const SimArgs& s, hipStream_t st);
+// streaming variants for bf16 storage (head width 128), chosen by the two launchers above
+void launch_sim_band_fwd_bf16(const SimArgs& s, hipStream_t st);
+void launch_sim_band_bwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_fwd_bf16_scalar(const AttnArgs& a, hipStream_t s);

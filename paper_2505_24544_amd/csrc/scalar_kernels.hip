@@ -439,23 +439,22 @@ __global__ __launch_bounds__(64) void sim_band_bwd_dkv_kernel(SimArgs s) {
 }
 
 void launch_sim_band_fwd(const SimArgs& s, hipStream_t st) {
+  if (s.is_bf16) return launch_sim_band_fwd_bf16(s, st);    // bf16 storage implies head width 128
   ProfScope ps("sim_band_fwd", st);
   dim3 grid(s.a.S, s.a.H, s.a.B);
-  if (s.is_bf16) hipLaunchKernelGGL(sim_band_fwd_kernel<bf16_t>, grid, dim3(64), 0, st, s);
-  else hipLaunchKernelGGL(sim_band_fwd_kernel<float>, grid, dim3(64), 0, st, s);
+  hipLaunchKernelGGL(sim_band_fwd_kernel<float>, grid, dim3(64), 0, st, s);
 }
 void launch_sim_band_bwd(const SimArgs& s, hipStream_t st) {
+  if (s.is_bf16) return launch_sim_band_bwd_bf16(s, st);
   {
     ProfScope ps("sim_band_bwd_dq", st);
     dim3 grid(s.a.S, s.a.H, s.a.B);
-    if (s.is_bf16) hipLaunchKernelGGL(sim_band_bwd_dq_kernel<bf16_t>, grid, dim3(64), 0, st, s);
-    else hipLaunchKernelGGL(sim_band_bwd_dq_kernel<float>, grid, dim3(64), 0, st, s);
+    hipLaunchKernelGGL(sim_band_bwd_dq_kernel<float>, grid, dim3(64), 0, st, s);
   }
   {
     ProfScope ps("sim_band_bwd_dkv", st);
     dim3 grid(s.a.L, s.a.G, s.a.B);
-    if (s.is_bf16) hipLaunchKernelGGL(sim_band_bwd_dkv_kernel<bf16_t>, grid, dim3(64), 0, st, s);
-    else hipLaunchKernelGGL(sim_band_bwd_dkv_kernel<float>, grid, dim3(64), 0, st, s);
+    hipLaunchKernelGGL(sim_band_bwd_dkv_kernel<float>, grid, dim3(64), 0, st, s);
   }
 }
 
