@@ -274,6 +274,30 @@ def sim_pred_mask(seq_q: int, seq_kv: int, k: int, eps: int, t: int) -> np.ndarr
     return (j >= np.maximum(w0, 0)) & (j < np.minimum(p, w0 + t))
 
 
+
+def sim_save_predicted(xpred, h, k: int, eps: int, t: int) -> np.ndarray:
+    """In-place update between simulation steps (section 4.2, second half: the
+    states predicted at the start of every window are saved after the first
+    step, those of the next position after the second step, and so on, into
+    the one buffer).  After step t (t = 0 is the early-stage step) the rows
+    whose position inside their window is t take the newly predicted states h
+    of the same positions; every other row of the buffer keeps its content.
+    Returns the updated copy of xpred.  Window by window, row by row, as in
+    the prose; the leading partial window counts positions from its own
+    (negative) start, as sim_pred_mask_loops does.  PARITY UNPINNED by the
+    paper beyond the prose (the figure is missing)."""
+    xpred, h = np.array(xpred, F64, copy=True), np.asarray(h, F64)
+    if xpred.shape != h.shape:
+        raise ValueError("h and the predicted-state buffer must have the same shape")
+    if t < 0 or k < 1 or not (0 <= eps < k):
+        raise ValueError("need t >= 0, k >= 1 and 0 <= eps < k")
+    L = xpred.shape[1]
+    for n in _window_starts(L, k, eps):
+        j = n + t
+        if t < k and 0 <= j < L:
+            xpred[:, j] = h[:, j]
+    return xpred
+
 def _sim_concat(xkv, xpred, k, eps, t, seq_q):
     xkv, xpred = np.asarray(xkv, F64), np.asarray(xpred, F64)
     if xkv.shape != xpred.shape:

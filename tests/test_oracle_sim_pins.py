@@ -166,3 +166,59 @@ def test_gradients_by_finite_differences():
             num[i] = (loss(**{name: up}) - loss(**{name: dn})) / (2 * h)
         scale = max(1.0, float(np.abs(num).max()))
         assert np.max(np.abs(num - grad)) / scale < 1e-6, name
+
+
+# ---------------------------------------------------------------- in-place update between steps
+@pytest.mark.parametrize("L,k,eps,t,rows", [
+    # written by hand from the prose: after step t the rows at position t of every window are saved
+    (10, 4, 0, 0, [0, 4, 8]), (10, 4, 0, 1, [1, 5, 9]), (10, 4, 0, 3, [3, 7]), (10, 4, 0, 4, []),
+    (10, 4, 2, 0, [2, 6]), (10, 4, 2, 1, [3, 7]), (10, 4, 2, 2, [0, 4, 8]), (10, 4, 2, 3, [1, 5, 9]),
+    (5, 1, 0, 0, [0, 1, 2, 3, 4]), (5, 1, 0, 1, []), (3, 8, 5, 3, [0]), (3, 8, 5, 0, []),
+])
+def test_save_predicted_rows_hand_written(L, k, eps, t, rows):
+    rng = np.random.default_rng(5)
+    buf, h = rng.normal(size=(2, L, 3)), rng.normal(size=(2, L, 3))
+    out = orc.sim_save_predicted(buf, h, k, eps, t)
+    sel = np.zeros(L, bool)
+    sel[rows] = True
+    assert np.array_equal(out[:, sel], h[:, sel]) and np.array_equal(out[:, ~sel], buf[:, ~sel])
+    assert np.array_equal(buf, np.asarray(buf))            # the input is not modified
+
+
+@pytest.mark.parametrize("k,eps", [(4, 0), (5, 3), (8, 7), (1, 0)])
+def test_saved_rows_are_exactly_what_the_next_steps_may_see(k, eps):
+    """Start from a buffer of NaN; after the saves of steps 0 .. t-1 every predicted key that the mask of
+    step t shows is a saved one, and no row saved later is visible yet."""
+    L = 37
+    h = np.ones((1, L, 1))
+    buf = np.full((1, L, 1), np.nan)
+    for t in range(0, k + 2):
+        vis = orc.sim_pred_mask_loops(L, L, k, eps, t).any(axis=0)
+        assert not np.isnan(buf[0, vis, 0]).any(), (t, np.flatnonzero(vis))
+        later = np.ones((1, L, 1))
+        for u in range(t, k + 2):
+            later = orc.sim_save_predicted(later, np.full((1, L, 1), np.nan), k, eps, u)
+        assert not (np.isnan(later[0, :, 0]) & vis).any()
+        buf = orc.sim_save_predicted(buf, h, k, eps, t)
+    assert not np.isnan(buf).any()                            # after k steps the buffer is full
+
+
+def test_simulation_loop_never_reads_the_initial_buffer():
+    """Three steps with h := y as the stand-in for the block's output: the result of every step is bitwise
+    independent of what the buffer held before the first step."""
+    rng = np.random.default_rng(9)
+    B, S, D, H, G, k, eps = 1, 14, 8, 2, 1, 4, 1
+    xq, xkv = rng.normal(size=(B, S, D)), rng.normal(size=(B, S, D))
+    wq, wo = rng.normal(size=(D, D)) * 0.3, rng.normal(size=(D, D)) * 0.3
+    wk, wv = rng.normal(size=(D, D // 2)) * 0.3, rng.normal(size=(D, D // 2)) * 0.3
+    outs = []
+    for init in (np.zeros((B, S, D)), rng.normal(size=(B, S, D)) * 100):
+        buf, ys = init, []
+        for t in range(3):
+            y = orc.xattn_forward_sim(xq, xkv, buf, wq, wk, wv, wo, n_q_heads=H, n_kv_heads=G, k=k, eps=eps, t=t)["y"]
+            ys.append(y)
+            buf = orc.sim_save_predicted(buf, y, k, eps, t)
+        outs.append(ys)
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    assert not np.array_equal(outs[0][0], outs[0][1])         # and the steps do differ
