@@ -167,6 +167,9 @@ def main():
         def sim_step():
             bx.beagle_xattn_fwd_sim(desc, t["xq"], t["xkv"], xp, t["wq"], t["wk"], t["wv"], t["wo"], tsim, y, lse,
                                     q, k, v, kp, vp, o, ws_f, stream)
+            # the in-place save of the newly predicted rows (y stands in for the draft block's output); the rows
+            # it overwrites are invisible at this step, so the backward below is unaffected
+            bx.beagle_xattn_sim_save(desc, y, xp, tsim, stream)
             bx.beagle_xattn_bwd_sim(desc, t["dy"], t["xq"], t["xkv"], xp, t["wq"], t["wk"], t["wv"], t["wo"], q, k, v,
                                     kp, vp, o, lse, tsim, dxq, dxkv, dxp, dwq, dwk, dwv, dwo, ws_s, stream)
         for _ in range(3):

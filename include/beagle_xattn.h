@@ -148,8 +148,8 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
  * half, and the caption of the mask figure).  Keys come from two sources: the
  * true target states xkv under the early-stage mask of beagle_xattn_fwd, and
  * the buffer xpred [B,L,D] of states that the draft model predicted in the
- * earlier simulation steps of this iteration (updated in place by the caller
- * between steps: constant space).  At step sim_step = t >= 0 query p, whose
+ * earlier simulation steps of this iteration (updated in place between steps
+ * with beagle_xattn_sim_save: constant space).  At step sim_step = t >= 0 query p, whose
  * window starts at w0(p) = eps + k*floor((p - eps)/k), also sees predicted key
  * j iff max(w0(p), 0) <= j < min(p, w0(p) + t): the first t positions of its
  * own window that lie before it.  t = 0 is beagle_xattn_fwd; t >= k - 1 shows
@@ -165,6 +165,23 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
     void* y, float* lse, void* q_save, void* k_save, void* v_save,
     void* kp_save, void* vp_save, void* o_save,
     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * In-place update of the predicted-state buffer between two simulated steps
+ * (section 4.2, second half: the states predicted at the start of every
+ * window are saved after the first step, those of the next position after
+ * the second, and so on, always into the same buffer).  After step
+ * sim_step = t the row at position t of every window (rows j with
+ * j - w0(j) == t, w0 as in beagle_xattn_fwd_sim) takes row j of h; all other
+ * rows of xpred keep their content.  h is whatever the caller's draft block
+ * produced for every position in step t (the residual adds and the MLP of
+ * Eq. 1 are outside this library).  t >= block_size changes nothing.
+ *   in    : h [B,L,D] (io dtype, device)
+ *   in/out: xpred [B,L,D] (device); h and xpred must not overlap
+ * Requires seq_q == seq_kv.  Asynchronous on hip_stream.
+ */
+beagle_status beagle_xattn_sim_save(const beagle_xattn_desc* desc,
+    const void* h, void* xpred, int32_t sim_step, void* hip_stream);
 
 /*
  * Backward of the simulated step: as beagle_xattn_bwd, with the gradient of

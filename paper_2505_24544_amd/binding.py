@@ -28,6 +28,7 @@ STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
     "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
+    "beagle_xattn_sim_save",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -80,6 +81,8 @@ def lib() -> C.CDLL:
     L.beagle_xattn_fwd_sim.argtypes = [dp] + [vp] * 7 + [C.c_int32] + [vp] * 8 + [vp, C.c_size_t, vp]
     L.beagle_xattn_bwd_sim.restype = C.c_int
     L.beagle_xattn_bwd_sim.argtypes = [dp] + [vp] * 15 + [C.c_int32] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_sim_save.restype = C.c_int
+    L.beagle_xattn_sim_save.argtypes = [dp, vp, vp, C.c_int32, vp]
     L.beagle_xattn_draft_step_tree.restype = C.c_int
     L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
@@ -153,6 +156,11 @@ def beagle_xattn_bwd_sim(desc, dy, xq, xkv, xpred, wq, wk, wv, wo, q_save, k_sav
         *(_ptr(t) for t in (dxq, dxkv, dxpred, dwq, dwk, dwv, dwo)),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_bwd_sim", check)
+
+
+def beagle_xattn_sim_save(desc, h, xpred, sim_step, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_sim_save(C.byref(desc), _ptr(h), _ptr(xpred), int(sim_step), _stream(stream))
+    return _check(st, "beagle_xattn_sim_save", check)
 
 
 def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true, tree_mask, mask_words, y, lse,

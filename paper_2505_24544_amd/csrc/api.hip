@@ -393,6 +393,21 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   return hip_status();
 }
 
+beagle_status beagle_xattn_sim_save(const beagle_xattn_desc* desc, const void* h, void* xpred, int32_t sim_step,
+                                    void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, false, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!h || !xpred) return BEAGLE_ERR_NULL;
+  if (!aligned16(h) || !aligned16(xpred)) return BEAGLE_ERR_ALIGN;
+  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  if ((d.D * (int64_t)d.esz) % 16) return BEAGLE_ERR_UNSUPPORTED;
+  if (sim_step >= desc->block_size) return BEAGLE_OK;      // every window is already full
+  (void)hipGetLastError();
+  launch_sim_save(h, xpred, (int)d.B, (int)d.L, d.D * (int64_t)d.esz, desc->block_size, desc->block_offset, sim_step,
+                  (hipStream_t)hip_stream);
+  return hip_status();
+}
+
 beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
     const void* dy, const void* xq, const void* xkv, const void* xpred, const void* wq, const void* wk,
     const void* wv, const void* wo, const void* q_save, const void* k_save, const void* v_save,

@@ -82,6 +82,7 @@ struct SimArgs {
 };
 void launch_sim_band_fwd(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd(const SimArgs& s, hipStream_t st);
+void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, int t, hipStream_t st);
 // streaming variants for bf16 storage (head width 128), chosen by the two launchers above
 void launch_sim_band_fwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd_bf16(const SimArgs& s, hipStream_t st);

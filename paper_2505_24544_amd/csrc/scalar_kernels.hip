@@ -458,6 +458,26 @@ void launch_sim_band_bwd(const SimArgs& s, hipStream_t st) {
   }
 }
 
+// In-place update of the predicted-state buffer between simulation steps (section 4.2, second half):
+// after step t the row at position t of every window takes the newly predicted state of that position.
+// blockIdx.x: window (the partial leading one first), blockIdx.y: batch entry; rows as 16-byte chunks.
+__global__ __launch_bounds__(256) void sim_save_kernel(const uint4* __restrict__ h, uint4* __restrict__ xpred, int L,
+                                                       int chunks, int k, int eps, int t) {
+  const int n0 = eps > 0 ? eps - k : 0;
+  const int j = n0 + (int)blockIdx.x * k + t;
+  if (j < 0 || j >= L) return;
+  const int64_t row = ((int64_t)blockIdx.y * L + j) * chunks;
+  for (int c = threadIdx.x; c < chunks; c += 256) xpred[row + c] = h[row + c];
+}
+
+void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, int t, hipStream_t st) {
+  ProfScope ps("sim_save", st);
+  const int n0 = eps > 0 ? eps - k : 0;
+  const int n_win = (L - n0 + k - 1) / k;
+  hipLaunchKernelGGL(sim_save_kernel, dim3(n_win, B), dim3(256), 0, st, (const uint4*)h, (uint4*)xpred, L,
+                     (int)(row_bytes / 16), k, eps, t);
+}
+
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s) {
   attn_bwd_scalar<float>(a, s, "attn_bwd_dq_f32", "attn_bwd_dkv_f32");
 }

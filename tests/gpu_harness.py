@@ -122,6 +122,37 @@ def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0):
     return ({n: to_host(v) for n, v in f.items()}, {n: to_host(v) for n, v in g.items() if v is not None})
 
 
+def run_sim_save(cfg, h, xpred, t, check=True):
+    """xpred after beagle_xattn_sim_save(h, xpred, t); host arrays in, host float64 out."""
+    d = desc_of(cfg)
+    hd, xp = to_dev(h, cfg), to_dev(xpred, cfg)
+    st = bx.beagle_xattn_sim_save(d, hd, xp, t, check=check)
+    torch.cuda.synchronize()
+    return to_host(xp) if check else st
+
+
+def run_sim_loop(cfg, inp, xpred0, steps):
+    """steps simulated forward steps on the device, the output y of each step saved into the buffer as the stand-in
+    for the draft block's predicted states.  Returns ([y of every step], final buffer) as host float64."""
+    d = desc_of(cfg)
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo")}
+    xp = to_dev(xpred0, cfg)
+    E = lambda *s, dtype=dt: torch.empty(*s, dtype=dtype, device=DEV)
+    y, lse, q, o = E(B, S, D), E(B, H, S, dtype=torch.float32), E(B, S, H, hd), E(B, S, H, hd)
+    k, v, kp, vp = (E(B, L, G, hd) for _ in range(4))
+    ws = workspace(d, bx.BEAGLE_WS_FWD)
+    ys = []
+    for t in range(steps):
+        bx.beagle_xattn_fwd_sim(d, dev["xq"], dev["xkv"], xp, dev["wq"], dev["wk"], dev["wv"], dev["wo"], t,
+                                y, lse, q, k, v, kp, vp, o, ws)
+        bx.beagle_xattn_sim_save(d, y, xp, t)
+        torch.cuda.synchronize()
+        ys.append(to_host(y))
+    return ys, to_host(xp)
+
+
 def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
     """x [M,D], kc/vc [L,G,d], float32 arrays of stored values."""
     d = desc_of(cfg, 0, scale)

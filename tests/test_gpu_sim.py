@@ -8,7 +8,7 @@ import pytest
 from oracle import beagle_oracle as orc
 from paper_2505_24544_amd import binding as bx
 from paper_2505_24544_amd import synth
-from gpu_harness import run_sim, run_fwd, run_bwd, max_abs, rel_fro, rel_max
+from gpu_harness import run_sim, run_sim_save, run_sim_loop, run_fwd, run_bwd, max_abs, rel_fro, rel_max
 
 pytestmark = pytest.mark.gpu
 F32_TOL = 1e-5
@@ -107,3 +107,77 @@ def test_simulation_argument_errors():
                       io_dtype=bx.BEAGLE_F32)
     assert bx.beagle_xattn_fwd_sim(d2, a, a, a, a, a, a, a, -1, a, a, a, a, a, a, a, a, None, check=False) == bx.BEAGLE_ERR_SHAPE
     assert bx.beagle_xattn_fwd_sim(d2, a, a, None, a, a, a, a, 1, a, a, a, a, a, a, a, a, None, check=False) == bx.BEAGLE_ERR_NULL
+
+
+@pytest.mark.parametrize("name,kw,steps", [
+    ("c1", dict(batch=2, seq_q=37, seq_kv=37, block_size=4), 6),
+    ("c1", dict(batch=1, seq_q=50, seq_kv=50, block_size=5, block_offset=3), 5),
+    ("c1", dict(batch=1, seq_q=9, seq_kv=9, block_size=1), 2),
+    ("c2", dict(batch=2, seq_q=130, seq_kv=130, block_size=8, block_offset=5, **SMALL), 8),
+])
+def test_save_of_predicted_states_is_bit_exact(name, kw, steps):
+    cfg = synth.CONFIGS[name].with_(seed_base=33, **kw)
+    inp, xp = _inputs(cfg)
+    h = inp["xkv"][:, ::-1].copy()                                           # any tensor of the buffer's shape
+    for t in range(steps):
+        ref = orc.sim_save_predicted(xp, h, cfg.block_size, cfg.block_offset, t)
+        got = run_sim_save(cfg, h, xp, t)
+        assert np.array_equal(got, ref), t
+        assert (t >= cfg.block_size) == np.array_equal(got, np.asarray(xp, np.float64))
+
+
+@pytest.mark.parametrize("name,kw,tol", [
+    ("c1", dict(batch=2, seq_q=45, seq_kv=45, block_size=4, block_offset=1), None),
+    ("c2", dict(batch=1, seq_q=200, seq_kv=200, block_size=4, **SMALL), (BF16_OUT_ABS, BF16_OUT_FRO)),
+])
+def test_three_simulated_steps_with_in_place_saves(name, kw, tol):
+    """fwd_sim(t) -> save y as the predicted states -> fwd_sim(t + 1) ..., all on the device, against the same loop
+    over the oracle; the buffer starts with large values: a step that read a row before it was saved would show."""
+    cfg = synth.CONFIGS[name].with_(seed_base=44, **kw)
+    inp, _ = _inputs(cfg)
+    steps = 3
+    init = inp["xkv"] * 64.0                                                # exact in the storage type
+    buf, ref = init.astype(np.float64), []
+    for t in range(steps):
+        y = orc.xattn_forward_sim(inp["xq"], inp["xkv"], buf, inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                                  n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size,
+                                  eps=cfg.block_offset, t=t)["y"]
+        ref.append(y)
+        buf = orc.sim_save_predicted(buf, y, cfg.block_size, cfg.block_offset, t)
+    ys, xp = run_sim_loop(cfg, inp, init, steps)
+    for t in range(steps):
+        if tol is None:
+            assert rel_max(ys[t], ref[t]) <= 2 * F32_TOL, (t, rel_max(ys[t], ref[t]))
+        else:
+            assert max_abs(ys[t], ref[t]) <= tol[0] and rel_fro(ys[t], ref[t]) <= tol[1], (t, rel_fro(ys[t], ref[t]))
+    assert not np.allclose(ref[0], ref[2])                                   # the steps differ where a band exists
+    assert (rel_max(xp, buf) <= 2 * F32_TOL) if tol is None else (rel_fro(xp, buf) <= tol[1])
+
+
+def test_save_argument_errors():
+    import torch
+    a = torch.zeros(1 << 14, device="cuda:0")
+    d = bx.make_desc(batch=1, seq_q=16, seq_kv=32, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=4,
+                     io_dtype=bx.BEAGLE_F32)
+    assert bx.beagle_xattn_sim_save(d, a, a, 0, check=False) == bx.BEAGLE_ERR_SHAPE
+    d2 = bx.make_desc(batch=1, seq_q=16, seq_kv=16, hidden=256, n_q_heads=4, n_kv_heads=4, head_dim=64, block_size=4,
+                      io_dtype=bx.BEAGLE_F32)
+    assert bx.beagle_xattn_sim_save(d2, a, a, -1, check=False) == bx.BEAGLE_ERR_SHAPE
+    assert bx.beagle_xattn_sim_save(d2, None, a, 0, check=False) == bx.BEAGLE_ERR_NULL
+
+
+def test_rows_saved_by_later_steps_do_not_change_this_step_bitwise():
+    """The rows that step t and later steps will overwrite are invisible at step t: forward results and all
+    gradients are bitwise the same whatever they hold (this is what lets one buffer serve every step)."""
+    cfg = synth.CONFIGS["c2"].with_(batch=1, seq_q=150, seq_kv=150, block_size=5, block_offset=2, **SMALL)
+    inp, xp = _inputs(cfg)
+    t = 2
+    pos = (np.arange(cfg.seq_kv) - cfg.block_offset) % cfg.block_size           # position inside the window
+    xp2 = xp.copy()
+    xp2[:, pos >= t] = xp[:, pos >= t] * -8.0
+    fw, gr = run_sim(cfg, inp, xp, t)
+    fw2, gr2 = run_sim(cfg, inp, xp2, t)
+    for n in ("y", "lse", "o"):
+        assert np.array_equal(fw[n], fw2[n], equal_nan=True), n
+    for n in GRADS:
+        assert np.array_equal(gr[n], gr2[n]), n
