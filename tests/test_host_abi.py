@@ -117,6 +117,23 @@ def test_tree_and_append_entry_points_validate_before_launching():
     assert bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_APPEND) > 0
 
 
+def test_simulation_entry_points_validate_before_launching():
+    a, ws = 4096, 1 << 40
+    d = _desc(S=64, L=64)
+    fwd = lambda dd, t, xp=a: bx.beagle_xattn_fwd_sim(dd, a, a, xp, a, a, a, a, t, a, a, a, a, a, a, a, a, a, stream=0,
+                                                      workspace_bytes=ws, check=False)
+    assert fwd(_desc(S=32, L=64), 1) == 2                       # needs seq_q == seq_kv
+    assert fwd(d, -1) == 2 and fwd(d, 1, None) == 1 and fwd(d, 1, a + 8) == 5
+    bwd = lambda dd, t, dxp=a, wsb=ws: bx.beagle_xattn_bwd_sim(dd, *([a] * 15), t, a, a, dxp, a, a, a, a, a, stream=0,
+                                                               workspace_bytes=wsb, check=False)
+    assert bwd(_desc(S=32, L=64), 1) == 2 and bwd(d, -1) == 2
+    assert bwd(d, 1, None) == 1                                 # the buffer's gradient is a required output
+    assert bwd(d, 1, a, 64) == 4
+    assert bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_BWD_SIM) > bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_BWD)
+    save = lambda dd, t, h=a: bx.beagle_xattn_sim_save(dd, h, a, t, stream=0, check=False)
+    assert save(_desc(S=32, L=64), 0) == 2 and save(d, -1) == 2 and save(d, 0, None) == 1 and save(d, 0, a + 4) == 5
+
+
 def test_entry_points_validate_before_launching():
     """NULL / misaligned / short-workspace arguments return a status without
     touching the GPU (this test runs where there is none)."""
