@@ -1,0 +1,144 @@
+"""Float64 CPU oracle for the whole single-layer draft block around the
+cross-attention (paper section 4.1, Eq. 1):
+
+    y_n = CrossAttn(h_{1:n-1}, e(t_n)) + e(t_n)
+    h_n = MLP(y_n) + y_n
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the
+CPU-baseline leg of the benchmark; shares no code with the HIP path.
+
+Eq. 1 fixes the two residual connections and says that the MLP is a
+point-wise feed-forward layer; it leaves out normalisation and the MLP's form
+on purpose ("layer details omitted").  Readings taken here, all PARITY
+UNPINNED by the paper beyond Eq. 1:
+  * the block follows the pre-normalisation layout of the LLaMA / Vicuna
+    targets the drafts are trained for: every sublayer reads an RMS-normalised
+    copy of its input, and each residual adds the UN-normalised stream;
+  * RMSNorm(x) = x / sqrt(mean_c(x_c^2) + rms_eps) * gain, one gain vector per
+    normalised input: g_q for the token embeddings e (the queries' source),
+    g_kv for the key/value states, g_mlp for y.  A gain of None switches that
+    normalisation off (identity), which gives Eq. 1 exactly as printed;
+  * the MLP is the gated SiLU feed-forward of those targets, no biases:
+        MLP(z) = ( silu(z W_gate) * (z W_up) ) W_down,  silu(u) = u * sigmoid(u),
+    with W_gate, W_up [D, F] and W_down [F, D] stored [in, out];
+  * the mask, scale and head conventions are those of beagle_oracle.
+
+Everything is written as the plain definition: dense matrices, no fusion, the
+backward is the chain rule term by term.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import beagle_oracle as orc
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# RMSNorm
+# --------------------------------------------------------------------------
+def rmsnorm(x, gain, rms_eps):
+    """x [..., D] -> x / sqrt(mean(x^2) + rms_eps) * gain; gain None: identity."""
+    x = np.asarray(x, F64)
+    if gain is None:
+        return x.copy()
+    r = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + rms_eps)
+    return x * r * np.asarray(gain, F64)
+
+
+def rmsnorm_backward(dout, x, gain, rms_eps):
+    """Gradients of sum(dout * rmsnorm(x)) w.r.t. x and gain.
+    With r = (mean(x^2) + eps)^(-1/2) and xh = x r:
+        d xh = dout * gain
+        dx   = r * (d xh - xh * mean_c(d xh * xh))      (derivative of r through x)
+        dgain = sum over rows of dout * xh
+    gain None: (dout, None)."""
+    dout, x = np.asarray(dout, F64), np.asarray(x, F64)
+    if gain is None:
+        return dout.copy(), None
+    gain = np.asarray(gain, F64)
+    r = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + rms_eps)
+    xh = x * r
+    dxh = dout * gain
+    dx = r * (dxh - xh * np.mean(dxh * xh, axis=-1, keepdims=True))
+    dgain = (dout * xh).reshape(-1, x.shape[-1]).sum(axis=0)
+    return dx, dgain
+
+
+# --------------------------------------------------------------------------
+# Gated SiLU feed-forward
+# --------------------------------------------------------------------------
+def _sigmoid(u):
+    return 1.0 / (1.0 + np.exp(-u))
+
+
+def mlp_forward(z, w_gate, w_up, w_down):
+    """Returns dict: u = z W_gate, w = z W_up, m = silu(u) * w, out = m W_down."""
+    z = np.asarray(z, F64)
+    w_gate, w_up, w_down = (np.asarray(a, F64) for a in (w_gate, w_up, w_down))
+    u = z @ w_gate
+    w = z @ w_up
+    m = u * _sigmoid(u) * w
+    return dict(u=u, w=w, m=m, out=m @ w_down)
+
+
+def mlp_backward(dout, z, w_gate, w_up, w_down):
+    """Gradients of sum(dout * MLP(z)): dz, dw_gate, dw_up, dw_down.
+    d silu(u)/du = sig(u) * (1 + u * (1 - sig(u)))."""
+    dout, z = np.asarray(dout, F64), np.asarray(z, F64)
+    w_gate, w_up, w_down = (np.asarray(a, F64) for a in (w_gate, w_up, w_down))
+    f = mlp_forward(z, w_gate, w_up, w_down)
+    u, w, m = f["u"], f["w"], f["m"]
+    D, F = w_gate.shape
+    z2, dout2 = z.reshape(-1, D), dout.reshape(-1, D)
+    dm = dout @ w_down.T
+    sg = _sigmoid(u)
+    du = dm * w * sg * (1.0 + u * (1.0 - sg))
+    dw = dm * u * sg
+    dz = du @ w_gate.T + dw @ w_up.T
+    return dict(dz=dz, dw_gate=z2.T @ du.reshape(-1, F), dw_up=z2.T @ dw.reshape(-1, F),
+                dw_down=m.reshape(-1, F).T @ dout2, du=du, dw=dw, dm=dm)
+
+
+# --------------------------------------------------------------------------
+# The block (Eq. 1)
+# --------------------------------------------------------------------------
+def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
+                  rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None):
+    """e [B,S,D] token embeddings, hs [B,L,D] key/value states.  Returns dict with
+    h [B,S,D] (the block's output), y (after the first residual), the normalised
+    inputs xq, xkv, z, the attention's own results (attn: the dict of
+    xattn_forward) and the MLP's (mlp)."""
+    e, hs = np.asarray(e, F64), np.asarray(hs, F64)
+    xq = rmsnorm(e, g_q, rms_eps)
+    xkv = rmsnorm(hs, g_kv, rms_eps)
+    mask = orc.dense_mask(e.shape[1], hs.shape[1], k, eps)
+    attn = orc.xattn_forward(xq, xkv, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask,
+                             scale=scale)
+    y = attn["y"] + e                                   # Eq. 1, second line
+    z = rmsnorm(y, g_mlp, rms_eps)
+    mlp = mlp_forward(z, w_gate, w_up, w_down)
+    h = mlp["out"] + y                                  # Eq. 1, first line
+    return dict(h=h, y=y, xq=xq, xkv=xkv, z=z, attn=attn, mlp=mlp, mask=mask)
+
+
+def block_backward(dh, e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
+                   rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None):
+    """Gradients of sum(dh * h) w.r.t. every input of block_forward: de, dhs, the
+    seven weight matrices and the three gains (None where the gain is None)."""
+    dh = np.asarray(dh, F64)
+    f = block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, g_q=g_q, g_kv=g_kv, g_mlp=g_mlp,
+                      rms_eps=rms_eps, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k, eps=eps, scale=scale)
+    # h = MLP(z) + y
+    mb = mlp_backward(dh, f["z"], w_gate, w_up, w_down)
+    dy_norm, dg_mlp = rmsnorm_backward(mb["dz"], f["y"], g_mlp, rms_eps)
+    dy = dh + dy_norm
+    # y = CrossAttn(xkv, xq) + e
+    ab = orc.xattn_backward(dy, f["xq"], f["xkv"], wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                            mask=f["mask"], scale=scale)
+    de_norm, dg_q = rmsnorm_backward(ab["dxq"], e, g_q, rms_eps)
+    dhs, dg_kv = rmsnorm_backward(ab["dxkv"], hs, g_kv, rms_eps)
+    return dict(de=dy + de_norm, dhs=dhs, dwq=ab["dwq"], dwk=ab["dwk"], dwv=ab["dwv"], dwo=ab["dwo"],
+                dw_gate=mb["dw_gate"], dw_up=mb["dw_up"], dw_down=mb["dw_down"],
+                dg_q=dg_q, dg_kv=dg_kv, dg_mlp=dg_mlp, dy=dy, fwd=f)
