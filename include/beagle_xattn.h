@@ -203,6 +203,82 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The whole draft block around the attention (section 4.1, Eq. 1):
+ *     y = CrossAttn(hs, e) + e          h = MLP(y) + y
+ * Eq. 1 fixes the two residual lines and calls the MLP a point-wise
+ * feed-forward layer; normalisation and the MLP's form are "layer details"
+ * the paper leaves out.  This library takes the layout of the LLaMA / Vicuna
+ * targets: every sublayer reads an RMS-normalised copy of its input and each
+ * residual adds the un-normalised stream,
+ *     xq = RMSNorm(e; g_q)   xkv = RMSNorm(hs; g_kv)   z = RMSNorm(y; g_mlp)
+ *     RMSNorm(x; g) = x / sqrt(mean_c(x_c^2) + rms_eps) * g
+ *     MLP(z) = (silu(z W_gate) * (z W_up)) W_down,   silu(u) = u / (1 + exp(-u))
+ * A NULL gain switches that normalisation off, which is Eq. 1 as printed.
+ * The attention inside is exactly beagle_xattn_fwd / beagle_xattn_bwd on (xq, xkv)
+ * with desc's mask; the residual adds run in the epilogues of the output
+ * projection and of the down projection.
+ *
+ * All pointers are device pointers (16-byte aligned, caller-owned) except the
+ * three structs themselves, which are read on the host during the call.
+ */
+typedef struct {
+  int32_t struct_size;          /* sizeof(beagle_block_params); checked          */
+  int32_t ffn;                  /* F, width of the feed-forward layer;
+                                   BEAGLE_F32: F % 4 == 0, BEAGLE_BF16: F % 64 == 0 */
+  float   rms_eps;              /* >= 0                                          */
+  int32_t reserved;             /* 0                                             */
+  const void *wq, *wk, *wv, *wo;        /* as beagle_xattn_fwd                   */
+  const void *w_gate, *w_up;            /* [D, F]                                */
+  const void *w_down;                   /* [F, D]                                */
+  const void *g_q, *g_kv, *g_mlp;       /* [D] gains in io_dtype, or NULL        */
+} beagle_block_params;
+
+/* Written by beagle_xattn_block_fwd, read by beagle_xattn_block_bwd.  xq_n / r_q, xkv_n /
+ * r_kv, z / r_mlp are needed only when the matching gain is given. */
+typedef struct {
+  void *xq_n;  float *r_q;      /* [B,S,D] normalised e, [B*S] 1/rms             */
+  void *xkv_n; float *r_kv;     /* [B,L,D] normalised hs, [B*L]                  */
+  void *q, *k, *v, *o; float *lse;      /* as the *_save / lse outputs of beagle_xattn_fwd */
+  void *y;                      /* [B,S,D] after the first residual              */
+  void *z;     float *r_mlp;    /* [B,S,D] normalised y, [B*S]                   */
+  void *u, *w, *m;              /* [B,S,F] z W_gate, z W_up, silu(u) * w         */
+} beagle_block_saved;
+
+typedef struct {
+  void *de;                     /* [B,S,D]                                       */
+  void *dhs;                    /* [B,L,D]; required iff BEAGLE_FLAG_NEED_DXKV   */
+  void *dwq, *dwk, *dwv, *dwo;  /* like the weights (io_dtype)                   */
+  void *dw_gate, *dw_up, *dw_down;
+  float *dg_q, *dg_kv, *dg_mlp; /* [D] float; required iff the gain is given     */
+} beagle_block_grads;
+
+enum { BEAGLE_WS_BLOCK_FWD = 0, BEAGLE_WS_BLOCK_BWD = 1 };
+
+/* Workspace bytes of the two block entry points (`which` is BEAGLE_WS_BLOCK_*);
+ * 0 for an invalid descriptor / ffn. */
+size_t beagle_xattn_block_workspace_bytes(const beagle_xattn_desc* desc, int32_t ffn, int which);
+
+/*
+ * Forward of the block.  in: e [B,S,D], hs [B,L,D]; out: h [B,S,D] and `saved`.
+ * BEAGLE_ERR_UNSUPPORTED additionally for D > 12288 when any gain is given and
+ * for BEAGLE_FLAG_WGRAD_F32.  Workspace: BEAGLE_WS_BLOCK_FWD (may be 0 bytes).
+ */
+beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* e, const void* hs, void* h, const beagle_block_saved* saved,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of the block: gradients of sum(dh * h) with respect to e, hs
+ * (optional), the seven weight matrices and the given gains.
+ *   in : dh [B,S,D], e, hs, params, saved (as written by the forward)
+ *   out: grads
+ * Workspace: BEAGLE_WS_BLOCK_BWD.
+ */
+beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* dh, const void* e, const void* hs, const beagle_block_saved* saved,
+    const beagle_block_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Appending states to the decode cache (section 4.1, KV-cache paragraph: new
  * K_i, V_i are appended as drafting proceeds, and the cache is reset to the
  * true states at the end of a speculative-decoding iteration).  The

@@ -22,6 +22,7 @@ BEAGLE_OK = 0
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
 BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32 = 1, 2
 BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
+BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD = 0, 1
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
                 4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
 
@@ -29,6 +30,7 @@ EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
     "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
+    "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -54,6 +56,50 @@ def make_desc(*, batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads, head_dim, 
               block_offset=0, io_dtype=BEAGLE_BF16, softmax_scale=0.0, flags=0) -> beagle_xattn_desc:
     return beagle_xattn_desc(C.sizeof(beagle_xattn_desc), batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads,
                              head_dim, block_size, block_offset, io_dtype, softmax_scale, flags)
+
+
+_VP = C.c_void_p
+
+
+class beagle_block_params(C.Structure):
+    _fields_ = [("struct_size", C.c_int32), ("ffn", C.c_int32), ("rms_eps", C.c_float), ("reserved", C.c_int32)] + \
+               [(n, _VP) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_q", "g_kv", "g_mlp")]
+
+
+class beagle_block_saved(C.Structure):
+    _fields_ = [(n, _VP) for n in ("xq_n", "r_q", "xkv_n", "r_kv", "q", "k", "v", "o", "lse", "y", "z", "r_mlp",
+                                   "u", "w", "m")]
+
+
+class beagle_block_grads(C.Structure):
+    _fields_ = [(n, _VP) for n in ("de", "dhs", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down",
+                                   "dg_q", "dg_kv", "dg_mlp")]
+
+
+def _fill(struct, tensors: dict):
+    """Pointer struct from a dict name -> tensor / address / None; keeps nothing alive (the caller does)."""
+    names = [f[0] for f in struct._fields_ if f[1] is _VP]
+    unknown = set(tensors) - set(names)
+    if unknown:
+        raise KeyError("unknown field(s): %s" % sorted(unknown))
+    out = struct()
+    for n in names:
+        setattr(out, n, _ptr(tensors.get(n)))
+    return out
+
+
+def make_block_params(ffn, rms_eps, **weights) -> beagle_block_params:
+    p = _fill(beagle_block_params, weights)
+    p.struct_size, p.ffn, p.rms_eps, p.reserved = C.sizeof(beagle_block_params), int(ffn), float(rms_eps), 0
+    return p
+
+
+def make_block_saved(**tensors) -> beagle_block_saved:
+    return _fill(beagle_block_saved, tensors)
+
+
+def make_block_grads(**tensors) -> beagle_block_grads:
+    return _fill(beagle_block_grads, tensors)
 
 
 _lib = None
@@ -83,6 +129,14 @@ def lib() -> C.CDLL:
     L.beagle_xattn_bwd_sim.argtypes = [dp] + [vp] * 15 + [C.c_int32] + [vp] * 7 + [vp, C.c_size_t, vp]
     L.beagle_xattn_sim_save.restype = C.c_int
     L.beagle_xattn_sim_save.argtypes = [dp, vp, vp, C.c_int32, vp]
+    L.beagle_xattn_block_workspace_bytes.restype = C.c_size_t
+    L.beagle_xattn_block_workspace_bytes.argtypes = [dp, C.c_int32, C.c_int]
+    L.beagle_xattn_block_fwd.restype = C.c_int
+    L.beagle_xattn_block_fwd.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.POINTER(beagle_block_saved),
+                                         vp, C.c_size_t, vp]
+    L.beagle_xattn_block_bwd.restype = C.c_int
+    L.beagle_xattn_block_bwd.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.POINTER(beagle_block_saved),
+                                         C.POINTER(beagle_block_grads), vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step_tree.restype = C.c_int
     L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
@@ -156,6 +210,28 @@ def beagle_xattn_bwd_sim(desc, dy, xq, xkv, xpred, wq, wk, wv, wo, q_save, k_sav
         *(_ptr(t) for t in (dxq, dxkv, dxpred, dwq, dwk, dwv, dwo)),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_bwd_sim", check)
+
+
+def beagle_xattn_block_workspace_bytes(desc, ffn, which) -> int:
+    return int(lib().beagle_xattn_block_workspace_bytes(C.byref(desc), int(ffn), int(which)))
+
+
+def beagle_xattn_block_fwd(desc, params, e, hs, h, saved, workspace=None, stream=None, *, workspace_bytes=None,
+                           check=True) -> int:
+    st = lib().beagle_xattn_block_fwd(
+        C.byref(desc), C.byref(params) if params is not None else None, _ptr(e), _ptr(hs), _ptr(h),
+        C.byref(saved) if saved is not None else None,
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_block_fwd", check)
+
+
+def beagle_xattn_block_bwd(desc, params, dh, e, hs, saved, grads, workspace, stream=None, *, workspace_bytes=None,
+                           check=True) -> int:
+    st = lib().beagle_xattn_block_bwd(
+        C.byref(desc), C.byref(params) if params is not None else None, _ptr(dh), _ptr(e), _ptr(hs),
+        C.byref(saved) if saved is not None else None, C.byref(grads) if grads is not None else None,
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_block_bwd", check)
 
 
 def beagle_xattn_sim_save(desc, h, xpred, sim_step, stream=None, *, check=True) -> int:

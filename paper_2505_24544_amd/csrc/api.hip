@@ -114,6 +114,73 @@ void run_gemm(const Dims& d, const GemmGroup& g, hipStream_t s, const char* name
 
 beagle_status hip_status() { return hipGetLastError() == hipSuccess ? BEAGLE_OK : BEAGLE_ERR_HIP; }
 
+// Projections, masked attention, output projection (+ y_res in its epilogue if given).
+void xattn_fwd_run(const Dims& d, const void* xq, const void* xkv, const void* wq, const void* wk, const void* wv,
+                   const void* wo, void* y, float* lse, void* q_save, void* k_save, void* v_save, void* o_save,
+                   const void* y_res, hipStream_t s) {
+  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
+  qkv.count = 3;
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
+  run_gemm(d, qkv, s, "proj_qkv");
+
+  AttnArgs a = attn_args(d);
+  a.q = q_save; a.k = k_save; a.v = v_save; a.o = o_save; a.lse = lse;
+  if (d.bf16) launch_attn_fwd_bf16(a, s); else launch_attn_fwd_f32(a, s);
+
+  GemmArgs out = gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD);
+  out.R = y_res; out.ldr = d.D;
+  run_gemm(d, group1(out), s, "proj_out");
+}
+
+// All gradients of the attention op; `base` is a workspace of BEAGLE_WS_BWD bytes.  dxq_res, if given, is added
+// to dxq in the epilogue of its GEMM.
+void xattn_bwd_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, const void* xq, const void* xkv,
+                   const void* wq, const void* wk, const void* wv, const void* wo, const void* q_save,
+                   const void* k_save, const void* v_save, const void* o_save, const float* lse, void* dxq,
+                   void* dxkv, void* dwq, void* dwk, void* dwv, void* dwo, char* base, const void* dxq_res,
+                   hipStream_t s) {
+  const BwdWs w = bwd_layout(d);
+  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
+  float* delta = (float*)(base + w.delta);
+  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
+
+  // dO = dY Wo^T ; dWo = O^T dY
+  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
+  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
+
+  AttnArgs a = attn_args(d);
+  a.q = q_save; a.k = k_save; a.v = v_save; a.o = (void*)o_save; a.lse = (float*)lse;
+  a.dout = dO; a.dq = dQ; a.dk = dK; a.dv = dV; a.delta = delta;
+  if (d.bf16) launch_attn_bwd_bf16(a, base + w.attn, s); else launch_attn_bwd_f32(a, s);
+
+  // input gradients
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 1;
+    g.p[0] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
+    g.p[0].R = dxq_res; g.p[0].ldr = d.D;
+    if (need_dxkv) {
+      // deeper problem first: dXkv contracts over the K and the V columns
+      g.count = 2;
+      g.p[1] = g.p[0];
+      g.p[0] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
+      g.p[0].A2 = dV; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
+    }
+    run_gemm(d, g, s, "bwd_dx");
+  }
+  // weight gradients
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 3;
+    g.p[0] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
+    g.p[1] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);
+    g.p[2] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
+    run_gemm(d, g, s, "bwd_dw");
+  }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ profiler
@@ -278,18 +345,7 @@ beagle_status beagle_xattn_fwd(const beagle_xattn_desc* desc,
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
-  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
-  qkv.count = 3;
-  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
-  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
-  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
-  run_gemm(d, qkv, s, "proj_qkv");
-
-  AttnArgs a = attn_args(d);
-  a.q = q_save; a.k = k_save; a.v = v_save; a.o = o_save; a.lse = lse;
-  if (d.bf16) launch_attn_fwd_bf16(a, s); else launch_attn_fwd_f32(a, s);
-
-  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD)), s, "proj_out");
+  xattn_fwd_run(d, xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save, nullptr, s);
   return hip_status();
 }
 
@@ -313,45 +369,8 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
-  const BwdWs w = bwd_layout(d);
-  char* base = (char*)workspace;
-  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
-  float* delta = (float*)(base + w.delta);
-  const bool wf32 = d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32);
-  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
-
-  // dO = dY Wo^T ; dWo = O^T dY
-  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
-  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
-
-  AttnArgs a = attn_args(d);
-  a.q = q_save; a.k = k_save; a.v = v_save; a.o = (void*)o_save; a.lse = (float*)lse;
-  a.dout = dO; a.dq = dQ; a.dk = dK; a.dv = dV; a.delta = delta;
-  if (d.bf16) launch_attn_bwd_bf16(a, base + w.attn, s); else launch_attn_bwd_f32(a, s);
-
-  // input gradients
-  {
-    GemmGroup g; memset(&g, 0, sizeof(g));
-    g.count = 1;
-    g.p[0] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
-    if (need_dxkv) {
-      // deeper problem first: dXkv contracts over the K and the V columns
-      g.count = 2;
-      g.p[1] = g.p[0];
-      g.p[0] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
-      g.p[0].A2 = dV; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
-    }
-    run_gemm(d, g, s, "bwd_dx");
-  }
-  // weight gradients
-  {
-    GemmGroup g; memset(&g, 0, sizeof(g));
-    g.count = 3;
-    g.p[0] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
-    g.p[1] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);
-    g.p[2] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
-    run_gemm(d, g, s, "bwd_dw");
-  }
+  xattn_bwd_run(d, need_dxkv, d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32), dy, xq, xkv, wq, wk, wv, wo, q_save, k_save,
+                v_save, o_save, lse, dxq, dxkv, dwq, dwk, dwv, dwo, (char*)workspace, nullptr, s);
   return hip_status();
 }
 
@@ -575,3 +594,163 @@ beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
 }
 
 }  // extern "C"
+
+// ------------------------------------------- the draft block around the attention (Eq. 1)
+namespace beagle {
+namespace {
+
+struct BlockWs { size_t dm, dw, dz, dy, dxq, dxkv, part, attn, total; };
+
+BlockWs block_bwd_layout(const Dims& d, int64_t F) {
+  BlockWs w; size_t o = 0;
+  const size_t Mq = (size_t)(d.B * d.S), Mk = (size_t)(d.B * d.L);
+  w.dm = o; o += align_up(Mq * F * d.esz);          // dm, then du in place
+  w.dw = o; o += align_up(Mq * F * d.esz);
+  w.dz = o; o += align_up(Mq * d.D * d.esz);
+  w.dy = o; o += align_up(Mq * d.D * d.esz);
+  w.dxq = o; o += align_up(Mq * d.D * d.esz);
+  w.dxkv = o; o += align_up(Mk * d.D * d.esz);
+  w.part = o; o += align_up((size_t)RMS_BWD_MAX_PARTS * d.D * sizeof(float));
+  w.attn = o;
+  w.total = o;
+  return w;
+}
+
+beagle_status check_block(const beagle_xattn_desc* desc, const beagle_block_params* p, Dims* d) {
+  beagle_status st = check_desc(desc, false, d);
+  if (st != BEAGLE_OK) return st;
+  if (!p) return BEAGLE_ERR_NULL;
+  if (p->struct_size != (int32_t)sizeof(beagle_block_params) || p->ffn < 1 || p->reserved != 0) return BEAGLE_ERR_SHAPE;
+  if (!(p->rms_eps >= 0.f) || isinf(p->rms_eps)) return BEAGLE_ERR_SHAPE;
+  if (p->ffn % (d->bf16 ? 64 : 4)) return BEAGLE_ERR_UNSUPPORTED;
+  if (desc->flags & BEAGLE_FLAG_WGRAD_F32) return BEAGLE_ERR_UNSUPPORTED;
+  if ((p->g_q || p->g_kv || p->g_mlp) && d->D > RMS_MAX_D) return BEAGLE_ERR_UNSUPPORTED;
+  if (d->B * d->S * (int64_t)p->ffn > (int64_t)INT32_MAX * 64) return BEAGLE_ERR_UNSUPPORTED;
+  return BEAGLE_OK;
+}
+
+}  // namespace
+}  // namespace beagle
+
+using namespace beagle;
+
+size_t beagle_xattn_block_workspace_bytes(const beagle_xattn_desc* desc, int32_t ffn, int which) {
+  Dims d;
+  if (check_desc(desc, false, &d) != BEAGLE_OK || ffn < 1 || ffn % (d.bf16 ? 64 : 4)) return 0;
+  if (which == BEAGLE_WS_BLOCK_FWD) return WS_ALIGN;
+  if (which == BEAGLE_WS_BLOCK_BWD)
+    return block_bwd_layout(d, ffn).total + beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD);
+  return 0;
+}
+
+beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* e, const void* hs, void* h, const beagle_block_saved* sv,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_block(desc, p, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!sv) return BEAGLE_ERR_NULL;
+  const void* req[] = {e, hs, h, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down,
+                       sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->u, sv->w, sv->m};
+  for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
+  if (p->g_q && (!sv->xq_n || !sv->r_q)) return BEAGLE_ERR_NULL;
+  if (p->g_kv && (!sv->xkv_n || !sv->r_kv)) return BEAGLE_ERR_NULL;
+  if (p->g_mlp && (!sv->z || !sv->r_mlp)) return BEAGLE_ERR_NULL;
+  const void* all[] = {e, hs, h, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down, p->g_q, p->g_kv, p->g_mlp,
+                       sv->xq_n, sv->r_q, sv->xkv_n, sv->r_kv, sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->z,
+                       sv->r_mlp, sv->u, sv->w, sv->m};
+  for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+  (void)workspace; (void)workspace_bytes;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const int64_t Mq = d.B * d.S, Mk = d.B * d.L, F = p->ffn;
+  const int D = (int)d.D;
+
+  const void* xq = e; const void* xkv = hs;
+  if (p->g_q) { launch_rmsnorm_fwd(d.bf16, e, p->g_q, sv->xq_n, sv->r_q, Mq, D, p->rms_eps, s, "norm_q"); xq = sv->xq_n; }
+  if (p->g_kv) { launch_rmsnorm_fwd(d.bf16, hs, p->g_kv, sv->xkv_n, sv->r_kv, Mk, D, p->rms_eps, s, "norm_kv"); xkv = sv->xkv_n; }
+  // y = CrossAttn(xkv, xq) + e: the residual is the epilogue operand of the output projection
+  xattn_fwd_run(d, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->y, sv->lse, sv->q, sv->k, sv->v, sv->o, e, s);
+  const void* z = sv->y;
+  if (p->g_mlp) { launch_rmsnorm_fwd(d.bf16, sv->y, p->g_mlp, sv->z, sv->r_mlp, Mq, D, p->rms_eps, s, "norm_mlp"); z = sv->z; }
+  GemmGroup gu; memset(&gu, 0, sizeof(gu));
+  gu.count = 2;
+  gu.p[0] = gemm_nn(z, p->w_gate, sv->u, Mq, F, d.D);
+  gu.p[1] = gemm_nn(z, p->w_up, sv->w, Mq, F, d.D);
+  run_gemm(d, gu, s, "mlp_gate_up");
+  launch_silu_mul_fwd(d.bf16, sv->u, sv->w, sv->m, Mq * F, s);
+  // h = m W_down + y
+  GemmArgs dn = gemm_nn(sv->m, p->w_down, h, Mq, d.D, F);
+  dn.R = sv->y; dn.ldr = d.D;
+  run_gemm(d, group1(dn), s, "mlp_down");
+  return hip_status();
+}
+
+beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* dh, const void* e, const void* hs, const beagle_block_saved* sv,
+    const beagle_block_grads* gr, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_block(desc, p, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!sv || !gr) return BEAGLE_ERR_NULL;
+  const bool need_dhs = desc->flags & BEAGLE_FLAG_NEED_DXKV;
+  const void* req[] = {dh, e, hs, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down,
+                       sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->u, sv->w, sv->m,
+                       gr->de, gr->dwq, gr->dwk, gr->dwv, gr->dwo, gr->dw_gate, gr->dw_up, gr->dw_down, workspace};
+  for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
+  if (need_dhs && !gr->dhs) return BEAGLE_ERR_NULL;
+  if (p->g_q && (!sv->xq_n || !sv->r_q || !gr->dg_q)) return BEAGLE_ERR_NULL;
+  if (p->g_kv && (!sv->xkv_n || !sv->r_kv || !gr->dg_kv)) return BEAGLE_ERR_NULL;
+  if (p->g_mlp && (!sv->z || !sv->r_mlp || !gr->dg_mlp)) return BEAGLE_ERR_NULL;
+  const void* all[] = {dh, e, hs, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down, p->g_q, p->g_kv, p->g_mlp,
+                       sv->xq_n, sv->r_q, sv->xkv_n, sv->r_kv, sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->z,
+                       sv->r_mlp, sv->u, sv->w, sv->m, gr->de, gr->dhs, gr->dwq, gr->dwk, gr->dwv, gr->dwo,
+                       gr->dw_gate, gr->dw_up, gr->dw_down, gr->dg_q, gr->dg_kv, gr->dg_mlp};
+  for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_BWD)) return BEAGLE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const int64_t Mq = d.B * d.S, Mk = d.B * d.L, F = p->ffn;
+  const int D = (int)d.D;
+  const BlockWs w = block_bwd_layout(d, F);
+  char* base = (char*)workspace;
+  void* dm = base + w.dm; void* dwp = base + w.dw; void* dz = base + w.dz; void* dy = base + w.dy;
+  void* dxq_n = base + w.dxq; void* dxkv_n = base + w.dxkv; float* part = (float*)(base + w.part);
+
+  // ---- h = m W_down + y
+  run_gemm(d, group1(gemm_nt(dh, p->w_down, dm, Mq, F, d.D)), s, "bwd_mlp_dm");
+  run_gemm(d, group1(gemm_tn(sv->m, dh, gr->dw_down, F, d.D, Mq, false)), s, "bwd_mlp_dwdown");
+  launch_silu_mul_bwd(d.bf16, dm, sv->u, sv->w, /*du, in place*/ dm, dwp, Mq * F, s);
+  const void* du = dm;
+  const void* z = p->g_mlp ? sv->z : sv->y;
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 2;
+    g.p[0] = gemm_tn(z, du, gr->dw_gate, d.D, F, Mq, false);
+    g.p[1] = gemm_tn(z, dwp, gr->dw_up, d.D, F, Mq, false);
+    run_gemm(d, g, s, "bwd_mlp_dwgu");
+  }
+  {
+    // dz = du W_gate^T + dw W_up^T; without the MLP's normalisation this is already dy - dh: add dh here
+    GemmArgs g = gemm_nt(du, p->w_gate, p->g_mlp ? dz : dy, Mq, d.D, F);
+    g.A2 = dwp; g.B2 = p->w_up; g.K2 = (int32_t)F; g.lda2 = F; g.ldb2 = F;
+    if (!p->g_mlp) { g.R = dh; g.ldr = d.D; }
+    run_gemm(d, group1(g), s, "bwd_mlp_dz");
+  }
+  if (p->g_mlp)   // dy = dh + dRMSNorm(dz)
+    launch_rmsnorm_bwd(d.bf16, dz, sv->y, p->g_mlp, sv->r_mlp, dh, dy, gr->dg_mlp, part, Mq, D, s, "bwd_norm_mlp");
+
+  // ---- y = CrossAttn(xkv, xq) + e
+  const bool need_dxkv = need_dhs || p->g_kv;      // the gain's gradient needs dxkv even if dhs is not wanted
+  const void* xq = p->g_q ? sv->xq_n : e;
+  const void* xkv = p->g_kv ? sv->xkv_n : hs;
+  void* dxq_out = p->g_q ? dxq_n : gr->de;
+  void* dxkv_out = p->g_kv ? dxkv_n : gr->dhs;
+  xattn_bwd_run(d, need_dxkv, false, dy, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->q, sv->k, sv->v, sv->o, sv->lse,
+                dxq_out, dxkv_out, gr->dwq, gr->dwk, gr->dwv, gr->dwo, base + w.attn, p->g_q ? nullptr : dy, s);
+  if (p->g_q)     // de = dy + dRMSNorm(dxq)
+    launch_rmsnorm_bwd(d.bf16, dxq_n, e, p->g_q, sv->r_q, dy, gr->de, gr->dg_q, part, Mq, D, s, "bwd_norm_q");
+  if (p->g_kv)
+    launch_rmsnorm_bwd(d.bf16, dxkv_n, hs, p->g_kv, sv->r_kv, nullptr, need_dhs ? gr->dhs : dxkv_n, gr->dg_kv, part, Mk, D,
+                       s, "bwd_norm_kv");
+  return hip_status();
+}

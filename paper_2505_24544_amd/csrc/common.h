@@ -47,6 +47,8 @@ struct GemmArgs {
   const void* A2; const void* B2;
   int32_t K2;
   int64_t lda2, ldb2;
+  const void* R;         // optional residual added in the epilogue: C = A B (+ A2 B2) + R; storage type of A,
+  int64_t ldr;           // row stride ldr; not with c_is_f32
 };
 // Up to 4 independent GEMMs in one launch (they share one grid).
 struct GemmGroup {
@@ -56,6 +58,20 @@ struct GemmGroup {
 void launch_gemm_f32(const GemmGroup& g, hipStream_t s, const char* name);
 void launch_gemm_bf16_scalar(const GemmGroup& g, hipStream_t s, const char* name);
 void launch_gemm_bf16(const GemmGroup& g, hipStream_t s, const char* name);
+
+// ---- draft block around the attention (section 4.1, Eq. 1): streaming kernels ----
+constexpr int RMS_BWD_MAX_PARTS = 1024;      // workgroups (= column-partial rows) of the RMSNorm backward
+constexpr int RMS_MAX_D = 12288;             // its column partials live in LDS: 4 * D bytes
+int rmsnorm_bwd_parts(int64_t rows);
+void launch_rmsnorm_fwd(bool bf16, const void* x, const void* gain, void* out, float* rinv, int64_t rows, int D,
+                        float eps, hipStream_t s, const char* name);
+// dx = d rmsnorm / dx applied to dout (+ add if given); dgain [D] float; part: rmsnorm_bwd_parts(rows) * D floats
+void launch_rmsnorm_bwd(bool bf16, const void* dout, const void* x, const void* gain, const float* rinv,
+                        const void* add, void* dx, float* dgain, float* part, int64_t rows, int D, hipStream_t s,
+                        const char* name);
+void launch_silu_mul_fwd(bool bf16, const void* u, const void* w, void* m, int64_t n, hipStream_t s);
+void launch_silu_mul_bwd(bool bf16, const void* dm, const void* u, const void* w, void* du, void* dw, int64_t n,
+                         hipStream_t s);
 
 // ---- attention -------------------------------------------------------------
 struct AttnArgs {

@@ -285,8 +285,13 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
       for (int q = 0; q < 4; ++q) {
         const int n = n0 + wn + 32 * j + 8 * q + 4 * (lane >> 5);
         if (n >= g.N) continue;
-        const float a0 = acc[i][j][4 * q], a1 = acc[i][j][4 * q + 1], a2 = acc[i][j][4 * q + 2],
-                    a3 = acc[i][j][4 * q + 3];
+        float a0 = acc[i][j][4 * q], a1 = acc[i][j][4 * q + 1], a2 = acc[i][j][4 * q + 2],
+              a3 = acc[i][j][4 * q + 3];
+        if (!F32OUT && g.R) {                   // residual operand (bf16, same shape as C)
+          const uint2 r = *(const uint2*)((const bf16_t*)g.R + (int64_t)m * g.ldr + n);
+          a0 += __uint_as_float(r.x << 16); a1 += __uint_as_float(r.x & 0xffff0000u);
+          a2 += __uint_as_float(r.y << 16); a3 += __uint_as_float(r.y & 0xffff0000u);
+        }
         if (F32OUT) {
           float4 v = {a0, a1, a2, a3};
           *(float4*)((float*)g.C + (int64_t)m * g.ldc + n) = v;

@@ -81,7 +81,9 @@ __global__ __launch_bounds__(256) void gemm_scalar_kernel(GemmGroup grp) {
     for (int j = 0; j < 4; ++j) {
       int gn = n0 + tx * 4 + j;
       if (gn >= g.N) continue;
-      Io<TO>::st(C + (int64_t)gm * g.ldc + gn, acc[i][j]);
+      float r = 0.f;
+      if (g.R) r = Io<TI>::ld((const TI*)g.R + (int64_t)gm * g.ldr + gn);
+      Io<TO>::st(C + (int64_t)gm * g.ldc + gn, acc[i][j] + r);
     }
   }
 }

@@ -141,3 +141,24 @@ def make_inputs(cfg: XattnConfig, *, peaked_queries: bool = False,
     if with_dy:
         out["dy"] = _store(rng[6].standard_normal((B, Sq, D), dtype=f32), cfg.dtype)
     return out
+
+
+def make_block_inputs(cfg: XattnConfig, ffn: int) -> dict:
+    """Tensors for the whole draft block (section 4.1, Eq. 1), float32 arrays of
+    stored values.  Unlike make_inputs the activations are NOT normalised (the
+    block does that): e ~ N(0, 0.02^2) like an embedding table's rows, hs ~
+    3 * N(0,1) * per-token LogNormal(0, 0.5) like a target model's top hidden
+    states.  All seven weight matrices ~ N(0, 0.02^2), gains ~ 1 + 0.1 N(0,1),
+    dh ~ N(0,1).  Seeds: seed_base + 20 + i in the order below."""
+    B, Sq, L, D = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden
+    H, G, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    f32 = np.float32
+    rng = [np.random.default_rng(cfg.seed_base + 20 + i) for i in range(14)]
+    n = lambda i, *shape: rng[i].standard_normal(shape, dtype=f32)
+    hs = 3.0 * n(1, B, L, D) * rng[1].lognormal(0.0, 0.5, size=(B, L, 1)).astype(f32)
+    t = dict(e=W_STD * n(0, B, Sq, D), hs=hs,
+             wq=W_STD * n(2, D, H * d), wk=W_STD * n(3, D, G * d), wv=W_STD * n(4, D, G * d), wo=W_STD * n(5, H * d, D),
+             w_gate=W_STD * n(6, D, ffn), w_up=W_STD * n(7, D, ffn), w_down=W_STD * n(8, ffn, D),
+             g_q=1.0 + 0.1 * n(9, D), g_kv=1.0 + 0.1 * n(10, D), g_mlp=1.0 + 0.1 * n(11, D),
+             dh=n(12, B, Sq, D))
+    return {k: _store(v, cfg.dtype) for k, v in t.items()}

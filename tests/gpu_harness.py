@@ -153,6 +153,48 @@ def run_sim_loop(cfg, inp, xpred0, steps):
     return ys, to_host(xp)
 
 
+BLOCK_W = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+BLOCK_G = ("g_q", "g_kv", "g_mlp")
+
+
+def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV):
+    """Forward + backward of the whole draft block through the C ABI.  bi: make_block_inputs' dict.
+    Returns host float64 dicts (forward results incl. the saved tensors, gradients)."""
+    d = desc_of(cfg, flags)
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(bi[n], cfg) for n in ("e", "hs", "dh") + BLOCK_W + (BLOCK_G if gains else ())}
+
+    def out(*shape, dtype=dt):
+        return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
+    f32 = torch.float32
+    sv = dict(q=out(B, S, H, hd), k=out(B, L, G, hd), v=out(B, L, G, hd), o=out(B, S, H, hd),
+              lse=out(B, H, S, dtype=f32), y=out(B, S, D), u=out(B, S, ffn), w=out(B, S, ffn), m=out(B, S, ffn))
+    if gains:
+        sv.update(xq_n=out(B, S, D), r_q=out(B * S, dtype=f32), xkv_n=out(B, L, D), r_kv=out(B * L, dtype=f32),
+                  z=out(B, S, D), r_mlp=out(B * S, dtype=f32))
+    h = out(B, S, D)
+    params = bx.make_block_params(ffn, rms_eps, **{n: dev[n] for n in BLOCK_W + (BLOCK_G if gains else ())})
+    saved = bx.make_block_saved(**sv)
+    bx.beagle_xattn_block_fwd(d, params, dev["e"], dev["hs"], h, saved,
+                              torch.empty(bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_FWD),
+                                          dtype=torch.uint8, device=DEV))
+    gr = dict(de=out(B, S, D), dwq=out(D, H * hd), dwk=out(D, G * hd), dwv=out(D, G * hd), dwo=out(H * hd, D),
+              dw_gate=out(D, ffn), dw_up=out(D, ffn), dw_down=out(ffn, D))
+    if flags & bx.BEAGLE_FLAG_NEED_DXKV:
+        gr["dhs"] = out(B, L, D)
+    if gains:
+        gr.update(dg_q=out(D, dtype=f32), dg_kv=out(D, dtype=f32), dg_mlp=out(D, dtype=f32))
+    nws = bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_BWD)
+    assert nws > 0
+    ws = torch.empty(nws, dtype=torch.uint8, device=DEV)
+    bx.beagle_xattn_block_bwd(d, params, dev["dh"], dev["e"], dev["hs"], saved, bx.make_block_grads(**gr), ws)
+    torch.cuda.synchronize()
+    fw = {n: to_host(v) for n, v in sv.items()}
+    fw["h"] = to_host(h)
+    return fw, {n: to_host(v) for n, v in gr.items()}
+
+
 def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
     """x [M,D], kc/vc [L,G,d], float32 arrays of stored values."""
     d = desc_of(cfg, 0, scale)

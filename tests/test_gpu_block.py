@@ -1,0 +1,115 @@
+"""GPU parity of the whole draft block (section 4.1, Eq. 1: RMS-normalised sublayer inputs, cross-attention +
+residual, gated feed-forward + residual), forward and backward, against the float64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import block_oracle as blk
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+from gpu_harness import run_block, BLOCK_W, BLOCK_G, max_abs, rel_fro, rel_max
+
+pytestmark = pytest.mark.gpu
+F32_TOL = 1e-5
+BF16_OUT_FRO, LSE_TOL, BF16_GRAD_FRO = 1e-2, 4e-3, 3e-2
+RMS_EPS = 1e-5
+GRADS = ("de", "dhs", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down")
+
+
+def _oracle(cfg, bi, gains):
+    g = {n: (bi[n] if gains else None) for n in BLOCK_G}
+    return blk.block_backward(bi["dh"], bi["e"], bi["hs"], *(bi[n] for n in BLOCK_W), **g, rms_eps=RMS_EPS,
+                              n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size,
+                              eps=cfg.block_offset)
+
+
+def _fwd_pairs(ref, gains):
+    f = ref["fwd"]
+    pairs = dict(h=f["h"], y=f["y"], q=f["attn"]["q"], k=f["attn"]["k"], v=f["attn"]["v"], o=f["attn"]["o"],
+                 u=f["mlp"]["u"], w=f["mlp"]["w"], m=f["mlp"]["m"])
+    if gains:
+        pairs.update(xq_n=f["xq"], xkv_n=f["xkv"], z=f["z"])
+    return pairs
+
+
+@pytest.mark.parametrize("kw,ffn,gains", [
+    (dict(seq_q=40, seq_kv=40, block_size=4), 96, True),
+    (dict(seq_q=40, seq_kv=40, block_size=4), 96, False),                   # Eq. 1 as printed: no normalisation
+    (dict(batch=2, seq_q=70, seq_kv=70, n_q_heads=4, n_kv_heads=2, block_size=5, block_offset=3), 172, True),
+    (dict(batch=1, seq_q=300, seq_kv=300, hidden=64, n_q_heads=1, n_kv_heads=1, block_size=8), 20, True),
+    (dict(batch=3, seq_q=33, seq_kv=50, block_size=1), 64, True),          # S != L
+])
+def test_fp32_block(kw, ffn, gains):
+    cfg = synth.CONFIGS["c1"].with_(seed_base=61, **kw)
+    bi = synth.make_block_inputs(cfg, ffn)
+    ref = _oracle(cfg, bi, gains)
+    fw, gr = run_block(cfg, bi, ffn, RMS_EPS, gains)
+    for n, want in _fwd_pairs(ref, gains).items():
+        assert rel_max(fw[n], want) <= F32_TOL, (n, rel_max(fw[n], want))
+    if gains:
+        rq = 1.0 / np.sqrt((np.asarray(bi["e"], np.float64) ** 2).mean(-1) + RMS_EPS).ravel()
+        assert rel_max(fw["r_q"], rq) <= F32_TOL
+    for n in GRADS + (tuple("d" + g for g in BLOCK_G) if gains else ()):
+        assert rel_max(gr[n], ref[n]) <= 2 * F32_TOL, (n, rel_max(gr[n], ref[n]))
+
+
+SMALL = dict(hidden=512, n_q_heads=4, n_kv_heads=4)
+
+
+@pytest.mark.parametrize("name,kw,ffn,gains", [
+    ("c2", dict(batch=2, seq_q=300, seq_kv=300, **SMALL), 1408, True),
+    ("c2", dict(batch=1, seq_q=300, seq_kv=300, **SMALL), 1408, False),
+    ("c3", dict(batch=1, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2, block_offset=5), 1344, True),
+    ("c2", dict(batch=1, seq_q=257, seq_kv=257, hidden=1024, n_q_heads=8, n_kv_heads=8, block_size=5), 2752, True),
+])
+def test_bf16_block(name, kw, ffn, gains):
+    cfg = synth.CONFIGS[name].with_(seed_base=71, **kw)
+    bi = synth.make_block_inputs(cfg, ffn)
+    ref = _oracle(cfg, bi, gains)
+    fw, gr = run_block(cfg, bi, ffn, RMS_EPS, gains)
+    for n, want in _fwd_pairs(ref, gains).items():
+        assert np.isfinite(fw[n]).all(), n
+        assert rel_fro(fw[n], want) <= BF16_OUT_FRO, (n, rel_fro(fw[n], want))
+    fin = np.isfinite(ref["fwd"]["attn"]["lse"])
+    assert np.array_equal(np.isneginf(fw["lse"]), ~fin)
+    assert max_abs(fw["lse"][fin], ref["fwd"]["attn"]["lse"][fin]) <= LSE_TOL
+    for n in GRADS + (tuple("d" + g for g in BLOCK_G) if gains else ()):
+        assert np.isfinite(gr[n]).all(), n
+        assert rel_fro(gr[n], ref[n]) <= BF16_GRAD_FRO, (n, rel_fro(gr[n], ref[n]))
+
+
+def test_block_without_dhs_still_yields_the_kv_gain_gradient():
+    cfg = synth.CONFIGS["c1"].with_(seed_base=63, seq_q=24, seq_kv=24, block_size=4)
+    bi = synth.make_block_inputs(cfg, 32)
+    ref = _oracle(cfg, bi, True)
+    _, gr = run_block(cfg, bi, 32, RMS_EPS, True, flags=0)
+    assert "dhs" not in gr
+    for n in ("de", "dwk", "dg_kv", "dg_q", "dg_mlp"):
+        assert rel_max(gr[n], ref[n]) <= 2 * F32_TOL, n
+
+
+def test_block_results_are_bitwise_reproducible():
+    cfg = synth.CONFIGS["c2"].with_(seed_base=72, batch=1, seq_q=200, seq_kv=200, **SMALL)
+    bi = synth.make_block_inputs(cfg, 1408)
+    a, b = run_block(cfg, bi, 1408, RMS_EPS), run_block(cfg, bi, 1408, RMS_EPS)
+    for x, y in zip(a, b):
+        for n in x:
+            assert np.array_equal(x[n], y[n], equal_nan=True), n
+
+
+def test_block_argument_errors():
+    import torch
+    a = torch.zeros(1 << 16, device="cuda:0")
+    d = bx.make_desc(batch=1, seq_q=16, seq_kv=16, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=64, block_size=4,
+                     io_dtype=bx.BEAGLE_F32)
+    W = {n: a for n in BLOCK_W}
+    sv = bx.make_block_saved(**{n: a for n in ("q", "k", "v", "o", "lse", "y", "u", "w", "m")})
+    ok = bx.make_block_params(32, 1e-5, **W)
+    f = lambda p, s=sv: bx.beagle_xattn_block_fwd(d, p, a, a, a, s, None, check=False)
+    assert f(bx.make_block_params(30, 1e-5, **W)) == bx.BEAGLE_ERR_UNSUPPORTED      # F % 4
+    assert f(bx.make_block_params(32, -1.0, **W)) == bx.BEAGLE_ERR_SHAPE
+    assert f(bx.make_block_params(32, 1e-5, **dict(W, w_up=None))) == bx.BEAGLE_ERR_NULL
+    assert f(bx.make_block_params(32, 1e-5, g_q=a, **W)) == bx.BEAGLE_ERR_NULL       # gain given but no xq_n / r_q
+    assert f(ok, None) == bx.BEAGLE_ERR_NULL
+    gr = bx.make_block_grads(**{n: a for n in ("de", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down")})
+    assert bx.beagle_xattn_block_bwd(d, ok, a, a, a, sv, gr, a, workspace_bytes=64, check=False) == bx.BEAGLE_ERR_WORKSPACE
+    assert bx.beagle_xattn_block_workspace_bytes(d, 30, bx.BEAGLE_WS_BLOCK_BWD) == 0
