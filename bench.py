@@ -190,6 +190,11 @@ def main():
                    algorithmic_tflop_per_step=round(fl_sim / 1e12, 4))
         del xp, kp, vp, dxp, ws_s
 
+    # ---- the whole draft block of Eq. 1 around the op (RMSNorm, residuals, gated feed-forward), same workload
+    block = None
+    if not args.no_decode:
+        block = bench_block(torch, bx, gh, cfg, t, fl, max(1, args.steps // 2))
+
     # ---- decode: draft step, cold HBM via buffer rotation
     decode = None
     if not args.no_decode:
@@ -210,9 +215,64 @@ def main():
         "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "tokens_per_s": round(B * S / (ms_step * 1e-3)),
         "algorithmic_tflop_per_step": round(fl["total"] / 1e12, 4),
-        "roofline": roofline, "kernels": kernels, "late_stage_sim": sim, "decode": decode, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "late_stage_sim": sim, "draft_block": block, "decode": decode, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def bench_block(torch, bx, gh, cfg, t, fl, nsteps):
+    """Forward + backward of the whole draft block (section 4.1, Eq. 1) at the training workload's shapes with the
+    feed-forward width of the matching LLaMA model; random weights (time is value-independent)."""
+    dev = "cuda:0"
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    F = {4096: 11008, 5120: 13824}.get(D, (8 * D // 3 + 63) // 64 * 64)
+    if G != H and D == 4096:
+        F = 14336                                       # the GQA 8B shape
+    bf, f32 = torch.bfloat16, torch.float32
+    g = torch.Generator(device=dev).manual_seed(11)
+    R = lambda *s, std=0.02: (torch.randn(*s, device=dev, generator=g) * std).to(bf)
+    E = lambda *s, dt=bf: torch.empty(*s, dtype=dt, device=dev)
+    desc = gh.desc_of(cfg, bx.BEAGLE_FLAG_NEED_DXKV)
+    W = dict(wq=t["wq"], wk=t["wk"], wv=t["wv"], wo=t["wo"], w_gate=R(D, F), w_up=R(D, F), w_down=R(F, D),
+             g_q=R(D, std=0.1) + 1, g_kv=R(D, std=0.1) + 1, g_mlp=R(D, std=0.1) + 1)
+    e, hs, dh = R(B, S, D), R(B, L, D, std=3.0), R(B, S, D, std=1.0)
+    sv = dict(xq_n=E(B, S, D), r_q=E(B * S, dt=f32), xkv_n=E(B, L, D), r_kv=E(B * L, dt=f32), q=E(B, S, H, hd),
+              k=E(B, L, G, hd), v=E(B, L, G, hd), o=E(B, S, H, hd), lse=E(B, H, S, dt=f32), y=E(B, S, D), z=E(B, S, D),
+              r_mlp=E(B * S, dt=f32), u=E(B, S, F), w=E(B, S, F), m=E(B, S, F))
+    gr = dict(de=E(B, S, D), dhs=E(B, L, D), dwq=E(D, H * hd), dwk=E(D, G * hd), dwv=E(D, G * hd), dwo=E(H * hd, D),
+              dw_gate=E(D, F), dw_up=E(D, F), dw_down=E(F, D), dg_q=E(D, dt=f32), dg_kv=E(D, dt=f32), dg_mlp=E(D, dt=f32))
+    h = E(B, S, D)
+    params, saved, grads = bx.make_block_params(F, 1e-5, **W), bx.make_block_saved(**sv), bx.make_block_grads(**gr)
+    ws = torch.empty(bx.beagle_xattn_block_workspace_bytes(desc, F, bx.BEAGLE_WS_BLOCK_BWD), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        bx.beagle_xattn_block_fwd(desc, params, e, hs, h, saved, None, stream)
+        bx.beagle_xattn_block_bwd(desc, params, dh, e, hs, saved, grads, ws, stream)
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    bx.beagle_xattn_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(nsteps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / nsteps * 1e3
+    prof = bx.beagle_xattn_profile_end()
+    # the attention op's FLOPs + the feed-forward's three GEMMs forward and six backward (2 M D F each)
+    fl_blk = fl["total"] + 18 * B * S * D * F
+    # bytes the streaming kernels must move at least (bf16): norm fwd r+w, norm bwd 3r+w, gate fwd 2r+w, bwd 3r+2w
+    MD, MF = B * S * D * 2, B * S * F * 2
+    stream_bytes = {"norm_q": 2 * MD, "norm_kv": 2 * B * L * D * 2, "norm_mlp": 2 * MD, "mlp_gate": 3 * MF,
+                    "bwd_mlp_gate": 5 * MF, "bwd_norm_mlp": 4 * MD, "bwd_norm_q": 4 * MD, "bwd_norm_kv": 3 * B * L * D * 2}
+    kern = {}
+    for n, (c, tot) in prof.items():
+        kern[n] = dict(avg_ms=round(tot / c, 4))
+        if n in stream_bytes:
+            kern[n]["gbs"] = round(stream_bytes[n] / (tot / c * 1e-3) / 1e9, 1)
+    return dict(ffn=F, ms_per_step=round(ms, 4), tflops=round(fl_blk / (ms * 1e-3) / 1e12, 1),
+                pct_bf16_mfma_peak=round(100 * fl_blk / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                algorithmic_tflop_per_step=round(fl_blk / 1e12, 4), tokens_per_s=round(B * S / (ms * 1e-3)), kernels=kern)
 
 
 def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):

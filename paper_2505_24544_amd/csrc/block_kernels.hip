@@ -135,14 +135,28 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* dout, const T
     for (int i = 0; i < N; ++i) part[(int64_t)blockIdx.x * D + c + i] = colsum[c + i];
 }
 
-// out[c] = sum_p part[p][c], p in a fixed order
+// out[c] = sum_p part[p][c] in a fixed order: a workgroup owns 64 columns, its four waves each sum every
+// fourth partial row (eight independent loads in flight), then the four sums are added in wave order.
 __global__ __launch_bounds__(256) void colsum_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
                                                             int nparts, int D) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= D) return;
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
   float s = 0.f;
-  for (int p = 0; p < nparts; ++p) s += part[(int64_t)p * D + c];
-  out[c] = s;
+  if (c < D) {
+    int p = wave;
+    for (; p + 28 < nparts; p += 32) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = part[(int64_t)(p + 4 * i) * D + c];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += v[i];
+    }
+    for (; p < nparts; p += 4) s += part[(int64_t)p * D + c];
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && c < D) out[c] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
 }
 
 __device__ __forceinline__ float sigmoidf(float u) { return 1.f / (1.f + expf(-u)); }
@@ -194,7 +208,7 @@ void rmsnorm_bwd_t(const void* dout, const void* x, const void* gain, const floa
                    float* dgain, float* part, int nparts, int64_t rows, int D, hipStream_t s) {
   hipLaunchKernelGGL(rmsnorm_bwd_kernel<T>, dim3(nparts), dim3(256), (size_t)D * sizeof(float), s, (const T*)dout,
                      (const T*)x, (const T*)gain, rinv, (const T*)add, (T*)dx, part, (int)rows, D);
-  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((D + 255) / 256), dim3(256), 0, s, part, dgain, nparts, D);
+  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((D + 63) / 64), dim3(256), 0, s, part, dgain, nparts, D);
 }
 
 int elementwise_grid(int64_t n, int per_thread) {

@@ -148,7 +148,9 @@ __device__ __forceinline__ void map_tile(int pid, const int* tiles, int count, i
   }
 }
 
-template <int TM, int TN, bool XK, bool WK, bool F32OUT>
+// RES: some problem of the group has a residual operand R (a separate instantiation, so that the kernels
+// without one keep their register allocation).
+template <int TM, int TN, bool XK, bool WK, bool F32OUT, bool RES>
 __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(GemmGroup grp, int total_tiles) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
   constexpr int XE = BM * BK, WE = BN * BK;      // elements per operand tile
@@ -273,22 +275,48 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
     __builtin_amdgcn_s_waitcnt(0x0F70);     // drain the look-ahead loads before the stages are reused
   }
 
+  // ---- residual operand: its tile goes HBM -> LDS in one burst (both stages are free now), so that the
+  // epilogue below does not pay one HBM round trip per store.  Chunk q = tid + 256 i (16 bytes) of the tile
+  // lands at 16 q; chunk position pc of row r holds global chunk pc ^ (r % CPR), which spreads the epilogue's
+  // same-column reads of 32 different rows over the banks.  The upper half of the rows lives in stage1.
+  constexpr int CPR = BN / 8;                      // 16-byte chunks per tile row
+  constexpr int RLOADS = BM * CPR / 256;           // per thread
+  const bool with_res = RES && !F32OUT && g.R != nullptr;
+  if (with_res) {
+    static_assert((BM / 2) * BN <= XE + WE, "half of the residual tile must fit one stage");
+    __syncthreads();                               // every wave is done reading the operand stages
+    const __amdgpu_buffer_rsrc_t rrs = make_rsrc(g.R, (int64_t)g.M * g.ldr * 2);
+#pragma unroll
+    for (int i = 0; i < RLOADS; ++i) {
+      const int q = tid + 256 * i, r = q / CPR, c = (q % CPR) ^ (r & (CPR - 1));
+      const int off = (int)(((int64_t)(m0 + r) * g.ldr + n0 + 8 * c) * 2);
+      bf16_t* st = i < RLOADS / 2 ? stage0 : stage1;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rrs, (lds_void_ptr)(st + ((i % (RLOADS / 2)) * 4 + wave) * 512), 16, off,
+                                               0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+  }
+
   // ---- epilogue: lane holds C row m = .. + lane % 32; register e of tile (i, j)
   // holds column n = .. + 8 * (e / 4) + 4 * (lane / 32) + e % 4.
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm + 32 * i + (lane & 31);
+    const int rt = wm + 32 * i + (lane & 31);      // row inside the tile
+    const int m = m0 + rt;
     if (m >= g.M) continue;
+    const bf16_t* rrow = (rt < BM / 2 ? stage0 : stage1) + (rt % (BM / 2)) * BN;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn + 32 * j + 8 * q + 4 * (lane >> 5);
+        const int ct = wn + 32 * j + 8 * q;        // first column of this 8-column chunk inside the tile
+        const int n = n0 + ct + 4 * (lane >> 5);
         if (n >= g.N) continue;
         float a0 = acc[i][j][4 * q], a1 = acc[i][j][4 * q + 1], a2 = acc[i][j][4 * q + 2],
               a3 = acc[i][j][4 * q + 3];
-        if (!F32OUT && g.R) {                   // residual operand (bf16, same shape as C)
-          const uint2 r = *(const uint2*)((const bf16_t*)g.R + (int64_t)m * g.ldr + n);
+        if (with_res) {
+          const uint2 r = *(const uint2*)(rrow + (((ct >> 3) ^ (rt & (CPR - 1))) << 3) + 4 * (lane >> 5));
           a0 += __uint_as_float(r.x << 16); a1 += __uint_as_float(r.x & 0xffff0000u);
           a2 += __uint_as_float(r.y << 16); a3 += __uint_as_float(r.y & 0xffff0000u);
         }
@@ -304,9 +332,9 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
   }
 }
 
-template <int TM, int TN, bool XK, bool WK, bool F32OUT>
+template <int TM, int TN, bool XK, bool WK, bool F32OUT, bool RES = false>
 static void launch_variant(const GemmGroup& grp, int total, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, XK, WK, F32OUT>), dim3(total), dim3(256), 0, s, grp, total);
+  hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, XK, WK, F32OUT, RES>), dim3(total), dim3(256), 0, s, grp, total);
 }
 
 template <int TM, int TN>
@@ -318,15 +346,20 @@ static void launch_tiles(const GemmGroup& grp, hipStream_t s) {
   if (total == 0) return;
   const bool xk = grp.p[0].a_kmajor, wk = grp.p[0].b_kmajor, f32 = grp.p[0].c_is_f32;
   bool fits = true;      // k-contiguous operands: K a multiple of BK; byte offsets must fit 31 bits
+  bool res = false;
   for (int i = 0; i < grp.count; ++i) {
     const GemmArgs& q = grp.p[i];
     const int64_t lim = (int64_t)1 << 31;
+    if (q.R) { res = true; if ((int64_t)q.M * q.ldr * 2 >= lim) fits = false; }
     if ((xk || wk) && (q.K % BK || (q.A2 && q.K2 % BK))) fits = false;
     if ((int64_t)(xk ? q.M : q.K) * q.lda * 2 >= lim || (int64_t)(wk ? q.N : q.K) * q.ldb * 2 >= lim) fits = false;
     if (q.A2 && ((int64_t)(xk ? q.M : q.K2) * q.lda2 * 2 >= lim || (int64_t)(wk ? q.N : q.K2) * q.ldb2 * 2 >= lim)) fits = false;
   }
   if (!fits) { launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar"); return; }
-  if (xk && !wk && !f32) launch_variant<TM, TN, true, false, false>(grp, total, s);
+  if (res && xk && !wk && !f32) launch_variant<TM, TN, true, false, false, true>(grp, total, s);
+  else if (res && xk && wk && !f32) launch_variant<TM, TN, true, true, false, true>(grp, total, s);
+  else if (res) launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar");   // no hot-path call lands here
+  else if (xk && !wk && !f32) launch_variant<TM, TN, true, false, false>(grp, total, s);
   else if (xk && wk && !f32) launch_variant<TM, TN, true, true, false>(grp, total, s);
   else if (!xk && !wk && !f32) launch_variant<TM, TN, false, false, false>(grp, total, s);
   else if (!xk && !wk && f32) launch_variant<TM, TN, false, false, true>(grp, total, s);

@@ -160,6 +160,12 @@ BLOCK_G = ("g_q", "g_kv", "g_mlp")
 def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV):
     """Forward + backward of the whole draft block through the C ABI.  bi: make_block_inputs' dict.
     Returns host float64 dicts (forward results incl. the saved tensors, gradients)."""
+    sv, gr = run_block_device(cfg, bi, ffn, rms_eps, gains, flags)
+    return {n: to_host(v) for n, v in sv.items()}, {n: to_host(v) for n, v in gr.items()}
+
+
+def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV):
+    """As run_block, results left on the device (forward dict includes h)."""
     d = desc_of(cfg, flags)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
@@ -190,9 +196,8 @@ def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV)
     ws = torch.empty(nws, dtype=torch.uint8, device=DEV)
     bx.beagle_xattn_block_bwd(d, params, dev["dh"], dev["e"], dev["hs"], saved, bx.make_block_grads(**gr), ws)
     torch.cuda.synchronize()
-    fw = {n: to_host(v) for n, v in sv.items()}
-    fw["h"] = to_host(h)
-    return fw, {n: to_host(v) for n, v in gr.items()}
+    sv["h"] = h
+    return sv, gr
 
 
 def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):

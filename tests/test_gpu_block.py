@@ -113,3 +113,39 @@ def test_block_argument_errors():
     gr = bx.make_block_grads(**{n: a for n in ("de", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down")})
     assert bx.beagle_xattn_block_bwd(d, ok, a, a, a, sv, gr, a, workspace_bytes=64, check=False) == bx.BEAGLE_ERR_WORKSPACE
     assert bx.beagle_xattn_block_workspace_bytes(d, 30, bx.BEAGLE_WS_BLOCK_BWD) == 0
+
+
+@pytest.mark.parametrize("gains", [True, False])
+def test_fullsize_block_on_sampled_rows(gains):
+    """The 7B-shaped training workload with the feed-forward width of that model (the shapes bench.py times, hence
+    the 256 x 256 GEMM tiles and their residual epilogues): h and de of sampled query rows of one batch entry
+    against the oracle evaluated row by row (a query row of the block depends on the other rows only through the
+    keys and values, which are projected in full)."""
+    from oracle import beagle_oracle as orc
+    cfg = synth.CONFIGS["c2"].with_(seed_base=80, batch=2)
+    ffn = 11008
+    bi = synth.make_block_inputs(cfg, ffn)
+    from gpu_harness import run_block_device, to_host
+    fw, gr = run_block_device(cfg, bi, ffn, RMS_EPS, gains)
+    b = 1
+    rows = np.array([0, 3, 4, 5, 127, 128, 255, 256, 1000, 1023, 1024, 2044, 2047])
+    H, G, k = cfg.n_q_heads, cfg.n_kv_heads, cfg.block_size
+    f64 = lambda n: np.asarray(bi[n], np.float64)
+    g = {n: (f64(n) if gains else None) for n in BLOCK_G}
+    e_r, dh_r = f64("e")[b:b + 1, rows], f64("dh")[b:b + 1, rows]
+    xq = blk.rmsnorm(e_r, g["g_q"], RMS_EPS)
+    xkv = blk.rmsnorm(f64("hs")[b:b + 1], g["g_kv"], RMS_EPS)
+    mask = orc.dense_mask(cfg.seq_q, cfg.seq_kv, k, cfg.block_offset)[rows]
+    W = [f64(n) for n in ("wq", "wk", "wv", "wo")]
+    y = orc.xattn_forward(xq, xkv, *W, n_q_heads=H, n_kv_heads=G, mask=mask)["y"] + e_r
+    z = blk.rmsnorm(y, g["g_mlp"], RMS_EPS)
+    mw = [f64(n) for n in ("w_gate", "w_up", "w_down")]
+    h = blk.mlp_forward(z, *mw)["out"] + y
+    dz = blk.mlp_backward(dh_r, z, *mw)["dz"]
+    dy = dh_r + blk.rmsnorm_backward(dz, y, g["g_mlp"], RMS_EPS)[0]
+    dxq = orc.xattn_backward(dy, xq, xkv, *W, n_q_heads=H, n_kv_heads=G, mask=mask)["dxq"]
+    de = dy + blk.rmsnorm_backward(dxq, e_r, g["g_q"], RMS_EPS)[0]
+    for name, got, want in (("y", fw["y"], y), ("h", fw["h"], h), ("de", gr["de"], de)):
+        got = to_host(got[b, rows])
+        assert np.isfinite(got).all(), name
+        assert rel_fro(got, want[0]) <= (BF16_GRAD_FRO if name == "de" else BF16_OUT_FRO), (name, rel_fro(got, want[0]))
