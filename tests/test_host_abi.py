@@ -134,6 +134,36 @@ def test_simulation_entry_points_validate_before_launching():
     assert save(_desc(S=32, L=64), 0) == 2 and save(d, -1) == 2 and save(d, 0, None) == 1 and save(d, 0, a + 4) == 5
 
 
+def test_block_entry_points_validate_before_launching():
+    a = 4096
+    d = _desc(S=16, L=16)
+    W = dict(wq=a, wk=a, wv=a, wo=a, w_gate=a, w_up=a, w_down=a)
+    sv = bx.make_block_saved(**{n: a for n in ("q", "k", "v", "o", "lse", "y", "u", "w", "m")})
+    fwd = lambda p, s=sv, e=a: bx.beagle_xattn_block_fwd(d, p, e, a, a, s, None, stream=0, check=False)
+    assert fwd(bx.make_block_params(30, 1e-5, **W)) == 3                 # F % 4 != 0
+    assert fwd(bx.make_block_params(0, 1e-5, **W)) == 2
+    assert fwd(bx.make_block_params(32, float("nan"), **W)) == 2
+    assert fwd(bx.make_block_params(32, 1e-5, **dict(W, w_down=None))) == 1
+    assert fwd(bx.make_block_params(32, 1e-5, g_mlp=a, **W)) == 1         # gain without z / r_mlp
+    assert fwd(bx.make_block_params(32, 1e-5, **W), None) == 1
+    assert fwd(bx.make_block_params(32, 1e-5, **W), sv, a + 4) == 5
+    bad = bx.make_block_params(32, 1e-5, **W)
+    bad.struct_size = 8
+    assert fwd(bad) == 2
+    gr = bx.make_block_grads(**{n: a for n in ("de", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down")})
+    ok = bx.make_block_params(32, 1e-5, **W)
+    bwd = lambda g, wsb: bx.beagle_xattn_block_bwd(d, ok, a, a, a, sv, g, a, stream=0, workspace_bytes=wsb, check=False)
+    assert bwd(gr, 64) == 4 and bwd(None, 1 << 40) == 1
+    assert bx.beagle_xattn_block_bwd(_desc(S=16, L=16, flags=bx.BEAGLE_FLAG_NEED_DXKV), ok, a, a, a, sv, gr, a, stream=0,
+                                     workspace_bytes=1 << 40, check=False) == 1   # dhs requested but not given
+    assert bx.beagle_xattn_block_bwd(_desc(S=16, L=16, flags=bx.BEAGLE_FLAG_WGRAD_F32), ok, a, a, a, sv, gr, a, stream=0,
+                                     workspace_bytes=1 << 40, check=False) == 3
+    n = bx.beagle_xattn_block_workspace_bytes(d, 32, bx.BEAGLE_WS_BLOCK_BWD)
+    assert n > bx.beagle_xattn_workspace_bytes(d, bx.BEAGLE_WS_BWD) and bx.beagle_xattn_block_workspace_bytes(d, 30, 1) == 0
+    with pytest.raises(KeyError):
+        bx.make_block_saved(nonsense=a)
+
+
 def test_entry_points_validate_before_launching():
     """NULL / misaligned / short-workspace arguments return a status without
     touching the GPU (this test runs where there is none)."""
