@@ -226,6 +226,40 @@ def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
         y=fw["y"], lse=fw["lse"], o=o, q=q, k=k, v=v)
 
 
+
+# --------------------------------------------------------------------------
+# One window offset per batch entry (section 4.2: the windows start "at a
+# random minor offset"; the paper does not say whether the offset is drawn per
+# step or per sequence -- with one value per sequence every batch entry simply
+# has its own early-stage mask).  Written as that sentence: sample by sample.
+# --------------------------------------------------------------------------
+def xattn_forward_sample_eps(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None):
+    """xattn_forward with batch entry b under dense_mask(Sq, L, k, eps_list[b])."""
+    xq, xkv = np.asarray(xq, F64), np.asarray(xkv, F64)
+    if len(eps_list) != xq.shape[0]:
+        raise ValueError("one offset per batch entry")
+    parts = [xattn_forward(xq[b:b + 1], xkv[b:b + 1], wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                           mask=dense_mask(xq.shape[1], xkv.shape[1], k, int(eps_list[b])), scale=scale)
+             for b in range(xq.shape[0])]
+    out = {n: np.concatenate([p[n] for p in parts], axis=0) for n in ("y", "lse", "q", "k", "v", "o")}
+    out["scale"] = parts[0]["scale"]
+    return out
+
+
+def xattn_backward_sample_eps(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None):
+    """Gradients under per-entry offsets: input gradients entry by entry, weight
+    gradients summed over the entries (the loss is a sum over the batch)."""
+    dy, xq, xkv = np.asarray(dy, F64), np.asarray(xq, F64), np.asarray(xkv, F64)
+    if len(eps_list) != xq.shape[0]:
+        raise ValueError("one offset per batch entry")
+    parts = [xattn_backward(dy[b:b + 1], xq[b:b + 1], xkv[b:b + 1], wq, wk, wv, wo, n_q_heads=n_q_heads,
+                            n_kv_heads=n_kv_heads, mask=dense_mask(xq.shape[1], xkv.shape[1], k, int(eps_list[b])),
+                            scale=scale) for b in range(xq.shape[0])]
+    out = {n: np.concatenate([p[n] for p in parts], axis=0) for n in ("dxq", "dxkv", "y", "lse", "o", "q", "k", "v")}
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        out[n] = sum(p[n] for p in parts)
+    return out
+
 # --------------------------------------------------------------------------
 # Late-stage training: simulated inference steps (section 4.2, second half, and
 # the caption of the mask figure; the figure itself is not available)
