@@ -85,6 +85,15 @@ typedef struct {
   int32_t io_dtype;      /* beagle_dtype                                        */
   float   softmax_scale; /* 0 selects 1/sqrt(d) as in Eq. 2                     */
   uint32_t flags;        /* BEAGLE_FLAG_*; unknown bits are rejected            */
+  const int32_t* block_offsets; /* NULL, or DEVICE pointer to B offsets: batch entry
+                            b uses eps = block_offsets[b] instead of block_offset
+                            (section 4.2's random offset drawn per sequence).
+                            Values must lie in [0, k); the kernels reduce them
+                            modulo k.  4-byte aligned.  Not used by the draft-step
+                            entry points; the host-side beagle_xattn_mask_* /
+                            beagle_xattn_tile_map helpers return
+                            BEAGLE_ERR_UNSUPPORTED when it is set (inspect one
+                            entry at a time through block_offset).              */
 } beagle_xattn_desc;
 
 /* Bytes of device workspace that the given entry point needs for `desc`

@@ -22,6 +22,7 @@ struct Dims {
   bool bf16;
   float scale;
   MaskParams mask;
+  const int32_t* eps_b;   // per-entry window offsets (device) or null
 };
 
 beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
@@ -62,6 +63,8 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
   d.mask.eps = draft ? 0 : c->block_offset;
   d.mask.seq_kv = (int32_t)d.L;
   d.mask.all_visible = draft ? 1 : 0;
+  if (c->block_offsets && (((uintptr_t)c->block_offsets) & 3u)) return BEAGLE_ERR_ALIGN;
+  d.eps_b = draft ? nullptr : c->block_offsets;
   *out = d;
   return BEAGLE_OK;
 }
@@ -82,7 +85,7 @@ BwdWs bwd_layout(const Dims& d) {
 AttnArgs attn_args(const Dims& d) {
   AttnArgs a; memset(&a, 0, sizeof(a));
   a.B = (int32_t)d.B; a.S = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G;
-  a.d = (int32_t)d.d; a.scale = d.scale; a.mask = d.mask;
+  a.d = (int32_t)d.d; a.scale = d.scale; a.mask = d.mask; a.eps_b = d.eps_b;
   return a;
 }
 
@@ -271,6 +274,7 @@ const char* beagle_xattn_version(void) { return "1.0"; }
 beagle_status beagle_xattn_mask_row_limit(const beagle_xattn_desc* desc, int32_t* ws_out) {
   Dims d; beagle_status st = check_desc(desc, false, &d);
   if (st != BEAGLE_OK) return st;
+  if (d.eps_b) return BEAGLE_ERR_UNSUPPORTED;   // per-entry offsets live on the device: inspect one entry at a time
   if (!ws_out) return BEAGLE_ERR_NULL;
   for (int32_t p = 0; p < d.S; ++p) ws_out[p] = row_limit(p, d.mask);
   return BEAGLE_OK;
@@ -279,6 +283,7 @@ beagle_status beagle_xattn_mask_row_limit(const beagle_xattn_desc* desc, int32_t
 beagle_status beagle_xattn_mask_dense(const beagle_xattn_desc* desc, uint8_t* mask_out) {
   Dims d; beagle_status st = check_desc(desc, false, &d);
   if (st != BEAGLE_OK) return st;
+  if (d.eps_b) return BEAGLE_ERR_UNSUPPORTED;   // per-entry offsets live on the device: inspect one entry at a time
   if (!mask_out) return BEAGLE_ERR_NULL;
   for (int64_t p = 0; p < d.S; ++p) {
     int32_t lim = row_limit((int32_t)p, d.mask);
@@ -290,6 +295,7 @@ beagle_status beagle_xattn_mask_dense(const beagle_xattn_desc* desc, uint8_t* ma
 beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, int32_t tk, uint8_t* cls_out) {
   Dims d; beagle_status st = check_desc(desc, false, &d);
   if (st != BEAGLE_OK) return st;
+  if (d.eps_b) return BEAGLE_ERR_UNSUPPORTED;   // per-entry offsets live on the device: inspect one entry at a time
   if (!cls_out) return BEAGLE_ERR_NULL;
   if (tq < 1 || tk < 1) return BEAGLE_ERR_SHAPE;
   const int64_t nq = (d.S + tq - 1) / tq, nk = (d.L + tk - 1) / tk;
@@ -422,7 +428,7 @@ beagle_status beagle_xattn_sim_save(const beagle_xattn_desc* desc, const void* h
   if ((d.D * (int64_t)d.esz) % 16) return BEAGLE_ERR_UNSUPPORTED;
   if (sim_step >= desc->block_size) return BEAGLE_OK;      // every window is already full
   (void)hipGetLastError();
-  launch_sim_save(h, xpred, (int)d.B, (int)d.L, d.D * (int64_t)d.esz, desc->block_size, desc->block_offset, sim_step,
+  launch_sim_save(h, xpred, (int)d.B, (int)d.L, d.D * (int64_t)d.esz, desc->block_size, desc->block_offset, d.eps_b, sim_step,
                   (hipStream_t)hip_stream);
   return hip_status();
 }

@@ -72,10 +72,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
   const int64_t li = ((int64_t)b * a.H + h) * a.S + qc;
 
-  const int lim = q_ok ? row_limit(q, a.mask) : 0;
-  const int wg_lim = row_limit(min(q0 + BQ, a.S) - 1, a.mask);
-  const int wave_hi = qw0 < a.S ? row_limit(min(qw0 + 32, a.S) - 1, a.mask) : 0;
-  const int wave_lo = qw0 < a.S ? row_limit(qw0, a.mask) : 0;
+  const MaskParams mk = sample_mask(a, b);
+  const int lim = q_ok ? row_limit(q, mk) : 0;
+  const int wg_lim = row_limit(min(q0 + BQ, a.S) - 1, mk);
+  const int wave_hi = qw0 < a.S ? row_limit(min(qw0 + 32, a.S) - 1, mk) : 0;
+  const int wave_lo = qw0 < a.S ? row_limit(qw0, mk) : 0;
   const int ntiles = (wg_lim + BJ - 1) / BJ;
 
   bf16x8_t qf[8], dof[8];
@@ -212,10 +213,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int64_t qs = (int64_t)a.H * HD;
 
   // first query that sees this lane's key / any key of the wave / every key of the wave / any of the workgroup
-  const int fq = j_ok ? first_query_seeing(j, a.mask) : a.S;
-  const int wave_first = jw0 < a.L ? first_query_seeing(jw0, a.mask) : a.S;
-  const int wave_all = jw0 < a.L ? first_query_seeing(min(jw0 + 32, a.L) - 1, a.mask) : a.S;
-  const int wg_first = first_query_seeing(j0, a.mask);
+  const MaskParams mk = sample_mask(a, b);
+  const int fq = j_ok ? first_query_seeing(j, mk) : a.S;
+  const int wave_first = jw0 < a.L ? first_query_seeing(jw0, mk) : a.S;
+  const int wave_all = jw0 < a.L ? first_query_seeing(min(jw0 + 32, a.L) - 1, mk) : a.S;
+  const int wg_first = first_query_seeing(j0, mk);
   const int qt0 = wg_first / BQ;
   const int nqt = (a.S + BQ - 1) / BQ;
   const int per_head = nqt > qt0 ? nqt - qt0 : 0;

@@ -57,12 +57,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
   const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
 
-  const int lim = q_ok ? row_limit(q, a.mask) : 0;                 // keys visible to this lane's query
+  const MaskParams mk = sample_mask(a, b);
+  const int lim = q_ok ? row_limit(q, mk) : 0;                     // keys visible to this lane's query
   const int q_last = min(q0 + BQ, a.S) - 1;
-  const int wg_lim = row_limit(q_last, a.mask);                    // limits never decrease with p
+  const int wg_lim = row_limit(q_last, mk);                    // limits never decrease with p
   const int w_last = min(qw0 + 32, a.S) - 1;
-  const int wave_hi = qw0 < a.S ? row_limit(w_last, a.mask) : 0;   // largest limit in this wave
-  const int wave_lo = qw0 < a.S ? row_limit(qw0, a.mask) : 0;      // smallest
+  const int wave_hi = qw0 < a.S ? row_limit(w_last, mk) : 0;   // largest limit in this wave
+  const int wave_lo = qw0 < a.S ? row_limit(qw0, mk) : 0;      // smallest
   const int ntiles = (wg_lim + BJ - 1) / BJ;
 
   // Q fragments: B operand, lane holds Q[q][16*s + 8*hf .. +7]

@@ -78,6 +78,7 @@ struct AttnArgs {
   int32_t B, S, L, H, G, d;
   float scale;
   MaskParams mask;
+  const int32_t* eps_b;                           // per batch entry window offsets (device, [B]) or null
   const void* q; const void* k; const void* v;   // [B,S,H,d], [B,L,G,d] x2
   void* o; float* lse;                            // [B,S,H,d], [B,H,S]
   // backward only
@@ -87,6 +88,16 @@ struct AttnArgs {
   // draft-tree decode only: keys >= n_true are visible to query p iff bit (j - n_true) of row p is set
   const uint32_t* tree; int32_t n_true, tree_words;
 };
+
+// The mask of batch entry b: the shared parameters, with the entry's own window offset if offsets were given.
+__device__ __forceinline__ MaskParams sample_mask(const AttnArgs& a, int b) {
+  MaskParams m = a.mask;
+  if (a.eps_b) {
+    const int32_t e = a.eps_b[b] % m.k;
+    m.eps = e < 0 ? e + m.k : e;
+  }
+  return m;
+}
 // Late-stage simulation: the band of predicted keys of every query, merged into / differentiated
 // against the result of the masked attention over the true keys.
 struct SimArgs {
@@ -98,7 +109,8 @@ struct SimArgs {
 };
 void launch_sim_band_fwd(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd(const SimArgs& s, hipStream_t st);
-void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, int t, hipStream_t st);
+void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, const int32_t* eps_b,
+                     int t, hipStream_t st);
 // streaming variants for bf16 storage (head width 128), chosen by the two launchers above
 void launch_sim_band_fwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd_bf16(const SimArgs& s, hipStream_t st);

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(64) void attn_fwd_scalar_kernel(AttnArgs a) {
   const int64_t kvs = (int64_t)a.G * d;
   T* O = (T*)a.o + (((int64_t)b * a.S + p) * a.H + h) * d;
   const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
-  const int n = row_limit(p, a.mask);
+  const int n = row_limit(p, sample_mask(a, b));
   for (int c = lane; c < d; c += 64) qs[c] = Io<T>::ld(Q + c);
   __syncthreads();
   if (n == 0) {
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_scalar_kernel(AttnArgs a) {
   const T* V = (const T*)a.v + ((int64_t)b * a.L * a.G + g) * d;
   const int64_t kvs = (int64_t)a.G * d;
   const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
-  const int n = row_limit(p, a.mask);
+  const int n = row_limit(p, sample_mask(a, b));
   float part = 0.f;
   for (int c = lane; c < d; c += 64) {
     qs[c] = Io<T>::ld(Q + c);
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_scalar_kernel(AttnArgs a) {
   T* dV = (T*)a.dv + kvrow;
   for (int c = lane; c < d; c += 64) { ks[c] = Io<T>::ld(K + c); vs[c] = Io<T>::ld(V + c); }
   __syncthreads();
-  const int pstart = first_query_seeing(j, a.mask);
+  const int pstart = first_query_seeing(j, sample_mask(a, b));
   const int64_t qst = (int64_t)a.H * d;
   float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
   for (int hh = 0; hh < rep; ++hh) {
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_scalar_kernel(AttnArgs a) {
     for (int p0 = pstart; p0 < a.S; p0 += 64) {
       int p = p0 + lane;
       float pj = 0.f, ds = 0.f;
-      if (p < a.S && j < row_limit(p, a.mask)) {
+      if (p < a.S && j < row_limit(p, sample_mask(a, b))) {
         pj = expf(a.scale * dot_row(ks, Q + p * qst, d) - lse[p]);
         float dp = dot_row(vs, dO + p * qst, d);
         ds = pj * (dp - dl[p]);
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(64) void sim_band_fwd_kernel(SimArgs s) {
   const AttnArgs& a = s.a;
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   int lo, hi;
-  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
+  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
   if (hi <= lo) return;
   const int d = a.d, g = h / (a.H / a.G);
   const int64_t kvs = (int64_t)a.G * d;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(64) void sim_band_bwd_dq_kernel(SimArgs s) {
   const AttnArgs& a = s.a;
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   int lo, hi;
-  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
+  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
   if (hi <= lo) return;
   const int d = a.d, g = h / (a.H / a.G);
   const int64_t kvs = (int64_t)a.G * d;
@@ -414,7 +414,7 @@ __global__ __launch_bounds__(64) void sim_band_bwd_dkv_kernel(SimArgs s) {
   const T* vr = (const T*)s.vp + kvrow;
   const bool c0 = lane < d, c1 = lane + 64 < d;
   float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
-  const int w0 = window_start_raw(j, a.mask.k, a.mask.eps);
+  const int w0 = window_start_raw(j, a.mask.k, sample_mask(a, b).eps);
   if (j - w0 < s.t) {                                  // this position holds a predicted state at step t
     const float k0 = c0 ? Io<T>::ld(kr + lane) : 0.f, k1 = c1 ? Io<T>::ld(kr + lane + 64) : 0.f;
     const float v0 = c0 ? Io<T>::ld(vr + lane) : 0.f, v1 = c1 ? Io<T>::ld(vr + lane + 64) : 0.f;
@@ -464,7 +464,8 @@ void launch_sim_band_bwd(const SimArgs& s, hipStream_t st) {
 // after step t the row at position t of every window takes the newly predicted state of that position.
 // blockIdx.x: window (the partial leading one first), blockIdx.y: batch entry; rows as 16-byte chunks.
 __global__ __launch_bounds__(256) void sim_save_kernel(const uint4* __restrict__ h, uint4* __restrict__ xpred, int L,
-                                                       int chunks, int k, int eps, int t) {
+                                                       int chunks, int k, int eps, const int32_t* eps_b, int t) {
+  if (eps_b) { eps = eps_b[blockIdx.y] % k; if (eps < 0) eps += k; }
   const int n0 = eps > 0 ? eps - k : 0;
   const int j = n0 + (int)blockIdx.x * k + t;
   if (j < 0 || j >= L) return;
@@ -472,12 +473,13 @@ __global__ __launch_bounds__(256) void sim_save_kernel(const uint4* __restrict__
   for (int c = threadIdx.x; c < chunks; c += 256) xpred[row + c] = h[row + c];
 }
 
-void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, int t, hipStream_t st) {
+void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, const int32_t* eps_b,
+                     int t, hipStream_t st) {
   ProfScope ps("sim_save", st);
-  const int n0 = eps > 0 ? eps - k : 0;
-  const int n_win = (L - n0 + k - 1) / k;
+  const int n0 = (eps_b || eps > 0) ? -k + 1 : 0;   // lowest possible start of the leading window
+  const int n_win = (L - n0 + k - 1) / k + 1;
   hipLaunchKernelGGL(sim_save_kernel, dim3(n_win, B), dim3(256), 0, st, (const uint4*)h, (uint4*)xpred, L,
-                     (int)(row_bytes / 16), k, eps, t);
+                     (int)(row_bytes / 16), k, eps, eps_b, t);
 }
 
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s) {

@@ -59,10 +59,10 @@ __global__ __launch_bounds__(256) void sim_band_fwd_bf16_kernel(SimArgs s) {
   const int rb = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (rb >= a.S * a.H) return;
   const int p = rb / a.H, h = rb - p * a.H, g = h / (a.H / a.G);
-  int lo, hi;
-  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
-  if (hi <= lo) return;
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    int lo, hi;
+    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+    if (hi <= lo) continue;
     const int64_t row = ((int64_t)b * a.S * a.H + rb) * BD;
     const bf16_t* Kp = (const bf16_t*)s.kp + ((int64_t)b * a.L * a.G + g) * BD;
     const bf16_t* Vp = (const bf16_t*)s.vp + ((int64_t)b * a.L * a.G + g) * BD;
@@ -99,10 +99,10 @@ __global__ __launch_bounds__(256) void sim_band_bwd_dq_bf16_kernel(SimArgs s) {
   const int rb = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (rb >= a.S * a.H) return;
   const int p = rb / a.H, h = rb - p * a.H, g = h / (a.H / a.G);
-  int lo, hi;
-  sim_band(p, a.mask.k, a.mask.eps, s.t, a.L, lo, hi);
-  if (hi <= lo) return;
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    int lo, hi;
+    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+    if (hi <= lo) continue;
     const int64_t row = ((int64_t)b * a.S * a.H + rb) * BD;
     const bf16_t* Kp = (const bf16_t*)s.kp + ((int64_t)b * a.L * a.G + g) * BD;
     const bf16_t* Vp = (const bf16_t*)s.vp + ((int64_t)b * a.L * a.G + g) * BD;
@@ -134,10 +134,10 @@ __global__ __launch_bounds__(256) void sim_band_bwd_dkv_bf16_kernel(SimArgs s) {
   const int rb = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 4), c = threadIdx.x & 15;
   if (rb >= a.L * a.G) return;
   const int j = rb / a.G, g = rb - j * a.G, rep = a.H / a.G;
-  const int w0 = window_start_raw(j, a.mask.k, a.mask.eps);
-  const bool holds_pred = j - w0 < s.t;                    // this position holds a predicted state at step t
-  const int p_end = min(w0 + a.mask.k, a.S);               // the later queries of the same window see it
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    const int w0 = window_start_raw(j, a.mask.k, sample_mask(a, b).eps);
+    const bool holds_pred = j - w0 < s.t;                  // this position holds a predicted state at step t
+    const int p_end = min(w0 + a.mask.k, a.S);             // the later queries of the same window see it
     const int64_t kvrow = ((int64_t)b * a.L * a.G + rb) * BD;
     Chunk dk, dv;
 #pragma unroll

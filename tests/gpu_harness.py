@@ -12,8 +12,9 @@ from paper_2505_24544_amd import synth
 DEV = "cuda:0"
 
 
-def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0):
-    return bx.make_desc(batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
+def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0, block_offsets=None):
+    """block_offsets: optional int32 device tensor of per-entry offsets (the caller keeps it alive)."""
+    return bx.make_desc(block_offsets=block_offsets, batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
                         n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                         block_size=cfg.block_size, block_offset=cfg.block_offset,
                         io_dtype=bx.BEAGLE_BF16 if cfg.dtype == "bf16" else bx.BEAGLE_F32,
