@@ -121,14 +121,54 @@ def masked_softmax(scores: np.ndarray, mask: np.ndarray):
     return P, lse[..., 0]
 
 
+# --------------------------------------------------------------------------
+# Rotary position embedding (optional).  Section 4.1 leaves positional
+# embeddings out "for clarity"; the LLaMA / Vicuna targets the drafts are built
+# for rotate queries and keys.  Reading taken here (PARITY UNPINNED by the
+# paper): the rotate-half convention of those models -- channel c < d/2 is
+# paired with channel c + d/2, angle = position * base^(-2c/d) -- applied to
+# the projected Q at the query's sequence position and to the projected K at
+# the key's sequence position, per head; V is not rotated.
+# --------------------------------------------------------------------------
+def rope_rotate(x, positions, base=10000.0, inverse=False):
+    """x [..., P, heads, d] with d even, positions [P]: every (x_c, x_{c+d/2})
+    pair is rotated by +angle (by -angle if inverse: the transpose, which is
+    what the backward pass applies to gradients)."""
+    x = np.asarray(x, F64)
+    d = x.shape[-1]
+    if d % 2:
+        raise ValueError("rotary embedding needs an even head width")
+    half = d // 2
+    pos = np.asarray(positions, F64)
+    if pos.shape != (x.shape[-3],):
+        raise ValueError("one position per row")
+    ang = pos[:, None] * (float(base) ** (-2.0 * np.arange(half) / d))[None, :]
+    if inverse:
+        ang = -ang
+    cos, sin = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * cos - x2 * sin, x2 * cos + x1 * sin], axis=-1)
+
+
+def _rope_args(rope, n_q, n_k):
+    """rope: None, or dict(base=..., q_pos=[n_q] or None, k_pos=[n_k] or None); default positions are the indices."""
+    base = rope.get("base", 10000.0) or 10000.0
+    q_pos = rope.get("q_pos")
+    k_pos = rope.get("k_pos")
+    return (base, np.arange(n_q) if q_pos is None else np.asarray(q_pos),
+            np.arange(n_k) if k_pos is None else np.asarray(k_pos))
+
+
 def xattn_forward(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
-                  scale=None, keep_probs=False):
+                  scale=None, keep_probs=False, rope=None):
     """Forward pass of Eq. 2 under an explicit dense mask.
 
     xq  [B, Sq, D]      draft-side query states e(t_i)
     xkv [B, L, D]       target hidden states h_j
     wq  [D, H*d]  wk, wv [D, G*d]  wo [H*d, D]
     mask bool [Sq, L]   shared by batch and heads
+    rope: None, or dict(base, q_pos, k_pos) -- Q and K are rotated after the
+    projections (rope_rotate); the returned q, k are the rotated ones.
     Returns dict: y [B,Sq,D], lse [B,H,Sq], q [B,Sq,H,d], k,v [B,L,G,d],
                   o [B,Sq,H,d] and, if keep_probs, p [B,H,Sq,L].
     """
@@ -147,6 +187,9 @@ def xattn_forward(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
     q = (xq @ wq).reshape(B, Sq, H, d)
     k = (xkv @ wk).reshape(B, L, G, d)
     v = (xkv @ wv).reshape(B, L, G, d)
+    if rope is not None:
+        base, q_pos, k_pos = _rope_args(rope, Sq, L)
+        q, k = rope_rotate(q, q_pos, base), rope_rotate(k, k_pos, base)
     o = np.zeros((B, Sq, H, d), F64)
     lse = np.zeros((B, H, Sq), F64)
     probs = np.zeros((B, H, Sq, L), F64) if keep_probs else None
@@ -169,7 +212,7 @@ def xattn_forward(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
 # Backward (chain rule of Eq. 2 on the dense probabilities)
 # --------------------------------------------------------------------------
 def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
-                   scale=None):
+                   scale=None, rope=None):
     """Gradients of sum(dy * y) with respect to every input of xattn_forward.
 
     Returns dict with dxq, dxkv, dwq, dwk, dwv, dwo and the intermediates
@@ -181,7 +224,7 @@ def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
     H, G = n_q_heads, n_kv_heads
     rep = _check_heads(H, G)
     fw = xattn_forward(xq, xkv, wq, wk, wv, wo, n_q_heads=H, n_kv_heads=G,
-                       mask=mask, scale=scale, keep_probs=False)
+                       mask=mask, scale=scale, keep_probs=False, rope=rope)
     q, k, v, o, scale = fw["q"], fw["k"], fw["v"], fw["o"], fw["scale"]
     B, Sq, D = xq.shape
     L = xkv.shape[1]
@@ -213,6 +256,11 @@ def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
             dq[b, :, h, :] = (dS @ k[b, :, g, :]) * scale
             dk[b, :, g, :] += (dS.T @ q[b, :, h, :]) * scale
 
+    if rope is not None:
+        # dq, dk above are gradients of the ROTATED q, k; the rotation is orthogonal, so the gradients of the
+        # projections' outputs are the same vectors rotated back
+        base, q_pos, k_pos = _rope_args(rope, Sq, L)
+        dq, dk = rope_rotate(dq, q_pos, base, inverse=True), rope_rotate(dk, k_pos, base, inverse=True)
     dq2 = dq.reshape(B * Sq, H * d)
     dk2 = dk.reshape(B * L, G * d)
     dv2 = dv.reshape(B * L, G * d)
@@ -233,20 +281,21 @@ def xattn_backward(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, mask,
 # step or per sequence -- with one value per sequence every batch entry simply
 # has its own early-stage mask).  Written as that sentence: sample by sample.
 # --------------------------------------------------------------------------
-def xattn_forward_sample_eps(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None):
+def xattn_forward_sample_eps(xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None, rope=None):
     """xattn_forward with batch entry b under dense_mask(Sq, L, k, eps_list[b])."""
     xq, xkv = np.asarray(xq, F64), np.asarray(xkv, F64)
     if len(eps_list) != xq.shape[0]:
         raise ValueError("one offset per batch entry")
     parts = [xattn_forward(xq[b:b + 1], xkv[b:b + 1], wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
-                           mask=dense_mask(xq.shape[1], xkv.shape[1], k, int(eps_list[b])), scale=scale)
+                           mask=dense_mask(xq.shape[1], xkv.shape[1], k, int(eps_list[b])), scale=scale, rope=rope)
              for b in range(xq.shape[0])]
     out = {n: np.concatenate([p[n] for p in parts], axis=0) for n in ("y", "lse", "q", "k", "v", "o")}
     out["scale"] = parts[0]["scale"]
     return out
 
 
-def xattn_backward_sample_eps(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None):
+def xattn_backward_sample_eps(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps_list, scale=None,
+                              rope=None):
     """Gradients under per-entry offsets: input gradients entry by entry, weight
     gradients summed over the entries (the loss is a sum over the batch)."""
     dy, xq, xkv = np.asarray(dy, F64), np.asarray(xq, F64), np.asarray(xkv, F64)
@@ -254,7 +303,7 @@ def xattn_backward_sample_eps(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_he
         raise ValueError("one offset per batch entry")
     parts = [xattn_backward(dy[b:b + 1], xq[b:b + 1], xkv[b:b + 1], wq, wk, wv, wo, n_q_heads=n_q_heads,
                             n_kv_heads=n_kv_heads, mask=dense_mask(xq.shape[1], xkv.shape[1], k, int(eps_list[b])),
-                            scale=scale) for b in range(xq.shape[0])]
+                            scale=scale, rope=rope) for b in range(xq.shape[0])]
     out = {n: np.concatenate([p[n] for p in parts], axis=0) for n in ("dxq", "dxkv", "y", "lse", "o", "q", "k", "v")}
     for n in ("dwq", "dwk", "dwv", "dwo"):
         out[n] = sum(p[n] for p in parts)
@@ -341,23 +390,32 @@ def _sim_concat(xkv, xpred, k, eps, t, seq_q):
     return np.concatenate([xkv, xpred], axis=1), mask, L
 
 
-def xattn_forward_sim(xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None):
+def _sim_rope(rope, L):
+    """A predicted state stands at its own sequence position: the concatenated keys have positions 0..L-1 twice."""
+    if rope is None:
+        return None
+    return dict(base=rope.get("base"), q_pos=None, k_pos=np.concatenate([np.arange(L), np.arange(L)]))
+
+
+def xattn_forward_sim(xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None, rope=None):
     """Forward of simulation step t: Eq. 2 over the keys [true states under the
     early-stage mask | predicted states under sim_pred_mask].  Returns the dict
     of xattn_forward with k, v split into k, v (true) and kp, vp (predicted)."""
     cat, mask, L = _sim_concat(xkv, xpred, k, eps, t, np.asarray(xq).shape[1])
-    out = xattn_forward(xq, cat, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask, scale=scale)
+    out = xattn_forward(xq, cat, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask, scale=scale,
+                        rope=_sim_rope(rope, L))
     out["kp"], out["vp"] = out["k"][:, L:], out["v"][:, L:]
     out["k"], out["v"] = out["k"][:, :L], out["v"][:, :L]
     return out
 
 
-def xattn_backward_sim(dy, xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None):
+def xattn_backward_sim(dy, xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_heads, k, eps, t, scale=None,
+                       rope=None):
     """Gradients of simulation step t with respect to every input, the
     predicted-state buffer included (dxpred; zero on rows that no query sees)."""
     cat, mask, L = _sim_concat(xkv, xpred, k, eps, t, np.asarray(xq).shape[1])
     out = xattn_backward(dy, xq, cat, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask,
-                         scale=scale)
+                         scale=scale, rope=_sim_rope(rope, L))
     out["dxpred"] = out["dxkv"][:, L:]
     out["dxkv"] = out["dxkv"][:, :L]
     for n in ("k", "v", "dk", "dv"):
@@ -368,11 +426,13 @@ def xattn_backward_sim(dy, xq, xkv, xpred, wq, wk, wv, wo, *, n_q_heads, n_kv_he
 # --------------------------------------------------------------------------
 # Decode-time draft step (section 4.1, KV-cache paragraph)
 # --------------------------------------------------------------------------
-def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None):
+def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None, rope=None):
     """M draft queries against a cache of L already-projected K/V rows.
 
     x [M, D]; k_cache, v_cache [L, G, d]; every query sees every cache row
-    (drafted states are not concatenated).  Returns y [M, D], lse [H, M].
+    (drafted states are not concatenated).  rope: None or dict(base, q_pos [M]):
+    the projected queries are rotated to those positions (the cache rows were
+    rotated when they were appended).  Returns y [M, D], lse [H, M].
     """
     x = np.asarray(x, F64)
     kc, vc = np.asarray(k_cache, F64), np.asarray(v_cache, F64)
@@ -384,6 +444,8 @@ def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None
     if scale is None or scale == 0:
         scale = 1.0 / math.sqrt(d)
     q = (x @ wq).reshape(M, H, d)
+    if rope is not None:
+        q = rope_rotate(q, rope["q_pos"], rope.get("base", 10000.0) or 10000.0)
     o = np.zeros((M, H, d), F64)
     lse = np.zeros((H, M), F64)
     allvis = np.ones((M, L), bool)
@@ -414,8 +476,9 @@ def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None
 #     an arbitrary boolean mask, ancestor_mask() builds this reading of it.
 #   * Resetting the cache is dropping the rows past n_true: no arithmetic.
 # --------------------------------------------------------------------------
-def kv_project(x_new, wk, wv, *, n_kv_heads):
-    """K and V rows of n new states (true or drafted): x_new [n, D] -> [n, G, d] each."""
+def kv_project(x_new, wk, wv, *, n_kv_heads, rope=None):
+    """K and V rows of n new states (true or drafted): x_new [n, D] -> [n, G, d] each.
+    rope: None or dict(base, k_pos [n]) -- the sequence positions of the new states, to which K is rotated."""
     x = np.asarray(x_new, F64)
     wk, wv = np.asarray(wk, F64), np.asarray(wv, F64)
     n = x.shape[0]
@@ -423,13 +486,16 @@ def kv_project(x_new, wk, wv, *, n_kv_heads):
     if wk.shape[1] % G or wk.shape != wv.shape:
         raise ValueError("K/V weight shapes")
     d = wk.shape[1] // G
-    return (x @ wk).reshape(n, G, d), (x @ wv).reshape(n, G, d)
+    kn = (x @ wk).reshape(n, G, d)
+    if rope is not None:
+        kn = rope_rotate(kn, rope["k_pos"], rope.get("base", 10000.0) or 10000.0)
+    return kn, (x @ wv).reshape(n, G, d)
 
 
-def kv_append(k_cache, v_cache, pos, x_new, wk, wv, *, n_kv_heads):
+def kv_append(k_cache, v_cache, pos, x_new, wk, wv, *, n_kv_heads, rope=None):
     """Copies of the caches with rows pos .. pos+n-1 replaced by the K/V rows of x_new."""
     kc, vc = np.array(k_cache, F64, copy=True), np.array(v_cache, F64, copy=True)
-    kn, vn = kv_project(x_new, wk, wv, n_kv_heads=n_kv_heads)
+    kn, vn = kv_project(x_new, wk, wv, n_kv_heads=n_kv_heads, rope=rope)
     n = kn.shape[0]
     if pos < 0 or pos + n > kc.shape[0]:
         raise ValueError("append range outside the cache")
@@ -461,7 +527,7 @@ def ancestor_mask(parents, query_nodes):
     return out
 
 
-def draft_step_tree(x, k_cache, v_cache, wq, wo, *, n_true, tree_mask, n_q_heads, n_kv_heads, scale=None):
+def draft_step_tree(x, k_cache, v_cache, wq, wo, *, n_true, tree_mask, n_q_heads, n_kv_heads, scale=None, rope=None):
     """M draft queries against n_true true rows plus T drafted rows of the cache.
 
     x [M, D]; k_cache, v_cache [n_true + T, G, d]; tree_mask boolean [M, T]:
@@ -483,6 +549,8 @@ def draft_step_tree(x, k_cache, v_cache, wq, wo, *, n_true, tree_mask, n_q_heads
         scale = 1.0 / math.sqrt(d)
     vis = np.concatenate([np.ones((M, n_true), bool), tm], axis=1)
     q = (x @ wq).reshape(M, H, d)
+    if rope is not None:
+        q = rope_rotate(q, rope["q_pos"], rope.get("base", 10000.0) or 10000.0)
     o = np.zeros((M, H, d), F64)
     lse = np.zeros((H, M), F64)
     for h in range(H):

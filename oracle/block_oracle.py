@@ -105,7 +105,7 @@ def mlp_backward(dout, z, w_gate, w_up, w_down):
 # The block (Eq. 1)
 # --------------------------------------------------------------------------
 def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
-                  rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None):
+                  rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None):
     """e [B,S,D] token embeddings, hs [B,L,D] key/value states.  Returns dict with
     h [B,S,D] (the block's output), y (after the first residual), the normalised
     inputs xq, xkv, z, the attention's own results (attn: the dict of
@@ -115,7 +115,7 @@ def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv
     xkv = rmsnorm(hs, g_kv, rms_eps)
     mask = orc.dense_mask(e.shape[1], hs.shape[1], k, eps)
     attn = orc.xattn_forward(xq, xkv, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask,
-                             scale=scale)
+                             scale=scale, rope=rope)
     y = attn["y"] + e                                   # Eq. 1, second line
     z = rmsnorm(y, g_mlp, rms_eps)
     mlp = mlp_forward(z, w_gate, w_up, w_down)
@@ -124,19 +124,19 @@ def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv
 
 
 def block_backward(dh, e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
-                   rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None):
+                   rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None):
     """Gradients of sum(dh * h) w.r.t. every input of block_forward: de, dhs, the
     seven weight matrices and the three gains (None where the gain is None)."""
     dh = np.asarray(dh, F64)
     f = block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, g_q=g_q, g_kv=g_kv, g_mlp=g_mlp,
-                      rms_eps=rms_eps, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k, eps=eps, scale=scale)
+                      rms_eps=rms_eps, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k, eps=eps, scale=scale, rope=rope)
     # h = MLP(z) + y
     mb = mlp_backward(dh, f["z"], w_gate, w_up, w_down)
     dy_norm, dg_mlp = rmsnorm_backward(mb["dz"], f["y"], g_mlp, rms_eps)
     dy = dh + dy_norm
     # y = CrossAttn(xkv, xq) + e
     ab = orc.xattn_backward(dy, f["xq"], f["xkv"], wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
-                            mask=f["mask"], scale=scale)
+                            mask=f["mask"], scale=scale, rope=rope)
     de_norm, dg_q = rmsnorm_backward(ab["dxq"], e, g_q, rms_eps)
     dhs, dg_kv = rmsnorm_backward(ab["dxkv"], hs, g_kv, rms_eps)
     return dict(de=dy + de_norm, dhs=dhs, dwq=ab["dwq"], dwk=ab["dwk"], dwv=ab["dwv"], dwo=ab["dwo"],
