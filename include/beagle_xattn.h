@@ -35,6 +35,17 @@
  *     -infinity and contributes no gradient.
  *   - Results are run-to-run bitwise reproducible (no floating-point atomics).
  *
+ * Rotary position embedding (optional, BEAGLE_FLAG_ROPE)
+ *   Section 4.1 leaves positional embeddings out of its equations; the LLaMA /
+ *   Vicuna targets rotate queries and keys.  With the flag set, the projected
+ *   Q (at the query's sequence position) and K (at the key's) are rotated per
+ *   head in the rotate-half convention of those models: channel c < d/2 pairs
+ *   with channel c + d/2, angle = position * rope_base^(-2c/d).  V is not
+ *   rotated.  q_save / k_save and the decode cache hold the ROTATED rows; the
+ *   backward rotates dQ, dK back before the projections' gradients.  In the
+ *   simulation step a predicted state stands at its own sequence position.
+ *   Not available for the bf16 draft step (BEAGLE_ERR_UNSUPPORTED).
+ *
  * Supported shapes
  *   BEAGLE_F32 : any d <= 128 with d % 4 == 0; D, H*d, G*d multiples of 4.
  *   BEAGLE_BF16: d == 128; D a multiple of 64.
@@ -65,8 +76,10 @@ typedef enum { BEAGLE_F32 = 0, BEAGLE_BF16 = 1 } beagle_dtype;
 
 enum {
   BEAGLE_FLAG_NEED_DXKV = 1u << 0, /* bwd also produces dxkv                    */
-  BEAGLE_FLAG_WGRAD_F32 = 1u << 1  /* bwd writes dwq/dwk/dwv/dwo as float even
+  BEAGLE_FLAG_WGRAD_F32 = 1u << 1, /* bwd writes dwq/dwk/dwv/dwo as float even
                                       when io_dtype is bf16                     */
+  BEAGLE_FLAG_ROPE = 1u << 2       /* rotary position embedding of Q and K, see
+                                      rope_base / rope_positions below          */
 };
 
 enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3, BEAGLE_WS_BWD_SIM = 4 };
@@ -94,6 +107,13 @@ typedef struct {
                             beagle_xattn_tile_map helpers return
                             BEAGLE_ERR_UNSUPPORTED when it is set (inspect one
                             entry at a time through block_offset).              */
+  float rope_base;       /* BEAGLE_FLAG_ROPE: frequency base; 0 selects 10000   */
+  const int32_t* rope_positions; /* BEAGLE_FLAG_ROPE, decode side only (DEVICE pointer
+                            or NULL): draft step -- the sequence positions of its
+                            M queries (NULL: all at seq_kv, the position after the
+                            cached rows); kv_append -- the positions of the n new
+                            rows (NULL: pos + i).  Must be NULL for the training
+                            entry points, where position = index.  4-byte aligned. */
 } beagle_xattn_desc;
 
 /* Bytes of device workspace that the given entry point needs for `desc`

@@ -20,7 +20,7 @@ BEAGLE_OK = 0
 (BEAGLE_ERR_NULL, BEAGLE_ERR_SHAPE, BEAGLE_ERR_UNSUPPORTED, BEAGLE_ERR_WORKSPACE, BEAGLE_ERR_ALIGN,
  BEAGLE_ERR_HIP) = range(1, 7)
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
-BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32 = 1, 2
+BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32, BEAGLE_FLAG_ROPE = 1, 2, 4
 BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
 BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD = 0, 1
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
@@ -49,15 +49,17 @@ class beagle_xattn_desc(C.Structure):
         ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block_size", C.c_int32), ("block_offset", C.c_int32), ("io_dtype", C.c_int32),
         ("softmax_scale", C.c_float), ("flags", C.c_uint32), ("block_offsets", C.c_void_p),
+        ("rope_base", C.c_float), ("rope_positions", C.c_void_p),
     ]
 
 
 def make_desc(*, batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads, head_dim, block_size=1,
               block_offset=0, io_dtype=BEAGLE_BF16, softmax_scale=0.0, flags=0,
-              block_offsets=None) -> beagle_xattn_desc:
+              block_offsets=None, rope_base=0.0, rope_positions=None) -> beagle_xattn_desc:
     """block_offsets: None, or an int32 device tensor / address of B per-entry offsets (kept alive by the caller)."""
     return beagle_xattn_desc(C.sizeof(beagle_xattn_desc), batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads,
-                             head_dim, block_size, block_offset, io_dtype, softmax_scale, flags, _ptr(block_offsets))
+                             head_dim, block_size, block_offset, io_dtype, softmax_scale, flags, _ptr(block_offsets),
+                             rope_base, _ptr(rope_positions))
 
 
 _VP = C.c_void_p

@@ -10,7 +10,7 @@ using namespace beagle;
 
 namespace {
 
-constexpr uint32_t KNOWN_FLAGS = BEAGLE_FLAG_NEED_DXKV | BEAGLE_FLAG_WGRAD_F32;
+constexpr uint32_t KNOWN_FLAGS = BEAGLE_FLAG_NEED_DXKV | BEAGLE_FLAG_WGRAD_F32 | BEAGLE_FLAG_ROPE;
 constexpr size_t WS_ALIGN = 256;
 
 size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
@@ -23,6 +23,7 @@ struct Dims {
   float scale;
   MaskParams mask;
   const int32_t* eps_b;   // per-entry window offsets (device) or null
+  bool rope; float rope_base; const int32_t* rope_pos;
 };
 
 beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
@@ -65,6 +66,18 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
   d.mask.all_visible = draft ? 1 : 0;
   if (c->block_offsets && (((uintptr_t)c->block_offsets) & 3u)) return BEAGLE_ERR_ALIGN;
   d.eps_b = draft ? nullptr : c->block_offsets;
+  d.rope = (c->flags & BEAGLE_FLAG_ROPE) != 0;
+  d.rope_base = 10000.f; d.rope_pos = nullptr;
+  if (d.rope) {
+    if (!(c->rope_base >= 0.f) || isinf(c->rope_base)) return BEAGLE_ERR_SHAPE;
+    if (c->rope_base > 0.f) d.rope_base = c->rope_base;
+    if (d.d % 4) return BEAGLE_ERR_UNSUPPORTED;
+    if (c->rope_positions) {
+      if (!draft) return BEAGLE_ERR_UNSUPPORTED;           // training: position = index
+      if (((uintptr_t)c->rope_positions) & 3u) return BEAGLE_ERR_ALIGN;
+      d.rope_pos = c->rope_positions;
+    }
+  }
   *out = d;
   return BEAGLE_OK;
 }
@@ -117,6 +130,16 @@ void run_gemm(const Dims& d, const GemmGroup& g, hipStream_t s, const char* name
 
 beagle_status hip_status() { return hipGetLastError() == hipSuccess ? BEAGLE_OK : BEAGLE_ERR_HIP; }
 
+RopeArgs rope_args(const Dims& d, bool inverse) {
+  RopeArgs r; memset(&r, 0, sizeof(r));
+  r.d = (int32_t)d.d; r.base = d.rope_base; r.inverse = inverse ? 1 : 0;
+  return r;
+}
+void rope_add(RopeArgs& r, void* x, int64_t rows, int64_t period, int64_t heads, int32_t pos0, const int32_t* pos) {
+  const int i = r.n++;
+  r.x[i] = x; r.rows[i] = rows; r.period[i] = (int32_t)period; r.heads[i] = (int32_t)heads; r.pos0[i] = pos0; r.pos[i] = pos;
+}
+
 // Projections, masked attention, output projection (+ y_res in its epilogue if given).
 void xattn_fwd_run(const Dims& d, const void* xq, const void* xkv, const void* wq, const void* wk, const void* wv,
                    const void* wo, void* y, float* lse, void* q_save, void* k_save, void* v_save, void* o_save,
@@ -127,6 +150,12 @@ void xattn_fwd_run(const Dims& d, const void* xq, const void* xkv, const void* w
   qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
   qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
   run_gemm(d, qkv, s, "proj_qkv");
+  if (d.rope) {
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, q_save, d.B * d.S, d.S, d.H, 0, nullptr);
+    rope_add(r, k_save, d.B * d.L, d.L, d.G, 0, nullptr);
+    launch_rope(d.bf16, r, s, "rope_qk");
+  }
 
   AttnArgs a = attn_args(d);
   a.q = q_save; a.k = k_save; a.v = v_save; a.o = o_save; a.lse = lse;
@@ -157,6 +186,12 @@ void xattn_bwd_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, con
   a.q = q_save; a.k = k_save; a.v = v_save; a.o = (void*)o_save; a.lse = (float*)lse;
   a.dout = dO; a.dq = dQ; a.dk = dK; a.dv = dV; a.delta = delta;
   if (d.bf16) launch_attn_bwd_bf16(a, base + w.attn, s); else launch_attn_bwd_f32(a, s);
+  if (d.rope) {   // dQ, dK are gradients of the rotated rows: rotate them back
+    RopeArgs r = rope_args(d, true);
+    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr);
+    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr);
+    launch_rope(d.bf16, r, s, "bwd_rope_qk");
+  }
 
   // input gradients
   {
@@ -406,6 +441,13 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.B * d.L, d.GD, d.D);
   kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.B * d.L, d.GD, d.D);
   run_gemm(d, kvp, s, "proj_kvp");
+  if (d.rope) {   // a predicted state stands at its own sequence position
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, q_save, d.B * d.S, d.S, d.H, 0, nullptr);
+    rope_add(r, k_save, d.B * d.L, d.L, d.G, 0, nullptr);
+    rope_add(r, kp_save, d.B * d.L, d.L, d.G, 0, nullptr);
+    launch_rope(d.bf16, r, s, "rope_qk");
+  }
 
   SimArgs sa; memset(&sa, 0, sizeof(sa));
   sa.a = attn_args(d);
@@ -478,6 +520,13 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   if (d.bf16) launch_attn_bwd_bf16(sa.a, base + w.attn, s); else launch_attn_bwd_f32(sa.a, s);
   // predicted-key band: adds to dQ, writes dKp and dVp (zeros where nothing is seen)
   launch_sim_band_bwd(sa, s);
+  if (d.rope) {
+    RopeArgs r = rope_args(d, true);
+    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr);
+    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr);
+    rope_add(r, dKp, Mk, d.L, d.G, 0, nullptr);
+    launch_rope(d.bf16, r, s, "bwd_rope_qk");
+  }
 
   {
     GemmGroup g; memset(&g, 0, sizeof(g));
@@ -532,6 +581,7 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
+  if (d.bf16 && d.rope) return BEAGLE_ERR_UNSUPPORTED;
   if (d.bf16) {
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
@@ -545,6 +595,11 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
   void* q = base;
   void* o = base + (size_t)(d.S * d.HD) * d.esz;
   launch_gemm_f32(group1(gemm_nn(x_draft, wq, q, d.S, d.HD, d.D)), s, "draft_proj_q");
+  if (d.rope) {   // the M queries at their own positions, or all at the position after the cached rows
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, q, d.S, d.rope_pos ? d.S : 1, d.H, (int32_t)d.L, d.rope_pos);
+    launch_rope(false, r, s, "draft_rope_q");
+  }
   AttnArgs a = attn_args(d);
   a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
   a.tree = tree; a.n_true = n_true; a.tree_words = words;
@@ -589,13 +644,18 @@ beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
   if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
     // a handful of states: HBM-bound on Wk and Wv, so the split-k streaming projection of the draft step
     launch_kv_append_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, workspace, s);
-    return hip_status();
+  } else {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 2;
+    g.p[0] = gemm_nn(x_new, wk, kdst, d.S, d.GD, d.D);
+    g.p[1] = gemm_nn(x_new, wv, vdst, d.S, d.GD, d.D);
+    run_gemm(d, g, s, "kv_append");
   }
-  GemmGroup g; memset(&g, 0, sizeof(g));
-  g.count = 2;
-  g.p[0] = gemm_nn(x_new, wk, kdst, d.S, d.GD, d.D);
-  g.p[1] = gemm_nn(x_new, wv, vdst, d.S, d.GD, d.D);
-  run_gemm(d, g, s, "kv_append");
+  if (d.rope) {   // the new K rows at their sequence positions (given, or the row indices)
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, kdst, d.S, d.S, d.G, pos, d.rope_pos);
+    launch_rope(d.bf16, r, s, "kv_append_rope");
+  }
   return hip_status();
 }
 

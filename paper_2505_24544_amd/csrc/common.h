@@ -73,6 +73,20 @@ void launch_silu_mul_fwd(bool bf16, const void* u, const void* w, void* m, int64
 void launch_silu_mul_bwd(bool bf16, const void* dm, const void* u, const void* w, void* du, void* dw, int64_t n,
                          hipStream_t s);
 
+// ---- rotary position embedding, in place, of up to three [rows, heads, d] tensors in one launch ----
+// Row r of tensor t stands at position pos[t] ? pos[t][r % period[t]] : pos0[t] + r % period[t].
+struct RopeArgs {
+  int32_t n;                    // tensors
+  void* x[3];
+  int64_t rows[3];
+  int32_t period[3], heads[3], pos0[3];
+  const int32_t* pos[3];        // device, or null
+  int32_t d;                    // head width, d % 4 == 0, d <= 128
+  float base;
+  int32_t inverse;              // rotate by -angle (gradients)
+};
+void launch_rope(bool bf16, const RopeArgs& r, hipStream_t s, const char* name);
+
 // ---- attention -------------------------------------------------------------
 struct AttnArgs {
   int32_t B, S, L, H, G, d;

@@ -12,9 +12,9 @@ from paper_2505_24544_amd import synth
 DEV = "cuda:0"
 
 
-def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0, block_offsets=None):
-    """block_offsets: optional int32 device tensor of per-entry offsets (the caller keeps it alive)."""
-    return bx.make_desc(block_offsets=block_offsets, batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
+def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0, block_offsets=None, rope_base=0.0, rope_positions=None):
+    """block_offsets / rope_positions: optional int32 device tensors (the caller keeps them alive)."""
+    return bx.make_desc(block_offsets=block_offsets, rope_base=rope_base, rope_positions=rope_positions, batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
                         n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                         block_size=cfg.block_size, block_offset=cfg.block_offset,
                         io_dtype=bx.BEAGLE_BF16 if cfg.dtype == "bf16" else bx.BEAGLE_F32,
@@ -97,10 +97,10 @@ def run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poi
     return g
 
 
-def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0):
+def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, desc=None):
     """Forward + backward of late-stage simulation step t through the C ABI.
     Returns host float64 dicts (forward results, gradients)."""
-    d = desc_of(cfg, flags, scale)
+    d = desc if desc is not None else desc_of(cfg, flags, scale)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
@@ -158,16 +158,16 @@ BLOCK_W = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 BLOCK_G = ("g_q", "g_kv", "g_mlp")
 
 
-def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV):
+def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None):
     """Forward + backward of the whole draft block through the C ABI.  bi: make_block_inputs' dict.
     Returns host float64 dicts (forward results incl. the saved tensors, gradients)."""
-    sv, gr = run_block_device(cfg, bi, ffn, rms_eps, gains, flags)
+    sv, gr = run_block_device(cfg, bi, ffn, rms_eps, gains, flags, desc)
     return {n: to_host(v) for n, v in sv.items()}, {n: to_host(v) for n, v in gr.items()}
 
 
-def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV):
+def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None):
     """As run_block, results left on the device (forward dict includes h)."""
-    d = desc_of(cfg, flags)
+    d = desc if desc is not None else desc_of(cfg, flags)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
     dev = {n: to_dev(bi[n], cfg) for n in ("e", "hs", "dh") + BLOCK_W + (BLOCK_G if gains else ())}
@@ -201,16 +201,38 @@ def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEE
     return sv, gr
 
 
-def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0):
+def run_train(cfg, inp, desc):
+    """Training forward + backward through the C ABI under a caller-built descriptor (dXkv requested).
+    Returns host float64 dicts (forward results, gradients)."""
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    t = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    out = lambda *s, dtype=dt: torch.full(s, float("nan"), dtype=dtype, device=DEV)
+    f = dict(y=out(B, S, D), lse=out(B, H, S, dtype=torch.float32), q=out(B, S, H, hd), k=out(B, L, G, hd),
+             v=out(B, L, G, hd), o=out(B, S, H, hd))
+    bx.beagle_xattn_fwd(desc, t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], f["y"], f["lse"], f["q"], f["k"],
+                        f["v"], f["o"], workspace(desc, bx.BEAGLE_WS_FWD))
+    g = dict(dxq=out(B, S, D), dxkv=out(B, L, D), dwq=out(D, H * hd), dwk=out(D, G * hd), dwv=out(D, G * hd),
+             dwo=out(H * hd, D))
+    bx.beagle_xattn_bwd(desc, t["dy"], t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], f["q"], f["k"], f["v"],
+                        f["o"], f["lse"], g["dxq"], g["dxkv"], g["dwq"], g["dwk"], g["dwv"], g["dwo"],
+                        workspace(desc, bx.BEAGLE_WS_BWD))
+    torch.cuda.synchronize()
+    return {n: to_host(v) for n, v in f.items()}, {n: to_host(v) for n, v in g.items()}
+
+
+def run_draft(cfg, x, kc, vc, wq, wo, scale=0.0, desc=None, check=True):
     """x [M,D], kc/vc [L,G,d], float32 arrays of stored values."""
-    d = desc_of(cfg, 0, scale)
+    d = desc if desc is not None else desc_of(cfg, 0, scale)
     M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
     t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
     y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
     lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
     ws = workspace(d, bx.BEAGLE_WS_DRAFT)
-    bx.beagle_xattn_draft_step(d, t["x"], t["kc"], t["vc"], t["wq"], t["wo"], y, lse, ws)
+    st = bx.beagle_xattn_draft_step(d, t["x"], t["kc"], t["vc"], t["wq"], t["wo"], y, lse, ws, check=check)
     torch.cuda.synchronize()
+    if not check:
+        return st
     return to_host(y), to_host(lse)
 
 
@@ -243,9 +265,9 @@ def run_draft_tree(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=T
     return to_host(y), to_host(lse)
 
 
-def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True):
+def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True, desc=None):
     """kc/vc: host arrays [capacity, G, d] (current cache contents).  Returns the caches after the call."""
-    d = desc_of(cfg, 0, 0.0)
+    d = desc if desc is not None else desc_of(cfg, 0, 0.0)
     t = {n: to_dev(a, cfg) for n, a in dict(x=x_new, wk=wk, wv=wv, kc=kc, vc=vc).items()}
     ws = workspace(d, bx.BEAGLE_WS_APPEND)
     st = bx.beagle_xattn_kv_append(d, t["x"], t["wk"], t["wv"], t["kc"], t["vc"], pos, ws, check=check)

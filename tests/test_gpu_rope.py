@@ -1,0 +1,154 @@
+"""GPU parity of the optional rotary position embedding of Q and K (the paper leaves positional embeddings out of
+section 4.1; rotate-half convention of the LLaMA family): training forward/backward, simulation step, draft block,
+cache append and the fp32 draft step, against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import beagle_oracle as orc
+from oracle import block_oracle as blk
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+F32_TOL = 1e-5
+OUT_ABS, OUT_FRO, LSE_TOL, GRAD_FRO = 2e-2, 1e-2, 4e-3, 3e-2
+GRADS = ("dxq", "dxkv", "dwq", "dwk", "dwv", "dwo")
+ROPE = bx.BEAGLE_FLAG_ROPE | bx.BEAGLE_FLAG_NEED_DXKV
+
+
+def _ref_train(cfg, inp, base):
+    mask = orc.dense_mask(cfg.seq_q, cfg.seq_kv, cfg.block_size, cfg.block_offset)
+    return orc.xattn_backward(inp["dy"], inp["xq"], inp["xkv"], inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                              n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, mask=mask, rope=dict(base=base))
+
+
+@pytest.mark.parametrize("kw,base", [
+    (dict(seq_q=40, seq_kv=40, block_size=4), 0.0),                          # 0 selects 10000
+    (dict(batch=2, seq_q=70, seq_kv=70, n_q_heads=4, n_kv_heads=2, block_size=5, block_offset=3), 500.0),
+    (dict(seq_q=33, seq_kv=50, hidden=128, n_q_heads=4, n_kv_heads=4, head_dim=32, block_size=1), 10000.0),
+    (dict(seq_q=3000, seq_kv=3000, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=64, block_size=500), 10000.0),
+])
+def test_fp32_training_with_rope(kw, base):
+    cfg = synth.CONFIGS["c1"].with_(seed_base=101, **kw)
+    inp = synth.make_inputs(cfg)
+    ref = _ref_train(cfg, inp, base or 10000.0)
+    fw, gr = gh.run_train(cfg, inp, gh.desc_of(cfg, ROPE, rope_base=base))
+    for n in ("y", "o", "q", "k", "v"):
+        assert gh.rel_max(fw[n], ref[n]) <= F32_TOL, (n, gh.rel_max(fw[n], ref[n]))
+    for n in GRADS:
+        assert gh.rel_max(gr[n], ref[n]) <= F32_TOL, (n, gh.rel_max(gr[n], ref[n]))
+    plain = gh.run_train(cfg, inp, gh.desc_of(cfg, bx.BEAGLE_FLAG_NEED_DXKV))[0]
+    assert not np.allclose(plain["y"], fw["y"], atol=1e-4)                   # the flag does something
+
+
+SMALL = dict(hidden=512, n_q_heads=4, n_kv_heads=4)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("c2", dict(batch=2, seq_q=300, seq_kv=300, **SMALL)),
+    ("c3", dict(batch=1, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2, block_offset=5)),
+])
+def test_bf16_training_with_rope(name, kw):
+    cfg = synth.CONFIGS[name].with_(**kw)
+    inp = synth.make_inputs(cfg, peaked_queries=True)
+    ref = _ref_train(cfg, inp, 10000.0)
+    fw, gr = gh.run_train(cfg, inp, gh.desc_of(cfg, ROPE))
+    for n in ("y", "o", "q", "k"):
+        assert np.isfinite(fw[n]).all(), n
+        assert gh.max_abs(fw[n], ref[n]) <= OUT_ABS and gh.rel_fro(fw[n], ref[n]) <= OUT_FRO, (n, gh.rel_fro(fw[n], ref[n]))
+    fin = np.isfinite(ref["lse"])
+    assert gh.max_abs(fw["lse"][fin], ref["lse"][fin]) <= LSE_TOL
+    for n in GRADS:
+        assert gh.rel_fro(gr[n], ref[n]) <= GRAD_FRO, (n, gh.rel_fro(gr[n], ref[n]))
+
+
+def test_simulation_step_with_rope():
+    cfg = synth.CONFIGS["c1"].with_(seed_base=103, batch=2, seq_q=45, seq_kv=45, block_size=4, block_offset=1)
+    inp = synth.make_inputs(cfg)
+    xp = synth.make_inputs(cfg.with_(seed_base=153), with_dy=False)["xkv"]
+    ref = orc.xattn_backward_sim(inp["dy"], inp["xq"], inp["xkv"], xp, inp["wq"], inp["wk"], inp["wv"], inp["wo"],
+                                 n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=4, eps=1, t=2, rope=dict(base=800.0))
+    fw, gr = gh.run_sim(cfg, inp, xp, 2, desc=gh.desc_of(cfg, ROPE, rope_base=800.0))
+    for n in ("y", "k", "kp", "o"):
+        assert gh.rel_max(fw[n], ref[n]) <= F32_TOL, n
+    for n in GRADS + ("dxpred",):
+        assert gh.rel_max(gr[n], ref[n]) <= F32_TOL, (n, gh.rel_max(gr[n], ref[n]))
+
+
+def test_draft_block_with_rope():
+    cfg = synth.CONFIGS["c2"].with_(seed_base=105, batch=1, seq_q=260, seq_kv=260, **SMALL)
+    bi = synth.make_block_inputs(cfg, 1408)
+    W = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+    ref = blk.block_backward(bi["dh"], bi["e"], bi["hs"], *(bi[n] for n in W), g_q=bi["g_q"], g_kv=bi["g_kv"],
+                             g_mlp=bi["g_mlp"], rms_eps=1e-5, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+                             k=cfg.block_size, eps=cfg.block_offset, rope=dict(base=10000.0))
+    fw, gr = gh.run_block(cfg, bi, 1408, 1e-5, True, desc=gh.desc_of(cfg, ROPE))
+    assert gh.rel_fro(fw["h"], ref["fwd"]["h"]) <= OUT_FRO
+    for n in ("de", "dhs", "dwq", "dwk", "dw_gate", "dg_q", "dg_kv"):
+        assert gh.rel_fro(gr[n], ref[n]) <= GRAD_FRO, (n, gh.rel_fro(gr[n], ref[n]))
+
+
+@pytest.mark.parametrize("dtype,n,pos,cap,G,D,d,explicit", [
+    ("f32", 5, 3, 20, 2, 256, 64, False), ("f32", 4, 1, 9, 2, 128, 32, True),
+    ("bf16", 10, 4000, 4100, 4, 512, 128, False), ("bf16", 10, 50, 100, 4, 512, 128, True),
+    ("bf16", 300, 0, 300, 2, 512, 128, False),
+])
+def test_kv_append_rotates_the_new_keys(dtype, n, pos, cap, G, D, d, explicit):
+    base_cfg = synth.CONFIGS["c4" if dtype == "bf16" else "c1"]
+    cfg = base_cfg.with_(batch=1, seq_q=n, seq_kv=cap, hidden=D, n_q_heads=G, n_kv_heads=G, head_dim=d, seed_base=910 + n)
+    inp = synth.make_inputs(cfg, with_dy=False)
+    x_new = inp["xq"][0]
+    rng = np.random.default_rng(5)
+    old_k, old_v = (rng.standard_normal((cap, G, d)).astype(np.float32) for _ in range(2))
+    if dtype == "bf16":
+        old_k, old_v = synth.round_to_bf16(old_k), synth.round_to_bf16(old_v)
+    # explicit positions: drafted rows of a tree, ten per depth, stand at n_true + depth, not at their row index
+    positions = (pos + np.arange(n) // 3) if explicit else (pos + np.arange(n))
+    pos_dev = torch.tensor(positions, dtype=torch.int32, device=gh.DEV) if explicit else None
+    wantk, wantv = orc.kv_append(old_k, old_v, pos, x_new, inp["wk"], inp["wv"], n_kv_heads=G,
+                                 rope=dict(base=10000.0, k_pos=positions))
+    gotk, gotv = gh.run_kv_append(cfg, x_new, inp["wk"], inp["wv"], old_k, old_v, pos,
+                                  desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE, rope_positions=pos_dev))
+    keep = np.ones(cap, bool)
+    keep[pos:pos + n] = False
+    assert np.array_equal(gotk[keep], old_k[keep].astype(np.float64)) and np.array_equal(gotv[keep], old_v[keep].astype(np.float64))
+    for got, want in ((gotk, wantk), (gotv, wantv)):
+        g, w = got[pos:pos + n], want[pos:pos + n]
+        if dtype == "f32":
+            assert gh.rel_max(g, w) <= F32_TOL
+        else:
+            assert gh.max_abs(g, w) <= OUT_ABS and gh.rel_fro(g, w) <= OUT_FRO
+
+
+@pytest.mark.parametrize("explicit", [False, True])
+def test_fp32_draft_step_rotates_the_queries(explicit):
+    M, rows, H, G, D, d = 6, 50, 4, 2, 256, 64
+    cfg = synth.CONFIGS["c1"].with_(batch=1, seq_q=M, seq_kv=rows, hidden=D, n_q_heads=H, n_kv_heads=G, head_dim=d, seed_base=920)
+    inp = synth.make_inputs(cfg, with_dy=False)
+    kc, vc = orc.kv_append(np.zeros((rows, G, d)), np.zeros((rows, G, d)), 0, inp["xkv"][0], inp["wk"], inp["wv"],
+                           n_kv_heads=G, rope=dict(base=10000.0, k_pos=np.arange(rows)))
+    kc, vc = kc.astype(np.float32), vc.astype(np.float32)
+    q_pos = np.array([50, 50, 51, 51, 52, 53]) if explicit else np.full(M, rows)
+    pos_dev = torch.tensor(q_pos, dtype=torch.int32, device=gh.DEV) if explicit else None
+    ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G, rope=dict(base=10000.0, q_pos=q_pos))
+    y, lse = gh.run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"],
+                          desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE, rope_positions=pos_dev))
+    assert gh.rel_max(y, ref["y"]) <= F32_TOL and gh.max_abs(lse, ref["lse"]) <= 1e-5 * max(1.0, np.abs(ref["lse"]).max())
+
+
+def test_rope_argument_errors():
+    a = torch.zeros(1 << 14, device=gh.DEV)
+    pos = torch.zeros(16, dtype=torch.int32, device=gh.DEV)
+    mk = lambda **kw: bx.make_desc(**dict(dict(batch=1, seq_q=16, seq_kv=16, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=64,
+                                               block_size=4, io_dtype=bx.BEAGLE_F32, flags=bx.BEAGLE_FLAG_ROPE), **kw))
+    assert bx.beagle_xattn_workspace_bytes(mk(rope_positions=pos), bx.BEAGLE_WS_BWD) == 0      # training: position = index
+    assert bx.beagle_xattn_workspace_bytes(mk(rope_base=-1.0), bx.BEAGLE_WS_BWD) == 0
+    assert bx.beagle_xattn_workspace_bytes(mk(rope_positions=pos), bx.BEAGLE_WS_DRAFT) > 0
+    # the bf16 draft step has no rotary path
+    cfg = synth.CONFIGS["c4"].with_(seq_q=2, seq_kv=64, hidden=512, n_q_heads=4, n_kv_heads=4)
+    z = np.zeros
+    st = gh.run_draft(cfg, z((2, 512), np.float32), z((64, 4, 128), np.float32), z((64, 4, 128), np.float32),
+                      z((512, 512), np.float32), z((512, 512), np.float32), desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE), check=False)
+    assert st == bx.BEAGLE_ERR_UNSUPPORTED
