@@ -44,7 +44,6 @@
  *   rotated.  q_save / k_save and the decode cache hold the ROTATED rows; the
  *   backward rotates dQ, dK back before the projections' gradients.  In the
  *   simulation step a predicted state stands at its own sequence position.
- *   Not available for the bf16 draft step (BEAGLE_ERR_UNSUPPORTED).
  *
  * Supported shapes
  *   BEAGLE_F32 : any d <= 128 with d % 4 == 0; D, H*d, G*d multiples of 4.

@@ -581,13 +581,13 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
-  if (d.bf16 && d.rope) return BEAGLE_ERR_UNSUPPORTED;
   if (d.bf16) {
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
     a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.wq = wq; a.wo = wo; a.y = y; a.lse = lse; a.ws = workspace;
     a.tree = tree; a.n_true = n_true; a.tree_words = words;
+    a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     launch_decode_bf16(a, s);
     return hip_status();
   }

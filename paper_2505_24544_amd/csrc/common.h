@@ -145,6 +145,8 @@ struct DecodeArgs {
   void* ws;
   // draft tree (tree == nullptr: every cache row is visible to every query)
   const uint32_t* tree; int32_t n_true, tree_words;
+  // rotary embedding of the queries (rope != 0): positions rope_pos[m] (device) or all at L
+  int32_t rope; float rope_base; const int32_t* rope_pos;
 };
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);

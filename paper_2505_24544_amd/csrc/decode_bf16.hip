@@ -228,7 +228,20 @@ struct DecAttnArgs {
   // draft tree (nullptr: all rows visible): rows >= n_true are visible to query m iff bit (row - n_true) of
   // tree[m * tree_words ...] is set
   const uint32_t* tree; int n_true, tree_words;
+  // rotary embedding of the queries: (cos, sin) of channel pair c of query m at rope_tab[m * 64 + c], or nullptr
+  const float2* rope_tab;
 };
+
+// (cos, sin) of the rotary angles of M queries, evaluated in double: query m stands at pos[m] (or pos0), channel
+// pair c < 64 turns by position * base^(-2c/128).
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* pos, int pos0, int M, float base, float2* tab) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= M * 64) return;
+  const int m = i >> 6, c = i & 63;
+  double sn, cs;
+  sincos((double)(pos ? pos[m] : pos0) * exp2(-2.0 * c / 128.0 * log2((double)base)), &sn, &cs);
+  tab[i] = make_float2((float)cs, (float)sn);
+}
 
 // One workgroup per (head, key range, block of 32 queries): grid (H, R, ceil(M / 32)).
 __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
@@ -274,6 +287,17 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
           __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
       const int oob = 0x7fffff00;
       float4 acc[4] = {zero4, zero4, zero4, zero4};
+      // rotary embedding: this thread's four channels of query m pair with the four that lane ^ 16 holds
+      // (float4 slot c4 ^ 16 of the same query); their (cos, sin) are requested first, ahead of the slices
+      float4 cs[4][2];
+      if (a.rope_tab) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int idx = tid + 64 * qwaves * i, m = min(idx >> 5, mrows - 1), c4 = idx & 15;
+          const float4* tp = (const float4*)(a.rope_tab + (int64_t)(m0 + m) * 64 + 4 * c4);
+          cs[i][0] = tp[0]; cs[i][1] = tp[1];
+        }
+      }
       for (int k0 = 0; k0 < a.KSq; k0 += 8) {                             // one pass for up to 8 slices
         u32x4_t t[4][8];
 #pragma unroll
@@ -292,6 +316,22 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
             acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
             acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
           }
+      }
+      if (a.rope_tab) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool upper = (tid & 16) != 0;               // channels 64 .. 127: x2 of the pair
+          const float4 own = acc[i];
+          float4 oth;
+          oth.x = __shfl_xor(own.x, 16, 64); oth.y = __shfl_xor(own.y, 16, 64);
+          oth.z = __shfl_xor(own.z, 16, 64); oth.w = __shfl_xor(own.w, 16, 64);
+          // x1' = x1 cos - x2 sin ; x2' = x2 cos + x1 sin  (cs holds (cos, sin) of pairs 4 c4 .. 4 c4 + 3)
+          const float sg = upper ? 1.f : -1.f;
+          acc[i].x = own.x * cs[i][0].x + sg * oth.x * cs[i][0].y;
+          acc[i].y = own.y * cs[i][0].z + sg * oth.y * cs[i][0].w;
+          acc[i].z = own.z * cs[i][1].x + sg * oth.z * cs[i][1].y;
+          acc[i].w = own.w * cs[i][1].z + sg * oth.w * cs[i][1].w;
+        }
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -513,7 +553,7 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
 namespace {
 struct DecLayout {
   int KSq, KSo, R, range, Mpad;
-  size_t qpart, opart, mlpart, o, ypart, total;
+  size_t qpart, opart, mlpart, o, ypart, ropetab, total;
 };
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 DecLayout dec_layout(int M, int L, int H, int d, int D) {
@@ -536,6 +576,7 @@ DecLayout dec_layout(int M, int L, int H, int d, int D) {
   w.mlpart = o; o += up256((size_t)H * w.R * w.Mpad * 2 * 4);
   w.o = o; o += up256((size_t)Mp * HDt * 2);
   w.ypart = o; o += up256((size_t)w.KSo * Mp * D * 4);
+  w.ropetab = o; o += up256((size_t)M * 64 * sizeof(float2));
   w.total = o;
   return w;
 }
@@ -555,6 +596,12 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
   float* mlpart = (float*)(base + w.mlpart);
   bf16_t* o = (bf16_t*)(base + w.o);
   float* ypart = (float*)(base + w.ypart);
+  float2* ropetab = a.rope ? (float2*)(base + w.ropetab) : nullptr;
+  if (a.rope) {
+    ProfScope ps("draft_rope_table", s);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((a.M * 64 + 255) / 256), dim3(256), 0, s, a.rope_pos, a.L, a.M,
+                       a.rope_base, ropetab);
+  }
   for (int m0 = 0; m0 < a.M; m0 += MAXM) {
     const int Mp = a.M - m0 < MAXM ? a.M - m0 : MAXM;
     const bf16_t* x = (const bf16_t*)a.x + (int64_t)m0 * a.D;
@@ -570,6 +617,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       t.M = Mp; t.Mpad = w.Mpad; t.L = a.L; t.H = a.H; t.G = a.G; t.R = w.R; t.range = w.range;
       t.scale = a.scale;
       t.tree = a.tree ? a.tree + (int64_t)m0 * a.tree_words : nullptr; t.n_true = a.n_true; t.tree_words = a.tree_words;
+      t.rope_tab = ropetab ? ropetab + (int64_t)m0 * 64 : nullptr;
       ProfScope ps("draft_attn", s);
       hipLaunchKernelGGL(decode_attn_kernel, dim3(a.H, w.R, (Mp + 31) / 32), dim3(256), 0, s, t);
     }

@@ -146,9 +146,29 @@ def test_rope_argument_errors():
     assert bx.beagle_xattn_workspace_bytes(mk(rope_positions=pos), bx.BEAGLE_WS_BWD) == 0      # training: position = index
     assert bx.beagle_xattn_workspace_bytes(mk(rope_base=-1.0), bx.BEAGLE_WS_BWD) == 0
     assert bx.beagle_xattn_workspace_bytes(mk(rope_positions=pos), bx.BEAGLE_WS_DRAFT) > 0
-    # the bf16 draft step has no rotary path
-    cfg = synth.CONFIGS["c4"].with_(seq_q=2, seq_kv=64, hidden=512, n_q_heads=4, n_kv_heads=4)
-    z = np.zeros
-    st = gh.run_draft(cfg, z((2, 512), np.float32), z((64, 4, 128), np.float32), z((64, 4, 128), np.float32),
-                      z((512, 512), np.float32), z((512, 512), np.float32), desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE), check=False)
-    assert st == bx.BEAGLE_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("M,rows,H,G,D,explicit", [
+    (1, 300, 4, 4, 512, False), (10, 300, 4, 4, 512, True), (8, 4096, 32, 32, 4096, True), (40, 200, 8, 2, 512, True),
+    (70, 130, 4, 4, 512, True),
+])
+def test_bf16_draft_step_rotates_the_queries(M, rows, H, G, D, explicit):
+    d = 128
+    cfg = synth.CONFIGS["c4"].with_(batch=1, seq_q=M, seq_kv=rows, hidden=D, n_q_heads=H, n_kv_heads=G, head_dim=d, seed_base=930 + M)
+    inp = synth.make_inputs(cfg, with_dy=False)
+    kc, vc = orc.kv_append(np.zeros((rows, G, d)), np.zeros((rows, G, d)), 0, inp["xkv"][0], inp["wk"], inp["wv"],
+                           n_kv_heads=G, rope=dict(base=10000.0, k_pos=np.arange(rows)))
+    kc, vc = synth.round_to_bf16(kc.astype(np.float32)), synth.round_to_bf16(vc.astype(np.float32))
+    q_pos = rows + np.arange(M) // 10 if explicit else np.full(M, rows)          # ten queries per tree depth
+    pos_dev = torch.tensor(q_pos, dtype=torch.int32, device=gh.DEV) if explicit else None
+    ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G, rope=dict(base=10000.0, q_pos=q_pos))
+    y, lse = gh.run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"],
+                          desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE, rope_positions=pos_dev))
+    assert np.isfinite(y).all()
+    assert gh.max_abs(y, ref["y"]) <= OUT_ABS and gh.rel_fro(y, ref["y"]) <= OUT_FRO, gh.rel_fro(y, ref["y"])
+    assert gh.max_abs(lse, ref["lse"]) <= 1e-3, gh.max_abs(lse, ref["lse"])
+    # and the plain step is untouched by the new code path (bitwise, two runs with and without a descriptor field set)
+    y0, l0 = gh.run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"])
+    y1, l1 = gh.run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], desc=gh.desc_of(cfg, 0, rope_base=123.0))
+    assert np.array_equal(y0, y1) and np.array_equal(l0, l1)
+    assert not np.allclose(y0, y, atol=1e-3)
