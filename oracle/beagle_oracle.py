@@ -309,6 +309,60 @@ def xattn_backward_sample_eps(dy, xq, xkv, wq, wk, wv, wo, *, n_q_heads, n_kv_he
         out[n] = sum(p[n] for p in parts)
     return out
 
+
+# --------------------------------------------------------------------------
+# Packed batches of sequences of different lengths (no padding rows): the
+# training inputs are conversations of unequal length.  xq is [Tq, D] with
+# sequence b in rows cu_q[b] .. cu_q[b+1]-1, xkv likewise with cu_kv.  Every
+# sequence is an independent instance of Eq. 2 under its own early-stage mask;
+# the weights are shared, so their gradients add up.  Written as that sentence.
+# --------------------------------------------------------------------------
+def _check_cu(cu, total):
+    cu = [int(v) for v in cu]
+    if len(cu) < 2 or cu[0] != 0 or cu[-1] != total or any(b <= a for a, b in zip(cu, cu[1:])):
+        raise ValueError("cu_seqlens must start at 0, end at the row count and increase (no empty sequence)")
+    return cu
+
+
+def xattn_forward_packed(xq, xkv, wq, wk, wv, wo, cu_q, cu_kv, *, n_q_heads, n_kv_heads, k, eps_list=None, scale=None,
+                         rope=None):
+    """Returns y [Tq, D], lse [H, Tq], q [Tq, H, d], k, v [Tkv, G, d], o [Tq, H, d].  eps_list: one offset per
+    sequence (default 0).  rope: positions restart at 0 in every sequence."""
+    xq, xkv = np.asarray(xq, F64), np.asarray(xkv, F64)
+    cu_q, cu_kv = _check_cu(cu_q, xq.shape[0]), _check_cu(cu_kv, xkv.shape[0])
+    if len(cu_q) != len(cu_kv):
+        raise ValueError("as many query sequences as key sequences")
+    B = len(cu_q) - 1
+    parts = []
+    for b in range(B):
+        a, e = xq[None, cu_q[b]:cu_q[b + 1]], xkv[None, cu_kv[b]:cu_kv[b + 1]]
+        eps = 0 if eps_list is None else int(eps_list[b])
+        parts.append(xattn_forward(a, e, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                                   mask=dense_mask(a.shape[1], e.shape[1], k, eps), scale=scale, rope=rope))
+    out = {n: np.concatenate([p[n][0] for p in parts], axis=0) for n in ("y", "q", "k", "v", "o")}
+    out["lse"] = np.concatenate([p["lse"][0] for p in parts], axis=1)
+    return out
+
+
+def xattn_backward_packed(dy, xq, xkv, wq, wk, wv, wo, cu_q, cu_kv, *, n_q_heads, n_kv_heads, k, eps_list=None,
+                          scale=None, rope=None):
+    """Gradients for packed sequences: dxq [Tq, D], dxkv [Tkv, D], weight gradients summed over the sequences."""
+    dy, xq, xkv = np.asarray(dy, F64), np.asarray(xq, F64), np.asarray(xkv, F64)
+    cu_q, cu_kv = _check_cu(cu_q, xq.shape[0]), _check_cu(cu_kv, xkv.shape[0])
+    B = len(cu_q) - 1
+    parts = []
+    for b in range(B):
+        sq, sk = slice(cu_q[b], cu_q[b + 1]), slice(cu_kv[b], cu_kv[b + 1])
+        eps = 0 if eps_list is None else int(eps_list[b])
+        parts.append(xattn_backward(dy[None, sq], xq[None, sq], xkv[None, sk], wq, wk, wv, wo, n_q_heads=n_q_heads,
+                                    n_kv_heads=n_kv_heads, mask=dense_mask(sq.stop - sq.start, sk.stop - sk.start, k, eps),
+                                    scale=scale, rope=rope))
+    out = {n: np.concatenate([p[n][0] for p in parts], axis=0) for n in ("dxq", "dxkv", "y", "o", "q", "k", "v")}
+    out["lse"] = np.concatenate([p["lse"][0] for p in parts], axis=1)
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        out[n] = sum(p[n] for p in parts)
+    return out
+
 # --------------------------------------------------------------------------
 # Late-stage training: simulated inference steps (section 4.2, second half, and
 # the caption of the mask figure; the figure itself is not available)
