@@ -106,6 +106,22 @@ typedef struct {
                             beagle_xattn_tile_map helpers return
                             BEAGLE_ERR_UNSUPPORTED when it is set (inspect one
                             entry at a time through block_offset).              */
+  /* Packed batches of sequences of different lengths (training entry points;
+   * NULL / 0 for the ordinary [B,S,..] layout; BEAGLE_ERR_UNSUPPORTED for the
+   * draft-step entry points).  cu_seqlens_q / cu_seqlens_kv are DEVICE pointers
+   * to B + 1 increasing int32 values, first 0, last total_q / total_kv: entry
+   * b owns query rows cu_seqlens_q[b] .. cu_seqlens_q[b+1]-1 of the packed
+   * [total_q, ..] tensors and key rows likewise.  seq_q / seq_kv are then the
+   * LONGEST lengths (every entry holds between 1 and seq_q, seq_kv rows); masks
+   * and positions restart in every entry.  Shapes: replace [B,S,..] by
+   * [total_q,..] and [B,L,..] by [total_kv,..]; lse (and the workspace's delta)
+   * become [H,total_q].  The arrays cannot be checked on the host: offsets
+   * that do not describe rows inside the packed tensors are clamped, which
+   * gives wrong results but no access outside the buffers.  The simulation
+   * entry points need cu_seqlens_q == cu_seqlens_kv.                          */
+  const int32_t* cu_seqlens_q;
+  const int32_t* cu_seqlens_kv;
+  int32_t total_q, total_kv;
   float rope_base;       /* BEAGLE_FLAG_ROPE: frequency base; 0 selects 10000   */
   const int32_t* rope_positions; /* BEAGLE_FLAG_ROPE, decode side only (DEVICE pointer
                             or NULL): draft step -- the sequence positions of its

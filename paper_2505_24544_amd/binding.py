@@ -49,17 +49,19 @@ class beagle_xattn_desc(C.Structure):
         ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block_size", C.c_int32), ("block_offset", C.c_int32), ("io_dtype", C.c_int32),
         ("softmax_scale", C.c_float), ("flags", C.c_uint32), ("block_offsets", C.c_void_p),
+        ("cu_seqlens_q", C.c_void_p), ("cu_seqlens_kv", C.c_void_p), ("total_q", C.c_int32), ("total_kv", C.c_int32),
         ("rope_base", C.c_float), ("rope_positions", C.c_void_p),
     ]
 
 
 def make_desc(*, batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads, head_dim, block_size=1,
               block_offset=0, io_dtype=BEAGLE_BF16, softmax_scale=0.0, flags=0,
-              block_offsets=None, rope_base=0.0, rope_positions=None) -> beagle_xattn_desc:
+              block_offsets=None, rope_base=0.0, rope_positions=None, cu_seqlens_q=None, cu_seqlens_kv=None,
+              total_q=0, total_kv=0) -> beagle_xattn_desc:
     """block_offsets: None, or an int32 device tensor / address of B per-entry offsets (kept alive by the caller)."""
     return beagle_xattn_desc(C.sizeof(beagle_xattn_desc), batch, seq_q, seq_kv, hidden, n_q_heads, n_kv_heads,
                              head_dim, block_size, block_offset, io_dtype, softmax_scale, flags, _ptr(block_offsets),
-                             rope_base, _ptr(rope_positions))
+                             _ptr(cu_seqlens_q), _ptr(cu_seqlens_kv), total_q, total_kv, rope_base, _ptr(rope_positions))
 
 
 _VP = C.c_void_p

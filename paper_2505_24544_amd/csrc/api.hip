@@ -24,6 +24,8 @@ struct Dims {
   MaskParams mask;
   const int32_t* eps_b;   // per-entry window offsets (device) or null
   bool rope; float rope_base; const int32_t* rope_pos;
+  int64_t Tq, Tk;          // query / key rows in total: B*S, B*L, or the packed row counts
+  const int32_t* cu_q; const int32_t* cu_kv;   // packed batches (device, B+1 entries each) or null
 };
 
 beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
@@ -66,6 +68,15 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
   d.mask.all_visible = draft ? 1 : 0;
   if (c->block_offsets && (((uintptr_t)c->block_offsets) & 3u)) return BEAGLE_ERR_ALIGN;
   d.eps_b = draft ? nullptr : c->block_offsets;
+  d.Tq = d.B * d.S; d.Tk = d.B * d.L; d.cu_q = d.cu_kv = nullptr;
+  if (c->cu_seqlens_q || c->cu_seqlens_kv) {
+    if (draft) return BEAGLE_ERR_UNSUPPORTED;
+    if (!c->cu_seqlens_q || !c->cu_seqlens_kv) return BEAGLE_ERR_NULL;
+    if ((((uintptr_t)c->cu_seqlens_q) | ((uintptr_t)c->cu_seqlens_kv)) & 3u) return BEAGLE_ERR_ALIGN;
+    // every entry holds between 1 and S (L) rows
+    if (c->total_q < d.B || c->total_q > d.B * d.S || c->total_kv < d.B || c->total_kv > d.B * d.L) return BEAGLE_ERR_SHAPE;
+    d.Tq = c->total_q; d.Tk = c->total_kv; d.cu_q = c->cu_seqlens_q; d.cu_kv = c->cu_seqlens_kv;
+  }
   d.rope = (c->flags & BEAGLE_FLAG_ROPE) != 0;
   d.rope_base = 10000.f; d.rope_pos = nullptr;
   if (d.rope) {
@@ -85,10 +96,10 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
 struct BwdWs { size_t dO, dQ, dK, dV, delta, attn, total; };
 BwdWs bwd_layout(const Dims& d) {
   BwdWs w; size_t o = 0;
-  w.dO = o; o += align_up((size_t)(d.B * d.S * d.HD) * d.esz);
-  w.dQ = o; o += align_up((size_t)(d.B * d.S * d.HD) * d.esz);
-  w.dK = o; o += align_up((size_t)(d.B * d.L * d.GD) * d.esz);
-  w.dV = o; o += align_up((size_t)(d.B * d.L * d.GD) * d.esz);
+  w.dO = o; o += align_up((size_t)(d.Tq * d.HD) * d.esz);
+  w.dQ = o; o += align_up((size_t)(d.Tq * d.HD) * d.esz);
+  w.dK = o; o += align_up((size_t)(d.Tk * d.GD) * d.esz);
+  w.dV = o; o += align_up((size_t)(d.Tk * d.GD) * d.esz);
   w.delta = o; o += align_up((size_t)(d.B * d.H * d.S) * sizeof(float));
   w.attn = o;
   w.total = o;
@@ -99,6 +110,7 @@ AttnArgs attn_args(const Dims& d) {
   AttnArgs a; memset(&a, 0, sizeof(a));
   a.B = (int32_t)d.B; a.S = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G;
   a.d = (int32_t)d.d; a.scale = d.scale; a.mask = d.mask; a.eps_b = d.eps_b;
+  a.cu_q = d.cu_q; a.cu_kv = d.cu_kv; a.Tq = (int32_t)d.Tq; a.Tk = (int32_t)d.Tk;
   return a;
 }
 
@@ -132,11 +144,14 @@ beagle_status hip_status() { return hipGetLastError() == hipSuccess ? BEAGLE_OK 
 
 RopeArgs rope_args(const Dims& d, bool inverse) {
   RopeArgs r; memset(&r, 0, sizeof(r));
+  r.nb = (int32_t)d.B;
   r.d = (int32_t)d.d; r.base = d.rope_base; r.inverse = inverse ? 1 : 0;
   return r;
 }
-void rope_add(RopeArgs& r, void* x, int64_t rows, int64_t period, int64_t heads, int32_t pos0, const int32_t* pos) {
+void rope_add(RopeArgs& r, void* x, int64_t rows, int64_t period, int64_t heads, int32_t pos0, const int32_t* pos,
+              const int32_t* cu = nullptr) {
   const int i = r.n++;
+  r.cu[i] = cu;
   r.x[i] = x; r.rows[i] = rows; r.period[i] = (int32_t)period; r.heads[i] = (int32_t)heads; r.pos0[i] = pos0; r.pos[i] = pos;
 }
 
@@ -146,14 +161,14 @@ void xattn_fwd_run(const Dims& d, const void* xq, const void* xkv, const void* w
                    const void* y_res, hipStream_t s) {
   GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
   qkv.count = 3;
-  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
-  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
-  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.Tq, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.Tk, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.Tk, d.GD, d.D);
   run_gemm(d, qkv, s, "proj_qkv");
   if (d.rope) {
     RopeArgs r = rope_args(d, false);
-    rope_add(r, q_save, d.B * d.S, d.S, d.H, 0, nullptr);
-    rope_add(r, k_save, d.B * d.L, d.L, d.G, 0, nullptr);
+    rope_add(r, q_save, d.Tq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, k_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
     launch_rope(d.bf16, r, s, "rope_qk");
   }
 
@@ -161,7 +176,7 @@ void xattn_fwd_run(const Dims& d, const void* xq, const void* xkv, const void* w
   a.q = q_save; a.k = k_save; a.v = v_save; a.o = o_save; a.lse = lse;
   if (d.bf16) launch_attn_fwd_bf16(a, s); else launch_attn_fwd_f32(a, s);
 
-  GemmArgs out = gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD);
+  GemmArgs out = gemm_nn(o_save, wo, y, d.Tq, d.D, d.HD);
   out.R = y_res; out.ldr = d.D;
   run_gemm(d, group1(out), s, "proj_out");
 }
@@ -176,7 +191,7 @@ void xattn_bwd_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, con
   const BwdWs w = bwd_layout(d);
   void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
   float* delta = (float*)(base + w.delta);
-  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
+  const int64_t Mq = d.Tq, Mk = d.Tk;
 
   // dO = dY Wo^T ; dWo = O^T dY
   run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
@@ -188,8 +203,8 @@ void xattn_bwd_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, con
   if (d.bf16) launch_attn_bwd_bf16(a, base + w.attn, s); else launch_attn_bwd_f32(a, s);
   if (d.rope) {   // dQ, dK are gradients of the rotated rows: rotate them back
     RopeArgs r = rope_args(d, true);
-    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr);
-    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr);
+    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
     launch_rope(d.bf16, r, s, "bwd_rope_qk");
   }
 
@@ -362,7 +377,7 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
       BwdWs w = bwd_layout(d);
       size_t extra = 0;
       if (d.bf16) { AttnArgs a = attn_args(d); extra = attn_bwd_bf16_ws_bytes(a); }
-      return w.total + align_up(extra) + 2 * align_up((size_t)(d.B * d.L * d.GD) * d.esz);   // + dKp, dVp
+      return w.total + align_up(extra) + 2 * align_up((size_t)(d.Tk * d.GD) * d.esz);   // + dKp, dVp
     }
     case BEAGLE_WS_APPEND:
       if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))
@@ -425,27 +440,27 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   const void* ptrs[] = {xq, xkv, xpred, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, kp_save, vp_save, o_save};
   for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
-  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
   (void)workspace; (void)workspace_bytes;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
   GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
   qkv.count = 3;
-  qkv.p[0] = gemm_nn(xq, wq, q_save, d.B * d.S, d.HD, d.D);
-  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.B * d.L, d.GD, d.D);
-  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.B * d.L, d.GD, d.D);
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.Tq, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.Tk, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.Tk, d.GD, d.D);
   run_gemm(d, qkv, s, "proj_qkv");
   GemmGroup kvp; memset(&kvp, 0, sizeof(kvp));
   kvp.count = 2;
-  kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.B * d.L, d.GD, d.D);
-  kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.B * d.L, d.GD, d.D);
+  kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.Tk, d.GD, d.D);
+  kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.Tk, d.GD, d.D);
   run_gemm(d, kvp, s, "proj_kvp");
   if (d.rope) {   // a predicted state stands at its own sequence position
     RopeArgs r = rope_args(d, false);
-    rope_add(r, q_save, d.B * d.S, d.S, d.H, 0, nullptr);
-    rope_add(r, k_save, d.B * d.L, d.L, d.G, 0, nullptr);
-    rope_add(r, kp_save, d.B * d.L, d.L, d.G, 0, nullptr);
+    rope_add(r, q_save, d.Tq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, k_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
+    rope_add(r, kp_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
     launch_rope(d.bf16, r, s, "rope_qk");
   }
 
@@ -456,7 +471,7 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   if (d.bf16) launch_attn_fwd_bf16(sa.a, s); else launch_attn_fwd_f32(sa.a, s);
   if (sim_step > 0) launch_sim_band_fwd(sa, s);
 
-  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.B * d.S, d.D, d.HD)), s, "proj_out");
+  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.Tq, d.D, d.HD)), s, "proj_out");
   return hip_status();
 }
 
@@ -466,12 +481,12 @@ beagle_status beagle_xattn_sim_save(const beagle_xattn_desc* desc, const void* h
   if (st != BEAGLE_OK) return st;
   if (!h || !xpred) return BEAGLE_ERR_NULL;
   if (!aligned16(h) || !aligned16(xpred)) return BEAGLE_ERR_ALIGN;
-  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
   if ((d.D * (int64_t)d.esz) % 16) return BEAGLE_ERR_UNSUPPORTED;
   if (sim_step >= desc->block_size) return BEAGLE_OK;      // every window is already full
   (void)hipGetLastError();
   launch_sim_save(h, xpred, (int)d.B, (int)d.L, d.D * (int64_t)d.esz, desc->block_size, desc->block_offset, d.eps_b, sim_step,
-                  (hipStream_t)hip_stream);
+                  d.cu_q, (int)d.Tq, (hipStream_t)hip_stream);
   return hip_status();
 }
 
@@ -492,7 +507,7 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   if (dxkv && !aligned16(dxkv)) return BEAGLE_ERR_ALIGN;
   if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
   if (workspace_bytes < beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM)) return BEAGLE_ERR_WORKSPACE;
-  if (sim_step < 0 || d.S != d.L) return BEAGLE_ERR_SHAPE;
+  if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
@@ -502,11 +517,11 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   float* delta = (float*)(base + w.delta);
   size_t extra = 0;
   if (d.bf16) { AttnArgs t = attn_args(d); extra = attn_bwd_bf16_ws_bytes(t); }
-  const size_t kvb = align_up((size_t)(d.B * d.L * d.GD) * d.esz);
+  const size_t kvb = align_up((size_t)(d.Tk * d.GD) * d.esz);
   void* dKp = base + w.total + align_up(extra);
   void* dVp = (char*)dKp + kvb;
   const bool wf32 = d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32);
-  const int64_t Mq = d.B * d.S, Mk = d.B * d.L;
+  const int64_t Mq = d.Tq, Mk = d.Tk;
 
   run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
   run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
@@ -522,9 +537,9 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   launch_sim_band_bwd(sa, s);
   if (d.rope) {
     RopeArgs r = rope_args(d, true);
-    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr);
-    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr);
-    rope_add(r, dKp, Mk, d.L, d.G, 0, nullptr);
+    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
+    rope_add(r, dKp, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
     launch_rope(d.bf16, r, s, "bwd_rope_qk");
   }
 
@@ -669,7 +684,7 @@ struct BlockWs { size_t dm, dw, dz, dy, dxq, dxkv, part, attn, total; };
 
 BlockWs block_bwd_layout(const Dims& d, int64_t F) {
   BlockWs w; size_t o = 0;
-  const size_t Mq = (size_t)(d.B * d.S), Mk = (size_t)(d.B * d.L);
+  const size_t Mq = (size_t)(d.Tq), Mk = (size_t)(d.Tk);
   w.dm = o; o += align_up(Mq * F * d.esz);          // dm, then du in place
   w.dw = o; o += align_up(Mq * F * d.esz);
   w.dz = o; o += align_up(Mq * d.D * d.esz);
@@ -728,7 +743,7 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
   (void)workspace; (void)workspace_bytes;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
-  const int64_t Mq = d.B * d.S, Mk = d.B * d.L, F = p->ffn;
+  const int64_t Mq = d.Tq, Mk = d.Tk, F = p->ffn;
   const int D = (int)d.D;
 
   const void* xq = e; const void* xkv = hs;
@@ -775,7 +790,7 @@ beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle
   if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_BWD)) return BEAGLE_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
-  const int64_t Mq = d.B * d.S, Mk = d.B * d.L, F = p->ffn;
+  const int64_t Mq = d.Tq, Mk = d.Tk, F = p->ffn;
   const int D = (int)d.D;
   const BlockWs w = block_bwd_layout(d, F);
   char* base = (char*)workspace;

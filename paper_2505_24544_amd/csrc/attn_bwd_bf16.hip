@@ -61,22 +61,24 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   const int qt = nqt - 1 - tpos;                  // heaviest (latest) query tiles first
   const int h = row % a.H, b = row / a.H, g = h / (a.H / a.G);
   const int q0 = qt * BQ, qw0 = q0 + wave * 32, q = qw0 + ql;
-  const bool q_ok = q < a.S;
-  const int qc = q_ok ? q : a.S - 1;
-  const int64_t qrow = (((int64_t)b * a.S + qc) * a.H + h) * HD;
+  const SeqView sv = seq_view(a, b);
+  if (q0 >= sv.S) return;                         // packed batch: this entry is shorter than the longest one
+  const bool q_ok = q < sv.S;
+  const int qc = q_ok ? q : sv.S - 1;
+  const int64_t qrow = ((sv.q0 + qc) * a.H + h) * HD;
   const bf16_t* Qg = (const bf16_t*)a.q + qrow;
   const bf16_t* Og = (const bf16_t*)a.o + qrow;
   const bf16_t* dOg = (const bf16_t*)a.dout + qrow;
   const int64_t kvs = (int64_t)a.G * HD;
-  const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
-  const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
-  const int64_t li = ((int64_t)b * a.H + h) * a.S + qc;
+  const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
+  const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
+  const int64_t li = sv.lse0 + h * sv.lse_hs + qc;
 
   const MaskParams mk = sample_mask(a, b);
   const int lim = q_ok ? row_limit(q, mk) : 0;
-  const int wg_lim = row_limit(min(q0 + BQ, a.S) - 1, mk);
-  const int wave_hi = qw0 < a.S ? row_limit(min(qw0 + 32, a.S) - 1, mk) : 0;
-  const int wave_lo = qw0 < a.S ? row_limit(qw0, mk) : 0;
+  const int wg_lim = row_limit(min(q0 + BQ, sv.S) - 1, mk);
+  const int wave_hi = qw0 < sv.S ? row_limit(min(qw0 + 32, sv.S) - 1, mk) : 0;
+  const int wave_lo = qw0 < sv.S ? row_limit(qw0, mk) : 0;
   const int ntiles = (wg_lim + BJ - 1) / BJ;
 
   bf16x8_t qf[8], dof[8];
@@ -205,21 +207,23 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int g = row % a.G, b = row / a.G;
   const int rep = a.H / a.G;
   const int j0 = jt * BJ, jw0 = j0 + wave * 32, j = jw0 + jl;
-  const bool j_ok = j < a.L;
-  const int jc = j_ok ? j : a.L - 1;
-  const int64_t kvrow = (((int64_t)b * a.L + jc) * a.G + g) * HD;
+  const SeqView sv = seq_view(a, b);
+  if (j0 >= sv.L) return;                         // packed batch: this entry is shorter than the longest one
+  const bool j_ok = j < sv.L;
+  const int jc = j_ok ? j : sv.L - 1;
+  const int64_t kvrow = ((sv.kv0 + jc) * a.G + g) * HD;
   const bf16_t* Kg = (const bf16_t*)a.k + kvrow;
   const bf16_t* Vg = (const bf16_t*)a.v + kvrow;
   const int64_t qs = (int64_t)a.H * HD;
 
   // first query that sees this lane's key / any key of the wave / every key of the wave / any of the workgroup
   const MaskParams mk = sample_mask(a, b);
-  const int fq = j_ok ? first_query_seeing(j, mk) : a.S;
-  const int wave_first = jw0 < a.L ? first_query_seeing(jw0, mk) : a.S;
-  const int wave_all = jw0 < a.L ? first_query_seeing(min(jw0 + 32, a.L) - 1, mk) : a.S;
+  const int fq = j_ok ? first_query_seeing(j, mk) : sv.S;
+  const int wave_first = jw0 < sv.L ? first_query_seeing(jw0, mk) : sv.S;
+  const int wave_all = jw0 < sv.L ? first_query_seeing(min(jw0 + 32, sv.L) - 1, mk) : sv.S;
   const int wg_first = first_query_seeing(j0, mk);
   const int qt0 = wg_first / BQ;
-  const int nqt = (a.S + BQ - 1) / BQ;
+  const int nqt = (sv.S + BQ - 1) / BQ;
   const int per_head = nqt > qt0 ? nqt - qt0 : 0;
   const int iters = per_head * rep;                 // (head, query tile) pairs, head-major
 
@@ -242,13 +246,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   // the sequence end arrive as zeros (zero Q and dO rows contribute nothing).
   int f_hh = 0, f_qt = qt0;                         // fetch cursor: head within the group, query tile
   int c_qt = qt0;                                   // compute cursor: query tile
-  const int64_t head0 = (int64_t)b * a.S * a.H + g * rep;
+  const int64_t head0 = sv.q0 * a.H + g * rep;
   const bf16_t* f_q = (const bf16_t*)a.q + head0 * HD;           // row 0 of the fetch cursor's head
   const bf16_t* f_do = (const bf16_t*)a.dout + head0 * HD;
-  const float* f_stat = (wave == 0 ? a.lse : a.delta) + ((int64_t)b * a.H + g * rep) * a.S;
+  const float* f_stat = (wave == 0 ? a.lse : a.delta) + sv.lse0 + (g * rep) * sv.lse_hs;
   auto fetch = [&](bf16_t* st, float* stat) {
     const int q0 = f_qt * BQ;
-    const int rows = f_hh < rep ? a.S : 0;          // past the last pair: fetch zeros
+    const int rows = f_hh < rep ? sv.S : 0;          // past the last pair: fetch zeros
     load_rows<BQ>(st, rows_rsrc(f_q, rows, qs), qs, q0, tid);
     load_rows<BQ>(st + TILE, rows_rsrc(f_do, rows, qs), qs, q0, tid);
     if (wave < 2) {
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     }
     if (++f_qt == nqt) {
       f_qt = qt0;
-      if (++f_hh < rep) { f_q += HD; f_do += HD; f_stat += a.S; }
+      if (++f_hh < rep) { f_q += HD; f_do += HD; f_stat += sv.lse_hs; }
     }
   };
 

@@ -47,23 +47,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   const int h = row % a.H, b = row / a.H;
   const int g = h / (a.H / a.G);
   const int q0 = qt * BQ;
+  const SeqView sv = seq_view(a, b);
+  if (q0 >= sv.S) return;                         // packed batch: this entry is shorter than the longest one
   const int qw0 = q0 + wave * 32;                 // first query of this wave
   const int q = qw0 + ql;                         // this lane's query
-  const bool q_ok = q < a.S;
-  const int qc = q_ok ? q : a.S - 1;
+  const bool q_ok = q < sv.S;
+  const int qc = q_ok ? q : sv.S - 1;
 
-  const bf16_t* Qg = (const bf16_t*)a.q + (((int64_t)b * a.S + qc) * a.H + h) * HD;
+  const bf16_t* Qg = (const bf16_t*)a.q + ((sv.q0 + qc) * a.H + h) * HD;
   const int64_t kvs = (int64_t)a.G * HD;
-  const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
-  const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + ((int64_t)b * a.L * a.G + g) * HD, a.L, kvs);
+  const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
+  const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
 
   const MaskParams mk = sample_mask(a, b);
   const int lim = q_ok ? row_limit(q, mk) : 0;                     // keys visible to this lane's query
-  const int q_last = min(q0 + BQ, a.S) - 1;
+  const int q_last = min(q0 + BQ, sv.S) - 1;
   const int wg_lim = row_limit(q_last, mk);                    // limits never decrease with p
-  const int w_last = min(qw0 + 32, a.S) - 1;
-  const int wave_hi = qw0 < a.S ? row_limit(w_last, mk) : 0;   // largest limit in this wave
-  const int wave_lo = qw0 < a.S ? row_limit(qw0, mk) : 0;      // smallest
+  const int w_last = min(qw0 + 32, sv.S) - 1;
+  const int wave_hi = qw0 < sv.S ? row_limit(w_last, mk) : 0;   // largest limit in this wave
+  const int wave_lo = qw0 < sv.S ? row_limit(qw0, mk) : 0;      // smallest
   const int ntiles = (wg_lim + BJ - 1) / BJ;
 
   // Q fragments: B operand, lane holds Q[q][16*s + 8*hf .. +7]
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   // ---- normalise and store: register e of block cb is channel 32 cb + 8 (e/4) + 4 hf + e%4
   if (q_ok) {
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    bf16_t* Og = (bf16_t*)a.o + (((int64_t)b * a.S + q) * a.H + h) * HD;
+    bf16_t* Og = (bf16_t*)a.o + ((sv.q0 + q) * a.H + h) * HD;
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
         *(uint2*)(Og + 32 * cb + 8 * qd + 4 * hf) = v;
       }
     if (hf == 0)
-      a.lse[((int64_t)b * a.H + h) * a.S + q] = l > 0.f ? m * a.scale + __logf(l) : -INFINITY;
+      a.lse[sv.lse0 + h * sv.lse_hs + q] = l > 0.f ? m * a.scale + __logf(l) : -INFINITY;
   }
 }
 

@@ -81,6 +81,8 @@ struct RopeArgs {
   int64_t rows[3];
   int32_t period[3], heads[3], pos0[3];
   const int32_t* pos[3];        // device, or null
+  const int32_t* cu[3];         // packed batch: row r of tensor t is row r - cu[b] of the entry b that holds it
+  int32_t nb;                   // entries (cu has nb + 1 values)
   int32_t d;                    // head width, d % 4 == 0, d <= 128
   float base;
   int32_t inverse;              // rotate by -angle (gradients)
@@ -93,6 +95,10 @@ struct AttnArgs {
   float scale;
   MaskParams mask;
   const int32_t* eps_b;                           // per batch entry window offsets (device, [B]) or null
+  // packed batches (cu_q != null): entry b owns query rows cu_q[b] .. cu_q[b+1]-1 of the Tq packed rows and key
+  // rows cu_kv[b] .. cu_kv[b+1]-1 of the Tk; S and L are then the longest lengths (they size the grids)
+  const int32_t* cu_q; const int32_t* cu_kv;
+  int32_t Tq, Tk;
   const void* q; const void* k; const void* v;   // [B,S,H,d], [B,L,G,d] x2
   void* o; float* lse;                            // [B,S,H,d], [B,H,S]
   // backward only
@@ -103,9 +109,30 @@ struct AttnArgs {
   const uint32_t* tree; int32_t n_true, tree_words;
 };
 
-// The mask of batch entry b: the shared parameters, with the entry's own window offset if offsets were given.
+// Where batch entry b lives: its lengths, its first query / key row, the offset of its LSE / delta entry (head 0,
+// query 0) and the distance between heads there.  Batched layout: rows b*S .., lse [B,H,S].  Packed layout: rows
+// from cu_q / cu_kv, lse [H,Tq].  Offsets that do not describe rows inside the packed tensors are clamped, so
+// that a wrong cu array gives wrong numbers but never an access outside the buffers.
+struct SeqView { int32_t S, L; int64_t q0, kv0, lse0, lse_hs; };
+__device__ __forceinline__ SeqView seq_view(const AttnArgs& a, int b) {
+  SeqView v;
+  if (!a.cu_q) {
+    v.S = a.S; v.L = a.L; v.q0 = (int64_t)b * a.S; v.kv0 = (int64_t)b * a.L;
+    v.lse0 = (int64_t)b * a.H * a.S; v.lse_hs = a.S;
+    return v;
+  }
+  const int32_t q0 = min(max(a.cu_q[b], 0), a.Tq), k0 = min(max(a.cu_kv[b], 0), a.Tk);
+  v.S = min(max(a.cu_q[b + 1] - q0, 0), min(a.S, a.Tq - q0));
+  v.L = min(max(a.cu_kv[b + 1] - k0, 0), min(a.L, a.Tk - k0));
+  v.q0 = q0; v.kv0 = k0; v.lse0 = q0; v.lse_hs = a.Tq;
+  return v;
+}
+
+// The mask of batch entry b: the shared parameters, with the entry's own window offset if offsets were given
+// and its own key count in a packed batch.
 __device__ __forceinline__ MaskParams sample_mask(const AttnArgs& a, int b) {
   MaskParams m = a.mask;
+  if (a.cu_q) m.seq_kv = seq_view(a, b).L;
   if (a.eps_b) {
     const int32_t e = a.eps_b[b] % m.k;
     m.eps = e < 0 ? e + m.k : e;
@@ -124,7 +151,7 @@ struct SimArgs {
 void launch_sim_band_fwd(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd(const SimArgs& s, hipStream_t st);
 void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, const int32_t* eps_b,
-                     int t, hipStream_t st);
+                     int t, const int32_t* cu, int total, hipStream_t st);
 // streaming variants for bf16 storage (head width 128), chosen by the two launchers above
 void launch_sim_band_fwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd_bf16(const SimArgs& s, hipStream_t st);

@@ -36,7 +36,16 @@ __global__ __launch_bounds__(256) void rope_kernel(RopeArgs r) {
   const int c = 2 * (threadIdx.x % 32), hg = threadIdx.x / 32;   // first channel of this thread, head group
   if (c >= half) return;
   (void)lanes;
-  const int idx = (int)(row % r.period[seg]);
+  int idx = (int)(row % r.period[seg]);
+  if (r.cu[seg]) {                               // packed batch: the entry whose rows include this one
+    const int32_t* cu = r.cu[seg];
+    int lo = 0, hi = r.nb;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (cu[mid] <= row) lo = mid; else hi = mid;
+    }
+    idx = (int)(row - cu[lo]);
+  }
   const int pos = r.pos[seg] ? r.pos[seg][idx] : r.pos0[seg] + idx;
   double s0, c0, s1, c1;
   const double l2b = log2((double)r.base);

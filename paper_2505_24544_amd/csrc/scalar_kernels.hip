@@ -140,13 +140,15 @@ __global__ __launch_bounds__(64) void attn_fwd_scalar_kernel(AttnArgs a) {
   __shared__ float qs[128];
   __shared__ float pch[64];
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (p >= sv.S) return;                               // packed batch: a shorter entry
   const int d = a.d, g = h / (a.H / a.G);
-  const T* Q = (const T*)a.q + (((int64_t)b * a.S + p) * a.H + h) * d;
-  const T* K = (const T*)a.k + ((int64_t)b * a.L * a.G + g) * d;
-  const T* V = (const T*)a.v + ((int64_t)b * a.L * a.G + g) * d;
+  const T* Q = (const T*)a.q + ((sv.q0 + p) * a.H + h) * d;
+  const T* K = (const T*)a.k + (sv.kv0 * a.G + g) * d;
+  const T* V = (const T*)a.v + (sv.kv0 * a.G + g) * d;
   const int64_t kvs = (int64_t)a.G * d;
-  T* O = (T*)a.o + (((int64_t)b * a.S + p) * a.H + h) * d;
-  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  T* O = (T*)a.o + ((sv.q0 + p) * a.H + h) * d;
+  const int64_t li = sv.lse0 + h * sv.lse_hs + p;
   const int n = row_limit(p, sample_mask(a, b));
   for (int c = lane; c < d; c += 64) qs[c] = Io<T>::ld(Q + c);
   __syncthreads();
@@ -206,16 +208,18 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_scalar_kernel(AttnArgs a) {
   __shared__ float dos[128];
   __shared__ float dsch[64];
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (p >= sv.S) return;                               // packed batch: a shorter entry
   const int d = a.d, g = h / (a.H / a.G);
-  const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * d;
+  const int64_t row = ((sv.q0 + p) * a.H + h) * d;
   const T* Q = (const T*)a.q + row;
   const T* O = (const T*)a.o + row;
   const T* dO = (const T*)a.dout + row;
   T* dQ = (T*)a.dq + row;
-  const T* K = (const T*)a.k + ((int64_t)b * a.L * a.G + g) * d;
-  const T* V = (const T*)a.v + ((int64_t)b * a.L * a.G + g) * d;
+  const T* K = (const T*)a.k + (sv.kv0 * a.G + g) * d;
+  const T* V = (const T*)a.v + (sv.kv0 * a.G + g) * d;
   const int64_t kvs = (int64_t)a.G * d;
-  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  const int64_t li = sv.lse0 + h * sv.lse_hs + p;
   const int n = row_limit(p, sample_mask(a, b));
   float part = 0.f;
   for (int c = lane; c < d; c += 64) {
@@ -261,8 +265,10 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_scalar_kernel(AttnArgs a) {
   __shared__ float pch[64];
   __shared__ float dsch[64];
   const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (j >= sv.L) return;                               // packed batch: a shorter entry
   const int d = a.d, rep = a.H / a.G;
-  const int64_t kvrow = (((int64_t)b * a.L + j) * a.G + g) * d;
+  const int64_t kvrow = ((sv.kv0 + j) * a.G + g) * d;
   const T* K = (const T*)a.k + kvrow;
   const T* V = (const T*)a.v + kvrow;
   T* dK = (T*)a.dk + kvrow;
@@ -274,21 +280,21 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_scalar_kernel(AttnArgs a) {
   float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
   for (int hh = 0; hh < rep; ++hh) {
     const int h = g * rep + hh;
-    const T* Q = (const T*)a.q + ((int64_t)b * a.S * a.H + h) * d;
-    const T* dO = (const T*)a.dout + ((int64_t)b * a.S * a.H + h) * d;
-    const float* lse = a.lse + ((int64_t)b * a.H + h) * a.S;
-    const float* dl = a.delta + ((int64_t)b * a.H + h) * a.S;
-    for (int p0 = pstart; p0 < a.S; p0 += 64) {
+    const T* Q = (const T*)a.q + (sv.q0 * a.H + h) * d;
+    const T* dO = (const T*)a.dout + (sv.q0 * a.H + h) * d;
+    const float* lse = a.lse + sv.lse0 + h * sv.lse_hs;
+    const float* dl = a.delta + sv.lse0 + h * sv.lse_hs;
+    for (int p0 = pstart; p0 < sv.S; p0 += 64) {
       int p = p0 + lane;
       float pj = 0.f, ds = 0.f;
-      if (p < a.S && j < row_limit(p, sample_mask(a, b))) {
+      if (p < sv.S && j < row_limit(p, sample_mask(a, b))) {
         pj = expf(a.scale * dot_row(ks, Q + p * qst, d) - lse[p]);
         float dp = dot_row(vs, dO + p * qst, d);
         ds = pj * (dp - dl[p]);
       }
       pch[lane] = pj; dsch[lane] = ds;
       __syncthreads();
-      int cnt = min(64, a.S - p0);
+      int cnt = min(64, sv.S - p0);
       for (int pp = 0; pp < cnt; ++pp) {
         const T* qr = Q + (int64_t)(p0 + pp) * qst;
         const T* dr = dO + (int64_t)(p0 + pp) * qst;
@@ -337,16 +343,18 @@ template <typename T>
 __global__ __launch_bounds__(64) void sim_band_fwd_kernel(SimArgs s) {
   const AttnArgs& a = s.a;
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (p >= sv.S) return;                               // packed batch: a shorter entry
   int lo, hi;
-  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, sv.L, lo, hi);
   if (hi <= lo) return;
   const int d = a.d, g = h / (a.H / a.G);
   const int64_t kvs = (int64_t)a.G * d;
-  const T* Q = (const T*)a.q + (((int64_t)b * a.S + p) * a.H + h) * d;
-  T* O = (T*)a.o + (((int64_t)b * a.S + p) * a.H + h) * d;
-  const T* Kp = (const T*)s.kp + ((int64_t)b * a.L * a.G + g) * d;
-  const T* Vp = (const T*)s.vp + ((int64_t)b * a.L * a.G + g) * d;
-  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  const T* Q = (const T*)a.q + ((sv.q0 + p) * a.H + h) * d;
+  T* O = (T*)a.o + ((sv.q0 + p) * a.H + h) * d;
+  const T* Kp = (const T*)s.kp + (sv.kv0 * a.G + g) * d;
+  const T* Vp = (const T*)s.vp + (sv.kv0 * a.G + g) * d;
+  const int64_t li = sv.lse0 + h * sv.lse_hs + p;
   const bool c0 = lane < d, c1 = lane + 64 < d;
   const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
   float m = a.lse[li];                                   // weight of the true-key part: exp(m) * 1
@@ -373,18 +381,20 @@ template <typename T>
 __global__ __launch_bounds__(64) void sim_band_bwd_dq_kernel(SimArgs s) {
   const AttnArgs& a = s.a;
   const int p = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (p >= sv.S) return;                               // packed batch: a shorter entry
   int lo, hi;
-  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+  sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, sv.L, lo, hi);
   if (hi <= lo) return;
   const int d = a.d, g = h / (a.H / a.G);
   const int64_t kvs = (int64_t)a.G * d;
-  const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * d;
+  const int64_t row = ((sv.q0 + p) * a.H + h) * d;
   const T* Q = (const T*)a.q + row;
   const T* dO = (const T*)a.dout + row;
   T* dQ = (T*)a.dq + row;
-  const T* Kp = (const T*)s.kp + ((int64_t)b * a.L * a.G + g) * d;
-  const T* Vp = (const T*)s.vp + ((int64_t)b * a.L * a.G + g) * d;
-  const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+  const T* Kp = (const T*)s.kp + (sv.kv0 * a.G + g) * d;
+  const T* Vp = (const T*)s.vp + (sv.kv0 * a.G + g) * d;
+  const int64_t li = sv.lse0 + h * sv.lse_hs + p;
   const bool c0 = lane < d, c1 = lane + 64 < d;
   const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
   const float g0 = c0 ? Io<T>::ld(dO + lane) : 0.f, g1 = c1 ? Io<T>::ld(dO + lane + 64) : 0.f;
@@ -408,8 +418,10 @@ template <typename T>
 __global__ __launch_bounds__(64) void sim_band_bwd_dkv_kernel(SimArgs s) {
   const AttnArgs& a = s.a;
   const int j = blockIdx.x, g = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const SeqView sv = seq_view(a, b);
+  if (j >= sv.L) return;                               // packed batch: a shorter entry
   const int d = a.d, rep = a.H / a.G;
-  const int64_t kvrow = (((int64_t)b * a.L + j) * a.G + g) * d;
+  const int64_t kvrow = ((sv.kv0 + j) * a.G + g) * d;
   const T* kr = (const T*)s.kp + kvrow;
   const T* vr = (const T*)s.vp + kvrow;
   const bool c0 = lane < d, c1 = lane + 64 < d;
@@ -418,14 +430,14 @@ __global__ __launch_bounds__(64) void sim_band_bwd_dkv_kernel(SimArgs s) {
   if (j - w0 < s.t) {                                  // this position holds a predicted state at step t
     const float k0 = c0 ? Io<T>::ld(kr + lane) : 0.f, k1 = c1 ? Io<T>::ld(kr + lane + 64) : 0.f;
     const float v0 = c0 ? Io<T>::ld(vr + lane) : 0.f, v1 = c1 ? Io<T>::ld(vr + lane + 64) : 0.f;
-    const int p_end = min(w0 + a.mask.k, a.S);         // the later queries of the same window see it
+    const int p_end = min(w0 + a.mask.k, sv.S);         // the later queries of the same window see it
     for (int p = j + 1; p < p_end; ++p)
       for (int hh = 0; hh < rep; ++hh) {
         const int h = g * rep + hh;
-        const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * d;
+        const int64_t row = ((sv.q0 + p) * a.H + h) * d;
         const T* Q = (const T*)a.q + row;
         const T* dO = (const T*)a.dout + row;
-        const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+        const int64_t li = sv.lse0 + h * sv.lse_hs + p;
         const float q0 = c0 ? Io<T>::ld(Q + lane) : 0.f, q1 = c1 ? Io<T>::ld(Q + lane + 64) : 0.f;
         const float g0 = c0 ? Io<T>::ld(dO + lane) : 0.f, g1 = c1 ? Io<T>::ld(dO + lane + 64) : 0.f;
         const float pj = expf(a.scale * wave_sum(q0 * k0 + q1 * k1) - a.lse[li]);
@@ -464,22 +476,29 @@ void launch_sim_band_bwd(const SimArgs& s, hipStream_t st) {
 // after step t the row at position t of every window takes the newly predicted state of that position.
 // blockIdx.x: window (the partial leading one first), blockIdx.y: batch entry; rows as 16-byte chunks.
 __global__ __launch_bounds__(256) void sim_save_kernel(const uint4* __restrict__ h, uint4* __restrict__ xpred, int L,
-                                                       int chunks, int k, int eps, const int32_t* eps_b, int t) {
+                                                       int chunks, int k, int eps, const int32_t* eps_b, int t,
+                                                       const int32_t* cu, int total) {
   if (eps_b) { eps = eps_b[blockIdx.y] % k; if (eps < 0) eps += k; }
+  int64_t first = (int64_t)blockIdx.y * L;          // first row of this entry
+  if (cu) {                                          // packed batch: clamped like the attention kernels' view
+    const int32_t r0 = min(max(cu[blockIdx.y], 0), total);
+    L = min(max(cu[blockIdx.y + 1] - r0, 0), min(L, total - r0));
+    first = r0;
+  }
   const int n0 = eps > 0 ? eps - k : 0;
   const int j = n0 + (int)blockIdx.x * k + t;
   if (j < 0 || j >= L) return;
-  const int64_t row = ((int64_t)blockIdx.y * L + j) * chunks;
+  const int64_t row = (first + j) * chunks;
   for (int c = threadIdx.x; c < chunks; c += 256) xpred[row + c] = h[row + c];
 }
 
 void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes, int k, int eps, const int32_t* eps_b,
-                     int t, hipStream_t st) {
+                     int t, const int32_t* cu, int total, hipStream_t st) {
   ProfScope ps("sim_save", st);
   const int n0 = (eps_b || eps > 0) ? -k + 1 : 0;   // lowest possible start of the leading window
   const int n_win = (L - n0 + k - 1) / k + 1;
   hipLaunchKernelGGL(sim_save_kernel, dim3(n_win, B), dim3(256), 0, st, (const uint4*)h, (uint4*)xpred, L,
-                     (int)(row_bytes / 16), k, eps, eps_b, t);
+                     (int)(row_bytes / 16), k, eps, eps_b, t, cu, total);
 }
 
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s) {

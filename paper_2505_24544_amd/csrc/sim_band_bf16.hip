@@ -60,13 +60,15 @@ __global__ __launch_bounds__(256) void sim_band_fwd_bf16_kernel(SimArgs s) {
   if (rb >= a.S * a.H) return;
   const int p = rb / a.H, h = rb - p * a.H, g = h / (a.H / a.G);
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    const SeqView sv = seq_view(a, b);
+    if (p >= sv.S) continue;                               // packed batch: a shorter entry
     int lo, hi;
-    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, sv.L, lo, hi);
     if (hi <= lo) continue;
-    const int64_t row = ((int64_t)b * a.S * a.H + rb) * BD;
-    const bf16_t* Kp = (const bf16_t*)s.kp + ((int64_t)b * a.L * a.G + g) * BD;
-    const bf16_t* Vp = (const bf16_t*)s.vp + ((int64_t)b * a.L * a.G + g) * BD;
-    const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+    const int64_t row = (sv.q0 * a.H + rb) * BD;
+    const bf16_t* Kp = (const bf16_t*)s.kp + (sv.kv0 * a.G + g) * BD;
+    const bf16_t* Vp = (const bf16_t*)s.vp + (sv.kv0 * a.G + g) * BD;
+    const int64_t li = sv.lse0 + h * sv.lse_hs + p;
     const Chunk q = load_chunk((const bf16_t*)a.q + row, c);
     float m = a.lse[li];                                   // weight of the true-key part: exp(m) * 1
     float l = m > -INFINITY ? 1.f : 0.f;
@@ -100,13 +102,15 @@ __global__ __launch_bounds__(256) void sim_band_bwd_dq_bf16_kernel(SimArgs s) {
   if (rb >= a.S * a.H) return;
   const int p = rb / a.H, h = rb - p * a.H, g = h / (a.H / a.G);
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    const SeqView sv = seq_view(a, b);
+    if (p >= sv.S) continue;                               // packed batch: a shorter entry
     int lo, hi;
-    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, a.L, lo, hi);
+    sim_band(p, a.mask.k, sample_mask(a, b).eps, s.t, sv.L, lo, hi);
     if (hi <= lo) continue;
-    const int64_t row = ((int64_t)b * a.S * a.H + rb) * BD;
-    const bf16_t* Kp = (const bf16_t*)s.kp + ((int64_t)b * a.L * a.G + g) * BD;
-    const bf16_t* Vp = (const bf16_t*)s.vp + ((int64_t)b * a.L * a.G + g) * BD;
-    const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+    const int64_t row = (sv.q0 * a.H + rb) * BD;
+    const bf16_t* Kp = (const bf16_t*)s.kp + (sv.kv0 * a.G + g) * BD;
+    const bf16_t* Vp = (const bf16_t*)s.vp + (sv.kv0 * a.G + g) * BD;
+    const int64_t li = sv.lse0 + h * sv.lse_hs + p;
     const Chunk q = load_chunk((const bf16_t*)a.q + row, c);
     const Chunk go = load_chunk((const bf16_t*)a.dout + row, c);
     Chunk dq = load_chunk((const bf16_t*)a.dq + row, c);
@@ -135,10 +139,12 @@ __global__ __launch_bounds__(256) void sim_band_bwd_dkv_bf16_kernel(SimArgs s) {
   if (rb >= a.L * a.G) return;
   const int j = rb / a.G, g = rb - j * a.G, rep = a.H / a.G;
   for (int b = blockIdx.y; b < a.B; b += gridDim.y) {
+    const SeqView sv = seq_view(a, b);
+    if (j >= sv.L) continue;                               // packed batch: a shorter entry
     const int w0 = window_start_raw(j, a.mask.k, sample_mask(a, b).eps);
     const bool holds_pred = j - w0 < s.t;                  // this position holds a predicted state at step t
-    const int p_end = min(w0 + a.mask.k, a.S);             // the later queries of the same window see it
-    const int64_t kvrow = ((int64_t)b * a.L * a.G + rb) * BD;
+    const int p_end = min(w0 + a.mask.k, sv.S);            // the later queries of the same window see it
+    const int64_t kvrow = (sv.kv0 * a.G + rb) * BD;
     Chunk dk, dv;
 #pragma unroll
     for (int i = 0; i < 8; ++i) dk.f[i] = dv.f[i] = 0.f;
@@ -148,8 +154,8 @@ __global__ __launch_bounds__(256) void sim_band_bwd_dkv_bf16_kernel(SimArgs s) {
       for (int p = j + 1; p < p_end; ++p)
         for (int hh = 0; hh < rep; ++hh) {
           const int h = g * rep + hh;
-          const int64_t row = (((int64_t)b * a.S + p) * a.H + h) * BD;
-          const int64_t li = ((int64_t)b * a.H + h) * a.S + p;
+          const int64_t row = ((sv.q0 + p) * a.H + h) * BD;
+          const int64_t li = sv.lse0 + h * sv.lse_hs + p;
           const Chunk q = load_chunk((const bf16_t*)a.q + row, c);
           const Chunk go = load_chunk((const bf16_t*)a.dout + row, c);
           const float pj = expf(a.scale * row16_sum(dot8(q, kk)) - a.lse[li]);

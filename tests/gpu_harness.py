@@ -12,9 +12,9 @@ from paper_2505_24544_amd import synth
 DEV = "cuda:0"
 
 
-def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0, block_offsets=None, rope_base=0.0, rope_positions=None):
-    """block_offsets / rope_positions: optional int32 device tensors (the caller keeps them alive)."""
-    return bx.make_desc(block_offsets=block_offsets, rope_base=rope_base, rope_positions=rope_positions, batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
+def desc_of(cfg: synth.XattnConfig, flags=0, scale=0.0, block_offsets=None, rope_base=0.0, rope_positions=None, **packed):
+    """block_offsets / rope_positions / cu_seqlens_*: optional int32 device tensors (the caller keeps them alive)."""
+    return bx.make_desc(block_offsets=block_offsets, rope_base=rope_base, rope_positions=rope_positions, **packed, batch=cfg.batch, seq_q=cfg.seq_q, seq_kv=cfg.seq_kv, hidden=cfg.hidden,
                         n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                         block_size=cfg.block_size, block_offset=cfg.block_offset,
                         io_dtype=bx.BEAGLE_BF16 if cfg.dtype == "bf16" else bx.BEAGLE_F32,

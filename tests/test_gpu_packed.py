@@ -1,0 +1,186 @@
+"""GPU parity for packed batches of sequences of different lengths (cu_seqlens): training forward/backward, with
+per-entry offsets and rotary embedding, the draft block and the simulation step, against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import beagle_oracle as orc
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+F32_TOL = 1e-5
+OUT_ABS, OUT_FRO, LSE_TOL, GRAD_FRO = 2e-2, 1e-2, 4e-3, 3e-2
+GRADS = ("dxq", "dxkv", "dwq", "dwk", "dwv", "dwo")
+
+
+def _pack(cfg, inp, lens_q, lens_kv):
+    """Packed inputs: entry b keeps its first lens_q[b] / lens_kv[b] rows of the batched recipe."""
+    cat = lambda a, lens: np.concatenate([a[b, :n] for b, n in enumerate(lens)], axis=0)
+    out = dict(inp, xq=cat(inp["xq"], lens_q), xkv=cat(inp["xkv"], lens_kv), dy=cat(inp["dy"], lens_q))
+    cu = lambda lens: np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    return out, cu(lens_q), cu(lens_kv)
+
+
+def _run(cfg, pk, cu_q, cu_kv, flags=bx.BEAGLE_FLAG_NEED_DXKV, eps_list=None, rope_base=0.0, totals=None):
+    dev_i = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=gh.DEV)
+    cq, ck = dev_i(cu_q), dev_i(cu_kv)
+    eb = dev_i(eps_list) if eps_list is not None else None
+    Tq, Tk = totals if totals is not None else (int(cu_q[-1]), int(cu_kv[-1]))
+    d = gh.desc_of(cfg, flags, block_offsets=eb, rope_base=rope_base, cu_seqlens_q=cq, cu_seqlens_kv=ck, total_q=Tq, total_kv=Tk)
+    dt = gh.tdtype(cfg)
+    D, H, G, hd = cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    t = {n: gh.to_dev(pk[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    out = lambda *s, dtype=dt: torch.full(s, float("nan"), dtype=dtype, device=gh.DEV)
+    f = dict(y=out(Tq, D), lse=out(H, Tq, dtype=torch.float32), q=out(Tq, H, hd), k=out(Tk, G, hd), v=out(Tk, G, hd), o=out(Tq, H, hd))
+    bx.beagle_xattn_fwd(d, t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], f["y"], f["lse"], f["q"], f["k"],
+                        f["v"], f["o"], gh.workspace(d, bx.BEAGLE_WS_FWD))
+    g = dict(dxq=out(Tq, D), dxkv=out(Tk, D), dwq=out(D, H * hd), dwk=out(D, G * hd), dwv=out(D, G * hd), dwo=out(H * hd, D))
+    bx.beagle_xattn_bwd(d, t["dy"], t["xq"], t["xkv"], t["wq"], t["wk"], t["wv"], t["wo"], f["q"], f["k"], f["v"],
+                        f["o"], f["lse"], g["dxq"], g["dxkv"], g["dwq"], g["dwk"], g["dwv"], g["dwo"],
+                        gh.workspace(d, bx.BEAGLE_WS_BWD))
+    torch.cuda.synchronize()
+    return {n: gh.to_host(v) for n, v in f.items()}, {n: gh.to_host(v) for n, v in g.items()}
+
+
+def _ref(cfg, pk, cu_q, cu_kv, eps_list=None, rope=None):
+    return orc.xattn_backward_packed(pk["dy"], pk["xq"], pk["xkv"], pk["wq"], pk["wk"], pk["wv"], pk["wo"], cu_q, cu_kv,
+                                     n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size,
+                                     eps_list=eps_list, rope=rope)
+
+
+@pytest.mark.parametrize("kw,lens_q,lens_kv,eps_list,rope", [
+    (dict(batch=3, seq_q=40, seq_kv=40, block_size=4), [40, 7, 23], [40, 7, 23], None, False),
+    (dict(batch=4, seq_q=70, seq_kv=90, n_q_heads=4, n_kv_heads=2, block_size=5), [70, 1, 33, 64], [90, 2, 10, 65], [0, 4, 2, 3], False),
+    (dict(batch=2, seq_q=50, seq_kv=50, block_size=3), [11, 50], [11, 50], [2, 1], True),
+])
+def test_fp32_packed(kw, lens_q, lens_kv, eps_list, rope):
+    cfg = synth.CONFIGS["c1"].with_(seed_base=111, **kw)
+    pk, cu_q, cu_kv = _pack(cfg, synth.make_inputs(cfg), lens_q, lens_kv)
+    ref = _ref(cfg, pk, cu_q, cu_kv, eps_list, dict(base=300.0) if rope else None)
+    fw, gr = _run(cfg, pk, cu_q, cu_kv, bx.BEAGLE_FLAG_NEED_DXKV | (bx.BEAGLE_FLAG_ROPE if rope else 0), eps_list, 300.0 if rope else 0.0)
+    for n in ("y", "o", "q", "k", "v"):
+        assert gh.rel_max(fw[n], ref[n]) <= F32_TOL, (n, gh.rel_max(fw[n], ref[n]))
+    fin = np.isfinite(ref["lse"])
+    assert np.array_equal(np.isneginf(fw["lse"]), ~fin)                       # [H, total_q]; masks restart per entry
+    assert gh.max_abs(fw["lse"][fin], ref["lse"][fin]) <= F32_TOL * max(1.0, float(np.abs(ref["lse"][fin]).max()))
+    for n in GRADS:
+        assert gh.rel_max(gr[n], ref[n]) <= F32_TOL, (n, gh.rel_max(gr[n], ref[n]))
+
+
+SMALL = dict(hidden=512, n_q_heads=4, n_kv_heads=4)
+
+
+@pytest.mark.parametrize("name,kw,lens", [
+    ("c2", dict(batch=4, seq_q=300, seq_kv=300, **SMALL), [300, 1, 129, 64]),
+    ("c3", dict(batch=3, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2), [128, 330, 257]),
+])
+def test_bf16_packed(name, kw, lens):
+    cfg = synth.CONFIGS[name].with_(**kw)
+    pk, cu_q, cu_kv = _pack(cfg, synth.make_inputs(cfg, peaked_queries=True), lens, lens)
+    ref = _ref(cfg, pk, cu_q, cu_kv)
+    fw, gr = _run(cfg, pk, cu_q, cu_kv)
+    for n in ("y", "o"):
+        assert np.isfinite(fw[n]).all(), n
+        assert gh.max_abs(fw[n], ref[n]) <= OUT_ABS and gh.rel_fro(fw[n], ref[n]) <= OUT_FRO, n
+    fin = np.isfinite(ref["lse"])
+    assert np.array_equal(np.isneginf(fw["lse"]), ~fin)
+    assert gh.max_abs(fw["lse"][fin], ref["lse"][fin]) <= LSE_TOL
+    for n in GRADS:
+        assert np.isfinite(gr[n]).all(), n
+        assert gh.rel_fro(gr[n], ref[n]) <= GRAD_FRO, (n, gh.rel_fro(gr[n], ref[n]))
+
+
+def test_equal_lengths_are_bitwise_the_batched_layout():
+    cfg = synth.CONFIGS["c2"].with_(batch=3, seq_q=200, seq_kv=200, **SMALL)
+    inp = synth.make_inputs(cfg)
+    pk, cu_q, cu_kv = _pack(cfg, inp, [200] * 3, [200] * 3)
+    fw, gr = _run(cfg, pk, cu_q, cu_kv)
+    fw0, gr0 = gh.run_train(cfg, inp, gh.desc_of(cfg, bx.BEAGLE_FLAG_NEED_DXKV))
+    for n in ("y", "o"):
+        assert np.array_equal(fw[n], fw0[n].reshape(fw[n].shape)), n
+    assert np.array_equal(fw["lse"], fw0["lse"].transpose(1, 0, 2).reshape(fw["lse"].shape), equal_nan=True)
+    for n in GRADS:
+        assert np.array_equal(gr[n], gr0[n].reshape(gr[n].shape)), n
+
+
+def test_wrong_offsets_are_clamped_not_followed():
+    """cu arrays cannot be validated on the host; the kernels clamp them so that nothing outside the packed
+    tensors is touched (results are then meaningless, but finite rows stay inside the buffers)."""
+    cfg = synth.CONFIGS["c1"].with_(seed_base=112, batch=2, seq_q=20, seq_kv=20, block_size=4)
+    pk, cu_q, cu_kv = _pack(cfg, synth.make_inputs(cfg), [20, 12], [20, 12])
+    bad = np.array([0, 1_000_000, -5], np.int32)
+    fw, _ = _run(cfg, pk, bad, bad, totals=(32, 32))                          # must return without a fault
+    assert fw["y"].shape == (32, cfg.hidden)
+
+
+def test_packed_argument_errors():
+    cu = torch.tensor([0, 5, 9], dtype=torch.int32, device=gh.DEV)
+    mk = lambda **kw: bx.make_desc(**dict(dict(batch=2, seq_q=8, seq_kv=8, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=64,
+                                               block_size=4, io_dtype=bx.BEAGLE_F32, cu_seqlens_q=cu, cu_seqlens_kv=cu,
+                                               total_q=9, total_kv=9), **kw))
+    assert bx.beagle_xattn_workspace_bytes(mk(), bx.BEAGLE_WS_BWD) > 0
+    assert bx.beagle_xattn_workspace_bytes(mk(cu_seqlens_kv=None), bx.BEAGLE_WS_BWD) == 0
+    assert bx.beagle_xattn_workspace_bytes(mk(total_q=17), bx.BEAGLE_WS_BWD) == 0      # more rows than B * seq_q
+    assert bx.beagle_xattn_workspace_bytes(mk(total_kv=1), bx.BEAGLE_WS_BWD) == 0      # fewer rows than entries
+    assert bx.beagle_xattn_workspace_bytes(mk(batch=1, total_q=8, total_kv=8), bx.BEAGLE_WS_DRAFT) == 0
+
+
+def _packed_desc(cfg, cu, flags=bx.BEAGLE_FLAG_NEED_DXKV, **kw):
+    cud = torch.tensor(cu, dtype=torch.int32, device=gh.DEV)
+    return gh.desc_of(cfg, flags, cu_seqlens_q=cud, cu_seqlens_kv=cud, total_q=int(cu[-1]), total_kv=int(cu[-1]), **kw), cud
+
+
+def test_simulation_step_and_save_on_a_packed_batch():
+    cfg = synth.CONFIGS["c1"].with_(seed_base=113, batch=3, seq_q=30, seq_kv=30, block_size=4, block_offset=1)
+    lens, t = [30, 9, 18], 2
+    inp = synth.make_inputs(cfg)
+    pk, cu, _ = _pack(cfg, inp, lens, lens)
+    xp_full = synth.make_inputs(cfg.with_(seed_base=163), with_dy=False)["xkv"]
+    xp = np.concatenate([xp_full[b, :n] for b, n in enumerate(lens)], axis=0)
+    T = int(cu[-1])
+    flat = cfg.with_(batch=1, seq_q=T, seq_kv=T)                      # allocation shapes of the packed tensors
+    d, keep = _packed_desc(cfg, cu)
+    one = {n: (v[None] if n in ("xq", "xkv", "dy") else v) for n, v in pk.items()}
+    fw, gr = gh.run_sim(flat, one, xp[None], t, desc=d)
+    W = [pk[n] for n in ("wq", "wk", "wv", "wo")]
+    kw = dict(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=4, eps=1, t=t)
+    refs = [orc.xattn_backward_sim(pk["dy"][None, cu[b]:cu[b + 1]], pk["xq"][None, cu[b]:cu[b + 1]], pk["xkv"][None, cu[b]:cu[b + 1]],
+                                   xp[None, cu[b]:cu[b + 1]], *W, **kw) for b in range(3)]
+    for n, src in (("y", fw), ("dxq", gr), ("dxkv", gr), ("dxpred", gr)):
+        want = np.concatenate([r[n][0] for r in refs], axis=0)
+        assert gh.rel_max(src[n][0], want) <= F32_TOL, (n, gh.rel_max(src[n][0], want))
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        assert gh.rel_max(gr[n], sum(r[n] for r in refs)) <= F32_TOL, n
+    # the save of the newly predicted rows restarts its windows in every entry
+    buf = gh.to_dev(xp, cfg).clone()
+    bx.beagle_xattn_sim_save(d, gh.to_dev(pk["xq"], cfg), buf, t)
+    torch.cuda.synchronize()
+    want = np.concatenate([orc.sim_save_predicted(xp[None, cu[b]:cu[b + 1]], pk["xq"][None, cu[b]:cu[b + 1]], 4, 1, t)[0]
+                           for b in range(3)], axis=0)
+    assert np.array_equal(gh.to_host(buf), want)
+
+
+def test_draft_block_on_a_packed_batch():
+    from oracle import block_oracle as blk
+    cfg = synth.CONFIGS["c2"].with_(seed_base=115, batch=3, seq_q=200, seq_kv=200, **SMALL)
+    lens, ffn = [200, 77, 130], 1408
+    bi = synth.make_block_inputs(cfg, ffn)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cat = lambda a: np.concatenate([a[b, :n] for b, n in enumerate(lens)], axis=0)
+    pk = dict(bi, e=cat(bi["e"])[None], hs=cat(bi["hs"])[None], dh=cat(bi["dh"])[None])
+    T = int(cu[-1])
+    d, keep = _packed_desc(cfg, cu, bx.BEAGLE_FLAG_NEED_DXKV | bx.BEAGLE_FLAG_ROPE)
+    fw, gr = gh.run_block(cfg.with_(batch=1, seq_q=T, seq_kv=T), pk, ffn, 1e-5, True, desc=d)
+    W = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+    refs = [blk.block_backward(pk["dh"][:, cu[b]:cu[b + 1]], pk["e"][:, cu[b]:cu[b + 1]], pk["hs"][:, cu[b]:cu[b + 1]],
+                               *(bi[n] for n in W), g_q=bi["g_q"], g_kv=bi["g_kv"], g_mlp=bi["g_mlp"], rms_eps=1e-5,
+                               n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size, eps=0,
+                               rope=dict(base=10000.0)) for b in range(3)]
+    h = np.concatenate([r["fwd"]["h"][0] for r in refs], axis=0)
+    assert gh.rel_fro(fw["h"][0], h) <= OUT_FRO
+    for n in ("de", "dhs"):
+        assert gh.rel_fro(gr[n][0], np.concatenate([r[n][0] for r in refs], axis=0)) <= GRAD_FRO, n
+    for n in ("dwq", "dwk", "dw_gate", "dw_down", "dg_q", "dg_kv", "dg_mlp"):
+        assert gh.rel_fro(gr[n], sum(r[n] for r in refs)) <= GRAD_FRO, (n, gh.rel_fro(gr[n], sum(r[n] for r in refs)))
