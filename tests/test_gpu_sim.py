@@ -181,3 +181,45 @@ def test_rows_saved_by_later_steps_do_not_change_this_step_bitwise():
         assert np.array_equal(fw[n], fw2[n], equal_nan=True), n
     for n in GRADS:
         assert np.array_equal(gr[n], gr2[n]), n
+
+
+def test_fullsize_simulation_step_on_sampled_rows():
+    """The 7B-shaped training workload at step t = 3 (what bench.py's late_stage_sim object times): y and dxq of
+    sampled query rows of one batch entry against the oracle evaluated on those rows over the concatenated
+    [true | predicted] keys."""
+    cfg = synth.CONFIGS["c2"].with_(seed_base=85, batch=2)
+    inp, xp = _inputs(cfg, peaked=True)
+    t, b = 3, 1
+    S, L, k = cfg.seq_q, cfg.seq_kv, cfg.block_size
+    d = bx.make_desc(batch=cfg.batch, seq_q=S, seq_kv=L, hidden=cfg.hidden, n_q_heads=cfg.n_q_heads,
+                     n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, block_size=k, io_dtype=bx.BEAGLE_BF16,
+                     flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    import torch
+    from gpu_harness import to_dev, to_host, workspace, DEV
+    B, D, H, G, hd = cfg.batch, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    dev["xp"] = to_dev(xp, cfg)
+    E = lambda *s, dtype=torch.bfloat16: torch.empty(*s, dtype=dtype, device=DEV)
+    y, lse, q, o = E(B, S, D), E(B, H, S, dtype=torch.float32), E(B, S, H, hd), E(B, S, H, hd)
+    kk, vv, kp, vp = (E(B, L, G, hd) for _ in range(4))
+    bx.beagle_xattn_fwd_sim(d, dev["xq"], dev["xkv"], dev["xp"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], t, y, lse, q,
+                            kk, vv, kp, vp, o, workspace(d, bx.BEAGLE_WS_FWD))
+    dxq, dxkv, dxp = E(B, S, D), E(B, L, D), E(B, L, D)
+    dwq, dwk, dwv, dwo = E(D, H * hd), E(D, G * hd), E(D, G * hd), E(H * hd, D)
+    bx.beagle_xattn_bwd_sim(d, dev["dy"], dev["xq"], dev["xkv"], dev["xp"], dev["wq"], dev["wk"], dev["wv"], dev["wo"], q, kk,
+                            vv, kp, vp, o, lse, t, dxq, dxkv, dxp, dwq, dwk, dwv, dwo, workspace(d, bx.BEAGLE_WS_BWD_SIM))
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 3, 4, 5, 6, 7, 127, 128, 129, 1023, 1025, 1026, 2046, 2047])
+    mask = np.concatenate([orc.dense_mask(S, L, k, 0), orc.sim_pred_mask(S, L, k, 0, t)], axis=1)[rows]
+    f64 = lambda a: np.asarray(a, np.float64)
+    cat = np.concatenate([f64(inp["xkv"])[b:b + 1], f64(xp)[b:b + 1]], axis=1)
+    ref = orc.xattn_backward(f64(inp["dy"])[b:b + 1, rows], f64(inp["xq"])[b:b + 1, rows], cat, inp["wq"], inp["wk"], inp["wv"],
+                             inp["wo"], n_q_heads=H, n_kv_heads=G, mask=mask)
+    got_y, got_dxq, got_lse = to_host(y[b, rows]), to_host(dxq[b, rows]), to_host(lse[b][:, rows])
+    assert max_abs(got_y, ref["y"][0]) <= BF16_OUT_ABS and rel_fro(got_y, ref["y"][0]) <= BF16_OUT_FRO
+    fin = np.isfinite(ref["lse"][0])
+    assert np.array_equal(np.isneginf(got_lse), ~fin) and max_abs(got_lse[fin], ref["lse"][0][fin]) <= 1.5e-2
+    assert rel_fro(got_dxq, ref["dxq"][0]) <= BF16_GRAD_FRO, rel_fro(got_dxq, ref["dxq"][0])
+    # rows that hold no predicted state at this step, or that no later query of their window can see, get exactly zero
+    used = orc.sim_pred_mask(S, L, k, 0, t).any(axis=0)
+    assert not to_host(dxp[:, ~used]).any() and to_host(dxp[:, used]).any()
