@@ -77,8 +77,17 @@ enum {
   BEAGLE_FLAG_NEED_DXKV = 1u << 0, /* bwd also produces dxkv                    */
   BEAGLE_FLAG_WGRAD_F32 = 1u << 1, /* bwd writes dwq/dwk/dwv/dwo as float even
                                       when io_dtype is bf16                     */
-  BEAGLE_FLAG_ROPE = 1u << 2       /* rotary position embedding of Q and K, see
+  BEAGLE_FLAG_ROPE = 1u << 2,      /* rotary position embedding of Q and K, see
                                       rope_base / rope_positions below          */
+  BEAGLE_FLAG_STATES_F16 = 1u << 3 /* the key/value source states (xkv; hs of the
+                                      block entry points) are stored as IEEE half
+                                      precision, as the offline-generated target
+                                      states of the paper's training set-up are;
+                                      they are converted to io_dtype on the way in
+                                      (workspace grows by one [B,L,D] tensor, also
+                                      for the forward entry points).  Everything
+                                      else, dxkv / dhs included, stays io_dtype.
+                                      Training entry points only; D % 8 == 0.    */
 };
 
 enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3, BEAGLE_WS_BWD_SIM = 4 };

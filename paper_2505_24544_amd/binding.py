@@ -20,7 +20,7 @@ BEAGLE_OK = 0
 (BEAGLE_ERR_NULL, BEAGLE_ERR_SHAPE, BEAGLE_ERR_UNSUPPORTED, BEAGLE_ERR_WORKSPACE, BEAGLE_ERR_ALIGN,
  BEAGLE_ERR_HIP) = range(1, 7)
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
-BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32, BEAGLE_FLAG_ROPE = 1, 2, 4
+BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32, BEAGLE_FLAG_ROPE, BEAGLE_FLAG_STATES_F16 = 1, 2, 4, 8
 BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
 BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD = 0, 1
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",

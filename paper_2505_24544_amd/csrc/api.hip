@@ -10,7 +10,7 @@ using namespace beagle;
 
 namespace {
 
-constexpr uint32_t KNOWN_FLAGS = BEAGLE_FLAG_NEED_DXKV | BEAGLE_FLAG_WGRAD_F32 | BEAGLE_FLAG_ROPE;
+constexpr uint32_t KNOWN_FLAGS = BEAGLE_FLAG_NEED_DXKV | BEAGLE_FLAG_WGRAD_F32 | BEAGLE_FLAG_ROPE | BEAGLE_FLAG_STATES_F16;
 constexpr size_t WS_ALIGN = 256;
 
 size_t align_up(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
@@ -26,6 +26,7 @@ struct Dims {
   bool rope; float rope_base; const int32_t* rope_pos;
   int64_t Tq, Tk;          // query / key rows in total: B*S, B*L, or the packed row counts
   const int32_t* cu_q; const int32_t* cu_kv;   // packed batches (device, B+1 entries each) or null
+  bool kv_f16;             // the key/value source states arrive as IEEE half
 };
 
 beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
@@ -77,6 +78,8 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
     if (c->total_q < d.B || c->total_q > d.B * d.S || c->total_kv < d.B || c->total_kv > d.B * d.L) return BEAGLE_ERR_SHAPE;
     d.Tq = c->total_q; d.Tk = c->total_kv; d.cu_q = c->cu_seqlens_q; d.cu_kv = c->cu_seqlens_kv;
   }
+  d.kv_f16 = (c->flags & BEAGLE_FLAG_STATES_F16) != 0;
+  if (d.kv_f16 && (draft || d.D % 8)) return BEAGLE_ERR_UNSUPPORTED;
   d.rope = (c->flags & BEAGLE_FLAG_ROPE) != 0;
   d.rope_base = 10000.f; d.rope_pos = nullptr;
   if (d.rope) {
@@ -141,6 +144,16 @@ void run_gemm(const Dims& d, const GemmGroup& g, hipStream_t s, const char* name
 }
 
 beagle_status hip_status() { return hipGetLastError() == hipSuccess ? BEAGLE_OK : BEAGLE_ERR_HIP; }
+
+// Half-precision key/value source states: bytes of the converted copy (kept at the END of every workspace), and
+// the conversion itself.  `need` is the entry point's whole workspace requirement.
+size_t states_ws(const Dims& d) { return d.kv_f16 ? align_up((size_t)(d.Tk * d.D) * d.esz) : 0; }
+const void* states_in(const Dims& d, const void* xkv, void* workspace, size_t need, hipStream_t s) {
+  if (!d.kv_f16) return xkv;
+  void* dst = (char*)workspace + need - states_ws(d);
+  launch_cvt_f16(d.bf16, xkv, dst, d.Tk * d.D, s);
+  return dst;
+}
 
 RopeArgs rope_args(const Dims& d, bool inverse) {
   RopeArgs r; memset(&r, 0, sizeof(r));
@@ -363,12 +376,12 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
   Dims d;
   if (check_desc(desc, which == BEAGLE_WS_DRAFT || which == BEAGLE_WS_APPEND, &d) != BEAGLE_OK) return 0;
   switch (which) {
-    case BEAGLE_WS_FWD: return WS_ALIGN;   // nothing beyond the saved tensors
+    case BEAGLE_WS_FWD: return WS_ALIGN + states_ws(d);   // nothing beyond the saved tensors (and the converted states)
     case BEAGLE_WS_BWD: {
       BwdWs w = bwd_layout(d);
       size_t extra = 0;
       if (d.bf16) { AttnArgs a = attn_args(d); extra = attn_bwd_bf16_ws_bytes(a); }
-      return w.total + align_up(extra);
+      return w.total + align_up(extra) + states_ws(d);
     }
     case BEAGLE_WS_DRAFT:
       if (d.bf16) return align_up(decode_bf16_ws_bytes((int32_t)d.S, (int32_t)d.L, (int32_t)d.H, (int32_t)d.d, (int32_t)d.D));
@@ -377,7 +390,7 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
       BwdWs w = bwd_layout(d);
       size_t extra = 0;
       if (d.bf16) { AttnArgs a = attn_args(d); extra = attn_bwd_bf16_ws_bytes(a); }
-      return w.total + align_up(extra) + 2 * align_up((size_t)(d.Tk * d.GD) * d.esz);   // + dKp, dVp
+      return w.total + align_up(extra) + 2 * align_up((size_t)(d.Tk * d.GD) * d.esz) + states_ws(d);   // + dKp, dVp
     }
     case BEAGLE_WS_APPEND:
       if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))
@@ -397,10 +410,16 @@ beagle_status beagle_xattn_fwd(const beagle_xattn_desc* desc,
   const void* ptrs[] = {xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save};
   for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
-  (void)workspace; (void)workspace_bytes;
+  const size_t need_ws = beagle_xattn_workspace_bytes(desc, BEAGLE_WS_FWD);
+  if (d.kv_f16) {
+    if (!workspace) return BEAGLE_ERR_NULL;
+    if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+    if (workspace_bytes < need_ws) return BEAGLE_ERR_WORKSPACE;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
+  xkv = states_in(d, xkv, workspace, need_ws, s);
   xattn_fwd_run(d, xq, xkv, wq, wk, wv, wo, y, lse, q_save, k_save, v_save, o_save, nullptr, s);
   return hip_status();
 }
@@ -425,6 +444,7 @@ beagle_status beagle_xattn_bwd(const beagle_xattn_desc* desc,
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
 
+  xkv = states_in(d, xkv, workspace, beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD), s);
   xattn_bwd_run(d, need_dxkv, d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32), dy, xq, xkv, wq, wk, wv, wo, q_save, k_save,
                 v_save, o_save, lse, dxq, dxkv, dwq, dwk, dwv, dwo, (char*)workspace, nullptr, s);
   return hip_status();
@@ -441,9 +461,15 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
   if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
-  (void)workspace; (void)workspace_bytes;
+  const size_t need_ws = beagle_xattn_workspace_bytes(desc, BEAGLE_WS_FWD);
+  if (d.kv_f16) {
+    if (!workspace) return BEAGLE_ERR_NULL;
+    if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+    if (workspace_bytes < need_ws) return BEAGLE_ERR_WORKSPACE;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
+  xkv = states_in(d, xkv, workspace, need_ws, s);
 
   GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
   qkv.count = 3;
@@ -510,6 +536,7 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
+  xkv = states_in(d, xkv, workspace, beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM), s);
 
   const BwdWs w = bwd_layout(d);
   char* base = (char*)workspace;
@@ -718,7 +745,7 @@ using namespace beagle;
 size_t beagle_xattn_block_workspace_bytes(const beagle_xattn_desc* desc, int32_t ffn, int which) {
   Dims d;
   if (check_desc(desc, false, &d) != BEAGLE_OK || ffn < 1 || ffn % (d.bf16 ? 64 : 4)) return 0;
-  if (which == BEAGLE_WS_BLOCK_FWD) return WS_ALIGN;
+  if (which == BEAGLE_WS_BLOCK_FWD) return WS_ALIGN + states_ws(d);
   if (which == BEAGLE_WS_BLOCK_BWD)
     return block_bwd_layout(d, ffn).total + beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD);
   return 0;
@@ -740,11 +767,17 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
                        sv->xq_n, sv->r_q, sv->xkv_n, sv->r_kv, sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->z,
                        sv->r_mlp, sv->u, sv->w, sv->m};
   for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
-  (void)workspace; (void)workspace_bytes;
+  const size_t need_ws = beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_FWD);
+  if (d.kv_f16) {
+    if (!workspace) return BEAGLE_ERR_NULL;
+    if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+    if (workspace_bytes < need_ws) return BEAGLE_ERR_WORKSPACE;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
   const int64_t Mq = d.Tq, Mk = d.Tk, F = p->ffn;
   const int D = (int)d.D;
+  hs = states_in(d, hs, workspace, need_ws, s);
 
   const void* xq = e; const void* xkv = hs;
   if (p->g_q) { launch_rmsnorm_fwd(d.bf16, e, p->g_q, sv->xq_n, sv->r_q, Mq, D, p->rms_eps, s, "norm_q"); xq = sv->xq_n; }
@@ -794,6 +827,7 @@ beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle
   const int D = (int)d.D;
   const BlockWs w = block_bwd_layout(d, F);
   char* base = (char*)workspace;
+  hs = states_in(d, hs, workspace, beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_BWD), s);
   void* dm = base + w.dm; void* dwp = base + w.dw; void* dz = base + w.dz; void* dy = base + w.dy;
   void* dxq_n = base + w.dxq; void* dxkv_n = base + w.dxkv; float* part = (float*)(base + w.part);
 

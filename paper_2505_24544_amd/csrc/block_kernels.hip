@@ -198,6 +198,25 @@ __global__ __launch_bounds__(256) void silu_mul_bwd_kernel(const T* dm, const T*
   }
 }
 
+// IEEE half -> storage type, eight elements per thread and step (the offline-generated target states arrive in
+// half precision: section 6, training details)
+template <typename T>
+__global__ __launch_bounds__(256) void cvt_f16_kernel(const _Float16* __restrict__ in, T* __restrict__ out, int64_t n) {
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8; i < n; i += (int64_t)gridDim.x * 256 * 8) {
+    const h8 v = *(const h8*)(in + i);
+    float f[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) f[k] = (float)v[k];
+    if (sizeof(T) == 2) {
+      Vec<bf16_t>::st((bf16_t*)out + i, f);
+    } else {
+      Vec<float>::st((float*)out + i, f);
+      Vec<float>::st((float*)out + i + 4, f + 4);
+    }
+  }
+}
+
 template <typename T>
 void rmsnorm_fwd_t(const void* x, const void* gain, void* out, float* rinv, int64_t rows, int D, float eps, hipStream_t s) {
   hipLaunchKernelGGL(rmsnorm_fwd_kernel<T>, dim3((unsigned)rows), dim3(256), 0, s, (const T*)x, (const T*)gain, (T*)out,
@@ -234,6 +253,14 @@ void launch_rmsnorm_bwd(bool bf16, const void* dout, const void* x, const void* 
   const int nparts = rmsnorm_bwd_parts(rows);
   if (bf16) rmsnorm_bwd_t<bf16_t>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, s);
   else rmsnorm_bwd_t<float>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, s);
+}
+
+void launch_cvt_f16(bool bf16, const void* in, void* out, int64_t n, hipStream_t s) {
+  ProfScope ps("states_f16", s);
+  if (bf16) hipLaunchKernelGGL(cvt_f16_kernel<bf16_t>, dim3(elementwise_grid(n, 8)), dim3(256), 0, s, (const _Float16*)in,
+                               (bf16_t*)out, n);
+  else hipLaunchKernelGGL(cvt_f16_kernel<float>, dim3(elementwise_grid(n, 8)), dim3(256), 0, s, (const _Float16*)in,
+                          (float*)out, n);
 }
 
 void launch_silu_mul_fwd(bool bf16, const void* u, const void* w, void* m, int64_t n, hipStream_t s) {

@@ -32,6 +32,17 @@ def to_dev(a: np.ndarray, cfg) -> torch.Tensor:
     return t.to(DEV).contiguous()
 
 
+def to_dev_f16(a: np.ndarray) -> torch.Tensor:
+    """Upload as IEEE half (the values must already be half-representable)."""
+    h = np.ascontiguousarray(a, np.float32).astype(np.float16)
+    assert np.array_equal(h.astype(np.float32), np.asarray(a, np.float32)), "values are not half-representable"
+    return torch.from_numpy(h).to(DEV).contiguous()
+
+
+def _up(inp, names, cfg, f16_keys=()):
+    return {n: (to_dev_f16(inp[n]) if n in f16_keys else to_dev(inp[n], cfg)) for n in names}
+
+
 def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").to(torch.float64).numpy()
 
@@ -97,13 +108,13 @@ def run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, poi
     return g
 
 
-def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, desc=None):
+def run_sim(cfg, inp, xpred, t, flags=bx.BEAGLE_FLAG_NEED_DXKV, scale=0.0, desc=None, f16_keys=()):
     """Forward + backward of late-stage simulation step t through the C ABI.
     Returns host float64 dicts (forward results, gradients)."""
     d = desc if desc is not None else desc_of(cfg, flags, scale)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-    dev = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    dev = _up(inp, ("xq", "xkv", "wq", "wk", "wv", "wo", "dy"), cfg, f16_keys)
     dev["xp"] = to_dev(xpred, cfg)
 
     def out(*shape, dtype=dt):
@@ -158,19 +169,19 @@ BLOCK_W = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
 BLOCK_G = ("g_q", "g_kv", "g_mlp")
 
 
-def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None):
+def run_block(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None, f16_keys=()):
     """Forward + backward of the whole draft block through the C ABI.  bi: make_block_inputs' dict.
     Returns host float64 dicts (forward results incl. the saved tensors, gradients)."""
-    sv, gr = run_block_device(cfg, bi, ffn, rms_eps, gains, flags, desc)
+    sv, gr = run_block_device(cfg, bi, ffn, rms_eps, gains, flags, desc, f16_keys)
     return {n: to_host(v) for n, v in sv.items()}, {n: to_host(v) for n, v in gr.items()}
 
 
-def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None):
+def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEED_DXKV, desc=None, f16_keys=()):
     """As run_block, results left on the device (forward dict includes h)."""
     d = desc if desc is not None else desc_of(cfg, flags)
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-    dev = {n: to_dev(bi[n], cfg) for n in ("e", "hs", "dh") + BLOCK_W + (BLOCK_G if gains else ())}
+    dev = _up(bi, ("e", "hs", "dh") + BLOCK_W + (BLOCK_G if gains else ()), cfg, f16_keys)
 
     def out(*shape, dtype=dt):
         return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
@@ -201,12 +212,12 @@ def run_block_device(cfg, bi, ffn, rms_eps, gains=True, flags=bx.BEAGLE_FLAG_NEE
     return sv, gr
 
 
-def run_train(cfg, inp, desc):
+def run_train(cfg, inp, desc, f16_keys=()):
     """Training forward + backward through the C ABI under a caller-built descriptor (dXkv requested).
-    Returns host float64 dicts (forward results, gradients)."""
+    f16_keys: inputs uploaded as IEEE half.  Returns host float64 dicts (forward results, gradients)."""
     dt = tdtype(cfg)
     B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-    t = {n: to_dev(inp[n], cfg) for n in ("xq", "xkv", "wq", "wk", "wv", "wo", "dy")}
+    t = _up(inp, ("xq", "xkv", "wq", "wk", "wv", "wo", "dy"), cfg, f16_keys)
     out = lambda *s, dtype=dt: torch.full(s, float("nan"), dtype=dtype, device=DEV)
     f = dict(y=out(B, S, D), lse=out(B, H, S, dtype=torch.float32), q=out(B, S, H, hd), k=out(B, L, G, hd),
              v=out(B, L, G, hd), o=out(B, S, H, hd))
