@@ -20,7 +20,7 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden")
 OUT_ABS, OUT_FRO, LSE_TOL, GRAD_FRO = 2e-2, 1e-2, 1e-3, 3e-2
 # Peaked-query variant (not one of the five configs): scores have std ~1.6, and the saved Q/K are rounded to
 # bf16 (unit roundoff 2^-9), which moves a score by ~2.6e-3 rms.  A row with few visible keys inherits that
-# directly in its LSE; 1.5e-2 is ~6 sigma (derivation in the design doc).
+# directly in its LSE; 1.5e-2 is ~6 sigma of that.
 LSE_TOL_PEAKED = 1.5e-2
 
 

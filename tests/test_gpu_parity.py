@@ -1,7 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the float64
 oracle on the same seeded inputs, element by element.
 
-Tolerances (from the problem statement; the derivations are in the design doc):
+Tolerances (from the problem statement):
   fp32 path      : max|gpu-ref| / max|ref| <= 1e-5 for every output and gradient
   bf16 outputs   : max abs error <= 2e-2 (unit-scale activations); LSE abs <= 1e-3
   bf16 gradients : relative Frobenius error <= 3e-2
@@ -123,7 +123,7 @@ def test_bf16_reduced_configs(name, kw, peaked):
     cfg = synth.CONFIGS[name].with_(**kw)
     inp = synth.make_inputs(cfg, peaked_queries=peaked)
     # peaked queries on rows with very few keys: the bf16 rounding of q and k
-    # moves single scores by ~2^-9 * |s|; see the design doc for the bound
+    # moves single scores by ~2^-9 * |s|
     check_bf16(cfg, inp, lse_tol=LSE_TOL if not peaked else 4e-3)
 
 
