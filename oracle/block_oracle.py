@@ -142,3 +142,26 @@ def block_backward(dh, e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None,
     return dict(de=dy + de_norm, dhs=dhs, dwq=ab["dwq"], dwk=ab["dwk"], dwv=ab["dwv"], dwo=ab["dwo"],
                 dw_gate=mb["dw_gate"], dw_up=mb["dw_up"], dw_down=mb["dw_down"],
                 dg_q=dg_q, dg_kv=dg_kv, dg_mlp=dg_mlp, dy=dy, fwd=f)
+
+
+# --------------------------------------------------------------------------
+# The block at decode time (section 4.1, last paragraphs: the same block decodes
+# draft tokens autoregressively against cached K/V rows)
+# --------------------------------------------------------------------------
+def block_draft_step(x, k_cache, v_cache, wq, wo, w_gate, w_up, w_down, *, g_q=None, g_mlp=None, rms_eps=1e-5,
+                     n_true=None, tree_mask=None, n_q_heads, n_kv_heads, scale=None, rope=None):
+    """M draft token embeddings x [M, D] through Eq. 1 against a cache of already projected (and, with rope,
+    already rotated) K/V rows: y = Attn(RMSNorm(x; g_q)) + x over the cache rows (all of them, or n_true true rows
+    plus the drafted rows that tree_mask shows), h = MLP(RMSNorm(y; g_mlp)) + y.  Returns dict h, y, lse.
+    The key/value side's normalisation (g_kv) and projections happened when the rows were appended."""
+    x = np.asarray(x, F64)
+    L = np.asarray(k_cache).shape[0]
+    if n_true is None:
+        n_true, tree_mask = L, np.zeros((x.shape[0], 0), bool)
+    xn = rmsnorm(x, g_q, rms_eps)
+    att = orc.draft_step_tree(xn, k_cache, v_cache, wq, wo, n_true=n_true, tree_mask=tree_mask, n_q_heads=n_q_heads,
+                              n_kv_heads=n_kv_heads, scale=scale, rope=rope)
+    y = att["y"] + x
+    z = rmsnorm(y, g_mlp, rms_eps)
+    h = mlp_forward(z, w_gate, w_up, w_down)["out"] + y
+    return dict(h=h, y=y, lse=att["lse"])

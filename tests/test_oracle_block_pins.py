@@ -185,3 +185,29 @@ def test_block_gradients_by_finite_differences():
         d = rng.normal(size=kw[n].shape)
         fd = (loss(c, dict(kw, **{n: kw[n] + 1e-6 * d})) - loss(c, dict(kw, **{n: kw[n] - 1e-6 * d}))) / 2e-6
         assert abs(fd - (b["d" + n] * d).sum()) <= 2e-6 * max(1.0, abs(fd)), n
+
+
+# ------------------------------------------------------------------ the block at decode time
+@pytest.mark.parametrize("gains,rope", [(True, None), (False, None), (True, dict(base=100.0))])
+def test_block_draft_step_reproduces_the_training_block_row(gains, rope):
+    """k = 1: row p of the training block sees keys j < p.  The decode-time block over a cache holding the K/V rows of
+    the (normalised) states 0 .. p-1, fed with embedding p, gives the same h (the training block is pinned above)."""
+    c, kw, _ = _case(B=1, S=9, gains=gains)
+    kw = dict(kw, k=1, eps=0)
+    f = blk.block_forward(**c, **kw, rope=rope)
+    G = kw["n_kv_heads"]
+    kc, vc = f["attn"]["k"][0], f["attn"]["v"][0]             # rows as the training forward projected (and rotated) them
+    for p in (1, 4, 8):
+        dkw = dict(g_q=kw.get("g_q"), g_mlp=kw.get("g_mlp"), rms_eps=kw["rms_eps"], n_q_heads=kw["n_q_heads"], n_kv_heads=G)
+        r = None if rope is None else dict(rope, q_pos=[p])
+        d = blk.block_draft_step(c["e"][0, p:p + 1], kc[:p], vc[:p], c["wq"], c["wo"], c["w_gate"], c["w_up"], c["w_down"],
+                                 **dkw, rope=r)
+        assert np.allclose(d["h"][0], f["h"][0, p], atol=1e-12), p
+        assert np.allclose(d["y"][0], f["y"][0, p], atol=1e-12), p
+    # drafted rows under a tree: hiding a drafted row equals dropping it from the cache
+    p = 6
+    tm = np.array([[True, False]])
+    a = blk.block_draft_step(c["e"][0, p:p + 1], kc[:p], vc[:p], c["wq"], c["wo"], c["w_gate"], c["w_up"], c["w_down"],
+                             **dkw, n_true=p - 2, tree_mask=tm)
+    b = blk.block_draft_step(c["e"][0, p:p + 1], kc[:p - 1], vc[:p - 1], c["wq"], c["wo"], c["w_gate"], c["w_up"], c["w_down"], **dkw)
+    assert np.allclose(a["h"], b["h"], atol=1e-13)
