@@ -354,7 +354,22 @@ def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):
         kc, vc, _, _ = sets[r % nset]
         bx.beagle_xattn_kv_append(adesc, x, wk, wv, kc, vc, L - T, aws, stream)
 
-    for name, fn in (("tree_M10_T50", tree_call), ("kv_append_n10", append_call)):
+    # the whole draft block per draft step (Eq. 1): the tree step above + RMSNorm, residuals and the feed-forward
+    # layer of the 7B shape; its three matrices rotate through four sets (1.1 GB) like the rest
+    F = 11008
+    R = lambda *sh, std=0.02: (torch.randn(*sh, device=dev, generator=g) * std).to(torch.bfloat16)
+    mlps = [(R(D, F), R(D, F), R(F, D)) for _ in range(4)]
+    gq, gm = R(D, std=0.1) + 1, R(D, std=0.1) + 1
+    hb = torch.empty(M, D, dtype=torch.bfloat16, device=dev)
+    bws = torch.empty(bx.beagle_xattn_block_workspace_bytes(desc, F, bx.BEAGLE_WS_BLOCK_DRAFT), dtype=torch.uint8, device=dev)
+
+    def block_call(r):
+        kc, vc, wq, wo = sets[r % nset]
+        wg, wu, wd = mlps[r % 4]
+        prm = bx.make_block_params(F, 1e-5, wq=wq, wo=wo, w_gate=wg, w_up=wu, w_down=wd, g_q=gq, g_mlp=gm)
+        bx.beagle_xattn_block_draft_step(desc, prm, x, kc, vc, L - T, tmd, 2, hb, lse, bws, stream)
+
+    for name, fn in (("tree_M10_T50", tree_call), ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call)):
         for r in range(nset):
             fn(r)
         torch.cuda.synchronize()
@@ -368,6 +383,8 @@ def bench_decode(torch, bx, gh, synth, k_train, v_train, t_train):
         us = e0.elapsed_time(e1) / reps * 1e3
         if name.startswith("tree"):
             nbytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2 + 2 * D * H * hd * 2
+        elif name.startswith("block"):
+            nbytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2 + 2 * D * H * hd * 2 + 3 * D * F * 2 + 2 * M * D * 2
         else:
             nbytes = 2 * D * G * hd * 2 + M * D * 2 + 2 * M * G * hd * 2
         res[name] = dict(us_per_call=round(us, 2), gbs=round(nbytes / us / 1e3, 1),

@@ -305,7 +305,7 @@ typedef struct {
   float *dg_q, *dg_kv, *dg_mlp; /* [D] float; required iff the gain is given     */
 } beagle_block_grads;
 
-enum { BEAGLE_WS_BLOCK_FWD = 0, BEAGLE_WS_BLOCK_BWD = 1 };
+enum { BEAGLE_WS_BLOCK_FWD = 0, BEAGLE_WS_BLOCK_BWD = 1, BEAGLE_WS_BLOCK_DRAFT = 2 };
 
 /* Workspace bytes of the two block entry points (`which` is BEAGLE_WS_BLOCK_*);
  * 0 for an invalid descriptor / ffn. */
@@ -330,6 +330,28 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
 beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* params,
     const void* dh, const void* e, const void* hs, const beagle_block_saved* saved,
     const beagle_block_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The block at decode time (section 4.1, last paragraphs: the same block
+ * decodes draft tokens autoregressively against the cached K/V rows): M draft
+ * token embeddings through Eq. 1,
+ *     y = DraftStep(RMSNorm(x; g_q)) + x        h = MLP(RMSNorm(y; g_mlp)) + y
+ * where DraftStep is beagle_xattn_draft_step_tree (n_true = seq_kv and a NULL
+ * mask give beagle_xattn_draft_step).  The key/value side (g_kv, wk, wv) is
+ * not used here: rows enter the cache through beagle_xattn_kv_append.
+ * desc as for the draft step (batch == 1, seq_q = M, seq_kv = cache rows).
+ *   in : x_draft [M,D]; k_cache, v_cache [L,G,d]; params (wq, wo, w_gate, w_up,
+ *        w_down required; g_q, g_mlp optional); tree mask as in
+ *        beagle_xattn_draft_step_tree
+ *   out: h [M,D]; lse [H,M] float
+ * Workspace: beagle_xattn_block_workspace_bytes(desc, ffn, BEAGLE_WS_BLOCK_DRAFT).
+ * BEAGLE_BF16: a handful of rows is HBM-bound on the weights (Wq, Wo and the
+ * three feed-forward matrices) and the cache, so every projection is the
+ * split-k streaming kernel of the draft step.
+ */
+beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* x_draft, const void* k_cache, const void* v_cache, int32_t n_true, const uint32_t* tree_mask,
+    int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Appending states to the decode cache (section 4.1, KV-cache paragraph: new

@@ -724,8 +724,8 @@ BlockWs block_bwd_layout(const Dims& d, int64_t F) {
   return w;
 }
 
-beagle_status check_block(const beagle_xattn_desc* desc, const beagle_block_params* p, Dims* d) {
-  beagle_status st = check_desc(desc, false, d);
+beagle_status check_block(const beagle_xattn_desc* desc, const beagle_block_params* p, Dims* d, bool draft = false) {
+  beagle_status st = check_desc(desc, draft, d);
   if (st != BEAGLE_OK) return st;
   if (!p) return BEAGLE_ERR_NULL;
   if (p->struct_size != (int32_t)sizeof(beagle_block_params) || p->ffn < 1 || p->reserved != 0) return BEAGLE_ERR_SHAPE;
@@ -742,8 +742,34 @@ beagle_status check_block(const beagle_xattn_desc* desc, const beagle_block_para
 
 using namespace beagle;
 
+namespace beagle {
+namespace {
+// decode-time block: xn [M,D], 1/rms [M], y [M,D], z [M,D], then the draft step's and the feed-forward's own space
+struct BlockDraftWs { size_t xn, rinv, y, z, u, w, m, step, mlp, total; };
+BlockDraftWs block_draft_layout(const beagle_xattn_desc* desc, const Dims& d, int64_t F) {
+  BlockDraftWs w; size_t o = 0;
+  const size_t MD = align_up((size_t)(d.S * d.D) * d.esz), MF = align_up((size_t)(d.S * F) * d.esz);
+  w.xn = o; o += MD;
+  w.rinv = o; o += align_up((size_t)d.S * sizeof(float));
+  w.y = o; o += MD;
+  w.z = o; o += MD;
+  w.u = o; o += d.bf16 ? 0 : MF;             // fp32 path: gate / up projections and their product in full
+  w.w = o; o += d.bf16 ? 0 : MF;
+  w.m = o; o += d.bf16 ? 0 : MF;
+  w.step = o; o += beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT);
+  w.mlp = o; o += d.bf16 ? align_up(block_mlp_bf16_ws_bytes((int32_t)d.S, (int32_t)d.D, (int32_t)F)) : 0;
+  w.total = o;
+  return w;
+}
+}  // namespace
+}  // namespace beagle
+
 size_t beagle_xattn_block_workspace_bytes(const beagle_xattn_desc* desc, int32_t ffn, int which) {
   Dims d;
+  if (which == BEAGLE_WS_BLOCK_DRAFT) {
+    if (check_desc(desc, true, &d) != BEAGLE_OK || ffn < 1 || ffn % (d.bf16 ? 64 : 4)) return 0;
+    return block_draft_layout(desc, d, ffn).total;
+  }
   if (check_desc(desc, false, &d) != BEAGLE_OK || ffn < 1 || ffn % (d.bf16 ? 64 : 4)) return 0;
   if (which == BEAGLE_WS_BLOCK_FWD) return WS_ALIGN + states_ws(d);
   if (which == BEAGLE_WS_BLOCK_BWD)
@@ -867,5 +893,83 @@ beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle
   if (p->g_kv)
     launch_rmsnorm_bwd(d.bf16, dxkv_n, hs, p->g_kv, sv->r_kv, nullptr, need_dhs ? gr->dhs : dxkv_n, gr->dg_kv, part, Mk, D,
                        s, "bwd_norm_kv");
+  return hip_status();
+}
+
+beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* x_draft, const void* k_cache, const void* v_cache, int32_t n_true, const uint32_t* tree_mask,
+    int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_block(desc, p, &d, true);
+  if (st != BEAGLE_OK) return st;
+  const void* req[] = {x_draft, k_cache, v_cache, p->wq, p->wo, p->w_gate, p->w_up, p->w_down, h, lse, workspace};
+  for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
+  const void* all[] = {x_draft, k_cache, v_cache, p->wq, p->wo, p->w_gate, p->w_up, p->w_down, p->g_q, p->g_mlp, h, lse};
+  for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  const int64_t F = p->ffn;
+  if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_DRAFT)) return BEAGLE_ERR_WORKSPACE;
+  if (d.bf16 && !block_mlp_bf16_fits((int32_t)d.D, (int32_t)F)) return BEAGLE_ERR_UNSUPPORTED;
+  if (n_true < 0 || n_true > d.L) return BEAGLE_ERR_SHAPE;
+  const int64_t T = d.L - n_true;
+  if (T > 0) {
+    if (!tree_mask) return BEAGLE_ERR_NULL;
+    if (((uintptr_t)tree_mask) % 4) return BEAGLE_ERR_ALIGN;
+    if (mask_words < (T + 31) / 32) return BEAGLE_ERR_SHAPE;
+  } else {
+    tree_mask = nullptr; mask_words = 0;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const BlockDraftWs w = block_draft_layout(desc, d, F);
+  char* base = (char*)workspace;
+  void* y = base + w.y;
+  const int D = (int)d.D;
+
+  // y = Attn(RMSNorm(x)) + x
+  const void* xn = x_draft;
+  if (p->g_q) { launch_rmsnorm_fwd(d.bf16, x_draft, p->g_q, base + w.xn, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_q"); xn = base + w.xn; }
+  if (d.bf16) {
+    DecodeArgs a; memset(&a, 0, sizeof(a));
+    a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
+    a.D = (int32_t)d.D; a.scale = d.scale;
+    a.x = xn; a.kc = k_cache; a.vc = v_cache; a.wq = p->wq; a.wo = p->wo; a.y = y; a.lse = lse; a.ws = base + w.step;
+    a.tree = tree_mask; a.n_true = n_true; a.tree_words = mask_words;
+    a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
+    a.y_res = x_draft;
+    launch_decode_bf16(a, s);
+  } else {
+    char* sb = base + w.step;
+    void* q = sb;
+    void* o = sb + (size_t)(d.S * d.HD) * d.esz;
+    launch_gemm_f32(group1(gemm_nn(xn, p->wq, q, d.S, d.HD, d.D)), s, "draft_proj_q");
+    if (d.rope) {
+      RopeArgs r = rope_args(d, false);
+      rope_add(r, q, d.S, d.rope_pos ? d.S : 1, d.H, (int32_t)d.L, d.rope_pos);
+      launch_rope(false, r, s, "draft_rope_q");
+    }
+    AttnArgs a = attn_args(d);
+    a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
+    a.tree = tree_mask; a.n_true = n_true; a.tree_words = mask_words;
+    launch_attn_fwd_f32(a, s);
+    GemmArgs out = gemm_nn(o, p->wo, y, d.S, d.D, d.HD);
+    out.R = x_draft; out.ldr = d.D;
+    launch_gemm_f32(group1(out), s, "draft_proj_out");
+  }
+  // h = MLP(RMSNorm(y)) + y
+  const void* z = y;
+  if (p->g_mlp) { launch_rmsnorm_fwd(d.bf16, y, p->g_mlp, base + w.z, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_mlp"); z = base + w.z; }
+  if (d.bf16) {
+    launch_block_mlp_bf16(z, p->w_gate, p->w_up, p->w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F, base + w.mlp, s);
+  } else {
+    GemmGroup gu; memset(&gu, 0, sizeof(gu));
+    gu.count = 2;
+    gu.p[0] = gemm_nn(z, p->w_gate, base + w.u, d.S, F, d.D);
+    gu.p[1] = gemm_nn(z, p->w_up, base + w.w, d.S, F, d.D);
+    launch_gemm_f32(gu, s, "draft_mlp_gate_up");
+    launch_silu_mul_fwd(false, base + w.u, base + w.w, base + w.m, d.S * F, s);
+    GemmArgs dn = gemm_nn(base + w.m, p->w_down, h, d.S, d.D, F);
+    dn.R = y; dn.ldr = d.D;
+    launch_gemm_f32(group1(dn), s, "draft_mlp_down");
+  }
   return hip_status();
 }

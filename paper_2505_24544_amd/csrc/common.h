@@ -176,11 +176,17 @@ struct DecodeArgs {
   const uint32_t* tree; int32_t n_true, tree_words;
   // rotary embedding of the queries (rope != 0): positions rope_pos[m] (device) or all at L
   int32_t rope; float rope_base; const int32_t* rope_pos;
+  const void* y_res;   // optional residual added to y (storage type, [M,D])
 };
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
 size_t kv_append_bf16_ws_bytes(int32_t n, int32_t N, int32_t K);
 bool kv_append_bf16_fits(int32_t n, int32_t N, int32_t K);
+// feed-forward layer for a handful of rows: h = (silu(z W_gate) * (z W_up)) W_down + y_res
+size_t block_mlp_bf16_ws_bytes(int32_t M, int32_t D, int32_t F);
+bool block_mlp_bf16_fits(int32_t D, int32_t F);
+void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, const void* w_down, const void* y_res,
+                           void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
 void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
                            int32_t K, void* ws, hipStream_t s);
 

@@ -200,11 +200,11 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
   }
 }
 
-// y[m][n] = sum_ks part[ks][m][n]  -> bf16
+// y[m][n] = sum_ks part[ks][m][n] (+ res[m][n])  -> bf16
 __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ part, bf16_t* __restrict__ y,
                                                          int64_t MN, int KS, const float* __restrict__ part_z1,
-                                                         bf16_t* __restrict__ y_z1) {
-  if (blockIdx.z == 1) { part = part_z1; y = y_z1; }
+                                                         bf16_t* __restrict__ y_z1, const bf16_t* __restrict__ res) {
+  if (blockIdx.z == 1) { part = part_z1; y = y_z1; res = nullptr; }
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
   float4 s = *(const float4*)(part + i);
@@ -212,8 +212,29 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
     const float4 t = *(const float4*)(part + (int64_t)k * MN + i);
     s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
   }
+  if (res) {                                  // residual connection of Eq. 1
+    const uint2 r = *(const uint2*)(res + i);
+    s.x += __uint_as_float(r.x << 16); s.y += __uint_as_float(r.x & 0xffff0000u);
+    s.z += __uint_as_float(r.y << 16); s.w += __uint_as_float(r.y & 0xffff0000u);
+  }
   uint2 v = {cvt_pk(s.x, s.y), cvt_pk(s.z, s.w)};
   *(uint2*)(y + i) = v;
+}
+
+// m[i] = silu(sum_ks upart[ks][i]) * sum_ks wpart[ks][i]  -> bf16   (gate of the feed-forward layer, Eq. 1)
+__global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__ upart, const float* __restrict__ wpart,
+                                                       bf16_t* __restrict__ m, int64_t MN, int KS) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= MN) return;
+  float4 u = *(const float4*)(upart + i), w = *(const float4*)(wpart + i);
+  for (int k = 1; k < KS; ++k) {
+    const float4 a = *(const float4*)(upart + (int64_t)k * MN + i), b = *(const float4*)(wpart + (int64_t)k * MN + i);
+    u.x += a.x; u.y += a.y; u.z += a.z; u.w += a.w;
+    w.x += b.x; w.y += b.y; w.z += b.z; w.w += b.w;
+  }
+  auto silu = [](float t) { return t / (1.f + expf(-t)); };
+  uint2 v = {cvt_pk(silu(u.x) * w.x, silu(u.y) * w.y), cvt_pk(silu(u.z) * w.z, silu(u.w) * w.w)};
+  *(uint2*)(m + i) = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -643,7 +664,8 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       ProfScope ps("draft_sum_out", s);
       const int64_t MN = (int64_t)Mp * a.D;
       hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, s, ypart,
-                         (bf16_t*)a.y + (int64_t)m0 * a.D, MN, w.KSo, (const float*)nullptr, (bf16_t*)nullptr);
+                         (bf16_t*)a.y + (int64_t)m0 * a.D, MN, w.KSo, (const float*)nullptr, (bf16_t*)nullptr,
+                         a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr);
     }
   }
 }
@@ -672,7 +694,69 @@ void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* 
     ProfScope ps("kv_append_sum", s);
     const int64_t MN = (int64_t)n * N;
     hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((MN / 4 + 255) / 256), 1, 2), dim3(256), 0, s, kpart,
-                       (bf16_t*)kdst, MN, KS, (const float*)vpart, (bf16_t*)vdst);
+                       (bf16_t*)kdst, MN, KS, (const float*)vpart, (bf16_t*)vdst, (const bf16_t*)nullptr);
+  }
+}
+
+
+// ---- feed-forward layer of the draft block for a handful of rows (decode time): HBM-bound on the three weight
+// matrices, so the same split-k streaming projection: [z W_gate, z W_up] in one launch (z = 0 / 1), the gate fused
+// into their slice sum, then m W_down with the residual added in its slice sum.  Rows are taken MAXM at a time.
+namespace {
+struct MlpLayout { int KSg, KSd; size_t upart, wpart, m, dpart, total; };
+MlpLayout mlp_layout(int M, int D, int F) {
+  MlpLayout w;
+  const int Mp = M < dec::MAXM ? M : dec::MAXM;
+  w.KSg = (D + dec::SG_K - 1) / dec::SG_K;
+  w.KSd = (F + dec::SG_K - 1) / dec::SG_K;
+  size_t o = 0;
+  w.upart = o; o += up256((size_t)w.KSg * Mp * F * 4);
+  w.wpart = o; o += up256((size_t)w.KSg * Mp * F * 4);
+  w.m = o; o += up256((size_t)Mp * F * 2);
+  w.dpart = o; o += up256((size_t)w.KSd * Mp * D * 4);
+  w.total = o;
+  return w;
+}
+}  // namespace
+
+size_t block_mlp_bf16_ws_bytes(int32_t M, int32_t D, int32_t F) { return mlp_layout(M, D, F).total; }
+bool block_mlp_bf16_fits(int32_t D, int32_t F) {
+  return D % dec::SG_N == 0 && F % dec::SG_N == 0 && (int64_t)D * F * 2 < ((int64_t)1 << 31);
+}
+void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, const void* w_down, const void* y_res,
+                           void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s) {
+  using namespace dec;
+  const MlpLayout w = mlp_layout(M, D, F);
+  char* base = (char*)ws;
+  float* upart = (float*)(base + w.upart);
+  float* wpart = (float*)(base + w.wpart);
+  bf16_t* mbuf = (bf16_t*)(base + w.m);
+  float* dpart = (float*)(base + w.dpart);
+  for (int m0 = 0; m0 < M; m0 += MAXM) {
+    const int Mp = M - m0 < MAXM ? M - m0 : MAXM;
+    const bf16_t* zr = (const bf16_t*)z + (int64_t)m0 * D;
+    {
+      ProfScope ps("draft_mlp_gate_up", s);
+      hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(F / SG_N, w.KSg, 2), dim3(256), 0, s, zr, (const bf16_t*)w_gate,
+                         upart, Mp, F, D, CombineArgs{}, (const bf16_t*)w_up, wpart);
+    }
+    {
+      ProfScope ps("draft_mlp_gate", s);
+      const int64_t MN = (int64_t)Mp * F;
+      hipLaunchKernelGGL(sum_gate_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, s, upart, wpart, mbuf, MN, w.KSg);
+    }
+    {
+      ProfScope ps("draft_mlp_down", s);
+      hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(D / SG_N, w.KSd), dim3(256), 0, s, (const bf16_t*)mbuf,
+                         (const bf16_t*)w_down, dpart, Mp, D, F, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
+    }
+    {
+      ProfScope ps("draft_mlp_sum", s);
+      const int64_t MN = (int64_t)Mp * D;
+      hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((MN / 4 + 255) / 256)), dim3(256), 0, s, dpart,
+                         (bf16_t*)h + (int64_t)m0 * D, MN, w.KSd, (const float*)nullptr, (bf16_t*)nullptr,
+                         (const bf16_t*)y_res + (int64_t)m0 * D);
+    }
   }
 }
 
