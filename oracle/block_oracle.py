@@ -105,15 +105,27 @@ def mlp_backward(dout, z, w_gate, w_up, w_down):
 # The block (Eq. 1)
 # --------------------------------------------------------------------------
 def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
-                  rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None):
+                  rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None, xpred=None, t=0):
     """e [B,S,D] token embeddings, hs [B,L,D] key/value states.  Returns dict with
     h [B,S,D] (the block's output), y (after the first residual), the normalised
     inputs xq, xkv, z, the attention's own results (attn: the dict of
-    xattn_forward) and the MLP's (mlp)."""
+    xattn_forward) and the MLP's (mlp).
+    xpred [B,L,D], t: late-stage simulation step t (section 4.2, second half) --
+    the attention is beagle_oracle.xattn_forward_sim; the predicted states are
+    key/value source states like hs (they are this block's own earlier outputs
+    h), so they pass through the same normalisation g_kv (xp in the result)."""
     e, hs = np.asarray(e, F64), np.asarray(hs, F64)
     xq = rmsnorm(e, g_q, rms_eps)
     xkv = rmsnorm(hs, g_kv, rms_eps)
     mask = orc.dense_mask(e.shape[1], hs.shape[1], k, eps)
+    if xpred is not None:
+        xp = rmsnorm(xpred, g_kv, rms_eps)
+        attn = orc.xattn_forward_sim(xq, xkv, xp, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k,
+                                     eps=eps, t=t, scale=scale, rope=rope)
+        y = attn["y"] + e
+        z = rmsnorm(y, g_mlp, rms_eps)
+        mlp = mlp_forward(z, w_gate, w_up, w_down)
+        return dict(h=mlp["out"] + y, y=y, xq=xq, xkv=xkv, xp=xp, z=z, attn=attn, mlp=mlp, mask=mask)
     attn = orc.xattn_forward(xq, xkv, wq, wk, wv, wo, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, mask=mask,
                              scale=scale, rope=rope)
     y = attn["y"] + e                                   # Eq. 1, second line
@@ -124,12 +136,26 @@ def block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv
 
 
 def block_backward(dh, e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, *, g_q=None, g_kv=None, g_mlp=None,
-                   rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None):
+                   rms_eps=1e-5, n_q_heads, n_kv_heads, k, eps=0, scale=None, rope=None, xpred=None, t=0):
     """Gradients of sum(dh * h) w.r.t. every input of block_forward: de, dhs, the
-    seven weight matrices and the three gains (None where the gain is None)."""
+    seven weight matrices and the three gains (None where the gain is None); with
+    xpred also dxpred, and g_kv's gradient collects both key/value sources."""
     dh = np.asarray(dh, F64)
     f = block_forward(e, hs, wq, wk, wv, wo, w_gate, w_up, w_down, g_q=g_q, g_kv=g_kv, g_mlp=g_mlp,
-                      rms_eps=rms_eps, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k, eps=eps, scale=scale, rope=rope)
+                      rms_eps=rms_eps, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, k=k, eps=eps, scale=scale, rope=rope,
+                      xpred=xpred, t=t)
+    if xpred is not None:
+        mb = mlp_backward(dh, f["z"], w_gate, w_up, w_down)
+        dy_norm, dg_mlp = rmsnorm_backward(mb["dz"], f["y"], g_mlp, rms_eps)
+        dy = dh + dy_norm
+        ab = orc.xattn_backward_sim(dy, f["xq"], f["xkv"], f["xp"], wq, wk, wv, wo, n_q_heads=n_q_heads,
+                                    n_kv_heads=n_kv_heads, k=k, eps=eps, t=t, scale=scale, rope=rope)
+        de_norm, dg_q = rmsnorm_backward(ab["dxq"], e, g_q, rms_eps)
+        dhs, dg_kv = rmsnorm_backward(ab["dxkv"], hs, g_kv, rms_eps)
+        dxpred, dg_kv2 = rmsnorm_backward(ab["dxpred"], xpred, g_kv, rms_eps)
+        return dict(de=dy + de_norm, dhs=dhs, dxpred=dxpred, dwq=ab["dwq"], dwk=ab["dwk"], dwv=ab["dwv"], dwo=ab["dwo"],
+                    dw_gate=mb["dw_gate"], dw_up=mb["dw_up"], dw_down=mb["dw_down"], dg_q=dg_q,
+                    dg_kv=None if g_kv is None else dg_kv + dg_kv2, dg_mlp=dg_mlp, dy=dy, fwd=f)
     # h = MLP(z) + y
     mb = mlp_backward(dh, f["z"], w_gate, w_up, w_down)
     dy_norm, dg_mlp = rmsnorm_backward(mb["dz"], f["y"], g_mlp, rms_eps)

@@ -211,3 +211,35 @@ def test_block_draft_step_reproduces_the_training_block_row(gains, rope):
                              **dkw, n_true=p - 2, tree_mask=tm)
     b = blk.block_draft_step(c["e"][0, p:p + 1], kc[:p - 1], vc[:p - 1], c["wq"], c["wo"], c["w_gate"], c["w_up"], c["w_down"], **dkw)
     assert np.allclose(a["h"], b["h"], atol=1e-13)
+
+
+# ------------------------------------------------------------------ the block in a late-stage simulation step
+def test_block_simulation_step_zero_is_the_plain_block_and_gradients_check():
+    c, kw, dh = _case(seed=8)
+    xp = np.random.default_rng(11).normal(size=c["hs"].shape) * 3
+    a = blk.block_backward(dh, **c, **kw, xpred=xp, t=0)
+    b = blk.block_backward(dh, **c, **kw)
+    for n in ("de", "dhs", "dwq", "dwk", "dw_gate", "dg_q", "dg_kv", "dg_mlp"):
+        assert np.allclose(a[n], b[n], atol=1e-12), n
+    assert np.allclose(a["fwd"]["h"], b["fwd"]["h"], atol=1e-13) and not a["dxpred"].any()
+    # t = 2: something changes, and every gradient agrees with finite differences (xpred and g_kv included:
+    # the gain sees both key/value sources)
+    g = blk.block_backward(dh, **c, **kw, xpred=xp, t=2)
+    assert not np.allclose(g["fwd"]["h"], b["fwd"]["h"], atol=1e-6) and g["dxpred"].any()
+    rng = np.random.default_rng(12)
+    loss = lambda cc, kk, x: float((blk.block_forward(**cc, **kk, xpred=x, t=2)["h"] * dh).sum())
+    for n, gn in (("e", "de"), ("hs", "dhs"), ("wk", "dwk"), ("wv", "dwv"), ("w_up", "dw_up")):
+        d = rng.normal(size=c[n].shape)
+        fd = (loss(dict(c, **{n: c[n] + 1e-6 * d}), kw, xp) - loss(dict(c, **{n: c[n] - 1e-6 * d}), kw, xp)) / 2e-6
+        assert abs(fd - (g[gn] * d).sum()) <= 2e-6 * max(1.0, abs(fd)), n
+    d = rng.normal(size=xp.shape)
+    fd = (loss(c, kw, xp + 1e-6 * d) - loss(c, kw, xp - 1e-6 * d)) / 2e-6
+    assert abs(fd - (g["dxpred"] * d).sum()) <= 2e-6 * max(1.0, abs(fd))
+    d = rng.normal(size=kw["g_kv"].shape)
+    fd = (loss(c, dict(kw, g_kv=kw["g_kv"] + 1e-6 * d), xp) - loss(c, dict(kw, g_kv=kw["g_kv"] - 1e-6 * d), xp)) / 2e-6
+    assert abs(fd - (g["dg_kv"] * d).sum()) <= 2e-6 * max(1.0, abs(fd))
+    # the predicted states pass through the key/value normalisation: scaling them changes nothing at rms_eps = 0
+    kw0 = dict(kw, rms_eps=0.0)
+    h1 = blk.block_forward(**c, **kw0, xpred=xp, t=2)["h"]
+    h2 = blk.block_forward(**c, **kw0, xpred=7.0 * xp, t=2)["h"]
+    assert np.allclose(h1, h2, atol=1e-12)
