@@ -295,6 +295,9 @@ typedef struct {
   void *y;                      /* [B,S,D] after the first residual              */
   void *z;     float *r_mlp;    /* [B,S,D] normalised y, [B*S]                   */
   void *u, *w, *m;              /* [B,S,F] z W_gate, z W_up, silu(u) * w         */
+  /* simulation entry points only */
+  void *xp_n;  float *r_p;      /* [B,L,D] normalised xpred, [B*L] (with g_kv)   */
+  void *kp, *vp;                /* [B,L,G,d] K, V of the predicted states        */
 } beagle_block_saved;
 
 typedef struct {
@@ -303,9 +306,10 @@ typedef struct {
   void *dwq, *dwk, *dwv, *dwo;  /* like the weights (io_dtype)                   */
   void *dw_gate, *dw_up, *dw_down;
   float *dg_q, *dg_kv, *dg_mlp; /* [D] float; required iff the gain is given     */
+  void *dxpred;                 /* [B,L,D]; simulation entry points only         */
 } beagle_block_grads;
 
-enum { BEAGLE_WS_BLOCK_FWD = 0, BEAGLE_WS_BLOCK_BWD = 1, BEAGLE_WS_BLOCK_DRAFT = 2 };
+enum { BEAGLE_WS_BLOCK_FWD = 0, BEAGLE_WS_BLOCK_BWD = 1, BEAGLE_WS_BLOCK_DRAFT = 2, BEAGLE_WS_BLOCK_BWD_SIM = 3 };
 
 /* Workspace bytes of the two block entry points (`which` is BEAGLE_WS_BLOCK_*);
  * 0 for an invalid descriptor / ffn. */
@@ -330,6 +334,25 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
 beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* params,
     const void* dh, const void* e, const void* hs, const beagle_block_saved* saved,
     const beagle_block_grads* grads, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The block in a late-stage simulation step (section 4.2, second half): as
+ * beagle_xattn_block_fwd / _bwd with the attention of beagle_xattn_fwd_sim /
+ * _bwd_sim.  The predicted states xpred [B,L,D] are this block's own earlier
+ * outputs h, written into the buffer by beagle_xattn_sim_save; as key/value
+ * source states they pass through the same normalisation as hs (g_kv, whose
+ * gradient then collects both sources).  sim_step = 0 is the plain block.
+ * Requires seq_q == seq_kv.  saved->kp, vp (and xp_n, r_p with g_kv) and
+ * grads->dxpred are required.  Workspace: BEAGLE_WS_BLOCK_FWD for the forward,
+ * BEAGLE_WS_BLOCK_BWD_SIM for the backward.
+ */
+beagle_status beagle_xattn_block_fwd_sim(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* e, const void* hs, const void* xpred, int32_t sim_step, void* h, const beagle_block_saved* saved,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+beagle_status beagle_xattn_block_bwd_sim(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* dh, const void* e, const void* hs, const void* xpred, int32_t sim_step,
+    const beagle_block_saved* saved, const beagle_block_grads* grads,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * The block at decode time (section 4.1, last paragraphs: the same block

@@ -22,7 +22,7 @@ BEAGLE_OK = 0
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
 BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32, BEAGLE_FLAG_ROPE, BEAGLE_FLAG_STATES_F16 = 1, 2, 4, 8
 BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
-BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD, BEAGLE_WS_BLOCK_DRAFT = 0, 1, 2
+BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD, BEAGLE_WS_BLOCK_DRAFT, BEAGLE_WS_BLOCK_BWD_SIM = 0, 1, 2, 3
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
                 4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
 
@@ -31,7 +31,7 @@ EXPORTS = (
     "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
-    "beagle_xattn_block_draft_step",
+    "beagle_xattn_block_draft_step", "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -75,12 +75,12 @@ class beagle_block_params(C.Structure):
 
 class beagle_block_saved(C.Structure):
     _fields_ = [(n, _VP) for n in ("xq_n", "r_q", "xkv_n", "r_kv", "q", "k", "v", "o", "lse", "y", "z", "r_mlp",
-                                   "u", "w", "m")]
+                                   "u", "w", "m", "xp_n", "r_p", "kp", "vp")]
 
 
 class beagle_block_grads(C.Structure):
     _fields_ = [(n, _VP) for n in ("de", "dhs", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down",
-                                   "dg_q", "dg_kv", "dg_mlp")]
+                                   "dg_q", "dg_kv", "dg_mlp", "dxpred")]
 
 
 def _fill(struct, tensors: dict):
@@ -144,6 +144,12 @@ def lib() -> C.CDLL:
     L.beagle_xattn_block_bwd.restype = C.c_int
     L.beagle_xattn_block_bwd.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.POINTER(beagle_block_saved),
                                          C.POINTER(beagle_block_grads), vp, C.c_size_t, vp]
+    L.beagle_xattn_block_fwd_sim.restype = C.c_int
+    L.beagle_xattn_block_fwd_sim.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp,
+                                             C.POINTER(beagle_block_saved), vp, C.c_size_t, vp]
+    L.beagle_xattn_block_bwd_sim.restype = C.c_int
+    L.beagle_xattn_block_bwd_sim.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, vp, C.c_int32,
+                                             C.POINTER(beagle_block_saved), C.POINTER(beagle_block_grads), vp, C.c_size_t, vp]
     L.beagle_xattn_block_draft_step.restype = C.c_int
     L.beagle_xattn_block_draft_step.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp, C.c_int32,
                                                 vp, vp, vp, C.c_size_t, vp]
@@ -242,6 +248,23 @@ def beagle_xattn_block_bwd(desc, params, dh, e, hs, saved, grads, workspace, str
         C.byref(saved) if saved is not None else None, C.byref(grads) if grads is not None else None,
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_block_bwd", check)
+
+
+def beagle_xattn_block_fwd_sim(desc, params, e, hs, xpred, sim_step, h, saved, workspace=None, stream=None, *,
+                               workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_block_fwd_sim(
+        C.byref(desc), C.byref(params), _ptr(e), _ptr(hs), _ptr(xpred), int(sim_step), _ptr(h), C.byref(saved),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_block_fwd_sim", check)
+
+
+def beagle_xattn_block_bwd_sim(desc, params, dh, e, hs, xpred, sim_step, saved, grads, workspace, stream=None, *,
+                               workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_block_bwd_sim(
+        C.byref(desc), C.byref(params), _ptr(dh), _ptr(e), _ptr(hs), _ptr(xpred), int(sim_step), C.byref(saved),
+        C.byref(grads), _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes,
+        _stream(stream))
+    return _check(st, "beagle_xattn_block_bwd_sim", check)
 
 
 def beagle_xattn_block_draft_step(desc, params, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words, h, lse,

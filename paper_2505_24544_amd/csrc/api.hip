@@ -247,6 +247,105 @@ void xattn_bwd_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, con
   }
 }
 
+// The simulation step's forward: as xattn_fwd_run, plus the predicted states' K / V and the band merge.
+void xattn_fwd_sim_run(const Dims& d, const void* xq, const void* xkv, const void* xpred, const void* wq, const void* wk,
+                       const void* wv, const void* wo, int32_t sim_step, void* y, float* lse, void* q_save, void* k_save,
+                       void* v_save, void* kp_save, void* vp_save, void* o_save, const void* y_res, hipStream_t s) {
+  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
+  qkv.count = 3;
+  qkv.p[0] = gemm_nn(xq, wq, q_save, d.Tq, d.HD, d.D);
+  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.Tk, d.GD, d.D);
+  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.Tk, d.GD, d.D);
+  run_gemm(d, qkv, s, "proj_qkv");
+  GemmGroup kvp; memset(&kvp, 0, sizeof(kvp));
+  kvp.count = 2;
+  kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.Tk, d.GD, d.D);
+  kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.Tk, d.GD, d.D);
+  run_gemm(d, kvp, s, "proj_kvp");
+  if (d.rope) {   // a predicted state stands at its own sequence position
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, q_save, d.Tq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, k_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
+    rope_add(r, kp_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
+    launch_rope(d.bf16, r, s, "rope_qk");
+  }
+
+  SimArgs sa; memset(&sa, 0, sizeof(sa));
+  sa.a = attn_args(d);
+  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = o_save; sa.a.lse = lse;
+  sa.kp = kp_save; sa.vp = vp_save; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
+  if (d.bf16) launch_attn_fwd_bf16(sa.a, s); else launch_attn_fwd_f32(sa.a, s);
+  if (sim_step > 0) launch_sim_band_fwd(sa, s);
+
+  GemmArgs out = gemm_nn(o_save, wo, y, d.Tq, d.D, d.HD);
+  out.R = y_res; out.ldr = d.D;
+  run_gemm(d, group1(out), s, "proj_out");
+}
+
+// The simulation step's backward; `base` is a workspace of BEAGLE_WS_BWD_SIM bytes (without the converted states).
+void xattn_bwd_sim_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy, const void* xq, const void* xkv,
+                       const void* xpred, const void* wq, const void* wk, const void* wv, const void* wo,
+                       const void* q_save, const void* k_save, const void* v_save, const void* kp_save,
+                       const void* vp_save, const void* o_save, const float* lse, int32_t sim_step, void* dxq, void* dxkv,
+                       void* dxpred, void* dwq, void* dwk, void* dwv, void* dwo, char* base, const void* dxq_res,
+                       hipStream_t s) {
+  const BwdWs w = bwd_layout(d);
+  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
+  float* delta = (float*)(base + w.delta);
+  size_t extra = 0;
+  if (d.bf16) { AttnArgs t = attn_args(d); extra = attn_bwd_bf16_ws_bytes(t); }
+  const size_t kvb = align_up((size_t)(d.Tk * d.GD) * d.esz);
+  void* dKp = base + w.total + align_up(extra);
+  void* dVp = (char*)dKp + kvb;
+  const int64_t Mq = d.Tq, Mk = d.Tk;
+
+  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
+  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
+
+  // true-key part: the main kernels, given the merged LSE and delta = rowsum(dO * O) of the merged O
+  SimArgs sa; memset(&sa, 0, sizeof(sa));
+  sa.a = attn_args(d);
+  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = (void*)o_save; sa.a.lse = (float*)lse;
+  sa.a.dout = dO; sa.a.dq = dQ; sa.a.dk = dK; sa.a.dv = dV; sa.a.delta = delta;
+  sa.kp = kp_save; sa.vp = vp_save; sa.dkp = dKp; sa.dvp = dVp; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
+  if (d.bf16) launch_attn_bwd_bf16(sa.a, base + w.attn, s); else launch_attn_bwd_f32(sa.a, s);
+  // predicted-key band: adds to dQ, writes dKp and dVp (zeros where nothing is seen)
+  launch_sim_band_bwd(sa, s);
+  if (d.rope) {
+    RopeArgs r = rope_args(d, true);
+    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr, d.cu_q);
+    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
+    rope_add(r, dKp, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
+    launch_rope(d.bf16, r, s, "bwd_rope_qk");
+  }
+
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 2;
+    g.p[0] = gemm_nt(dKp, wk, dxpred, Mk, d.D, d.GD);
+    g.p[0].A2 = dVp; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
+    g.p[1] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
+    g.p[1].R = dxq_res; g.p[1].ldr = d.D;
+    if (need_dxkv) {
+      g.count = 3;
+      g.p[2] = g.p[1];
+      g.p[1] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
+      g.p[1].A2 = dV; g.p[1].B2 = wv; g.p[1].K2 = (int32_t)d.GD; g.p[1].lda2 = d.GD; g.p[1].ldb2 = d.GD;
+    }
+    run_gemm(d, g, s, "bwd_dx");
+  }
+  {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 3;
+    g.p[0] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);        // two k segments: true and predicted rows
+    g.p[0].A2 = xpred; g.p[0].B2 = dKp; g.p[0].K2 = (int32_t)Mk; g.p[0].lda2 = d.D; g.p[0].ldb2 = d.GD;
+    g.p[1] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
+    g.p[1].A2 = xpred; g.p[1].B2 = dVp; g.p[1].K2 = (int32_t)Mk; g.p[1].lda2 = d.D; g.p[1].ldb2 = d.GD;
+    g.p[2] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
+    run_gemm(d, g, s, "bwd_dw");
+  }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ profiler
@@ -471,33 +570,8 @@ beagle_status beagle_xattn_fwd_sim(const beagle_xattn_desc* desc,
   (void)hipGetLastError();
   xkv = states_in(d, xkv, workspace, need_ws, s);
 
-  GemmGroup qkv; memset(&qkv, 0, sizeof(qkv));
-  qkv.count = 3;
-  qkv.p[0] = gemm_nn(xq, wq, q_save, d.Tq, d.HD, d.D);
-  qkv.p[1] = gemm_nn(xkv, wk, k_save, d.Tk, d.GD, d.D);
-  qkv.p[2] = gemm_nn(xkv, wv, v_save, d.Tk, d.GD, d.D);
-  run_gemm(d, qkv, s, "proj_qkv");
-  GemmGroup kvp; memset(&kvp, 0, sizeof(kvp));
-  kvp.count = 2;
-  kvp.p[0] = gemm_nn(xpred, wk, kp_save, d.Tk, d.GD, d.D);
-  kvp.p[1] = gemm_nn(xpred, wv, vp_save, d.Tk, d.GD, d.D);
-  run_gemm(d, kvp, s, "proj_kvp");
-  if (d.rope) {   // a predicted state stands at its own sequence position
-    RopeArgs r = rope_args(d, false);
-    rope_add(r, q_save, d.Tq, d.S, d.H, 0, nullptr, d.cu_q);
-    rope_add(r, k_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
-    rope_add(r, kp_save, d.Tk, d.L, d.G, 0, nullptr, d.cu_kv);
-    launch_rope(d.bf16, r, s, "rope_qk");
-  }
-
-  SimArgs sa; memset(&sa, 0, sizeof(sa));
-  sa.a = attn_args(d);
-  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = o_save; sa.a.lse = lse;
-  sa.kp = kp_save; sa.vp = vp_save; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
-  if (d.bf16) launch_attn_fwd_bf16(sa.a, s); else launch_attn_fwd_f32(sa.a, s);
-  if (sim_step > 0) launch_sim_band_fwd(sa, s);
-
-  run_gemm(d, group1(gemm_nn(o_save, wo, y, d.Tq, d.D, d.HD)), s, "proj_out");
+  xattn_fwd_sim_run(d, xq, xkv, xpred, wq, wk, wv, wo, sim_step, y, lse, q_save, k_save, v_save, kp_save, vp_save, o_save,
+                    nullptr, s);
   return hip_status();
 }
 
@@ -538,62 +612,9 @@ beagle_status beagle_xattn_bwd_sim(const beagle_xattn_desc* desc,
   (void)hipGetLastError();
   xkv = states_in(d, xkv, workspace, beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM), s);
 
-  const BwdWs w = bwd_layout(d);
-  char* base = (char*)workspace;
-  void* dO = base + w.dO; void* dQ = base + w.dQ; void* dK = base + w.dK; void* dV = base + w.dV;
-  float* delta = (float*)(base + w.delta);
-  size_t extra = 0;
-  if (d.bf16) { AttnArgs t = attn_args(d); extra = attn_bwd_bf16_ws_bytes(t); }
-  const size_t kvb = align_up((size_t)(d.Tk * d.GD) * d.esz);
-  void* dKp = base + w.total + align_up(extra);
-  void* dVp = (char*)dKp + kvb;
-  const bool wf32 = d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32);
-  const int64_t Mq = d.Tq, Mk = d.Tk;
-
-  run_gemm(d, group1(gemm_nt(dy, wo, dO, Mq, d.HD, d.D)), s, "bwd_dout");
-  run_gemm(d, group1(gemm_tn(o_save, dy, dwo, d.HD, d.D, Mq, wf32)), s, "bwd_dwo");
-
-  // true-key part: the main kernels, given the merged LSE and delta = rowsum(dO * O) of the merged O
-  SimArgs sa; memset(&sa, 0, sizeof(sa));
-  sa.a = attn_args(d);
-  sa.a.q = q_save; sa.a.k = k_save; sa.a.v = v_save; sa.a.o = (void*)o_save; sa.a.lse = (float*)lse;
-  sa.a.dout = dO; sa.a.dq = dQ; sa.a.dk = dK; sa.a.dv = dV; sa.a.delta = delta;
-  sa.kp = kp_save; sa.vp = vp_save; sa.dkp = dKp; sa.dvp = dVp; sa.t = sim_step; sa.is_bf16 = d.bf16 ? 1 : 0;
-  if (d.bf16) launch_attn_bwd_bf16(sa.a, base + w.attn, s); else launch_attn_bwd_f32(sa.a, s);
-  // predicted-key band: adds to dQ, writes dKp and dVp (zeros where nothing is seen)
-  launch_sim_band_bwd(sa, s);
-  if (d.rope) {
-    RopeArgs r = rope_args(d, true);
-    rope_add(r, dQ, Mq, d.S, d.H, 0, nullptr, d.cu_q);
-    rope_add(r, dK, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
-    rope_add(r, dKp, Mk, d.L, d.G, 0, nullptr, d.cu_kv);
-    launch_rope(d.bf16, r, s, "bwd_rope_qk");
-  }
-
-  {
-    GemmGroup g; memset(&g, 0, sizeof(g));
-    g.count = 2;
-    g.p[0] = gemm_nt(dKp, wk, dxpred, Mk, d.D, d.GD);
-    g.p[0].A2 = dVp; g.p[0].B2 = wv; g.p[0].K2 = (int32_t)d.GD; g.p[0].lda2 = d.GD; g.p[0].ldb2 = d.GD;
-    g.p[1] = gemm_nt(dQ, wq, dxq, Mq, d.D, d.HD);
-    if (need_dxkv) {
-      g.count = 3;
-      g.p[2] = g.p[1];
-      g.p[1] = gemm_nt(dK, wk, dxkv, Mk, d.D, d.GD);
-      g.p[1].A2 = dV; g.p[1].B2 = wv; g.p[1].K2 = (int32_t)d.GD; g.p[1].lda2 = d.GD; g.p[1].ldb2 = d.GD;
-    }
-    run_gemm(d, g, s, "bwd_dx");
-  }
-  {
-    GemmGroup g; memset(&g, 0, sizeof(g));
-    g.count = 3;
-    g.p[0] = gemm_tn(xkv, dK, dwk, d.D, d.GD, Mk, wf32);        // two k segments: true and predicted rows
-    g.p[0].A2 = xpred; g.p[0].B2 = dKp; g.p[0].K2 = (int32_t)Mk; g.p[0].lda2 = d.D; g.p[0].ldb2 = d.GD;
-    g.p[1] = gemm_tn(xkv, dV, dwv, d.D, d.GD, Mk, wf32);
-    g.p[1].A2 = xpred; g.p[1].B2 = dVp; g.p[1].K2 = (int32_t)Mk; g.p[1].lda2 = d.D; g.p[1].ldb2 = d.GD;
-    g.p[2] = gemm_tn(xq, dQ, dwq, d.D, d.HD, Mq, wf32);
-    run_gemm(d, g, s, "bwd_dw");
-  }
+  xattn_bwd_sim_run(d, need_dxkv, d.bf16 && (desc->flags & BEAGLE_FLAG_WGRAD_F32), dy, xq, xkv, xpred, wq, wk, wv, wo, q_save,
+                    k_save, v_save, kp_save, vp_save, o_save, lse, sim_step, dxq, dxkv, dxpred, dwq, dwk, dwv, dwo,
+                    (char*)workspace, nullptr, s);
   return hip_status();
 }
 
@@ -774,15 +795,26 @@ size_t beagle_xattn_block_workspace_bytes(const beagle_xattn_desc* desc, int32_t
   if (which == BEAGLE_WS_BLOCK_FWD) return WS_ALIGN + states_ws(d);
   if (which == BEAGLE_WS_BLOCK_BWD)
     return block_bwd_layout(d, ffn).total + beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD);
+  if (which == BEAGLE_WS_BLOCK_BWD_SIM)   // + the gradient of the normalised predicted states
+    return block_bwd_layout(d, ffn).total + align_up((size_t)(d.Tk * d.D) * d.esz) +
+           beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BWD_SIM);
   return 0;
 }
 
-beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
-    const void* e, const void* hs, void* h, const beagle_block_saved* sv,
+namespace {
+// sim: the attention is the simulation step's (xpred, sim_step); otherwise the early-stage one
+beagle_status block_fwd_impl(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* e, const void* hs, bool sim, const void* xpred, int32_t sim_step, void* h, const beagle_block_saved* sv,
     void* workspace, size_t workspace_bytes, void* hip_stream) {
   Dims d; beagle_status st = check_block(desc, p, &d);
   if (st != BEAGLE_OK) return st;
   if (!sv) return BEAGLE_ERR_NULL;
+  if (sim) {
+    if (!xpred || !sv->kp || !sv->vp || (p->g_kv && (!sv->xp_n || !sv->r_p))) return BEAGLE_ERR_NULL;
+    const void* more[] = {xpred, sv->kp, sv->vp, sv->xp_n, sv->r_p};
+    for (const void* q : more) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+    if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
+  }
   const void* req[] = {e, hs, h, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down,
                        sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->u, sv->w, sv->m};
   for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
@@ -809,7 +841,14 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
   if (p->g_q) { launch_rmsnorm_fwd(d.bf16, e, p->g_q, sv->xq_n, sv->r_q, Mq, D, p->rms_eps, s, "norm_q"); xq = sv->xq_n; }
   if (p->g_kv) { launch_rmsnorm_fwd(d.bf16, hs, p->g_kv, sv->xkv_n, sv->r_kv, Mk, D, p->rms_eps, s, "norm_kv"); xkv = sv->xkv_n; }
   // y = CrossAttn(xkv, xq) + e: the residual is the epilogue operand of the output projection
-  xattn_fwd_run(d, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->y, sv->lse, sv->q, sv->k, sv->v, sv->o, e, s);
+  if (sim) {
+    const void* xp = xpred;     // predicted states are key/value source states: same normalisation as hs
+    if (p->g_kv) { launch_rmsnorm_fwd(d.bf16, xpred, p->g_kv, sv->xp_n, sv->r_p, Mk, D, p->rms_eps, s, "norm_pred"); xp = sv->xp_n; }
+    xattn_fwd_sim_run(d, xq, xkv, xp, p->wq, p->wk, p->wv, p->wo, sim_step, sv->y, sv->lse, sv->q, sv->k, sv->v, sv->kp,
+                      sv->vp, sv->o, e, s);
+  } else {
+    xattn_fwd_run(d, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->y, sv->lse, sv->q, sv->k, sv->v, sv->o, e, s);
+  }
   const void* z = sv->y;
   if (p->g_mlp) { launch_rmsnorm_fwd(d.bf16, sv->y, p->g_mlp, sv->z, sv->r_mlp, Mq, D, p->rms_eps, s, "norm_mlp"); z = sv->z; }
   GemmGroup gu; memset(&gu, 0, sizeof(gu));
@@ -825,12 +864,20 @@ beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle
   return hip_status();
 }
 
-beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
-    const void* dh, const void* e, const void* hs, const beagle_block_saved* sv,
-    const beagle_block_grads* gr, void* workspace, size_t workspace_bytes, void* hip_stream) {
+beagle_status block_bwd_impl(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* dh, const void* e, const void* hs, bool sim, const void* xpred, int32_t sim_step,
+    const beagle_block_saved* sv, const beagle_block_grads* gr, void* workspace, size_t workspace_bytes,
+    void* hip_stream) {
   Dims d; beagle_status st = check_block(desc, p, &d);
   if (st != BEAGLE_OK) return st;
   if (!sv || !gr) return BEAGLE_ERR_NULL;
+  if (sim) {
+    if (!xpred || !sv->kp || !sv->vp || !gr->dxpred || (p->g_kv && (!sv->xp_n || !sv->r_p))) return BEAGLE_ERR_NULL;
+    const void* more[] = {xpred, sv->kp, sv->vp, sv->xp_n, sv->r_p, gr->dxpred};
+    for (const void* q : more) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+    if (sim_step < 0 || d.S != d.L || d.Tq != d.Tk) return BEAGLE_ERR_SHAPE;
+  }
+  const int ws_kind = sim ? BEAGLE_WS_BLOCK_BWD_SIM : BEAGLE_WS_BLOCK_BWD;
   const bool need_dhs = desc->flags & BEAGLE_FLAG_NEED_DXKV;
   const void* req[] = {dh, e, hs, p->wq, p->wk, p->wv, p->wo, p->w_gate, p->w_up, p->w_down,
                        sv->q, sv->k, sv->v, sv->o, sv->lse, sv->y, sv->u, sv->w, sv->m,
@@ -846,14 +893,14 @@ beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle
                        gr->dw_gate, gr->dw_up, gr->dw_down, gr->dg_q, gr->dg_kv, gr->dg_mlp};
   for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
   if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
-  if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_BWD)) return BEAGLE_ERR_WORKSPACE;
+  if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, ws_kind)) return BEAGLE_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
   const int64_t Mq = d.Tq, Mk = d.Tk, F = p->ffn;
   const int D = (int)d.D;
   const BlockWs w = block_bwd_layout(d, F);
   char* base = (char*)workspace;
-  hs = states_in(d, hs, workspace, beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_BWD), s);
+  hs = states_in(d, hs, workspace, beagle_xattn_block_workspace_bytes(desc, p->ffn, ws_kind), s);
   void* dm = base + w.dm; void* dwp = base + w.dw; void* dz = base + w.dz; void* dy = base + w.dy;
   void* dxq_n = base + w.dxq; void* dxkv_n = base + w.dxkv; float* part = (float*)(base + w.part);
 
@@ -886,14 +933,48 @@ beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle
   const void* xkv = p->g_kv ? sv->xkv_n : hs;
   void* dxq_out = p->g_q ? dxq_n : gr->de;
   void* dxkv_out = p->g_kv ? dxkv_n : gr->dhs;
-  xattn_bwd_run(d, need_dxkv, false, dy, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->q, sv->k, sv->v, sv->o, sv->lse,
-                dxq_out, dxkv_out, gr->dwq, gr->dwk, gr->dwv, gr->dwo, base + w.attn, p->g_q ? nullptr : dy, s);
+  void* dxp_n = base + w.attn;                      // simulation only: gradient of the normalised predicted states
+  if (sim) {
+    char* attn_ws = base + w.attn + align_up((size_t)(Mk * d.D) * d.esz);
+    xattn_bwd_sim_run(d, need_dxkv, false, dy, xq, xkv, p->g_kv ? sv->xp_n : xpred, p->wq, p->wk, p->wv, p->wo, sv->q, sv->k,
+                      sv->v, sv->kp, sv->vp, sv->o, sv->lse, sim_step, dxq_out, dxkv_out, p->g_kv ? dxp_n : gr->dxpred,
+                      gr->dwq, gr->dwk, gr->dwv, gr->dwo, attn_ws, p->g_q ? nullptr : dy, s);
+  } else {
+    xattn_bwd_run(d, need_dxkv, false, dy, xq, xkv, p->wq, p->wk, p->wv, p->wo, sv->q, sv->k, sv->v, sv->o, sv->lse,
+                  dxq_out, dxkv_out, gr->dwq, gr->dwk, gr->dwv, gr->dwo, base + w.attn, p->g_q ? nullptr : dy, s);
+  }
   if (p->g_q)     // de = dy + dRMSNorm(dxq)
     launch_rmsnorm_bwd(d.bf16, dxq_n, e, p->g_q, sv->r_q, dy, gr->de, gr->dg_q, part, Mq, D, s, "bwd_norm_q");
   if (p->g_kv)
     launch_rmsnorm_bwd(d.bf16, dxkv_n, hs, p->g_kv, sv->r_kv, nullptr, need_dhs ? gr->dhs : dxkv_n, gr->dg_kv, part, Mk, D,
                        s, "bwd_norm_kv");
+  if (sim && p->g_kv)   // the same gain normalised the predicted states: its gradient collects both
+    launch_rmsnorm_bwd(d.bf16, dxp_n, xpred, p->g_kv, sv->r_p, nullptr, gr->dxpred, gr->dg_kv, part, Mk, D, s,
+                       "bwd_norm_pred", true);
   return hip_status();
+}
+}  // namespace
+
+beagle_status beagle_xattn_block_fwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* e, const void* hs, void* h, const beagle_block_saved* sv,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return block_fwd_impl(desc, p, e, hs, false, nullptr, 0, h, sv, workspace, workspace_bytes, hip_stream);
+}
+beagle_status beagle_xattn_block_fwd_sim(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* e, const void* hs, const void* xpred, int32_t sim_step, void* h, const beagle_block_saved* sv,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return block_fwd_impl(desc, p, e, hs, true, xpred, sim_step, h, sv, workspace, workspace_bytes, hip_stream);
+}
+beagle_status beagle_xattn_block_bwd(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* dh, const void* e, const void* hs, const beagle_block_saved* sv,
+    const beagle_block_grads* gr, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return block_bwd_impl(desc, p, dh, e, hs, false, nullptr, 0, sv, gr, workspace, workspace_bytes, hip_stream);
+}
+beagle_status beagle_xattn_block_bwd_sim(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* dh, const void* e, const void* hs, const void* xpred, int32_t sim_step,
+    const beagle_block_saved* sv, const beagle_block_grads* gr, void* workspace, size_t workspace_bytes,
+    void* hip_stream) {
+  return block_bwd_impl(desc, p, dh, e, hs, true, xpred, sim_step, sv, gr, workspace, workspace_bytes, hip_stream);
 }
 
 beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* p,

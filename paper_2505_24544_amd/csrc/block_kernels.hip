@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* dout, const T
 // out[c] = sum_p part[p][c] in a fixed order: a workgroup owns 64 columns, its four waves each sum every
 // fourth partial row (eight independent loads in flight), then the four sums are added in wave order.
 __global__ __launch_bounds__(256) void colsum_reduce_kernel(const float* __restrict__ part, float* __restrict__ out,
-                                                            int nparts, int D) {
+                                                            int nparts, int D, int accumulate) {
   __shared__ float red[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
@@ -156,7 +156,10 @@ __global__ __launch_bounds__(256) void colsum_reduce_kernel(const float* __restr
   }
   red[wave][lane] = s;
   __syncthreads();
-  if (wave == 0 && c < D) out[c] = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+  if (wave == 0 && c < D) {
+    const float t = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    out[c] = accumulate ? out[c] + t : t;      // a gain shared by two normalised inputs collects both
+  }
 }
 
 __device__ __forceinline__ float sigmoidf(float u) { return 1.f / (1.f + expf(-u)); }
@@ -224,10 +227,10 @@ void rmsnorm_fwd_t(const void* x, const void* gain, void* out, float* rinv, int6
 }
 template <typename T>
 void rmsnorm_bwd_t(const void* dout, const void* x, const void* gain, const float* rinv, const void* add, void* dx,
-                   float* dgain, float* part, int nparts, int64_t rows, int D, hipStream_t s) {
+                   float* dgain, float* part, int nparts, int64_t rows, int D, bool accumulate, hipStream_t s) {
   hipLaunchKernelGGL(rmsnorm_bwd_kernel<T>, dim3(nparts), dim3(256), (size_t)D * sizeof(float), s, (const T*)dout,
                      (const T*)x, (const T*)gain, rinv, (const T*)add, (T*)dx, part, (int)rows, D);
-  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((D + 63) / 64), dim3(256), 0, s, part, dgain, nparts, D);
+  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((D + 63) / 64), dim3(256), 0, s, part, dgain, nparts, D, accumulate ? 1 : 0);
 }
 
 int elementwise_grid(int64_t n, int per_thread) {
@@ -248,11 +251,11 @@ void launch_rmsnorm_fwd(bool bf16, const void* x, const void* gain, void* out, f
 
 void launch_rmsnorm_bwd(bool bf16, const void* dout, const void* x, const void* gain, const float* rinv,
                         const void* add, void* dx, float* dgain, float* part, int64_t rows, int D, hipStream_t s,
-                        const char* name) {
+                        const char* name, bool accumulate) {
   ProfScope ps(name, s);
   const int nparts = rmsnorm_bwd_parts(rows);
-  if (bf16) rmsnorm_bwd_t<bf16_t>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, s);
-  else rmsnorm_bwd_t<float>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, s);
+  if (bf16) rmsnorm_bwd_t<bf16_t>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, accumulate, s);
+  else rmsnorm_bwd_t<float>(dout, x, gain, rinv, add, dx, dgain, part, nparts, rows, D, accumulate, s);
 }
 
 void launch_cvt_f16(bool bf16, const void* in, void* out, int64_t n, hipStream_t s) {

@@ -68,7 +68,7 @@ void launch_rmsnorm_fwd(bool bf16, const void* x, const void* gain, void* out, f
 // dx = d rmsnorm / dx applied to dout (+ add if given); dgain [D] float; part: rmsnorm_bwd_parts(rows) * D floats
 void launch_rmsnorm_bwd(bool bf16, const void* dout, const void* x, const void* gain, const float* rinv,
                         const void* add, void* dx, float* dgain, float* part, int64_t rows, int D, hipStream_t s,
-                        const char* name);
+                        const char* name, bool accumulate = false);   // accumulate: dgain += instead of =
 // n IEEE half values -> the storage type (n % 8 == 0)
 void launch_cvt_f16(bool bf16, const void* in, void* out, int64_t n, hipStream_t s);
 void launch_silu_mul_fwd(bool bf16, const void* u, const void* w, void* m, int64_t n, hipStream_t s);

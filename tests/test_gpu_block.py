@@ -149,3 +149,62 @@ def test_fullsize_block_on_sampled_rows(gains):
         got = to_host(got[b, rows])
         assert np.isfinite(got).all(), name
         assert rel_fro(got, want[0]) <= (BF16_GRAD_FRO if name == "de" else BF16_OUT_FRO), (name, rel_fro(got, want[0]))
+
+
+def _run_block_sim(cfg, bi, xp, t, ffn, gains):
+    import torch
+    from gpu_harness import to_dev, to_host, desc_of, tdtype, DEV
+    d = desc_of(cfg, bx.BEAGLE_FLAG_NEED_DXKV)
+    dt = tdtype(cfg)
+    B, S, L, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.seq_kv, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    dev = {n: to_dev(bi[n], cfg) for n in ("e", "hs", "dh") + BLOCK_W + (BLOCK_G if gains else ())}
+    xpd = to_dev(xp, cfg)
+    out = lambda *s, dtype=dt: torch.full(s, float("nan"), dtype=dtype, device=DEV)
+    f32 = torch.float32
+    sv = dict(q=out(B, S, H, hd), k=out(B, L, G, hd), v=out(B, L, G, hd), o=out(B, S, H, hd), lse=out(B, H, S, dtype=f32),
+              y=out(B, S, D), u=out(B, S, ffn), w=out(B, S, ffn), m=out(B, S, ffn), kp=out(B, L, G, hd), vp=out(B, L, G, hd))
+    if gains:
+        sv.update(xq_n=out(B, S, D), r_q=out(B * S, dtype=f32), xkv_n=out(B, L, D), r_kv=out(B * L, dtype=f32),
+                  z=out(B, S, D), r_mlp=out(B * S, dtype=f32), xp_n=out(B, L, D), r_p=out(B * L, dtype=f32))
+    h = out(B, S, D)
+    params = bx.make_block_params(ffn, RMS_EPS, **{n: dev[n] for n in BLOCK_W + (BLOCK_G if gains else ())})
+    saved = bx.make_block_saved(**sv)
+    bx.beagle_xattn_block_fwd_sim(d, params, dev["e"], dev["hs"], xpd, t, h, saved,
+                                  torch.empty(bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_FWD),
+                                              dtype=torch.uint8, device=DEV))
+    gr = dict(de=out(B, S, D), dhs=out(B, L, D), dxpred=out(B, L, D), dwq=out(D, H * hd), dwk=out(D, G * hd),
+              dwv=out(D, G * hd), dwo=out(H * hd, D), dw_gate=out(D, ffn), dw_up=out(D, ffn), dw_down=out(ffn, D))
+    if gains:
+        gr.update(dg_q=out(D, dtype=f32), dg_kv=out(D, dtype=f32), dg_mlp=out(D, dtype=f32))
+    ws = torch.empty(bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_BWD_SIM), dtype=torch.uint8, device=DEV)
+    bx.beagle_xattn_block_bwd_sim(d, params, dev["dh"], dev["e"], dev["hs"], xpd, t, saved, bx.make_block_grads(**gr), ws)
+    torch.cuda.synchronize()
+    return to_host(h), {n: to_host(v) for n, v in gr.items()}
+
+
+@pytest.mark.parametrize("name,kw,ffn,gains,t", [
+    ("c1", dict(batch=2, seq_q=45, seq_kv=45, block_size=4, block_offset=1), 96, True, 2),
+    ("c1", dict(batch=1, seq_q=30, seq_kv=30, block_size=5), 64, False, 3),
+    ("c2", dict(batch=2, seq_q=260, seq_kv=260, **SMALL), 1408, True, 3),
+])
+def test_block_in_a_simulation_step(name, kw, ffn, gains, t):
+    """The block with the late-stage attention: predicted states pass through the key/value normalisation, the
+    gain's gradient collects both sources, dxpred comes back through the normalisation."""
+    cfg = synth.CONFIGS[name].with_(seed_base=64, **kw)
+    bi = synth.make_block_inputs(cfg, ffn)
+    xp = synth.make_block_inputs(cfg.with_(seed_base=99), ffn)["hs"]
+    g = {n: (bi[n] if gains else None) for n in BLOCK_G}
+    ref = blk.block_backward(bi["dh"], bi["e"], bi["hs"], *(bi[n] for n in BLOCK_W), **g, rms_eps=RMS_EPS,
+                             n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, k=cfg.block_size, eps=cfg.block_offset,
+                             xpred=xp, t=t)
+    h, gr = _run_block_sim(cfg, bi, xp, t, ffn, gains)
+    names = GRADS + ("dxpred",) + (tuple("d" + n for n in BLOCK_G) if gains else ())
+    if cfg.dtype == "f32":
+        assert rel_max(h, ref["fwd"]["h"]) <= F32_TOL
+        for n in names:
+            assert rel_max(gr[n], ref[n]) <= 2 * F32_TOL, (n, rel_max(gr[n], ref[n]))
+    else:
+        assert rel_fro(h, ref["fwd"]["h"]) <= BF16_OUT_FRO
+        for n in names:
+            assert rel_fro(gr[n], ref[n]) <= BF16_GRAD_FRO, (n, rel_fro(gr[n], ref[n]))
+    assert gr["dxpred"].any()
