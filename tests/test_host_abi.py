@@ -164,6 +164,39 @@ def test_block_entry_points_validate_before_launching():
         bx.make_block_saved(nonsense=a)
 
 
+def test_block_simulation_and_decode_entry_points_validate_before_launching():
+    a, big = 4096, 1 << 40
+    d = _desc(S=16, L=16)
+    W = dict(wq=a, wk=a, wv=a, wo=a, w_gate=a, w_up=a, w_down=a)
+    base = {n: a for n in ("q", "k", "v", "o", "lse", "y", "u", "w", "m")}
+    ok = bx.make_block_params(32, 1e-5, **W)
+    fwd = lambda sv, xp=a, t=1, dd=d: bx.beagle_xattn_block_fwd_sim(dd, ok, a, a, xp, t, a, bx.make_block_saved(**sv), None,
+                                                                    stream=0, check=False)
+    assert fwd(base) == 1                                          # kp / vp missing
+    full = dict(base, kp=a, vp=a)
+    assert fwd(full, None) == 1 and fwd(full, a, -1) == 2 and fwd(full, a, 1, _desc(S=8, L=16)) == 2
+    withg = bx.make_block_params(32, 1e-5, g_kv=a, **W)
+    sv_g = bx.make_block_saved(**dict(full, xkv_n=a, r_kv=a))       # gain given, but no room for the normalised xpred
+    assert bx.beagle_xattn_block_fwd_sim(d, withg, a, a, a, 1, a, sv_g, None, stream=0, check=False) == 1
+    gr = {n: a for n in ("de", "dwq", "dwk", "dwv", "dwo", "dw_gate", "dw_up", "dw_down")}
+    bwd = lambda g, wsb=big: bx.beagle_xattn_block_bwd_sim(d, ok, a, a, a, a, 1, bx.make_block_saved(**full),
+                                                           bx.make_block_grads(**g), a, stream=0, workspace_bytes=wsb, check=False)
+    assert bwd(gr) == 1                                            # dxpred is a required output
+    assert bwd(dict(gr, dxpred=a), 64) == 4
+    n_sim = bx.beagle_xattn_block_workspace_bytes(d, 32, bx.BEAGLE_WS_BLOCK_BWD_SIM)
+    assert n_sim > bx.beagle_xattn_block_workspace_bytes(d, 32, bx.BEAGLE_WS_BLOCK_BWD)
+    # decode-time block
+    dd = _desc(S=2, L=16)
+    step = lambda p, n_true=16, wsb=big: bx.beagle_xattn_block_draft_step(dd, p, a, a, a, n_true, None, 0, a, a, a, stream=0,
+                                                                         workspace_bytes=wsb, check=False)
+    dW = dict(wq=a, wo=a, w_gate=a, w_up=a, w_down=a)              # wk, wv, g_kv are not needed at decode time
+    assert step(bx.make_block_params(32, 1e-5, **dict(dW, w_gate=None))) == 1
+    assert step(bx.make_block_params(32, 1e-5, **dW), 17) == 2 and step(bx.make_block_params(32, 1e-5, **dW), 10) == 1
+    assert step(bx.make_block_params(32, 1e-5, **dW), 16, 64) == 4
+    assert bx.beagle_xattn_block_workspace_bytes(dd, 32, bx.BEAGLE_WS_BLOCK_DRAFT) > 0
+    assert bx.beagle_xattn_block_workspace_bytes(_desc(S=2, L=16, batch=2), 32, bx.BEAGLE_WS_BLOCK_DRAFT) == 0
+
+
 def test_entry_points_validate_before_launching():
     """NULL / misaligned / short-workspace arguments return a status without
     touching the GPU (this test runs where there is none)."""
