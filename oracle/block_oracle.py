@@ -191,3 +191,10 @@ def block_draft_step(x, k_cache, v_cache, wq, wo, w_gate, w_up, w_down, *, g_q=N
     z = rmsnorm(y, g_mlp, rms_eps)
     h = mlp_forward(z, w_gate, w_up, w_down)["out"] + y
     return dict(h=h, y=y, lse=att["lse"])
+
+
+def block_kv_append(k_cache, v_cache, pos, x_new, wk, wv, *, g_kv=None, rms_eps=1e-5, n_kv_heads, rope=None):
+    """New cache rows for the block: the states (true ones from the target model, or drafted ones = earlier block
+    outputs h) are key/value source states, so they take the key/value normalisation g_kv before the projections --
+    exactly what block_forward does to hs.  Returns the updated copies of the caches."""
+    return orc.kv_append(k_cache, v_cache, pos, rmsnorm(x_new, g_kv, rms_eps), wk, wv, n_kv_heads=n_kv_heads, rope=rope)

@@ -243,3 +243,20 @@ def test_block_simulation_step_zero_is_the_plain_block_and_gradients_check():
     h1 = blk.block_forward(**c, **kw0, xpred=xp, t=2)["h"]
     h2 = blk.block_forward(**c, **kw0, xpred=7.0 * xp, t=2)["h"]
     assert np.allclose(h1, h2, atol=1e-12)
+
+
+def test_block_kv_append_builds_the_rows_the_training_block_uses():
+    c, kw, _ = _case(B=1, S=9)
+    f = blk.block_forward(**c, **dict(kw, k=1, eps=0), rope=dict(base=50.0))
+    G = kw["n_kv_heads"]
+    d = f["attn"]["k"].shape[-1]
+    kc, vc = np.zeros((9, G, d)), np.zeros((9, G, d))
+    kc, vc = blk.block_kv_append(kc, vc, 0, c["hs"][0, :5], c["wk"], c["wv"], g_kv=kw["g_kv"], rms_eps=kw["rms_eps"],
+                                 n_kv_heads=G, rope=dict(base=50.0, k_pos=np.arange(5)))
+    kc, vc = blk.block_kv_append(kc, vc, 5, c["hs"][0, 5:], c["wk"], c["wv"], g_kv=kw["g_kv"], rms_eps=kw["rms_eps"],
+                                 n_kv_heads=G, rope=dict(base=50.0, k_pos=np.arange(5, 9)))
+    assert np.allclose(kc, f["attn"]["k"][0], atol=1e-13) and np.allclose(vc, f["attn"]["v"][0], atol=1e-13)
+    # without the gain it is the plain append
+    a = blk.block_kv_append(kc, vc, 2, c["hs"][0, :3], c["wk"], c["wv"], n_kv_heads=G)
+    b = orc.kv_append(kc, vc, 2, c["hs"][0, :3], c["wk"], c["wv"], n_kv_heads=G)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
