@@ -90,7 +90,8 @@ enum {
                                       Training entry points only; D % 8 == 0.    */
 };
 
-enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3, BEAGLE_WS_BWD_SIM = 4 };
+enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPEND = 3, BEAGLE_WS_BWD_SIM = 4,
+       BEAGLE_WS_BLOCK_APPEND = 5 };
 
 typedef struct {
   int32_t struct_size;   /* sizeof(beagle_xattn_desc); checked                  */
@@ -375,6 +376,19 @@ beagle_status beagle_xattn_block_bwd_sim(const beagle_xattn_desc* desc, const be
 beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* params,
     const void* x_draft, const void* k_cache, const void* v_cache, int32_t n_true, const uint32_t* tree_mask,
     int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Cache append for the block: new states (true ones, or drafted ones = earlier
+ * outputs h of beagle_xattn_block_draft_step) are key/value source states, so
+ * they take the key/value normalisation RMSNorm(.; params->g_kv) before the
+ * projections, exactly as hs does in beagle_xattn_block_fwd; then as
+ * beagle_xattn_kv_append with params->wk, params->wv (the other fields of params
+ * are not read; g_kv NULL gives the plain append).
+ * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BLOCK_APPEND).
+ */
+beagle_status beagle_xattn_block_kv_append(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const void* x_new, void* k_cache, void* v_cache, int32_t pos,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Appending states to the decode cache (section 4.1, KV-cache paragraph: new

@@ -21,7 +21,7 @@ BEAGLE_OK = 0
  BEAGLE_ERR_HIP) = range(1, 7)
 BEAGLE_F32, BEAGLE_BF16 = 0, 1
 BEAGLE_FLAG_NEED_DXKV, BEAGLE_FLAG_WGRAD_F32, BEAGLE_FLAG_ROPE, BEAGLE_FLAG_STATES_F16 = 1, 2, 4, 8
-BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM = 0, 1, 2, 3, 4
+BEAGLE_WS_FWD, BEAGLE_WS_BWD, BEAGLE_WS_DRAFT, BEAGLE_WS_APPEND, BEAGLE_WS_BWD_SIM, BEAGLE_WS_BLOCK_APPEND = 0, 1, 2, 3, 4, 5
 BEAGLE_WS_BLOCK_FWD, BEAGLE_WS_BLOCK_BWD, BEAGLE_WS_BLOCK_DRAFT, BEAGLE_WS_BLOCK_BWD_SIM = 0, 1, 2, 3
 STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: "BEAGLE_ERR_UNSUPPORTED",
                 4: "BEAGLE_ERR_WORKSPACE", 5: "BEAGLE_ERR_ALIGN", 6: "BEAGLE_ERR_HIP"}
@@ -32,6 +32,7 @@ EXPORTS = (
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
     "beagle_xattn_block_draft_step", "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
+    "beagle_xattn_block_kv_append",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
     "beagle_xattn_status_string", "beagle_xattn_version",
@@ -150,6 +151,8 @@ def lib() -> C.CDLL:
     L.beagle_xattn_block_bwd_sim.restype = C.c_int
     L.beagle_xattn_block_bwd_sim.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, vp, C.c_int32,
                                              C.POINTER(beagle_block_saved), C.POINTER(beagle_block_grads), vp, C.c_size_t, vp]
+    L.beagle_xattn_block_kv_append.restype = C.c_int
+    L.beagle_xattn_block_kv_append.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp, C.c_size_t, vp]
     L.beagle_xattn_block_draft_step.restype = C.c_int
     L.beagle_xattn_block_draft_step.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp, C.c_int32,
                                                 vp, vp, vp, C.c_size_t, vp]
@@ -265,6 +268,14 @@ def beagle_xattn_block_bwd_sim(desc, params, dh, e, hs, xpred, sim_step, saved, 
         C.byref(grads), _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes,
         _stream(stream))
     return _check(st, "beagle_xattn_block_bwd_sim", check)
+
+
+def beagle_xattn_block_kv_append(desc, params, x_new, k_cache, v_cache, pos, workspace, stream=None, *,
+                                 workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_block_kv_append(
+        C.byref(desc), C.byref(params) if params is not None else None, _ptr(x_new), _ptr(k_cache), _ptr(v_cache), int(pos),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_block_kv_append", check)
 
 
 def beagle_xattn_block_draft_step(desc, params, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words, h, lse,

@@ -346,6 +346,29 @@ void xattn_bwd_sim_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy,
   }
 }
 
+// K / V rows of the n = d.S new states into cache rows pos .. pos + n - 1 (+ rotary embedding of the K rows).
+void kv_append_run(const Dims& d, const void* x_new, const void* wk, const void* wv, void* k_cache, void* v_cache,
+                   int32_t pos, void* workspace, hipStream_t s) {
+  // rows pos .. pos + n - 1 of the caches are the output matrices (leading dimension G*d)
+  char* kdst = (char*)k_cache + (size_t)pos * d.GD * d.esz;
+  char* vdst = (char*)v_cache + (size_t)pos * d.GD * d.esz;
+  if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
+    // a handful of states: HBM-bound on Wk and Wv, so the split-k streaming projection of the draft step
+    launch_kv_append_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, workspace, s);
+  } else {
+    GemmGroup g; memset(&g, 0, sizeof(g));
+    g.count = 2;
+    g.p[0] = gemm_nn(x_new, wk, kdst, d.S, d.GD, d.D);
+    g.p[1] = gemm_nn(x_new, wv, vdst, d.S, d.GD, d.D);
+    run_gemm(d, g, s, "kv_append");
+  }
+  if (d.rope) {   // the new K rows at their sequence positions (given, or the row indices)
+    RopeArgs r = rope_args(d, false);
+    rope_add(r, kdst, d.S, d.S, d.G, pos, d.rope_pos);
+    launch_rope(d.bf16, r, s, "kv_append_rope");
+  }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ profiler
@@ -473,7 +496,8 @@ beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, i
 // ---------------------------------------------------------------- workspace
 size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
   Dims d;
-  if (check_desc(desc, which == BEAGLE_WS_DRAFT || which == BEAGLE_WS_APPEND, &d) != BEAGLE_OK) return 0;
+  if (check_desc(desc, which == BEAGLE_WS_DRAFT || which == BEAGLE_WS_APPEND || which == BEAGLE_WS_BLOCK_APPEND, &d) != BEAGLE_OK)
+    return 0;
   switch (which) {
     case BEAGLE_WS_FWD: return WS_ALIGN + states_ws(d);   // nothing beyond the saved tensors (and the converted states)
     case BEAGLE_WS_BWD: {
@@ -492,9 +516,14 @@ size_t beagle_xattn_workspace_bytes(const beagle_xattn_desc* desc, int which) {
       return w.total + align_up(extra) + 2 * align_up((size_t)(d.Tk * d.GD) * d.esz) + states_ws(d);   // + dKp, dVp
     }
     case BEAGLE_WS_APPEND:
+    case BEAGLE_WS_BLOCK_APPEND: {
+      size_t n = WS_ALIGN;
       if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))
-        return WS_ALIGN + align_up(kv_append_bf16_ws_bytes((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D));
-      return WS_ALIGN;
+        n += align_up(kv_append_bf16_ws_bytes((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D));
+      if (which == BEAGLE_WS_BLOCK_APPEND)   // + the normalised states and their 1/rms
+        n += align_up((size_t)(d.S * d.D) * d.esz) + align_up((size_t)d.S * sizeof(float));
+      return n;
+    }
     default: return 0;
   }
 }
@@ -701,24 +730,7 @@ beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
   if (pos < 0 || (int64_t)pos + d.S > d.L) return BEAGLE_ERR_SHAPE;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
-  // rows pos .. pos + n - 1 of the caches are the output matrices (leading dimension G*d)
-  char* kdst = (char*)k_cache + (size_t)pos * d.GD * d.esz;
-  char* vdst = (char*)v_cache + (size_t)pos * d.GD * d.esz;
-  if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
-    // a handful of states: HBM-bound on Wk and Wv, so the split-k streaming projection of the draft step
-    launch_kv_append_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, workspace, s);
-  } else {
-    GemmGroup g; memset(&g, 0, sizeof(g));
-    g.count = 2;
-    g.p[0] = gemm_nn(x_new, wk, kdst, d.S, d.GD, d.D);
-    g.p[1] = gemm_nn(x_new, wv, vdst, d.S, d.GD, d.D);
-    run_gemm(d, g, s, "kv_append");
-  }
-  if (d.rope) {   // the new K rows at their sequence positions (given, or the row indices)
-    RopeArgs r = rope_args(d, false);
-    rope_add(r, kdst, d.S, d.S, d.G, pos, d.rope_pos);
-    launch_rope(d.bf16, r, s, "kv_append_rope");
-  }
+  kv_append_run(d, x_new, wk, wv, k_cache, v_cache, pos, workspace, s);
   return hip_status();
 }
 
@@ -1052,5 +1064,35 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
     dn.R = y; dn.ldr = d.D;
     launch_gemm_f32(group1(dn), s, "draft_mlp_down");
   }
+  return hip_status();
+}
+
+beagle_status beagle_xattn_block_kv_append(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* x_new, void* k_cache, void* v_cache, int32_t pos,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!p) return BEAGLE_ERR_NULL;
+  if (p->struct_size != (int32_t)sizeof(beagle_block_params) || p->reserved != 0) return BEAGLE_ERR_SHAPE;
+  if (!(p->rms_eps >= 0.f) || isinf(p->rms_eps)) return BEAGLE_ERR_SHAPE;
+  const void* ptrs[] = {x_new, p->wk, p->wv, k_cache, v_cache, workspace};
+  for (const void* q : ptrs) if (!q) return BEAGLE_ERR_NULL;
+  for (const void* q : ptrs) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (p->g_kv && !aligned16(p->g_kv)) return BEAGLE_ERR_ALIGN;
+  if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
+  const size_t need = beagle_xattn_workspace_bytes(desc, BEAGLE_WS_BLOCK_APPEND);
+  if (workspace_bytes < need) return BEAGLE_ERR_WORKSPACE;
+  if (pos < 0 || (int64_t)pos + d.S > d.L) return BEAGLE_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  // the normalised copy of the new states and their 1/rms live behind the plain append's own workspace
+  char* tail = (char*)workspace + beagle_xattn_workspace_bytes(desc, BEAGLE_WS_APPEND);
+  const void* xn = x_new;
+  if (p->g_kv) {
+    launch_rmsnorm_fwd(d.bf16, x_new, p->g_kv, tail, (float*)(tail + align_up((size_t)(d.S * d.D) * d.esz)), d.S, (int)d.D,
+                       p->rms_eps, s, "append_norm_kv");
+    xn = tail;
+  }
+  kv_append_run(d, xn, p->wk, p->wv, k_cache, v_cache, pos, workspace, s);
   return hip_status();
 }

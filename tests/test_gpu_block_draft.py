@@ -104,3 +104,74 @@ def test_block_draft_step_argument_errors():
     assert f(bx.make_block_params(30, 1e-5, **W)) == bx.BEAGLE_ERR_UNSUPPORTED
     d2 = bx.make_desc(batch=2, seq_q=2, seq_kv=16, hidden=64, n_q_heads=1, n_kv_heads=1, head_dim=64, io_dtype=bx.BEAGLE_F32)
     assert bx.beagle_xattn_block_workspace_bytes(d2, 32, bx.BEAGLE_WS_BLOCK_DRAFT) == 0
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_block_speculative_iteration_append_draft_append_draft(dtype):
+    """Cache built by beagle_xattn_block_kv_append from true states (with rotary positions), one draft step of three
+    tokens, their outputs h appended as drafted rows at position n_true + 0, a second draft step of three tokens
+    that each see their own parent only -- every stage against the same chain over the oracle."""
+    D, H, G, d, ffn = (256, 4, 2, 64, 96) if dtype == "f32" else (512, 4, 4, 128, 1408)
+    n_true, cap, M = 40, 64, 3
+    cfg, bi, _, _ = _problem(dtype, M, cap, H, G, D, d, ffn, 171)
+    cfgA = cfg.with_(seq_q=n_true)
+    rope = dict(base=10000.0)
+    names = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_q", "g_kv", "g_mlp")
+    dev = {n: gh.to_dev(bi[n], cfg) for n in names}
+    params = bx.make_block_params(ffn, 1e-5, **dev)
+    dt = gh.tdtype(cfg)
+    kc = torch.zeros(cap, G, d, dtype=dt, device=gh.DEV)
+    vc = torch.zeros(cap, G, d, dtype=dt, device=gh.DEV)
+    tol = (lambda a, b: gh.rel_max(a, b) <= 3 * F32_TOL) if dtype == "f32" else (lambda a, b: gh.rel_fro(a, b) <= OUT_FRO)
+    i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=gh.DEV)
+
+    def append(x_host, pos, positions):
+        n = x_host.shape[0]
+        pd = i32(positions)
+        dsc = gh.desc_of(cfg.with_(seq_q=n), bx.BEAGLE_FLAG_ROPE, rope_positions=pd)
+        ws = gh.workspace(dsc, bx.BEAGLE_WS_BLOCK_APPEND)
+        bx.beagle_xattn_block_kv_append(dsc, params, gh.to_dev(x_host, cfg), kc, vc, pos, ws)
+        torch.cuda.synchronize()
+
+    def draft(x_host, rows, n_true_, tree, positions):
+        pd = i32(positions)
+        dsc = gh.desc_of(cfg.with_(seq_q=x_host.shape[0], seq_kv=rows), bx.BEAGLE_FLAG_ROPE, rope_positions=pd)
+        h = torch.empty(x_host.shape[0], D, dtype=dt, device=gh.DEV)
+        lse = torch.empty(H, x_host.shape[0], dtype=torch.float32, device=gh.DEV)
+        ws = torch.empty(bx.beagle_xattn_block_workspace_bytes(dsc, ffn, bx.BEAGLE_WS_BLOCK_DRAFT), dtype=torch.uint8, device=gh.DEV)
+        if tree is None:
+            tm, words = None, 0
+        else:
+            packed = gh.pack_tree_mask(tree)
+            tm, words = torch.from_numpy(packed.view(np.int32)).to(gh.DEV), packed.shape[1]
+        bx.beagle_xattn_block_draft_step(dsc, params, gh.to_dev(x_host, cfg), kc[:rows].contiguous(), vc[:rows].contiguous(),
+                                         n_true_, tm, words, h, lse, ws)
+        torch.cuda.synchronize()
+        return gh.to_host(h)
+
+    okw = dict(g_q=bi["g_q"], g_mlp=bi["g_mlp"], rms_eps=1e-5, n_q_heads=H, n_kv_heads=G)
+    W5 = [bi[n] for n in ("wq", "wo", "w_gate", "w_up", "w_down")]
+    # 1. true states into the cache
+    hs_true = bi["hs"][0, :n_true]
+    append(hs_true, 0, np.arange(n_true))
+    rk, rv = blk.block_kv_append(np.zeros((cap, G, d)), np.zeros((cap, G, d)), 0, hs_true, bi["wk"], bi["wv"], g_kv=bi["g_kv"],
+                                 n_kv_heads=G, rope=dict(rope, k_pos=np.arange(n_true)))
+    assert tol(gh.to_host(kc[:n_true]), rk[:n_true]) and tol(gh.to_host(vc[:n_true]), rv[:n_true])
+    # 2. first draft depth: three candidate tokens at position n_true
+    x1 = bi["e"][0, :M]
+    h1 = draft(x1, n_true, n_true, None, [n_true] * M)
+    r1 = blk.block_draft_step(x1, rk[:n_true], rv[:n_true], *W5, **okw, rope=dict(rope, q_pos=[n_true] * M))["h"]
+    assert tol(h1, r1)
+    # 3. their states become drafted rows (positions n_true, not the row indices)
+    h1_stored = synth.round_to_bf16(h1.astype(np.float32)) if dtype == "bf16" else h1.astype(np.float32)
+    append(h1_stored, n_true, [n_true] * M)
+    rk, rv = blk.block_kv_append(rk, rv, n_true, h1_stored, bi["wk"], bi["wv"], g_kv=bi["g_kv"], n_kv_heads=G,
+                                 rope=dict(rope, k_pos=[n_true] * M))
+    assert tol(gh.to_host(kc[n_true:n_true + M]), rk[n_true:n_true + M])
+    # 4. second depth: child i sees drafted row i only
+    x2 = np.ascontiguousarray(bi["e"][0, ::-1])                  # three other embeddings (the same ones, reordered)
+    tree = np.eye(M, dtype=bool)
+    h2 = draft(x2, n_true + M, n_true, tree, [n_true + 1] * M)
+    r2 = blk.block_draft_step(x2, rk[:n_true + M], rv[:n_true + M], *W5, **okw, n_true=n_true, tree_mask=tree,
+                              rope=dict(rope, q_pos=[n_true + 1] * M))["h"]
+    assert tol(h2, r2)
