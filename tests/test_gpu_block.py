@@ -208,3 +208,41 @@ def test_block_in_a_simulation_step(name, kw, ffn, gains, t):
         for n in names:
             assert rel_fro(gr[n], ref[n]) <= BF16_GRAD_FRO, (n, rel_fro(gr[n], ref[n]))
     assert gr["dxpred"].any()
+
+
+def test_three_simulated_steps_through_the_block_with_in_place_saves():
+    """block_fwd_sim(t) -> its output h saved as the predicted states -> block_fwd_sim(t + 1) ..., on the device,
+    against the same loop over the oracle (the buffer starts with large values that must never be read)."""
+    import torch
+    from oracle import beagle_oracle as orc
+    from gpu_harness import to_dev, to_host, desc_of, DEV
+    cfg = synth.CONFIGS["c1"].with_(seed_base=66, batch=2, seq_q=41, seq_kv=41, block_size=4, block_offset=2)
+    ffn, steps = 96, 3
+    bi = synth.make_block_inputs(cfg, ffn)
+    B, S, D, H, G, hd = cfg.batch, cfg.seq_q, cfg.hidden, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    d = desc_of(cfg)
+    dev = {n: to_dev(bi[n], cfg) for n in ("e", "hs") + BLOCK_W + BLOCK_G}
+    E = lambda *s, dtype=torch.float32: torch.empty(*s, dtype=dtype, device=DEV)
+    sv = dict(q=E(B, S, H, hd), k=E(B, S, G, hd), v=E(B, S, G, hd), o=E(B, S, H, hd), lse=E(B, H, S), y=E(B, S, D),
+              u=E(B, S, ffn), w=E(B, S, ffn), m=E(B, S, ffn), kp=E(B, S, G, hd), vp=E(B, S, G, hd), xq_n=E(B, S, D),
+              r_q=E(B * S), xkv_n=E(B, S, D), r_kv=E(B * S), z=E(B, S, D), r_mlp=E(B * S), xp_n=E(B, S, D), r_p=E(B * S))
+    params = bx.make_block_params(ffn, RMS_EPS, **{n: dev[n] for n in BLOCK_W + BLOCK_G})
+    saved = bx.make_block_saved(**sv)
+    init = bi["hs"] * 64.0
+    xp, h = to_dev(init, cfg), E(B, S, D)
+    buf = init.astype(np.float64)
+    g = {n: bi[n] for n in BLOCK_G}
+    hs_all = []
+    for t in range(steps):
+        bx.beagle_xattn_block_fwd_sim(d, params, dev["e"], dev["hs"], xp, t, h, saved, None)
+        bx.beagle_xattn_sim_save(d, h, xp, t)
+        torch.cuda.synchronize()
+        ref = blk.block_forward(bi["e"], bi["hs"], *(bi[n] for n in BLOCK_W), **g, rms_eps=RMS_EPS, n_q_heads=H,
+                                n_kv_heads=G, k=cfg.block_size, eps=cfg.block_offset, xpred=buf, t=t)["h"]
+        assert rel_max(to_host(h), ref) <= 3 * F32_TOL, (t, rel_max(to_host(h), ref))
+        buf = orc.sim_save_predicted(buf, ref, cfg.block_size, cfg.block_offset, t)
+        hs_all.append(ref)
+    assert not np.allclose(hs_all[0], hs_all[2])
+    saved_rows = (np.arange(S) - cfg.block_offset) % cfg.block_size < steps
+    assert rel_max(to_host(xp)[:, saved_rows], buf[:, saved_rows]) <= 3 * F32_TOL
+    assert np.array_equal(to_host(xp)[:, ~saved_rows], init[:, ~saved_rows].astype(np.float64))
