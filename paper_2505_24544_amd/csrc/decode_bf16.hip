@@ -16,7 +16,8 @@
 //                     q at ~16 bits.  Waves are merged in LDS; each range writes
 //                     an unnormalised partial.
 //   (C) combine       merges the key ranges, writes o (bf16) and the LSE; with up
-//                     to 8 queries this runs in the prologue of (D) instead
+//                     to 12 queries (the paper's draft width is 10) this runs in the
+//                     prologue of (D) instead
 //   (D) skinny_gemm   y_part[ks] = o * Wo[k-slice ks]
 //   (E) sum_slices    y = sum_ks y_part[ks]  (bf16)
 //
@@ -62,7 +63,7 @@ struct CombineArgs {
   int Mpad, R;
   float scale;
 };
-constexpr int COMB_MAXM = 8, COMB_MAXR = 8;
+constexpr int COMB_MAXM = 12, COMB_MAXR = 8;
 
 template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
