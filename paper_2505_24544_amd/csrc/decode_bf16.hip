@@ -293,15 +293,15 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   // picks up its B-operand fragments, split into bf16 hi + lo.
   //
   // The first two K/V steps are requested while the q slices are still on their way: the load counter of
-  // a wave retires in order, so the roles are split by wave.  Up to 8 queries are summed by wave 0 alone
-  // (more by all four): a summing wave loads, adds, stores to LDS and only then requests its share of K/V
+  // a wave retires in order, so the roles are split by wave.  Up to 8 queries are summed by wave 0 alone, up
+  // to 16 by two waves (more by all four): a summing wave loads, adds, stores to LDS and only then requests its share of K/V
   // rows; the other waves request theirs at once.  The fragments are read after the barrier that also
   // waits for the first step, with explicit ds_read instructions: the compiler cannot tell these reads
   // from the K/V requests in flight and would wait for all of them.
   {
     typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
     const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    const int qwaves = mrows <= 8 ? 1 : 4;
+    const int qwaves = mrows <= 8 ? 1 : (mrows <= 16 ? 2 : 4);     // a summing wave covers 8 queries
     if (wave < qwaves) {
       // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
       const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
@@ -361,8 +361,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
       }
     } else {
-      // rows 8 .. 31 of the block have no query here (only reached with qwaves == 1): zeros
-      for (int idx = 256 + (tid - 64); idx < 32 * 32; idx += 192) *(float4*)(qbuf + 4 * idx) = zero4;
+      // the rows behind the summed ones hold no query (only reached with fewer than four summing waves): zeros
+      for (int idx = 256 * qwaves + (tid - 64 * qwaves); idx < 32 * 32; idx += 256 - 64 * qwaves)
+        *(float4*)(qbuf + 4 * idx) = zero4;
     }
     __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 0) fetch(stage0, 0);
