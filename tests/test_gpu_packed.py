@@ -72,13 +72,14 @@ def test_fp32_packed(kw, lens_q, lens_kv, eps_list, rope):
 SMALL = dict(hidden=512, n_q_heads=4, n_kv_heads=4)
 
 
-@pytest.mark.parametrize("name,kw,lens", [
-    ("c2", dict(batch=4, seq_q=300, seq_kv=300, **SMALL), [300, 1, 129, 64]),
-    ("c3", dict(batch=3, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2), [128, 330, 257]),
+@pytest.mark.parametrize("name,kw,lens,lens_kv", [
+    ("c2", dict(batch=4, seq_q=300, seq_kv=300, **SMALL), [300, 1, 129, 64], None),
+    ("c3", dict(batch=3, seq_q=330, seq_kv=330, hidden=512, n_q_heads=8, n_kv_heads=2), [128, 330, 257], None),
+    ("c2", dict(batch=3, seq_q=260, seq_kv=400, **SMALL), [260, 70, 200], [130, 400, 65]),    # queries and keys differ
 ])
-def test_bf16_packed(name, kw, lens):
+def test_bf16_packed(name, kw, lens, lens_kv):
     cfg = synth.CONFIGS[name].with_(**kw)
-    pk, cu_q, cu_kv = _pack(cfg, synth.make_inputs(cfg, peaked_queries=True), lens, lens)
+    pk, cu_q, cu_kv = _pack(cfg, synth.make_inputs(cfg, peaked_queries=True), lens, lens_kv or lens)
     ref = _ref(cfg, pk, cu_q, cu_kv)
     fw, gr = _run(cfg, pk, cu_q, cu_kv)
     for n in ("y", "o"):
