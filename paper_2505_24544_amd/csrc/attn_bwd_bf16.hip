@@ -10,7 +10,7 @@
 //      S^T = K Q^T and dP^T = V dO^T come out with column q = lane % 32, so LSE
 //      and delta are per-lane scalars, and dS^T goes straight from the
 //      accumulator registers into the B operand of dQ^T += K^T dS^T.  The kernel
-//      also computes delta and stores it for kernel (2).
+//      also computes delta and stores it, with -log2(e) * LSE, for kernel (2).
 //
 //  (2) dkv kernel  one workgroup = 128 keys of one (b, kv head), loop over the
 //      H/G query heads of the group and over the query tiles that can see those
@@ -27,7 +27,6 @@
 // Mask: query p sees key j iff j < row_limit(p) iff p >= first_query_seeing(j).
 // Key tiles beyond a workgroup's last limit / query tiles before a key tile's
 // first viewer are never visited (whole-tile skipping).
-#include <type_traits>
 #include "attn_tiles.h"
 
 namespace beagle {
@@ -91,8 +90,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
     part += bwd::dot8(dof[s], of);
   }
   const float delta = part + __shfl_xor(part, 32, 64);
-  if (q_ok && hf == 0) a.delta[li] = delta;
   const float lse = a.lse[li];
+  if (q_ok && hf == 0) { a.delta[li] = delta; a.nlse2[li] = -LOG2E * lse; }   // blind rows: +inf, masked in the dK/dV kernel
   const float c2 = a.scale * LOG2E;
   const float lse2 = (lim > 0 ? lse : 0.f) * LOG2E;    // blind rows are fully masked below
   const FragOffs fo = make_frag_offs(lane);
@@ -199,7 +198,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   using namespace dkv;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  __shared__ __attribute__((aligned(256))) float stat0[2 * BQ];    // [lse 64 | delta 64] of the stage's queries
+  __shared__ __attribute__((aligned(256))) float stat0[2 * BQ];    // [-log2(e) lse 64 | delta 64] of the stage's queries
   __shared__ __attribute__((aligned(256))) float stat1[2 * BQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, jl = lane & 31;
   int row, jt;                                    // key tile 0 is seen by the most queries: heaviest first
@@ -216,11 +215,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const bf16_t* Vg = (const bf16_t*)a.v + kvrow;
   const int64_t qs = (int64_t)a.H * HD;
 
-  // first query that sees this lane's key / any key of the wave / every key of the wave / any of the workgroup
+  // first query that sees this lane's key / any key of the wave / any of the workgroup
   const MaskParams mk = sample_mask(a, b);
   const int fq = j_ok ? first_query_seeing(j, mk) : sv.S;
   const int wave_first = jw0 < sv.L ? first_query_seeing(jw0, mk) : sv.S;
-  const int wave_all = jw0 < sv.L ? first_query_seeing(min(jw0 + 32, sv.L) - 1, mk) : sv.S;
   const int wg_first = first_query_seeing(j0, mk);
   const int qt0 = wg_first / BQ;
   const int nqt = (sv.S + BQ - 1) / BQ;
@@ -249,7 +247,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int64_t head0 = sv.q0 * a.H + g * rep;
   const bf16_t* f_q = (const bf16_t*)a.q + head0 * HD;           // row 0 of the fetch cursor's head
   const bf16_t* f_do = (const bf16_t*)a.dout + head0 * HD;
-  const float* f_stat = (wave == 0 ? a.lse : a.delta) + sv.lse0 + (g * rep) * sv.lse_hs;
+  const float* f_stat = (wave == 0 ? a.nlse2 : a.delta) + sv.lse0 + (g * rep) * sv.lse_hs;
   auto fetch = [&](bf16_t* st, float* stat) {
     const int q0 = f_qt * BQ;
     const int rows = f_hh < rep ? sv.S : 0;          // past the last pair: fetch zeros
@@ -273,63 +271,86 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
     if (q0 + BQ > wave_first) {                       // some query of the tile sees some key of the wave
       const bf16_t* qsm = cur;
       const bf16_t* dsm = cur + TILE;
-      f32x16_t s2[2], dp[2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s2[qb][e] = 0.f; dp[qb][e] = 0.f; }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          s2[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(qsm, fo, qb, s), kf[s], s2[qb], 0, 0, 0);
-          dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(dsm, fo, qb, s), vf[s], dp[qb], 0, 0, 0);
-        }
-      }
-      pipeline_reads_mfma<32, 1>();
-      __builtin_amdgcn_sched_barrier(0);
-      // register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key
-      uint32_t pp[2][8], pd[2][8];
       const int relq = fq - q0 - 4 * hf;    // query offsets inside the tile are compile-time constants
-      auto probs = [&](auto masked) {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+      // The two 32-query blocks of the tile go through  scores -> probabilities -> accumulation  one
+      // phase apart, so that the exponentials and products of one block issue between the MFMAs of
+      // the other (this kernel has one wave per SIMD: nothing else would fill the matrix pipe then).
+      // Register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key.
+      // The per-element predicate is evaluated on every tile: its two instructions per element ride along
+      // between the MFMAs, and a second, predicate-free copy of this body made the register allocator shuffle
+      // the 128 accumulators on every step (measured: 15 % slower).
+      {
+        constexpr int VPM = 10;   // vector instructions of one block slotted in per MFMA of the other
+        f32x16_t s2[2], dp[2];
+        float4 l4[4], d4[4];
+        uint32_t pp[2][8], pd[2][8];
+        auto stats = [&](int qb) {
 #pragma unroll
           for (int e4 = 0; e4 < 4; ++e4) {
             const int r = 32 * qb + 8 * e4 + 4 * hf;
-            const float4 l4 = *(const float4*)(sl + r);
-            const float4 d4 = *(const float4*)(sl + BQ + r);
-            const float ls[4] = {l4.x, l4.y, l4.z, l4.w};
-            const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+            l4[e4] = *(const float4*)(sl + r);
+            d4[e4] = *(const float4*)(sl + BQ + r);
+          }
+        };
+        auto scores = [&](int qb) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { s2[qb][e] = 0.f; dp[qb][e] = 0.f; }
+#pragma unroll
+          for (int s = 0; s < 8; ++s) {
+            s2[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(qsm, fo, qb, s), kf[s], s2[qb], 0, 0, 0);
+            dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(dsm, fo, qb, s), vf[s], dp[qb], 0, 0, 0);
+          }
+        };
+        auto probs = [&](int qb) {
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const float ls[4] = {l4[e4].x, l4[e4].y, l4[e4].z, l4[e4].w};
+            const float dl[4] = {d4[e4].x, d4[e4].y, d4[e4].z, d4[e4].w};
             float pv[4], dsv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
               const int e = 4 * e4 + u;
-              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][e], c2, -LOG2E * ls[u]));
-              if (decltype(masked)::value && 32 * qb + 8 * e4 + u < relq) p = 0.f;   // also kills the +inf of blind queries (LSE = -inf)
+              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][e], c2, ls[u]));
+              if (32 * qb + 8 * e4 + u < relq) p = 0.f;   // also kills the +inf of blind queries (-log2(e) LSE = +inf)
               pv[u] = p;
               dsv[u] = p * (dp[qb][e] - dl[u]);
             }
             pp[qb][2 * e4] = cvt_pk(pv[0], pv[1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[2], pv[3]);
             pd[qb][2 * e4] = cvt_pk(dsv[0], dsv[1]); pd[qb][2 * e4 + 1] = cvt_pk(dsv[2], dsv[3]);
           }
-      };
-      // a blind query (LSE = -inf) is below fq for every key, so its tiles always take the masked form
-      if (q0 < wave_all) probs(std::true_type{}); else probs(std::false_type{});
-      __builtin_amdgcn_sched_barrier(0);
+        };
+        auto accum = [&](int qb) {
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+          for (int t = 0; t < 2; ++t) {
+            union { uint32_t u[4]; bf16x8_t v; } pf, sf;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          union { uint32_t u[4]; bf16x8_t v; } pf, sf;
+            for (int i = 0; i < 4; ++i) { pf.u[i] = pp[qb][4 * t + i]; sf.u[i] = pd[qb][4 * t + i]; }
 #pragma unroll
-          for (int i = 0; i < 4; ++i) { pf.u[i] = pp[qb][4 * t + i]; sf.u[i] = pd[qb][4 * t + i]; }
-#pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dsm, fo, 32 * qb + 16 * t, cb), pf.v, dv[cb], 0, 0, 0);
-            dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qsm, fo, 32 * qb + 16 * t, cb), sf.v, dk[cb], 0, 0, 0);
+            for (int cb = 0; cb < 4; ++cb) {
+              dv[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dsm, fo, 32 * qb + 16 * t, cb), pf.v, dv[cb], 0, 0, 0);
+              dk[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qsm, fo, 32 * qb + 16 * t, cb), sf.v, dk[cb], 0, 0, 0);
+            }
           }
-        }
-      pipeline_reads_mfma<32, 2>();
-      __builtin_amdgcn_sched_barrier(0);
+        };
+        scores(0);
+        pipeline_reads_mfma<16, 1>();
+        __builtin_amdgcn_sched_barrier(0);
+        stats(0);
+        scores(1);
+        probs(0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        pipeline_reads_mfma_valu<16, 1, VPM>();
+        __builtin_amdgcn_sched_barrier(0);
+        stats(1);
+        accum(0);
+        probs(1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        pipeline_reads_mfma_valu<16, 2, VPM>();
+        __builtin_amdgcn_sched_barrier(0);
+        accum(1);
+        pipeline_reads_mfma<16, 2>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     wait_vmem();
     __syncthreads();
@@ -361,9 +382,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   }
 }
 
-size_t attn_bwd_bf16_ws_bytes(const AttnArgs&) { return 0; }
+// workspace: the pre-scaled LSE array, as large as delta
+size_t attn_bwd_bf16_ws_bytes(const AttnArgs& a) { return (size_t)a.B * a.H * a.S * sizeof(float); }
 
-void launch_attn_bwd_bf16(const AttnArgs& a, void*, hipStream_t s) {
+void launch_attn_bwd_bf16(const AttnArgs& args, void* ws, hipStream_t s) {
+  AttnArgs a = args;
+  a.nlse2 = (float*)ws;
   {
     ProfScope ps("attn_bwd_dq_bf16", s);
     dim3 grid(((a.S + dqk::BQ - 1) / dqk::BQ) * a.H * a.B);

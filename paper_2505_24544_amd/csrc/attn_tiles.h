@@ -125,6 +125,24 @@ __device__ __forceinline__ void pipeline_reads_mfma() {
   __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 }
 
+// The same run with V vector instructions (ordinary or transcendental) of independent work slotted
+// in after every MFMA, so that they issue while the matrix pipe is busy.
+template <int N, int RPM, int V>
+__device__ __forceinline__ void pipeline_reads_mfma_valu() {
+  __builtin_amdgcn_sched_group_barrier(0x100, 4 * RPM, 0);
+#pragma unroll
+  for (int i = 0; i < N - 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+    __builtin_amdgcn_sched_group_barrier(0x402, V, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x402, V, 0);
+  }
+}
+
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).  Memory loads complete in
 // order, so vmcnt(N) means "all but the N youngest loads have landed".

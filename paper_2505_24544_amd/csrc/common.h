@@ -107,6 +107,7 @@ struct AttnArgs {
   const void* dout;                               // dO [B,S,H,d]
   void* dq; void* dk; void* dv;                   // [B,S,H,d], [B,L,G,d] x2
   float* delta;                                   // [B,H,S]
+  float* nlse2;                                   // [B,H,S] -log2(e) * LSE, from the dQ kernel to the dK/dV kernel (bf16 path)
   // draft-tree decode only: keys >= n_true are visible to query p iff bit (j - n_true) of row p is set
   const uint32_t* tree; int32_t n_true, tree_words;
 };
