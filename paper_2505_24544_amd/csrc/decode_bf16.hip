@@ -100,6 +100,7 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
       }
   } else {
     // item = (query m, head hh of the 4, float4 column c4): all R ranges are loaded before any is used
+    // (two items in flight per thread were measured: no faster)
     const float c2 = cb.scale * LOG2E;
     for (int idx = tid; idx < M * 4 * 32; idx += 256) {
       const int c4 = idx & 31, hh = (idx >> 5) & 3, m = idx >> 7;
@@ -208,10 +209,15 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
   if (blockIdx.z == 1) { part = part_z1; y = y_z1; res = nullptr; }
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
-  float4 s = *(const float4*)(part + i);
-  for (int k = 1; k < KS; ++k) {
-    const float4 t = *(const float4*)(part + (int64_t)k * MN + i);
-    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+  // eight slices are loaded before any is added (one round trip to memory, not eight); the order of the sum is fixed
+  float4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < KS; k0 += 8) {
+    float4 t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = *(const float4*)(part + (int64_t)min(k0 + k, KS - 1) * MN + i);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k0 + k < KS) { s.x += t[k].x; s.y += t[k].y; s.z += t[k].z; s.w += t[k].w; }
   }
   if (res) {                                  // residual connection of Eq. 1
     const uint2 r = *(const uint2*)(res + i);
@@ -227,11 +233,20 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
                                                        bf16_t* __restrict__ m, int64_t MN, int KS) {
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
-  float4 u = *(const float4*)(upart + i), w = *(const float4*)(wpart + i);
-  for (int k = 1; k < KS; ++k) {
-    const float4 a = *(const float4*)(upart + (int64_t)k * MN + i), b = *(const float4*)(wpart + (int64_t)k * MN + i);
-    u.x += a.x; u.y += a.y; u.z += a.z; u.w += a.w;
-    w.x += b.x; w.y += b.y; w.z += b.z; w.w += b.w;
+  float4 u = {0.f, 0.f, 0.f, 0.f}, w = {0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < KS; k0 += 8) {        // eight slices of each in flight at a time
+    float4 a[8], b[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int64_t o = (int64_t)min(k0 + k, KS - 1) * MN + i;
+      a[k] = *(const float4*)(upart + o); b[k] = *(const float4*)(wpart + o);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k0 + k < KS) {
+        u.x += a[k].x; u.y += a[k].y; u.z += a[k].z; u.w += a[k].w;
+        w.x += b[k].x; w.y += b[k].y; w.z += b[k].z; w.w += b[k].w;
+      }
   }
   auto silu = [](float t) { return t / (1.f + expf(-t)); };
   uint2 v = {cvt_pk(silu(u.x) * w.x, silu(u.y) * w.y), cvt_pk(silu(u.z) * w.z, silu(u.w) * w.w)};
@@ -265,17 +280,21 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* pos, int
   tab[i] = make_float2((float)cs, (float)sn);
 }
 
-// One workgroup per (head, key range, block of 32 queries): grid (H, R, ceil(M / 32)).
+// One workgroup per (head, key range, block of 32 NQB queries): grid (H, R, ceil(M / (32 NQB))).  NQB = 1: the
+// four waves split each 128-key step, 32 keys each.  More than 32 queries (NQB = 2): waves 0, 1 take the first 32
+// queries and waves 2, 3 the next 32, each wave 64 keys of a step as two blocks of 32 -- the K / V tiles in LDS
+// serve both query blocks, so the cache is read once instead of once per block.
+template <int NQB>
 __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   using namespace dec;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];    // K step tile, V step tile: 64 KB
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  __shared__ __attribute__((aligned(16))) float qbuf[32 * HD];          // q of the block, float
+  __shared__ __attribute__((aligned(16))) float qbuf[32 * HD];          // q of one block, float
   __shared__ float s_ml[4][2][32];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int h = blockIdx.x, r = blockIdx.y;
-  const int m0 = 32 * blockIdx.z;                            // first query of the block
-  const int mrows = min(32, a.M - m0);                       // queries in the block
+  const int m0 = 32 * NQB * blockIdx.z;                      // first query of the workgroup
+  const int mtot = min(32 * NQB, a.M - m0);                  // its queries
   const int g = h / (a.H / a.G);
   const int HDt = a.H * HD;
   const int j_begin = r * a.range, j_end = min(j_begin + a.range, a.L);
@@ -288,7 +307,25 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     load_rows<KSTEP>(st, krs, kvs, j_begin + step * KSTEP, tid);
     load_rows<KSTEP>(st + TILE, vrs, kvs, j_begin + step * KSTEP, tid);
   };
-  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums it once into LDS (float4
+  // the same step requested by waves 1 .. 3 only: request n of the 64 (32 per tile, 64 chunks of 16 bytes each) is wave 1 + n % 3's
+  auto fetch3 = [&](bf16_t* st, int step) {
+    const int row0 = j_begin + step * KSTEP;
+#pragma unroll
+    for (int n0 = 0; n0 < 66; n0 += 3) {
+      const int n = n0 + wave - 1;
+      if (n < 64) {
+        const int q = 64 * (n & 31) + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
+        const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(n < 32 ? krs : vrs, (lds_void_ptr)(st + (n >> 5) * TILE + (n & 31) * 512), 16, off, 0, 0, 0);
+      }
+    }
+  };
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) float* lds_float_ptr;
+  const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums a block once into LDS (float4
   // slot c4 of row m sits at (c4 + 2 m) % 32 to spread the fragment reads over the banks), then every lane
   // picks up its B-operand fragments, split into bf16 hi + lo.
   //
@@ -298,88 +335,67 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   // rows; the other waves request theirs at once.  The fragments are read after the barrier that also
   // waits for the first step, with explicit ds_read instructions: the compiler cannot tell these reads
   // from the K/V requests in flight and would wait for all of them.
-  {
-    typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-    const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
-    const int qwaves = mrows <= 8 ? 1 : (mrows <= 16 ? 2 : 4);     // a summing wave covers 8 queries
-    if (wave < qwaves) {
-      // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
-      const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
-      const __amdgpu_buffer_rsrc_t qrs =
-          __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
-      const int oob = 0x7fffff00;
-      float4 acc[4] = {zero4, zero4, zero4, zero4};
-      // rotary embedding: this thread's four channels of query m pair with the four that lane ^ 16 holds
-      // (float4 slot c4 ^ 16 of the same query); their (cos, sin) are requested first, ahead of the slices
-      float4 cs[4][2];
-      if (a.rope_tab) {
+
+  // sum of the slices of block qb (queries m0 + 32 qb ..) held by this thread: four float4 (query idx >> 5,
+  // slot idx & 31 with idx = tid + 64 qwaves i), rotated if a rotary table is given
+  auto sum_block = [&](int qb, int mrows, int qwaves, float4 (&acc)[4]) {
+    // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
+    const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
+    const __amdgpu_buffer_rsrc_t qrs =
+        __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
+    const int oob = 0x7fffff00;
+    const int mb = m0 + 32 * qb;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int idx = tid + 64 * qwaves * i, m = min(idx >> 5, mrows - 1), c4 = idx & 15;
-          const float4* tp = (const float4*)(a.rope_tab + (int64_t)(m0 + m) * 64 + 4 * c4);
-          cs[i][0] = tp[0]; cs[i][1] = tp[1];
-        }
+    for (int i = 0; i < 4; ++i) acc[i] = zero4;
+    // rotary embedding: this thread's four channels of query m pair with the four that lane ^ 16 holds
+    // (float4 slot c4 ^ 16 of the same query); their (cos, sin) are requested first, ahead of the slices
+    float4 cs[4][2];
+    if (a.rope_tab) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 64 * qwaves * i, m = min(idx >> 5, mrows - 1), c4 = idx & 15;
+        const float4* tp = (const float4*)(a.rope_tab + (int64_t)(mb + m) * 64 + 4 * c4);
+        cs[i][0] = tp[0]; cs[i][1] = tp[1];
       }
-      for (int k0 = 0; k0 < a.KSq; k0 += 8) {                             // one pass for up to 8 slices
-        u32x4_t t[4][8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const int off = (int)((((int64_t)(k0 + k) * a.M + m0 + m) * HDt + h * HD + 4 * c4) * 4);
-            t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < mrows && k0 + k < a.KSq) ? off : oob, 0, 0);
-          }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
-            acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
-          }
-      }
-      if (a.rope_tab) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool upper = (tid & 16) != 0;               // channels 64 .. 127: x2 of the pair
-          const float4 own = acc[i];
-          float4 oth;
-          oth.x = __shfl_xor(own.x, 16, 64); oth.y = __shfl_xor(own.y, 16, 64);
-          oth.z = __shfl_xor(own.z, 16, 64); oth.w = __shfl_xor(own.w, 16, 64);
-          // x1' = x1 cos - x2 sin ; x2' = x2 cos + x1 sin  (cs holds (cos, sin) of pairs 4 c4 .. 4 c4 + 3)
-          const float sg = upper ? 1.f : -1.f;
-          acc[i].x = own.x * cs[i][0].x + sg * oth.x * cs[i][0].y;
-          acc[i].y = own.y * cs[i][0].z + sg * oth.y * cs[i][0].w;
-          acc[i].z = own.z * cs[i][1].x + sg * oth.z * cs[i][1].y;
-          acc[i].w = own.w * cs[i][1].z + sg * oth.w * cs[i][1].w;
-        }
-      }
+    }
+    for (int k0 = 0; k0 < a.KSq; k0 += 8) {                             // one pass for up to 8 slices
+      u32x4_t t[4][8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
-        *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int off = (int)((((int64_t)(k0 + k) * a.M + mb + m) * HDt + h * HD + 4 * c4) * 4);
+          t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < mrows && k0 + k < a.KSq) ? off : oob, 0, 0);
+        }
       }
-    } else {
-      // the rows behind the summed ones hold no query (only reached with fewer than four summing waves): zeros
-      for (int idx = 256 * qwaves + (tid - 64 * qwaves); idx < 32 * 32; idx += 256 - 64 * qwaves)
-        *(float4*)(qbuf + 4 * idx) = zero4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
+          acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
+        }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    if (nsteps > 0) fetch(stage0, 0);
-    if (nsteps > 1) fetch(stage1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  if (nsteps > 0) {
-    // the first step's loads are the oldest 16 of (up to) 32 in flight
-    if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
-  }
-  lds_barrier();                                             // first K/V step landed; q sum visible
-
-  bf16x8_t qh[8], qlo[8];
-  {
-    typedef float f32x4_t __attribute__((ext_vector_type(4)));
-    typedef __attribute__((address_space(3))) float* lds_float_ptr;
+    if (a.rope_tab) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool upper = (tid & 16) != 0;               // channels 64 .. 127: x2 of the pair
+        const float4 own = acc[i];
+        float4 oth;
+        oth.x = __shfl_xor(own.x, 16, 64); oth.y = __shfl_xor(own.y, 16, 64);
+        oth.z = __shfl_xor(own.z, 16, 64); oth.w = __shfl_xor(own.w, 16, 64);
+        // x1' = x1 cos - x2 sin ; x2' = x2 cos + x1 sin  (cs holds (cos, sin) of pairs 4 c4 .. 4 c4 + 3)
+        const float sg = upper ? 1.f : -1.f;
+        acc[i].x = own.x * cs[i][0].x + sg * oth.x * cs[i][0].y;
+        acc[i].y = own.y * cs[i][0].z + sg * oth.y * cs[i][0].w;
+        acc[i].z = own.z * cs[i][1].x + sg * oth.z * cs[i][1].y;
+        acc[i].w = own.w * cs[i][1].z + sg * oth.w * cs[i][1].w;
+      }
+    }
+  };
+  // B-operand fragments of the block in qbuf, as bf16 hi + lo (explicit ds_read, see above)
+  auto read_frags = [&](bf16x8_t (&qh)[8], bf16x8_t (&qlo)[8]) {
     f32x4_t t0[8], t1[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -400,6 +416,82 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         qlo[s][i] = (__bf16)(v[i] - (float)hi);
       }
     }
+  };
+
+  constexpr int WPB = 4 / NQB;                               // waves per query block
+  const int qbw = wave / WPB;                                // this wave's query block
+  bf16x8_t qh[8], qlo[8];
+  if constexpr (NQB == 1) {
+    const int qwaves = mtot <= 8 ? 1 : (mtot <= 16 ? 2 : 4);     // a summing wave covers 8 queries
+    if (wave < qwaves) {
+      float4 acc[4];
+      sum_block(0, mtot, qwaves, acc);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+        *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
+      }
+    } else {
+      // the rows behind the summed ones hold no query (only reached with fewer than four summing waves): zeros
+      for (int idx = 256 * qwaves + (tid - 64 * qwaves); idx < 32 * 32; idx += 256 - 64 * qwaves)
+        *(float4*)(qbuf + 4 * idx) = zero4;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (qwaves == 1) {
+      // One summing wave: it would only get to its share of the K/V requests once q is there, and the other
+      // three would wait for that at the barrier.  They take its share instead: the 64 requests of a step go
+      // round waves 1, 2, 3 (22, 21 and 21 of them).
+      if (wave > 0) {
+        if (nsteps > 0) fetch3(stage0, 0);
+        if (nsteps > 1) fetch3(stage1, 1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (nsteps > 0 && wave > 0) {
+        // all but the wave's requests of the second step have landed
+        if (nsteps == 1) wait_vmem(); else if (wave == 1) wait_vmem_n<22>(); else wait_vmem_n<21>();
+      }
+    } else {
+      if (nsteps > 0) fetch(stage0, 0);
+      if (nsteps > 1) fetch(stage1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (nsteps > 0) {
+        // the first step's loads are the oldest 16 of (up to) 32 in flight
+        if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
+      }
+    }
+    lds_barrier();                                             // first K/V step landed; q sum visible
+    read_frags(qh, qlo);
+  } else {
+    // two blocks, all four waves sum: block 0 goes to LDS before the K/V requests; block 1 is summed while they
+    // are in flight and goes through the same buffer once waves 0, 1 have their block-0 fragments.  After the
+    // requests the buffer is touched with explicit ds instructions only (see above).
+    float4 acc[4];
+    sum_block(0, 32, 4, acc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
+      *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
+    }
+    sum_block(1, mtot - 32, 4, acc);                           // rows past the last query: zeros
+    __builtin_amdgcn_sched_barrier(0);
+    if (nsteps > 0) fetch(stage0, 0);
+    if (nsteps > 1) fetch(stage1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_barrier();                                             // block 0 visible
+    if (qbw == 0) read_frags(qh, qlo);
+    lds_barrier();                                             // block 0 has been read
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
+      const f32x4_t v = {acc[i].x, acc[i].y, acc[i].z, acc[i].w};
+      asm volatile("ds_write_b128 %0, %1" : : "v"((lds_float_ptr)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31))), "v"(v) : "memory");
+    }
+    lds_barrier();                                             // block 1 visible
+    if (qbw == 1) read_frags(qh, qlo);
+    if (nsteps > 0) {
+      if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
+    }
+    lds_barrier();                                             // first K/V step landed
   }
   const float c2 = a.scale * LOG2E;
   const FragOffs fo = make_frag_offs(lane);
@@ -411,87 +503,91 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
   float mrun = -INFINITY, lrun = 0.f;
 
-  // one 128-key step: this wave takes rows 32 wave .. 32 wave + 31 of the step tiles
+  // one 128-key step: this wave takes NQB blocks of 32 rows of the step tiles, one after the other
   auto step_compute = [&](const bf16_t* cur, int step) {
     const bf16_t* ks = cur;
     const bf16_t* vs = cur + TILE;
-    const int jw = j_begin + step * KSTEP + 32 * wave;       // first key of this wave's block
-    if (jw < j_end) {
-      bf16x8_t kf[8];
 #pragma unroll
-      for (int s = 0; s < 8; ++s) kf[s] = row_frag(ks, fo, wave, s);
-      bf16x8_t vf[2][4];
+    for (int sub = 0; sub < NQB; ++sub) {
+      const int kb = (wave % WPB) * NQB + sub;                 // 32-row block of the step tiles
+      const int jw = j_begin + step * KSTEP + 32 * kb;         // its first key
+      if (jw < j_end) {
+        bf16x8_t kf[8];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+        for (int s = 0; s < 8; ++s) kf[s] = row_frag(ks, fo, kb, s);
+        bf16x8_t vf[2][4];
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) vf[t][cb] = tr_frag(vs, fo, 32 * wave + 16 * t, cb);
-      // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
-      f32x16_t st, st2;
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
+          for (int cb = 0; cb < 4; ++cb) vf[t][cb] = tr_frag(vs, fo, 32 * kb + 16 * t, cb);
+        // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
+        f32x16_t st, st2;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[s], st, 0, 0, 0);
-        st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[s], st2, 0, 0, 0);
-      }
+        for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) st[e] += st2[e];
-      if (jw + 32 > j_end) {
+        for (int s = 0; s < 8; ++s) {
+          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[s], st, 0, 0, 0);
+          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[s], st2, 0, 0, 0);
+        }
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
-      }
-      if (a.tree != nullptr && jw + 32 > a.n_true) {
-        // drafted rows: bit i of `vis` says whether this lane's query sees key jw + i (true rows: yes)
-        const int off = jw - a.n_true;                       // tree bit of key jw; negative inside the true rows
-        const int w0 = off >> 5, sh = off & 31;              // floor division: -1 for the straddling block
-        const uint32_t* row = a.tree + (int64_t)(m0 + ql) * a.tree_words;
-        const bool real = ql < mrows;
-        const uint32_t lo = w0 < 0 ? 0xffffffffu : (real && w0 < a.tree_words ? row[w0] : 0u);
-        const uint32_t hi = real && w0 + 1 < a.tree_words ? row[w0 + 1] : 0u;
-        const uint32_t vis = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
+        for (int e = 0; e < 16; ++e) st[e] += st2[e];
+        if (jw + 32 > j_end) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (!((vis >> (8 * (e >> 2) + 4 * hf + (e & 3))) & 1u)) st[e] = -INFINITY;
-      }
-      float mx = st[0];
+          for (int e = 0; e < 16; ++e)
+            if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
+        }
+        if (a.tree != nullptr && jw + 32 > a.n_true) {
+          // drafted rows: bit i of `vis` says whether this lane's query sees key jw + i (true rows: yes)
+          const int off = jw - a.n_true;                       // tree bit of key jw; negative inside the true rows
+          const int w0 = off >> 5, sh = off & 31;              // floor division: -1 for the straddling block
+          const uint32_t* row = a.tree + (int64_t)(m0 + 32 * qbw + ql) * a.tree_words;
+          const bool real = 32 * qbw + ql < mtot;
+          const uint32_t lo = w0 < 0 ? 0xffffffffu : (real && w0 < a.tree_words ? row[w0] : 0u);
+          const uint32_t hi = real && w0 + 1 < a.tree_words ? row[w0 + 1] : 0u;
+          const uint32_t vis = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
 #pragma unroll
-      for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
-      // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
-      // steps skip the rescaling of O
-      const bool grow = (mx - mrun) * c2 > 8.f;              // also true at the first step (reference -inf)
-      if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // wave-uniform
-        const float m_new = grow ? mx : mrun;                // finite: the block holds at least one real key
-        const float alpha = grow ? __builtin_amdgcn_exp2f((mrun - m_new) * c2) : 1.f;
-        lrun *= alpha;
-        mrun = m_new;
+          for (int e = 0; e < 16; ++e)
+            if (!((vis >> (8 * (e >> 2) + 4 * hf + (e & 3))) & 1u)) st[e] = -INFINITY;
+        }
+        float mx = st[0];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
+        // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
+        // steps skip the rescaling of O
+        const bool grow = (mx - mrun) * c2 > 8.f;              // also true at the first step (reference -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // wave-uniform
+          const float m_new = grow ? mx : mrun;                // finite: the block holds at least one real key
+          const float alpha = grow ? __builtin_amdgcn_exp2f((mrun - m_new) * c2) : 1.f;
+          lrun *= alpha;
+          mrun = m_new;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
-      }
-      const float mc = (mrun == -INFINITY ? 0.f : mrun) * c2;   // nothing visible so far: p = exp2(-inf) = 0
-      float rs = 0.f;
-      uint32_t pk[8];
+          for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(st[e] * c2 - mc);
-        const float p1 = __builtin_amdgcn_exp2f(st[e + 1] * c2 - mc);
-        rs += p0 + p1;
-        pk[e >> 1] = cvt_pk(p0, p1);
-      }
-      rs += __shfl_xor(rs, 32, 64);
-      lrun += rs;
+            for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+        }
+        const float mc = (mrun == -INFINITY ? 0.f : mrun) * c2;   // nothing visible so far: p = exp2(-inf) = 0
+        float rs = 0.f;
+        uint32_t pk[8];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        union { uint32_t u[4]; bf16x8_t v; } pf;
+        for (int e = 0; e < 16; e += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(st[e] * c2 - mc);
+          const float p1 = __builtin_amdgcn_exp2f(st[e + 1] * c2 - mc);
+          rs += p0 + p1;
+          pk[e >> 1] = cvt_pk(p0, p1);
+        }
+        rs += __shfl_xor(rs, 32, 64);
+        lrun += rs;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
+        for (int t = 0; t < 2; ++t) {
+          union { uint32_t u[4]; bf16x8_t v; } pf;
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-          o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb], pf.v, o[cb], 0, 0, 0);
+          for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb)
+            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb], pf.v, o[cb], 0, 0, 0);
+        }
       }
     }
   };
@@ -516,7 +612,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     }
   }
 
-  // ---- merge the four waves (fixed order) and write this key range's partial
+  // ---- merge the waves of each query block (fixed order) and write this key range's partial
   __syncthreads();
   // merge buffer [4 waves][32 queries][128 channels] floats = one stage; channel c of query q is stored at
   // (c + q) % 128 so that neither the per-query writes nor the per-channel reads conflict
@@ -532,22 +628,22 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     }
   if (hf == 0) { s_ml[wave][0][ql] = mrun; s_ml[wave][1][ql] = lrun; }
   __syncthreads();
-  for (int i = tid; i < mrows * HD; i += 256) {              // padding rows of the block are never read
-    const int c = i & (HD - 1), q = i >> 7;
+  for (int i = tid; i < mtot * HD; i += 256) {               // padding rows are never read
+    const int c = i & (HD - 1), qq = i >> 7, q = qq & 31, w0 = (qq >> 5) * WPB;   // query, its row in the block, first wave of the block
     float mm = -INFINITY;
 #pragma unroll
-    for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, s_ml[wv][0][q]);
+    for (int wv = 0; wv < WPB; ++wv) mm = fmaxf(mm, s_ml[w0 + wv][0][q]);
     float acc = 0.f, lt = 0.f;
     if (mm > -INFINITY) {
 #pragma unroll
-      for (int wv = 0; wv < 4; ++wv) {
-        const float sc = __builtin_amdgcn_exp2f((s_ml[wv][0][q] - mm) * c2);
-        acc += ob[(wv * 32 + q) * HD + ((c + q) & (HD - 1))] * sc;
-        lt += s_ml[wv][1][q] * sc;
+      for (int wv = 0; wv < WPB; ++wv) {
+        const float sc = __builtin_amdgcn_exp2f((s_ml[w0 + wv][0][q] - mm) * c2);
+        acc += ob[((w0 + wv) * 32 + q) * HD + ((c + q) & (HD - 1))] * sc;
+        lt += s_ml[w0 + wv][1][q] * sc;
       }
     }
-    a.opart[(pbase + q) * HD + c] = acc;
-    if (c == 0) { a.mlpart[(pbase + q) * 2] = mm; a.mlpart[(pbase + q) * 2 + 1] = lt; }
+    a.opart[(pbase + qq) * HD + c] = acc;
+    if (c == 0) { a.mlpart[(pbase + qq) * 2] = mm; a.mlpart[(pbase + qq) * 2 + 1] = lt; }
   }
 }
 
@@ -557,16 +653,31 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
                                                              int lse_stride, int Mpad, int H, int R, float scale) {
   const int m = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   const float c2 = scale * LOG2E;
+  const int64_t p0 = (int64_t)h * R * Mpad + m;              // range s sits at p0 + s * Mpad
+  // eight ranges are loaded at a time before any is used (one round trip to memory instead of eight); a batch
+  // that reaches past the last range repeats it, which changes neither the maximum nor (weight 0) the sums
   float mm = -INFINITY;
-  for (int s = 0; s < R; ++s) mm = fmaxf(mm, mlpart[(((int64_t)h * R + s) * Mpad + m) * 2]);
+  for (int s0 = 0; s0 < R; s0 += 8) {
+    float t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = mlpart[(p0 + (int64_t)min(s0 + k, R - 1) * Mpad) * 2];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mm = fmaxf(mm, t[k]);
+  }
   float acc = 0.f, lt = 0.f;
-  for (int s = 0; s < R; ++s) {
-    const int64_t pb = ((int64_t)h * R + s) * Mpad + m;
-    const float ms = mlpart[pb * 2];
-    if (ms == -INFINITY) continue;
-    const float sc = __builtin_amdgcn_exp2f((ms - mm) * c2);
-    acc += opart[pb * HD + c] * sc;
-    lt += mlpart[pb * 2 + 1] * sc;
+  for (int s0 = 0; s0 < R; s0 += 8) {
+    float ms[8], ls[8], ov[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int64_t pb = p0 + (int64_t)min(s0 + k, R - 1) * Mpad;
+      ms[k] = mlpart[pb * 2]; ls[k] = mlpart[pb * 2 + 1]; ov[k] = opart[pb * HD + c];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {                              // fixed order
+      const float sc = (s0 + k < R && ms[k] > -INFINITY) ? __builtin_amdgcn_exp2f((ms[k] - mm) * c2) : 0.f;
+      acc += ov[k] * sc;
+      lt += ls[k] * sc;
+    }
   }
   o[((int64_t)m * H + h) * HD + c] = f32_to_bf16(lt > 0.f ? acc / lt : 0.f);
   if (c == 0) lse[(int64_t)h * lse_stride + m] = lt > 0.f ? mm * scale + logf(lt) : -INFINITY;
@@ -642,7 +753,8 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       t.tree = a.tree ? a.tree + (int64_t)m0 * a.tree_words : nullptr; t.n_true = a.n_true; t.tree_words = a.tree_words;
       t.rope_tab = ropetab ? ropetab + (int64_t)m0 * 64 : nullptr;
       ProfScope ps("draft_attn", s);
-      hipLaunchKernelGGL(decode_attn_kernel, dim3(a.H, w.R, (Mp + 31) / 32), dim3(256), 0, s, t);
+      if (Mp > 32) hipLaunchKernelGGL(decode_attn_kernel<2>, dim3(a.H, w.R, (Mp + 63) / 64), dim3(256), 0, s, t);
+      else hipLaunchKernelGGL(decode_attn_kernel<1>, dim3(a.H, w.R, 1), dim3(256), 0, s, t);
     }
     if (Mp <= COMB_MAXM && w.R <= COMB_MAXR && HDt % SG_K == 0) {
       // few queries: the merge of the key ranges rides in the projection's prologue
