@@ -53,7 +53,7 @@ constexpr int TILE = KSTEP * HD;       // one K or V step tile
 // (4 consecutive k-rows x 64 B) hit four different bank quarters.
 // ---------------------------------------------------------------------------
 //
-// COMBINE: x is not read from memory.  It is the attention output of the M <= 8 draft queries, merged here
+// COMBINE: x is not read from memory.  It is the attention output of the M <= COMB_MAXM draft queries, merged here
 // from the split-KV partials of (B) while the W tile is on its way: the workgroup's 512 k are the channels
 // of 4 heads, each the (max, sum)-weighted mean of R key ranges; the result is rounded to bf16 as the
 // stand-alone merge (C) does.  Workgroups of the first column block also write the LSE of their heads.
@@ -63,7 +63,9 @@ struct CombineArgs {
   int Mpad, R;
   float scale;
 };
-constexpr int COMB_MAXM = 12, COMB_MAXR = 8;
+// every projection workgroup repeats the merge of its 4 heads, one round trip to memory per two queries: beyond
+// four queries the merge as a launch of its own is cheaper (measured at 8 and 10 queries)
+constexpr int COMB_MAXM = 4, COMB_MAXR = 8;
 
 template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
