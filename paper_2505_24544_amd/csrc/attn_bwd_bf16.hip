@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
     bf16x8_t of = *(const bf16x8_t*)(Og + 16 * s + 8 * hf);
     part += bwd::dot8(dof[s], of);
   }
-  const float delta = part + __shfl_xor(part, 32, 64);
+  const float delta = half_pair_sum(part);
   const float lse = a.lse[li];
   if (q_ok && hf == 0) { a.delta[li] = delta; a.nlse2[li] = -LOG2E * lse; }   // blind rows: +inf, masked in the dK/dV kernel
   const float c2 = a.scale * LOG2E;

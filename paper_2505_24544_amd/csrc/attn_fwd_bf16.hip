@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
           for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[jb][e]);
       };
       if (j0 + BJ > wave_lo) tile_max(std::true_type{}); else tile_max(std::false_type{});
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = half_pair_max(mx);
       // ---- online softmax for this lane's query.  The running reference m only moves when the
       // tile maximum exceeds it by more than 2^RESCALE_LOG2 in the exponent, so that most tiles
       // skip the rescaling of O; p then ranges up to 2^RESCALE_LOG2 instead of 1, which float
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
           rs += p0 + p1;
           pk[jb][e >> 1] = cvt_pk(p0, p1);
         }
-      rs += __shfl_xor(rs, 32, 64);
+      rs = half_pair_sum(rs);
       l += rs;
       // ---- O^T += V^T P^T ; step t of block jb uses S^T registers 8t .. 8t+7
       __builtin_amdgcn_sched_barrier(0);

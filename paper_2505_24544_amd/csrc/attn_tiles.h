@@ -88,6 +88,19 @@ __device__ __forceinline__ bf16x8_t tr_frag(const bf16_t* tile, const FragOffs& 
   return u.v;
 }
 
+// Maximum / sum of a value over a lane and its partner lane ^ 32, in every lane.  v_permlane32_swap exchanges the
+// upper half of one register with the lower half of another: fed the same value twice, every lane ends up with its
+// own value in one result and its partner's in the other -- one vector instruction instead of a trip through the
+// LDS crossbar (ds_bpermute), which sat on the critical path of every softmax step.
+__device__ __forceinline__ float half_pair_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_pair_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __device__ __forceinline__ uint32_t cvt_pk(float lo, float hi) {
   f32x2_t f = {lo, hi};
   bf16x2_t b = __builtin_convertvector(f, bf16x2_t);

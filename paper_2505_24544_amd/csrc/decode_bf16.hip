@@ -554,7 +554,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         float mx = st[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = half_pair_max(mx);
         // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
         // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
         // steps skip the rescaling of O
@@ -579,7 +579,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
           rs += p0 + p1;
           pk[e >> 1] = cvt_pk(p0, p1);
         }
-        rs += __shfl_xor(rs, 32, 64);
+        rs = half_pair_sum(rs);
         lrun += rs;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
