@@ -108,10 +108,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   };
 
   auto tile_step = [&](const bf16_t* cur, bf16_t* nxt, int jt) {
-    fetch(nxt, jt + 1);
-    __builtin_amdgcn_sched_barrier(0);
     const int j0 = jt * BJ;
+    if (j0 >= wave_hi) fetch(nxt, jt + 1);        // a wave that sees nothing of the tile only requests its share of the next
     if (j0 < wave_hi) {
+      fetch(nxt, jt + 1);                         // issued between the MFMAs below
       const bf16_t* ks = cur;
       const bf16_t* vs = cur + TILE;
       f32x16_t st[2], dp[2];
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
           dp[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(vs, fo, jb, s), dof[s], dp[jb], 0, 0, 0);
         }
       }
-      pipeline_reads_mfma<32, 1>();
+      pipeline_reads_mfma_loads<32, 1, 8>();
       __builtin_amdgcn_sched_barrier(0);
       // key offsets inside the tile are compile-time constants; tiles below every limit of the wave never mask
       const int rel = j0 + BJ > wave_lo ? lim - j0 - 4 * hf : BJ;

@@ -88,10 +88,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   };
 
   auto tile_step = [&](const bf16_t* cur, bf16_t* nxt, int jt) {
-    fetch(nxt, jt + 1);                           // past the last tile: zeros / unused, harmless
-    __builtin_amdgcn_sched_barrier(0);
     const int j0 = jt * BJ;
+    if (j0 >= wave_hi) fetch(nxt, jt + 1);        // a wave that sees nothing of the tile only requests its share of the next
     if (j0 < wave_hi) {                           // wave-uniform: this wave sees part of the tile
+      fetch(nxt, jt + 1);                         // past the last tile: zeros / unused, harmless; issued between the MFMAs below
       const bf16_t* ks = cur;
       const bf16_t* vs = cur + TILE;
       // ---- S^T = K Q^T  (two blocks of 32 keys)
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
         for (int s = 0; s < HD / 16; ++s)
           st[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag(ks, fo, jb, s), qf[s], st[jb], 0, 0, 0);
       }
-      pipeline_reads_mfma<16, 1>();
+      pipeline_reads_mfma_loads<16, 1, 8>();
       __builtin_amdgcn_sched_barrier(0);
       // ---- mask + tile maximum (register e of block jb is key j0 + 32 jb + 8 (e/4) + 4 hf + e%4).
       // Only tiles that straddle a limit of this wave evaluate the per-element predicate.

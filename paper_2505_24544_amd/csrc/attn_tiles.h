@@ -138,6 +138,22 @@ __device__ __forceinline__ void pipeline_reads_mfma() {
   __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 }
 
+// The same run with the first NL MFMAs each followed by one HBM -> LDS request: all waves of a workgroup pass
+// the barrier together, and requests issued in one burst right behind it queue up in the CU's address unit
+// (a 1 KB request takes it 16 cycles) while the waves' MFMAs wait behind them in program order.
+template <int N, int RPM, int NL>
+__device__ __forceinline__ void pipeline_reads_mfma_loads() {
+  static_assert(NL <= N - 4, "requests ride on the MFMAs that still have reads to issue");
+  __builtin_amdgcn_sched_group_barrier(0x100, 4 * RPM, 0);
+#pragma unroll
+  for (int i = 0; i < N - 4; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+    if (i < NL) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+}
+
 // The same run with V vector instructions (ordinary or transcendental) of independent work slotted
 // in after every MFMA, so that they issue while the matrix pipe is busy.
 template <int N, int RPM, int V>
