@@ -12,16 +12,15 @@ typedef uint16_t bf16_t;   // storage type: raw bfloat16 bits
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) {
   return __uint_as_float(((uint32_t)v) << 16);
 }
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// round-to-nearest-even, NaN stays NaN: the hardware conversion (v_cvt_pk_bf16_f32), two values per instruction
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __attribute__((__vector_size__(2 * sizeof(float)))) float cvt_f32x2_t;
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 cvt_bf16x2_t;
+  const cvt_f32x2_t f = {lo, hi};
+  const cvt_bf16x2_t b = __builtin_convertvector(f, cvt_bf16x2_t);
+  return *(const uint32_t*)&b;
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // ---- launch profiler (see beagle_xattn_profile_* in the public header) ----
 void prof_before(const char* name, hipStream_t s);

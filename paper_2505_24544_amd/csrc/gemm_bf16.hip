@@ -300,34 +300,72 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
 
   // ---- epilogue: lane holds C row m = .. + lane % 32; register e of tile (i, j)
   // holds column n = .. + 8 * (e / 4) + 4 * (lane / 32) + e % 4.
+  if constexpr (F32OUT) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int rt = wm + 32 * i + (lane & 31);      // row inside the tile
-    const int m = m0 + rt;
-    if (m >= g.M) continue;
-    const bf16_t* rrow = (rt < BM / 2 ? stage0 : stage1) + (rt % (BM / 2)) * BN;
+    for (int i = 0; i < TM; ++i) {
+      const int m = m0 + wm + 32 * i + (lane & 31);
+      if (m >= g.M) continue;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+      for (int j = 0; j < TN; ++j) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int ct = wn + 32 * j + 8 * q;        // first column of this 8-column chunk inside the tile
-        const int n = n0 + ct + 4 * (lane >> 5);
-        if (n >= g.N) continue;
-        float a0 = acc[i][j][4 * q], a1 = acc[i][j][4 * q + 1], a2 = acc[i][j][4 * q + 2],
-              a3 = acc[i][j][4 * q + 3];
-        if (with_res) {
-          const uint2 r = *(const uint2*)(rrow + (((ct >> 3) ^ (rt & (CPR - 1))) << 3) + 4 * (lane >> 5));
-          a0 += __uint_as_float(r.x << 16); a1 += __uint_as_float(r.x & 0xffff0000u);
-          a2 += __uint_as_float(r.y << 16); a3 += __uint_as_float(r.y & 0xffff0000u);
-        }
-        if (F32OUT) {
-          float4 v = {a0, a1, a2, a3};
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + wn + 32 * j + 8 * q + 4 * (lane >> 5);
+          if (n >= g.N) continue;
+          float4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
           *(float4*)((float*)g.C + (int64_t)m * g.ldc + n) = v;
-        } else {
-          uint2 v = {pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
-          *(uint2*)((bf16_t*)g.C + (int64_t)m * g.ldc + n) = v;
         }
       }
+    }
+  } else {
+    // bf16 output.  Straight from the registers a store instruction would carry 16 bytes for each of 32 rows, and
+    // the workgroup -- the only one on its CU -- spent 15 % of its life issuing them (measured: 27 500 cycles per
+    // 256 x 256 tile against 2 350 per k slice).  Each wave therefore transposes its part of the tile through a
+    // patch of LDS of its own (the operand stages are free now; two patches per stage) and writes whole row
+    // segments: 16 bytes per lane, 64 / CPW rows per instruction.  Patch rows hold CPW 16-byte chunks; chunk c
+    // of row r sits at position c ^ (r % CPW), which spreads the column-wise writes over the banks.
+    constexpr int CPW = 4 * TN;                      // chunks per patch row (32 TN columns)
+    constexpr int PROWS = 32 * TM;                   // patch rows
+    constexpr int RPI = 64 / CPW;                    // rows per store instruction
+    static_assert(CPW <= 64 && 64 % CPW == 0 && PROWS % RPI == 0, "patch rows must tile a wave");
+    static_assert(2 * PROWS * CPW * 8 <= XE + WE, "two patches per stage");
+    if (with_res) {
+      // the residual tile occupies the stages: take it into the accumulators first, then let go of it
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rt = wm + 32 * i + (lane & 31);      // row inside the tile
+        const bf16_t* rrow = (rt < BM / 2 ? stage0 : stage1) + (rt % (BM / 2)) * BN;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int ct = wn + 32 * j + 8 * q;        // first column of this 8-column chunk inside the tile
+            const uint2 r = *(const uint2*)(rrow + (((ct >> 3) ^ (rt & (CPR - 1))) << 3) + 4 * (lane >> 5));
+            acc[i][j][4 * q] += __uint_as_float(r.x << 16); acc[i][j][4 * q + 1] += __uint_as_float(r.x & 0xffff0000u);
+            acc[i][j][4 * q + 2] += __uint_as_float(r.y << 16); acc[i][j][4 * q + 3] += __uint_as_float(r.y & 0xffff0000u);
+          }
+      }
+    }
+    __syncthreads();                                 // every wave is done reading the stages
+    bf16_t* patch = (wave < 2 ? stage0 : stage1) + (wave & 1) * (PROWS * CPW * 8);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int pr = 32 * i + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint2 v = {pack_bf16x2(acc[i][j][4 * q], acc[i][j][4 * q + 1]), pack_bf16x2(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3])};
+          *(uint2*)(patch + pr * (CPW * 8) + (((4 * j + q) ^ (pr & (CPW - 1))) << 3) + 4 * (lane >> 5)) = v;
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the wave's own writes have landed; no other wave touches its patch
+    const int pp = lane % CPW, rsub = lane / CPW;
+#pragma unroll
+    for (int it = 0; it < PROWS / RPI; ++it) {
+      const int pr = it * RPI + rsub;
+      const uint4 v = *(const uint4*)(patch + pr * (CPW * 8) + pp * 8);
+      const int m = m0 + wm + pr, n = n0 + wn + 8 * (pp ^ (pr & (CPW - 1)));
+      if (m < g.M && n < g.N) { typedef unsigned int nt_u32x4 __attribute__((ext_vector_type(4))); const nt_u32x4 w = {v.x, v.y, v.z, v.w}; __builtin_nontemporal_store(w, (nt_u32x4*)((bf16_t*)g.C + (int64_t)m * g.ldc + n)); }
     }
   }
 }
