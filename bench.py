@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # scaled by a plain 1 GiB copy in the same run (profiles/hbm_traffic_c2_c4.md).  Counters cannot be read
 # from inside this process, so the figures are carried here for the workload they were measured on.
 MEASURED_TRAFFIC_BYTES = {
-    "c2": {"proj_qkv": 1222e6 + 201e6, "proj_out": 408e6 + 67e6, "bwd_dout": 412e6 + 67e6, "bwd_dwo": 403e6 + 34e6,
-           "bwd_dx": 1235e6 + 134e6, "bwd_dw": 1210e6 + 101e6},
+    "c2": {"proj_qkv": 1213e6 + 201e6, "proj_out": 405e6 + 67e6, "bwd_dout": 409e6 + 67e6, "bwd_dwo": 403e6 + 34e6,
+           "bwd_dx": 1231e6 + 134e6, "bwd_dw": 1212e6 + 101e6},
 }
 
 
