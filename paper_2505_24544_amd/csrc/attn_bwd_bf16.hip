@@ -215,10 +215,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const bf16_t* Vg = (const bf16_t*)a.v + kvrow;
   const int64_t qs = (int64_t)a.H * HD;
 
-  // first query that sees this lane's key / any key of the wave / any of the workgroup
+  // first query that sees this lane's key / any key of the wave / every key of the wave / any of the workgroup
   const MaskParams mk = sample_mask(a, b);
   const int fq = j_ok ? first_query_seeing(j, mk) : sv.S;
   const int wave_first = jw0 < sv.L ? first_query_seeing(jw0, mk) : sv.S;
+  const int wave_all = jw0 < sv.L ? first_query_seeing(min(jw0 + 32, sv.L) - 1, mk) : sv.S;
   const int wg_first = first_query_seeing(j0, mk);
   const int qt0 = wg_first / BQ;
   const int nqt = (sv.S + BQ - 1) / BQ;
@@ -276,9 +277,6 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
       // phase apart, so that the exponentials and products of one block issue between the MFMAs of
       // the other (this kernel has one wave per SIMD: nothing else would fill the matrix pipe then).
       // Register e of block qb is query q0 + 32 qb + 8 (e/4) + 4 hf + e%4 ; column = this lane's key.
-      // The per-element predicate is evaluated on every tile: its two instructions per element ride along
-      // between the MFMAs, and a second, predicate-free copy of this body made the register allocator shuffle
-      // the 128 accumulators on every step (measured: 15 % slower).
       {
         constexpr int VPM = 10;   // vector instructions of one block slotted in per MFMA of the other
         f32x16_t s2[2], dp[2];
@@ -302,20 +300,29 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
           }
         };
         auto probs = [&](int qb) {
+          float pv[16];
 #pragma unroll
           for (int e4 = 0; e4 < 4; ++e4) {
             const float ls[4] = {l4[e4].x, l4[e4].y, l4[e4].z, l4[e4].w};
-            const float dl[4] = {d4[e4].x, d4[e4].y, d4[e4].z, d4[e4].w};
-            float pv[4], dsv[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-              const int e = 4 * e4 + u;
-              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][e], c2, ls[u]));
-              if (32 * qb + 8 * e4 + u < relq) p = 0.f;   // also kills the +inf of blind queries (-log2(e) LSE = +inf)
-              pv[u] = p;
-              dsv[u] = p * (dp[qb][e] - dl[u]);
-            }
-            pp[qb][2 * e4] = cvt_pk(pv[0], pv[1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[2], pv[3]);
+            for (int u = 0; u < 4; ++u) pv[4 * e4 + u] = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[qb][4 * e4 + u], c2, ls[u]));
+          }
+          // The per-element predicate only where some key of the wave is hidden from some query of the block (a
+          // scalar branch around the compares and selects alone: the kernel is bound by instruction issue, and a
+          // second copy of the whole body made the register allocator shuffle the accumulators).  A blind query
+          // (-log2(e) LSE = +inf, p = +inf) is below fq for every key, so its block always comes through here.
+          if (q0 + 32 * qb < wave_all) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+              if (32 * qb + 8 * (e >> 2) + (e & 3) < relq) pv[e] = 0.f;
+          }
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const float dl[4] = {d4[e4].x, d4[e4].y, d4[e4].z, d4[e4].w};
+            float dsv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) dsv[u] = pv[4 * e4 + u] * (dp[qb][4 * e4 + u] - dl[u]);
+            pp[qb][2 * e4] = cvt_pk(pv[4 * e4], pv[4 * e4 + 1]); pp[qb][2 * e4 + 1] = cvt_pk(pv[4 * e4 + 2], pv[4 * e4 + 3]);
             pd[qb][2 * e4] = cvt_pk(dsv[0], dsv[1]); pd[qb][2 * e4 + 1] = cvt_pk(dsv[2], dsv[3]);
           }
         };
