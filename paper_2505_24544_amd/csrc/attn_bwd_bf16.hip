@@ -127,23 +127,29 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
       }
       pipeline_reads_mfma_loads<32, 1, 8>();
       __builtin_amdgcn_sched_barrier(0);
-      // key offsets inside the tile are compile-time constants; tiles below every limit of the wave never mask
-      const int rel = j0 + BJ > wave_lo ? lim - j0 - 4 * hf : BJ;
+      // dS = P (dP - delta); key offsets inside the tile are compile-time constants, and only tiles that reach
+      // past the smallest limit of the wave run the compares and selects (a scalar branch around them alone)
+      float dsv[2][16];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(st[jb][e] * c2 - lse2);
+          dsv[jb][e] = p * (dp[jb][e] - delta);
+        }
+      if (j0 + BJ > wave_lo) {
+        const int rel = lim - j0 - 4 * hf;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (32 * jb + 8 * (e >> 2) + (e & 3) >= rel) dsv[jb][e] = 0.f;
+      }
       uint32_t pk[2][8];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-          float ds[2];
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const int jo = 32 * jb + 8 * ((e + u) >> 2) + ((e + u) & 3);
-            const float p = __builtin_amdgcn_exp2f(st[jb][e + u] * c2 - lse2);
-            const float v = p * (dp[jb][e + u] - delta);
-            ds[u] = jo >= rel ? 0.f : v;
-          }
-          pk[jb][e >> 1] = cvt_pk(ds[0], ds[1]);
-        }
+        for (int e = 0; e < 16; e += 2) pk[jb][e >> 1] = cvt_pk(dsv[jb][e], dsv[jb][e + 1]);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
