@@ -182,13 +182,18 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
   xo.init(lane, wm);
   wo.init(lane, wn);
 
+  // The accumulators are cleared behind the first segment's first requests, not ahead of them: 256 register
+  // writes per lane are 2 000 cycles that the first round trip to memory can hide.
   f32x16_t acc[TM][TN];
+  auto clear_acc = [&]() {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  };
+  bool fresh = true;
 
 #pragma unroll 1
   for (int seg = 0; seg < 2; ++seg) {
@@ -261,6 +266,9 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
     __syncthreads();                        // previous segment: all reads done, both stages free
     fetch_x(stage0, 0);
     fetch_w(stage0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (fresh) { clear_acc(); fresh = false; }
+    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     frags(stage0, 0, 0);
@@ -274,6 +282,7 @@ __global__ __launch_bounds__(256, TM * TN >= 16 ? 1 : 2) void gemm_bf16_kernel(G
     if (kt < nk) slice(stage0, stage1, kt);
     __builtin_amdgcn_s_waitcnt(0x0F70);     // drain the look-ahead loads before the stages are reused
   }
+  if (fresh) clear_acc();                   // no segment at all: C = 0 (+ residual)
 
   // ---- residual operand: its tile goes HBM -> LDS in one burst (both stages are free now), so that the
   // epilogue below does not pay one HBM round trip per store.  Chunk q = tid + 256 i (16 bytes) of the tile
