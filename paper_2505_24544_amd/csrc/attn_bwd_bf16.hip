@@ -204,8 +204,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   using namespace dkv;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  __shared__ __attribute__((aligned(256))) float stat0[2 * BQ];    // [-log2(e) lse 64 | delta 64] of the stage's queries
-  __shared__ __attribute__((aligned(256))) float stat1[2 * BQ];
+  // [-log2(e) lse 64 | delta 64] of the stage's queries; waves 2 and 3 repeat the two requests into the second half,
+  // which nobody reads, so that the request sequence has no branch and can be issued between MFMAs
+  __shared__ __attribute__((aligned(256))) float stat0[4 * BQ];
+  __shared__ __attribute__((aligned(256))) float stat1[4 * BQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, jl = lane & 31;
   int row, jt;                                    // key tile 0 is seen by the most queries: heaviest first
   map_block(blockIdx.x, a.G * a.B, row, jt);
@@ -254,28 +256,30 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   const int64_t head0 = sv.q0 * a.H + g * rep;
   const bf16_t* f_q = (const bf16_t*)a.q + head0 * HD;           // row 0 of the fetch cursor's head
   const bf16_t* f_do = (const bf16_t*)a.dout + head0 * HD;
-  const float* f_stat = (wave == 0 ? a.nlse2 : a.delta) + sv.lse0 + (g * rep) * sv.lse_hs;
+  const float* f_stat = ((wave & 1) == 0 ? a.nlse2 : a.delta) + sv.lse0 + (g * rep) * sv.lse_hs;
+  const int tile_bytes = sv.S > 0 ? (int)((((int64_t)sv.S - 1) * qs + HD) * 2) : 0;   // one head's Q (dO) rows of this entry
   auto fetch = [&](bf16_t* st, float* stat) {
     const int q0 = f_qt * BQ;
-    const int rows = f_hh < rep ? sv.S : 0;          // past the last pair: fetch zeros
-    load_rows<BQ>(st, rows_rsrc(f_q, rows, qs), qs, q0, tid);
-    load_rows<BQ>(st + TILE, rows_rsrc(f_do, rows, qs), qs, q0, tid);
-    if (wave < 2) {
-      const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void*)f_stat, 0, rows * 4, 0x00020000);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(srs, (lds_void_ptr)(stat + wave * BQ), 4, (q0 + lane) * 4, 0, 0, 0);
-    }
-    if (++f_qt == nqt) {
-      f_qt = qt0;
-      if (++f_hh < rep) { f_q += HD; f_do += HD; f_stat += sv.lse_hs; }
-    }
+    const bool live = f_hh < rep;                    // past the last pair: empty descriptors, i.e. zeros
+    const int tbytes = live ? tile_bytes : 0, sbytes = live ? sv.S * 4 : 0;
+    load_rows<BQ>(st, __builtin_amdgcn_make_buffer_rsrc((void*)f_q, 0, tbytes, 0x00020000), qs, q0, tid);
+    load_rows<BQ>(st + TILE, __builtin_amdgcn_make_buffer_rsrc((void*)f_do, 0, tbytes, 0x00020000), qs, q0, tid);
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void*)f_stat, 0, sbytes, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(srs, (lds_void_ptr)(stat + wave * BQ), 4, (q0 + lane) * 4, 0, 0, 0);
+    // advance the cursor without branches
+    const bool wrap = f_qt + 1 == nqt;
+    const bool adv = wrap && f_hh + 1 < rep;
+    f_qt = wrap ? qt0 : f_qt + 1;
+    f_hh += wrap ? 1 : 0;
+    f_q += adv ? HD : 0; f_do += adv ? HD : 0; f_stat += adv ? sv.lse_hs : 0;
   };
 
   auto tile_step = [&](const bf16_t* cur, const float* sl, bf16_t* nxt, float* nstat) {
-    fetch(nxt, nstat);
-    __builtin_amdgcn_sched_barrier(0);
     const int q0 = c_qt * BQ;
     if (++c_qt == nqt) c_qt = qt0;
+    if (q0 + BQ <= wave_first) fetch(nxt, nstat);     // a wave that sees nothing of the tile only requests its share of the next
     if (q0 + BQ > wave_first) {                       // some query of the tile sees some key of the wave
+      fetch(nxt, nstat);                              // issued between the first MFMAs below
       const bf16_t* qsm = cur;
       const bf16_t* dsm = cur + TILE;
       const int relq = fq - q0 - 4 * hf;    // query offsets inside the tile are compile-time constants
@@ -346,7 +350,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
           }
         };
         scores(0);
-        pipeline_reads_mfma<16, 1>();
+        pipeline_reads_mfma_loads<16, 1, 9>();
         __builtin_amdgcn_sched_barrier(0);
         stats(0);
         scores(1);
