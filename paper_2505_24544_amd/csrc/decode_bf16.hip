@@ -40,7 +40,8 @@ using namespace tiles;
 namespace dec {
 constexpr int MAXM = 64;               // queries per pass
 constexpr int SG_N = 64;               // output columns per workgroup
-constexpr int SG_K = 512;              // k rows per workgroup (128 per wave)
+constexpr int SG_K = 512;              // k rows per workgroup
+constexpr int SG_KQ = SG_K / 4;        // k rows per quarter tile (32 per wave)
 constexpr int KSTEP = 128;             // keys per attention step (32 per wave)
 constexpr int TILE = KSTEP * HD;       // one K or V step tile
 }  // namespace dec
@@ -48,9 +49,10 @@ constexpr int TILE = KSTEP * HD;       // one K or V step tile
 // ---------------------------------------------------------------------------
 // (A)/(C)  part[ks][m][n] = sum_{k in slice ks} x[m][k] * W[k][n]   (float)
 //
-// W tile in LDS: 512 k-rows of 64 columns (128 B, 8 chunks); chunk c of k-row k
-// sits at chunk c ^ (((k >> 1) & 1) << 2), which makes the transpose reads
-// (4 consecutive k-rows x 64 B) hit four different bank quarters.
+// W tile in LDS: 512 k-rows of 64 columns (128 B, 8 chunks) in four quarters of
+// 128 k-rows; chunk c of k-row k sits at chunk c ^ (((k >> 1) & 1) << 2), which
+// makes the transpose reads (4 consecutive k-rows x 64 B) hit four different
+// bank quarters.
 // ---------------------------------------------------------------------------
 //
 // COMBINE: x is not read from memory.  It is the attention output of the M <= COMB_MAXM draft queries, merged here
@@ -73,65 +75,95 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
                                                              const bf16_t* __restrict__ W_z1, float* __restrict__ part_z1) {
   using namespace dec;
   if (blockIdx.z == 1) { W = W_z1; part = part_z1; }        // second weight matrix of the launch (same x)
-  __shared__ __attribute__((aligned(1024))) bf16_t wt[SG_K * SG_N];     // 64 KB
+  // The 64 KB tile as four quarters of 128 k-rows, one LDS variable each: requests land in the order they were
+  // issued, so quarter c is complete when all but the 12 - 4c youngest have landed, and its transpose reads
+  // (half-rate LDS instructions: 2 100 cycles for the whole tile with two workgroups per CU) run while the later
+  // quarters are still on their way.  Only the last quarter's reads are exposed behind the data.
+  __shared__ __attribute__((aligned(1024))) bf16_t wt0[SG_KQ * SG_N];
+  __shared__ __attribute__((aligned(1024))) bf16_t wt1[SG_KQ * SG_N];
+  __shared__ __attribute__((aligned(1024))) bf16_t wt2[SG_KQ * SG_N];
+  __shared__ __attribute__((aligned(1024))) bf16_t wt3[SG_KQ * SG_N];
   __shared__ __attribute__((aligned(16))) bf16_t xs[COMBINE ? COMB_MAXM * SG_K : 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5;
   const int n0 = blockIdx.x * SG_N, ks = blockIdx.y, k0 = ks * SG_K;
   const int mblocks = (M + 31) / 32;
 
-  // the whole tile is requested at once: 16 loads of 16 bytes per lane in flight
-  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, (int)((int64_t)K * N * 2), 0x00020000);
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int q = tid + 256 * i, k = q >> 3, c = (q & 7) ^ (((k >> 1) & 1) << 2);
-    const int off = (int)(((int64_t)(k0 + k) * N + n0 + 8 * c) * 2);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, (lds_void_ptr)(wt + (i * 4 + wave) * 512), 16, off, 0, 0, 0);
-  }
-
-  // x fragments (B operand): lane holds x[m][k0 + 128 wave + 16 st + 8 hf .. +7]
+  // Loads whose values this wave needs first go first (a wave's loads return in order).
+  // plain: x fragments (B operand): lane holds x[m][k0 + 128 c + 32 wave + 16 s2 + 8 hf .. +7] as xf[mb][2 c + s2]
   bf16x8_t xf[2][8];
+  // COMBINE: item = (query m, head hh of the 4, float4 column c4); all R ranges of a thread's (up to two) items
+  constexpr int NIT = COMB_MAXM * 4 * 32 / 256;
+  float2 ml[COMBINE ? NIT : 1][COMB_MAXR];
+  float4 ov[COMBINE ? NIT : 1][COMB_MAXR];
   if (!COMBINE) {
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int st = 0; st < 8; ++st) {
-        const int m = 32 * mb + (lane & 31), k = k0 + wave * 128 + st * 16 + 8 * hf;
+        const int m = 32 * mb + (lane & 31), k = k0 + (st >> 1) * SG_KQ + wave * 32 + (st & 1) * 16 + 8 * hf;
         bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
         xf[mb][st] = z;
         if (mb < mblocks && m < M && k < K) xf[mb][st] = *(const bf16x8_t*)(x + (int64_t)m * K + k);
       }
   } else {
-    // item = (query m, head hh of the 4, float4 column c4): all R ranges are loaded before any is used
-    // (two items in flight per thread were measured: no faster)
+    // unconditional loads from clamped indices (ranges past R repeat range 0, queries past M repeat the last one): a
+    // select on a loaded value here would make the compiler wait for each load before it issues the next
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (256 * it < M * 128) {
+        const int idx = tid + 256 * it;
+        const int c4 = idx & 31, hh = (idx >> 5) & 3, m = min(idx >> 7, M - 1);
+        const int h = k0 / HD + hh;
+#pragma unroll
+        for (int r = 0; r < COMB_MAXR; ++r) {
+          const int64_t pb = ((int64_t)h * cb.R + (r < cb.R ? r : 0)) * cb.Mpad + m;
+          ml[it][r] = *(const float2*)(cb.mlpart + pb * 2);
+          ov[it][r] = *(const float4*)(cb.opart + pb * HD + 4 * c4);
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // the whole tile is requested at once: 16 loads of 16 bytes per lane in flight
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)W, 0, (int)((int64_t)K * N * 2), 0x00020000);
+  auto request = [&](bf16_t* wq, int c) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int q = tid + 256 * i, k = q >> 3, ch = (q & 7) ^ (((k >> 1) & 1) << 2);
+      const int off = (int)(((int64_t)(k0 + c * SG_KQ + k) * N + n0 + 8 * ch) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, (lds_void_ptr)(wq + (i * 4 + wave) * 512), 16, off, 0, 0, 0);
+    }
+  };
+  request(wt0, 0); request(wt1, 1); request(wt2, 2); request(wt3, 3);
+  __builtin_amdgcn_sched_barrier(0);
+
+  float lsev[COMBINE ? NIT : 1];             // stored at the end: a store in flight would blur the count of landed requests
+  if (COMBINE) {
     const float c2 = cb.scale * LOG2E;
-    for (int idx = tid; idx < M * 4 * 32; idx += 256) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int idx = tid + 256 * it;
       const int c4 = idx & 31, hh = (idx >> 5) & 3, m = idx >> 7;
-      const int h = k0 / HD + hh;
-      float mr[COMB_MAXR], lr[COMB_MAXR];
-      float4 ov[COMB_MAXR];
+      lsev[it] = 0.f;
+      if (m < M) {
+        float mr[COMB_MAXR];
+        float mm = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < COMB_MAXR; ++r) {
-        const int64_t pb = ((int64_t)h * cb.R + (r < cb.R ? r : 0)) * cb.Mpad + m;
-        const float2 ml = *(const float2*)(cb.mlpart + pb * 2);
-        mr[r] = r < cb.R ? ml.x : -INFINITY;
-        lr[r] = ml.y;
-        ov[r] = *(const float4*)(cb.opart + pb * HD + 4 * c4);
+        for (int r = 0; r < COMB_MAXR; ++r) { mr[r] = r < cb.R ? ml[it][r].x : -INFINITY; mm = fmaxf(mm, mr[r]); }
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        float lt = 0.f;
+#pragma unroll
+        for (int r = 0; r < COMB_MAXR; ++r) {                  // fixed order
+          const float sc = mr[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mr[r] - mm) * c2);
+          acc.x += ov[it][r].x * sc; acc.y += ov[it][r].y * sc; acc.z += ov[it][r].z * sc; acc.w += ov[it][r].w * sc;
+          lt += ml[it][r].y * sc;
+        }
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        uint2 v = {cvt_pk(acc.x * inv, acc.y * inv), cvt_pk(acc.z * inv, acc.w * inv)};
+        *(uint2*)(xs + m * SG_K + hh * HD + 4 * c4) = v;
+        lsev[it] = lt > 0.f ? mm * cb.scale + logf(lt) : -INFINITY;
       }
-      float mm = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < COMB_MAXR; ++r) mm = fmaxf(mm, mr[r]);
-      float4 acc = {0.f, 0.f, 0.f, 0.f};
-      float lt = 0.f;
-#pragma unroll
-      for (int r = 0; r < COMB_MAXR; ++r) {                  // fixed order
-        const float sc = mr[r] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mr[r] - mm) * c2);
-        acc.x += ov[r].x * sc; acc.y += ov[r].y * sc; acc.z += ov[r].z * sc; acc.w += ov[r].w * sc;
-        lt += lr[r] * sc;
-      }
-      const float inv = lt > 0.f ? 1.f / lt : 0.f;
-      uint2 v = {cvt_pk(acc.x * inv, acc.y * inv), cvt_pk(acc.z * inv, acc.w * inv)};
-      *(uint2*)(xs + m * SG_K + hh * HD + 4 * c4) = v;
-      if (blockIdx.x == 0 && c4 == 0) cb.lse[(int64_t)h * cb.lse_stride + m] = lt > 0.f ? mm * cb.scale + logf(lt) : -INFINITY;
     }
   }
 
@@ -143,64 +175,101 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-  wait_vmem();
-  __syncthreads();
+  const int gi = lane >> 4, r16 = lane & 15;
+  // one quarter: the wave's 32 k-rows of it; the number of query blocks is a compile-time constant of each copy so that
+  // the eight transpose reads are issued together, ahead of the MFMAs
+  auto quarter_mb = [&](const bf16_t* wq, int c, auto mbc) {
+    constexpr int MB = decltype(mbc)::value;
+    bf16x8_t wf[2][2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int kr = wave * 32 + s2 * 16 + 8 * (gi >> 1) + (r16 >> 2);
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int col = 32 * nb + 16 * (gi & 1) + 4 * (r16 & 3);
+        const bf16_t* p0 = wq + kr * SG_N + ((((col >> 3) ^ (((kr >> 1) & 1) << 2)) << 3) | (col & 7));
+        const bf16_t* p1 = wq + (kr + 4) * SG_N + ((((col >> 3) ^ ((((kr + 4) >> 1) & 1) << 2)) << 3) | (col & 7));
+        union { struct { s16x4_t a, b; } s; bf16x8_t v; } u;
+        u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
+        u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p1);
+        wf[s2][nb] = u.v;
+      }
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s2][nb], xf[mb][2 * c + s2], acc[nb][mb], 0, 0, 0);
+  };
+  auto quarter = [&](const bf16_t* wq, int c) {
+    if (mblocks == 1) quarter_mb(wq, c, std::integral_constant<int, 1>{});
+    else quarter_mb(wq, c, std::integral_constant<int, 2>{});
+  };
+
+  wait_vmem_n<12>();
+  lds_barrier();                            // quarter 0 (and the merged x) complete for every wave
   if (COMBINE) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int m = lane & 31;
       bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
-      xf[0][st] = m < M ? *(const bf16x8_t*)(xs + m * SG_K + wave * 128 + st * 16 + 8 * hf) : z;
+      xf[0][st] = m < M ? *(const bf16x8_t*)(xs + m * SG_K + (st >> 1) * SG_KQ + wave * 32 + (st & 1) * 16 + 8 * hf) : z;
       xf[1][st] = z;
     }
   }
+  quarter(wt0, 0);
+  wait_vmem_n<8>();
+  lds_barrier();
+  quarter(wt1, 1);
+  wait_vmem_n<4>();
+  lds_barrier();
+  quarter(wt2, 2);
+  wait_vmem_n<0>();
+  lds_barrier();
+  quarter(wt3, 3);
+  lds_barrier();                            // every wave is done with the W tile
 
-  const int gi = lane >> 4, r16 = lane & 15;
-#pragma unroll
-  for (int st = 0; st < 8; ++st) {
-    const int kr = wave * 128 + st * 16 + 8 * (gi >> 1) + (r16 >> 2);
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int col = 32 * nb + 16 * (gi & 1) + 4 * (r16 & 3);
-      const bf16_t* p0 = wt + kr * SG_N + ((((col >> 3) ^ (((kr >> 1) & 1) << 2)) << 3) | (col & 7));
-      const bf16_t* p1 = wt + (kr + 4) * SG_N + ((((col >> 3) ^ ((((kr + 4) >> 1) & 1) << 2)) << 3) | (col & 7));
-      union { struct { s16x4_t a, b; } s; bf16x8_t v; } wf;
-      wf.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
-      wf.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p1);
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-        if (mb < mblocks) acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xf[mb][st], acc[nb][mb], 0, 0, 0);
-    }
-  }
-  __syncthreads();                          // every wave is done with the W tile
-  // merge the four waves' k-quarters through LDS: red[wave][m][(n + 4 m) % 64] (the rotation spreads the
-  // per-row float4 writes over the banks)
-  float* red = (float*)wt;
-  constexpr int RLD = SG_N;
-  static_assert(4 * MAXM * RLD * sizeof(float) <= sizeof(wt), "merge buffer must fit in the W tile");
+  // merge the four waves' k-shares through LDS, one quarter per (column half nb, query block mb):
+  // red[2 nb + mb][wave][m % 32][(n % 32 + 4 m) % 32] (the rotation spreads the per-row float4 writes over the banks)
+  auto red = [&](int i) -> float* { return (float*)(i == 0 ? wt0 : i == 1 ? wt1 : i == 2 ? wt2 : wt3); };
+  static_assert(4 * 32 * 32 * sizeof(float) <= sizeof(wt0), "merge buffer must fit in a quarter tile");
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
       if (mb < mblocks) {
+        const int ml = lane & 31;
+        if (32 * mb + ml < M) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int m = 32 * mb + (lane & 31), n = 32 * nb + 8 * q + 4 * hf;
-          float4 v = {acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
-          *(float4*)(red + (wave * MAXM + m) * RLD + ((n + 4 * m) & (SG_N - 1))) = v;
+          for (int q = 0; q < 4; ++q) {
+            const int nl = 8 * q + 4 * hf;
+            float4 v = {acc[nb][mb][4 * q], acc[nb][mb][4 * q + 1], acc[nb][mb][4 * q + 2], acc[nb][mb][4 * q + 3]};
+            *(float4*)(red(2 * nb + mb) + (wave * 32 + ml) * 32 + ((nl + 4 * ml) & 31)) = v;
+          }
         }
       }
   __syncthreads();
   for (int i = tid; i < M * (SG_N / 4); i += 256) {
     const int m = i / (SG_N / 4), n = (i % (SG_N / 4)) * 4;
-    const int nr = (n + 4 * m) & (SG_N - 1);
-    float4 s = *(const float4*)(red + m * RLD + nr);
+    const int ml = m & 31, nr = ((n & 31) + 4 * ml) & 31;
+    const float* rp = red(2 * (n >> 5) + (m >> 5)) + ml * 32 + nr;
+    float4 s = *(const float4*)rp;
 #pragma unroll
     for (int wv = 1; wv < 4; ++wv) {
-      const float4 t = *(const float4*)(red + (wv * MAXM + m) * RLD + nr);
+      const float4 t = *(const float4*)(rp + wv * 32 * 32);
       s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
     *(float4*)(part + ((int64_t)ks * M + m) * N + n0 + n) = s;
+  }
+  if (COMBINE && blockIdx.x == 0) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int idx = tid + 256 * it;
+      const int c4 = idx & 31, hh = (idx >> 5) & 3, m = idx >> 7;
+      if (m < M && c4 == 0) cb.lse[(int64_t)(k0 / HD + hh) * cb.lse_stride + m] = lsev[it];
+    }
   }
 }
 
