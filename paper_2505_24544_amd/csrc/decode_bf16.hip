@@ -69,6 +69,8 @@ struct CombineArgs {
 // four queries the merge as a launch of its own is cheaper (measured at 8 and 10 queries)
 constexpr int COMB_MAXM = 4, COMB_MAXR = 8;
 
+typedef unsigned int xload_t __attribute__((ext_vector_type(4)));
+
 template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
                                                              float* __restrict__ part, int M, int N, int K, CombineArgs cb,
@@ -96,15 +98,25 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
   float2 ml[COMBINE ? NIT : 1][COMB_MAXR];
   float4 ov[COMBINE ? NIT : 1][COMB_MAXR];
   if (!COMBINE) {
+    // branch-free: rows past M and channels past K are asked for beyond the end of the descriptor and arrive as zeros
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void*)x, 0, (int)((int64_t)M * K * 2), 0x00020000);
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
       for (int st = 0; st < 8; ++st) {
-        const int m = 32 * mb + (lane & 31), k = k0 + (st >> 1) * SG_KQ + wave * 32 + (st & 1) * 16 + 8 * hf;
-        bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+        const bf16x8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
         xf[mb][st] = z;
-        if (mb < mblocks && m < M && k < K) xf[mb][st] = *(const bf16x8_t*)(x + (int64_t)m * K + k);
       }
+      if (mb < mblocks) {
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+          const int m = 32 * mb + (lane & 31), k = k0 + (st >> 1) * SG_KQ + wave * 32 + (st & 1) * 16 + 8 * hf;
+          union { xload_t u; bf16x8_t v; } t;
+          t.u = __builtin_amdgcn_raw_buffer_load_b128(xrs, (m < M && k < K) ? (m * K + k) * 2 : (int)0x80000000, 0, 0);
+          xf[mb][st] = t.v;
+        }
+      }
+    }
   } else {
     // unconditional loads from clamped indices (ranges past R repeat range 0, queries past M repeat the last one): a
     // select on a loaded value here would make the compiler wait for each load before it issues the next
@@ -114,11 +126,13 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
         const int idx = tid + 256 * it;
         const int c4 = idx & 31, hh = (idx >> 5) & 3, m = min(idx >> 7, M - 1);
         const int h = k0 / HD + hh;
+        const float* mlp = cb.mlpart + ((int64_t)h * cb.R * cb.Mpad + m) * 2;
+        const float* ovp = cb.opart + ((int64_t)h * cb.R * cb.Mpad + m) * HD + 4 * c4;
 #pragma unroll
         for (int r = 0; r < COMB_MAXR; ++r) {
-          const int64_t pb = ((int64_t)h * cb.R + (r < cb.R ? r : 0)) * cb.Mpad + m;
-          ml[it][r] = *(const float2*)(cb.mlpart + pb * 2);
-          ov[it][r] = *(const float4*)(cb.opart + pb * HD + 4 * c4);
+          const int rr = (r < cb.R ? r : 0) * cb.Mpad;          // wave-uniform
+          ml[it][r] = *(const float2*)(mlp + rr * 2);
+          ov[it][r] = *(const float4*)(ovp + rr * HD);
         }
       }
     }
@@ -229,7 +243,8 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
   wait_vmem_n<0>();
   lds_barrier();
   quarter(wt3, 3);
-  lds_barrier();                            // every wave is done with the W tile
+  // up to 32 queries the merge below uses quarters 0 and 2 only, which every wave has left behind at the last barrier
+  if (mblocks > 1) lds_barrier();
 
   // merge the four waves' k-shares through LDS, one quarter per (column half nb, query block mb):
   // red[2 nb + mb][wave][m % 32][(n % 32 + 4 m) % 32] (the rotation spreads the per-row float4 writes over the banks)
