@@ -409,6 +409,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) float* lds_float_ptr;
+  typedef __attribute__((address_space(3))) bf16_t* lds_bf16_ptr;
+  typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
   const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums a block once into LDS (float4
@@ -598,22 +600,32 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       const int kb = (wave % WPB) * NQB + sub;                 // 32-row block of the step tiles
       const int jw = j_begin + step * KSTEP + 32 * kb;         // its first key
       if (jw < j_end) {
-        bf16x8_t kf[8];
+        // Explicit ds_read instructions (same addresses as row_frag / tr_frag): for LDS reads it can see, the compiler
+        // waits until no HBM -> LDS request is in flight at all (the requests sit in branches, so it cannot count
+        // the ones behind this stage's), and the refill of the other stage would never overlap this arithmetic.
+        union { u32x4_t u; bf16x8_t v; } kf[8];
+        union { struct { u32x2_t x, y; } s; bf16x8_t v; } vf[2][4];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) kf[s] = row_frag(ks, fo, kb, s);
-        bf16x8_t vf[2][4];
+        for (int s = 0; s < 8; ++s)
+          asm volatile("ds_read_b128 %0, %1" : "=v"(kf[s].u) : "v"((lds_bf16_ptr)(ks + kb * 32 * HD + fo.row[s])));
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) vf[t][cb] = tr_frag(vs, fo, 32 * kb + 16 * t, cb);
+          for (int cb = 0; cb < 4; ++cb) {
+            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.x) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][0])));
+            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.y) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][1])));
+          }
+        asm volatile("s_waitcnt lgkmcnt(16)" ::: "memory");      // LDS reads return in order: the 8 K fragments are there
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
         // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
         f32x16_t st, st2;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qh[s], st, 0, 0, 0);
-          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qlo[s], st2, 0, 0, 0);
+          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qh[s], st, 0, 0, 0);
+          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qlo[s], st2, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) st[e] += st2[e];
@@ -665,6 +677,11 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         }
         rs = half_pair_sum(rs);
         lrun += rs;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the V fragments
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) asm volatile("" : "+v"(vf[t][cb].s.x), "+v"(vf[t][cb].s.y));
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
@@ -672,28 +689,29 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
           for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb)
-            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb], pf.v, o[cb], 0, 0, 0);
+            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb].v, pf.v, o[cb], 0, 0, 0);
         }
       }
     }
   };
 
-  // two stages, both requested up front; a stage is refilled as soon as every wave is done with it
+  // two stages, both requested up front; a stage is refilled as soon as every wave is done with it, and the refill
+  // stays in flight while the other stage is worked on (barriers without a fence: a fence would wait for it)
 #pragma unroll 1
   for (int step = 0; step < nsteps; step += 2) {
     step_compute(stage0, step);
-    __syncthreads();                                        // all waves done with stage0
+    lds_barrier();                                          // all waves done with stage0
     if (step + 2 < nsteps) fetch(stage0, step + 2);
     if (step + 1 < nsteps) {
       // stage1's loads (step + 1) are older than the refill just issued
       if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-      __syncthreads();
+      lds_barrier();
       step_compute(stage1, step + 1);
-      __syncthreads();
+      lds_barrier();
       if (step + 3 < nsteps) fetch(stage1, step + 3);
       if (step + 2 < nsteps) {
         if (step + 3 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-        __syncthreads();
+        lds_barrier();
       }
     }
   }
