@@ -6,7 +6,8 @@
 // single round); the matrix cores only keep arithmetic off the critical path.
 //
 //   (A) skinny_gemm   q_part[ks] = x * Wq[k-slice ks]        grid (N/64) x (K/512),
-//                     two workgroups per CU, the whole chip resident at once
+//                     two workgroups per CU, the whole chip resident at once; the
+//                     64 KB tile is worked on in quarters as they land
 //   (B) decode_attn   one workgroup per (head, key range, block of 32 queries);
 //                     its 4 waves split each 128-key step by rows.  A lane owns
 //                     one query (as in the training forward): online softmax per
@@ -16,8 +17,7 @@
 //                     q at ~16 bits.  Waves are merged in LDS; each range writes
 //                     an unnormalised partial.
 //   (C) combine       merges the key ranges, writes o (bf16) and the LSE; with up
-//                     to 12 queries (the paper's draft width is 10) this runs in the
-//                     prologue of (D) instead
+//                     to 4 queries this runs in the prologue of (D) instead
 //   (D) skinny_gemm   y_part[ks] = o * Wo[k-slice ks]
 //   (E) sum_slices    y = sum_ks y_part[ks]  (bf16)
 //
