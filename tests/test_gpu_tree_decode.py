@@ -124,6 +124,7 @@ def test_c4_tree_step_paper_shaped_tree():
     ("f32", 5, 3, 20, 2, 256, 64), ("f32", 1, 0, 1, 4, 256, 64),
     ("bf16", 1, 4096, 4200, 32, 4096, 128), ("bf16", 10, 37, 300, 4, 512, 128), ("bf16", 60, 100, 160, 2, 1024, 128),
     ("bf16", 300, 0, 300, 8, 512, 128),
+    ("bf16", 7, 11, 64, 2, 832, 128), ("bf16", 40, 0, 40, 1, 320, 128),   # partial last k-slice; two blocks of states
 ])
 def test_kv_append(dtype, n, pos, cap, G, D, d):
     rng = np.random.default_rng(n + pos)
