@@ -615,7 +615,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
             asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.x) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][0])));
             asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.y) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][1])));
           }
-        asm volatile("s_waitcnt lgkmcnt(16)" ::: "memory");      // LDS reads return in order: the 8 K fragments are there
+        // LDS reads return in order and the counter holds at most 15: at most 15 of the 24 still out means the
+        // first 9 are there, the 8 K fragments among them
+        asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
         // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
