@@ -200,7 +200,8 @@ def _decode_problem(M, L, H, G, D, seed):
                                        (100, 300, 4, 2, 512),     # two passes of 64 queries
                                        (3, 500, 2, 2, 8192),      # 16 k-slices of q
                                        (2, 300, 4, 4, 576),       # hidden width not a multiple of the 512-row k-slice
-                                       (33, 200, 2, 1, 320)])     # one partial k-slice, two query blocks
+                                       (33, 200, 2, 1, 320),      # one partial k-slice, two query blocks
+                                       (12, 700, 4, 4, 512), (10, 90, 4, 2, 512)])   # two waves sum q; a single step
 def test_decode_reduced(M, L, H, G, D):
     cfg, inp, kc, vc = _decode_problem(M, L, H, G, D, 400 + M)
     ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G)
