@@ -697,6 +697,38 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     }
   };
 
+  if constexpr (NQB == 1) {
+    // Two stages, both requested up front.  A wave reads only its own 32 rows of a step's K and V tiles, so in the
+    // loop every wave refills exactly those rows itself, right after it has used them: past the first two steps
+    // (whose requests were shared out differently above) the waves do not depend on each other and the loop has
+    // no barrier; the refill stays in flight while the other stage is worked on.
+    auto fetch_own = [&](bf16_t* st, int step) {
+      const int row0 = j_begin + step * KSTEP;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int q = 512 * wave + 64 * i + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
+          const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(t ? vrs : krs, (lds_void_ptr)(st + t * TILE + (8 * wave + i) * 512), 16, off, 0, 0, 0);
+        }
+    };
+#pragma unroll 1
+    for (int step = 0; step < nsteps; step += 2) {
+      if (step > 0) {
+        // this wave's rows of `step` are older than its refill for step + 1
+        if (step + 1 < nsteps) wait_vmem_n<16>(); else wait_vmem();
+      }
+      step_compute(stage0, step);
+      if (step + 2 < nsteps) fetch_own(stage0, step + 2);
+      if (step + 1 < nsteps) {
+        if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
+        if (step == 0) lds_barrier();                         // step 1 was requested by other waves
+        step_compute(stage1, step + 1);
+        if (step + 3 < nsteps) fetch_own(stage1, step + 3);
+      }
+    }
+  } else {
   // two stages, both requested up front; a stage is refilled as soon as every wave is done with it, and the refill
   // stays in flight while the other stage is worked on (barriers without a fence: a fence would wait for it)
 #pragma unroll 1
@@ -716,6 +748,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         lds_barrier();
       }
     }
+  }
   }
 
   // ---- merge the waves of each query block (fixed order) and write this key range's partial
