@@ -47,9 +47,12 @@
  *
  * Supported shapes
  *   BEAGLE_F32 : any d <= 128 with d % 4 == 0; D, H*d, G*d multiples of 4.
- *   BEAGLE_BF16: d == 128; D a multiple of 64.
+ *   BEAGLE_BF16: d == 128; D a multiple of 64; every operand smaller than
+ *                2 GiB: max(B*S, B*L) * max(D, H*d) * 2 < 2^31 and
+ *                D * H*d * 2 < 2^31 (block entry points: the same with F).
  *   B, S, L >= 1 arbitrary (ragged tiles are handled); anything else returns
- *   BEAGLE_ERR_UNSUPPORTED -- there is no fallback path.
+ *   BEAGLE_ERR_UNSUPPORTED before anything is enqueued -- there is no fallback
+ *   path and no slower kernel behind these limits.
  */
 #ifndef BEAGLE_XATTN_H
 #define BEAGLE_XATTN_H
@@ -96,13 +99,13 @@ enum { BEAGLE_WS_FWD = 0, BEAGLE_WS_BWD = 1, BEAGLE_WS_DRAFT = 2, BEAGLE_WS_APPE
 typedef struct {
   int32_t struct_size;   /* sizeof(beagle_xattn_desc); checked                  */
   int32_t batch;         /* B                                                   */
-  int32_t seq_q;         /* S  (draft step: M, the number of draft queries)     */
-  int32_t seq_kv;        /* L  (training: usually == S)                         */
+  int32_t seq_q;         /* S <= 2^30 (draft step: M, the number of draft queries) */
+  int32_t seq_kv;        /* L <= 2^30 (training: usually == S)                  */
   int32_t hidden;        /* D                                                   */
   int32_t n_q_heads;     /* H                                                   */
   int32_t n_kv_heads;    /* G, divides H                                        */
   int32_t head_dim;      /* d                                                   */
-  int32_t block_size;    /* k >= 1 (section 4.2 window size)                    */
+  int32_t block_size;    /* 1 <= k <= 2^30 (section 4.2 window size)            */
   int32_t block_offset;  /* eps in [0, k) (section 4.2 random offset)           */
   int32_t io_dtype;      /* beagle_dtype                                        */
   float   softmax_scale; /* 0 selects 1/sqrt(d) as in Eq. 2                     */
@@ -413,7 +416,8 @@ beagle_status beagle_xattn_kv_append(const beagle_xattn_desc* desc,
 
 /*
  * Draft step with the drafted states concatenated to the cache, under a draft
- * tree (section 6: the "concate" option with the dynamic drafting tree).  The
+ * tree (appendix "Ablation Study": the "concate" option with the dynamic
+ * drafting tree; tree shape in section 5.1).  The
  * cache holds n_true rows of true states followed by T = desc->seq_kv - n_true
  * rows of drafted states.  Query m sees every true row, and drafted row
  * n_true + t iff bit (t % 32) of tree_mask[m * mask_words + t / 32] is set.
@@ -455,6 +459,17 @@ beagle_status beagle_xattn_tile_map(const beagle_xattn_desc* desc, int32_t tq, i
 beagle_status beagle_xattn_profile_begin(void);
 int32_t       beagle_xattn_profile_end(void);
 beagle_status beagle_xattn_profile_get(int32_t i, const char** name, int32_t* launches, double* total_ms);
+
+/* ---- streaming-read reference (measurement aid) ----------------------------
+ * Enqueues a kernel that does nothing but read `bytes` bytes (a multiple of 16)
+ * from the DEVICE buffer `buf` with 16-byte loads, `workgroups` workgroups of
+ * 256 threads, eight loads in flight per thread.  Timed by the caller over a
+ * buffer it has not touched recently, this is what the memory system delivers
+ * to a read-only kernel: the practical ceiling next to which the decode step's
+ * achieved bandwidth (section 4.1, KV-cache paragraph: the step streams the
+ * cache once) is reported.  `sink` is a DEVICE pointer to 4 writable bytes
+ * (written only if the XOR of all words read equals one magic value).        */
+beagle_status beagle_xattn_probe_read(const void* buf, size_t bytes, int32_t workgroups, void* sink, void* hip_stream);
 
 const char* beagle_xattn_status_string(beagle_status s);
 /* "major.minor" of this ABI. */

@@ -514,10 +514,11 @@ def draft_step(x, k_cache, v_cache, wq, wo, *, n_q_heads, n_kv_heads, scale=None
 
 # --------------------------------------------------------------------------
 # Decode with drafted states concatenated to the cache, under a draft tree
-# (section 4.1, KV-cache paragraph: "append new states K_i, V_i ... reset
-# KV-cache to only contain true states at the end of SD iteration"; section 6:
-# the "concate" option and the EAGLE-style dynamic drafting tree, depth 1+6,
-# top-k 10, 60 candidates)
+# (section 4.1, KV-cache paragraph: newly drafted states' K and V rows are
+# appended as drafting proceeds and the cache goes back to the true states
+# when a speculative-decoding iteration ends; appendix "Ablation Study": the
+# "concate" option and the dynamic drafting tree; section 5.1: its shape,
+# depth 1+6, top-k 10, 60 candidates)
 #
 # Readings taken here (the paper gives no formula for the tree mask):
 #   * The cache holds n_true rows of true target states followed by the rows

@@ -35,7 +35,7 @@ EXPORTS = (
     "beagle_xattn_block_kv_append",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
-    "beagle_xattn_status_string", "beagle_xattn_version",
+    "beagle_xattn_probe_read", "beagle_xattn_status_string", "beagle_xattn_version",
 )
 
 
@@ -173,6 +173,8 @@ def lib() -> C.CDLL:
     L.beagle_xattn_profile_get.restype = C.c_int
     L.beagle_xattn_profile_get.argtypes = [C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int32),
                                            C.POINTER(C.c_double)]
+    L.beagle_xattn_probe_read.restype = C.c_int
+    L.beagle_xattn_probe_read.argtypes = [vp, C.c_size_t, C.c_int32, vp, vp]
     L.beagle_xattn_status_string.restype = C.c_char_p
     L.beagle_xattn_status_string.argtypes = [C.c_int]
     L.beagle_xattn_version.restype = C.c_char_p
@@ -376,6 +378,11 @@ def beagle_xattn_profile_end() -> dict:
                "beagle_xattn_profile_get", True)
         out[name.value.decode()] = (cnt.value, ms.value)
     return out
+
+
+def beagle_xattn_probe_read(buf, nbytes: int, workgroups: int, sink, stream=None) -> None:
+    _check(lib().beagle_xattn_probe_read(_ptr(buf), nbytes, workgroups, _ptr(sink), _stream(stream)),
+           "beagle_xattn_probe_read", True)
 
 
 def beagle_xattn_status_string(status: int) -> str:

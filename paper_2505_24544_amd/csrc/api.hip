@@ -23,6 +23,8 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
   if (!draft && (c->block_size < 1 || c->block_offset < 0 || c->block_offset >= c->block_size))
     return BEAGLE_ERR_SHAPE;
   if (draft && c->batch != 1) return BEAGLE_ERR_SHAPE;
+  // the index code works in int32: lengths and window sizes up to 2^30 keep every intermediate in range
+  if (c->seq_q > (1 << 30) || c->seq_kv > (1 << 30) || (!draft && c->block_size > (1 << 30))) return BEAGLE_ERR_UNSUPPORTED;
   if (c->flags & ~KNOWN_FLAGS) return BEAGLE_ERR_UNSUPPORTED;
   if (c->io_dtype != BEAGLE_F32 && c->io_dtype != BEAGLE_BF16) return BEAGLE_ERR_UNSUPPORTED;
   if (!(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return BEAGLE_ERR_SHAPE;
@@ -42,7 +44,12 @@ beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out) {
     // through 32-bit buffer descriptors
     const int64_t lim = (int64_t)1 << 31;
     if (d.S * d.HD * 2 >= lim || d.L * d.GD * 2 >= lim) return BEAGLE_ERR_UNSUPPORTED;
-    if (draft && (d.D * d.HD * 2 >= lim || d.D * d.GD * 2 >= lim)) return BEAGLE_ERR_UNSUPPORTED;
+    // ... and the projection kernels every operand as a whole: activations [rows, D], projected rows
+    // [rows, H*d], weights [D, H*d].  There is no slower kernel behind these limits.
+    const int64_t rows = c->cu_seqlens_q ? (int64_t)(c->total_q > c->total_kv ? c->total_q : c->total_kv)
+                                         : d.B * (d.S > d.L ? d.S : d.L);
+    const int64_t width = d.D > d.HD ? d.D : d.HD;
+    if (rows * width * 2 >= lim || d.D * d.HD * 2 >= lim) return BEAGLE_ERR_UNSUPPORTED;
   } else {
     if (d.d > 128 || d.d % 4 || d.D % 4) return BEAGLE_ERR_UNSUPPORTED;
   }
@@ -436,6 +443,15 @@ const char* beagle_xattn_status_string(beagle_status s) {
     case BEAGLE_ERR_HIP: return "HIP runtime error";
   }
   return "unknown status";
+}
+
+beagle_status beagle_xattn_probe_read(const void* buf, size_t bytes, int32_t workgroups, void* sink, void* hip_stream) {
+  if (!buf || !sink) return BEAGLE_ERR_NULL;
+  if (!aligned16(buf) || (((uintptr_t)sink) & 3u)) return BEAGLE_ERR_ALIGN;
+  if (bytes < 16 || workgroups < 1 || workgroups > 65535) return BEAGLE_ERR_SHAPE;
+  (void)hipGetLastError();
+  launch_read_probe(buf, (int64_t)bytes, workgroups, (uint32_t*)sink, (hipStream_t)hip_stream);
+  return hip_status();
 }
 
 const char* beagle_xattn_version(void) { return "1.0"; }

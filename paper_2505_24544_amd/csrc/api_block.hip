@@ -40,6 +40,8 @@ beagle_status check_block(const beagle_xattn_desc* desc, const beagle_block_para
   if (desc->flags & BEAGLE_FLAG_WGRAD_F32) return BEAGLE_ERR_UNSUPPORTED;
   if ((p->g_q || p->g_kv || p->g_mlp) && d->D > RMS_MAX_D) return BEAGLE_ERR_UNSUPPORTED;
   if (d->B * d->S * (int64_t)p->ffn > (int64_t)INT32_MAX * 64) return BEAGLE_ERR_UNSUPPORTED;
+  // bf16: the feed-forward operands [rows, F], [D, F] through 32-bit buffer descriptors, like the attention's
+  if (d->bf16 && ((d->Tq > d->D ? d->Tq : d->D) * (int64_t)p->ffn * 2 >= ((int64_t)1 << 31))) return BEAGLE_ERR_UNSUPPORTED;
   return BEAGLE_OK;
 }
 

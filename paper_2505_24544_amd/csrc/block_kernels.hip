@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void silu_mul_bwd_kernel(const T* dm, const T*
 }
 
 // IEEE half -> storage type, eight elements per thread and step (the offline-generated target states arrive in
-// half precision: section 6, training details)
+// half precision: section 5.1, experimental set-up)
 template <typename T>
 __global__ __launch_bounds__(256) void cvt_f16_kernel(const _Float16* __restrict__ in, T* __restrict__ out, int64_t n) {
   typedef _Float16 h8 __attribute__((ext_vector_type(8)));

@@ -55,8 +55,9 @@ struct GemmGroup {
   GemmArgs p[4];
 };
 void launch_gemm_f32(const GemmGroup& g, hipStream_t s, const char* name);
-void launch_gemm_bf16_scalar(const GemmGroup& g, hipStream_t s, const char* name);
 void launch_gemm_bf16(const GemmGroup& g, hipStream_t s, const char* name);
+// whether the MFMA kernel covers the group (storage orders, k granularity, 32-bit operand extents)
+bool gemm_bf16_supported(const GemmGroup& g);
 
 // ---- draft block around the attention (section 4.1, Eq. 1): streaming kernels ----
 constexpr int RMS_BWD_MAX_PARTS = 1024;      // workgroups (= column-partial rows) of the RMSNorm backward
@@ -159,8 +160,6 @@ void launch_sim_band_fwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_sim_band_bwd_bf16(const SimArgs& s, hipStream_t st);
 void launch_attn_fwd_f32(const AttnArgs& a, hipStream_t s);
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s);
-void launch_attn_fwd_bf16_scalar(const AttnArgs& a, hipStream_t s);
-void launch_attn_bwd_bf16_scalar(const AttnArgs& a, hipStream_t s);
 void launch_attn_fwd_bf16(const AttnArgs& a, hipStream_t s);
 void launch_attn_bwd_bf16(const AttnArgs& a, void* ws, hipStream_t s);
 size_t attn_bwd_bf16_ws_bytes(const AttnArgs& a);
@@ -180,6 +179,7 @@ struct DecodeArgs {
 };
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
+void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s);
 size_t kv_append_bf16_ws_bytes(int32_t n, int32_t N, int32_t K);
 bool kv_append_bf16_fits(int32_t n, int32_t N, int32_t K);
 // feed-forward layer for a handful of rows: h = (silu(z W_gate) * (z W_up)) W_down + y_res

@@ -21,7 +21,7 @@
 //   (D) skinny_gemm   y_part[ks] = o * Wo[k-slice ks]
 //   (E) sum_slices    y = sum_ks y_part[ks]  (bf16)
 //
-// With drafted states concatenated to the cache (section 6, "concate" with the
+// With drafted states concatenated to the cache (appendix "Ablation Study", "concate" with the
 // drafting tree) the rows at and past n_true are visible to a query only where
 // its row of the tree bitmask has a bit; (B) applies it to the 32-key blocks
 // that reach past n_true.  Appending up to 64 states to the cache runs (A) on
@@ -820,6 +820,27 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
   }
   o[((int64_t)m * H + h) * HD + c] = f32_to_bf16(lt > 0.f ? acc / lt : 0.f);
   if (c == 0) lse[(int64_t)h * lse_stride + m] = lt > 0.f ? mm * scale + logf(lt) : -INFINITY;
+}
+
+// Plain streaming read of `bytes` bytes (16 bytes per lane, eight loads in flight per lane): the reference point for
+// what the memory system delivers to a kernel that does nothing but read.
+__global__ __launch_bounds__(256) void read_probe_kernel(const uint4* __restrict__ p, int64_t n16, uint32_t* __restrict__ sink) {
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  uint32_t acc = 0;
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < n16; i0 += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int64_t i = i0 + u * stride;
+      v[u] = i < n16 ? p[i] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9e3779b9u) *sink = acc;          // keeps the loads alive; practically never taken
+}
+void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s) {
+  hipLaunchKernelGGL(read_probe_kernel, dim3(wgs), dim3(256), 0, s, (const uint4*)buf, bytes / 16, sink);
 }
 
 // ---- host side ----------------------------------------------------------------

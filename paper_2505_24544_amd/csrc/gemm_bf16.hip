@@ -37,6 +37,8 @@
 //     that XCD's L2.
 //   * Several independent GEMMs can share one launch (Q, K, V projections;
 //     the three weight gradients) so that small ones do not leave CUs idle.
+#include <stdio.h>
+#include <stdlib.h>
 #include "common.h"
 
 namespace beagle {
@@ -384,6 +386,27 @@ static void launch_variant(const GemmGroup& grp, int total, hipStream_t s) {
   hipLaunchKernelGGL((gemm_bf16_kernel<TM, TN, XK, WK, F32OUT, RES>), dim3(total), dim3(256), 0, s, grp, total);
 }
 
+// What the MFMA kernel needs of a group (checked by the entry points before anything is enqueued, see
+// gemm_bf16_supported): k-contiguous operands with K a multiple of the k slice, every operand (and the residual)
+// addressable through a 32-bit buffer descriptor, and one of the storage-order combinations instantiated below.
+static bool group_fits(const GemmGroup& grp) {
+  if (grp.count < 1 || grp.count > 4) return false;
+  const bool xk = grp.p[0].a_kmajor, wk = grp.p[0].b_kmajor, f32 = grp.p[0].c_is_f32;
+  const int64_t lim = (int64_t)1 << 31;
+  bool res = false;
+  for (int i = 0; i < grp.count; ++i) {
+    const GemmArgs& q = grp.p[i];
+    if ((bool)q.a_kmajor != xk || (bool)q.b_kmajor != wk || (bool)q.c_is_f32 != f32) return false;
+    if (q.R) { res = true; if ((int64_t)q.M * q.ldr * 2 >= lim) return false; }
+    if ((xk || wk) && (q.K % BK || (q.A2 && q.K2 % BK))) return false;
+    if ((int64_t)(xk ? q.M : q.K) * q.lda * 2 >= lim || (int64_t)(wk ? q.N : q.K) * q.ldb * 2 >= lim) return false;
+    if (q.A2 && ((int64_t)(xk ? q.M : q.K2) * q.lda2 * 2 >= lim || (int64_t)(wk ? q.N : q.K2) * q.ldb2 * 2 >= lim)) return false;
+  }
+  if (res) return xk && !f32;
+  return (xk && !f32) || (!xk && !wk);
+}
+bool gemm_bf16_supported(const GemmGroup& grp) { return group_fits(grp); }
+
 template <int TM, int TN>
 static void launch_tiles(const GemmGroup& grp, hipStream_t s) {
   constexpr int BM = 64 * TM, BN = 64 * TN;
@@ -392,25 +415,20 @@ static void launch_tiles(const GemmGroup& grp, hipStream_t s) {
     total += ((grp.p[i].M + BM - 1) / BM) * ((grp.p[i].N + BN - 1) / BN);
   if (total == 0) return;
   const bool xk = grp.p[0].a_kmajor, wk = grp.p[0].b_kmajor, f32 = grp.p[0].c_is_f32;
-  bool fits = true;      // k-contiguous operands: K a multiple of BK; byte offsets must fit 31 bits
   bool res = false;
-  for (int i = 0; i < grp.count; ++i) {
-    const GemmArgs& q = grp.p[i];
-    const int64_t lim = (int64_t)1 << 31;
-    if (q.R) { res = true; if ((int64_t)q.M * q.ldr * 2 >= lim) fits = false; }
-    if ((xk || wk) && (q.K % BK || (q.A2 && q.K2 % BK))) fits = false;
-    if ((int64_t)(xk ? q.M : q.K) * q.lda * 2 >= lim || (int64_t)(wk ? q.N : q.K) * q.ldb * 2 >= lim) fits = false;
-    if (q.A2 && ((int64_t)(xk ? q.M : q.K2) * q.lda2 * 2 >= lim || (int64_t)(wk ? q.N : q.K2) * q.ldb2 * 2 >= lim)) fits = false;
+  for (int i = 0; i < grp.count; ++i) if (grp.p[i].R) res = true;
+  if (!group_fits(grp)) {
+    // The entry points refuse such problems with BEAGLE_ERR_UNSUPPORTED before they enqueue anything; there is no
+    // slower kernel to fall back to.  Getting here is a bug in the library's own host code.
+    fprintf(stderr, "beagle_xattn: internal error: GEMM group outside the MFMA kernel's domain reached the launcher\n");
+    abort();
   }
-  if (!fits) { launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar"); return; }
-  if (res && xk && !wk && !f32) launch_variant<TM, TN, true, false, false, true>(grp, total, s);
-  else if (res && xk && wk && !f32) launch_variant<TM, TN, true, true, false, true>(grp, total, s);
-  else if (res) launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar");   // no hot-path call lands here
-  else if (xk && !wk && !f32) launch_variant<TM, TN, true, false, false>(grp, total, s);
-  else if (xk && wk && !f32) launch_variant<TM, TN, true, true, false>(grp, total, s);
-  else if (!xk && !wk && !f32) launch_variant<TM, TN, false, false, false>(grp, total, s);
-  else if (!xk && !wk && f32) launch_variant<TM, TN, false, false, true>(grp, total, s);
-  else launch_gemm_bf16_scalar(grp, s, "gemm_bf16_scalar");   // no hot-path call lands here
+  if (res && !wk) launch_variant<TM, TN, true, false, false, true>(grp, total, s);
+  else if (res) launch_variant<TM, TN, true, true, false, true>(grp, total, s);
+  else if (xk && !wk) launch_variant<TM, TN, true, false, false>(grp, total, s);
+  else if (xk) launch_variant<TM, TN, true, true, false>(grp, total, s);
+  else if (!f32) launch_variant<TM, TN, false, false, false>(grp, total, s);
+  else launch_variant<TM, TN, false, false, true>(grp, total, s);
 }
 
 // Every GEMM of a group must share storage orders and output type; the hot

@@ -12,6 +12,8 @@
 
 namespace beagle {
 
+// Value ranges (enforced by the descriptor check): positions and lengths below 2^30, 1 <= k <= 2^30,
+// 0 <= eps < k.  Inside them no expression below leaves the int32 range.
 struct MaskParams {
   int32_t k;        // window size >= 1
   int32_t eps;      // window offset in [0, k)
@@ -38,11 +40,12 @@ BEAGLE_HD int32_t window_start_raw(int32_t p, int32_t k, int32_t eps) {
 
 // Late-stage simulation, step t (section 4.2, second half): the predicted keys
 // that query p may attend are [lo, hi): the first t positions of p's own
-// window that lie before p.  hi <= lo: none.
+// window that lie before p.  hi <= lo: none.  Any t >= k shows the whole window
+// (t is clamped first: w0 + t must not overflow for a caller's large step count).
 BEAGLE_HD void sim_band(int32_t p, int32_t k, int32_t eps, int32_t t, int32_t seq_kv, int32_t& lo, int32_t& hi) {
   int32_t w0 = window_start_raw(p, k, eps);
   lo = w0 > 0 ? w0 : 0;
-  hi = w0 + t;
+  hi = w0 + (t < k ? t : k);
   if (hi > p) hi = p;
   if (hi > seq_kv) hi = seq_kv;
 }

@@ -1,8 +1,9 @@
 // Scalar-FMA path: reference-grade kernels, templated on the storage type
 // (float, or bfloat16 bits that are widened on load and rounded on store).
 // Plain FMA arithmetic, float accumulation, accurate expf/logf.  This is the
-// path of io_dtype == BEAGLE_F32 (parity at 1e-5, not speed) and of the few
-// bf16 steps that have no MFMA kernel; the bf16 MFMA kernels are the fast path.
+// path of io_dtype == BEAGLE_F32 (parity at 1e-5, not speed); bf16 problems run
+// on the MFMA kernels only -- what those do not cover is refused by the entry
+// points, never routed here.
 #include "common.h"
 
 namespace beagle {
@@ -104,7 +105,6 @@ static void gemm_scalar_launch(const GemmGroup& grp, hipStream_t s, const char* 
 }
 
 void launch_gemm_f32(const GemmGroup& g, hipStream_t s, const char* name) { gemm_scalar_launch<float>(g, s, name); }
-void launch_gemm_bf16_scalar(const GemmGroup& g, hipStream_t s, const char* name) { gemm_scalar_launch<bf16_t>(g, s, name); }
 
 // --------------------------------------------------------------------------
 // Attention, one wavefront per (b, h, p) query row (forward, dQ) or per
@@ -503,10 +503,6 @@ void launch_sim_save(const void* h, void* xpred, int B, int L, int64_t row_bytes
 
 void launch_attn_bwd_f32(const AttnArgs& a, hipStream_t s) {
   attn_bwd_scalar<float>(a, s, "attn_bwd_dq_f32", "attn_bwd_dkv_f32");
-}
-void launch_attn_fwd_bf16_scalar(const AttnArgs& a, hipStream_t s) { attn_fwd_scalar<bf16_t>(a, s, "attn_fwd_bf16_scalar"); }
-void launch_attn_bwd_bf16_scalar(const AttnArgs& a, hipStream_t s) {
-  attn_bwd_scalar<bf16_t>(a, s, "attn_bwd_dq_bf16_scalar", "attn_bwd_dkv_bf16_scalar");
 }
 
 }  // namespace beagle

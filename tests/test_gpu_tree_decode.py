@@ -1,6 +1,6 @@
 """GPU parity of the decode extensions -- drafted states concatenated to the
 cache under a draft-tree mask, and appending states to the cache -- against
-the float64 oracle (section 4.1 KV-cache paragraph; section 6 "concate" with
+the float64 oracle (section 4.1 KV-cache paragraph; appendix "Ablation Study", "concate" with
 the dynamic drafting tree).  Inputs are seeded and synthetic; trees have the
 shape the paper states for its evaluation (depth 1 + 6, top-k 10, at most 60
 drafted nodes) or are random."""

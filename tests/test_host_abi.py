@@ -94,10 +94,44 @@ def test_invalid_descriptors_are_rejected_on_the_host():
         assert ei.value.status == 3
     with pytest.raises(E):
         bx.beagle_xattn_tile_map(_desc(), 0, 4)
+    # window sizes and lengths beyond 2^30 would overflow the int32 index code
+    for kw in (dict(k=2 ** 30 + 1), dict(S=2 ** 30 + 1, L=4), dict(S=4, L=2 ** 30 + 1)):
+        assert bx.beagle_xattn_workspace_bytes(_desc(**kw), bx.BEAGLE_WS_FWD) == 0
+    assert bx.beagle_xattn_workspace_bytes(_desc(k=2 ** 30), bx.BEAGLE_WS_FWD) > 0
     # bf16: one batch entry's K/V slab must stay below 2 GiB (32-bit buffer descriptors)
     big = dict(io_dtype=bx.BEAGLE_BF16, head_dim=128, hidden=4096, n_q_heads=32, n_kv_heads=32)
     assert bx.beagle_xattn_workspace_bytes(_desc(S=262143, **big), bx.BEAGLE_WS_FWD) > 0
     assert bx.beagle_xattn_workspace_bytes(_desc(S=262144, **big), bx.BEAGLE_WS_FWD) == 0
+
+
+def test_projection_operands_of_2_gib_are_refused_not_rerouted():
+    """bf16: every operand of the projection kernels is addressed through a 32-bit buffer descriptor; a batch whose
+    activations reach 2 GiB (B*S*D*2 bytes) is refused with BEAGLE_ERR_UNSUPPORTED before anything is enqueued --
+    there is no slower kernel it could be sent to."""
+    a, ws = 4096, 1 << 62
+    big = dict(io_dtype=bx.BEAGLE_BF16, head_dim=128, hidden=4096, n_q_heads=32, n_kv_heads=32, k=4)
+    ok = _desc(S=2048, batch=127, **big)            # 127 * 2048 * 4096 * 2 < 2^31
+    no = _desc(S=2048, batch=128, **big)            # exactly 2^31
+    assert bx.beagle_xattn_workspace_bytes(ok, bx.BEAGLE_WS_BWD) > 0
+    assert bx.beagle_xattn_workspace_bytes(no, bx.BEAGLE_WS_BWD) == 0
+    assert bx.beagle_xattn_fwd(no, *([a] * 12), a, stream=0, workspace_bytes=ws, check=False) == 3
+    assert bx.beagle_xattn_bwd(no, *([a] * 18), a, stream=0, workspace_bytes=ws, check=False) == 3
+    # S != L: the longer side decides; GQA: the query side's H*d decides
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=16, L=262144, **big), bx.BEAGLE_WS_FWD) == 0
+    gqa = dict(big, n_kv_heads=8)
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=2048, batch=128, **gqa), bx.BEAGLE_WS_FWD) == 0
+    # packed batches: the packed row count decides, not batch * longest
+    pk = dict(big, cu_seqlens_q=a, cu_seqlens_kv=a)
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=2048, batch=200, total_q=200000, total_kv=200000, **pk), bx.BEAGLE_WS_FWD) > 0
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=2048, batch=200, total_q=262144, total_kv=200000, **pk), bx.BEAGLE_WS_FWD) == 0
+    # a weight matrix of 2 GiB
+    wide = dict(io_dtype=bx.BEAGLE_BF16, head_dim=128, hidden=32768, n_q_heads=256, n_kv_heads=256, k=4)
+    assert bx.beagle_xattn_workspace_bytes(_desc(S=16, **wide), bx.BEAGLE_WS_FWD) == 0
+    # the feed-forward operands of the block entry points
+    assert bx.beagle_xattn_block_workspace_bytes(ok, 4096, bx.BEAGLE_WS_BLOCK_BWD) > 0
+    prm = bx.make_block_params(8192, 1e-5, **{n: a for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")})
+    sv = bx.make_block_saved(**{n: a for n in ("q", "k", "v", "o", "lse", "y", "u", "w", "m")})
+    assert bx.beagle_xattn_block_fwd(ok, prm, a, a, a, sv, a, stream=0, workspace_bytes=ws, check=False) == 3
 
 
 def test_tree_and_append_entry_points_validate_before_launching():
