@@ -201,6 +201,30 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * beagle_xattn_draft_step for callers that cannot allocate or hand over device
+ * memory of their own for scratch: code under HIP-graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * (bitwise) and kernels as beagle_xattn_draft_step, without the workspace: the
+ * partial sums live in a buffer of BEAGLE_STATIC_SCRATCH_BYTES that is part of
+ * the library's device image (every GPU the library runs on holds its own copy
+ * until the process ends).  The call allocates and frees nothing.
+ *   - The first call on a device looks up that device's copy of the buffer
+ *     (once; make that call outside graph capture).
+ *   - A problem whose beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT)
+ *     exceeds BEAGLE_STATIC_SCRATCH_BYTES returns BEAGLE_ERR_WORKSPACE and
+ *     enqueues nothing (the decode configuration of 64 queries, 4096 cache
+ *     rows, D = 4096 needs 26 MB).
+ *   - All calls on one GPU share the one buffer, whose content is whatever the
+ *     last call left (no kernel of the step needs it cleared): calls that may
+ *     overlap on one GPU -- different streams, or graphs replayed concurrently
+ *     -- race; keep them on one stream.
+ */
+#define BEAGLE_STATIC_SCRATCH_BYTES (32u << 20)
+beagle_status beagle_xattn_draft_step_static(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache,
+    const void* wq, const void* wo, void* y, float* lse, void* hip_stream);
+
+/*
  * Late-stage training: one simulated inference step (section 4.2, second
  * half, and the caption of the mask figure).  Keys come from two sources: the
  * true target states xkv under the early-stage mask of beagle_xattn_fwd, and

@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: 
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
-    "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
+    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
     "beagle_xattn_block_draft_step", "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
@@ -131,6 +131,8 @@ def lib() -> C.CDLL:
     L.beagle_xattn_bwd.argtypes = [dp] + [vp] * 18 + [vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step.restype = C.c_int
     L.beagle_xattn_draft_step.argtypes = [dp] + [vp] * 7 + [vp, C.c_size_t, vp]
+    L.beagle_xattn_draft_step_static.restype = C.c_int
+    L.beagle_xattn_draft_step_static.argtypes = [dp] + [vp] * 7 + [vp]
     L.beagle_xattn_fwd_sim.restype = C.c_int
     L.beagle_xattn_fwd_sim.argtypes = [dp] + [vp] * 7 + [C.c_int32] + [vp] * 8 + [vp, C.c_size_t, vp]
     L.beagle_xattn_bwd_sim.restype = C.c_int
@@ -339,6 +341,15 @@ def beagle_xattn_draft_step(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, wor
         C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo, y, lse)),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_draft_step", check)
+
+
+BEAGLE_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def beagle_xattn_draft_step_static(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_draft_step_static(
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo, y, lse)), _stream(stream))
+    return _check(st, "beagle_xattn_draft_step_static", check)
 
 
 def beagle_xattn_mask_row_limit(desc) -> np.ndarray:

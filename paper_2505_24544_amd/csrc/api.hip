@@ -5,6 +5,7 @@
 #include "api_internal.h"
 
 #include <math.h>
+#include <mutex>
 #include <string.h>
 
 using namespace beagle;
@@ -708,6 +709,41 @@ beagle_status beagle_xattn_draft_step(const beagle_xattn_desc* desc,
   const int32_t L = desc ? desc->seq_kv : 0;
   return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo, L, nullptr, 0, y, lse, workspace, workspace_bytes,
                          hip_stream);
+}
+
+// The draft step without a caller-provided workspace: the scratch buffer is part of the device image.
+// In host code `scratch` is only a handle for hipGetSymbolAddress; kernels get the address it resolves to.
+namespace {
+static __device__ __align__(256) unsigned char scratch[BEAGLE_STATIC_SCRATCH_BYTES];
+constexpr int SCRATCH_MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_addr[SCRATCH_MAX_DEVICES];      // per device: every GPU holds its own copy at its own address
+beagle_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_DEVICES) return BEAGLE_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return BEAGLE_ERR_HIP; }
+    g_scratch_addr[dev] = p;
+  }
+  *out = g_scratch_addr[dev];
+  return BEAGLE_OK;
+}
+}  // namespace
+
+beagle_status beagle_xattn_draft_step_static(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
+    void* y, float* lse, void* hip_stream) {
+  const size_t need = beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT);   // 0: the descriptor check below says why
+  if (need > BEAGLE_STATIC_SCRATCH_BYTES) return BEAGLE_ERR_WORKSPACE;
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != BEAGLE_OK) return st;
+  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo, desc->seq_kv, nullptr, 0, y, lse, ws,
+                         BEAGLE_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
