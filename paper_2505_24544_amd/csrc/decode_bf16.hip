@@ -366,17 +366,27 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* pos, int
   tab[i] = make_float2((float)cs, (float)sn);
 }
 
-// One workgroup per (head, key range, block of 32 NQB queries): grid (H, R, ceil(M / (32 NQB))).  NQB = 1: the
-// four waves split each 128-key step, 32 keys each.  More than 32 queries (NQB = 2): waves 0, 1 take the first 32
-// queries and waves 2, 3 the next 32, each wave 64 keys of a step as two blocks of 32 -- the K / V tiles in LDS
-// serve both query blocks, so the cache is read once instead of once per block.
+// One workgroup per (head, key range, block of 32 NQB queries): grid (H, R, ceil(M / (32 NQB))).
+// NQB = 1 (up to 32 queries): the four waves split each 128-key step by rows, 32 keys each.  A wave requests, reads
+// and refills only its own 32 rows of the two stages, so the step loop has no barrier; a stage half (the wave's K
+// rows, then its V rows) is refilled for the step after next as soon as its fragments sit in registers, i.e. BEFORE
+// the step's arithmetic: with both stages landed and nothing requested, HBM would idle for as long as a step
+// computes (measured: 3 us of the kernel's 16).
+// NQB = 2 (33 .. 64 queries): waves 0, 1 take the first 32 queries and waves 2, 3 the next 32, each wave 64 keys of
+// a step as two blocks of 32 -- the K / V tiles in LDS serve both query blocks, so the cache is read once instead
+// of once per block; the stages are shared between waves there, so the loop keeps its (fence-free) barriers.
+// (Both blocks in every wave, which would free that loop of barriers too, needs 256 registers for the two output
+// accumulators and q fragments alone and did not survive register allocation.)
 template <int NQB>
 __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   using namespace dec;
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];    // K step tile, V step tile: 64 KB
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  __shared__ __attribute__((aligned(16))) float qbuf[32 * HD];          // q of one block, float
-  __shared__ float s_ml[4][2][32];
+  // q as bf16 planes of 32 queries: plane 0 = hi part of the block being set up, plane 1 + b = lo part of block b
+  __shared__ __attribute__((aligned(1024))) bf16_t qbuf[(1 + NQB) * 32 * HD];
+  __shared__ float s_ml[4][2][32];                                      // per wave: running max, sum of its queries
+  __shared__ float s_sc[4][32];                                         // merge weight of a wave's partial
+  __shared__ float s_mm[NQB][2][32];                                    // merged max, sum per block
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int h = blockIdx.x, r = blockIdx.y;
   const int m0 = 32 * NQB * blockIdx.z;                      // first query of the workgroup
@@ -406,6 +416,17 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       }
     }
   };
+  // this wave's own 32 rows of a step's K (t = 0) or V (t = 1) tile: 8 requests, no branch (rows past the range read as zero)
+  auto fetch_own_half = [&](bf16_t* st, int step, int t) {
+    const int row0 = j_begin + step * KSTEP;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int q = 512 * wave + 64 * i + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
+      const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(t ? vrs : krs, (lds_void_ptr)(st + t * TILE + (8 * wave + i) * 512), 16, off, 0, 0, 0);
+    }
+  };
+  auto fetch_own = [&](bf16_t* st, int step) { fetch_own_half(st, step, 0); fetch_own_half(st, step, 1); };
   typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) float* lds_float_ptr;
@@ -413,173 +434,215 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
   const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
-  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums a block once into LDS (float4
-  // slot c4 of row m sits at (c4 + 2 m) % 32 to spread the fragment reads over the banks), then every lane
-  // picks up its B-operand fragments, split into bf16 hi + lo.
-  //
-  // The first two K/V steps are requested while the q slices are still on their way: the load counter of
-  // a wave retires in order, so the roles are split by wave.  Up to 8 queries are summed by wave 0 alone, up
-  // to 16 by two waves (more by all four): a summing wave loads, adds, stores to LDS and only then requests its share of K/V
-  // rows; the other waves request theirs at once.  The fragments are read after the barrier that also
-  // waits for the first step, with explicit ds_read instructions: the compiler cannot tell these reads
-  // from the K/V requests in flight and would wait for all of them.
-
-  // sum of the slices of block qb (queries m0 + 32 qb ..) held by this thread: four float4 (query idx >> 5,
-  // slot idx & 31 with idx = tid + 64 qwaves i), rotated if a rotary table is given
-  auto sum_block = [&](int qb, int mrows, int qwaves, float4 (&acc)[4]) {
-    // slices and rows that do not exist are read past the end of the buffer, i.e. as zeros: no branches
-    const int64_t slice = (int64_t)a.M * HDt;                           // floats per k-slice
-    const __amdgpu_buffer_rsrc_t qrs =
-        __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
-    const int oob = 0x7fffff00;
+  // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums a block once and leaves it in LDS
+  // as a bf16 hi + lo pair (hi = bf16(q), lo = bf16(q - hi): scores, and the LSE, see q at ~16 bits), rows of 128
+  // channels = 16 chunks of 16 bytes, chunk c of row m at chunk position c ^ (m % 16) so that the per-query
+  // fragment reads spread over the banks; then every lane picks up its B-operand fragments.  A thread of a summing
+  // wave holds four float4 of the block: (query idx >> 5, channels 4 (idx & 31) ..) with idx = tid + 64 qwaves i.
+  // Loads of slices, rows and waves that do not take part are asked for past the end of the buffer, i.e. arrive as
+  // zeros: no branches around loads, so that the compiler can count the requests between a load and its use (a
+  // wave's loads return in order).
+  const int64_t slice = (int64_t)a.M * HDt;                             // floats per k-slice
+  const __amdgpu_buffer_rsrc_t qrs =
+      __builtin_amdgcn_make_buffer_rsrc((void*)a.qpart, 0, (int)(a.KSq * slice * 4), 0x00020000);
+  const int oob = 0x7fffff00;
+  auto q_issue = [&](int qb, int mrows, int qwaves, int k0, u32x4_t (&t)[4][8]) {
     const int mb = m0 + 32 * qb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc[i] = zero4;
-    // rotary embedding: this thread's four channels of query m pair with the four that lane ^ 16 holds
-    // (float4 slot c4 ^ 16 of the same query); their (cos, sin) are requested first, ahead of the slices
-    float4 cs[4][2];
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int off = (int)((((int64_t)(k0 + k) * a.M + mb + m) * HDt + h * HD + 4 * c4) * 4);
+        t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (wave < qwaves && m < mrows && k0 + k < a.KSq) ? off : oob, 0, 0);
+      }
+    }
+  };
+  auto q_add = [&](const u32x4_t (&t)[4][8], float4 (&acc)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
+        acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
+      }
+  };
+  // slices past the first eight (model widths above 4096), and the rotary embedding: this thread's four channels of
+  // query m pair with the four that lane ^ 16 holds (float4 slot c4 ^ 16 of the same query)
+  auto q_finish = [&](int qb, int mrows, int qwaves, float4 (&acc)[4]) {
+    for (int k0 = 8; k0 < a.KSq; k0 += 8) {
+      u32x4_t t[4][8];
+      q_issue(qb, mrows, qwaves, k0, t);
+      q_add(t, acc);
+    }
     if (a.rope_tab) {
+      const int mb = m0 + 32 * qb;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int idx = tid + 64 * qwaves * i, m = min(idx >> 5, mrows - 1), c4 = idx & 15;
         const float4* tp = (const float4*)(a.rope_tab + (int64_t)(mb + m) * 64 + 4 * c4);
-        cs[i][0] = tp[0]; cs[i][1] = tp[1];
-      }
-    }
-    for (int k0 = 0; k0 < a.KSq; k0 += 8) {                             // one pass for up to 8 slices
-      u32x4_t t[4][8];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const int off = (int)((((int64_t)(k0 + k) * a.M + mb + m) * HDt + h * HD + 4 * c4) * 4);
-          t[i][k] = __builtin_amdgcn_raw_buffer_load_b128(qrs, (m < mrows && k0 + k < a.KSq) ? off : oob, 0, 0);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          acc[i].x += __uint_as_float(t[i][k][0]); acc[i].y += __uint_as_float(t[i][k][1]);
-          acc[i].z += __uint_as_float(t[i][k][2]); acc[i].w += __uint_as_float(t[i][k][3]);
-        }
-    }
-    if (a.rope_tab) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool upper = (tid & 16) != 0;               // channels 64 .. 127: x2 of the pair
+        const float4 cs0 = tp[0], cs1 = tp[1];                 // (cos, sin) of pairs 4 c4 .. 4 c4 + 3
+        const bool upper = (tid & 16) != 0;                    // channels 64 .. 127: x2 of the pair
         const float4 own = acc[i];
         float4 oth;
         oth.x = __shfl_xor(own.x, 16, 64); oth.y = __shfl_xor(own.y, 16, 64);
         oth.z = __shfl_xor(own.z, 16, 64); oth.w = __shfl_xor(own.w, 16, 64);
-        // x1' = x1 cos - x2 sin ; x2' = x2 cos + x1 sin  (cs holds (cos, sin) of pairs 4 c4 .. 4 c4 + 3)
+        // x1' = x1 cos - x2 sin ; x2' = x2 cos + x1 sin
         const float sg = upper ? 1.f : -1.f;
-        acc[i].x = own.x * cs[i][0].x + sg * oth.x * cs[i][0].y;
-        acc[i].y = own.y * cs[i][0].z + sg * oth.y * cs[i][0].w;
-        acc[i].z = own.z * cs[i][1].x + sg * oth.z * cs[i][1].y;
-        acc[i].w = own.w * cs[i][1].z + sg * oth.w * cs[i][1].w;
+        acc[i].x = own.x * cs0.x + sg * oth.x * cs0.y;
+        acc[i].y = own.y * cs0.z + sg * oth.y * cs0.w;
+        acc[i].z = own.z * cs1.x + sg * oth.z * cs1.y;
+        acc[i].w = own.w * cs1.z + sg * oth.w * cs1.w;
       }
     }
   };
-  // B-operand fragments of the block in qbuf, as bf16 hi + lo (explicit ds_read, see above)
-  auto read_frags = [&](bf16x8_t (&qh)[8], bf16x8_t (&qlo)[8]) {
-    f32x4_t t0[8], t1[8];
+  // hi / lo halves (8 bytes each) of four channels of row m
+  auto q_split = [&](const float4& v, uint2& hi, uint2& lo) {
+    const float f[4] = {v.x, v.y, v.z, v.w};
+    float rem[4];
+    uint32_t h16[4];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      asm volatile("ds_read_b128 %0, %1" : "=v"(t0[s]) : "v"((lds_float_ptr)(qbuf + ql * HD + 4 * ((4 * s + 2 * hf + 2 * ql) & 31))));
-      asm volatile("ds_read_b128 %0, %1" : "=v"(t1[s]) : "v"((lds_float_ptr)(qbuf + ql * HD + 4 * ((4 * s + 2 * hf + 1 + 2 * ql) & 31))));
+    for (int i = 0; i < 4; ++i) {
+      const __bf16 hb = (__bf16)f[i];
+      rem[i] = f[i] - (float)hb;
+      h16[i] = (uint32_t)__builtin_bit_cast(unsigned short, hb);
     }
+    hi = make_uint2(h16[0] | (h16[1] << 16), h16[2] | (h16[3] << 16));
+    lo = make_uint2(cvt_pk(rem[0], rem[1]), cvt_pk(rem[2], rem[3]));
+  };
+  auto q_slot = [&](int m, int c4) { return m * HD + ((((c4 >> 1) ^ (m & 15)) << 3) | ((c4 & 1) << 2)); };   // element offset
+  // a summing wave's four float4 into the block buffer, with explicit LDS instructions: HBM -> LDS requests are in
+  // flight, and for LDS accesses it can see the compiler would wait for all of them
+  auto q_store = [&](int qb, int qwaves, const float4 (&acc)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
+      uint2 hi, lo;
+      q_split(acc[i], hi, lo);
+      const u32x2_t vh = {hi.x, hi.y}, vl = {lo.x, lo.y};
+      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + q_slot(m, c4))), "v"(vh) : "memory");
+      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + (1 + qb) * 32 * HD + q_slot(m, c4))), "v"(vl) : "memory");
+    }
+  };
+  // B-operand fragments of a plane (explicit ds_read, see above): channels 16 s + 8 hf .. + 7 of query ql
+  typedef union { u32x4_t u; bf16x8_t v; } qfrag_t;
+  auto issue_frags = [&](int plane, qfrag_t (&f)[8]) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      asm volatile("ds_read_b128 %0, %1" : "=v"(f[s].u) : "v"((lds_bf16_ptr)(qbuf + plane * 32 * HD + ql * HD + (((2 * s + hf) ^ (ql & 15)) << 3))));
+  };
+  auto tie_frags = [&](qfrag_t (&f)[8]) {     // after the wait: nothing that uses the values may be scheduled above it
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(f[s].u));
+  };
+  auto read_frags = [&](int plane, bf16x8_t (&out)[8]) {
+    qfrag_t f[8];
+    issue_frags(plane, f);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    // tie the values to the wait: nothing that uses them may be scheduled above it
+    tie_frags(f);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(t0[s]), "+v"(t1[s]));
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const float v[8] = {t0[s][0], t0[s][1], t0[s][2], t0[s][3], t1[s][0], t1[s][1], t1[s][2], t1[s][3]};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const __bf16 hi = (__bf16)v[i];
-        qh[s][i] = hi;
-        qlo[s][i] = (__bf16)(v[i] - (float)hi);
-      }
-    }
+    for (int s = 0; s < 8; ++s) out[s] = f[s].v;
   };
 
   constexpr int WPB = 4 / NQB;                               // waves per query block
   const int qbw = wave / WPB;                                // this wave's query block
-  bf16x8_t qh[8], qlo[8];
-  if constexpr (NQB == 1) {
-    const int qwaves = mtot <= 8 ? 1 : (mtot <= 16 ? 2 : 4);     // a summing wave covers 8 queries
-    if (wave < qwaves) {
-      float4 acc[4];
-      sum_block(0, mtot, qwaves, acc);
+  bf16x8_t qh[8], qlo[8];                                    // its fragments of q
+  bool shared_first_steps = false;                           // steps 0 and 1 requested across waves (barrier before step 1)
+  if (NQB == 1 && mtot <= 8) {
+    // Up to 8 queries: wave 0 alone sums (one round trip for its 32 loads) while waves 1 .. 3 request the first
+    // two K/V steps at once, wave 0's share included: the 64 requests of a step go round waves 1, 2, 3 (22, 21 and
+    // 21 of them).  q is there long before the first step has landed.
+    shared_first_steps = true;
+    if (wave == 0) {
+      u32x4_t t[4][8];
+      float4 acc[4] = {zero4, zero4, zero4, zero4};
+      q_issue(0, mtot, 1, 0, t);
+      q_add(t, acc);
+      q_finish(0, mtot, 1, acc);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 64 * qwaves * i, m = idx >> 5, c4 = idx & 31;
-        *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
+        const int idx = tid + 64 * i, m = idx >> 5, c4 = idx & 31;
+        uint2 hi, lo;
+        q_split(acc[i], hi, lo);
+        *(uint2*)(qbuf + q_slot(m, c4)) = hi;
+        *(uint2*)(qbuf + 32 * HD + q_slot(m, c4)) = lo;
       }
     } else {
-      // the rows behind the summed ones hold no query (only reached with fewer than four summing waves): zeros
-      for (int idx = 256 * qwaves + (tid - 64 * qwaves); idx < 32 * 32; idx += 256 - 64 * qwaves)
-        *(float4*)(qbuf + 4 * idx) = zero4;
+      // rows 8 .. 31 hold no query: zeros in both planes (16 bytes per thread and step)
+      for (int idx = tid - 64; idx < 2 * 24 * 16; idx += 192) {
+        const int pl = idx / (24 * 16), rest = idx % (24 * 16);
+        *(uint4*)(qbuf + pl * 32 * HD + (8 + rest / 16) * HD + (rest % 16) * 8) = make_uint4(0, 0, 0, 0);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (qwaves == 1) {
-      // One summing wave: it would only get to its share of the K/V requests once q is there, and the other
-      // three would wait for that at the barrier.  They take its share instead: the 64 requests of a step go
-      // round waves 1, 2, 3 (22, 21 and 21 of them).
-      if (wave > 0) {
-        if (nsteps > 0) fetch3(stage0, 0);
-        if (nsteps > 1) fetch3(stage1, 1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      if (nsteps > 0 && wave > 0) {
-        // all but the wave's requests of the second step have landed
-        if (nsteps == 1) wait_vmem(); else if (wave == 1) wait_vmem_n<22>(); else wait_vmem_n<21>();
-      }
-    } else {
-      if (nsteps > 0) fetch(stage0, 0);
-      if (nsteps > 1) fetch(stage1, 1);
-      __builtin_amdgcn_sched_barrier(0);
-      if (nsteps > 0) {
-        // the first step's loads are the oldest 16 of (up to) 32 in flight
-        if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
-      }
+    if (wave > 0) {
+      if (nsteps > 0) fetch3(stage0, 0);
+      if (nsteps > 1) fetch3(stage1, 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (nsteps > 0 && wave > 0) {
+      // all but the wave's requests of the second step have landed
+      if (nsteps == 1) wait_vmem(); else if (wave == 1) wait_vmem_n<22>(); else wait_vmem_n<21>();
     }
     lds_barrier();                                             // first K/V step landed; q sum visible
-    read_frags(qh, qlo);
+    read_frags(0, qh);
+    read_frags(1, qlo);
+  } else if (NQB == 1) {
+    // 9 .. 32 queries: two or four waves sum.  Every wave requests its own rows of step 0, then its q slices, then
+    // its rows of step 1 -- the K/V stream starts with the kernel, and q (loads return in order) is complete when
+    // step 0 has landed, which the arithmetic has to wait for anyway.
+    const int qwaves = mtot <= 16 ? 2 : 4;
+    u32x4_t t[4][8];
+    float4 acc[4] = {zero4, zero4, zero4, zero4};
+    fetch_own(stage0, 0);
+    q_issue(0, mtot, qwaves, 0, t);
+    fetch_own(stage1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmem_n<16>();                                         // all but step 1's requests
+    q_add(t, acc);
+    if (wave < qwaves) {
+      q_finish(0, mtot, qwaves, acc);
+      q_store(0, qwaves, acc);
+    } else {
+      // rows 16 .. 31 hold no query (two summing waves cover 16): zeros in both planes, from the other two waves
+      for (int idx = tid - 64 * qwaves; idx < 2 * 16 * 16; idx += 256 - 64 * qwaves) {
+        const int pl = idx >> 8, rest = idx & 255;
+        const u32x4_t z = {0u, 0u, 0u, 0u};
+        asm volatile("ds_write_b128 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + pl * 32 * HD + (16 + (rest >> 4)) * HD + (rest & 15) * 8)), "v"(z) : "memory");
+      }
+    }
+    lds_barrier();                                             // q visible
+    read_frags(0, qh);
+    read_frags(1, qlo);
   } else {
-    // two blocks, all four waves sum: block 0 goes to LDS before the K/V requests; block 1 is summed while they
-    // are in flight and goes through the same buffer once waves 0, 1 have their block-0 fragments.  After the
-    // requests the buffer is touched with explicit ds instructions only (see above).
-    float4 acc[4];
-    sum_block(0, 32, 4, acc);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
-      *(float4*)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31)) = acc[i];
-    }
-    sum_block(1, mtot - 32, 4, acc);                           // rows past the last query: zeros
+    // 33 .. 64 queries, all four waves sum both blocks: step 0 (requests dealt across the waves), block 0's slices,
+    // step 1; block 1's slices are requested as soon as block 0's have been added up (one set of load registers)
+    // and arrive while block 0 goes through the buffer.  Every barrier below is passed by a wave only after its
+    // own share of step 0 (at the last one: of step 1) has landed, so the stages are complete behind them.
+    u32x4_t t[4][8];
+    float4 acc[4] = {zero4, zero4, zero4, zero4};
+    fetch(stage0, 0);
+    q_issue(0, 32, 4, 0, t);
+    fetch(stage1, 1);
     __builtin_amdgcn_sched_barrier(0);
-    if (nsteps > 0) fetch(stage0, 0);
-    if (nsteps > 1) fetch(stage1, 1);
+    wait_vmem_n<16>();                                         // step 0 and block 0's slices
+    q_add(t, acc);
     __builtin_amdgcn_sched_barrier(0);
+    q_issue(1, mtot - 32, 4, 0, t);                            // rows past the last query: zeros
+    __builtin_amdgcn_sched_barrier(0);
+    q_finish(0, 32, 4, acc);
+    q_store(0, 4, acc);
     lds_barrier();                                             // block 0 visible
-    if (qbw == 0) read_frags(qh, qlo);
-    lds_barrier();                                             // block 0 has been read
+    if (qbw == 0) { read_frags(0, qh); read_frags(1, qlo); }
+    lds_barrier();                                             // block 0's hi plane has been read
+    wait_vmem();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = tid + 256 * i, m = idx >> 5, c4 = idx & 31;
-      const f32x4_t v = {acc[i].x, acc[i].y, acc[i].z, acc[i].w};
-      asm volatile("ds_write_b128 %0, %1" : : "v"((lds_float_ptr)(qbuf + m * HD + 4 * ((c4 + 2 * m) & 31))), "v"(v) : "memory");
-    }
-    lds_barrier();                                             // block 1 visible
-    if (qbw == 1) read_frags(qh, qlo);
-    if (nsteps > 0) {
-      if (nsteps > 1) wait_vmem_n<16>(); else wait_vmem();
-    }
-    lds_barrier();                                             // first K/V step landed
+    for (int i = 0; i < 4; ++i) acc[i] = zero4;
+    q_add(t, acc);
+    q_finish(1, mtot - 32, 4, acc);
+    q_store(NQB - 1, 4, acc);
+    lds_barrier();                                             // block 1 visible; steps 0 and 1 landed
+    if (qbw == NQB - 1) { read_frags(0, qh); read_frags(NQB, qlo); }
   }
   const float c2 = a.scale * LOG2E;
   const FragOffs fo = make_frag_offs(lane);
@@ -591,8 +654,10 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
   float mrun = -INFINITY, lrun = 0.f;
 
-  // one 128-key step: this wave takes NQB blocks of 32 rows of the step tiles, one after the other
-  auto step_compute = [&](const bf16_t* cur, int step) {
+  // One 128-key step.  One block: this wave's 32 rows of the step tiles; `refill` requests the same rows of step + 2
+  // into the stage as soon as their fragments have been read.  Two blocks: 64 rows (two blocks of 32, one after the
+  // other) against the wave's query block; the stages are shared and refilled by the step loop.
+  auto step_compute = [&](bf16_t* cur, int step, bool refill) {
     const bf16_t* ks = cur;
     const bf16_t* vs = cur + TILE;
 #pragma unroll
@@ -601,8 +666,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       const int jw = j_begin + step * KSTEP + 32 * kb;         // its first key
       if (jw < j_end) {
         // Explicit ds_read instructions (same addresses as row_frag / tr_frag): for LDS reads it can see, the compiler
-        // waits until no HBM -> LDS request is in flight at all (the requests sit in branches, so it cannot count
-        // the ones behind this stage's), and the refill of the other stage would never overlap this arithmetic.
+        // waits until no HBM -> LDS request is in flight at all, and the refills would never overlap the arithmetic.
         union { u32x4_t u; bf16x8_t v; } kf[8];
         union { struct { u32x2_t x, y; } s; bf16x8_t v; } vf[2][4];
 #pragma unroll
@@ -620,6 +684,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
+        if constexpr (NQB == 1) {
+          if (refill) fetch_own_half(cur, step + 2, 0);        // the wave's K rows are in registers: refill them
+        }
         // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
         f32x16_t st, st2;
 #pragma unroll
@@ -679,11 +746,14 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         }
         rs = half_pair_sum(rs);
         lrun += rs;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the V fragments
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the V fragments
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb) asm volatile("" : "+v"(vf[t][cb].s.x), "+v"(vf[t][cb].s.y));
+        if constexpr (NQB == 1) {
+          if (refill) fetch_own_half(cur, step + 2, 1);        // ... and the wave's V rows
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
@@ -693,96 +763,94 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
           for (int cb = 0; cb < 4; ++cb)
             o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb].v, pf.v, o[cb], 0, 0, 0);
         }
+      } else if (NQB == 1 && refill) {
+        fetch_own(cur, step + 2);                              // keeps every wave's request count the same
       }
     }
   };
 
   if constexpr (NQB == 1) {
-    // Two stages, both requested up front.  A wave reads only its own 32 rows of a step's K and V tiles, so in the
-    // loop every wave refills exactly those rows itself, right after it has used them: past the first two steps
-    // (whose requests were shared out differently above) the waves do not depend on each other and the loop has
-    // no barrier; the refill stays in flight while the other stage is worked on.
-    auto fetch_own = [&](bf16_t* st, int step) {
-      const int row0 = j_begin + step * KSTEP;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int q = 512 * wave + 64 * i + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
-          const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(t ? vrs : krs, (lds_void_ptr)(st + t * TILE + (8 * wave + i) * 512), 16, off, 0, 0, 0);
-        }
-    };
+    // Two stages.  Before step s the wave's rows of s must have landed: the only younger requests are those of
+    // step s + 1 (issued during step s - 1).  With up to 8 queries the first two steps were requested across
+    // waves, hence the one barrier before step 1.
 #pragma unroll 1
     for (int step = 0; step < nsteps; step += 2) {
       if (step > 0) {
-        // this wave's rows of `step` are older than its refill for step + 1
         if (step + 1 < nsteps) wait_vmem_n<16>(); else wait_vmem();
       }
-      step_compute(stage0, step);
-      if (step + 2 < nsteps) fetch_own(stage0, step + 2);
+      step_compute(stage0, step, step + 2 < nsteps);
       if (step + 1 < nsteps) {
         if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-        if (step == 0) lds_barrier();                         // step 1 was requested by other waves
-        step_compute(stage1, step + 1);
-        if (step + 3 < nsteps) fetch_own(stage1, step + 3);
+        if (shared_first_steps && step == 0) lds_barrier();
+        step_compute(stage1, step + 1, step + 3 < nsteps);
       }
     }
   } else {
-  // two stages, both requested up front; a stage is refilled as soon as every wave is done with it, and the refill
-  // stays in flight while the other stage is worked on (barriers without a fence: a fence would wait for it)
+    // two stages, both complete at this point; a stage is refilled as soon as every wave is done with it, and the
+    // refill stays in flight while the other stage is worked on (barriers without a fence: a fence would wait for it)
 #pragma unroll 1
-  for (int step = 0; step < nsteps; step += 2) {
-    step_compute(stage0, step);
-    lds_barrier();                                          // all waves done with stage0
-    if (step + 2 < nsteps) fetch(stage0, step + 2);
-    if (step + 1 < nsteps) {
-      // stage1's loads (step + 1) are older than the refill just issued
-      if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-      lds_barrier();
-      step_compute(stage1, step + 1);
-      lds_barrier();
-      if (step + 3 < nsteps) fetch(stage1, step + 3);
-      if (step + 2 < nsteps) {
-        if (step + 3 < nsteps) wait_vmem_n<16>(); else wait_vmem();
+    for (int step = 0; step < nsteps; step += 2) {
+      step_compute(stage0, step, false);
+      lds_barrier();                                          // all waves done with stage0
+      if (step + 2 < nsteps) fetch(stage0, step + 2);
+      if (step + 1 < nsteps) {
+        // stage1's loads (step + 1) are older than the refill just issued
+        if (step > 0) { if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem(); lds_barrier(); }
+        step_compute(stage1, step + 1, false);
         lds_barrier();
+        if (step + 3 < nsteps) fetch(stage1, step + 3);
+        if (step + 2 < nsteps) {
+          if (step + 3 < nsteps) wait_vmem_n<16>(); else wait_vmem();
+          lds_barrier();
+        }
       }
     }
   }
-  }
 
-  // ---- merge the waves of each query block (fixed order) and write this key range's partial
+  // ---- merge the waves' partials of each query block (fixed order) and write this key range's partial.
+  // Buffer: [4 waves][32 queries][128 channels] floats = one stage; a float4 of query q sits 4 q floats further
+  // round its row, so that neither the per-query writes nor the per-channel reads conflict.
   __syncthreads();
-  // merge buffer [4 waves][32 queries][128 channels] floats = one stage; channel c of query q is stored at
-  // (c + q) % 128 so that neither the per-query writes nor the per-channel reads conflict
   float* ob = (float*)stage0;
   static_assert(4 * 32 * HD * sizeof(float) <= sizeof(stage0), "merge buffer must fit in one stage");
   const int64_t pbase = ((int64_t)h * a.R + r) * a.Mpad + m0;
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int c = 32 * cb + 8 * (e >> 2) + 4 * hf + (e & 3);
-      ob[(wave * 32 + ql) * HD + ((c + ql) & (HD - 1))] = o[cb][e];
+    for (int e4 = 0; e4 < 4; ++e4) {
+      const int c = 32 * cb + 8 * e4 + 4 * hf;
+      const float4 v = {o[cb][4 * e4], o[cb][4 * e4 + 1], o[cb][4 * e4 + 2], o[cb][4 * e4 + 3]};
+      *(float4*)(ob + (wave * 32 + ql) * HD + ((c + 4 * ql) & (HD - 1))) = v;
     }
   if (hf == 0) { s_ml[wave][0][ql] = mrun; s_ml[wave][1][ql] = lrun; }
   __syncthreads();
-  for (int i = tid; i < mtot * HD; i += 256) {               // padding rows are never read
-    const int c = i & (HD - 1), qq = i >> 7, q = qq & 31, w0 = (qq >> 5) * WPB;   // query, its row in the block, first wave of the block
+  if (tid < 32 * NQB) {                                       // per query: the merged (max, sum) and each wave's weight
+    const int qb = tid >> 5, q = tid & 31, w0 = qb * WPB;
     float mm = -INFINITY;
 #pragma unroll
     for (int wv = 0; wv < WPB; ++wv) mm = fmaxf(mm, s_ml[w0 + wv][0][q]);
-    float acc = 0.f, lt = 0.f;
-    if (mm > -INFINITY) {
+    float lt = 0.f;
 #pragma unroll
-      for (int wv = 0; wv < WPB; ++wv) {
-        const float sc = __builtin_amdgcn_exp2f((s_ml[w0 + wv][0][q] - mm) * c2);
-        acc += ob[((w0 + wv) * 32 + q) * HD + ((c + q) & (HD - 1))] * sc;
-        lt += s_ml[w0 + wv][1][q] * sc;
-      }
+    for (int wv = 0; wv < WPB; ++wv) {
+      const float mw = s_ml[w0 + wv][0][q];
+      const float sc = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mw - mm) * c2);
+      s_sc[w0 + wv][q] = sc;
+      lt += s_ml[w0 + wv][1][q] * sc;
     }
-    a.opart[(pbase + qq) * HD + c] = acc;
-    if (c == 0) { a.mlpart[(pbase + qq) * 2] = mm; a.mlpart[(pbase + qq) * 2 + 1] = lt; }
+    s_mm[qb][0][q] = mm; s_mm[qb][1][q] = lt;
+  }
+  __syncthreads();
+  for (int i = tid; i < mtot * 32; i += 256) {                 // padding rows are never read
+    const int c4 = i & 31, qq = i >> 5, qb = qq >> 5, q = qq & 31, w0 = qb * WPB;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int wv = 0; wv < WPB; ++wv) {
+      const float sc = s_sc[w0 + wv][q];
+      const float4 v = *(const float4*)(ob + ((w0 + wv) * 32 + q) * HD + ((4 * c4 + 4 * q) & (HD - 1)));
+      acc.x += v.x * sc; acc.y += v.y * sc; acc.z += v.z * sc; acc.w += v.w * sc;
+    }
+    *(float4*)(a.opart + (pbase + qq) * HD + 4 * c4) = acc;
+    if (c4 == 0) { a.mlpart[(pbase + qq) * 2] = s_mm[qb][0][q]; a.mlpart[(pbase + qq) * 2 + 1] = s_mm[qb][1][q]; }
   }
 }
 
