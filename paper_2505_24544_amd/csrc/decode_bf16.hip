@@ -616,20 +616,18 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     read_frags(1, qlo);
   } else {
     // 33 .. 64 queries, all four waves sum both blocks: step 0 (requests dealt across the waves), block 0's slices,
-    // step 1; block 1's slices are requested as soon as block 0's have been added up (one set of load registers)
-    // and arrive while block 0 goes through the buffer.  Every barrier below is passed by a wave only after its
-    // own share of step 0 (at the last one: of step 1) has landed, so the stages are complete behind them.
-    u32x4_t t[4][8];
+    // step 1, block 1's slices -- the last of these only issue as the oldest requests retire (a wave holds at most
+    // 63), which is when step 0 lands, and are back soon after step 1.  Every barrier below is passed by a wave only
+    // after its own share of step 0 (at the last one: of step 1) has landed, so the stages are complete behind them.
+    u32x4_t t0[4][8], t1[4][8];
     float4 acc[4] = {zero4, zero4, zero4, zero4};
     fetch(stage0, 0);
-    q_issue(0, 32, 4, 0, t);
+    q_issue(0, 32, 4, 0, t0);
     fetch(stage1, 1);
+    q_issue(1, mtot - 32, 4, 0, t1);                           // rows past the last query: zeros
     __builtin_amdgcn_sched_barrier(0);
-    wait_vmem_n<16>();                                         // step 0 and block 0's slices
-    q_add(t, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    q_issue(1, mtot - 32, 4, 0, t);                            // rows past the last query: zeros
-    __builtin_amdgcn_sched_barrier(0);
+    wait_vmem_n<48>();                                         // step 0 and block 0's slices
+    q_add(t0, acc);
     q_finish(0, 32, 4, acc);
     q_store(0, 4, acc);
     lds_barrier();                                             // block 0 visible
@@ -638,7 +636,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     wait_vmem();
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = zero4;
-    q_add(t, acc);
+    q_add(t1, acc);
     q_finish(1, mtot - 32, 4, acc);
     q_store(NQB - 1, 4, acc);
     lds_barrier();                                             // block 1 visible; steps 0 and 1 landed
@@ -684,9 +682,6 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
-        if constexpr (NQB == 1) {
-          if (refill) fetch_own_half(cur, step + 2, 0);        // the wave's K rows are in registers: refill them
-        }
         // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
         f32x16_t st, st2;
 #pragma unroll
@@ -695,6 +690,14 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         for (int s = 0; s < 8; ++s) {
           st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qh[s], st, 0, 0, 0);
           st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qlo[s], st2, 0, 0, 0);
+        }
+        if constexpr (NQB == 1) {
+          // The wave's K rows are in registers: refill them.  Behind the MFMAs in program order: while every CU
+          // streams, a request waits in the issue stage for a slot in the memory pipeline (about 170 cycles each),
+          // and the matrix pipe works through the scores meanwhile.
+          __builtin_amdgcn_sched_barrier(0);
+          if (refill) fetch_own_half(cur, step + 2, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) st[e] += st2[e];
@@ -751,9 +754,6 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb) asm volatile("" : "+v"(vf[t][cb].s.x), "+v"(vf[t][cb].s.y));
-        if constexpr (NQB == 1) {
-          if (refill) fetch_own_half(cur, step + 2, 1);        // ... and the wave's V rows
-        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
@@ -762,6 +762,11 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb)
             o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb].v, pf.v, o[cb], 0, 0, 0);
+        }
+        if constexpr (NQB == 1) {
+          __builtin_amdgcn_sched_barrier(0);
+          if (refill) fetch_own_half(cur, step + 2, 1);        // ... and the wave's V rows, behind the P V MFMAs
+          __builtin_amdgcn_sched_barrier(0);
         }
       } else if (NQB == 1 && refill) {
         fetch_own(cur, step + 2);                              // keeps every wave's request count the same
