@@ -163,6 +163,15 @@ class ClockSampler:
         return out
 
 
+def run_calib_copy(torch):
+    """One plain 1 GiB device-to-device copy: what FETCH_SIZE / WRITE_SIZE read for a known size."""
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def train_leg(torch, bx, dm, synth, name, steps, warmup, profile=True, sampler=None, calib_copy=False):
     """fwd + bwd at one training configuration.  Returns (summary dict, device tensors for later legs)."""
     dev = "cuda:0"
@@ -189,11 +198,7 @@ def train_leg(torch, bx, dm, synth, name, steps, warmup, profile=True, sampler=N
                             dxq, dxkv, dwq, dwk, dwv, dwo, ws_b, stream)
 
     if calib_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        run_calib_copy(torch)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
@@ -250,6 +255,10 @@ def train_leg(torch, bx, dm, synth, name, steps, warmup, profile=True, sampler=N
     return summ, keep
 
 
+class _Skip(Exception):
+    pass
+
+
 class _Null:
     def __enter__(self):
         return self
@@ -271,6 +280,8 @@ def main():
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with events")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="decode leg: skip the HIP-graph replays (for counter runs, which look at single dispatches)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
@@ -285,7 +296,9 @@ def main():
     full = args.only == "all"
 
     if args.only == "decode":
-        print(json.dumps({"decode": bench_decode(torch, bx, dm, synth)}))
+        if args.calib_copy:
+            run_calib_copy(torch)
+        print(json.dumps({"decode": bench_decode(torch, bx, dm, synth, not args.no_graph)}))
         return
 
     sampler = ClockSampler()
@@ -316,7 +329,7 @@ def main():
                                 kernel_avg_ms={n: k["avg_ms"] for n, k in s["kernels"].items()})
 
     if full and not args.no_decode:
-        decode = bench_decode(torch, bx, dm, synth)
+        decode = bench_decode(torch, bx, dm, synth, not args.no_graph)
 
     cpu = cpu_other = None
     if full and not args.no_cpu_baseline:
@@ -451,7 +464,7 @@ def _time_calls(torch, fn, n_sets, reps):
     return e0.elapsed_time(e1) / reps * 1e3
 
 
-def bench_decode(torch, bx, dm, synth):
+def bench_decode(torch, bx, dm, synth, graphs=True):
     """Draft step at the decode config (L=4096, D=4096, H=32, d=128): random bf16 cache rows and weights of those
     shapes (time is value-independent), ten buffer sets so that every call reads cold HBM."""
     cfg = synth.CONFIGS["c4"]
@@ -502,6 +515,8 @@ def bench_decode(torch, bx, dm, synth):
         # the same fifty calls as five replays of a HIP graph that holds one call per buffer set
         graph_us = None
         try:
+            if not graphs:
+                raise _Skip()
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr):
                 cs = torch.cuda.current_stream()
@@ -517,6 +532,8 @@ def bench_decode(torch, bx, dm, synth):
             torch.cuda.synchronize()
             graph_us = e0.elapsed_time(e1) / (5 * nset) * 1e3
             del gr
+        except _Skip:
+            pass
         except Exception as ex:        # reported, not hidden: the eager figure stands
             graph_us = None
             res.setdefault("graph_errors", []).append("M%d: %r" % (M, ex))

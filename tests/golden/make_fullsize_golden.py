@@ -16,7 +16,8 @@ values there (float64).  Two oracle runs per config:
   * "group" : the op restricted to one KV head and its query heads (weights
               sliced to that group) over ALL batch elements: o, lse of the
               group and the group's rows/columns of dwq, dwk, dwv, dwo are
-              exact (they do not mix heads).
+              exact (they do not mix heads).  Several groups per config (the
+              first, the last and one in between), stored as <tensor>@g<group>.
 """
 import os
 import sys
@@ -33,11 +34,11 @@ N_SAMPLES = 6000
 OUT = os.path.dirname(os.path.abspath(__file__))
 
 PLAN = {
-    # name: (config, peaked, batch element of the full run, KV group of the group run)
-    "c2": ("c2", False, 0, 5),
-    "c2_peaked": ("c2", True, 3, None),
-    "c3": ("c3", False, 1, 3),
-    "c5": ("c5", False, 0, None),
+    # name: (config, peaked, batch element of the full run, KV groups of the group runs)
+    "c2": ("c2", False, 0, (5, 0, 31)),
+    "c2_peaked": ("c2", True, 3, ()),
+    "c3": ("c3", False, 1, (3, 0, 7)),
+    "c5": ("c5", False, 0, ()),
 }
 
 
@@ -47,7 +48,7 @@ def sample(rng, shape, n=N_SAMPLES):
 
 
 def run(name):
-    cname, peaked, b_full, grp = PLAN[name]
+    cname, peaked, b_full, groups = PLAN[name]
     cfg = synth.CONFIGS[cname]
     t0 = time.time()
     inp = synth.make_inputs(cfg, peaked_queries=peaked)
@@ -83,8 +84,9 @@ def run(name):
             put(tname, r[tname].shape, idx, r[tname].reshape(-1)[idx])
     del r
 
-    # ---- group run over all batch elements
-    if grp is not None:
+    # ---- group runs over all batch elements
+    for gi, grp in enumerate(groups):
+        sfx = "" if gi == 0 else "@g%d" % grp
         t1 = time.time()
         hs = slice(grp * rep * d, (grp + 1) * rep * d)      # query-head columns of the group
         gs = slice(grp * d, (grp + 1) * d)                  # kv-head columns
@@ -94,11 +96,11 @@ def run(name):
         # o and lse of the group's heads, all batches
         o_idx = sample(rng, r["o"].shape)
         bb, pp, hh, cc = np.unravel_index(o_idx, r["o"].shape)
-        put("o_group", (B, S, H, d), np.ravel_multi_index((bb, pp, hh + grp * rep, cc), (B, S, H, d)),
+        put("o_group" + sfx, (B, S, H, d), np.ravel_multi_index((bb, pp, hh + grp * rep, cc), (B, S, H, d)),
             r["o"].reshape(-1)[o_idx])
         l_idx = sample(rng, r["lse"].shape)
         bb, hh, pp = np.unravel_index(l_idx, r["lse"].shape)
-        put("lse_group", (B, H, S), np.ravel_multi_index((bb, hh + grp * rep, pp), (B, H, S)),
+        put("lse_group" + sfx, (B, H, S), np.ravel_multi_index((bb, hh + grp * rep, pp), (B, H, S)),
             r["lse"].reshape(-1)[l_idx])
         # weight-gradient slices
         for tname, full_shape, col0, is_rows in (("dwq", (D, H * d), grp * rep * d, False),
@@ -112,9 +114,9 @@ def run(name):
                 full_idx = np.ravel_multi_index((i0 + col0, i1), full_shape)
             else:
                 full_idx = np.ravel_multi_index((i0, i1 + col0), full_shape)
-            put(tname, full_shape, full_idx, g_.reshape(-1)[idx])
+            put(tname + sfx, full_shape, full_idx, g_.reshape(-1)[idx])
         del r
-    out["meta"] = np.array([b_full, -1 if grp is None else grp, int(peaked)], np.int64)
+    out["meta"] = np.array([b_full, groups[0] if groups else -1, int(peaked)], np.int64)
     path = os.path.join(OUT, "fullsize_%s.npz" % name)
     np.savez_compressed(path, **out)
     print("wrote %s (%.0f KB) in %.0f s" % (path, os.path.getsize(path) / 1e3, time.time() - t0), flush=True)

@@ -48,7 +48,7 @@ def test_fullsize_sampled_parity(name):
         if not key.startswith("idx_"):
             continue
         tname = key[4:]
-        t = tensors[tname]
+        t = tensors[tname.split("@")[0]]                 # <tensor>@g<group>: the same tensor, another KV group's part
         assert tuple(gold["shape_" + tname]) == tuple(t.shape), tname
         got, ref = _gather(t, gold[key]), gold["val_" + tname]
         checked += 1
