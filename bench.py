@@ -41,12 +41,17 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_training_c2.md")
 
 
+TRAINING_KERNEL_SOURCES = ("gemm_bf16.hip", "attn_fwd_bf16.hip", "attn_bwd_bf16.hip", "attn_tiles.h", "common.h",
+                           "mask_index.h")
+
+
 def kernel_source_digest():
-    """sha256 over the HIP sources: identifies the kernels a counter table was measured on."""
+    """sha256 over the sources the training step's kernels are compiled from: identifies the kernels a counter
+    table was measured on."""
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2505_24544_amd", "csrc", "*.h*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for f in TRAINING_KERNEL_SOURCES:
+        h.update(f.encode())
+        h.update(open(os.path.join(ROOT, "paper_2505_24544_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -163,6 +168,25 @@ class ClockSampler:
         return out
 
 
+def shader_clock_summary(samples):
+    """Mean shader clock per step from consecutive clock samples [n + 1, slots, (cycle counter, 100 MHz clock)]:
+    per step the median over the compute units whose slot was written by both samples."""
+    import numpy as np
+    mhz = []
+    for s0, s1 in zip(samples[:-1], samples[1:]):
+        both = (s0[:, 1] > 0) & (s1[:, 1] > s0[:, 1])
+        if both.any():
+            d = (s1[both] - s0[both]).astype(np.float64)
+            mhz.append(float(np.median(d[:, 0] / d[:, 1])) * 100.0)
+    ok = [m for m in mhz if 300.0 <= m <= 3000.0]
+    if not ok:
+        return dict(note="no plausible sample pair", raw_mhz=[round(m, 1) for m in mhz[:4]])
+    return dict(source="beagle_xattn_probe_clock: per-compute-unit shader-cycle counter over the 100 MHz device clock, one sample per step",
+                mhz_median=round(statistics.median(ok)), mhz_min=round(min(ok)), mhz_max=round(max(ok)),
+                steps_used=len(ok), steps_dropped=len(samples) - 1 - len(ok), nominal_mhz=2400,
+                bf16_mfma_peak_at_median_clock_tflops=round(PEAK_BF16_TFLOPS * statistics.median(ok) / 2400.0, 1))
+
+
 def run_calib_copy(torch):
     """One plain 1 GiB device-to-device copy: what FETCH_SIZE / WRITE_SIZE read for a known size."""
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -211,13 +235,18 @@ def train_leg(torch, bx, dm, synth, name, steps, warmup, profile=True, sampler=N
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         # (2) the same loop with one event pair per step: spread of the step time
+        # and one sample of the shader-cycle counter against the 100 MHz device clock after every step
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        for a, b in ev:
+        clk = torch.zeros(steps + 1, bx.BEAGLE_CLOCK_SLOTS, 2, dtype=torch.int64, device=dev)
+        bx.beagle_xattn_probe_clock(clk[0], stream)
+        for i, (a, b) in enumerate(ev):
             a.record()
             step()
             b.record()
+            bx.beagle_xattn_probe_clock(clk[i + 1], stream)
         torch.cuda.synchronize()
         per_step = [a.elapsed_time(b) for a, b in ev]
+        shader_clock = shader_clock_summary(clk.cpu().numpy())
         # (3) every launch bracketed by events: the per-kernel table
         prof = {}
         if profile:
@@ -249,6 +278,7 @@ def train_leg(torch, bx, dm, synth, name, steps, warmup, profile=True, sampler=N
                 pct_bf16_mfma_peak=round(100 * tflops / PEAK_BF16_TFLOPS, 2), tokens_per_s=round(B * S / (ms_step * 1e-3)),
                 step_ms=dict(mean_wall=round(ms_step, 4), median=round(statistics.median(per_step), 4),
                              min=round(min(per_step), 4), max=round(max(per_step), 4), n=steps),
+                shader_clock=shader_clock,
                 algorithmic_tflop_per_step=round(fl["total"] / 1e12, 4), roofline=roofline, kernels=kernels)
     keep = dict(cfg=cfg, desc=desc, t=t, fl=fl, y=y, lse=lse, q=q, k=k, v=v, o=o, dxq=dxq, dxkv=dxkv, dwq=dwq, dwk=dwk,
                 dwv=dwv, dwo=dwo, ws_f=ws_f, E=E)
@@ -324,7 +354,8 @@ def main():
             torch.cuda.empty_cache()
             others[name] = dict(workload=s["workload"], ms_per_step=s["ms_per_step"], tflops=s["tflops"],
                                 pct_bf16_mfma_peak=s["pct_bf16_mfma_peak"], tokens_per_s=s["tokens_per_s"],
-                                step_ms=s["step_ms"], algorithmic_tflop_per_step=s["algorithmic_tflop_per_step"],
+                                step_ms=s["step_ms"], shader_clock_mhz=(s["shader_clock"] or {}).get("mhz_median"),
+                                algorithmic_tflop_per_step=s["algorithmic_tflop_per_step"],
                                 roofline=s["roofline"],
                                 kernel_avg_ms={n: k["avg_ms"] for n, k in s["kernels"].items()})
 
@@ -345,7 +376,7 @@ def main():
         "pct_bf16_mfma_peak": head["pct_bf16_mfma_peak"],
         "tokens_per_s": head["tokens_per_s"],
         "algorithmic_tflop_per_step": head["algorithmic_tflop_per_step"],
-        "step_ms": head["step_ms"], "clock": sampler.summary(),
+        "step_ms": head["step_ms"], "clock": dict(sampler.summary(), shader_clock=head["shader_clock"]),
         "roofline": head["roofline"],
         "roofline_decode": (decode or {}).get("roofline_decode"),
         "cpu_baseline": cpu,

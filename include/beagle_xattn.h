@@ -495,6 +495,23 @@ beagle_status beagle_xattn_profile_get(int32_t i, const char** name, int32_t* la
  * (written only if the XOR of all words read equals one magic value).        */
 beagle_status beagle_xattn_probe_read(const void* buf, size_t bytes, int32_t workgroups, void* sink, void* hip_stream);
 
+/* ---- clock sample (measurement aid) -----------------------------------------
+ * Enqueues a kernel of 1024 one-wave workgroups, each of which writes two
+ * 64-bit counters, read back to back, into the slot of the compute unit it ran
+ * on: out[2 s] = that unit's shader-cycle counter, out[2 s + 1] = the device's
+ * constant-rate clock (100 MHz); s = 0 .. BEAGLE_CLOCK_SLOTS - 1 is formed from
+ * the XCD number and the unit's position bits.  `out` is a DEVICE buffer of
+ * BEAGLE_CLOCK_SLOTS x 16 writable bytes, 8-byte aligned, zeroed by the caller
+ * before its first use; a slot whose unit ran no workgroup keeps its old
+ * contents.  Cycle counters of different units are not aligned: take
+ * differences within one slot only.  Two samples on one stream around a region
+ * of work give (delta cycles) / (delta clock) x 100 MHz = the mean shader clock
+ * over that region; the benchmark's timed loops report it next to their
+ * throughput, since the matrix-pipe peak that the throughput is set against
+ * assumes 2.4 GHz.  Not part of the method.                                    */
+#define BEAGLE_CLOCK_SLOTS 2048
+beagle_status beagle_xattn_probe_clock(void* out, void* hip_stream);
+
 const char* beagle_xattn_status_string(beagle_status s);
 /* "major.minor" of this ABI. */
 const char* beagle_xattn_version(void);

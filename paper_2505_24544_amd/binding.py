@@ -35,7 +35,7 @@ EXPORTS = (
     "beagle_xattn_block_kv_append",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
-    "beagle_xattn_probe_read", "beagle_xattn_status_string", "beagle_xattn_version",
+    "beagle_xattn_probe_read", "beagle_xattn_probe_clock", "beagle_xattn_status_string", "beagle_xattn_version",
 )
 
 
@@ -177,6 +177,8 @@ def lib() -> C.CDLL:
                                            C.POINTER(C.c_double)]
     L.beagle_xattn_probe_read.restype = C.c_int
     L.beagle_xattn_probe_read.argtypes = [vp, C.c_size_t, C.c_int32, vp, vp]
+    L.beagle_xattn_probe_clock.restype = C.c_int
+    L.beagle_xattn_probe_clock.argtypes = [vp, vp]
     L.beagle_xattn_status_string.restype = C.c_char_p
     L.beagle_xattn_status_string.argtypes = [C.c_int]
     L.beagle_xattn_version.restype = C.c_char_p
@@ -344,6 +346,7 @@ def beagle_xattn_draft_step(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, wor
 
 
 BEAGLE_STATIC_SCRATCH_BYTES = 32 << 20
+BEAGLE_CLOCK_SLOTS = 2048
 
 
 def beagle_xattn_draft_step_static(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, stream=None, *, check=True) -> int:
@@ -389,6 +392,10 @@ def beagle_xattn_profile_end() -> dict:
                "beagle_xattn_profile_get", True)
         out[name.value.decode()] = (cnt.value, ms.value)
     return out
+
+
+def beagle_xattn_probe_clock(out, stream=None) -> None:
+    _check(lib().beagle_xattn_probe_clock(_ptr(out), _stream(stream)), "beagle_xattn_probe_clock", True)
 
 
 def beagle_xattn_probe_read(buf, nbytes: int, workgroups: int, sink, stream=None) -> None:

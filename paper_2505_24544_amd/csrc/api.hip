@@ -455,6 +455,14 @@ beagle_status beagle_xattn_probe_read(const void* buf, size_t bytes, int32_t wor
   return hip_status();
 }
 
+beagle_status beagle_xattn_probe_clock(void* out, void* hip_stream) {
+  if (!out) return BEAGLE_ERR_NULL;
+  if (((uintptr_t)out) & 7u) return BEAGLE_ERR_ALIGN;
+  (void)hipGetLastError();
+  launch_clock_probe((uint64_t*)out, (hipStream_t)hip_stream);
+  return hip_status();
+}
+
 const char* beagle_xattn_version(void) { return "1.0"; }
 
 // ------------------------------------------------------------- mask helpers

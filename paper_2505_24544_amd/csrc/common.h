@@ -180,6 +180,7 @@ struct DecodeArgs {
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
 void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s);
+void launch_clock_probe(uint64_t* out, hipStream_t s);
 size_t kv_append_bf16_ws_bytes(int32_t n, int32_t N, int32_t K);
 bool kv_append_bf16_fits(int32_t n, int32_t N, int32_t K);
 // feed-forward layer for a handful of rows: h = (silu(z W_gate) * (z W_up)) W_down + y_res

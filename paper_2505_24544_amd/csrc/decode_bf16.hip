@@ -916,6 +916,26 @@ void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, 
   hipLaunchKernelGGL(read_probe_kernel, dim3(wgs), dim3(256), 0, s, (const uint4*)buf, bytes / 16, sink);
 }
 
+// Many one-wave workgroups, so that nearly every compute unit runs one: each writes the shader-cycle counter and the
+// constant-rate (100 MHz) device clock, read back to back, into the slot of the place it finds itself on (XCD number
+// and the shader-engine / array / compute-unit bits of the hardware id).  Cycle counters of different places are not
+// aligned, so differences are only taken within a slot.
+__global__ void clock_probe_kernel(uint64_t* __restrict__ out) {
+  if (threadIdx.x == 0) {
+    uint32_t xcc, hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw));
+    const uint32_t slot = ((xcc & 7u) << 8) | ((hw >> 8) & 0xffu);
+    const uint64_t cyc = __builtin_readcyclecounter();
+    const uint64_t real = __builtin_amdgcn_s_memrealtime();
+    out[2 * slot] = cyc;
+    out[2 * slot + 1] = real;
+  }
+}
+void launch_clock_probe(uint64_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(clock_probe_kernel, dim3(1024), dim3(64), 0, s, out);
+}
+
 // ---- host side ----------------------------------------------------------------
 namespace {
 struct DecLayout {
