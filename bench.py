@@ -515,6 +515,11 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         slab[i, 3].copy_((torch.randn(per, device=dev, generator=g) * 0.02).to(torch.bfloat16))
         sets.append((slab[i, 0].view(L, G, hd), slab[i, 1].view(L, G, hd), slab[i, 2].view(D, H * hd),
                      slab[i, 3].view(H * hd, D)))
+    # the output projections once more in the decode-time layout (transposed, laid out once per model load):
+    # the same bytes per call, streamed from these buffers instead
+    wo_t = torch.empty(nset, D, H * hd, dtype=torch.bfloat16, device=dev)
+    for i in range(nset):
+        bx.beagle_xattn_prepare_wo(dm.desc_of(cfg.with_(seq_q=1)), sets[i][3], wo_t[i])
     res, roof = {}, {}
     stream = torch.cuda.current_stream()
 
@@ -543,6 +548,11 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         ws = dm.workspace(desc, bx.BEAGLE_WS_DRAFT)
         call = lambda r, st=stream: bx.beagle_xattn_draft_step(desc, x, *sets[r % nset], y, lse, ws, st)
         us = _time_calls(torch, call, nset, 50)
+        prep_us = None
+        if M <= bx.BEAGLE_PREPARED_MAX_QUERIES:
+            prep = lambda r: bx.beagle_xattn_draft_step_prepared(desc, x, sets[r % nset][0], sets[r % nset][1],
+                                                                 sets[r % nset][2], wo_t[r % nset], L, None, 0, y, lse, ws, stream)
+            prep_us = _time_calls(torch, prep, nset, 50)
         # the same fifty calls as five replays of a HIP graph that holds one call per buffer set
         graph_us = None
         try:
@@ -583,13 +593,19 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
                               pct_hbm_peak=round(100 * call_bytes / us / 1e3 / PEAK_HBM_GBS, 2),
                               draft_tokens_per_s=round(M / (us * 1e-6)), bytes=call_bytes,
                               kernel_us_bracketed=kern)
+        if prep_us:
+            res["M%d" % M]["prepared_wo"] = dict(us_per_call=round(prep_us, 2), gbs=round(call_bytes / prep_us / 1e3, 1),
+                                                 pct_hbm_peak=round(100 * call_bytes / prep_us / 1e3 / PEAK_HBM_GBS, 2))
         att = kern.get("draft_attn")
         roof["M%d" % M] = dict(
             bound="hbm", kernel="beagle_xattn_draft_step (whole call: projections, attention, merges)",
             bytes=call_bytes, avg_us=round(us, 2), achieved=round(call_bytes / us / 1e3, 1), peak=PEAK_HBM_GBS,
             unit="GB/s", frac=round(call_bytes / us / 1e3 / PEAK_HBM_GBS, 4),
             graph_replay=dict(avg_us=round(graph_us, 2), frac=round(call_bytes / graph_us / 1e3 / PEAK_HBM_GBS, 4)) if graph_us else None,
-            frac_of_read_probe=round(probe["whole_step_134MB"]["us"] / best, 4),
+            prepared_wo=dict(entry="beagle_xattn_draft_step_prepared (wo transposed once per model load; same bytes per call)",
+                             avg_us=round(prep_us, 2), achieved=round(call_bytes / prep_us / 1e3, 1),
+                             frac=round(call_bytes / prep_us / 1e3 / PEAK_HBM_GBS, 4)) if prep_us else None,
+            frac_of_read_probe=round(probe["whole_step_134MB"]["us"] / min(best, prep_us or best), 4),
             attention_core=dict(kernel="decode_attn_kernel", bytes=core_bytes, avg_us_bracketed=att,
                                 frac_bracketed=round(core_bytes / att / 1e3 / PEAK_HBM_GBS, 4) if att else None,
                                 note="event-bracketed (includes the bracket's own gaps); the kernel-trace duration is in profiles/"))
@@ -621,6 +637,10 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         kc, vc, wq, wo = sets[r % nset]
         bx.beagle_xattn_draft_step_tree(desc, x, kc, vc, wq, wo, L - T, tmd, 2, y, lse, ws, stream)
 
+    def tree_prepared_call(r):
+        kc, vc, wq, _ = sets[r % nset]
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_t[r % nset], L - T, tmd, 2, y, lse, ws, stream)
+
     def append_call(r):
         kc, vc, _, _ = sets[r % nset]
         bx.beagle_xattn_kv_append(adesc, x, wk, wv, kc, vc, L - T, aws, stream)
@@ -640,7 +660,8 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         prm = bx.make_block_params(F, 1e-5, wq=wq, wo=wo, w_gate=wg, w_up=wu, w_down=wd, g_q=gq, g_mlp=gm)
         bx.beagle_xattn_block_draft_step(desc, prm, x, kc, vc, L - T, tmd, 2, hb, lse, bws, stream)
 
-    for name, fn in (("tree_M10_T50", tree_call), ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call)):
+    for name, fn in (("tree_M10_T50", tree_call), ("tree_M10_T50_prepared_wo", tree_prepared_call),
+                     ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call)):
         us = _time_calls(torch, fn, nset, 50)
         if name.startswith("tree"):
             nbytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2 + 2 * D * H * hd * 2

@@ -459,6 +459,34 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
     const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Decode-time weight layout.  The draft step streams each weight matrix once;
+ * with the output projection stored transposed, wo_t [D, H*d] (the k run of an
+ * output column contiguous), a workgroup can own a few output columns over the
+ * whole of k and still read long runs, so the projection needs no k split, no
+ * partial sums in memory and no launch to add them.  Weights are fixed while
+ * drafting (section 4.1: the draft model is trained beforehand), so the
+ * re-layout is paid once per model load, not per step.
+ *   beagle_xattn_prepare_wo: wo [H*d, D] -> wo_t [D, H*d], both DEVICE, bf16 only
+ *     (BEAGLE_ERR_UNSUPPORTED otherwise); wo_t must not overlap wo.
+ *   beagle_xattn_draft_step_prepared: beagle_xattn_draft_step_tree with wo_t in
+ *     the place of wo (n_true == seq_kv and tree_mask == NULL give the plain
+ *     draft step).  Same definition of y and lse; sums run in a different
+ *     (fixed) order than in beagle_xattn_draft_step, so results agree with it to
+ *     rounding, not bitwise.  Serves 1 <= seq_q <= BEAGLE_PREPARED_MAX_QUERIES,
+ *     bf16, D % 16 == 0, and H*d <= 9216 (<= 4096 above 8 queries);
+ *     BEAGLE_ERR_UNSUPPORTED otherwise, before anything is enqueued: use the
+ *     plain entry points there.
+ * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT).
+ */
+#define BEAGLE_PREPARED_MAX_QUERIES 16
+beagle_status beagle_xattn_prepare_wo(const beagle_xattn_desc* desc, const void* wo, void* wo_t, void* hip_stream);
+beagle_status beagle_xattn_draft_step_prepared(const beagle_xattn_desc* desc,
+    const void* x_draft, const void* k_cache, const void* v_cache,
+    const void* wq, const void* wo_t, int32_t n_true,
+    const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- mask / index inspection (HOST memory, integers only, no GPU needed) --
  * These run the same index code that the kernels use, so that it can be
  * compared bit for bit with a mask built independently from the paper. */

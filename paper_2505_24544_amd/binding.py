@@ -28,7 +28,8 @@ STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: 
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
-    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
+    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_prepare_wo",
+    "beagle_xattn_draft_step_prepared", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
     "beagle_xattn_block_draft_step", "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
@@ -160,6 +161,10 @@ def lib() -> C.CDLL:
                                                 vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step_tree.restype = C.c_int
     L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+    L.beagle_xattn_draft_step_prepared.restype = C.c_int
+    L.beagle_xattn_draft_step_prepared.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+    L.beagle_xattn_prepare_wo.restype = C.c_int
+    L.beagle_xattn_prepare_wo.argtypes = [dp, vp, vp, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
     L.beagle_xattn_kv_append.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_size_t, vp]
     L.beagle_xattn_mask_row_limit.restype = C.c_int
@@ -307,6 +312,20 @@ def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true
     return _check(st, "beagle_xattn_draft_step_tree", check)
 
 
+def beagle_xattn_prepare_wo(desc, wo, wo_t, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_prepare_wo(C.byref(desc), _ptr(wo), _ptr(wo_t), _stream(stream))
+    return _check(st, "beagle_xattn_prepare_wo", check)
+
+
+def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq, wo_t, n_true, tree_mask, mask_words, y, lse,
+                                     workspace, stream=None, *, workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_draft_step_prepared(
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo_t)), int(n_true), _ptr(tree_mask),
+        int(mask_words), _ptr(y), _ptr(lse),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_draft_step_prepared", check)
+
+
 def beagle_xattn_kv_append(desc, x_new, wk, wv, k_cache, v_cache, pos, workspace, stream=None, *,
                            workspace_bytes=None, check=True) -> int:
     st = lib().beagle_xattn_kv_append(
@@ -347,6 +366,7 @@ def beagle_xattn_draft_step(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, wor
 
 BEAGLE_STATIC_SCRATCH_BYTES = 32 << 20
 BEAGLE_CLOCK_SLOTS = 2048
+BEAGLE_PREPARED_MAX_QUERIES = 16
 
 
 def beagle_xattn_draft_step_static(desc, x_draft, k_cache, v_cache, wq, wo, y, lse, stream=None, *, check=True) -> int:

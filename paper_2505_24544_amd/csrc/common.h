@@ -176,7 +176,10 @@ struct DecodeArgs {
   // rotary embedding of the queries (rope != 0): positions rope_pos[m] (device) or all at L
   int32_t rope; float rope_base; const int32_t* rope_pos;
   const void* y_res;   // optional residual added to y (storage type, [M,D])
+  const void* wo_t;    // optional: wo transposed ([D, H*d]); then wo is not read (needs strip_gemm_fits(M, D, H*d))
 };
+bool strip_gemm_fits(int32_t M, int32_t N, int32_t K);
+void launch_transpose_bf16(const void* in, void* out, int32_t R, int32_t C, hipStream_t s);
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
 void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s);

@@ -340,6 +340,206 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------
+// (D')  y[m][n] = sum_k a[m][k] * Wt[n][k]  (+ res[m][n]) for up to 16 rows, on a weight matrix that is stored
+// transposed ([N][K] row-major, laid out once per model load).  With the k run of an output column contiguous, a
+// workgroup owns a strip of 16 output columns over the whole of K and still reads long runs (its eight waves
+// take the 128-k macro-steps in turn: 16 rows x 256 B per step), so there are N / 16 workgroups (one per CU at
+// N = 4096) without any k split: no partial sums in memory and no launch to add them up.
+//
+// Weights go straight into the registers of the lane that feeds them to the MFMA (column n = lane % 16, k group
+// lane / 16 of a 32-k instruction; which 8 k a group holds is free as long as both operands agree: group g of
+// instruction j holds chunk 4 j + g of the macro-step, so one load instruction reads 64 contiguous bytes of each
+// of the 16 rows).  ST_RING macro-steps per wave are in flight: 128 KB per CU, the whole strip at K = 4096.  The activations are small and come
+// from L2: each wave parks those of its own macro-steps in LDS (chunk c of row m at chunk c ^ m).  Everything here is
+// ordinary loads and LDS traffic that the compiler counts by itself.
+// Rows past M hold whatever LDS held: an MFMA output row depends on its own input row only, and rows past M
+// are not stored.
+//
+// MERGE1 (one query): a is not read; it is the attention output merged here from the split-KV partials of (B), as
+// in skinny_gemm_kernel<true>, each wave for the heads that are its macro-steps; workgroup 0 writes the LSE.
+// ---------------------------------------------------------------------------
+namespace dec {
+constexpr int ST_N = 16;                 // output columns per workgroup
+constexpr int ST_RING = 4;               // weight macro-steps in flight per wave (4 KB each)
+constexpr int ST_WAVES = 8;
+constexpr int ST_ABYTES = 144 * 1024;    // LDS for the activations of all waves
+constexpr int ST_MAXM = 16;              // rows per launch
+constexpr int ST_CHUNK = 16;             // activation loads per lane in flight while they are parked
+}  // namespace dec
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+template <bool MERGE1, bool OUT_F32>
+__global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
+                                                            void* __restrict__ yout, const bf16_t* __restrict__ res, int M,
+                                                            int N, int K, CombineArgs cb) {
+  using namespace dec;
+  __shared__ __attribute__((aligned(1024))) unsigned char abuf[ST_ABYTES];
+  __shared__ __attribute__((aligned(16))) float red[ST_WAVES][16][16];
+  __shared__ __attribute__((aligned(16))) float wsc[ST_WAVES][64];
+  __shared__ float winv[ST_WAVES][8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n0 = blockIdx.x * ST_N;
+  const int S = K >> 7;                               // macro-steps; wave w takes s = w, w + 8, ... 
+  const int nst = (S - wave + 7) >> 3, nstw = (S + 7) >> 3;
+  const int rows = M <= 8 ? 8 : 16, lsh = M <= 8 ? 1 : 2;      // activation rows kept per step; loads per step = 1 << lsh
+  unsigned char* aw = abuf + wave * nstw * rows * 256;
+  const int nl = lane & 15, kg = lane >> 4;
+
+  float lse_out = -INFINITY;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  if (nst > 0) {                        // (a wave without a macro-step, K < 1024, only adds zeros below)
+  // ---- activations first (requests complete in order: issued behind the weights they would arrive behind them, and
+  // the MFMAs of a macro-step could not start when its weights land).  Load q of a chunk covers rows 4 g + kg of step i, (i, g) = divmod(q, loads per step):
+  // lane (kg, nl) reads chunk nl ^ row of its row and parks it at chunk nl, i.e. at lane * 16 of the 1 KB piece.
+  const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void*)a, 0, MERGE1 ? 0 : (int)((int64_t)M * K * 2), 0x00020000);
+  xload_t av[MERGE1 ? 1 : ST_CHUNK];
+  auto stage_issue = [&](int q0) {
+#pragma unroll
+    for (int q = 0; q < ST_CHUNK; ++q) {
+      const int i = (q0 + q) >> lsh, row = 4 * ((q0 + q) & ((1 << lsh) - 1)) + kg;
+      av[q] = __builtin_amdgcn_raw_buffer_load_b128(
+          ars, (i < nst && row < M) ? (row * K + (wave + 8 * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
+    }
+  };
+  auto stage_park = [&](int q0) {
+#pragma unroll
+    for (int q = 0; q < ST_CHUNK; ++q) {
+      const int i = (q0 + q) >> lsh, g = (q0 + q) & ((1 << lsh) - 1);
+      if (i < nst) *(xload_t*)(aw + (i * rows + 4 * g) * 256 + lane * 16) = av[q];
+    }
+  };
+  float2 mlv = {-INFINITY, 0.f};
+  float4 ov[MERGE1 ? 2 : 1][COMB_MAXR];
+  if (!MERGE1) {
+    stage_issue(0);
+  } else {
+    // (max, sum) of head slot lane / 8, range lane % 8; then the partial outputs: item j = head slot 2 j + lane / 32,
+    // float4 column lane % 32, all ranges (ranges past R repeat range 0 with weight 0; slots past the wave's last
+    // repeat the last head: loads stay unconditional)
+    const int hl = lane >> 3, r = lane & 7;
+    if (hl < nst && r < cb.R)
+      mlv = *(const float2*)(cb.mlpart + ((int64_t)((wave + 8 * hl) * cb.R + r) * cb.Mpad) * 2);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int h2 = min(wave + 8 * (2 * j + (lane >> 5)), S - 1);
+#pragma unroll
+      for (int rr = 0; rr < COMB_MAXR; ++rr)
+        ov[j][rr] = *(const float4*)(cb.opart + ((int64_t)(h2 * cb.R + (rr < cb.R ? rr : 0)) * cb.Mpad) * HD + 4 * (lane & 31));
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- the first ST_RING macro-steps of weights (at K = 4096: all of them)
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)((int64_t)N * K * 2), 0x00020000);
+  const int wbase = ((n0 + nl) * K + 8 * kg) * 2;
+  union frag_t { xload_t u; bf16x8_t v; };
+  frag_t bw[ST_RING][4];
+  auto load_b = [&](int u, int i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      bw[u][j].u = __builtin_amdgcn_raw_buffer_load_b128(wrs, i < nst ? wbase + ((wave + 8 * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
+  };
+#pragma unroll
+  for (int u = 0; u < ST_RING; ++u) load_b(u, u);
+  __builtin_amdgcn_sched_barrier(0);
+
+  if (MERGE1) {
+    const int hl = lane >> 3;
+    const float c2 = cb.scale * LOG2E;
+    float mm = mlv.x;
+    mm = fmaxf(mm, __shfl_xor(mm, 1)); mm = fmaxf(mm, __shfl_xor(mm, 2)); mm = fmaxf(mm, __shfl_xor(mm, 4));
+    const float sc = mlv.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mlv.x - mm) * c2);
+    float lt = mlv.y * sc;
+    lt += __shfl_xor(lt, 1); lt += __shfl_xor(lt, 2); lt += __shfl_xor(lt, 4);
+    wsc[wave][lane] = sc;
+    if ((lane & 7) == 0) winv[wave][hl] = lt > 0.f ? 1.f / lt : 0.f;
+    lse_out = lt > 0.f ? mm * cb.scale + logf(lt) : -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int hl2 = 2 * j + (lane >> 5), c4 = lane & 31;
+      if (hl2 < nst) {
+        const float4 s0 = *(const float4*)&wsc[wave][hl2 * 8], s1 = *(const float4*)&wsc[wave][hl2 * 8 + 4];
+        const float w[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float inv = winv[wave][hl2];
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int rr = 0; rr < COMB_MAXR; ++rr) {               // fixed order
+          acc.x += ov[j][rr].x * w[rr]; acc.y += ov[j][rr].y * w[rr]; acc.z += ov[j][rr].z * w[rr]; acc.w += ov[j][rr].w * w[rr];
+        }
+        uint2 v = {cvt_pk(acc.x * inv, acc.y * inv), cvt_pk(acc.z * inv, acc.w * inv)};
+        *(uint2*)(aw + hl2 * rows * 256 + (c4 >> 1) * 16 + (c4 & 1) * 8) = v;     // row 0: chunk c at chunk c
+      }
+    }
+  } else {
+    stage_park(0);
+    // more macro-steps than one chunk holds (K beyond 8192, which only the 8-row layout holds): the rest, each chunk one more
+    // round trip behind the weights already requested
+    for (int q0 = ST_CHUNK; q0 < (nst << lsh); q0 += ST_CHUNK) { stage_issue(q0); stage_park(q0); }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- macro-steps: activation fragments from LDS, weights from the ring, refill behind the MFMAs.  No branches
+  // inside a round of the ring: past the wave's last macro-step the weights arrive as zeros and the activations of
+  // its last step are read again, so every path through the loop holds the same number of requests in flight.
+  const int mr = nl & (rows - 1);
+  auto step = [&](int u, int i) {
+    const int ic = min(i, nst - 1);
+    frag_t af[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) af[j].u = *(const xload_t*)(aw + (ic * rows + mr) * 256 + (((4 * j + kg) ^ mr) & 15) * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j].v, bw[u][j].v, acc, 0, 0, 0);
+  };
+  if (nst <= ST_RING) {                 // the ring holds every macro-step: nothing to request any more
+#pragma unroll
+    for (int u = 0; u < ST_RING; ++u) step(u, u);
+  } else {
+    int i0 = 0;
+    do {
+#pragma unroll
+      for (int u = 0; u < ST_RING; ++u) { step(u, i0 + u); load_b(u, i0 + u + ST_RING); }
+      i0 += ST_RING;
+    } while (i0 < nst);
+  }
+  }
+
+  // ---- the waves' k shares, added in wave order; output row 4 kg + e, column nl
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[wave][4 * kg + e][nl] = acc[e];
+  __syncthreads();
+  if (tid < M * 16) {
+    const int m = tid >> 4, n = tid & 15;
+    float v = red[0][m][n];
+#pragma unroll
+    for (int wv = 1; wv < ST_WAVES; ++wv) v += red[wv][m][n];
+    const int64_t o = (int64_t)m * N + n0 + n;
+    if (res) v += __uint_as_float((uint32_t)res[o] << 16);
+    if (OUT_F32) ((float*)yout)[o] = v;
+    else ((bf16_t*)yout)[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
+  }
+  if (MERGE1 && blockIdx.x == 0 && (lane & 7) == 0 && (lane >> 3) < nst)
+    cb.lse[(int64_t)(wave + 8 * (lane >> 3)) * cb.lse_stride] = lse_out;
+}
+
+// out[c][r] = in[r][c]: the one-time re-layout of a weight matrix for strip_gemm_kernel
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int R, int C) {
+  __shared__ bf16_t t[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;
+    if (r0 + r < R && c0 + c < C) t[r][c] = in[(int64_t)(r0 + r) * C + c0 + c];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int c = i >> 6, r = i & 63;
+    if (r0 + r < R && c0 + c < C) out[(int64_t)(c0 + c) * R + r0 + r] = t[r][c];
+  }
+}
+void launch_transpose_bf16(const void* in, void* out, int32_t R, int32_t C, hipStream_t s) {
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((C + 63) / 64, (R + 63) / 64), dim3(256), 0, s, (const bf16_t*)in, (bf16_t*)out, R, C);
+}
+
+// ---------------------------------------------------------------------------
 // (B) split-KV attention: per (head, key range) partials
 // ---------------------------------------------------------------------------
 struct DecAttnArgs {
@@ -969,6 +1169,15 @@ DecLayout dec_layout(int M, int L, int H, int d, int D) {
 }
 }  // namespace
 
+// strip_gemm_kernel serves [M, K] x [N, K]^T when its rows fit one launch, its strips tile N and the activations of
+// all macro-steps fit the LDS set aside for them
+bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || M > dec::ST_MAXM || N % dec::ST_N || K % 128 || K < 128) return false;
+  if ((int64_t)N * K * 2 >= ((int64_t)1 << 31)) return false;
+  const int nstw = (K / 128 + dec::ST_WAVES - 1) / dec::ST_WAVES, rows = M <= 8 ? 8 : 16;
+  return dec::ST_WAVES * nstw * rows * 256 <= dec::ST_ABYTES;
+}
+
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
   return dec_layout(M, L, H, d, D).total;
 }
@@ -1008,6 +1217,29 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       ProfScope ps("draft_attn", s);
       if (Mp > 32) hipLaunchKernelGGL(decode_attn_kernel<2>, dim3(a.H, w.R, (Mp + 63) / 64), dim3(256), 0, s, t);
       else hipLaunchKernelGGL(decode_attn_kernel<1>, dim3(a.H, w.R, 1), dim3(256), 0, s, t);
+    }
+    if (a.wo_t) {
+      // out-projection on the transposed weights: no k split, so no partial sums and no launch to add them
+      CombineArgs cb;
+      cb.opart = opart; cb.mlpart = mlpart; cb.lse = a.lse + m0; cb.lse_stride = a.M; cb.Mpad = w.Mpad; cb.R = w.R;
+      cb.scale = a.scale;
+      bf16_t* yo = (bf16_t*)a.y + (int64_t)m0 * a.D;
+      const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
+      if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
+        ProfScope ps("draft_proj_out", s);
+        hipLaunchKernelGGL((strip_gemm_kernel<true, false>), dim3(a.D / ST_N), dim3(64 * ST_WAVES), 0, s, (const bf16_t*)nullptr,
+                           (const bf16_t*)a.wo_t, (void*)yo, yr, Mp, a.D, HDt, cb);
+      } else {
+        {
+          ProfScope ps("draft_combine", s);
+          hipLaunchKernelGGL(decode_combine_kernel, dim3(Mp, a.H), dim3(128), 0, s, opart, mlpart, o, a.lse + m0, a.M,
+                             w.Mpad, a.H, w.R, a.scale);
+        }
+        ProfScope ps("draft_proj_out", s);
+        hipLaunchKernelGGL((strip_gemm_kernel<false, false>), dim3(a.D / ST_N), dim3(64 * ST_WAVES), 0, s, (const bf16_t*)o,
+                           (const bf16_t*)a.wo_t, (void*)yo, yr, Mp, a.D, HDt, CombineArgs{});
+      }
+      continue;
     }
     if (Mp <= COMB_MAXM && w.R <= COMB_MAXR && HDt % SG_K == 0) {
       // few queries: the merge of the key ranges rides in the projection's prologue

@@ -250,6 +250,29 @@ def run_draft_tree(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=T
     return to_host(y), to_host(lse)
 
 
+def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True):
+    """run_draft_tree through the prepared-weights entry points: wo is re-laid by beagle_xattn_prepare_wo on the
+    device, then beagle_xattn_draft_step_prepared runs on the result.  Also returns the re-laid matrix."""
+    d = desc_of(cfg, 0, scale)
+    M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
+    t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
+    wo_t = torch.full((D, H * cfg.head_dim), float("nan"), dtype=tdtype(cfg), device=DEV)
+    st = bx.beagle_xattn_prepare_wo(d, t["wo"], wo_t, check=check)
+    if not check and st != 0:
+        return st
+    packed = pack_tree_mask(tree_bool)
+    tm = torch.from_numpy(packed.view(np.int32)).to(DEV) if packed.size else None
+    y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
+    lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
+    ws = workspace(d, bx.BEAGLE_WS_DRAFT)
+    st = bx.beagle_xattn_draft_step_prepared(d, t["x"], t["kc"], t["vc"], t["wq"], wo_t, n_true, tm, packed.shape[1],
+                                             y, lse, ws, check=check)
+    torch.cuda.synchronize()
+    if not check:
+        return st
+    return to_host(y), to_host(lse), to_host(wo_t)
+
+
 def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True, desc=None):
     """kc/vc: host arrays [capacity, G, d] (current cache contents).  Returns the caches after the call."""
     d = desc if desc is not None else desc_of(cfg, 0, 0.0)

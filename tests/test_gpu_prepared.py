@@ -1,0 +1,94 @@
+"""GPU parity of the draft step on a prepared (transposed) output projection against the float64 oracle
+(section 4.1, KV-cache paragraph; appendix "Ablation Study" for the tree variant): the same definition of y and LSE
+as the plain draft step, so the same oracle functions and the same tolerances; plus the re-layout itself (exact),
+agreement with the plain entry point, and the shapes the prepared path refuses."""
+import numpy as np
+import pytest
+
+from oracle import beagle_oracle as orc
+from paper_2505_24544_amd import binding as bx
+from paper_2505_24544_amd import synth
+from gpu_harness import run_draft_prepared, run_draft_tree, max_abs, rel_fro
+from test_gpu_tree_decode import _problem, _random_tree, BF16_OUT_ABS, BF16_OUT_FRO, LSE_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("M,n_true,T,H,G,D", [
+    (1, 1000, 0, 4, 4, 512),          # one query: the merge of the key ranges rides in the projection
+    (1, 130, 40, 4, 2, 512),
+    (1, 4096, 0, 32, 32, 4096),       # the decode configuration
+    (2, 900, 0, 4, 4, 512), (4, 1000, 17, 8, 8, 1024), (5, 640, 0, 4, 1, 512),
+    (8, 1000, 31, 4, 2, 512), (9, 1000, 0, 4, 4, 512), (10, 4096, 50, 32, 32, 4096), (16, 777, 33, 8, 8, 1024),
+    (8, 300, 0, 36, 36, 4608),        # K past 4096 in the 8-row layout; waves with four and with five macro-steps
+    (5, 300, 0, 72, 72, 512),         # the widest K: nine macro-steps per wave, activations parked in two chunks
+    (3, 500, 0, 9, 9, 1152),          # waves with one and with two macro-steps
+    (11, 500, 20, 5, 5, 640),         # K = 640: three waves without any
+    (7, 0, 90, 4, 4, 512),            # no true row at all
+])
+def test_prepared_step_matches_the_oracle(M, n_true, T, H, G, D):
+    rng = np.random.default_rng(300 + M + T)
+    cfg, inp, kc, vc = _problem("bf16", M, n_true + T, H, G, D, 128, 1800 + M)
+    if T:
+        parents = _random_tree(rng, T)
+        tm = orc.ancestor_mask(parents, [int(v) for v in rng.integers(0, T, M)])
+        if M > 1:
+            tm[M // 2] = rng.random(T) < 0.5
+    else:
+        tm = np.zeros((M, 0), bool)
+    ref = orc.draft_step_tree(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true=n_true, tree_mask=tm,
+                              n_q_heads=H, n_kv_heads=G)
+    y, lse, wo_t = run_draft_prepared(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true, tm)
+    assert np.array_equal(wo_t, inp["wo"].T)                   # the re-layout moves values, nothing else
+    fin = np.isfinite(ref["lse"])
+    assert np.array_equal(np.isneginf(lse), ~fin)
+    assert np.isfinite(y).all()
+    assert max_abs(y, ref["y"]) <= BF16_OUT_ABS and rel_fro(y, ref["y"]) <= BF16_OUT_FRO, rel_fro(y, ref["y"])
+    assert max_abs(lse[fin], ref["lse"][fin]) <= LSE_TOL
+    assert (y[~fin.any(axis=0)] == 0).all()
+    # and next to the plain entry point: same attention kernel, so the same LSE bit for bit above one query (the
+    # one-query merge sums in another order); y differs by the order of the projection's sums only
+    y0, l0 = run_draft_tree(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true, tm)
+    if M > 1:
+        assert np.array_equal(l0, lse)
+    else:
+        assert max_abs(l0[fin], lse[fin]) <= 1e-5
+    assert max_abs(y, y0) <= 2.0 ** -7 * max(1.0, float(np.abs(y0).max()))
+
+
+@pytest.mark.parametrize("M,H,D,dtype", [(17, 4, 512, "bf16"), (64, 4, 512, "bf16"), (12, 40, 5120, "bf16"), (9, 33, 512, "bf16"),
+                                         (4, 4, 520, "bf16"), (3, 4, 256, "f32")])
+def test_shapes_outside_the_prepared_path_are_refused(M, H, D, dtype):
+    d = 128 if dtype == "bf16" else 64
+    cfg, inp, kc, vc = _problem(dtype, M, 64, H, H, D, d, 1900)
+    st = run_draft_prepared(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], 64, np.zeros((M, 0), bool), check=False)
+    assert st == bx.BEAGLE_ERR_UNSUPPORTED
+
+
+def test_prepared_step_in_a_hip_graph_replays_to_the_eager_result():
+    import torch
+    import gpu_harness as gh
+    M, L, H, D = 10, 1500, 8, 1024
+    cfg = synth.CONFIGS["c4"].with_(seq_q=M, seq_kv=L, hidden=D, n_q_heads=H, n_kv_heads=H)
+    desc = gh.desc_of(cfg)
+    g = torch.Generator(device=gh.DEV).manual_seed(77)
+    R = lambda *s, std=1.0: (torch.randn(*s, device=gh.DEV, generator=g) * std).to(torch.bfloat16)
+    x, kc, vc, wq, wo = R(M, D), R(L, H, 128, std=1.28), R(L, H, 128, std=1.28), R(D, H * 128, std=0.02), R(H * 128, D, std=0.02)
+    wo_t = torch.empty(D, H * 128, dtype=torch.bfloat16, device=gh.DEV)
+    bx.beagle_xattn_prepare_wo(desc, wo, wo_t)
+    ws, ws_g = gh.workspace(desc, bx.BEAGLE_WS_DRAFT), gh.workspace(desc, bx.BEAGLE_WS_DRAFT)
+    y_e = torch.full((M, D), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    l_e = torch.full((H, M), float("nan"), dtype=torch.float32, device=gh.DEV)
+    bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_t, L, None, 0, y_e, l_e, ws)
+    torch.cuda.synchronize()
+    y_g, l_g = torch.empty_like(y_e), torch.empty_like(l_e)
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_t, L, None, 0, y_g, l_g, ws_g, torch.cuda.current_stream())
+    for rep in range(3):
+        y_g.fill_(float("nan")); l_g.fill_(float("nan"))
+        gr.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_g.view(torch.int16), y_e.view(torch.int16)) and torch.equal(l_g, l_e), rep
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_t, L, None, 0, y_e, l_e, ws)   # eager work in between
+        torch.cuda.synchronize()
