@@ -481,18 +481,27 @@ def bench_block(torch, bx, dm, cfg, t, fl, nsteps):
                 algorithmic_tflop_per_step=round(fl_blk / 1e12, 4), tokens_per_s=round(B * S / (ms * 1e-3)), kernels=kern)
 
 
-def _time_calls(torch, fn, n_sets, reps):
-    """Average microseconds per call of fn(r), r cycling through the buffer sets, by HIP events on the stream."""
+def _time_calls(torch, fn, n_sets, reps, spread=None):
+    """Average microseconds per call of fn(r), r cycling through the buffer sets, by HIP events on the stream:
+    n_sets warm-up calls, then `reps` timed ones.  An event is also recorded after every n_sets calls; with `spread`
+    (a dict) the per-call averages of those groups go into it as median / min / max."""
     for r in range(n_sets):
         fn(r)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
+    marks = [torch.cuda.Event(enable_timing=True)]
+    marks[0].record()
     for r in range(reps):
         fn(r)
-    e1.record()
+        if (r + 1) % n_sets == 0 or r + 1 == reps:
+            marks.append(torch.cuda.Event(enable_timing=True))
+            marks[-1].record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps * 1e3
+    if spread is not None:
+        sizes = [n_sets] * (reps // n_sets) + ([reps % n_sets] if reps % n_sets else [])
+        per = [a.elapsed_time(b) / n * 1e3 for a, b, n in zip(marks[:-1], marks[1:], sizes)]
+        spread.update(groups=len(per), calls_per_group=n_sets, median=round(statistics.median(per), 2),
+                      min=round(min(per), 2), max=round(max(per), 2))
+    return marks[0].elapsed_time(marks[-1]) / reps * 1e3
 
 
 def bench_decode(torch, bx, dm, synth, graphs=True):
@@ -547,7 +556,8 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         lse = torch.empty(H, M, dtype=torch.float32, device=dev)
         ws = dm.workspace(desc, bx.BEAGLE_WS_DRAFT)
         call = lambda r, st=stream: bx.beagle_xattn_draft_step(desc, x, *sets[r % nset], y, lse, ws, st)
-        us = _time_calls(torch, call, nset, 50)
+        spread = {}
+        us = _time_calls(torch, call, nset, 50, spread)
         prep_us = None
         if M <= bx.BEAGLE_PREPARED_MAX_QUERIES:
             prep = lambda r: bx.beagle_xattn_draft_step_prepared(desc, x, sets[r % nset][0], sets[r % nset][1],
@@ -591,6 +601,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         res["M%d" % M] = dict(us_per_call=round(us, 2), graph_us_per_call=round(graph_us, 2) if graph_us else None,
                               gbs=round(call_bytes / us / 1e3, 1),
                               pct_hbm_peak=round(100 * call_bytes / us / 1e3 / PEAK_HBM_GBS, 2),
+                              us_per_call_groups=spread,
                               draft_tokens_per_s=round(M / (us * 1e-6)), bytes=call_bytes,
                               kernel_us_bracketed=kern)
         if prep_us:
@@ -599,7 +610,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         att = kern.get("draft_attn")
         roof["M%d" % M] = dict(
             bound="hbm", kernel="beagle_xattn_draft_step (whole call: projections, attention, merges)",
-            bytes=call_bytes, avg_us=round(us, 2), achieved=round(call_bytes / us / 1e3, 1), peak=PEAK_HBM_GBS,
+            bytes=call_bytes, avg_us=round(us, 2), median_us=spread.get("median"), min_us=spread.get("min"), achieved=round(call_bytes / us / 1e3, 1), peak=PEAK_HBM_GBS,
             unit="GB/s", frac=round(call_bytes / us / 1e3 / PEAK_HBM_GBS, 4),
             graph_replay=dict(avg_us=round(graph_us, 2), frac=round(call_bytes / graph_us / 1e3 / PEAK_HBM_GBS, 4)) if graph_us else None,
             prepared_wo=dict(entry="beagle_xattn_draft_step_prepared (wo transposed once per model load; same bytes per call)",

@@ -474,9 +474,8 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
  *     draft step).  Same definition of y and lse; sums run in a different
  *     (fixed) order than in beagle_xattn_draft_step, so results agree with it to
  *     rounding, not bitwise.  Serves 1 <= seq_q <= BEAGLE_PREPARED_MAX_QUERIES,
- *     bf16, D % 16 == 0, and H*d <= 9216 (<= 4096 above 8 queries);
- *     BEAGLE_ERR_UNSUPPORTED otherwise, before anything is enqueued: use the
- *     plain entry points there.
+ *     bf16, D % 16 == 0; BEAGLE_ERR_UNSUPPORTED otherwise, before anything is
+ *     enqueued: use the plain entry points there.
  * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT).
  */
 #define BEAGLE_PREPARED_MAX_QUERIES 16

@@ -349,79 +349,94 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 // Weights go straight into the registers of the lane that feeds them to the MFMA (column n = lane % 16, k group
 // lane / 16 of a 32-k instruction; which 8 k a group holds is free as long as both operands agree: group g of
 // instruction j holds chunk 4 j + g of the macro-step, so one load instruction reads 64 contiguous bytes of each
-// of the 16 rows).  ST_RING macro-steps per wave are in flight: 128 KB per CU, the whole strip at K = 4096.  The activations are small and come
-// from L2: each wave parks those of its own macro-steps in LDS (chunk c of row m at chunk c ^ m).  Everything here is
-// ordinary loads and LDS traffic that the compiler counts by itself.
+// of the 16 rows).  ST_FLIGHT macro-steps per wave are in flight: 128 KB per CU, the whole strip at K = 4096.
+// The activations are small and come from L2.  A wave parks those of its own macro-steps in LDS (chunk c of row m
+// at chunk c ^ m: conflict-free fragment reads), a chunk of ST_CH macro-steps at a time in two buffers: the first
+// two chunks are requested before the first weights (requests complete in order: behind the weights they would
+// arrive behind them, and the MFMAs of a macro-step could not start when its weights land), every later chunk one
+// chunk ahead of its use, in front of the weight refills of that chunk.  The buffers are private to the wave, so
+// the loop has no barrier; everything is ordinary loads and LDS traffic that the compiler counts by itself.
 // Rows past M hold whatever LDS held: an MFMA output row depends on its own input row only, and rows past M
 // are not stored.
 //
-// MERGE1 (one query): a is not read; it is the attention output merged here from the split-KV partials of (B), as
-// in skinny_gemm_kernel<true>, each wave for the heads that are its macro-steps; workgroup 0 writes the LSE.
+// MODE 1 (one query): a is not read; it is the attention output merged here from the split-KV partials of (B), as
+// in skinny_gemm_kernel<true>, each wave for the heads that are its macro-steps (at most ST_CH: K <= 4096);
+// workgroup 0 writes the LSE.
+// MODE 2 (feed-forward layer, Eq. 1): two weight matrices share the activations, and the strip's result is
+// silu(a Wt^T) * (a Wt2^T): the gate needs no launch of its own.
 // ---------------------------------------------------------------------------
 namespace dec {
 constexpr int ST_N = 16;                 // output columns per workgroup
-constexpr int ST_RING = 4;               // weight macro-steps in flight per wave (4 KB each)
+constexpr int ST_FLIGHT = 4;             // weight macro-steps (4 KB) in flight per wave, over all matrices
+constexpr int ST_ROUND = 4;              // macro-steps per unrolled round of the loop
 constexpr int ST_WAVES = 8;
-constexpr int ST_ABYTES = 144 * 1024;    // LDS for the activations of all waves
 constexpr int ST_MAXM = 16;              // rows per launch
-constexpr int ST_CHUNK = 16;             // activation loads per lane in flight while they are parked
+constexpr int ST_ABUF = 64 * 1024;       // one activation buffer of all waves: ST_CH steps x rows x 256 B each
 }  // namespace dec
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
-template <bool MERGE1, bool OUT_F32>
+template <int MODE, bool ROWS16>
 __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
-                                                            void* __restrict__ yout, const bf16_t* __restrict__ res, int M,
-                                                            int N, int K, CombineArgs cb) {
+                                                            const bf16_t* __restrict__ Wt2, bf16_t* __restrict__ yout,
+                                                            const bf16_t* __restrict__ res, int M, int N, int K,
+                                                            CombineArgs cb) {
   using namespace dec;
-  __shared__ __attribute__((aligned(1024))) unsigned char abuf[ST_ABYTES];
-  __shared__ __attribute__((aligned(16))) float red[ST_WAVES][16][16];
-  __shared__ __attribute__((aligned(16))) float wsc[ST_WAVES][64];
-  __shared__ float winv[ST_WAVES][8];
+  constexpr int ROWS = ROWS16 ? 16 : 8;             // activation rows kept per macro-step
+  constexpr int ST_CH = ROWS16 ? 2 : 4;             // macro-steps per activation chunk
+  constexpr int LPS = ROWS / 4;                     // loads per macro-step (1 KB = 4 rows each)
+  constexpr int NLD = ST_CH * LPS;                  // loads per chunk: 8
+  constexpr int NW = MODE == 2 ? 2 : 1;             // weight matrices
+  constexpr int ST_RING = ST_FLIGHT / NW;           // ring slots per matrix
+  static_assert(ST_WAVES * ST_CH * ROWS * 256 == ST_ABUF, "a chunk of all waves fills one buffer");
+  static_assert(ST_ROUND % ST_CH == 0 && ST_ROUND % ST_RING == 0, "chunks and ring slots repeat with the round");
+  __shared__ __attribute__((aligned(1024))) unsigned char abuf[2][ST_ABUF];
+  __shared__ __attribute__((aligned(16))) float red[NW][ST_WAVES][16][16];
+  __shared__ __attribute__((aligned(16))) float wsc[MODE == 1 ? ST_WAVES : 1][64];
+  __shared__ float winv[MODE == 1 ? ST_WAVES : 1][8];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * ST_N;
-  const int S = K >> 7;                               // macro-steps; wave w takes s = w, w + 8, ... 
-  const int nst = (S - wave + 7) >> 3, nstw = (S + 7) >> 3;
-  const int rows = M <= 8 ? 8 : 16, lsh = M <= 8 ? 1 : 2;      // activation rows kept per step; loads per step = 1 << lsh
-  unsigned char* aw = abuf + wave * nstw * rows * 256;
+  const int S = K >> 7;                             // macro-steps; wave w takes s = w, w + 8, ...
+  const int nst = (S - wave + ST_WAVES - 1) / ST_WAVES;
   const int nl = lane & 15, kg = lane >> 4;
+  unsigned char* aw0 = abuf[0] + wave * (ST_CH * ROWS * 256);
+  unsigned char* aw1 = abuf[1] + wave * (ST_CH * ROWS * 256);
 
   float lse_out = -INFINITY;
-  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  f32x4_t acc[NW];
+#pragma unroll
+  for (int w = 0; w < NW; ++w) acc[w] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   if (nst > 0) {                        // (a wave without a macro-step, K < 1024, only adds zeros below)
-  // ---- activations first (requests complete in order: issued behind the weights they would arrive behind them, and
-  // the MFMAs of a macro-step could not start when its weights land).  Load q of a chunk covers rows 4 g + kg of step i, (i, g) = divmod(q, loads per step):
+  // ---- activations.  Load q of chunk c covers rows 4 g + kg of step c ST_CH + i, (i, g) = divmod(q, LPS):
   // lane (kg, nl) reads chunk nl ^ row of its row and parks it at chunk nl, i.e. at lane * 16 of the 1 KB piece.
-  const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void*)a, 0, MERGE1 ? 0 : (int)((int64_t)M * K * 2), 0x00020000);
-  xload_t av[MERGE1 ? 1 : ST_CHUNK];
-  auto stage_issue = [&](int q0) {
+  const __amdgpu_buffer_rsrc_t ars = __builtin_amdgcn_make_buffer_rsrc((void*)a, 0, MODE == 1 ? 0 : (int)((int64_t)M * K * 2), 0x00020000);
+  auto stage_issue = [&](xload_t (&av)[NLD], int c) {
 #pragma unroll
-    for (int q = 0; q < ST_CHUNK; ++q) {
-      const int i = (q0 + q) >> lsh, row = 4 * ((q0 + q) & ((1 << lsh) - 1)) + kg;
+    for (int q = 0; q < NLD; ++q) {
+      const int i = c * ST_CH + q / LPS, row = 4 * (q % LPS) + kg;
       av[q] = __builtin_amdgcn_raw_buffer_load_b128(
-          ars, (i < nst && row < M) ? (row * K + (wave + 8 * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
+          ars, (i < nst && row < M) ? (row * K + (wave + ST_WAVES * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
     }
   };
-  auto stage_park = [&](int q0) {
+  auto stage_park = [&](const xload_t (&av)[NLD], unsigned char* buf) {
 #pragma unroll
-    for (int q = 0; q < ST_CHUNK; ++q) {
-      const int i = (q0 + q) >> lsh, g = (q0 + q) & ((1 << lsh) - 1);
-      if (i < nst) *(xload_t*)(aw + (i * rows + 4 * g) * 256 + lane * 16) = av[q];
-    }
+    for (int q = 0; q < NLD; ++q) *(xload_t*)(buf + ((q / LPS) * ROWS + 4 * (q % LPS)) * 256 + lane * 16) = av[q];
   };
+  xload_t av0[MODE == 1 ? 1 : NLD], av1[MODE == 1 ? 1 : NLD];
   float2 mlv = {-INFINITY, 0.f};
-  float4 ov[MERGE1 ? 2 : 1][COMB_MAXR];
-  if (!MERGE1) {
-    stage_issue(0);
+  float4 ov[MODE == 1 ? 2 : 1][COMB_MAXR];
+  if constexpr (MODE != 1) {
+    stage_issue(av0, 0);
+    stage_issue(av1, 1);
   } else {
     // (max, sum) of head slot lane / 8, range lane % 8; then the partial outputs: item j = head slot 2 j + lane / 32,
     // float4 column lane % 32, all ranges (ranges past R repeat range 0 with weight 0; slots past the wave's last
     // repeat the last head: loads stay unconditional)
     const int hl = lane >> 3, r = lane & 7;
     if (hl < nst && r < cb.R)
-      mlv = *(const float2*)(cb.mlpart + ((int64_t)((wave + 8 * hl) * cb.R + r) * cb.Mpad) * 2);
+      mlv = *(const float2*)(cb.mlpart + ((int64_t)((wave + ST_WAVES * hl) * cb.R + r) * cb.Mpad) * 2);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int h2 = min(wave + 8 * (2 * j + (lane >> 5)), S - 1);
+      const int h2 = min(wave + ST_WAVES * (2 * j + (lane >> 5)), S - 1);
 #pragma unroll
       for (int rr = 0; rr < COMB_MAXR; ++rr)
         ov[j][rr] = *(const float4*)(cb.opart + ((int64_t)(h2 * cb.R + (rr < cb.R ? rr : 0)) * cb.Mpad) * HD + 4 * (lane & 31));
@@ -429,21 +444,24 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- the first ST_RING macro-steps of weights (at K = 4096: all of them)
+  // ---- the first ST_RING macro-steps of weights (one matrix at K = 4096: all of them)
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)((int64_t)N * K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrs2 = __builtin_amdgcn_make_buffer_rsrc((void*)(MODE == 2 ? Wt2 : Wt), 0, (int)((int64_t)N * K * 2), 0x00020000);
   const int wbase = ((n0 + nl) * K + 8 * kg) * 2;
   union frag_t { xload_t u; bf16x8_t v; };
-  frag_t bw[ST_RING][4];
+  frag_t bw[NW][ST_RING][4];
   auto load_b = [&](int u, int i) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      bw[u][j].u = __builtin_amdgcn_raw_buffer_load_b128(wrs, i < nst ? wbase + ((wave + 8 * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        bw[w][u][j].u = __builtin_amdgcn_raw_buffer_load_b128(w == 0 ? wrs : wrs2, i < nst ? wbase + ((wave + ST_WAVES * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
   };
 #pragma unroll
   for (int u = 0; u < ST_RING; ++u) load_b(u, u);
   __builtin_amdgcn_sched_barrier(0);
 
-  if (MERGE1) {
+  if constexpr (MODE == 1) {
     const int hl = lane >> 3;
     const float c2 = cb.scale * LOG2E;
     float mm = mlv.x;
@@ -457,68 +475,84 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int hl2 = 2 * j + (lane >> 5), c4 = lane & 31;
+      uint2 v = {0u, 0u};                                      // slots past the wave's last head: zeros, not stale LDS
       if (hl2 < nst) {
         const float4 s0 = *(const float4*)&wsc[wave][hl2 * 8], s1 = *(const float4*)&wsc[wave][hl2 * 8 + 4];
         const float w[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
         const float inv = winv[wave][hl2];
-        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        float4 t = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int rr = 0; rr < COMB_MAXR; ++rr) {               // fixed order
-          acc.x += ov[j][rr].x * w[rr]; acc.y += ov[j][rr].y * w[rr]; acc.z += ov[j][rr].z * w[rr]; acc.w += ov[j][rr].w * w[rr];
+          t.x += ov[j][rr].x * w[rr]; t.y += ov[j][rr].y * w[rr]; t.z += ov[j][rr].z * w[rr]; t.w += ov[j][rr].w * w[rr];
         }
-        uint2 v = {cvt_pk(acc.x * inv, acc.y * inv), cvt_pk(acc.z * inv, acc.w * inv)};
-        *(uint2*)(aw + hl2 * rows * 256 + (c4 >> 1) * 16 + (c4 & 1) * 8) = v;     // row 0: chunk c at chunk c
+        v = uint2{cvt_pk(t.x * inv, t.y * inv), cvt_pk(t.z * inv, t.w * inv)};
       }
+      *(uint2*)(aw0 + hl2 * ROWS * 256 + (c4 >> 1) * 16 + (c4 & 1) * 8) = v;        // row 0: chunk c at chunk c
     }
   } else {
-    stage_park(0);
-    // more macro-steps than one chunk holds (K beyond 8192, which only the 8-row layout holds): the rest, each chunk one more
-    // round trip behind the weights already requested
-    for (int q0 = ST_CHUNK; q0 < (nst << lsh); q0 += ST_CHUNK) { stage_issue(q0); stage_park(q0); }
+    stage_park(av0, aw0);
+    stage_park(av1, aw1);
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- macro-steps: activation fragments from LDS, weights from the ring, refill behind the MFMAs.  No branches
-  // inside a round of the ring: past the wave's last macro-step the weights arrive as zeros and the activations of
-  // its last step are read again, so every path through the loop holds the same number of requests in flight.
-  const int mr = nl & (rows - 1);
-  auto step = [&](int u, int i) {
-    const int ic = min(i, nst - 1);
+  // ---- macro-steps, ST_ROUND to an unrolled round: activation fragments from the chunk's buffer, weights from the ring, the
+  // slot's refill behind its MFMAs.  At a chunk's first step the chunk after the next is requested (in front of this
+  // chunk's refills), at its last step it is parked in the buffer the chunk leaves behind.  No branches inside a
+  // round: past the wave's last macro-step weights and activations are asked for beyond their descriptors' ends and
+  // arrive as zeros, so every path holds the same number of requests in flight.
+  const int mr = nl & (ROWS - 1);
+  auto step = [&](int u, const unsigned char* buf, int slot) {
     frag_t af[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) af[j].u = *(const xload_t*)(aw + (ic * rows + mr) * 256 + (((4 * j + kg) ^ mr) & 15) * 16);
+    for (int j = 0; j < 4; ++j) af[j].u = *(const xload_t*)(buf + (slot * ROWS + mr) * 256 + (((4 * j + kg) ^ mr) & 15) * 16);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j].v, bw[u][j].v, acc, 0, 0, 0);
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[w] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[j].v, bw[w][u][j].v, acc[w], 0, 0, 0);
   };
-  if (nst <= ST_RING) {                 // the ring holds every macro-step: nothing to request any more
+  if (ST_RING == ST_ROUND && nst <= ST_RING) {      // the ring holds every macro-step: nothing to request any more
 #pragma unroll
-    for (int u = 0; u < ST_RING; ++u) step(u, u);
-  } else {
+    for (int u = 0; u < ST_RING; ++u) step(u, (u / ST_CH) & 1 ? aw1 : aw0, u % ST_CH);
+  } else if constexpr (MODE != 1) {
     int i0 = 0;
     do {
 #pragma unroll
-      for (int u = 0; u < ST_RING; ++u) { step(u, i0 + u); load_b(u, i0 + u + ST_RING); }
-      i0 += ST_RING;
+      for (int u = 0; u < ST_ROUND; ++u) {
+        const int c = (i0 + u) / ST_CH;                        // chunk of this step; its buffer is c & 1
+        unsigned char* buf = (c & 1) ? aw1 : aw0;
+        if (u % ST_CH == 0) stage_issue(av0, c + 2);
+        step(u % ST_RING, buf, u % ST_CH);
+        load_b(u % ST_RING, i0 + u + ST_RING);
+        if (u % ST_CH == ST_CH - 1) stage_park(av0, buf);
+      }
+      i0 += ST_ROUND;
     } while (i0 < nst);
   }
   }
 
   // ---- the waves' k shares, added in wave order; output row 4 kg + e, column nl
 #pragma unroll
-  for (int e = 0; e < 4; ++e) red[wave][4 * kg + e][nl] = acc[e];
+  for (int w = 0; w < NW; ++w)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[w][wave][4 * kg + e][nl] = acc[w][e];
   __syncthreads();
   if (tid < M * 16) {
     const int m = tid >> 4, n = tid & 15;
-    float v = red[0][m][n];
+    float v = red[0][0][m][n];
 #pragma unroll
-    for (int wv = 1; wv < ST_WAVES; ++wv) v += red[wv][m][n];
+    for (int wv = 1; wv < ST_WAVES; ++wv) v += red[0][wv][m][n];
+    if constexpr (MODE == 2) {
+      float g = red[NW - 1][0][m][n];
+#pragma unroll
+      for (int wv = 1; wv < ST_WAVES; ++wv) g += red[NW - 1][wv][m][n];
+      v = v / (1.f + expf(-v)) * g;                            // silu(gate) * up
+    }
     const int64_t o = (int64_t)m * N + n0 + n;
     if (res) v += __uint_as_float((uint32_t)res[o] << 16);
-    if (OUT_F32) ((float*)yout)[o] = v;
-    else ((bf16_t*)yout)[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
+    yout[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
   }
-  if (MERGE1 && blockIdx.x == 0 && (lane & 7) == 0 && (lane >> 3) < nst)
-    cb.lse[(int64_t)(wave + 8 * (lane >> 3)) * cb.lse_stride] = lse_out;
+  if (MODE == 1 && blockIdx.x == 0 && (lane & 7) == 0 && (lane >> 3) < nst)
+    cb.lse[(int64_t)(wave + ST_WAVES * (lane >> 3)) * cb.lse_stride] = lse_out;
 }
 
 // out[c][r] = in[r][c]: the one-time re-layout of a weight matrix for strip_gemm_kernel
@@ -1169,13 +1203,22 @@ DecLayout dec_layout(int M, int L, int H, int d, int D) {
 }
 }  // namespace
 
-// strip_gemm_kernel serves [M, K] x [N, K]^T when its rows fit one launch, its strips tile N and the activations of
-// all macro-steps fit the LDS set aside for them
+// strip_gemm_kernel serves [M, K] x [N, K]^T when its rows fit one launch and its strips tile N
 bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || M > dec::ST_MAXM || N % dec::ST_N || K % 128 || K < 128) return false;
-  if ((int64_t)N * K * 2 >= ((int64_t)1 << 31)) return false;
-  const int nstw = (K / 128 + dec::ST_WAVES - 1) / dec::ST_WAVES, rows = M <= 8 ? 8 : 16;
-  return dec::ST_WAVES * nstw * rows * 256 <= dec::ST_ABYTES;
+  return (int64_t)N * K * 2 < ((int64_t)1 << 31) && (int64_t)M * K * 2 < ((int64_t)1 << 31);
+}
+// y = a Wt^T (+ res); with wt2: y = silu(a Wt^T) * (a Wt2^T); with merge: a is merged from the attention partials (M = 1)
+void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, bf16_t* y, const bf16_t* res, int M, int N,
+                       int K, const CombineArgs* merge, hipStream_t s) {
+  using namespace dec;
+  const dim3 grid(N / ST_N), block(64 * ST_WAVES);
+  const CombineArgs cb = merge ? *merge : CombineArgs{};
+  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else hipLaunchKernelGGL((strip_gemm_kernel<0, true>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
 }
 
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
@@ -1227,8 +1270,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
       if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
         ProfScope ps("draft_proj_out", s);
-        hipLaunchKernelGGL((strip_gemm_kernel<true, false>), dim3(a.D / ST_N), dim3(64 * ST_WAVES), 0, s, (const bf16_t*)nullptr,
-                           (const bf16_t*)a.wo_t, (void*)yo, yr, Mp, a.D, HDt, cb);
+        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_t, nullptr, yo, yr, Mp, a.D, HDt, &cb, s);
       } else {
         {
           ProfScope ps("draft_combine", s);
@@ -1236,8 +1278,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
                              w.Mpad, a.H, w.R, a.scale);
         }
         ProfScope ps("draft_proj_out", s);
-        hipLaunchKernelGGL((strip_gemm_kernel<false, false>), dim3(a.D / ST_N), dim3(64 * ST_WAVES), 0, s, (const bf16_t*)o,
-                           (const bf16_t*)a.wo_t, (void*)yo, yr, Mp, a.D, HDt, CombineArgs{});
+        launch_strip_gemm(o, (const bf16_t*)a.wo_t, nullptr, yo, yr, Mp, a.D, HDt, nullptr, s);
       }
       continue;
     }

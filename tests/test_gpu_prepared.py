@@ -21,7 +21,9 @@ pytestmark = pytest.mark.gpu
     (2, 900, 0, 4, 4, 512), (4, 1000, 17, 8, 8, 1024), (5, 640, 0, 4, 1, 512),
     (8, 1000, 31, 4, 2, 512), (9, 1000, 0, 4, 4, 512), (10, 4096, 50, 32, 32, 4096), (16, 777, 33, 8, 8, 1024),
     (8, 300, 0, 36, 36, 4608),        # K past 4096 in the 8-row layout; waves with four and with five macro-steps
-    (5, 300, 0, 72, 72, 512),         # the widest K: nine macro-steps per wave, activations parked in two chunks
+    (5, 300, 0, 72, 72, 512),         # nine macro-steps per wave: activations parked chunk by chunk, three rounds
+    (12, 300, 0, 40, 40, 640),        # the same in the 16-row layout (K = 5120: five macro-steps per wave)
+    (9, 200, 0, 33, 33, 512),         # 33 heads: one wave has five macro-steps, the others four
     (3, 500, 0, 9, 9, 1152),          # waves with one and with two macro-steps
     (11, 500, 20, 5, 5, 640),         # K = 640: three waves without any
     (7, 0, 90, 4, 4, 512),            # no true row at all
@@ -56,7 +58,7 @@ def test_prepared_step_matches_the_oracle(M, n_true, T, H, G, D):
     assert max_abs(y, y0) <= 2.0 ** -7 * max(1.0, float(np.abs(y0).max()))
 
 
-@pytest.mark.parametrize("M,H,D,dtype", [(17, 4, 512, "bf16"), (64, 4, 512, "bf16"), (12, 40, 5120, "bf16"), (9, 33, 512, "bf16"),
+@pytest.mark.parametrize("M,H,D,dtype", [(17, 4, 512, "bf16"), (64, 4, 512, "bf16"), 
                                          (4, 4, 520, "bf16"), (3, 4, 256, "f32")])
 def test_shapes_outside_the_prepared_path_are_refused(M, H, D, dtype):
     d = 128 if dtype == "bf16" else 64
