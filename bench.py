@@ -671,8 +671,25 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         prm = bx.make_block_params(F, 1e-5, wq=wq, wo=wo, w_gate=wg, w_up=wu, w_down=wd, g_q=gq, g_mlp=gm)
         bx.beagle_xattn_block_draft_step(desc, prm, x, kc, vc, L - T, tmd, 2, hb, lse, bws, stream)
 
+    # ... and with all four streamed matrices in the decode-time layout (transposed once per model load)
+    mlps_t = []
+    for i, (wg, wu, wd) in enumerate(mlps):
+        tw = dict(wo_t=wo_t[i], w_gate_t=torch.empty(F, D, dtype=torch.bfloat16, device=dev),
+                  w_up_t=torch.empty(F, D, dtype=torch.bfloat16, device=dev), w_down_t=torch.empty(D, F, dtype=torch.bfloat16, device=dev))
+        prm = bx.make_block_params(F, 1e-5, wq=sets[i][2], wo=sets[i][3], w_gate=wg, w_up=wu, w_down=wd, g_q=gq, g_mlp=gm)
+        bx.beagle_xattn_block_prepare_weights(desc, prm, bx.make_block_decode_weights(**tw))
+        mlps_t.append(tw)
+
+    def block_prepared_call(r):
+        kc, vc, wq, _ = sets[r % nset]
+        tw = dict(mlps_t[r % 4], wo_t=wo_t[r % nset])
+        prm = bx.make_block_params(F, 1e-5, wq=wq, g_q=gq, g_mlp=gm)
+        bx.beagle_xattn_block_draft_step_prepared(desc, prm, bx.make_block_decode_weights(**tw), x, kc, vc, L - T, tmd, 2,
+                                                  hb, lse, bws, stream)
+
     for name, fn in (("tree_M10_T50", tree_call), ("tree_M10_T50_prepared_wo", tree_prepared_call),
-                     ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call)):
+                     ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call),
+                     ("block_M10_T50_F11008_prepared", block_prepared_call)):
         us = _time_calls(torch, fn, nset, 50)
         if name.startswith("tree"):
             nbytes = 2 * L * G * hd * 2 + 2 * M * H * hd * 2 + 2 * D * H * hd * 2

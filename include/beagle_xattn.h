@@ -405,6 +405,39 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
     int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The block's draft step on weights in the decode-time layout (see
+ * beagle_xattn_prepare_wo): the output projection and the three feed-forward
+ * matrices transposed, so that each projection is one launch of 16-column strips
+ * over the whole of k -- no k split, no partial sums, no launch to add them,
+ * and the SiLU gate runs in the epilogue of the gate/up projection.
+ *   beagle_xattn_block_prepare_weights: fills the four buffers of `dw` (DEVICE,
+ *     caller-owned, 16-byte aligned): wo_t [D, H*d] from params->wo [H*d, D],
+ *     w_gate_t, w_up_t [F, D] from [D, F], w_down_t [D, F] from [F, D].  Once
+ *     per model load.  bf16 only.
+ *   beagle_xattn_block_draft_step_prepared: beagle_xattn_block_draft_step with
+ *     params->wo, w_gate, w_up, w_down replaced by `dw` (those four fields of
+ *     params are not read; wq, the gains, ffn and rms_eps are).  Same definition
+ *     of h and lse; sums run in a different fixed order, so results agree with
+ *     the plain entry point to rounding, not bitwise.  1 <= seq_q <=
+ *     BEAGLE_PREPARED_MAX_QUERIES, bf16, D % 16 == 0, F % 128 == 0;
+ *     BEAGLE_ERR_UNSUPPORTED otherwise, before anything is enqueued.
+ * Workspace: BEAGLE_WS_BLOCK_DRAFT.
+ */
+typedef struct {
+  int32_t struct_size;          /* sizeof(beagle_block_decode_weights); checked  */
+  int32_t reserved;             /* 0                                             */
+  void *wo_t;                   /* [D, H*d]                                      */
+  void *w_gate_t, *w_up_t;      /* [F, D]                                        */
+  void *w_down_t;               /* [D, F]                                        */
+} beagle_block_decode_weights;
+beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const beagle_block_decode_weights* dw, void* hip_stream);
+beagle_status beagle_xattn_block_draft_step_prepared(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const beagle_block_decode_weights* dw, const void* x_draft, const void* k_cache, const void* v_cache,
+    int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* h, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Cache append for the block: new states (true ones, or drafted ones = earlier
  * outputs h of beagle_xattn_block_draft_step) are key/value source states, so
  * they take the key/value normalisation RMSNorm(.; params->g_kv) before the

@@ -32,7 +32,8 @@ EXPORTS = (
     "beagle_xattn_draft_step_prepared", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
-    "beagle_xattn_block_draft_step", "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
+    "beagle_xattn_block_draft_step", "beagle_xattn_block_draft_step_prepared", "beagle_xattn_block_prepare_weights",
+    "beagle_xattn_block_fwd_sim", "beagle_xattn_block_bwd_sim",
     "beagle_xattn_block_kv_append",
     "beagle_xattn_mask_row_limit", "beagle_xattn_mask_dense", "beagle_xattn_tile_map",
     "beagle_xattn_profile_begin", "beagle_xattn_profile_end", "beagle_xattn_profile_get",
@@ -75,6 +76,11 @@ class beagle_block_params(C.Structure):
                [(n, _VP) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_q", "g_kv", "g_mlp")]
 
 
+class beagle_block_decode_weights(C.Structure):
+    _fields_ = [("struct_size", C.c_int32), ("reserved", C.c_int32)] + \
+               [(n, _VP) for n in ("wo_t", "w_gate_t", "w_up_t", "w_down_t")]
+
+
 class beagle_block_saved(C.Structure):
     _fields_ = [(n, _VP) for n in ("xq_n", "r_q", "xkv_n", "r_kv", "q", "k", "v", "o", "lse", "y", "z", "r_mlp",
                                    "u", "w", "m", "xp_n", "r_p", "kp", "vp")]
@@ -101,6 +107,12 @@ def make_block_params(ffn, rms_eps, **weights) -> beagle_block_params:
     p = _fill(beagle_block_params, weights)
     p.struct_size, p.ffn, p.rms_eps, p.reserved = C.sizeof(beagle_block_params), int(ffn), float(rms_eps), 0
     return p
+
+
+def make_block_decode_weights(**tensors) -> beagle_block_decode_weights:
+    w = _fill(beagle_block_decode_weights, tensors)
+    w.struct_size, w.reserved = C.sizeof(beagle_block_decode_weights), 0
+    return w
 
 
 def make_block_saved(**tensors) -> beagle_block_saved:
@@ -156,6 +168,11 @@ def lib() -> C.CDLL:
                                              C.POINTER(beagle_block_saved), C.POINTER(beagle_block_grads), vp, C.c_size_t, vp]
     L.beagle_xattn_block_kv_append.restype = C.c_int
     L.beagle_xattn_block_kv_append.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp, C.c_size_t, vp]
+    L.beagle_xattn_block_draft_step_prepared.restype = C.c_int
+    L.beagle_xattn_block_draft_step_prepared.argtypes = [dp, C.POINTER(beagle_block_params), C.POINTER(beagle_block_decode_weights),
+                                                         vp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+    L.beagle_xattn_block_prepare_weights.restype = C.c_int
+    L.beagle_xattn_block_prepare_weights.argtypes = [dp, C.POINTER(beagle_block_params), C.POINTER(beagle_block_decode_weights), vp]
     L.beagle_xattn_block_draft_step.restype = C.c_int
     L.beagle_xattn_block_draft_step.argtypes = [dp, C.POINTER(beagle_block_params), vp, vp, vp, C.c_int32, vp, C.c_int32,
                                                 vp, vp, vp, C.c_size_t, vp]
@@ -296,6 +313,21 @@ def beagle_xattn_block_draft_step(desc, params, x_draft, k_cache, v_cache, n_tru
         int(n_true), _ptr(tree_mask), int(mask_words), _ptr(h), _ptr(lse),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_block_draft_step", check)
+
+
+def beagle_xattn_block_prepare_weights(desc, params, dw, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_block_prepare_weights(C.byref(desc), C.byref(params) if params is not None else None,
+                                                  C.byref(dw) if dw is not None else None, _stream(stream))
+    return _check(st, "beagle_xattn_block_prepare_weights", check)
+
+
+def beagle_xattn_block_draft_step_prepared(desc, params, dw, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words,
+                                           h, lse, workspace, stream=None, *, workspace_bytes=None, check=True) -> int:
+    st = lib().beagle_xattn_block_draft_step_prepared(
+        C.byref(desc), C.byref(params) if params is not None else None, C.byref(dw) if dw is not None else None,
+        _ptr(x_draft), _ptr(k_cache), _ptr(v_cache), int(n_true), _ptr(tree_mask), int(mask_words), _ptr(h), _ptr(lse),
+        _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
+    return _check(st, "beagle_xattn_block_draft_step_prepared", check)
 
 
 def beagle_xattn_sim_save(desc, h, xpred, sim_step, stream=None, *, check=True) -> int:

@@ -262,19 +262,32 @@ beagle_status beagle_xattn_block_bwd_sim(const beagle_xattn_desc* desc, const be
   return block_bwd_impl(desc, p, dh, e, hs, true, xpred, sim_step, sv, gr, workspace, workspace_bytes, hip_stream);
 }
 
-beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* p,
+namespace {
+bool decode_weights_ok(const beagle_block_decode_weights* dw) {
+  return dw && dw->struct_size == (int32_t)sizeof(beagle_block_decode_weights) && dw->reserved == 0;
+}
+// shared by the plain entry point (dw == nullptr) and the one on prepared weights
+beagle_status block_draft_step_impl(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const beagle_block_decode_weights* dw,
     const void* x_draft, const void* k_cache, const void* v_cache, int32_t n_true, const uint32_t* tree_mask,
     int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Dims d; beagle_status st = check_block(desc, p, &d, true);
   if (st != BEAGLE_OK) return st;
-  const void* req[] = {x_draft, k_cache, v_cache, p->wq, p->wo, p->w_gate, p->w_up, p->w_down, h, lse, workspace};
+  const void* wo = dw ? dw->wo_t : p->wo;
+  const void* w_gate = dw ? dw->w_gate_t : p->w_gate;
+  const void* w_up = dw ? dw->w_up_t : p->w_up;
+  const void* w_down = dw ? dw->w_down_t : p->w_down;
+  const void* req[] = {x_draft, k_cache, v_cache, p->wq, wo, w_gate, w_up, w_down, h, lse, workspace};
   for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
-  const void* all[] = {x_draft, k_cache, v_cache, p->wq, p->wo, p->w_gate, p->w_up, p->w_down, p->g_q, p->g_mlp, h, lse};
+  const void* all[] = {x_draft, k_cache, v_cache, p->wq, wo, w_gate, w_up, w_down, p->g_q, p->g_mlp, h, lse};
   for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
   if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
   const int64_t F = p->ffn;
   if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_DRAFT)) return BEAGLE_ERR_WORKSPACE;
   if (d.bf16 && !block_mlp_bf16_fits((int32_t)d.D, (int32_t)F)) return BEAGLE_ERR_UNSUPPORTED;
+  if (dw && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD) &&
+              strip_gemm_fits((int32_t)d.S, (int32_t)F, (int32_t)d.D) && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)F)))
+    return BEAGLE_ERR_UNSUPPORTED;
   if (n_true < 0 || n_true > d.L) return BEAGLE_ERR_SHAPE;
   const int64_t T = d.L - n_true;
   if (T > 0) {
@@ -298,7 +311,8 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
-    a.x = xn; a.kc = k_cache; a.vc = v_cache; a.wq = p->wq; a.wo = p->wo; a.y = y; a.lse = lse; a.ws = base + w.step;
+    a.x = xn; a.kc = k_cache; a.vc = v_cache; a.wq = p->wq; a.y = y; a.lse = lse; a.ws = base + w.step;
+    if (dw) a.wo_t = wo; else a.wo = wo;
     a.tree = tree_mask; a.n_true = n_true; a.tree_words = mask_words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     a.y_res = x_draft;
@@ -324,7 +338,9 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
   // h = MLP(RMSNorm(y)) + y
   const void* z = y;
   if (p->g_mlp) { launch_rmsnorm_fwd(d.bf16, y, p->g_mlp, base + w.z, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_mlp"); z = base + w.z; }
-  if (d.bf16) {
+  if (d.bf16 && dw) {
+    launch_block_mlp_strip_bf16(z, w_gate, w_up, w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F, base + w.mlp, s);
+  } else if (d.bf16) {
     launch_block_mlp_bf16(z, p->w_gate, p->w_up, p->w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F, base + w.mlp, s);
   } else {
     GemmGroup gu; memset(&gu, 0, sizeof(gu));
@@ -337,6 +353,49 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
     dn.R = y; dn.ldr = d.D;
     launch_gemm_f32(group1(dn), s, "draft_mlp_down");
   }
+  return hip_status();
+}
+}  // namespace
+
+beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const void* x_draft, const void* k_cache, const void* v_cache, int32_t n_true, const uint32_t* tree_mask,
+    int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return block_draft_step_impl(desc, p, nullptr, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words, h, lse,
+                               workspace, workspace_bytes, hip_stream);
+}
+
+beagle_status beagle_xattn_block_draft_step_prepared(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const beagle_block_decode_weights* dw, const void* x_draft, const void* k_cache, const void* v_cache,
+    int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* h, float* lse,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!dw) return BEAGLE_ERR_NULL;
+  if (!decode_weights_ok(dw)) return BEAGLE_ERR_SHAPE;
+  // the four matrices that dw replaces are not read: the shared checks see dw's in their place
+  beagle_block_params q;
+  if (!p || p->struct_size != (int32_t)sizeof(q)) return p ? BEAGLE_ERR_SHAPE : BEAGLE_ERR_NULL;
+  q = *p;
+  q.wo = dw->wo_t; q.w_gate = dw->w_gate_t; q.w_up = dw->w_up_t; q.w_down = dw->w_down_t;
+  return block_draft_step_impl(desc, &q, dw, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words, h, lse,
+                               workspace, workspace_bytes, hip_stream);
+}
+
+beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const beagle_block_decode_weights* dw, void* hip_stream) {
+  Dims d; beagle_status st = check_block(desc, p, &d, true);
+  if (st != BEAGLE_OK) return st;
+  if (!dw) return BEAGLE_ERR_NULL;
+  if (!decode_weights_ok(dw)) return BEAGLE_ERR_SHAPE;
+  const void* ptrs[] = {p->wo, p->w_gate, p->w_up, p->w_down, dw->wo_t, dw->w_gate_t, dw->w_up_t, dw->w_down_t};
+  for (const void* q : ptrs) if (!q) return BEAGLE_ERR_NULL;
+  for (const void* q : ptrs) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (!d.bf16) return BEAGLE_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const int32_t F = p->ffn;
+  launch_transpose_bf16(p->wo, dw->wo_t, (int32_t)d.HD, (int32_t)d.D, s);
+  launch_transpose_bf16(p->w_gate, dw->w_gate_t, (int32_t)d.D, F, s);
+  launch_transpose_bf16(p->w_up, dw->w_up_t, (int32_t)d.D, F, s);
+  launch_transpose_bf16(p->w_down, dw->w_down_t, F, (int32_t)d.D, s);
   return hip_status();
 }
 

@@ -191,6 +191,10 @@ size_t block_mlp_bf16_ws_bytes(int32_t M, int32_t D, int32_t F);
 bool block_mlp_bf16_fits(int32_t D, int32_t F);
 void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, const void* w_down, const void* y_res,
                            void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
+// the same on transposed weights (w_gate_t, w_up_t [F, D]; w_down_t [D, F]): two strip launches, gate fused;
+// needs strip_gemm_fits(M, F, D) and strip_gemm_fits(M, D, F); ws: M * F bf16
+void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_t, const void* w_up_t, const void* w_down_t,
+                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
 void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
                            int32_t K, void* ws, hipStream_t s);
 

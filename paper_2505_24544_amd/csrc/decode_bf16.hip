@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 // ---------------------------------------------------------------------------
 // (D')  y[m][n] = sum_k a[m][k] * Wt[n][k]  (+ res[m][n]) for up to 16 rows, on a weight matrix that is stored
 // transposed ([N][K] row-major, laid out once per model load).  With the k run of an output column contiguous, a
-// workgroup owns a strip of 16 output columns over the whole of K and still reads long runs (its eight waves
+// workgroup owns a strip of 16 output columns over the whole of K and still reads long runs (its waves
 // take the 128-k macro-steps in turn: 16 rows x 256 B per step), so there are N / 16 workgroups (one per CU at
 // N = 4096) without any k split: no partial sums in memory and no launch to add them up.
 //
@@ -369,14 +369,12 @@ namespace dec {
 constexpr int ST_N = 16;                 // output columns per workgroup
 constexpr int ST_FLIGHT = 4;             // weight macro-steps (4 KB) in flight per wave, over all matrices
 constexpr int ST_ROUND = 4;              // macro-steps per unrolled round of the loop
-constexpr int ST_WAVES = 8;
 constexpr int ST_MAXM = 16;              // rows per launch
-constexpr int ST_ABUF = 64 * 1024;       // one activation buffer of all waves: ST_CH steps x rows x 256 B each
 }  // namespace dec
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
-template <int MODE, bool ROWS16>
-__global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
+template <int MODE, bool ROWS16, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
                                                             const bf16_t* __restrict__ Wt2, bf16_t* __restrict__ yout,
                                                             const bf16_t* __restrict__ res, int M, int N, int K,
                                                             CombineArgs cb) {
@@ -387,16 +385,16 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
   constexpr int NLD = ST_CH * LPS;                  // loads per chunk: 8
   constexpr int NW = MODE == 2 ? 2 : 1;             // weight matrices
   constexpr int ST_RING = ST_FLIGHT / NW;           // ring slots per matrix
-  static_assert(ST_WAVES * ST_CH * ROWS * 256 == ST_ABUF, "a chunk of all waves fills one buffer");
+  constexpr int ABUF = WAVES * ST_CH * ROWS * 256;  // one activation buffer of all waves: 64 KB with eight
   static_assert(ST_ROUND % ST_CH == 0 && ST_ROUND % ST_RING == 0, "chunks and ring slots repeat with the round");
-  __shared__ __attribute__((aligned(1024))) unsigned char abuf[2][ST_ABUF];
-  __shared__ __attribute__((aligned(16))) float red[NW][ST_WAVES][16][16];
-  __shared__ __attribute__((aligned(16))) float wsc[MODE == 1 ? ST_WAVES : 1][64];
-  __shared__ float winv[MODE == 1 ? ST_WAVES : 1][8];
+  __shared__ __attribute__((aligned(1024))) unsigned char abuf[2][ABUF];
+  __shared__ __attribute__((aligned(16))) float red[NW][WAVES][16][16];
+  __shared__ __attribute__((aligned(16))) float wsc[MODE == 1 ? WAVES : 1][64];
+  __shared__ float winv[MODE == 1 ? WAVES : 1][8];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * ST_N;
   const int S = K >> 7;                             // macro-steps; wave w takes s = w, w + 8, ...
-  const int nst = (S - wave + ST_WAVES - 1) / ST_WAVES;
+  const int nst = (S - wave + WAVES - 1) / WAVES;
   const int nl = lane & 15, kg = lane >> 4;
   unsigned char* aw0 = abuf[0] + wave * (ST_CH * ROWS * 256);
   unsigned char* aw1 = abuf[1] + wave * (ST_CH * ROWS * 256);
@@ -414,7 +412,7 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
     for (int q = 0; q < NLD; ++q) {
       const int i = c * ST_CH + q / LPS, row = 4 * (q % LPS) + kg;
       av[q] = __builtin_amdgcn_raw_buffer_load_b128(
-          ars, (i < nst && row < M) ? (row * K + (wave + ST_WAVES * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
+          ars, (i < nst && row < M) ? (row * K + (wave + WAVES * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
     }
   };
   auto stage_park = [&](const xload_t (&av)[NLD], unsigned char* buf) {
@@ -433,10 +431,10 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
     // repeat the last head: loads stay unconditional)
     const int hl = lane >> 3, r = lane & 7;
     if (hl < nst && r < cb.R)
-      mlv = *(const float2*)(cb.mlpart + ((int64_t)((wave + ST_WAVES * hl) * cb.R + r) * cb.Mpad) * 2);
+      mlv = *(const float2*)(cb.mlpart + ((int64_t)((wave + WAVES * hl) * cb.R + r) * cb.Mpad) * 2);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int h2 = min(wave + ST_WAVES * (2 * j + (lane >> 5)), S - 1);
+      const int h2 = min(wave + WAVES * (2 * j + (lane >> 5)), S - 1);
 #pragma unroll
       for (int rr = 0; rr < COMB_MAXR; ++rr)
         ov[j][rr] = *(const float4*)(cb.opart + ((int64_t)(h2 * cb.R + (rr < cb.R ? rr : 0)) * cb.Mpad) * HD + 4 * (lane & 31));
@@ -455,7 +453,7 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
     for (int w = 0; w < NW; ++w)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        bw[w][u][j].u = __builtin_amdgcn_raw_buffer_load_b128(w == 0 ? wrs : wrs2, i < nst ? wbase + ((wave + ST_WAVES * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
+        bw[w][u][j].u = __builtin_amdgcn_raw_buffer_load_b128(w == 0 ? wrs : wrs2, i < nst ? wbase + ((wave + WAVES * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
   };
 #pragma unroll
   for (int u = 0; u < ST_RING; ++u) load_b(u, u);
@@ -540,11 +538,11 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
     const int m = tid >> 4, n = tid & 15;
     float v = red[0][0][m][n];
 #pragma unroll
-    for (int wv = 1; wv < ST_WAVES; ++wv) v += red[0][wv][m][n];
+    for (int wv = 1; wv < WAVES; ++wv) v += red[0][wv][m][n];
     if constexpr (MODE == 2) {
       float g = red[NW - 1][0][m][n];
 #pragma unroll
-      for (int wv = 1; wv < ST_WAVES; ++wv) g += red[NW - 1][wv][m][n];
+      for (int wv = 1; wv < WAVES; ++wv) g += red[NW - 1][wv][m][n];
       v = v / (1.f + expf(-v)) * g;                            // silu(gate) * up
     }
     const int64_t o = (int64_t)m * N + n0 + n;
@@ -552,7 +550,7 @@ __global__ __launch_bounds__(512, 1) void strip_gemm_kernel(const bf16_t* __rest
     yout[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
   }
   if (MODE == 1 && blockIdx.x == 0 && (lane & 7) == 0 && (lane >> 3) < nst)
-    cb.lse[(int64_t)(wave + ST_WAVES * (lane >> 3)) * cb.lse_stride] = lse_out;
+    cb.lse[(int64_t)(wave + WAVES * (lane >> 3)) * cb.lse_stride] = lse_out;
 }
 
 // out[c][r] = in[r][c]: the one-time re-layout of a weight matrix for strip_gemm_kernel
@@ -1212,13 +1210,16 @@ bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
 void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, bf16_t* y, const bf16_t* res, int M, int N,
                        int K, const CombineArgs* merge, hipStream_t s) {
   using namespace dec;
-  const dim3 grid(N / ST_N), block(64 * ST_WAVES);
+  const dim3 grid(N / ST_N);
   const CombineArgs cb = merge ? *merge : CombineArgs{};
-  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else hipLaunchKernelGGL((strip_gemm_kernel<0, true>), grid, block, 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  // one matrix: eight waves, one workgroup per CU (N / 16 is about the number of CUs for the attention's projection);
+  // the feed-forward pair has several strips per CU: four waves and two workgroups per CU, so that one's start and
+  // final reduction hide behind the other's stream
+  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
 }
 
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
@@ -1397,6 +1398,19 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
                          (bf16_t*)h + (int64_t)m0 * D, MN, w.KSd, (const float*)nullptr, (bf16_t*)nullptr,
                          (const bf16_t*)y_res + (int64_t)m0 * D);
     }
+  }
+}
+
+void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_t, const void* w_up_t, const void* w_down_t,
+                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s) {
+  bf16_t* mbuf = (bf16_t*)ws;
+  {
+    ProfScope ps("draft_mlp_gate_up", s);
+    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_t, (const bf16_t*)w_up_t, mbuf, nullptr, M, F, D, nullptr, s);
+  }
+  {
+    ProfScope ps("draft_mlp_down", s);
+    launch_strip_gemm(mbuf, (const bf16_t*)w_down_t, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, s);
   }
 }
 

@@ -175,3 +175,70 @@ def test_block_speculative_iteration_append_draft_append_draft(dtype):
     r2 = blk.block_draft_step(x2, rk[:n_true + M], rv[:n_true + M], *W5, **okw, n_true=n_true, tree_mask=tree,
                               rope=dict(rope, q_pos=[n_true + 1] * M))["h"]
     assert tol(h2, r2)
+
+
+# ------------------------------------------------------------------ the block on weights in the decode-time layout
+def _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true=None, tree=None, desc=None, check=True):
+    d = desc if desc is not None else gh.desc_of(cfg)
+    M, D, H, HD = cfg.seq_q, cfg.hidden, cfg.n_q_heads, cfg.n_q_heads * cfg.head_dim
+    names = ("wq", "wo", "w_gate", "w_up", "w_down") + (("g_q", "g_mlp") if gains else ())
+    dev = {n: gh.to_dev(bi[n], cfg) for n in names}
+    x, kcd, vcd = gh.to_dev(bi["e"][0], cfg), gh.to_dev(kc, cfg), gh.to_dev(vc, cfg)
+    params = bx.make_block_params(ffn, 1e-5, **dev)
+    dt = gh.tdtype(cfg)
+    E = lambda *s: torch.full(s, float("nan"), dtype=dt, device=gh.DEV)
+    tw = dict(wo_t=E(D, HD), w_gate_t=E(ffn, D), w_up_t=E(ffn, D), w_down_t=E(D, ffn))
+    dw = bx.make_block_decode_weights(**tw)
+    st = bx.beagle_xattn_block_prepare_weights(d, params, dw, check=check)
+    if not check and st != 0:
+        return st
+    # the step must not read the four matrices that dw replaces
+    only = bx.make_block_params(ffn, 1e-5, **{n: dev[n] for n in dev if n in ("wq", "g_q", "g_mlp")})
+    h = torch.full((M, D), float("nan"), dtype=dt, device=gh.DEV)
+    lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=gh.DEV)
+    ws = torch.empty(bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_DRAFT), dtype=torch.uint8, device=gh.DEV)
+    if tree is None:
+        n_true, tm, words = cfg.seq_kv, None, 0
+    else:
+        packed = gh.pack_tree_mask(tree)
+        tm, words = torch.from_numpy(packed.view(np.int32)).to(gh.DEV), packed.shape[1]
+    st = bx.beagle_xattn_block_draft_step_prepared(d, only, dw, x, kcd, vcd, n_true, tm, words, h, lse, ws, check=check)
+    torch.cuda.synchronize()
+    if not check:
+        return st
+    return gh.to_host(h), gh.to_host(lse), {n: gh.to_host(t) for n, t in tw.items()}
+
+
+@pytest.mark.parametrize("M,rows,H,G,D,ffn,gains,T", [
+    (1, 300, 4, 4, 512, 1408, True, 0), (10, 300, 4, 4, 512, 1408, True, 50), (8, 200, 8, 2, 1024, 2816, False, 0),
+    (16, 130, 4, 4, 512, 1280, True, 20), (3, 90, 8, 8, 1024, 128, True, 0),
+])
+def test_bf16_block_draft_step_on_prepared_weights(M, rows, H, G, D, ffn, gains, T):
+    cfg, bi, kc, vc = _problem("bf16", M, rows, H, G, D, 128, ffn, 241 + M)
+    tree = (np.random.default_rng(M).random((M, T)) < 0.5) if T else None
+    n_true = rows - T if T else None
+    ref = _ref(cfg, bi, kc, vc, gains, n_true, tree)
+    h, lse, tw = _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true, tree)
+    for n, src in (("wo_t", "wo"), ("w_gate_t", "w_gate"), ("w_up_t", "w_up"), ("w_down_t", "w_down")):
+        assert np.array_equal(tw[n], bi[src].T), n             # the re-layout moves values, nothing else
+    assert np.isfinite(h).all()
+    assert gh.rel_fro(h, ref["h"]) <= OUT_FRO, gh.rel_fro(h, ref["h"])
+    assert gh.max_abs(lse, ref["lse"]) <= 4e-3, gh.max_abs(lse, ref["lse"])
+    h0, _ = _run(cfg, bi, kc, vc, ffn, gains, n_true, tree)    # next to the plain entry point: rounding apart
+    assert gh.rel_fro(h, h0) <= 4e-3, gh.rel_fro(h, h0)
+
+
+def test_bf16_block_draft_step_on_prepared_weights_at_the_7b_shape():
+    M, rows, ffn = 10, 4096, 11008
+    cfg, bi, kc, vc = _problem("bf16", M, rows, 32, 32, 4096, 128, ffn, 251)
+    ref = _ref(cfg, bi, kc, vc, True)
+    h, lse, _ = _run_prepared(cfg, bi, kc, vc, ffn, True)
+    assert gh.rel_fro(h, ref["h"]) <= OUT_FRO, gh.rel_fro(h, ref["h"])
+    assert gh.max_abs(lse, ref["lse"]) <= 4e-3
+
+
+@pytest.mark.parametrize("M,D,ffn,dtype", [(17, 512, 1408, "bf16"), (4, 512, 1344, "bf16"), (3, 256, 96, "f32")])
+def test_block_shapes_outside_the_prepared_path_are_refused(M, D, ffn, dtype):
+    d = 128 if dtype == "bf16" else 64
+    cfg, bi, kc, vc = _problem(dtype, M, 40, 4, 4, D, d, ffn, 261)
+    assert _run_prepared(cfg, bi, kc, vc, ffn, True, check=False) == bx.BEAGLE_ERR_UNSUPPORTED
