@@ -78,7 +78,7 @@ class beagle_block_params(C.Structure):
 
 class beagle_block_decode_weights(C.Structure):
     _fields_ = [("struct_size", C.c_int32), ("reserved", C.c_int32)] + \
-               [(n, _VP) for n in ("wo_t", "w_gate_t", "w_up_t", "w_down_t")]
+               [(n, _VP) for n in ("wo_pk", "w_gate_pk", "w_up_pk", "w_down_pk")]
 
 
 class beagle_block_saved(C.Structure):
@@ -344,15 +344,15 @@ def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true
     return _check(st, "beagle_xattn_draft_step_tree", check)
 
 
-def beagle_xattn_prepare_wo(desc, wo, wo_t, stream=None, *, check=True) -> int:
-    st = lib().beagle_xattn_prepare_wo(C.byref(desc), _ptr(wo), _ptr(wo_t), _stream(stream))
+def beagle_xattn_prepare_wo(desc, wo, wo_pk, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_prepare_wo(C.byref(desc), _ptr(wo), _ptr(wo_pk), _stream(stream))
     return _check(st, "beagle_xattn_prepare_wo", check)
 
 
-def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq, wo_t, n_true, tree_mask, mask_words, y, lse,
+def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq, wo_pk, n_true, tree_mask, mask_words, y, lse,
                                      workspace, stream=None, *, workspace_bytes=None, check=True) -> int:
     st = lib().beagle_xattn_draft_step_prepared(
-        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo_t)), int(n_true), _ptr(tree_mask),
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo_pk)), int(n_true), _ptr(tree_mask),
         int(mask_words), _ptr(y), _ptr(lse),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_draft_step_prepared", check)

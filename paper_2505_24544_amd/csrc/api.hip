@@ -663,10 +663,10 @@ namespace {
 beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
     int32_t n_true, const uint32_t* tree, int32_t words,
-    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, bool wo_transposed = false) {
+    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, bool wo_packed = false) {
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
-  if (wo_transposed && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD))) return BEAGLE_ERR_UNSUPPORTED;
+  if (wo_packed && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD))) return BEAGLE_ERR_UNSUPPORTED;
   const void* ptrs[] = {x_draft, k_cache, v_cache, wq, wo, y, lse, workspace};
   for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
@@ -689,7 +689,7 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
     a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.wq = wq; a.y = y; a.lse = lse; a.ws = workspace;
-    if (wo_transposed) a.wo_t = wo; else a.wo = wo;
+    if (wo_packed) a.wo_pk = wo; else a.wo = wo;
     a.tree = tree; a.n_true = n_true; a.tree_words = words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     launch_decode_bf16(a, s);
@@ -764,22 +764,22 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
                          workspace_bytes, hip_stream);
 }
 
-beagle_status beagle_xattn_prepare_wo(const beagle_xattn_desc* desc, const void* wo, void* wo_t, void* hip_stream) {
+beagle_status beagle_xattn_prepare_wo(const beagle_xattn_desc* desc, const void* wo, void* wo_pk, void* hip_stream) {
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
-  if (!wo || !wo_t) return BEAGLE_ERR_NULL;
-  if (!aligned16(wo) || !aligned16(wo_t)) return BEAGLE_ERR_ALIGN;
-  if (!d.bf16) return BEAGLE_ERR_UNSUPPORTED;
+  if (!wo || !wo_pk) return BEAGLE_ERR_NULL;
+  if (!aligned16(wo) || !aligned16(wo_pk)) return BEAGLE_ERR_ALIGN;
+  if (!d.bf16 || d.D % 16 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
   (void)hipGetLastError();
-  launch_transpose_bf16(wo, wo_t, (int32_t)d.HD, (int32_t)d.D, (hipStream_t)hip_stream);
+  launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, (hipStream_t)hip_stream);
   return hip_status();
 }
 
 beagle_status beagle_xattn_draft_step_prepared(const beagle_xattn_desc* desc,
-    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo_t,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo_pk,
     int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo_t, n_true, tree_mask, mask_words, y, lse, workspace,
+  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo_pk, n_true, tree_mask, mask_words, y, lse, workspace,
                          workspace_bytes, hip_stream, true);
 }
 

@@ -176,10 +176,11 @@ struct DecodeArgs {
   // rotary embedding of the queries (rope != 0): positions rope_pos[m] (device) or all at L
   int32_t rope; float rope_base; const int32_t* rope_pos;
   const void* y_res;   // optional residual added to y (storage type, [M,D])
-  const void* wo_t;    // optional: wo transposed ([D, H*d]); then wo is not read (needs strip_gemm_fits(M, D, H*d))
+  const void* wo_pk;   // optional: wo packed for strip_gemm_kernel; then wo is not read (needs strip_gemm_fits(M, D, H*d))
 };
 bool strip_gemm_fits(int32_t M, int32_t N, int32_t K);
-void launch_transpose_bf16(const void* in, void* out, int32_t R, int32_t C, hipStream_t s);
+// W [K][N] row-major -> the packed layout that strip_gemm_kernel streams (K % 128 == 0, N % 16 == 0)
+void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, hipStream_t s);
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
 void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s);
@@ -191,9 +192,9 @@ size_t block_mlp_bf16_ws_bytes(int32_t M, int32_t D, int32_t F);
 bool block_mlp_bf16_fits(int32_t D, int32_t F);
 void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, const void* w_down, const void* y_res,
                            void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
-// the same on transposed weights (w_gate_t, w_up_t [F, D]; w_down_t [D, F]): two strip launches, gate fused;
+// the same on packed weights: two strip launches, gate fused;
 // needs strip_gemm_fits(M, F, D) and strip_gemm_fits(M, D, F); ws: M * F bf16
-void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_t, const void* w_up_t, const void* w_down_t,
+void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
                                  const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
 void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
                            int32_t K, void* ws, hipStream_t s);

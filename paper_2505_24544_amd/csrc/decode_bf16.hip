@@ -340,16 +340,18 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------
-// (D')  y[m][n] = sum_k a[m][k] * Wt[n][k]  (+ res[m][n]) for up to 16 rows, on a weight matrix that is stored
-// transposed ([N][K] row-major, laid out once per model load).  With the k run of an output column contiguous, a
-// workgroup owns a strip of 16 output columns over the whole of K and still reads long runs (its waves
-// take the 128-k macro-steps in turn: 16 rows x 256 B per step), so there are N / 16 workgroups (one per CU at
-// N = 4096) without any k split: no partial sums in memory and no launch to add them up.
+// (D')  y[m][n] = sum_k a[m][k] * W[k][n]  (+ res[m][n]) for up to 16 rows, on a weight matrix that was packed for
+// this kernel once per model load (pack_strips_kernel below).  A workgroup owns a strip of 16 output columns over the
+// whole of K, so there are N / 16 workgroups (one per CU at N = 4096) without any k split: no partial sums in memory
+// and no launch to add them up.  Its waves take the 128-k macro-steps of the strip in turn.
 //
-// Weights go straight into the registers of the lane that feeds them to the MFMA (column n = lane % 16, k group
-// lane / 16 of a 32-k instruction; which 8 k a group holds is free as long as both operands agree: group g of
-// instruction j holds chunk 4 j + g of the macro-step, so one load instruction reads 64 contiguous bytes of each
-// of the 16 rows).  ST_FLIGHT macro-steps per wave are in flight: 128 KB per CU, the whole strip at K = 4096.
+// Packed layout: the 16 columns x 128 k of (macro-step m, strip s) are one 4 KB block at ((m * N/16) + s) * 4 KB, in
+// the order the lanes consume them: 16 bytes of lane l for MFMA j at (j * 64 + l) * 16, holding
+// W[128 m + 32 j + 8 (l / 16) + e][16 s + l % 16], e = 0..7 (column n = lane % 16, k group lane / 16 of a 32-k
+// instruction).  So every load instruction reads 1 KB contiguous, a macro-step's blocks of all strips are contiguous,
+// and the workgroups sweep the matrix together front to back: measured with loads only, 90 MB stream in 15.8 us
+// this way (5.7 TB/s, what a plain contiguous read gets), against 17.5 us with each strip's blocks contiguous
+// and 21.3 us for 16 rows x 64 B per instruction on a transposed matrix.  ST_FLIGHT macro-steps per wave are in flight.
 // The activations are small and come from L2.  A wave parks those of its own macro-steps in LDS (chunk c of row m
 // at chunk c ^ m: conflict-free fragment reads), a chunk of ST_CH macro-steps at a time in two buffers: the first
 // two chunks are requested before the first weights (requests complete in order: behind the weights they would
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 // in skinny_gemm_kernel<true>, each wave for the heads that are its macro-steps (at most ST_CH: K <= 4096);
 // workgroup 0 writes the LSE.
 // MODE 2 (feed-forward layer, Eq. 1): two weight matrices share the activations, and the strip's result is
-// silu(a Wt^T) * (a Wt2^T): the gate needs no launch of its own.
+// silu(a W) * (a W2): the gate needs no launch of its own.
 // ---------------------------------------------------------------------------
 namespace dec {
 constexpr int ST_N = 16;                 // output columns per workgroup
@@ -445,7 +447,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
   // ---- the first ST_RING macro-steps of weights (one matrix at K = 4096: all of them)
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)((int64_t)N * K * 2), 0x00020000);
   const __amdgpu_buffer_rsrc_t wrs2 = __builtin_amdgcn_make_buffer_rsrc((void*)(MODE == 2 ? Wt2 : Wt), 0, (int)((int64_t)N * K * 2), 0x00020000);
-  const int wbase = ((n0 + nl) * K + 8 * kg) * 2;
+  const int wbase = blockIdx.x * 4096 + lane * 16;          // this strip's block of macro-step 0, this lane's 16 bytes
+  const int wstep = (N / ST_N) * 4096;                      // from one macro-step's blocks to the next's
   union frag_t { xload_t u; bf16x8_t v; };
   frag_t bw[NW][ST_RING][4];
   auto load_b = [&](int u, int i) {
@@ -453,7 +456,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
     for (int w = 0; w < NW; ++w)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        bw[w][u][j].u = __builtin_amdgcn_raw_buffer_load_b128(w == 0 ? wrs : wrs2, i < nst ? wbase + ((wave + WAVES * i) * 128 + 32 * j) * 2 : (int)0x80000000, 0, 0);
+        bw[w][u][j].u = __builtin_amdgcn_raw_buffer_load_b128(w == 0 ? wrs : wrs2, i < nst ? wbase + (wave + WAVES * i) * wstep + j * 1024 : (int)0x80000000, 0, 0);
   };
 #pragma unroll
   for (int u = 0; u < ST_RING; ++u) load_b(u, u);
@@ -553,22 +556,25 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
     cb.lse[(int64_t)(wave + WAVES * (lane >> 3)) * cb.lse_stride] = lse_out;
 }
 
-// out[c][r] = in[r][c]: the one-time re-layout of a weight matrix for strip_gemm_kernel
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int R, int C) {
-  __shared__ bf16_t t[64][66];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-    const int r = i >> 6, c = i & 63;
-    if (r0 + r < R && c0 + c < C) t[r][c] = in[(int64_t)(r0 + r) * C + c0 + c];
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-    const int c = i >> 6, r = i & 63;
-    if (r0 + r < R && c0 + c < C) out[(int64_t)(c0 + c) * R + r0 + r] = t[r][c];
-  }
+// The one-time re-layout of a weight matrix W [K][N] (row-major) for strip_gemm_kernel: one thread per 16 bytes of
+// the packed matrix (layout above).  K % 128 == 0, N % 16 == 0.
+__global__ __launch_bounds__(256) void pack_strips_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int K, int N) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;          // 16-byte piece of the output
+  if (t >= (int64_t)K * N / 8) return;
+  const int lane = (int)(t & 63), j = (int)((t >> 6) & 3);
+  const int64_t blk = t >> 8;                                          // (m, s) = divmod(blk, N / 16)
+  const int ns = N / 16, m = (int)(blk / ns), sidx = (int)(blk % ns);
+  const int k0 = 128 * m + 32 * j + 8 * (lane >> 4), n = 16 * sidx + (lane & 15);
+  bf16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = in[(int64_t)(k0 + e) * N + n];
+  uint4 o = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16),
+             (uint32_t)v[4] | ((uint32_t)v[5] << 16), (uint32_t)v[6] | ((uint32_t)v[7] << 16)};
+  *(uint4*)(out + t * 8) = o;
 }
-void launch_transpose_bf16(const void* in, void* out, int32_t R, int32_t C, hipStream_t s) {
-  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((C + 63) / 64, (R + 63) / 64), dim3(256), 0, s, (const bf16_t*)in, (bf16_t*)out, R, C);
+void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, hipStream_t s) {
+  const int64_t pieces = (int64_t)K * N / 8;
+  hipLaunchKernelGGL(pack_strips_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const bf16_t*)in, (bf16_t*)out, K, N);
 }
 
 // ---------------------------------------------------------------------------
@@ -1206,7 +1212,7 @@ bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || M > dec::ST_MAXM || N % dec::ST_N || K % 128 || K < 128) return false;
   return (int64_t)N * K * 2 < ((int64_t)1 << 31) && (int64_t)M * K * 2 < ((int64_t)1 << 31);
 }
-// y = a Wt^T (+ res); with wt2: y = silu(a Wt^T) * (a Wt2^T); with merge: a is merged from the attention partials (M = 1)
+// y = a W (+ res) on packed W; with wt2: y = silu(a W) * (a W2); with merge: a is merged from the attention partials (M = 1)
 void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, bf16_t* y, const bf16_t* res, int M, int N,
                        int K, const CombineArgs* merge, hipStream_t s) {
   using namespace dec;
@@ -1262,7 +1268,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       if (Mp > 32) hipLaunchKernelGGL(decode_attn_kernel<2>, dim3(a.H, w.R, (Mp + 63) / 64), dim3(256), 0, s, t);
       else hipLaunchKernelGGL(decode_attn_kernel<1>, dim3(a.H, w.R, 1), dim3(256), 0, s, t);
     }
-    if (a.wo_t) {
+    if (a.wo_pk) {
       // out-projection on the transposed weights: no k split, so no partial sums and no launch to add them
       CombineArgs cb;
       cb.opart = opart; cb.mlpart = mlpart; cb.lse = a.lse + m0; cb.lse_stride = a.M; cb.Mpad = w.Mpad; cb.R = w.R;
@@ -1271,7 +1277,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
       if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_t, nullptr, yo, yr, Mp, a.D, HDt, &cb, s);
+        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, s);
       } else {
         {
           ProfScope ps("draft_combine", s);
@@ -1279,7 +1285,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
                              w.Mpad, a.H, w.R, a.scale);
         }
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(o, (const bf16_t*)a.wo_t, nullptr, yo, yr, Mp, a.D, HDt, nullptr, s);
+        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, s);
       }
       continue;
     }
@@ -1401,16 +1407,16 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
   }
 }
 
-void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_t, const void* w_up_t, const void* w_down_t,
+void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
                                  const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s) {
   bf16_t* mbuf = (bf16_t*)ws;
   {
     ProfScope ps("draft_mlp_gate_up", s);
-    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_t, (const bf16_t*)w_up_t, mbuf, nullptr, M, F, D, nullptr, s);
+    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, s);
   }
   {
     ProfScope ps("draft_mlp_down", s);
-    launch_strip_gemm(mbuf, (const bf16_t*)w_down_t, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, s);
+    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, s);
   }
 }
 

@@ -250,14 +250,29 @@ def run_draft_tree(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=T
     return to_host(y), to_host(lse)
 
 
+def packed_strips(w):
+    """The decode-time layout of a matrix W [K, N] as the header states it, built with plain index arithmetic:
+    flat[((((m * N/16) + s) * 4 + j) * 64 + l) * 8 + e] = W[128 m + 32 j + 8 (l // 16) + e][16 s + l % 16]."""
+    K, N = w.shape
+    assert K % 128 == 0 and N % 16 == 0
+    out = np.empty(K * N, w.dtype)
+    for m in range(K // 128):
+        for s in range(N // 16):
+            blk = w[128 * m:128 * m + 128, 16 * s:16 * s + 16]          # [k, n]
+            # k = 32 j + 8 g + e, lane l = 16 g + n
+            piece = blk.reshape(4, 4, 8, 16).transpose(0, 1, 3, 2)       # [j, g, n, e]
+            out[(m * (N // 16) + s) * 2048:(m * (N // 16) + s + 1) * 2048] = piece.reshape(-1)
+    return out
+
+
 def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True):
-    """run_draft_tree through the prepared-weights entry points: wo is re-laid by beagle_xattn_prepare_wo on the
-    device, then beagle_xattn_draft_step_prepared runs on the result.  Also returns the re-laid matrix."""
+    """run_draft_tree through the prepared-weights entry points: wo is packed by beagle_xattn_prepare_wo on the
+    device, then beagle_xattn_draft_step_prepared runs on the result.  Also returns the packed matrix (flat)."""
     d = desc_of(cfg, 0, scale)
     M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
     t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
-    wo_t = torch.full((D, H * cfg.head_dim), float("nan"), dtype=tdtype(cfg), device=DEV)
-    st = bx.beagle_xattn_prepare_wo(d, t["wo"], wo_t, check=check)
+    wo_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)
+    st = bx.beagle_xattn_prepare_wo(d, t["wo"], wo_pk, check=check)
     if not check and st != 0:
         return st
     packed = pack_tree_mask(tree_bool)
@@ -265,12 +280,12 @@ def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, che
     y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
     lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
     ws = workspace(d, bx.BEAGLE_WS_DRAFT)
-    st = bx.beagle_xattn_draft_step_prepared(d, t["x"], t["kc"], t["vc"], t["wq"], wo_t, n_true, tm, packed.shape[1],
+    st = bx.beagle_xattn_draft_step_prepared(d, t["x"], t["kc"], t["vc"], t["wq"], wo_pk, n_true, tm, packed.shape[1],
                                              y, lse, ws, check=check)
     torch.cuda.synchronize()
     if not check:
         return st
-    return to_host(y), to_host(lse), to_host(wo_t)
+    return to_host(y), to_host(lse), to_host(wo_pk)
 
 
 def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True, desc=None):

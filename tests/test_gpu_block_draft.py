@@ -186,8 +186,8 @@ def _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true=None, tree=None, desc=None
     x, kcd, vcd = gh.to_dev(bi["e"][0], cfg), gh.to_dev(kc, cfg), gh.to_dev(vc, cfg)
     params = bx.make_block_params(ffn, 1e-5, **dev)
     dt = gh.tdtype(cfg)
-    E = lambda *s: torch.full(s, float("nan"), dtype=dt, device=gh.DEV)
-    tw = dict(wo_t=E(D, HD), w_gate_t=E(ffn, D), w_up_t=E(ffn, D), w_down_t=E(D, ffn))
+    E = lambda n: torch.full((n,), float("nan"), dtype=dt, device=gh.DEV)
+    tw = dict(wo_pk=E(D * HD), w_gate_pk=E(ffn * D), w_up_pk=E(ffn * D), w_down_pk=E(D * ffn))
     dw = bx.make_block_decode_weights(**tw)
     st = bx.beagle_xattn_block_prepare_weights(d, params, dw, check=check)
     if not check and st != 0:
@@ -219,8 +219,8 @@ def test_bf16_block_draft_step_on_prepared_weights(M, rows, H, G, D, ffn, gains,
     n_true = rows - T if T else None
     ref = _ref(cfg, bi, kc, vc, gains, n_true, tree)
     h, lse, tw = _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true, tree)
-    for n, src in (("wo_t", "wo"), ("w_gate_t", "w_gate"), ("w_up_t", "w_up"), ("w_down_t", "w_down")):
-        assert np.array_equal(tw[n], bi[src].T), n             # the re-layout moves values, nothing else
+    for n, src in (("wo_pk", "wo"), ("w_gate_pk", "w_gate"), ("w_up_pk", "w_up"), ("w_down_pk", "w_down")):
+        assert np.array_equal(tw[n], gh.packed_strips(bi[src])), n   # packing moves values, nothing else
     assert np.isfinite(h).all()
     assert gh.rel_fro(h, ref["h"]) <= OUT_FRO, gh.rel_fro(h, ref["h"])
     assert gh.max_abs(lse, ref["lse"]) <= 4e-3, gh.max_abs(lse, ref["lse"])
@@ -237,7 +237,7 @@ def test_bf16_block_draft_step_on_prepared_weights_at_the_7b_shape():
     assert gh.max_abs(lse, ref["lse"]) <= 4e-3
 
 
-@pytest.mark.parametrize("M,D,ffn,dtype", [(17, 512, 1408, "bf16"), (4, 512, 1344, "bf16"), (3, 256, 96, "f32")])
+@pytest.mark.parametrize("M,D,ffn,dtype", [(17, 512, 1408, "bf16"), (4, 512, 1344, "bf16"), (3, 256, 96, "f32")])   # rows; F % 128; dtype
 def test_block_shapes_outside_the_prepared_path_are_refused(M, D, ffn, dtype):
     d = 128 if dtype == "bf16" else 64
     cfg, bi, kc, vc = _problem(dtype, M, 40, 4, 4, D, d, ffn, 261)
