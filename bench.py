@@ -524,11 +524,12 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         slab[i, 3].copy_((torch.randn(per, device=dev, generator=g) * 0.02).to(torch.bfloat16))
         sets.append((slab[i, 0].view(L, G, hd), slab[i, 1].view(L, G, hd), slab[i, 2].view(D, H * hd),
                      slab[i, 3].view(H * hd, D)))
-    # the output projections once more in the decode-time layout (packed once per model load):
+    # the two projections once more in the decode-time layout (packed once per model load):
     # the same bytes per call, streamed from these buffers instead
-    wo_pk = torch.empty(nset, D, H * hd, dtype=torch.bfloat16, device=dev)
+    wq_pk = torch.empty(nset, D * H * hd, dtype=torch.bfloat16, device=dev)
+    wo_pk = torch.empty(nset, D * H * hd, dtype=torch.bfloat16, device=dev)
     for i in range(nset):
-        bx.beagle_xattn_prepare_wo(dm.desc_of(cfg.with_(seq_q=1)), sets[i][3], wo_pk[i])
+        bx.beagle_xattn_prepare_weights(dm.desc_of(cfg.with_(seq_q=1)), sets[i][2], sets[i][3], wq_pk[i], wo_pk[i])
     res, roof = {}, {}
     stream = torch.cuda.current_stream()
 
@@ -561,7 +562,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         prep_us = None
         if M <= bx.BEAGLE_PREPARED_MAX_QUERIES:
             prep = lambda r: bx.beagle_xattn_draft_step_prepared(desc, x, sets[r % nset][0], sets[r % nset][1],
-                                                                 sets[r % nset][2], wo_pk[r % nset], L, None, 0, y, lse, ws, stream)
+                                                                 wq_pk[r % nset], wo_pk[r % nset], L, None, 0, y, lse, ws, stream)
             prep_us = _time_calls(torch, prep, nset, 50)
         # the same fifty calls as five replays of a HIP graph that holds one call per buffer set
         graph_us = None
@@ -613,7 +614,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
             bytes=call_bytes, avg_us=round(us, 2), median_us=spread.get("median"), min_us=spread.get("min"), achieved=round(call_bytes / us / 1e3, 1), peak=PEAK_HBM_GBS,
             unit="GB/s", frac=round(call_bytes / us / 1e3 / PEAK_HBM_GBS, 4),
             graph_replay=dict(avg_us=round(graph_us, 2), frac=round(call_bytes / graph_us / 1e3 / PEAK_HBM_GBS, 4)) if graph_us else None,
-            prepared_wo=dict(entry="beagle_xattn_draft_step_prepared (wo packed once per model load; same bytes per call)",
+            prepared_wo=dict(entry="beagle_xattn_draft_step_prepared (wq, wo packed once per model load; same bytes per call)",
                              avg_us=round(prep_us, 2), achieved=round(call_bytes / prep_us / 1e3, 1),
                              frac=round(call_bytes / prep_us / 1e3 / PEAK_HBM_GBS, 4)) if prep_us else None,
             frac_of_read_probe=round(probe["whole_step_134MB"]["us"] / min(best, prep_us or best), 4),
@@ -649,8 +650,8 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         bx.beagle_xattn_draft_step_tree(desc, x, kc, vc, wq, wo, L - T, tmd, 2, y, lse, ws, stream)
 
     def tree_prepared_call(r):
-        kc, vc, wq, _ = sets[r % nset]
-        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_pk[r % nset], L - T, tmd, 2, y, lse, ws, stream)
+        kc, vc, _, _ = sets[r % nset]
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq_pk[r % nset], wo_pk[r % nset], L - T, tmd, 2, y, lse, ws, stream)
 
     def append_call(r):
         kc, vc, _, _ = sets[r % nset]
@@ -674,16 +675,16 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
     # ... and with all four streamed matrices in the decode-time layout (packed once per model load)
     mlps_t = []
     for i, (wg, wu, wd) in enumerate(mlps):
-        tw = dict(wo_pk=wo_pk[i], w_gate_pk=torch.empty(D * F, dtype=torch.bfloat16, device=dev),
+        tw = dict(wq_pk=wq_pk[i], wo_pk=wo_pk[i], w_gate_pk=torch.empty(D * F, dtype=torch.bfloat16, device=dev),
                   w_up_pk=torch.empty(D * F, dtype=torch.bfloat16, device=dev), w_down_pk=torch.empty(F * D, dtype=torch.bfloat16, device=dev))
         prm = bx.make_block_params(F, 1e-5, wq=sets[i][2], wo=sets[i][3], w_gate=wg, w_up=wu, w_down=wd, g_q=gq, g_mlp=gm)
         bx.beagle_xattn_block_prepare_weights(desc, prm, bx.make_block_decode_weights(**tw))
         mlps_t.append(tw)
 
     def block_prepared_call(r):
-        kc, vc, wq, _ = sets[r % nset]
-        tw = dict(mlps_t[r % 4], wo_pk=wo_pk[r % nset])
-        prm = bx.make_block_params(F, 1e-5, wq=wq, g_q=gq, g_mlp=gm)
+        kc, vc, _, _ = sets[r % nset]
+        tw = dict(mlps_t[r % 4], wq_pk=wq_pk[r % nset], wo_pk=wo_pk[r % nset])
+        prm = bx.make_block_params(F, 1e-5, g_q=gq, g_mlp=gm)
         bx.beagle_xattn_block_draft_step_prepared(desc, prm, bx.make_block_decode_weights(**tw), x, kc, vc, L - T, tmd, 2,
                                                   hb, lse, bws, stream)
 

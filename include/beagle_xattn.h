@@ -406,28 +406,28 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
 
 /*
  * The block's draft step on weights in the decode-time layout (see
- * beagle_xattn_prepare_wo): the output projection and the three feed-forward
- * matrices packed, so that each projection is one launch of 16-column strips
+ * beagle_xattn_prepare_weights): the two attention projections and the three
+ * feed-forward matrices packed, so that each projection is one launch of 16-column strips
  * over the whole of k -- no k split, no partial sums, no launch to add them,
  * and the SiLU gate runs in the epilogue of the gate/up projection.
- *   beagle_xattn_block_prepare_weights: fills the four buffers of `dw` (DEVICE,
- *     caller-owned, 16-byte aligned, each the size of its source): wo_pk from
- *     params->wo [H*d, D], w_gate_pk, w_up_pk from [D, F], w_down_pk from
- *     [F, D].  Once per model load.  bf16 with F % 128 == 0, else
- *     BEAGLE_ERR_UNSUPPORTED.
+ *   beagle_xattn_block_prepare_weights: fills the five buffers of `dw` (DEVICE,
+ *     caller-owned, 16-byte aligned, each the size of its source): wq_pk from
+ *     params->wq [D, H*d], wo_pk from params->wo [H*d, D], w_gate_pk, w_up_pk from [D, F], w_down_pk from
+ *     [F, D].  Once per model load.  bf16 with D % 128 == 0 and F % 128 == 0,
+ *     else BEAGLE_ERR_UNSUPPORTED.
  *   beagle_xattn_block_draft_step_prepared: beagle_xattn_block_draft_step with
- *     params->wo, w_gate, w_up, w_down replaced by `dw` (those four fields of
- *     params are not read; wq, the gains, ffn and rms_eps are).  Same definition
+ *     params->wq, wo, w_gate, w_up, w_down replaced by `dw` (those five fields
+ *     of params are not read; the gains, ffn and rms_eps are).  Same definition
  *     of h and lse; sums run in a different fixed order, so results agree with
  *     the plain entry point to rounding, not bitwise.  1 <= seq_q <=
- *     BEAGLE_PREPARED_MAX_QUERIES, bf16, F % 128 == 0; BEAGLE_ERR_UNSUPPORTED
- *     otherwise, before anything is enqueued.
+ *     BEAGLE_PREPARED_MAX_QUERIES, bf16, D % 128 == 0, F % 128 == 0;
+ *     BEAGLE_ERR_UNSUPPORTED otherwise, before anything is enqueued.
  * Workspace: BEAGLE_WS_BLOCK_DRAFT.
  */
 typedef struct {
   int32_t struct_size;          /* sizeof(beagle_block_decode_weights); checked  */
   int32_t reserved;             /* 0                                             */
-  void *wo_pk;                  /* packed wo:     D * H*d elements               */
+  void *wq_pk, *wo_pk;          /* packed wq, wo: D * H*d elements each          */
   void *w_gate_pk, *w_up_pk;    /* packed w_gate, w_up: D * F elements each      */
   void *w_down_pk;              /* packed w_down: F * D elements                 */
 } beagle_block_decode_weights;
@@ -507,24 +507,25 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
  * and no launch to add them.  Weights are fixed while drafting (section 4.1:
  * the draft model is trained beforehand), so packing is paid once per model
  * load, not per step.  A packed matrix has the size of the original.
- *   beagle_xattn_prepare_wo: wo [H*d, D] -> wo_pk (packed, K = H*d, N = D), both
- *     DEVICE, bf16 only (BEAGLE_ERR_UNSUPPORTED otherwise); wo_pk must not
- *     overlap wo.
- *   beagle_xattn_draft_step_prepared: beagle_xattn_draft_step_tree with wo_pk in
- *     the place of wo (n_true == seq_kv and tree_mask == NULL give the plain
- *     draft step).  Same definition of y and lse; sums run in a different
- *     (fixed) order than in beagle_xattn_draft_step, so results agree with it to
- *     rounding, not bitwise.  Serves 1 <= seq_q <= BEAGLE_PREPARED_MAX_QUERIES,
- *     bf16 (whose shapes have H*d % 128 == 0 and D % 16 == 0);
- *     BEAGLE_ERR_UNSUPPORTED otherwise, before anything is enqueued: use the
- *     plain entry points there.
+ *   beagle_xattn_prepare_weights: packs wq [D, H*d] into wq_pk and wo [H*d, D]
+ *     into wo_pk (all DEVICE; a source and its destination may both be NULL to
+ *     skip that matrix; a destination must not overlap its source).  bf16 with
+ *     D % 128 == 0 only (BEAGLE_ERR_UNSUPPORTED otherwise).
+ *   beagle_xattn_draft_step_prepared: beagle_xattn_draft_step_tree with wq_pk,
+ *     wo_pk in the place of wq, wo (n_true == seq_kv and tree_mask == NULL give
+ *     the plain draft step).  Same definition of y and lse; sums run in a
+ *     different (fixed) order than in beagle_xattn_draft_step, so results agree
+ *     with it to rounding, not bitwise.  Serves 1 <= seq_q <=
+ *     BEAGLE_PREPARED_MAX_QUERIES, bf16, D % 128 == 0; BEAGLE_ERR_UNSUPPORTED
+ *     otherwise, before anything is enqueued: use the plain entry points there.
  * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT).
  */
 #define BEAGLE_PREPARED_MAX_QUERIES 16
-beagle_status beagle_xattn_prepare_wo(const beagle_xattn_desc* desc, const void* wo, void* wo_pk, void* hip_stream);
+beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc, const void* wq, const void* wo,
+    void* wq_pk, void* wo_pk, void* hip_stream);
 beagle_status beagle_xattn_draft_step_prepared(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache,
-    const void* wq, const void* wo_pk, int32_t n_true,
+    const void* wq_pk, const void* wo_pk, int32_t n_true,
     const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream);
 

@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: 
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
-    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_prepare_wo",
+    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_prepare_weights",
     "beagle_xattn_draft_step_prepared", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
@@ -78,7 +78,7 @@ class beagle_block_params(C.Structure):
 
 class beagle_block_decode_weights(C.Structure):
     _fields_ = [("struct_size", C.c_int32), ("reserved", C.c_int32)] + \
-               [(n, _VP) for n in ("wo_pk", "w_gate_pk", "w_up_pk", "w_down_pk")]
+               [(n, _VP) for n in ("wq_pk", "wo_pk", "w_gate_pk", "w_up_pk", "w_down_pk")]
 
 
 class beagle_block_saved(C.Structure):
@@ -180,8 +180,8 @@ def lib() -> C.CDLL:
     L.beagle_xattn_draft_step_tree.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_draft_step_prepared.restype = C.c_int
     L.beagle_xattn_draft_step_prepared.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
-    L.beagle_xattn_prepare_wo.restype = C.c_int
-    L.beagle_xattn_prepare_wo.argtypes = [dp, vp, vp, vp]
+    L.beagle_xattn_prepare_weights.restype = C.c_int
+    L.beagle_xattn_prepare_weights.argtypes = [dp, vp, vp, vp, vp, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
     L.beagle_xattn_kv_append.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_size_t, vp]
     L.beagle_xattn_mask_row_limit.restype = C.c_int
@@ -344,15 +344,15 @@ def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true
     return _check(st, "beagle_xattn_draft_step_tree", check)
 
 
-def beagle_xattn_prepare_wo(desc, wo, wo_pk, stream=None, *, check=True) -> int:
-    st = lib().beagle_xattn_prepare_wo(C.byref(desc), _ptr(wo), _ptr(wo_pk), _stream(stream))
-    return _check(st, "beagle_xattn_prepare_wo", check)
+def beagle_xattn_prepare_weights(desc, wq, wo, wq_pk, wo_pk, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_prepare_weights(C.byref(desc), _ptr(wq), _ptr(wo), _ptr(wq_pk), _ptr(wo_pk), _stream(stream))
+    return _check(st, "beagle_xattn_prepare_weights", check)
 
 
-def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq, wo_pk, n_true, tree_mask, mask_words, y, lse,
+def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq_pk, wo_pk, n_true, tree_mask, mask_words, y, lse,
                                      workspace, stream=None, *, workspace_bytes=None, check=True) -> int:
     st = lib().beagle_xattn_draft_step_prepared(
-        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq, wo_pk)), int(n_true), _ptr(tree_mask),
+        C.byref(desc), *(_ptr(t) for t in (x_draft, k_cache, v_cache, wq_pk, wo_pk)), int(n_true), _ptr(tree_mask),
         int(mask_words), _ptr(y), _ptr(lse),
         _ptr(workspace), _nbytes(workspace) if workspace_bytes is None else workspace_bytes, _stream(stream))
     return _check(st, "beagle_xattn_draft_step_prepared", check)

@@ -663,10 +663,11 @@ namespace {
 beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo,
     int32_t n_true, const uint32_t* tree, int32_t words,
-    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, bool wo_packed = false) {
+    void* y, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream, bool wo_packed = false) {   // wo_packed: wq and wo are both packed
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
-  if (wo_packed && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD))) return BEAGLE_ERR_UNSUPPORTED;
+  if (wo_packed && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD) &&
+                     strip_gemm_fits((int32_t)d.S, (int32_t)d.HD, (int32_t)d.D))) return BEAGLE_ERR_UNSUPPORTED;
   const void* ptrs[] = {x_draft, k_cache, v_cache, wq, wo, y, lse, workspace};
   for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
   for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
@@ -688,8 +689,8 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
-    a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.wq = wq; a.y = y; a.lse = lse; a.ws = workspace;
-    if (wo_packed) a.wo_pk = wo; else a.wo = wo;
+    a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.y = y; a.lse = lse; a.ws = workspace;
+    if (wo_packed) { a.wq_pk = wq; a.wo_pk = wo; } else { a.wq = wq; a.wo = wo; }
     a.tree = tree; a.n_true = n_true; a.tree_words = words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     launch_decode_bf16(a, s);
@@ -764,22 +765,25 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
                          workspace_bytes, hip_stream);
 }
 
-beagle_status beagle_xattn_prepare_wo(const beagle_xattn_desc* desc, const void* wo, void* wo_pk, void* hip_stream) {
+beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc, const void* wq, const void* wo,
+    void* wq_pk, void* wo_pk, void* hip_stream) {
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
-  if (!wo || !wo_pk) return BEAGLE_ERR_NULL;
-  if (!aligned16(wo) || !aligned16(wo_pk)) return BEAGLE_ERR_ALIGN;
-  if (!d.bf16 || d.D % 16 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
+  if ((!wq) != (!wq_pk) || (!wo) != (!wo_pk) || (!wq && !wo)) return BEAGLE_ERR_NULL;
+  const void* ptrs[] = {wq, wo, wq_pk, wo_pk};
+  for (const void* q : ptrs) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (!d.bf16 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
   (void)hipGetLastError();
-  launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, (hipStream_t)hip_stream);
+  if (wq) launch_pack_strips_bf16(wq, wq_pk, (int32_t)d.D, (int32_t)d.HD, (hipStream_t)hip_stream);
+  if (wo) launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, (hipStream_t)hip_stream);
   return hip_status();
 }
 
 beagle_status beagle_xattn_draft_step_prepared(const beagle_xattn_desc* desc,
-    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq, const void* wo_pk,
+    const void* x_draft, const void* k_cache, const void* v_cache, const void* wq_pk, const void* wo_pk,
     int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* y, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq, wo_pk, n_true, tree_mask, mask_words, y, lse, workspace,
+  return draft_step_impl(desc, x_draft, k_cache, v_cache, wq_pk, wo_pk, n_true, tree_mask, mask_words, y, lse, workspace,
                          workspace_bytes, hip_stream, true);
 }
 

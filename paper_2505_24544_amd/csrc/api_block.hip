@@ -273,19 +273,20 @@ beagle_status block_draft_step_impl(const beagle_xattn_desc* desc, const beagle_
     int32_t mask_words, void* h, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
   Dims d; beagle_status st = check_block(desc, p, &d, true);
   if (st != BEAGLE_OK) return st;
+  const void* wq = dw ? dw->wq_pk : p->wq;
   const void* wo = dw ? dw->wo_pk : p->wo;
   const void* w_gate = dw ? dw->w_gate_pk : p->w_gate;
   const void* w_up = dw ? dw->w_up_pk : p->w_up;
   const void* w_down = dw ? dw->w_down_pk : p->w_down;
-  const void* req[] = {x_draft, k_cache, v_cache, p->wq, wo, w_gate, w_up, w_down, h, lse, workspace};
+  const void* req[] = {x_draft, k_cache, v_cache, wq, wo, w_gate, w_up, w_down, h, lse, workspace};
   for (const void* q : req) if (!q) return BEAGLE_ERR_NULL;
-  const void* all[] = {x_draft, k_cache, v_cache, p->wq, wo, w_gate, w_up, w_down, p->g_q, p->g_mlp, h, lse};
+  const void* all[] = {x_draft, k_cache, v_cache, wq, wo, w_gate, w_up, w_down, p->g_q, p->g_mlp, h, lse};
   for (const void* q : all) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
   if (((uintptr_t)workspace) % WS_ALIGN) return BEAGLE_ERR_ALIGN;
   const int64_t F = p->ffn;
   if (workspace_bytes < beagle_xattn_block_workspace_bytes(desc, p->ffn, BEAGLE_WS_BLOCK_DRAFT)) return BEAGLE_ERR_WORKSPACE;
   if (d.bf16 && !block_mlp_bf16_fits((int32_t)d.D, (int32_t)F)) return BEAGLE_ERR_UNSUPPORTED;
-  if (dw && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD) &&
+  if (dw && !(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)d.HD) && strip_gemm_fits((int32_t)d.S, (int32_t)d.HD, (int32_t)d.D) &&
               strip_gemm_fits((int32_t)d.S, (int32_t)F, (int32_t)d.D) && strip_gemm_fits((int32_t)d.S, (int32_t)d.D, (int32_t)F)))
     return BEAGLE_ERR_UNSUPPORTED;
   if (n_true < 0 || n_true > d.L) return BEAGLE_ERR_SHAPE;
@@ -311,8 +312,8 @@ beagle_status block_draft_step_impl(const beagle_xattn_desc* desc, const beagle_
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
-    a.x = xn; a.kc = k_cache; a.vc = v_cache; a.wq = p->wq; a.y = y; a.lse = lse; a.ws = base + w.step;
-    if (dw) a.wo_pk = wo; else a.wo = wo;
+    a.x = xn; a.kc = k_cache; a.vc = v_cache; a.y = y; a.lse = lse; a.ws = base + w.step;
+    if (dw) { a.wq_pk = wq; a.wo_pk = wo; } else { a.wq = wq; a.wo = wo; }
     a.tree = tree_mask; a.n_true = n_true; a.tree_words = mask_words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     a.y_res = x_draft;
@@ -370,11 +371,11 @@ beagle_status beagle_xattn_block_draft_step_prepared(const beagle_xattn_desc* de
     void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!dw) return BEAGLE_ERR_NULL;
   if (!decode_weights_ok(dw)) return BEAGLE_ERR_SHAPE;
-  // the four matrices that dw replaces are not read: the shared checks see dw's in their place
+  // the five matrices that dw replaces are not read: the shared checks see dw's in their place
   beagle_block_params q;
   if (!p || p->struct_size != (int32_t)sizeof(q)) return p ? BEAGLE_ERR_SHAPE : BEAGLE_ERR_NULL;
   q = *p;
-  q.wo = dw->wo_pk; q.w_gate = dw->w_gate_pk; q.w_up = dw->w_up_pk; q.w_down = dw->w_down_pk;
+  q.wq = dw->wq_pk; q.wo = dw->wo_pk; q.w_gate = dw->w_gate_pk; q.w_up = dw->w_up_pk; q.w_down = dw->w_down_pk;
   return block_draft_step_impl(desc, &q, dw, x_draft, k_cache, v_cache, n_true, tree_mask, mask_words, h, lse,
                                workspace, workspace_bytes, hip_stream);
 }
@@ -385,13 +386,14 @@ beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, 
   if (st != BEAGLE_OK) return st;
   if (!dw) return BEAGLE_ERR_NULL;
   if (!decode_weights_ok(dw)) return BEAGLE_ERR_SHAPE;
-  const void* ptrs[] = {p->wo, p->w_gate, p->w_up, p->w_down, dw->wo_pk, dw->w_gate_pk, dw->w_up_pk, dw->w_down_pk};
+  const void* ptrs[] = {p->wq, p->wo, p->w_gate, p->w_up, p->w_down, dw->wq_pk, dw->wo_pk, dw->w_gate_pk, dw->w_up_pk, dw->w_down_pk};
   for (const void* q : ptrs) if (!q) return BEAGLE_ERR_NULL;
   for (const void* q : ptrs) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
   const int32_t F = p->ffn;
-  if (!d.bf16 || F % 128 || d.D % 16 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
+  if (!d.bf16 || F % 128 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
+  launch_pack_strips_bf16(p->wq, dw->wq_pk, (int32_t)d.D, (int32_t)d.HD, s);
   launch_pack_strips_bf16(p->wo, dw->wo_pk, (int32_t)d.HD, (int32_t)d.D, s);
   launch_pack_strips_bf16(p->w_gate, dw->w_gate_pk, (int32_t)d.D, F, s);
   launch_pack_strips_bf16(p->w_up, dw->w_up_pk, (int32_t)d.D, F, s);

@@ -176,7 +176,8 @@ struct DecodeArgs {
   // rotary embedding of the queries (rope != 0): positions rope_pos[m] (device) or all at L
   int32_t rope; float rope_base; const int32_t* rope_pos;
   const void* y_res;   // optional residual added to y (storage type, [M,D])
-  const void* wo_pk;   // optional: wo packed for strip_gemm_kernel; then wo is not read (needs strip_gemm_fits(M, D, H*d))
+  // optional: wq / wo packed for strip_gemm_kernel; then wq / wo is not read (needs strip_gemm_fits for M and its shape)
+  const void* wq_pk; const void* wo_pk;
 };
 bool strip_gemm_fits(int32_t M, int32_t N, int32_t K);
 // W [K][N] row-major -> the packed layout that strip_gemm_kernel streams (K % 128 == 0, N % 16 == 0)

@@ -377,9 +377,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 template <int MODE, bool ROWS16, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
-                                                            const bf16_t* __restrict__ Wt2, bf16_t* __restrict__ yout,
+                                                            const bf16_t* __restrict__ Wt2, void* __restrict__ yout,
                                                             const bf16_t* __restrict__ res, int M, int N, int K,
-                                                            CombineArgs cb) {
+                                                            CombineArgs cb, int out_f32) {
   using namespace dec;
   constexpr int ROWS = ROWS16 ? 16 : 8;             // activation rows kept per macro-step
   constexpr int ST_CH = ROWS16 ? 2 : 4;             // macro-steps per activation chunk
@@ -550,7 +550,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
     }
     const int64_t o = (int64_t)m * N + n0 + n;
     if (res) v += __uint_as_float((uint32_t)res[o] << 16);
-    yout[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
+    if (out_f32) ((float*)yout)[o] = v;                       // the queries: the attention kernel wants them unrounded
+    else ((bf16_t*)yout)[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
   }
   if (MODE == 1 && blockIdx.x == 0 && (lane & 7) == 0 && (lane >> 3) < nst)
     cb.lse[(int64_t)(wave + WAVES * (lane >> 3)) * cb.lse_stride] = lse_out;
@@ -1213,19 +1214,20 @@ bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
   return (int64_t)N * K * 2 < ((int64_t)1 << 31) && (int64_t)M * K * 2 < ((int64_t)1 << 31);
 }
 // y = a W (+ res) on packed W; with wt2: y = silu(a W) * (a W2); with merge: a is merged from the attention partials (M = 1)
-void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, bf16_t* y, const bf16_t* res, int M, int N,
-                       int K, const CombineArgs* merge, hipStream_t s) {
+void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, void* y, const bf16_t* res, int M, int N,
+                       int K, const CombineArgs* merge, bool out_f32, hipStream_t s) {
   using namespace dec;
   const dim3 grid(N / ST_N);
   const CombineArgs cb = merge ? *merge : CombineArgs{};
-  // one matrix: eight waves, one workgroup per CU (N / 16 is about the number of CUs for the attention's projection);
+  const int f = out_f32 ? 1 : 0;
+  // one matrix: eight waves, one workgroup per CU (N / 16 is about the number of CUs for the attention's projections);
   // the feed-forward pair has several strips per CU: four waves and two workgroups per CU, so that one's start and
   // final reduction hide behind the other's stream
-  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
-  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb);
+  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
+  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
+  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
+  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
+  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
 }
 
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
@@ -1251,14 +1253,17 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
   for (int m0 = 0; m0 < a.M; m0 += MAXM) {
     const int Mp = a.M - m0 < MAXM ? a.M - m0 : MAXM;
     const bf16_t* x = (const bf16_t*)a.x + (int64_t)m0 * a.D;
-    {
+    if (a.wq_pk) {                    // packed Wq: the whole of k in one strip, so q arrives as a single slice
+      ProfScope ps("draft_proj_q", s);
+      launch_strip_gemm(x, (const bf16_t*)a.wq_pk, nullptr, qpart, nullptr, Mp, HDt, a.D, nullptr, true, s);
+    } else {
       ProfScope ps("draft_proj_q", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
                          Mp, HDt, a.D, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
     }
     {
       DecAttnArgs t;
-      t.qpart = qpart; t.KSq = w.KSq; t.kc = (const bf16_t*)a.kc; t.vc = (const bf16_t*)a.vc;
+      t.qpart = qpart; t.KSq = a.wq_pk ? 1 : w.KSq; t.kc = (const bf16_t*)a.kc; t.vc = (const bf16_t*)a.vc;
       t.opart = opart; t.mlpart = mlpart;
       t.M = Mp; t.Mpad = w.Mpad; t.L = a.L; t.H = a.H; t.G = a.G; t.R = w.R; t.range = w.range;
       t.scale = a.scale;
@@ -1277,7 +1282,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
       if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, s);
+        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, false, s);
       } else {
         {
           ProfScope ps("draft_combine", s);
@@ -1285,7 +1290,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
                              w.Mpad, a.H, w.R, a.scale);
         }
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, s);
+        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, false, s);
       }
       continue;
     }
@@ -1412,11 +1417,11 @@ void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const voi
   bf16_t* mbuf = (bf16_t*)ws;
   {
     ProfScope ps("draft_mlp_gate_up", s);
-    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, s);
+    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, false, s);
   }
   {
     ProfScope ps("draft_mlp_down", s);
-    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, s);
+    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, false, s);
   }
 }
 

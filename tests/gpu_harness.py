@@ -266,13 +266,14 @@ def packed_strips(w):
 
 
 def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True):
-    """run_draft_tree through the prepared-weights entry points: wo is packed by beagle_xattn_prepare_wo on the
-    device, then beagle_xattn_draft_step_prepared runs on the result.  Also returns the packed matrix (flat)."""
+    """run_draft_tree through the prepared-weights entry points: wq and wo are packed by beagle_xattn_prepare_weights
+    on the device, then beagle_xattn_draft_step_prepared runs on the results.  Also returns the packed matrices."""
     d = desc_of(cfg, 0, scale)
     M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
     t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
+    wq_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)
     wo_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)
-    st = bx.beagle_xattn_prepare_wo(d, t["wo"], wo_pk, check=check)
+    st = bx.beagle_xattn_prepare_weights(d, t["wq"], t["wo"], wq_pk, wo_pk, check=check)
     if not check and st != 0:
         return st
     packed = pack_tree_mask(tree_bool)
@@ -280,12 +281,12 @@ def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, che
     y = torch.full((M, D), float("nan"), dtype=tdtype(cfg), device=DEV)
     lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=DEV)
     ws = workspace(d, bx.BEAGLE_WS_DRAFT)
-    st = bx.beagle_xattn_draft_step_prepared(d, t["x"], t["kc"], t["vc"], t["wq"], wo_pk, n_true, tm, packed.shape[1],
+    st = bx.beagle_xattn_draft_step_prepared(d, t["x"], t["kc"], t["vc"], wq_pk, wo_pk, n_true, tm, packed.shape[1],
                                              y, lse, ws, check=check)
     torch.cuda.synchronize()
     if not check:
         return st
-    return to_host(y), to_host(lse), to_host(wo_pk)
+    return to_host(y), to_host(lse), (to_host(wq_pk), to_host(wo_pk))
 
 
 def run_kv_append(cfg, x_new, wk, wv, kc, vc, pos, check=True, desc=None):

@@ -187,13 +187,13 @@ def _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true=None, tree=None, desc=None
     params = bx.make_block_params(ffn, 1e-5, **dev)
     dt = gh.tdtype(cfg)
     E = lambda n: torch.full((n,), float("nan"), dtype=dt, device=gh.DEV)
-    tw = dict(wo_pk=E(D * HD), w_gate_pk=E(ffn * D), w_up_pk=E(ffn * D), w_down_pk=E(D * ffn))
+    tw = dict(wq_pk=E(D * HD), wo_pk=E(D * HD), w_gate_pk=E(ffn * D), w_up_pk=E(ffn * D), w_down_pk=E(D * ffn))
     dw = bx.make_block_decode_weights(**tw)
     st = bx.beagle_xattn_block_prepare_weights(d, params, dw, check=check)
     if not check and st != 0:
         return st
-    # the step must not read the four matrices that dw replaces
-    only = bx.make_block_params(ffn, 1e-5, **{n: dev[n] for n in dev if n in ("wq", "g_q", "g_mlp")})
+    # the step must not read the five matrices that dw replaces
+    only = bx.make_block_params(ffn, 1e-5, **{n: dev[n] for n in dev if n in ("g_q", "g_mlp")})
     h = torch.full((M, D), float("nan"), dtype=dt, device=gh.DEV)
     lse = torch.full((H, M), float("nan"), dtype=torch.float32, device=gh.DEV)
     ws = torch.empty(bx.beagle_xattn_block_workspace_bytes(d, ffn, bx.BEAGLE_WS_BLOCK_DRAFT), dtype=torch.uint8, device=gh.DEV)
@@ -219,7 +219,7 @@ def test_bf16_block_draft_step_on_prepared_weights(M, rows, H, G, D, ffn, gains,
     n_true = rows - T if T else None
     ref = _ref(cfg, bi, kc, vc, gains, n_true, tree)
     h, lse, tw = _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true, tree)
-    for n, src in (("wo_pk", "wo"), ("w_gate_pk", "w_gate"), ("w_up_pk", "w_up"), ("w_down_pk", "w_down")):
+    for n, src in (("wq_pk", "wq"), ("wo_pk", "wo"), ("w_gate_pk", "w_gate"), ("w_up_pk", "w_up"), ("w_down_pk", "w_down")):
         assert np.array_equal(tw[n], gh.packed_strips(bi[src])), n   # packing moves values, nothing else
     assert np.isfinite(h).all()
     assert gh.rel_fro(h, ref["h"]) <= OUT_FRO, gh.rel_fro(h, ref["h"])

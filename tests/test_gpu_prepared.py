@@ -1,4 +1,4 @@
-"""GPU parity of the draft step on a prepared (packed) output projection against the float64 oracle
+"""GPU parity of the draft step on prepared (packed) projection weights against the float64 oracle
 (section 4.1, KV-cache paragraph; appendix "Ablation Study" for the tree variant): the same definition of y and LSE
 as the plain draft step, so the same oracle functions and the same tolerances; plus the packing itself (exact,
 against the layout the header documents),
@@ -41,21 +41,18 @@ def test_prepared_step_matches_the_oracle(M, n_true, T, H, G, D):
         tm = np.zeros((M, 0), bool)
     ref = orc.draft_step_tree(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true=n_true, tree_mask=tm,
                               n_q_heads=H, n_kv_heads=G)
-    y, lse, wo_pk = run_draft_prepared(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true, tm)
-    assert np.array_equal(wo_pk, packed_strips(inp["wo"]))      # packing moves values, nothing else
+    y, lse, (wq_pk, wo_pk) = run_draft_prepared(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true, tm)
+    assert np.array_equal(wq_pk, packed_strips(inp["wq"]))      # packing moves values, nothing else
+    assert np.array_equal(wo_pk, packed_strips(inp["wo"]))
     fin = np.isfinite(ref["lse"])
     assert np.array_equal(np.isneginf(lse), ~fin)
     assert np.isfinite(y).all()
     assert max_abs(y, ref["y"]) <= BF16_OUT_ABS and rel_fro(y, ref["y"]) <= BF16_OUT_FRO, rel_fro(y, ref["y"])
     assert max_abs(lse[fin], ref["lse"][fin]) <= LSE_TOL
     assert (y[~fin.any(axis=0)] == 0).all()
-    # and next to the plain entry point: same attention kernel, so the same LSE bit for bit above one query (the
-    # one-query merge sums in another order); y differs by the order of the projection's sums only
+    # and next to the plain entry point: both differ by the order of the projections' sums only
     y0, l0 = run_draft_tree(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_true, tm)
-    if M > 1:
-        assert np.array_equal(l0, lse)
-    else:
-        assert max_abs(l0[fin], lse[fin]) <= 1e-5
+    assert max_abs(l0[fin], lse[fin]) <= 1e-4
     assert max_abs(y, y0) <= 2.0 ** -7 * max(1.0, float(np.abs(y0).max()))
 
 
@@ -77,21 +74,22 @@ def test_prepared_step_in_a_hip_graph_replays_to_the_eager_result():
     g = torch.Generator(device=gh.DEV).manual_seed(77)
     R = lambda *s, std=1.0: (torch.randn(*s, device=gh.DEV, generator=g) * std).to(torch.bfloat16)
     x, kc, vc, wq, wo = R(M, D), R(L, H, 128, std=1.28), R(L, H, 128, std=1.28), R(D, H * 128, std=0.02), R(H * 128, D, std=0.02)
+    wq_pk = torch.empty(D * H * 128, dtype=torch.bfloat16, device=gh.DEV)
     wo_pk = torch.empty(D * H * 128, dtype=torch.bfloat16, device=gh.DEV)
-    bx.beagle_xattn_prepare_wo(desc, wo, wo_pk)
+    bx.beagle_xattn_prepare_weights(desc, wq, wo, wq_pk, wo_pk)
     ws, ws_g = gh.workspace(desc, bx.BEAGLE_WS_DRAFT), gh.workspace(desc, bx.BEAGLE_WS_DRAFT)
     y_e = torch.full((M, D), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
     l_e = torch.full((H, M), float("nan"), dtype=torch.float32, device=gh.DEV)
-    bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_pk, L, None, 0, y_e, l_e, ws)
+    bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq_pk, wo_pk, L, None, 0, y_e, l_e, ws)
     torch.cuda.synchronize()
     y_g, l_g = torch.empty_like(y_e), torch.empty_like(l_e)
     gr = torch.cuda.CUDAGraph()
     with torch.cuda.graph(gr):
-        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_pk, L, None, 0, y_g, l_g, ws_g, torch.cuda.current_stream())
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq_pk, wo_pk, L, None, 0, y_g, l_g, ws_g, torch.cuda.current_stream())
     for rep in range(3):
         y_g.fill_(float("nan")); l_g.fill_(float("nan"))
         gr.replay()
         torch.cuda.synchronize()
         assert torch.equal(y_g.view(torch.int16), y_e.view(torch.int16)) and torch.equal(l_g, l_e), rep
-        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq, wo_pk, L, None, 0, y_e, l_e, ws)   # eager work in between
+        bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq_pk, wo_pk, L, None, 0, y_e, l_e, ws)   # eager work in between
         torch.cuda.synchronize()
