@@ -265,10 +265,10 @@ def packed_strips(w):
     return out
 
 
-def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True):
+def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, check=True, desc=None):
     """run_draft_tree through the prepared-weights entry points: wq and wo are packed by beagle_xattn_prepare_weights
     on the device, then beagle_xattn_draft_step_prepared runs on the results.  Also returns the packed matrices."""
-    d = desc_of(cfg, 0, scale)
+    d = desc if desc is not None else desc_of(cfg, 0, scale)
     M, D, H = cfg.seq_q, cfg.hidden, cfg.n_q_heads
     t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
     wq_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)

@@ -172,3 +172,22 @@ def test_bf16_draft_step_rotates_the_queries(M, rows, H, G, D, explicit):
     y1, l1 = gh.run_draft(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], desc=gh.desc_of(cfg, 0, rope_base=123.0))
     assert np.array_equal(y0, y1) and np.array_equal(l0, l1)
     assert not np.allclose(y0, y, atol=1e-3)
+
+
+@pytest.mark.parametrize("M,rows,H,G,D,explicit", [(1, 300, 4, 4, 512, False), (10, 300, 4, 4, 512, True), (16, 1000, 8, 2, 1024, True)])
+def test_bf16_draft_step_on_packed_weights_rotates_the_queries(M, rows, H, G, D, explicit):
+    """The same step through beagle_xattn_draft_step_prepared: the query projection hands the attention kernel one
+    unrounded slice of q, which it rotates as before."""
+    d = 128
+    cfg = synth.CONFIGS["c4"].with_(batch=1, seq_q=M, seq_kv=rows, hidden=D, n_q_heads=H, n_kv_heads=G, head_dim=d, seed_base=960 + M)
+    inp = synth.make_inputs(cfg, with_dy=False)
+    kc, vc = orc.kv_append(np.zeros((rows, G, d)), np.zeros((rows, G, d)), 0, inp["xkv"][0], inp["wk"], inp["wv"],
+                           n_kv_heads=G, rope=dict(base=10000.0, k_pos=np.arange(rows)))
+    kc, vc = synth.round_to_bf16(kc.astype(np.float32)), synth.round_to_bf16(vc.astype(np.float32))
+    q_pos = rows + np.arange(M) // 10 if explicit else np.full(M, rows)
+    pos_dev = torch.tensor(q_pos, dtype=torch.int32, device=gh.DEV) if explicit else None
+    ref = orc.draft_step(inp["xq"][0], kc, vc, inp["wq"], inp["wo"], n_q_heads=H, n_kv_heads=G, rope=dict(base=10000.0, q_pos=q_pos))
+    y, lse, _ = gh.run_draft_prepared(cfg, inp["xq"][0], kc, vc, inp["wq"], inp["wo"], rows, np.zeros((M, 0), bool),
+                                      desc=gh.desc_of(cfg, bx.BEAGLE_FLAG_ROPE, rope_positions=pos_dev))
+    assert gh.max_abs(y, ref["y"]) <= OUT_ABS and gh.rel_fro(y, ref["y"]) <= OUT_FRO, gh.rel_fro(y, ref["y"])
+    assert gh.max_abs(lse, ref["lse"]) <= 1e-3, gh.max_abs(lse, ref["lse"])
