@@ -606,7 +606,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
                               draft_tokens_per_s=round(M / (us * 1e-6)), bytes=call_bytes,
                               kernel_us_bracketed=kern)
         if prep_us:
-            res["M%d" % M]["prepared_wo"] = dict(us_per_call=round(prep_us, 2), gbs=round(call_bytes / prep_us / 1e3, 1),
+            res["M%d" % M]["packed_weights"] = dict(us_per_call=round(prep_us, 2), gbs=round(call_bytes / prep_us / 1e3, 1),
                                                  pct_hbm_peak=round(100 * call_bytes / prep_us / 1e3 / PEAK_HBM_GBS, 2))
         att = kern.get("draft_attn")
         roof["M%d" % M] = dict(
@@ -614,7 +614,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
             bytes=call_bytes, avg_us=round(us, 2), median_us=spread.get("median"), min_us=spread.get("min"), achieved=round(call_bytes / us / 1e3, 1), peak=PEAK_HBM_GBS,
             unit="GB/s", frac=round(call_bytes / us / 1e3 / PEAK_HBM_GBS, 4),
             graph_replay=dict(avg_us=round(graph_us, 2), frac=round(call_bytes / graph_us / 1e3 / PEAK_HBM_GBS, 4)) if graph_us else None,
-            prepared_wo=dict(entry="beagle_xattn_draft_step_prepared (wq, wo packed once per model load; same bytes per call)",
+            packed_weights=dict(entry="beagle_xattn_draft_step_prepared (wq, wo packed once per model load; same bytes per call)",
                              avg_us=round(prep_us, 2), achieved=round(call_bytes / prep_us / 1e3, 1),
                              frac=round(call_bytes / prep_us / 1e3 / PEAK_HBM_GBS, 4)) if prep_us else None,
             frac_of_read_probe=round(probe["whole_step_134MB"]["us"] / min(best, prep_us or best), 4),
@@ -688,7 +688,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         bx.beagle_xattn_block_draft_step_prepared(desc, prm, bx.make_block_decode_weights(**tw), x, kc, vc, L - T, tmd, 2,
                                                   hb, lse, bws, stream)
 
-    for name, fn in (("tree_M10_T50", tree_call), ("tree_M10_T50_prepared_wo", tree_prepared_call),
+    for name, fn in (("tree_M10_T50", tree_call), ("tree_M10_T50_packed_weights", tree_prepared_call),
                      ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call),
                      ("block_M10_T50_F11008_prepared", block_prepared_call)):
         us = _time_calls(torch, fn, nset, 50)
