@@ -414,10 +414,17 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
  *     caller-owned, 16-byte aligned, each the size of its source): wq_pk from
  *     params->wq [D, H*d], wo_pk from params->wo [H*d, D], w_gate_pk, w_up_pk from [D, F], w_down_pk from
  *     [F, D].  Once per model load.  bf16 with D % 128 == 0 and F % 128 == 0,
- *     else BEAGLE_ERR_UNSUPPORTED.
+ *     else BEAGLE_ERR_UNSUPPORTED.  The gains of the two normalisations are
+ *     folded into the matrices that read the normalised rows: wq_pk packs
+ *     diag(g_q) wq, w_gate_pk and w_up_pk pack diag(g_mlp) w_gate / w_up (each
+ *     product rounded to bf16), for whichever of g_q, g_mlp is not NULL.
  *   beagle_xattn_block_draft_step_prepared: beagle_xattn_block_draft_step with
  *     params->wq, wo, w_gate, w_up, w_down replaced by `dw` (those five fields
- *     of params are not read; the gains, ffn and rms_eps are).  Same definition
+ *     of params are not read; ffn and rms_eps are, and g_q, g_mlp only as
+ *     switches: non-NULL exactly where they were when `dw` was prepared).  The
+ *     two normalisations run inside the projections that follow them (the
+ *     row factor 1 / sqrt(mean(x^2) + eps) multiplies the finished sums), so
+ *     the normalised rows are never rounded to bf16 on their own.  Same definition
  *     of h and lse; sums run in a different fixed order, so results agree with
  *     the plain entry point to rounding, not bitwise.  1 <= seq_q <=
  *     BEAGLE_PREPARED_MAX_QUERIES, bf16, D % 128 == 0, F % 128 == 0;

@@ -690,7 +690,7 @@ beagle_status draft_step_impl(const beagle_xattn_desc* desc,
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
     a.x = x_draft; a.kc = k_cache; a.vc = v_cache; a.y = y; a.lse = lse; a.ws = workspace;
-    if (wo_packed) { a.wq_pk = wq; a.wo_pk = wo; } else { a.wq = wq; a.wo = wo; }
+    if (wo_packed) { a.wq_pk = wq; a.wo_pk = wo; a.x_norm_eps = -1.f; } else { a.wq = wq; a.wo = wo; }
     a.tree = tree; a.n_true = n_true; a.tree_words = words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     launch_decode_bf16(a, s);
@@ -774,8 +774,8 @@ beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc, const 
   for (const void* q : ptrs) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
   if (!d.bf16 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
   (void)hipGetLastError();
-  if (wq) launch_pack_strips_bf16(wq, wq_pk, (int32_t)d.D, (int32_t)d.HD, (hipStream_t)hip_stream);
-  if (wo) launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, (hipStream_t)hip_stream);
+  if (wq) launch_pack_strips_bf16(wq, wq_pk, (int32_t)d.D, (int32_t)d.HD, nullptr, (hipStream_t)hip_stream);
+  if (wo) launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, nullptr, (hipStream_t)hip_stream);
   return hip_status();
 }
 

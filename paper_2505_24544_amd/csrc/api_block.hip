@@ -307,13 +307,14 @@ beagle_status block_draft_step_impl(const beagle_xattn_desc* desc, const beagle_
 
   // y = Attn(RMSNorm(x)) + x
   const void* xn = x_draft;
-  if (p->g_q) { launch_rmsnorm_fwd(d.bf16, x_draft, p->g_q, base + w.xn, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_q"); xn = base + w.xn; }
+  // (on packed weights the normalisations ride in the projections: gains in the matrices, row factors in the epilogues)
+  if (p->g_q && !dw) { launch_rmsnorm_fwd(d.bf16, x_draft, p->g_q, base + w.xn, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_q"); xn = base + w.xn; }
   if (d.bf16) {
     DecodeArgs a; memset(&a, 0, sizeof(a));
     a.M = (int32_t)d.S; a.L = (int32_t)d.L; a.H = (int32_t)d.H; a.G = (int32_t)d.G; a.d = (int32_t)d.d;
     a.D = (int32_t)d.D; a.scale = d.scale;
     a.x = xn; a.kc = k_cache; a.vc = v_cache; a.y = y; a.lse = lse; a.ws = base + w.step;
-    if (dw) { a.wq_pk = wq; a.wo_pk = wo; } else { a.wq = wq; a.wo = wo; }
+    if (dw) { a.wq_pk = wq; a.wo_pk = wo; a.x_norm_eps = p->g_q ? p->rms_eps : -1.f; } else { a.wq = wq; a.wo = wo; }
     a.tree = tree_mask; a.n_true = n_true; a.tree_words = mask_words;
     a.rope = d.rope ? 1 : 0; a.rope_base = d.rope_base; a.rope_pos = d.rope_pos;
     a.y_res = x_draft;
@@ -338,9 +339,10 @@ beagle_status block_draft_step_impl(const beagle_xattn_desc* desc, const beagle_
   }
   // h = MLP(RMSNorm(y)) + y
   const void* z = y;
-  if (p->g_mlp) { launch_rmsnorm_fwd(d.bf16, y, p->g_mlp, base + w.z, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_mlp"); z = base + w.z; }
+  if (p->g_mlp && !dw) { launch_rmsnorm_fwd(d.bf16, y, p->g_mlp, base + w.z, (float*)(base + w.rinv), d.S, D, p->rms_eps, s, "draft_norm_mlp"); z = base + w.z; }
   if (d.bf16 && dw) {
-    launch_block_mlp_strip_bf16(z, w_gate, w_up, w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F, base + w.mlp, s);
+    launch_block_mlp_strip_bf16(z, w_gate, w_up, w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F,
+                                p->g_mlp ? p->rms_eps : -1.f, base + w.mlp, s);
   } else if (d.bf16) {
     launch_block_mlp_bf16(z, p->w_gate, p->w_up, p->w_down, y, h, (int32_t)d.S, (int32_t)d.D, (int32_t)F, base + w.mlp, s);
   } else {
@@ -393,11 +395,12 @@ beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, 
   if (!d.bf16 || F % 128 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
-  launch_pack_strips_bf16(p->wq, dw->wq_pk, (int32_t)d.D, (int32_t)d.HD, s);
-  launch_pack_strips_bf16(p->wo, dw->wo_pk, (int32_t)d.HD, (int32_t)d.D, s);
-  launch_pack_strips_bf16(p->w_gate, dw->w_gate_pk, (int32_t)d.D, F, s);
-  launch_pack_strips_bf16(p->w_up, dw->w_up_pk, (int32_t)d.D, F, s);
-  launch_pack_strips_bf16(p->w_down, dw->w_down_pk, F, (int32_t)d.D, s);
+  // the gains of the two normalisations go into the matrices that read the normalised rows
+  launch_pack_strips_bf16(p->wq, dw->wq_pk, (int32_t)d.D, (int32_t)d.HD, p->g_q, s);
+  launch_pack_strips_bf16(p->wo, dw->wo_pk, (int32_t)d.HD, (int32_t)d.D, nullptr, s);
+  launch_pack_strips_bf16(p->w_gate, dw->w_gate_pk, (int32_t)d.D, F, p->g_mlp, s);
+  launch_pack_strips_bf16(p->w_up, dw->w_up_pk, (int32_t)d.D, F, p->g_mlp, s);
+  launch_pack_strips_bf16(p->w_down, dw->w_down_pk, F, (int32_t)d.D, nullptr, s);
   return hip_status();
 }
 

@@ -178,10 +178,11 @@ struct DecodeArgs {
   const void* y_res;   // optional residual added to y (storage type, [M,D])
   // optional: wq / wo packed for strip_gemm_kernel; then wq / wo is not read (needs strip_gemm_fits for M and its shape)
   const void* wq_pk; const void* wo_pk;
+  float x_norm_eps;    // with wq_pk: >= 0 applies RMSNorm's row factor to x inside the query projection (gain folded into wq_pk)
 };
 bool strip_gemm_fits(int32_t M, int32_t N, int32_t K);
 // W [K][N] row-major -> the packed layout that strip_gemm_kernel streams (K % 128 == 0, N % 16 == 0)
-void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, hipStream_t s);
+void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, const void* gain, hipStream_t s);
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D);
 void launch_decode_bf16(const DecodeArgs& a, hipStream_t s);
 void launch_read_probe(const void* buf, int64_t bytes, int wgs, uint32_t* sink, hipStream_t s);
@@ -196,7 +197,8 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
 // the same on packed weights: two strip launches, gate fused;
 // needs strip_gemm_fits(M, F, D) and strip_gemm_fits(M, D, F); ws: M * F bf16
 void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
-                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
+                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, float z_norm_eps, void* ws,
+                                 hipStream_t s);
 void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* kdst, void* vdst, int32_t n, int32_t N,
                            int32_t K, void* ws, hipStream_t s);
 

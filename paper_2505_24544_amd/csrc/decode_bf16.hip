@@ -379,7 +379,7 @@ template <int MODE, bool ROWS16, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
                                                             const bf16_t* __restrict__ Wt2, void* __restrict__ yout,
                                                             const bf16_t* __restrict__ res, int M, int N, int K,
-                                                            CombineArgs cb, int out_f32) {
+                                                            CombineArgs cb, int out_f32, float norm_eps) {
   using namespace dec;
   constexpr int ROWS = ROWS16 ? 16 : 8;             // activation rows kept per macro-step
   constexpr int ST_CH = ROWS16 ? 2 : 4;             // macro-steps per activation chunk
@@ -393,6 +393,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
   __shared__ __attribute__((aligned(16))) float red[NW][WAVES][16][16];
   __shared__ __attribute__((aligned(16))) float wsc[MODE == 1 ? WAVES : 1][64];
   __shared__ float winv[MODE == 1 ? WAVES : 1][8];
+  __shared__ float ssw[WAVES][16];                  // RMSNorm: each wave's share of the rows' sums of squares
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n0 = blockIdx.x * ST_N;
   const int S = K >> 7;                             // macro-steps; wave w takes s = w, w + 8, ...
@@ -405,6 +406,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
   f32x4_t acc[NW];
 #pragma unroll
   for (int w = 0; w < NW; ++w) acc[w] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float ssl[LPS];                       // RMSNorm: this lane's share of its rows' sums of squares
+#pragma unroll
+  for (int g = 0; g < LPS; ++g) ssl[g] = 0.f;
+  const bool rownorm = norm_eps >= 0.f;
   if (nst > 0) {                        // (a wave without a macro-step, K < 1024, only adds zeros below)
   // ---- activations.  Load q of chunk c covers rows 4 g + kg of step c ST_CH + i, (i, g) = divmod(q, LPS):
   // lane (kg, nl) reads chunk nl ^ row of its row and parks it at chunk nl, i.e. at lane * 16 of the 1 KB piece.
@@ -417,9 +422,22 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
           ars, (i < nst && row < M) ? (row * K + (wave + WAVES * i) * 128 + 8 * (nl ^ row)) * 2 : (int)0x80000000, 0, 0);
     }
   };
+  // RMSNorm of the activation rows (norm_eps >= 0; Eq. 1's block normalises each sublayer's input): the gain is folded
+  // into the packed weights and the row factor 1 / sqrt(mean(a^2) + eps) is applied to the finished sums, so all that is
+  // needed here is the rows' sums of squares, gathered while the rows pass through registers on their way to LDS.
+  // Load q of a chunk holds 8 values of row 4 (q % LPS) + kg; rows and steps past the end arrive as zeros.
   auto stage_park = [&](const xload_t (&av)[NLD], unsigned char* buf) {
 #pragma unroll
     for (int q = 0; q < NLD; ++q) *(xload_t*)(buf + ((q / LPS) * ROWS + 4 * (q % LPS)) * 256 + lane * 16) = av[q];
+    if (rownorm) {
+#pragma unroll
+      for (int q = 0; q < NLD; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float lo = __uint_as_float(av[q][e] << 16), hi = __uint_as_float(av[q][e] & 0xffff0000u);
+          ssl[q % LPS] += lo * lo + hi * hi;
+        }
+    }
   };
   xload_t av0[MODE == 1 ? 1 : NLD], av1[MODE == 1 ? 1 : NLD];
   float2 mlv = {-INFINITY, 0.f};
@@ -536,17 +554,35 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
   for (int w = 0; w < NW; ++w)
 #pragma unroll
     for (int e = 0; e < 4; ++e) red[w][wave][4 * kg + e][nl] = acc[w][e];
+  if (MODE != 1 && rownorm) {
+    // a row's 16 chunk lanes (same kg) add up, then the waves do below
+#pragma unroll
+    for (int g = 0; g < LPS; ++g) {
+      float t = ssl[g];
+      t += __shfl_xor(t, 1); t += __shfl_xor(t, 2); t += __shfl_xor(t, 4); t += __shfl_xor(t, 8);
+      if (nl == 0) ssw[wave][4 * g + kg] = t;
+    }
+    if (ROWS == 8 && lane < 8) ssw[wave][8 + lane] = 0.f;
+  }
   __syncthreads();
   if (tid < M * 16) {
     const int m = tid >> 4, n = tid & 15;
     float v = red[0][0][m][n];
 #pragma unroll
     for (int wv = 1; wv < WAVES; ++wv) v += red[0][wv][m][n];
+    float rn = 1.f;
+    if (MODE != 1 && rownorm) {
+      float ss = ssw[0][m];
+#pragma unroll
+      for (int wv = 1; wv < WAVES; ++wv) ss += ssw[wv][m];
+      rn = 1.f / sqrtf(ss / (float)K + norm_eps);
+      v *= rn;
+    }
     if constexpr (MODE == 2) {
       float g = red[NW - 1][0][m][n];
 #pragma unroll
       for (int wv = 1; wv < WAVES; ++wv) g += red[NW - 1][wv][m][n];
-      v = v / (1.f + expf(-v)) * g;                            // silu(gate) * up
+      v = v / (1.f + expf(-v)) * (g * rn);                     // silu(gate) * up
     }
     const int64_t o = (int64_t)m * N + n0 + n;
     if (res) v += __uint_as_float((uint32_t)res[o] << 16);
@@ -559,7 +595,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
 
 // The one-time re-layout of a weight matrix W [K][N] (row-major) for strip_gemm_kernel: one thread per 16 bytes of
 // the packed matrix (layout above).  K % 128 == 0, N % 16 == 0.
-__global__ __launch_bounds__(256) void pack_strips_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int K, int N) {
+// With a gain vector g [K] the packed matrix is diag(g) W (each product rounded to bf16): the gain of an RMSNorm in front
+// of the projection, so that the projection can take the un-normalised rows.
+__global__ __launch_bounds__(256) void pack_strips_kernel(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int K, int N,
+                                                          const bf16_t* __restrict__ gain) {
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;          // 16-byte piece of the output
   if (t >= (int64_t)K * N / 8) return;
   const int lane = (int)(t & 63), j = (int)((t >> 6) & 3);
@@ -568,14 +607,18 @@ __global__ __launch_bounds__(256) void pack_strips_kernel(const bf16_t* __restri
   const int k0 = 128 * m + 32 * j + 8 * (lane >> 4), n = 16 * sidx + (lane & 15);
   bf16_t v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = in[(int64_t)(k0 + e) * N + n];
+  for (int e = 0; e < 8; ++e) {
+    v[e] = in[(int64_t)(k0 + e) * N + n];
+    if (gain) v[e] = (bf16_t)(cvt_pk(__uint_as_float((uint32_t)v[e] << 16) * __uint_as_float((uint32_t)gain[k0 + e] << 16), 0.f) & 0xffffu);
+  }
   uint4 o = {(uint32_t)v[0] | ((uint32_t)v[1] << 16), (uint32_t)v[2] | ((uint32_t)v[3] << 16),
              (uint32_t)v[4] | ((uint32_t)v[5] << 16), (uint32_t)v[6] | ((uint32_t)v[7] << 16)};
   *(uint4*)(out + t * 8) = o;
 }
-void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, hipStream_t s) {
+void launch_pack_strips_bf16(const void* in, void* out, int32_t K, int32_t N, const void* gain, hipStream_t s) {
   const int64_t pieces = (int64_t)K * N / 8;
-  hipLaunchKernelGGL(pack_strips_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const bf16_t*)in, (bf16_t*)out, K, N);
+  hipLaunchKernelGGL(pack_strips_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const bf16_t*)in, (bf16_t*)out, K, N,
+                     (const bf16_t*)gain);
 }
 
 // ---------------------------------------------------------------------------
@@ -1215,7 +1258,7 @@ bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
 }
 // y = a W (+ res) on packed W; with wt2: y = silu(a W) * (a W2); with merge: a is merged from the attention partials (M = 1)
 void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, void* y, const bf16_t* res, int M, int N,
-                       int K, const CombineArgs* merge, bool out_f32, hipStream_t s) {
+                       int K, const CombineArgs* merge, bool out_f32, float norm_eps, hipStream_t s) {
   using namespace dec;
   const dim3 grid(N / ST_N);
   const CombineArgs cb = merge ? *merge : CombineArgs{};
@@ -1223,11 +1266,11 @@ void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, voi
   // one matrix: eight waves, one workgroup per CU (N / 16 is about the number of CUs for the attention's projections);
   // the feed-forward pair has several strips per CU: four waves and two workgroups per CU, so that one's start and
   // final reduction hide behind the other's stream
-  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
-  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
-  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
-  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
-  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f);
+  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
+  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
+  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
+  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
+  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
 }
 
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
@@ -1255,7 +1298,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
     const bf16_t* x = (const bf16_t*)a.x + (int64_t)m0 * a.D;
     if (a.wq_pk) {                    // packed Wq: the whole of k in one strip, so q arrives as a single slice
       ProfScope ps("draft_proj_q", s);
-      launch_strip_gemm(x, (const bf16_t*)a.wq_pk, nullptr, qpart, nullptr, Mp, HDt, a.D, nullptr, true, s);
+      launch_strip_gemm(x, (const bf16_t*)a.wq_pk, nullptr, qpart, nullptr, Mp, HDt, a.D, nullptr, true, a.x_norm_eps, s);
     } else {
       ProfScope ps("draft_proj_q", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
@@ -1282,7 +1325,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
       if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, false, s);
+        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, false, -1.f, s);
       } else {
         {
           ProfScope ps("draft_combine", s);
@@ -1290,7 +1333,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
                              w.Mpad, a.H, w.R, a.scale);
         }
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, false, s);
+        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, false, -1.f, s);
       }
       continue;
     }
@@ -1413,15 +1456,16 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
 }
 
 void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
-                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s) {
+                                 const void* y_res, void* h, int32_t M, int32_t D, int32_t F, float z_norm_eps, void* ws,
+                                 hipStream_t s) {
   bf16_t* mbuf = (bf16_t*)ws;
   {
     ProfScope ps("draft_mlp_gate_up", s);
-    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, false, s);
+    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, false, z_norm_eps, s);
   }
   {
     ProfScope ps("draft_mlp_down", s);
-    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, false, s);
+    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, false, -1.f, s);
   }
 }
 

@@ -219,13 +219,22 @@ def test_bf16_block_draft_step_on_prepared_weights(M, rows, H, G, D, ffn, gains,
     n_true = rows - T if T else None
     ref = _ref(cfg, bi, kc, vc, gains, n_true, tree)
     h, lse, tw = _run_prepared(cfg, bi, kc, vc, ffn, gains, n_true, tree)
+    # packing moves values, nothing else -- except that the gain of a normalisation is folded into the matrices that
+    # read the normalised rows (each product of two bf16 values rounded to bf16 once)
+    fold = {"wq": "g_q", "w_gate": "g_mlp", "w_up": "g_mlp"} if gains else {}
     for n, src in (("wq_pk", "wq"), ("wo_pk", "wo"), ("w_gate_pk", "w_gate"), ("w_up_pk", "w_up"), ("w_down_pk", "w_down")):
-        assert np.array_equal(tw[n], gh.packed_strips(bi[src])), n   # packing moves values, nothing else
+        w = bi[src]
+        if src in fold:
+            w = synth.round_to_bf16(bi[fold[src]].astype(np.float32)[:, None] * w.astype(np.float32))
+        assert np.array_equal(tw[n], gh.packed_strips(w)), n
     assert np.isfinite(h).all()
     assert gh.rel_fro(h, ref["h"]) <= OUT_FRO, gh.rel_fro(h, ref["h"])
     assert gh.max_abs(lse, ref["lse"]) <= 4e-3, gh.max_abs(lse, ref["lse"])
-    h0, _ = _run(cfg, bi, kc, vc, ffn, gains, n_true, tree)    # next to the plain entry point: rounding apart
-    assert gh.rel_fro(h, h0) <= 4e-3, gh.rel_fro(h, h0)
+    # next to the plain entry point: rounding apart (the plain path rounds the normalised rows to bf16, this one the
+    # gain-times-weight products: two independent sets of bf16 roundings, each within the oracle tolerance above)
+    h0, _ = _run(cfg, bi, kc, vc, ffn, gains, n_true, tree)
+    assert gh.rel_fro(h, h0) <= 8e-3, gh.rel_fro(h, h0)
+    assert gh.rel_fro(h, ref["h"]) <= 1.25 * gh.rel_fro(h0, ref["h"]) + 1e-3      # and no further from the oracle than it
 
 
 def test_bf16_block_draft_step_on_prepared_weights_at_the_7b_shape():
