@@ -529,7 +529,7 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
     wq_pk = torch.empty(nset, D * H * hd, dtype=torch.bfloat16, device=dev)
     wo_pk = torch.empty(nset, D * H * hd, dtype=torch.bfloat16, device=dev)
     for i in range(nset):
-        bx.beagle_xattn_prepare_weights(dm.desc_of(cfg.with_(seq_q=1)), sets[i][2], sets[i][3], wq_pk[i], wo_pk[i])
+        bx.beagle_xattn_prepare_weights(dm.desc_of(cfg.with_(seq_q=1)), wq=sets[i][2], wo=sets[i][3], wq_pk=wq_pk[i], wo_pk=wo_pk[i])
     res, roof = {}, {}
     stream = torch.cuda.current_stream()
 
@@ -657,6 +657,13 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
         kc, vc, _, _ = sets[r % nset]
         bx.beagle_xattn_kv_append(adesc, x, wk, wv, kc, vc, L - T, aws, stream)
 
+    wk_pk, wv_pk = torch.empty_like(wk).view(-1), torch.empty_like(wv).view(-1)
+    bx.beagle_xattn_prepare_weights(adesc, wk=wk, wv=wv, wk_pk=wk_pk, wv_pk=wv_pk)
+
+    def append_packed_call(r):
+        kc, vc, _, _ = sets[r % nset]
+        bx.beagle_xattn_kv_append_prepared(adesc, x, wk_pk, wv_pk, kc, vc, L - T, stream)
+
     # the whole draft block per draft step (Eq. 1): the tree step above + RMSNorm, residuals and the feed-forward
     # layer of the 7B shape; its three matrices rotate through four sets (1.1 GB) like the rest
     F = 11008
@@ -689,7 +696,8 @@ def bench_decode(torch, bx, dm, synth, graphs=True):
                                                   hb, lse, bws, stream)
 
     for name, fn in (("tree_M10_T50", tree_call), ("tree_M10_T50_packed_weights", tree_prepared_call),
-                     ("kv_append_n10", append_call), ("block_M10_T50_F11008", block_call),
+                     ("kv_append_n10", append_call), ("kv_append_n10_packed_weights", append_packed_call),
+                     ("block_M10_T50_F11008", block_call),
                      ("block_M10_T50_F11008_prepared", block_prepared_call)):
         us = _time_calls(torch, fn, nset, 50)
         if name.startswith("tree"):

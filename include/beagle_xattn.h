@@ -410,7 +410,7 @@ beagle_status beagle_xattn_block_draft_step(const beagle_xattn_desc* desc, const
  * feed-forward matrices packed, so that each projection is one launch of 16-column strips
  * over the whole of k -- no k split, no partial sums, no launch to add them,
  * and the SiLU gate runs in the epilogue of the gate/up projection.
- *   beagle_xattn_block_prepare_weights: fills the five buffers of `dw` (DEVICE,
+ *   beagle_xattn_block_prepare_weights: fills the buffers of `dw` (DEVICE,
  *     caller-owned, 16-byte aligned, each the size of its source): wq_pk from
  *     params->wq [D, H*d], wo_pk from params->wo [H*d, D], w_gate_pk, w_up_pk from [D, F], w_down_pk from
  *     [F, D].  Once per model load.  bf16 with D % 128 == 0 and F % 128 == 0,
@@ -435,6 +435,8 @@ typedef struct {
   int32_t struct_size;          /* sizeof(beagle_block_decode_weights); checked  */
   int32_t reserved;             /* 0                                             */
   void *wq_pk, *wo_pk;          /* packed wq, wo: D * H*d elements each          */
+  void *wk_pk, *wv_pk;          /* packed wk, wv: D * G*d elements each; both NULL
+                                   if the cache is appended to another way       */
   void *w_gate_pk, *w_up_pk;    /* packed w_gate, w_up: D * F elements each      */
   void *w_down_pk;              /* packed w_down: F * D elements                 */
 } beagle_block_decode_weights;
@@ -444,6 +446,13 @@ beagle_status beagle_xattn_block_draft_step_prepared(const beagle_xattn_desc* de
     const beagle_block_decode_weights* dw, const void* x_draft, const void* k_cache, const void* v_cache,
     int32_t n_true, const uint32_t* tree_mask, int32_t mask_words, void* h, float* lse,
     void* workspace, size_t workspace_bytes, void* hip_stream);
+/* beagle_xattn_block_kv_append on dw->wk_pk, dw->wv_pk (which beagle_xattn_block_prepare_weights fills, with
+ * diag(g_kv) folded in, when params->wk, wv and both destinations are given): the key/value normalisation and both
+ * projections in one launch, no workspace.  Of params only rms_eps is read, and g_kv as a switch.  Up to
+ * BEAGLE_PREPARED_MAX_QUERIES new states, bf16, D % 128 == 0; BEAGLE_ERR_UNSUPPORTED otherwise. */
+beagle_status beagle_xattn_block_kv_append_prepared(const beagle_xattn_desc* desc, const beagle_block_params* params,
+    const beagle_block_decode_weights* dw, const void* x_new, void* k_cache, void* v_cache, int32_t pos,
+    void* hip_stream);
 
 /*
  * Cache append for the block: new states (true ones, or drafted ones = earlier
@@ -514,10 +523,11 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
  * and no launch to add them.  Weights are fixed while drafting (section 4.1:
  * the draft model is trained beforehand), so packing is paid once per model
  * load, not per step.  A packed matrix has the size of the original.
- *   beagle_xattn_prepare_weights: packs wq [D, H*d] into wq_pk and wo [H*d, D]
- *     into wo_pk (all DEVICE; a source and its destination may both be NULL to
- *     skip that matrix; a destination must not overlap its source).  bf16 with
- *     D % 128 == 0 only (BEAGLE_ERR_UNSUPPORTED otherwise).
+ *   beagle_xattn_prepare_weights: packs wq [D, H*d], wk, wv [D, G*d] and wo
+ *     [H*d, D] into wq_pk, wk_pk, wv_pk, wo_pk (all DEVICE; a source and its
+ *     destination may both be NULL to skip that matrix, at least one pair must be
+ *     given; a destination must not overlap its source).  bf16 with D % 128 == 0
+ *     only (BEAGLE_ERR_UNSUPPORTED otherwise).
  *   beagle_xattn_draft_step_prepared: beagle_xattn_draft_step_tree with wq_pk,
  *     wo_pk in the place of wq, wo (n_true == seq_kv and tree_mask == NULL give
  *     the plain draft step).  Same definition of y and lse; sums run in a
@@ -528,8 +538,15 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
  * Workspace: beagle_xattn_workspace_bytes(desc, BEAGLE_WS_DRAFT).
  */
 #define BEAGLE_PREPARED_MAX_QUERIES 16
-beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc, const void* wq, const void* wo,
-    void* wq_pk, void* wo_pk, void* hip_stream);
+beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc,
+    const void* wq, const void* wk, const void* wv, const void* wo,
+    void* wq_pk, void* wk_pk, void* wv_pk, void* wo_pk, void* hip_stream);
+/* beagle_xattn_kv_append on packed wk_pk, wv_pk: one launch, no partial sums, hence no workspace.  Serves
+ * 1 <= seq_q (the number of new states) <= BEAGLE_PREPARED_MAX_QUERIES, bf16, D % 128 == 0;
+ * BEAGLE_ERR_UNSUPPORTED otherwise. */
+beagle_status beagle_xattn_kv_append_prepared(const beagle_xattn_desc* desc,
+    const void* x_new, const void* wk_pk, const void* wv_pk,
+    void* k_cache, void* v_cache, int32_t pos, void* hip_stream);
 beagle_status beagle_xattn_draft_step_prepared(const beagle_xattn_desc* desc,
     const void* x_draft, const void* k_cache, const void* v_cache,
     const void* wq_pk, const void* wo_pk, int32_t n_true,

@@ -28,7 +28,7 @@ STATUS_NAMES = {0: "BEAGLE_OK", 1: "BEAGLE_ERR_NULL", 2: "BEAGLE_ERR_SHAPE", 3: 
 
 EXPORTS = (
     "beagle_xattn_workspace_bytes", "beagle_xattn_fwd", "beagle_xattn_bwd", "beagle_xattn_draft_step",
-    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_prepare_weights",
+    "beagle_xattn_draft_step_static", "beagle_xattn_draft_step_tree", "beagle_xattn_prepare_weights", "beagle_xattn_kv_append_prepared", "beagle_xattn_block_kv_append_prepared",
     "beagle_xattn_draft_step_prepared", "beagle_xattn_kv_append", "beagle_xattn_fwd_sim", "beagle_xattn_bwd_sim",
     "beagle_xattn_sim_save",
     "beagle_xattn_block_workspace_bytes", "beagle_xattn_block_fwd", "beagle_xattn_block_bwd",
@@ -78,7 +78,7 @@ class beagle_block_params(C.Structure):
 
 class beagle_block_decode_weights(C.Structure):
     _fields_ = [("struct_size", C.c_int32), ("reserved", C.c_int32)] + \
-               [(n, _VP) for n in ("wq_pk", "wo_pk", "w_gate_pk", "w_up_pk", "w_down_pk")]
+               [(n, _VP) for n in ("wq_pk", "wo_pk", "wk_pk", "wv_pk", "w_gate_pk", "w_up_pk", "w_down_pk")]
 
 
 class beagle_block_saved(C.Structure):
@@ -181,7 +181,12 @@ def lib() -> C.CDLL:
     L.beagle_xattn_draft_step_prepared.restype = C.c_int
     L.beagle_xattn_draft_step_prepared.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
     L.beagle_xattn_prepare_weights.restype = C.c_int
-    L.beagle_xattn_prepare_weights.argtypes = [dp, vp, vp, vp, vp, vp]
+    L.beagle_xattn_prepare_weights.argtypes = [dp] + [vp] * 9
+    L.beagle_xattn_kv_append_prepared.restype = C.c_int
+    L.beagle_xattn_kv_append_prepared.argtypes = [dp, vp, vp, vp, vp, vp, C.c_int32, vp]
+    L.beagle_xattn_block_kv_append_prepared.restype = C.c_int
+    L.beagle_xattn_block_kv_append_prepared.argtypes = [dp, C.POINTER(beagle_block_params), C.POINTER(beagle_block_decode_weights),
+                                                        vp, vp, vp, C.c_int32, vp]
     L.beagle_xattn_kv_append.restype = C.c_int
     L.beagle_xattn_kv_append.argtypes = [dp] + [vp] * 5 + [C.c_int32, vp, C.c_size_t, vp]
     L.beagle_xattn_mask_row_limit.restype = C.c_int
@@ -344,9 +349,24 @@ def beagle_xattn_draft_step_tree(desc, x_draft, k_cache, v_cache, wq, wo, n_true
     return _check(st, "beagle_xattn_draft_step_tree", check)
 
 
-def beagle_xattn_prepare_weights(desc, wq, wo, wq_pk, wo_pk, stream=None, *, check=True) -> int:
-    st = lib().beagle_xattn_prepare_weights(C.byref(desc), _ptr(wq), _ptr(wo), _ptr(wq_pk), _ptr(wo_pk), _stream(stream))
+def beagle_xattn_prepare_weights(desc, wq=None, wk=None, wv=None, wo=None, wq_pk=None, wk_pk=None, wv_pk=None, wo_pk=None,
+                                 stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_prepare_weights(C.byref(desc), *(_ptr(t) for t in (wq, wk, wv, wo, wq_pk, wk_pk, wv_pk, wo_pk)),
+                                            _stream(stream))
     return _check(st, "beagle_xattn_prepare_weights", check)
+
+
+def beagle_xattn_kv_append_prepared(desc, x_new, wk_pk, wv_pk, k_cache, v_cache, pos, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_kv_append_prepared(C.byref(desc), *(_ptr(t) for t in (x_new, wk_pk, wv_pk, k_cache, v_cache)),
+                                               int(pos), _stream(stream))
+    return _check(st, "beagle_xattn_kv_append_prepared", check)
+
+
+def beagle_xattn_block_kv_append_prepared(desc, params, dw, x_new, k_cache, v_cache, pos, stream=None, *, check=True) -> int:
+    st = lib().beagle_xattn_block_kv_append_prepared(
+        C.byref(desc), C.byref(params) if params is not None else None, C.byref(dw) if dw is not None else None,
+        _ptr(x_new), _ptr(k_cache), _ptr(v_cache), int(pos), _stream(stream))
+    return _check(st, "beagle_xattn_block_kv_append_prepared", check)
 
 
 def beagle_xattn_draft_step_prepared(desc, x_draft, k_cache, v_cache, wq_pk, wo_pk, n_true, tree_mask, mask_words, y, lse,

@@ -339,11 +339,13 @@ void xattn_bwd_sim_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy,
 
 // K / V rows of the n = d.S new states into cache rows pos .. pos + n - 1 (+ rotary embedding of the K rows).
 void kv_append_run(const Dims& d, const void* x_new, const void* wk, const void* wv, void* k_cache, void* v_cache,
-                   int32_t pos, void* workspace, hipStream_t s) {
+                   int32_t pos, void* workspace, hipStream_t s, float packed_norm_eps) {
   // rows pos .. pos + n - 1 of the caches are the output matrices (leading dimension G*d)
   char* kdst = (char*)k_cache + (size_t)pos * d.GD * d.esz;
   char* vdst = (char*)v_cache + (size_t)pos * d.GD * d.esz;
-  if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
+  if (packed_norm_eps == packed_norm_eps) {      // not NaN: packed weights (the caller has checked strip_gemm_fits)
+    launch_kv_append_strip_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, packed_norm_eps, s);
+  } else if (d.bf16 && kv_append_bf16_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D)) {
     // a handful of states: HBM-bound on Wk and Wv, so the split-k streaming projection of the draft step
     launch_kv_append_bf16(x_new, wk, wv, kdst, vdst, (int32_t)d.S, (int32_t)d.GD, (int32_t)d.D, workspace, s);
   } else {
@@ -765,17 +767,42 @@ beagle_status beagle_xattn_draft_step_tree(const beagle_xattn_desc* desc,
                          workspace_bytes, hip_stream);
 }
 
-beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc, const void* wq, const void* wo,
-    void* wq_pk, void* wo_pk, void* hip_stream) {
+beagle_status beagle_xattn_prepare_weights(const beagle_xattn_desc* desc,
+    const void* wq, const void* wk, const void* wv, const void* wo,
+    void* wq_pk, void* wk_pk, void* wv_pk, void* wo_pk, void* hip_stream) {
   Dims d; beagle_status st = check_desc(desc, true, &d);
   if (st != BEAGLE_OK) return st;
-  if ((!wq) != (!wq_pk) || (!wo) != (!wo_pk) || (!wq && !wo)) return BEAGLE_ERR_NULL;
-  const void* ptrs[] = {wq, wo, wq_pk, wo_pk};
-  for (const void* q : ptrs) if (q && !aligned16(q)) return BEAGLE_ERR_ALIGN;
-  if (!d.bf16 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
+  const void* src[] = {wq, wk, wv, wo};
+  void* dst[] = {wq_pk, wk_pk, wv_pk, wo_pk};
+  int given = 0;
+  for (int i = 0; i < 4; ++i) {
+    if ((!src[i]) != (!dst[i])) return BEAGLE_ERR_NULL;
+    if (src[i]) ++given;
+  }
+  if (!given) return BEAGLE_ERR_NULL;
+  for (int i = 0; i < 4; ++i) if (src[i] && (!aligned16(src[i]) || !aligned16(dst[i]))) return BEAGLE_ERR_ALIGN;
+  if (!d.bf16 || d.D % 128 || d.HD % 128 || d.GD % 16) return BEAGLE_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
-  if (wq) launch_pack_strips_bf16(wq, wq_pk, (int32_t)d.D, (int32_t)d.HD, nullptr, (hipStream_t)hip_stream);
-  if (wo) launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, nullptr, (hipStream_t)hip_stream);
+  if (wq) launch_pack_strips_bf16(wq, wq_pk, (int32_t)d.D, (int32_t)d.HD, nullptr, s);
+  if (wk) launch_pack_strips_bf16(wk, wk_pk, (int32_t)d.D, (int32_t)d.GD, nullptr, s);
+  if (wv) launch_pack_strips_bf16(wv, wv_pk, (int32_t)d.D, (int32_t)d.GD, nullptr, s);
+  if (wo) launch_pack_strips_bf16(wo, wo_pk, (int32_t)d.HD, (int32_t)d.D, nullptr, s);
+  return hip_status();
+}
+
+beagle_status beagle_xattn_kv_append_prepared(const beagle_xattn_desc* desc,
+    const void* x_new, const void* wk_pk, const void* wv_pk, void* k_cache, void* v_cache, int32_t pos, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  const void* ptrs[] = {x_new, wk_pk, wv_pk, k_cache, v_cache};
+  for (const void* p : ptrs) if (!p) return BEAGLE_ERR_NULL;
+  for (const void* p : ptrs) if (!aligned16(p)) return BEAGLE_ERR_ALIGN;
+  if (!(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))) return BEAGLE_ERR_UNSUPPORTED;
+  if (pos < 0 || (int64_t)pos + d.S > d.L) return BEAGLE_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  kv_append_run(d, x_new, wk_pk, wv_pk, k_cache, v_cache, pos, nullptr, s, -1.f);
   return hip_status();
 }
 

@@ -391,8 +391,15 @@ beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, 
   const void* ptrs[] = {p->wq, p->wo, p->w_gate, p->w_up, p->w_down, dw->wq_pk, dw->wo_pk, dw->w_gate_pk, dw->w_up_pk, dw->w_down_pk};
   for (const void* q : ptrs) if (!q) return BEAGLE_ERR_NULL;
   for (const void* q : ptrs) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
+  // the key/value side is optional: both sources and both destinations, or none
+  const bool kv = p->wk || p->wv || dw->wk_pk || dw->wv_pk;
+  if (kv) {
+    const void* kvp[] = {p->wk, p->wv, dw->wk_pk, dw->wv_pk};
+    for (const void* q : kvp) if (!q) return BEAGLE_ERR_NULL;
+    for (const void* q : kvp) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
+  }
   const int32_t F = p->ffn;
-  if (!d.bf16 || F % 128 || d.D % 128 || d.HD % 128) return BEAGLE_ERR_UNSUPPORTED;
+  if (!d.bf16 || F % 128 || d.D % 128 || d.HD % 128 || d.GD % 16) return BEAGLE_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
   (void)hipGetLastError();
   // the gains of the two normalisations go into the matrices that read the normalised rows
@@ -401,6 +408,29 @@ beagle_status beagle_xattn_block_prepare_weights(const beagle_xattn_desc* desc, 
   launch_pack_strips_bf16(p->w_gate, dw->w_gate_pk, (int32_t)d.D, F, p->g_mlp, s);
   launch_pack_strips_bf16(p->w_up, dw->w_up_pk, (int32_t)d.D, F, p->g_mlp, s);
   launch_pack_strips_bf16(p->w_down, dw->w_down_pk, F, (int32_t)d.D, nullptr, s);
+  if (kv) {
+    launch_pack_strips_bf16(p->wk, dw->wk_pk, (int32_t)d.D, (int32_t)d.GD, p->g_kv, s);
+    launch_pack_strips_bf16(p->wv, dw->wv_pk, (int32_t)d.D, (int32_t)d.GD, p->g_kv, s);
+  }
+  return hip_status();
+}
+
+beagle_status beagle_xattn_block_kv_append_prepared(const beagle_xattn_desc* desc, const beagle_block_params* p,
+    const beagle_block_decode_weights* dw, const void* x_new, void* k_cache, void* v_cache, int32_t pos, void* hip_stream) {
+  Dims d; beagle_status st = check_desc(desc, true, &d);
+  if (st != BEAGLE_OK) return st;
+  if (!p || !dw) return BEAGLE_ERR_NULL;
+  if (p->struct_size != (int32_t)sizeof(beagle_block_params) || p->reserved != 0 || !decode_weights_ok(dw)) return BEAGLE_ERR_SHAPE;
+  if (!(p->rms_eps >= 0.f) || isinf(p->rms_eps)) return BEAGLE_ERR_SHAPE;
+  const void* ptrs[] = {x_new, dw->wk_pk, dw->wv_pk, k_cache, v_cache};
+  for (const void* q : ptrs) if (!q) return BEAGLE_ERR_NULL;
+  for (const void* q : ptrs) if (!aligned16(q)) return BEAGLE_ERR_ALIGN;
+  if (!(d.bf16 && strip_gemm_fits((int32_t)d.S, (int32_t)d.GD, (int32_t)d.D))) return BEAGLE_ERR_UNSUPPORTED;
+  if (pos < 0 || (int64_t)pos + d.S > d.L) return BEAGLE_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  // the key/value normalisation rides in the projection: gain in the packed matrices, row factor in the epilogue
+  kv_append_run(d, x_new, dw->wk_pk, dw->wv_pk, k_cache, v_cache, pos, nullptr, s, p->g_kv ? p->rms_eps : -1.f);
   return hip_status();
 }
 

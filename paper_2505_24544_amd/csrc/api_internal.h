@@ -60,8 +60,10 @@ void xattn_bwd_sim_run(const Dims& d, bool need_dxkv, bool wf32, const void* dy,
                        const void* vp_save, const void* o_save, const float* lse, int32_t sim_step, void* dxq, void* dxkv,
                        void* dxpred, void* dwq, void* dwk, void* dwv, void* dwo, char* base, const void* dxq_res,
                        hipStream_t s);
+// packed_norm_eps: NaN = wk, wv in their stored layout; otherwise they are packed for strip_gemm_kernel, with (>= 0) or
+// without (< 0) the row factor of an RMSNorm in front of them (its gain folded into the matrices)
 void kv_append_run(const Dims& d, const void* x_new, const void* wk, const void* wv, void* k_cache, void* v_cache,
-                   int32_t pos, void* workspace, hipStream_t s);
+                   int32_t pos, void* workspace, hipStream_t s, float packed_norm_eps = __builtin_nanf(""));
 
 }  // namespace detail
 }  // namespace beagle

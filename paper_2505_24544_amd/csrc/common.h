@@ -196,6 +196,8 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
                            void* h, int32_t M, int32_t D, int32_t F, void* ws, hipStream_t s);
 // the same on packed weights: two strip launches, gate fused;
 // needs strip_gemm_fits(M, F, D) and strip_gemm_fits(M, D, F); ws: M * F bf16
+void launch_kv_append_strip_bf16(const void* x, const void* wk_pk, const void* wv_pk, void* kdst, void* vdst, int32_t n,
+                                 int32_t N, int32_t K, float norm_eps, hipStream_t s);
 void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
                                  const void* y_res, void* h, int32_t M, int32_t D, int32_t F, float z_norm_eps, void* ws,
                                  hipStream_t s);

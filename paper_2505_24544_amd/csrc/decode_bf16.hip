@@ -366,6 +366,7 @@ __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__
 // workgroup 0 writes the LSE.
 // MODE 2 (feed-forward layer, Eq. 1): two weight matrices share the activations, and the strip's result is
 // silu(a W) * (a W2): the gate needs no launch of its own.
+// MODE 3 (cache append): two weight matrices share the activations, each with an output of its own (K and V rows).
 // ---------------------------------------------------------------------------
 namespace dec {
 constexpr int ST_N = 16;                 // output columns per workgroup
@@ -378,14 +379,15 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 template <int MODE, bool ROWS16, int WAVES>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const bf16_t* __restrict__ a, const bf16_t* __restrict__ Wt,
                                                             const bf16_t* __restrict__ Wt2, void* __restrict__ yout,
-                                                            const bf16_t* __restrict__ res, int M, int N, int K,
-                                                            CombineArgs cb, int out_f32, float norm_eps) {
+                                                            bf16_t* __restrict__ yout2, const bf16_t* __restrict__ res,
+                                                            int M, int N, int K, CombineArgs cb, int out_f32,
+                                                            float norm_eps) {
   using namespace dec;
   constexpr int ROWS = ROWS16 ? 16 : 8;             // activation rows kept per macro-step
   constexpr int ST_CH = ROWS16 ? 2 : 4;             // macro-steps per activation chunk
   constexpr int LPS = ROWS / 4;                     // loads per macro-step (1 KB = 4 rows each)
   constexpr int NLD = ST_CH * LPS;                  // loads per chunk: 8
-  constexpr int NW = MODE == 2 ? 2 : 1;             // weight matrices
+  constexpr int NW = MODE >= 2 ? 2 : 1;             // weight matrices
   constexpr int ST_RING = ST_FLIGHT / NW;           // ring slots per matrix
   constexpr int ABUF = WAVES * ST_CH * ROWS * 256;  // one activation buffer of all waves: 64 KB with eight
   static_assert(ST_ROUND % ST_CH == 0 && ST_ROUND % ST_RING == 0, "chunks and ring slots repeat with the round");
@@ -464,7 +466,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
 
   // ---- the first ST_RING macro-steps of weights (one matrix at K = 4096: all of them)
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void*)Wt, 0, (int)((int64_t)N * K * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t wrs2 = __builtin_amdgcn_make_buffer_rsrc((void*)(MODE == 2 ? Wt2 : Wt), 0, (int)((int64_t)N * K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrs2 = __builtin_amdgcn_make_buffer_rsrc((void*)(MODE >= 2 ? Wt2 : Wt), 0, (int)((int64_t)N * K * 2), 0x00020000);
   const int wbase = blockIdx.x * 4096 + lane * 16;          // this strip's block of macro-step 0, this lane's 16 bytes
   const int wstep = (N / ST_N) * 4096;                      // from one macro-step's blocks to the next's
   union frag_t { xload_t u; bf16x8_t v; };
@@ -578,13 +580,14 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
       rn = 1.f / sqrtf(ss / (float)K + norm_eps);
       v *= rn;
     }
-    if constexpr (MODE == 2) {
+    const int64_t o = (int64_t)m * N + n0 + n;
+    if constexpr (MODE >= 2) {
       float g = red[NW - 1][0][m][n];
 #pragma unroll
       for (int wv = 1; wv < WAVES; ++wv) g += red[NW - 1][wv][m][n];
-      v = v / (1.f + expf(-v)) * (g * rn);                     // silu(gate) * up
+      if (MODE == 2) v = v / (1.f + expf(-v)) * (g * rn);      // silu(gate) * up
+      else yout2[o] = (bf16_t)(cvt_pk(g * rn, 0.f) & 0xffffu); // the second matrix has its own output
     }
-    const int64_t o = (int64_t)m * N + n0 + n;
     if (res) v += __uint_as_float((uint32_t)res[o] << 16);
     if (out_f32) ((float*)yout)[o] = v;                       // the queries: the attention kernel wants them unrounded
     else ((bf16_t*)yout)[o] = (bf16_t)(cvt_pk(v, 0.f) & 0xffffu);
@@ -1257,20 +1260,24 @@ bool strip_gemm_fits(int32_t M, int32_t N, int32_t K) {
   return (int64_t)N * K * 2 < ((int64_t)1 << 31) && (int64_t)M * K * 2 < ((int64_t)1 << 31);
 }
 // y = a W (+ res) on packed W; with wt2: y = silu(a W) * (a W2); with merge: a is merged from the attention partials (M = 1)
-void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, void* y, const bf16_t* res, int M, int N,
-                       int K, const CombineArgs* merge, bool out_f32, float norm_eps, hipStream_t s) {
+void launch_strip_gemm(const bf16_t* a, const bf16_t* wt, const bf16_t* wt2, void* y, bf16_t* y2, const bf16_t* res, int M,
+                       int N, int K, const CombineArgs* merge, bool out_f32, float norm_eps, hipStream_t s) {
   using namespace dec;
   const dim3 grid(N / ST_N);
   const CombineArgs cb = merge ? *merge : CombineArgs{};
   const int f = out_f32 ? 1 : 0;
   // one matrix: eight waves, one workgroup per CU (N / 16 is about the number of CUs for the attention's projections);
   // the feed-forward pair has several strips per CU: four waves and two workgroups per CU, so that one's start and
-  // final reduction hide behind the other's stream
-  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
-  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
-  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
-  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
-  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, a, wt, wt2, y, res, M, N, K, cb, f, norm_eps);
+  // final reduction hide behind the other's stream; the K/V pair of the cache append (y2 given) is as wide as one matrix
+#define STRIP_ARGS a, wt, wt2, y, y2, res, M, N, K, cb, f, norm_eps
+  if (merge) hipLaunchKernelGGL((strip_gemm_kernel<1, false, 8>), grid, dim3(512), 0, s, STRIP_ARGS);
+  else if (wt2 && y2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<3, false, 8>), grid, dim3(512), 0, s, STRIP_ARGS);
+  else if (wt2 && y2) hipLaunchKernelGGL((strip_gemm_kernel<3, true, 8>), grid, dim3(512), 0, s, STRIP_ARGS);
+  else if (wt2 && M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<2, false, 4>), grid, dim3(256), 0, s, STRIP_ARGS);
+  else if (wt2) hipLaunchKernelGGL((strip_gemm_kernel<2, true, 4>), grid, dim3(256), 0, s, STRIP_ARGS);
+  else if (M <= 8) hipLaunchKernelGGL((strip_gemm_kernel<0, false, 8>), grid, dim3(512), 0, s, STRIP_ARGS);
+  else hipLaunchKernelGGL((strip_gemm_kernel<0, true, 8>), grid, dim3(512), 0, s, STRIP_ARGS);
+#undef STRIP_ARGS
 }
 
 size_t decode_bf16_ws_bytes(int32_t M, int32_t L, int32_t H, int32_t d, int32_t D) {
@@ -1298,7 +1305,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
     const bf16_t* x = (const bf16_t*)a.x + (int64_t)m0 * a.D;
     if (a.wq_pk) {                    // packed Wq: the whole of k in one strip, so q arrives as a single slice
       ProfScope ps("draft_proj_q", s);
-      launch_strip_gemm(x, (const bf16_t*)a.wq_pk, nullptr, qpart, nullptr, Mp, HDt, a.D, nullptr, true, a.x_norm_eps, s);
+      launch_strip_gemm(x, (const bf16_t*)a.wq_pk, nullptr, qpart, nullptr, nullptr, Mp, HDt, a.D, nullptr, true, a.x_norm_eps, s);
     } else {
       ProfScope ps("draft_proj_q", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
@@ -1325,7 +1332,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       const bf16_t* yr = a.y_res ? (const bf16_t*)a.y_res + (int64_t)m0 * a.D : (const bf16_t*)nullptr;
       if (Mp == 1 && w.R <= COMB_MAXR && HDt / HD <= 32) {
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, &cb, false, -1.f, s);
+        launch_strip_gemm(nullptr, (const bf16_t*)a.wo_pk, nullptr, yo, nullptr, yr, Mp, a.D, HDt, &cb, false, -1.f, s);
       } else {
         {
           ProfScope ps("draft_combine", s);
@@ -1333,7 +1340,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
                              w.Mpad, a.H, w.R, a.scale);
         }
         ProfScope ps("draft_proj_out", s);
-        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, yr, Mp, a.D, HDt, nullptr, false, -1.f, s);
+        launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, nullptr, yr, Mp, a.D, HDt, nullptr, false, -1.f, s);
       }
       continue;
     }
@@ -1455,17 +1462,26 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
   }
 }
 
+// K and V rows of up to 16 new states on packed Wk, Wv (norm_eps >= 0: the RMSNorm in front of them, gain folded into
+// the matrices): one strip launch, no workspace
+void launch_kv_append_strip_bf16(const void* x, const void* wk_pk, const void* wv_pk, void* kdst, void* vdst, int32_t n,
+                                 int32_t N, int32_t K, float norm_eps, hipStream_t s) {
+  ProfScope ps("kv_append_proj", s);
+  launch_strip_gemm((const bf16_t*)x, (const bf16_t*)wk_pk, (const bf16_t*)wv_pk, kdst, (bf16_t*)vdst, nullptr, n, N, K, nullptr,
+                    false, norm_eps, s);
+}
+
 void launch_block_mlp_strip_bf16(const void* z, const void* w_gate_pk, const void* w_up_pk, const void* w_down_pk,
                                  const void* y_res, void* h, int32_t M, int32_t D, int32_t F, float z_norm_eps, void* ws,
                                  hipStream_t s) {
   bf16_t* mbuf = (bf16_t*)ws;
   {
     ProfScope ps("draft_mlp_gate_up", s);
-    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, M, F, D, nullptr, false, z_norm_eps, s);
+    launch_strip_gemm((const bf16_t*)z, (const bf16_t*)w_gate_pk, (const bf16_t*)w_up_pk, mbuf, nullptr, nullptr, M, F, D, nullptr, false, z_norm_eps, s);
   }
   {
     ProfScope ps("draft_mlp_down", s);
-    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, (const bf16_t*)y_res, M, D, F, nullptr, false, -1.f, s);
+    launch_strip_gemm(mbuf, (const bf16_t*)w_down_pk, nullptr, (bf16_t*)h, nullptr, (const bf16_t*)y_res, M, D, F, nullptr, false, -1.f, s);
   }
 }
 

@@ -273,7 +273,7 @@ def run_draft_prepared(cfg, x, kc, vc, wq, wo, n_true, tree_bool, scale=0.0, che
     t = {n: to_dev(a, cfg) for n, a in dict(x=x, kc=kc, vc=vc, wq=wq, wo=wo).items()}
     wq_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)
     wo_pk = torch.full((D * H * cfg.head_dim,), float("nan"), dtype=tdtype(cfg), device=DEV)
-    st = bx.beagle_xattn_prepare_weights(d, t["wq"], t["wo"], wq_pk, wo_pk, check=check)
+    st = bx.beagle_xattn_prepare_weights(d, wq=t["wq"], wo=t["wo"], wq_pk=wq_pk, wo_pk=wo_pk, check=check)
     if not check and st != 0:
         return st
     packed = pack_tree_mask(tree_bool)

@@ -106,11 +106,13 @@ def test_block_draft_step_argument_errors():
     assert bx.beagle_xattn_block_workspace_bytes(d2, 32, bx.BEAGLE_WS_BLOCK_DRAFT) == 0
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_block_speculative_iteration_append_draft_append_draft(dtype):
+@pytest.mark.parametrize("dtype,on_packed", [("f32", False), ("bf16", False), ("bf16", True)])
+def test_block_speculative_iteration_append_draft_append_draft(dtype, on_packed):
     """Cache built by beagle_xattn_block_kv_append from true states (with rotary positions), one draft step of three
     tokens, their outputs h appended as drafted rows at position n_true + 0, a second draft step of three tokens
-    that each see their own parent only -- every stage against the same chain over the oracle."""
+    that each see their own parent only -- every stage against the same chain over the oracle.  on_packed: the draft
+    steps and the append of the drafted states through the entry points on packed weights (the 40 true states at
+    the start are more than those serve: they go in through the plain append)."""
     D, H, G, d, ffn = (256, 4, 2, 64, 96) if dtype == "f32" else (512, 4, 4, 128, 1408)
     n_true, cap, M = 40, 64, 3
     cfg, bi, _, _ = _problem(dtype, M, cap, H, G, D, d, ffn, 171)
@@ -124,13 +126,27 @@ def test_block_speculative_iteration_append_draft_append_draft(dtype):
     vc = torch.zeros(cap, G, d, dtype=dt, device=gh.DEV)
     tol = (lambda a, b: gh.rel_max(a, b) <= 3 * F32_TOL) if dtype == "f32" else (lambda a, b: gh.rel_fro(a, b) <= OUT_FRO)
     i32 = lambda a: torch.tensor(np.asarray(a), dtype=torch.int32, device=gh.DEV)
+    dw = None
+    if on_packed:
+        E = lambda n: torch.full((n,), float("nan"), dtype=dt, device=gh.DEV)
+        tw = dict(wq_pk=E(D * H * d), wo_pk=E(D * H * d), wk_pk=E(D * G * d), wv_pk=E(D * G * d), w_gate_pk=E(ffn * D),
+                  w_up_pk=E(ffn * D), w_down_pk=E(D * ffn))
+        dw = bx.make_block_decode_weights(**tw)
+        bx.beagle_xattn_block_prepare_weights(gh.desc_of(cfg), params, dw)
+        g_kv = bi["g_kv"].astype(np.float32)[:, None]
+        for n, src in (("wk_pk", "wk"), ("wv_pk", "wv")):
+            assert np.array_equal(gh.to_host(tw[n]), gh.packed_strips(synth.round_to_bf16(g_kv * bi[src].astype(np.float32)))), n
+        gains_only = bx.make_block_params(ffn, 1e-5, g_q=dev["g_q"], g_kv=dev["g_kv"], g_mlp=dev["g_mlp"])
 
     def append(x_host, pos, positions):
         n = x_host.shape[0]
         pd = i32(positions)
         dsc = gh.desc_of(cfg.with_(seq_q=n), bx.BEAGLE_FLAG_ROPE, rope_positions=pd)
-        ws = gh.workspace(dsc, bx.BEAGLE_WS_BLOCK_APPEND)
-        bx.beagle_xattn_block_kv_append(dsc, params, gh.to_dev(x_host, cfg), kc, vc, pos, ws)
+        if on_packed and n <= bx.BEAGLE_PREPARED_MAX_QUERIES:
+            bx.beagle_xattn_block_kv_append_prepared(dsc, gains_only, dw, gh.to_dev(x_host, cfg), kc, vc, pos)
+        else:
+            ws = gh.workspace(dsc, bx.BEAGLE_WS_BLOCK_APPEND)
+            bx.beagle_xattn_block_kv_append(dsc, params, gh.to_dev(x_host, cfg), kc, vc, pos, ws)
         torch.cuda.synchronize()
 
     def draft(x_host, rows, n_true_, tree, positions):
@@ -144,8 +160,12 @@ def test_block_speculative_iteration_append_draft_append_draft(dtype):
         else:
             packed = gh.pack_tree_mask(tree)
             tm, words = torch.from_numpy(packed.view(np.int32)).to(gh.DEV), packed.shape[1]
-        bx.beagle_xattn_block_draft_step(dsc, params, gh.to_dev(x_host, cfg), kc[:rows].contiguous(), vc[:rows].contiguous(),
-                                         n_true_, tm, words, h, lse, ws)
+        if on_packed:
+            bx.beagle_xattn_block_draft_step_prepared(dsc, gains_only, dw, gh.to_dev(x_host, cfg), kc[:rows].contiguous(),
+                                                      vc[:rows].contiguous(), n_true_, tm, words, h, lse, ws)
+        else:
+            bx.beagle_xattn_block_draft_step(dsc, params, gh.to_dev(x_host, cfg), kc[:rows].contiguous(), vc[:rows].contiguous(),
+                                             n_true_, tm, words, h, lse, ws)
         torch.cuda.synchronize()
         return gh.to_host(h)
 

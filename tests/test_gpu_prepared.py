@@ -76,7 +76,7 @@ def test_prepared_step_in_a_hip_graph_replays_to_the_eager_result():
     x, kc, vc, wq, wo = R(M, D), R(L, H, 128, std=1.28), R(L, H, 128, std=1.28), R(D, H * 128, std=0.02), R(H * 128, D, std=0.02)
     wq_pk = torch.empty(D * H * 128, dtype=torch.bfloat16, device=gh.DEV)
     wo_pk = torch.empty(D * H * 128, dtype=torch.bfloat16, device=gh.DEV)
-    bx.beagle_xattn_prepare_weights(desc, wq, wo, wq_pk, wo_pk)
+    bx.beagle_xattn_prepare_weights(desc, wq=wq, wo=wo, wq_pk=wq_pk, wo_pk=wo_pk)
     ws, ws_g = gh.workspace(desc, bx.BEAGLE_WS_DRAFT), gh.workspace(desc, bx.BEAGLE_WS_DRAFT)
     y_e = torch.full((M, D), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
     l_e = torch.full((H, M), float("nan"), dtype=torch.float32, device=gh.DEV)
@@ -93,3 +93,44 @@ def test_prepared_step_in_a_hip_graph_replays_to_the_eager_result():
         assert torch.equal(y_g.view(torch.int16), y_e.view(torch.int16)) and torch.equal(l_g, l_e), rep
         bx.beagle_xattn_draft_step_prepared(desc, x, kc, vc, wq_pk, wo_pk, L, None, 0, y_e, l_e, ws)   # eager work in between
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("n,pos,cap,G,D", [(1, 4096, 4200, 32, 4096), (10, 37, 300, 4, 512), (16, 100, 160, 2, 1024),
+                                           (7, 11, 64, 2, 896), (9, 0, 9, 1, 640)])
+def test_kv_append_on_packed_weights(n, pos, cap, G, D):
+    """beagle_xattn_kv_append_prepared against the oracle's kv_append; rows outside [pos, pos + n) stay as they were."""
+    import torch
+    import gpu_harness as gh
+    d = 128
+    rng = np.random.default_rng(n + pos)
+    cfg, inp, _, _ = _problem("bf16", n, cap, G, G, D, d, 1900 + n)
+    x_new = inp["xq"][0]
+    old_k = synth.round_to_bf16(rng.standard_normal((cap, G, d)).astype(np.float32))
+    old_v = synth.round_to_bf16(rng.standard_normal((cap, G, d)).astype(np.float32))
+    wantk, wantv = orc.kv_append(old_k, old_v, pos, x_new, inp["wk"], inp["wv"], n_kv_heads=G)
+    desc = gh.desc_of(cfg)
+    t = {k: gh.to_dev(a, cfg) for k, a in dict(x=x_new, wk=inp["wk"], wv=inp["wv"], kc=old_k, vc=old_v).items()}
+    wk_pk = torch.full((D * G * d,), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    wv_pk = torch.full((D * G * d,), float("nan"), dtype=torch.bfloat16, device=gh.DEV)
+    bx.beagle_xattn_prepare_weights(desc, wk=t["wk"], wv=t["wv"], wk_pk=wk_pk, wv_pk=wv_pk)
+    assert np.array_equal(gh.to_host(wk_pk), packed_strips(inp["wk"])) and np.array_equal(gh.to_host(wv_pk), packed_strips(inp["wv"]))
+    bx.beagle_xattn_kv_append_prepared(desc, t["x"], wk_pk, wv_pk, t["kc"], t["vc"], pos)
+    torch.cuda.synchronize()
+    gotk, gotv = gh.to_host(t["kc"]), gh.to_host(t["vc"])
+    keep = np.ones(cap, bool)
+    keep[pos:pos + n] = False
+    assert np.array_equal(gotk[keep], old_k[keep]) and np.array_equal(gotv[keep], old_v[keep])
+    for got, want in ((gotk, wantk), (gotv, wantv)):
+        assert max_abs(got[pos:pos + n], want[pos:pos + n]) <= BF16_OUT_ABS
+        assert rel_fro(got[pos:pos + n], want[pos:pos + n]) <= BF16_OUT_FRO
+
+
+def test_kv_append_on_packed_weights_refuses_what_it_does_not_serve():
+    import torch
+    import gpu_harness as gh
+    cfg, inp, _, _ = _problem("bf16", 17, 64, 4, 4, 512, 128, 1950)
+    a = torch.zeros(1 << 20, dtype=torch.bfloat16, device=gh.DEV)
+    assert bx.beagle_xattn_kv_append_prepared(gh.desc_of(cfg), a, a, a, a, a, 0, check=False) == bx.BEAGLE_ERR_UNSUPPORTED   # 17 states
+    cfg2 = cfg.with_(seq_q=4)
+    assert bx.beagle_xattn_kv_append_prepared(gh.desc_of(cfg2), a, a, a, a, a, 61, check=False) == bx.BEAGLE_ERR_SHAPE        # past the end
+    assert bx.beagle_xattn_kv_append_prepared(gh.desc_of(cfg2), a, None, a, a, a, 0, check=False) == bx.BEAGLE_ERR_NULL

@@ -66,7 +66,10 @@ SWEEP = textwrap.dedent('''
         bx.beagle_xattn_draft_step(desc, z, z, z, z, z, z, z, z, check=False, workspace_bytes=1 << 40, stream=0)
         bx.beagle_xattn_draft_step_tree(desc, z, z, z, z, z, 5, z, 1, z, z, z, check=False, workspace_bytes=1 << 40, stream=0)
         bx.beagle_xattn_draft_step_prepared(desc, z, z, z, z, z, 5, z, 1, z, z, z, check=False, workspace_bytes=1 << 40, stream=0)
-        bx.beagle_xattn_prepare_weights(desc, z, z, z, z, check=False, stream=0)
+        bx.beagle_xattn_prepare_weights(desc, check=False, stream=0)
+        bx.beagle_xattn_kv_append_prepared(desc, z, z, z, z, z, 3, check=False, stream=0)
+        bx.beagle_xattn_block_kv_append_prepared(desc, bx.make_block_params(64, 1e-5), bx.make_block_decode_weights(), z, z, z, 3,
+                                                 check=False, stream=0)
         bx.beagle_xattn_kv_append(desc, z, z, z, z, z, 3, z, check=False, workspace_bytes=1 << 40, stream=0)
         for ffn in (64, 11008, 2**31 - 64):
             p = bx.make_block_params(ffn, 1e-5)
