@@ -651,27 +651,49 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* pos, int
   tab[i] = make_float2((float)cs, (float)sn);
 }
 
+// LDS reads with the address split into a register and a compile-time byte offset (at most 65 535): one address
+// register serves every stage, plane and 16-row step that a fragment kind is read from.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+template <int OFF> __device__ __forceinline__ void lds_read_b128(xload_t& d, uint32_t addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
+}
+template <int OFF> __device__ __forceinline__ void lds_read_tr16_b64(u32x2_t& d, uint32_t addr) {
+  static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF));
+}
+template <int V> struct int_c { static constexpr int value = V; };
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) { f(int_c<I>{}); static_for<I + 1, N>(f); }
+}
+
 // One workgroup per (head, key range, block of 32 NQB queries): grid (H, R, ceil(M / (32 NQB))).
 // NQB = 1 (up to 32 queries): the four waves split each 128-key step by rows, 32 keys each.  A wave requests, reads
 // and refills only its own 32 rows of the two stages, so the step loop has no barrier; a stage half (the wave's K
 // rows, then its V rows) is refilled for the step after next as soon as its fragments sit in registers, i.e. BEFORE
 // the step's arithmetic: with both stages landed and nothing requested, HBM would idle for as long as a step
 // computes (measured: 3 us of the kernel's 16).
-// NQB = 2 (33 .. 64 queries): waves 0, 1 take the first 32 queries and waves 2, 3 the next 32, each wave 64 keys of
-// a step as two blocks of 32 -- the K / V tiles in LDS serve both query blocks, so the cache is read once instead
-// of once per block; the stages are shared between waves there, so the loop keeps its (fence-free) barriers.
-// (Both blocks in every wave, which would free that loop of barriers too, needs 256 registers for the two output
-// accumulators and q fragments alone and did not survive register allocation.)
+// NQB = 2 (33 .. 64 queries): the same split of a step by rows; every wave works its 32 keys against both blocks of
+// 32 queries, so K and V fragments are read from LDS once for the two blocks, no wave reads another's rows and the
+// loop is as free of barriers as with one block.  (Waves 0, 1 on the first block and waves 2, 3 on the second, each
+// with 64 keys of a step, was the earlier shape: stages shared between waves, hence a barrier per step with the
+// refill issued only behind it -- 4 400 cycles of arithmetic and 2 700 of request issue per step, one after the other.)
 template <int NQB>
 __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   using namespace dec;
-  __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];    // K step tile, V step tile: 64 KB
-  __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
-  // q as bf16 planes of 32 queries: plane 0 = hi part of the block being set up, plane 1 + b = lo part of block b
-  __shared__ __attribute__((aligned(1024))) bf16_t qbuf[(1 + NQB) * 32 * HD];
-  __shared__ float s_ml[4][2][32];                                      // per wave: running max, sum of its queries
-  __shared__ float s_sc[4][32];                                         // merge weight of a wave's partial
-  __shared__ float s_mm[NQB][2][32];                                    // merged max, sum per block
+  // two stages of one K and one V step tile each: tile t (0: K, 1: V) of stage i at (2 t + i) * TILE, so that the
+  // two stages of a tile kind are 32 KB apart (within the offset field of an LDS read)
+  __shared__ __attribute__((aligned(1024))) bf16_t kvt[4 * TILE];
+  auto tile_of = [&](int si, int t) { return kvt + (2 * t + si) * TILE; };
+  // q as bf16 planes of 32 queries: plane b = hi part of block b, plane NQB + b = its lo part.  With two blocks that
+  // makes 160 KB with the stages: the merge's small arrays live in the planes, which are dead after the prologue.
+  __shared__ __attribute__((aligned(1024))) bf16_t qbuf[2 * NQB * 32 * HD];
+  typedef float ml_t[NQB][2][32];
+  typedef float sc_t[NQB][32];
+  ml_t* const s_ml = (ml_t*)qbuf;                                       // [wave]: running max, sum of its queries
+  sc_t* const s_sc = (sc_t*)((float*)qbuf + 4 * NQB * 2 * 32);          // [wave]: merge weight of a wave's partial
+  ml_t& s_mm = *(ml_t*)((float*)qbuf + 4 * NQB * 3 * 32);               // merged max, sum per block
+  static_assert((4 * NQB * 3 * 32 + NQB * 2 * 32) * sizeof(float) <= sizeof(qbuf), "merge arrays must fit in the q planes");
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
   const int h = blockIdx.x, r = blockIdx.y;
   const int m0 = 32 * NQB * blockIdx.z;                      // first query of the workgroup
@@ -684,12 +706,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   const int64_t kvs = (int64_t)a.G * HD;
   const __amdgpu_buffer_rsrc_t krs = rows_rsrc(a.kc + (int64_t)g * HD, j_end, kvs);   // rows >= j_end read as zero
   const __amdgpu_buffer_rsrc_t vrs = rows_rsrc(a.vc + (int64_t)g * HD, j_end, kvs);
-  auto fetch = [&](bf16_t* st, int step) {
-    load_rows<KSTEP>(st, krs, kvs, j_begin + step * KSTEP, tid);
-    load_rows<KSTEP>(st + TILE, vrs, kvs, j_begin + step * KSTEP, tid);
-  };
   // the same step requested by waves 1 .. 3 only: request n of the 64 (32 per tile, 64 chunks of 16 bytes each) is wave 1 + n % 3's
-  auto fetch3 = [&](bf16_t* st, int step) {
+  auto fetch3 = [&](int si, int step) {
     const int row0 = j_begin + step * KSTEP;
 #pragma unroll
     for (int n0 = 0; n0 < 66; n0 += 3) {
@@ -697,26 +715,25 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       if (n < 64) {
         const int q = 64 * (n & 31) + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
         const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(n < 32 ? krs : vrs, (lds_void_ptr)(st + (n >> 5) * TILE + (n & 31) * 512), 16, off, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(n < 32 ? krs : vrs, (lds_void_ptr)(tile_of(si, n >> 5) + (n & 31) * 512), 16, off, 0, 0, 0);
       }
     }
   };
   // this wave's own 32 rows of a step's K (t = 0) or V (t = 1) tile: 8 requests, no branch (rows past the range read as zero)
-  auto fetch_own_half = [&](bf16_t* st, int step, int t) {
+  auto fetch_own_half = [&](int si, int step, int t) {
     const int row0 = j_begin + step * KSTEP;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int q = 512 * wave + 64 * i + lane, rr = q >> 4, c = (q & 15) ^ swz(rr);
       const int off = (int)(((int64_t)(row0 + rr) * kvs + 8 * c) * 2);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(t ? vrs : krs, (lds_void_ptr)(st + t * TILE + (8 * wave + i) * 512), 16, off, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(t ? vrs : krs, (lds_void_ptr)(tile_of(si, t) + (8 * wave + i) * 512), 16, off, 0, 0, 0);
     }
   };
-  auto fetch_own = [&](bf16_t* st, int step) { fetch_own_half(st, step, 0); fetch_own_half(st, step, 1); };
+  auto fetch_own = [&](int si, int step) { fetch_own_half(si, step, 0); fetch_own_half(si, step, 1); };
   typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
   typedef float f32x4_t __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) float* lds_float_ptr;
   typedef __attribute__((address_space(3))) bf16_t* lds_bf16_ptr;
-  typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
   const float4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
   // ---- q = sum of the projection's k-slices (fixed order).  The workgroup sums a block once and leaves it in LDS
@@ -805,8 +822,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       uint2 hi, lo;
       q_split(acc[i], hi, lo);
       const u32x2_t vh = {hi.x, hi.y}, vl = {lo.x, lo.y};
-      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + q_slot(m, c4))), "v"(vh) : "memory");
-      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + (1 + qb) * 32 * HD + q_slot(m, c4))), "v"(vl) : "memory");
+      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + qb * 32 * HD + q_slot(m, c4))), "v"(vh) : "memory");
+      asm volatile("ds_write_b64 %0, %1" : : "v"((lds_bf16_ptr)(qbuf + (NQB + qb) * 32 * HD + q_slot(m, c4))), "v"(vl) : "memory");
     }
   };
   // B-operand fragments of a plane (explicit ds_read, see above): channels 16 s + 8 hf .. + 7 of query ql
@@ -829,9 +846,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     for (int s = 0; s < 8; ++s) out[s] = f[s].v;
   };
 
-  constexpr int WPB = 4 / NQB;                               // waves per query block
-  const int qbw = wave / WPB;                                // this wave's query block
-  bf16x8_t qh[8], qlo[8];                                    // its fragments of q
+  // this lane's fragments of q (one block; with two they stay in their LDS planes and are read again in every step)
+  bf16x8_t qh[1][8], qlo[1][8];
   bool shared_first_steps = false;                           // steps 0 and 1 requested across waves (barrier before step 1)
   if (NQB == 1 && mtot <= 8) {
     // Up to 8 queries: wave 0 alone sums (one round trip for its 32 loads) while waves 1 .. 3 request the first
@@ -861,8 +877,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     }
     __builtin_amdgcn_sched_barrier(0);
     if (wave > 0) {
-      if (nsteps > 0) fetch3(stage0, 0);
-      if (nsteps > 1) fetch3(stage1, 1);
+      if (nsteps > 0) fetch3(0, 0);
+      if (nsteps > 1) fetch3(1, 1);
     }
     __builtin_amdgcn_sched_barrier(0);
     if (nsteps > 0 && wave > 0) {
@@ -870,8 +886,8 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       if (nsteps == 1) wait_vmem(); else if (wave == 1) wait_vmem_n<22>(); else wait_vmem_n<21>();
     }
     lds_barrier();                                             // first K/V step landed; q sum visible
-    read_frags(0, qh);
-    read_frags(1, qlo);
+    read_frags(0, qh[0]);
+    read_frags(1, qlo[0]);
   } else if (NQB == 1) {
     // 9 .. 32 queries: two or four waves sum.  Every wave requests its own rows of step 0, then its q slices, then
     // its rows of step 1 -- the K/V stream starts with the kernel, and q (loads return in order) is complete when
@@ -879,9 +895,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
     const int qwaves = mtot <= 16 ? 2 : 4;
     u32x4_t t[4][8];
     float4 acc[4] = {zero4, zero4, zero4, zero4};
-    fetch_own(stage0, 0);
+    fetch_own(0, 0);
     q_issue(0, mtot, qwaves, 0, t);
-    fetch_own(stage1, 1);
+    fetch_own(1, 1);
     __builtin_amdgcn_sched_barrier(0);
     wait_vmem_n<16>();                                         // all but step 1's requests
     q_add(t, acc);
@@ -897,246 +913,284 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
       }
     }
     lds_barrier();                                             // q visible
-    read_frags(0, qh);
-    read_frags(1, qlo);
+    read_frags(0, qh[0]);
+    read_frags(1, qlo[0]);
   } else {
-    // 33 .. 64 queries, all four waves sum both blocks: step 0 (requests dealt across the waves), block 0's slices,
-    // step 1, block 1's slices -- the last of these only issue as the oldest requests retire (a wave holds at most
-    // 63), which is when step 0 lands, and are back soon after step 1.  Every barrier below is passed by a wave only
-    // after its own share of step 0 (at the last one: of step 1) has landed, so the stages are complete behind them.
+    // 33 .. 64 queries, all four waves sum both blocks: own rows of step 0, block 0's slices, own rows of step 1,
+    // block 1's slices -- the last of these only issue as the oldest requests retire (a wave holds at most 63), which
+    // is when step 0 lands, and are back soon after step 1.
     u32x4_t t0[4][8], t1[4][8];
     float4 acc[4] = {zero4, zero4, zero4, zero4};
-    fetch(stage0, 0);
+    fetch_own(0, 0);
     q_issue(0, 32, 4, 0, t0);
-    fetch(stage1, 1);
+    fetch_own(1, 1);
     q_issue(1, mtot - 32, 4, 0, t1);                           // rows past the last query: zeros
     __builtin_amdgcn_sched_barrier(0);
     wait_vmem_n<48>();                                         // step 0 and block 0's slices
     q_add(t0, acc);
     q_finish(0, 32, 4, acc);
     q_store(0, 4, acc);
-    lds_barrier();                                             // block 0 visible
-    if (qbw == 0) { read_frags(0, qh); read_frags(1, qlo); }
-    lds_barrier();                                             // block 0's hi plane has been read
     wait_vmem();
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = zero4;
     q_add(t1, acc);
     q_finish(1, mtot - 32, 4, acc);
     q_store(NQB - 1, 4, acc);
-    lds_barrier();                                             // block 1 visible; steps 0 and 1 landed
-    if (qbw == NQB - 1) { read_frags(0, qh); read_frags(NQB, qlo); }
+    lds_barrier();                                             // both blocks visible
   }
   const float c2 = a.scale * LOG2E;
   const FragOffs fo = make_frag_offs(lane);
 
-  f32x16_t o[4];
+  f32x16_t o[NQB][4];
+  float mrun[NQB], lrun[NQB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int b = 0; b < NQB; ++b) {
+    mrun[b] = -INFINITY; lrun[b] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) o[i][e] = 0.f;
-  float mrun = -INFINITY, lrun = 0.f;
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[b][i][e] = 0.f;
+  }
 
-  // One 128-key step.  One block: this wave's 32 rows of the step tiles; `refill` requests the same rows of step + 2
-  // into the stage as soon as their fragments have been read.  Two blocks: 64 rows (two blocks of 32, one after the
-  // other) against the wave's query block; the stages are shared and refilled by the step loop.
-  auto step_compute = [&](bf16_t* cur, int step, bool refill) {
-    const bf16_t* ks = cur;
-    const bf16_t* vs = cur + TILE;
+  bool o_zero = true;                                        // wave-uniform: nothing accumulated into O yet
+  // Per-lane LDS byte addresses of the three fragment kinds; stages, planes and 16-row steps add compile-time offsets.
+  const uint32_t kvt_a = (uint32_t)(uintptr_t)(lds_bf16_ptr)kvt, qbuf_a = (uint32_t)(uintptr_t)(lds_bf16_ptr)qbuf;
+  uint32_t ka[8], va[4][2], qa[8];
 #pragma unroll
-    for (int sub = 0; sub < NQB; ++sub) {
-      const int kb = (wave % WPB) * NQB + sub;                 // 32-row block of the step tiles
-      const int jw = j_begin + step * KSTEP + 32 * kb;         // its first key
-      if (jw < j_end) {
-        // Explicit ds_read instructions (same addresses as row_frag / tr_frag): for LDS reads it can see, the compiler
-        // waits until no HBM -> LDS request is in flight at all, and the refills would never overlap the arithmetic.
-        union { u32x4_t u; bf16x8_t v; } kf[8];
-        union { struct { u32x2_t x, y; } s; bf16x8_t v; } vf[2][4];
+  for (int s = 0; s < 8; ++s) {
+    ka[s] = kvt_a + 2 * (wave * 32 * HD + fo.row[s]);                          // K tile of stage 0, this wave's rows
+    qa[s] = qbuf_a + 2 * (ql * HD + (((2 * s + hf) ^ (ql & 15)) << 3));        // plane 0
+  }
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
-          asm volatile("ds_read_b128 %0, %1" : "=v"(kf[s].u) : "v"((lds_bf16_ptr)(ks + kb * 32 * HD + fo.row[s])));
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+    for (int i = 0; i < 2; ++i) va[cb][i] = kvt_a + 2 * (2 * TILE + wave * 32 * HD + fo.tr[cb][i]);   // V tile of stage 0
+  constexpr int STAGE_B = TILE * 2, PLANE_B = 32 * HD * 2, TSTEP_B = 16 * HD * 2;   // byte distances
+
+  // One 128-key step on stage SI: this wave's 32 rows of the step tiles against its query blocks; `refill` requests
+  // the same rows of step + 2 into the stage as soon as their fragments have been read.
+  auto step_compute = [&](auto stage_c, int step, bool refill) {
+    constexpr int SI = decltype(stage_c)::value;
+    const int kb = wave;                                       // 32-row block of the step tiles
+    const int jw = j_begin + step * KSTEP + 32 * kb;           // its first key
+    if (jw < j_end) {
+      // Explicit ds_read instructions (same addresses as row_frag / tr_frag): for LDS reads it can see, the compiler
+      // waits until no HBM -> LDS request is in flight at all, and the refills would never overlap the arithmetic.
+      union { xload_t u; bf16x8_t v; } kf[8];
+      union { struct { u32x2_t x, y; } s; bf16x8_t v; } vf[2][4];
+      auto issue_v = [&]() {
+        static_for<0, 2>([&](auto t_) {
+          constexpr int t = decltype(t_)::value;
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb) {
-            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.x) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][0])));
-            asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(vf[t][cb].s.y) : "v"((lds_bf16_ptr)(vs + (32 * kb + 16 * t) * HD + fo.tr[cb][1])));
+            lds_read_tr16_b64<SI * STAGE_B + t * TSTEP_B>(vf[t][cb].s.x, va[cb][0]);
+            lds_read_tr16_b64<SI * STAGE_B + t * TSTEP_B>(vf[t][cb].s.y, va[cb][1]);
           }
-        // LDS reads return in order and the counter holds at most 15: at most 15 of the 24 still out means the
-        // first 9 are there, the 8 K fragments among them
+        });
+      };
+#pragma unroll
+      for (int s = 0; s < 8; ++s) lds_read_b128<SI * STAGE_B>(kf[s].u, ka[s]);
+      f32x16_t st[NQB];
+#pragma unroll
+      for (int b = 0; b < NQB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[b][e] = 0.f;
+      // LDS reads return in order and the counter holds at most 15: at most 15 of 24 still out means the first 9
+      // are there, the 8 K fragments among them
+      if constexpr (NQB == 1) {
+        issue_v();
         asm volatile("s_waitcnt lgkmcnt(15)" ::: "memory");
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
         // two independent accumulation chains (hi and lo part of q) halve the dependent-MFMA latency
-        f32x16_t st, st2;
+        f32x16_t st2;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { st[e] = 0.f; st2[e] = 0.f; }
+        for (int e = 0; e < 16; ++e) st2[e] = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qh[s], st, 0, 0, 0);
-          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qlo[s], st2, 0, 0, 0);
-        }
-        if constexpr (NQB == 1) {
-          // The wave's K rows are in registers: refill them.  Behind the MFMAs in program order: while every CU
-          // streams, a request waits in the issue stage for a slot in the memory pipeline (about 170 cycles each),
-          // and the matrix pipe works through the scores meanwhile.
-          __builtin_amdgcn_sched_barrier(0);
-          if (refill) fetch_own_half(cur, step + 2, 0);
-          __builtin_amdgcn_sched_barrier(0);
+          st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qh[0][s], st[0], 0, 0, 0);
+          st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qlo[0][s], st2, 0, 0, 0);
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) st[e] += st2[e];
+        for (int e = 0; e < 16; ++e) st[0][e] += st2[e];
+      } else {
+        // One chain per block, hi parts first.  q's fragments come from their LDS planes in every step (the two output
+        // accumulators fill the accumulation registers, and 128 more registers of fragments did not survive register
+        // allocation): the lo fragments land during the hi parts' MFMAs, the V fragments during the lo parts'.
+        qfrag_t qf[NQB][8], ql_[NQB][8];
+        static_for<0, NQB>([&](auto b_) {
+          constexpr int b = decltype(b_)::value;
+#pragma unroll
+          for (int s = 0; s < 8; ++s) lds_read_b128<b * PLANE_B>(qf[b][s].u, qa[s]);
+        });
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[s].u));
+#pragma unroll
+        for (int b = 0; b < NQB; ++b) tie_frags(qf[b]);
+        static_for<0, NQB>([&](auto b_) {
+          constexpr int b = decltype(b_)::value;
+#pragma unroll
+          for (int s = 0; s < 8; ++s) lds_read_b128<(NQB + b) * PLANE_B>(ql_[b][s].u, qa[s]);
+        });
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+          for (int b = 0; b < NQB; ++b) st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[b][s].v, st[b], 0, 0, 0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int b = 0; b < NQB; ++b) tie_frags(ql_[b]);
+        issue_v();
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+          for (int b = 0; b < NQB; ++b) st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, ql_[b][s].v, st[b], 0, 0, 0);
+      }
+      // The wave's K rows are in registers: refill them.  Behind the MFMAs in program order: while every CU
+      // streams, a request waits in the issue stage for a slot in the memory pipeline (about 170 cycles each),
+      // and the matrix pipe works through the scores meanwhile.
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) fetch_own_half(SI, step + 2, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      uint32_t pk[NQB][8];
+#pragma unroll
+      for (int b = 0; b < NQB; ++b) {
+        f32x16_t& sb = st[b];
         if (jw + 32 > j_end) {
 #pragma unroll
           for (int e = 0; e < 16; ++e)
-            if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) st[e] = -INFINITY;
+            if (jw + 8 * (e >> 2) + 4 * hf + (e & 3) >= j_end) sb[e] = -INFINITY;
         }
         if (a.tree != nullptr && jw + 32 > a.n_true) {
           // drafted rows: bit i of `vis` says whether this lane's query sees key jw + i (true rows: yes)
           const int off = jw - a.n_true;                       // tree bit of key jw; negative inside the true rows
           const int w0 = off >> 5, sh = off & 31;              // floor division: -1 for the straddling block
-          const uint32_t* row = a.tree + (int64_t)(m0 + 32 * qbw + ql) * a.tree_words;
-          const bool real = 32 * qbw + ql < mtot;
+          const uint32_t* row = a.tree + (int64_t)(m0 + 32 * b + ql) * a.tree_words;
+          const bool real = 32 * b + ql < mtot;
           const uint32_t lo = w0 < 0 ? 0xffffffffu : (real && w0 < a.tree_words ? row[w0] : 0u);
           const uint32_t hi = real && w0 + 1 < a.tree_words ? row[w0 + 1] : 0u;
           const uint32_t vis = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh);
 #pragma unroll
           for (int e = 0; e < 16; ++e)
-            if (!((vis >> (8 * (e >> 2) + 4 * hf + (e & 3))) & 1u)) st[e] = -INFINITY;
+            if (!((vis >> (8 * (e >> 2) + 4 * hf + (e & 3))) & 1u)) sb[e] = -INFINITY;
         }
-        float mx = st[0];
+        float mx = sb[0];
 #pragma unroll
-        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, st[e]);
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, sb[e]);
         mx = half_pair_max(mx);
         // the running reference moves only when the block maximum exceeds it by more than 2^8 in the
         // exponent (p then ranges up to 2^8: harmless for float sums and bf16 probabilities), so that most
         // steps skip the rescaling of O
-        const bool grow = (mx - mrun) * c2 > 8.f;              // also true at the first step (reference -inf)
+        const bool grow = (mx - mrun[b]) * c2 > 8.f;           // also true at the first step (reference -inf)
         if (__builtin_amdgcn_ballot_w64(grow) != 0) {          // wave-uniform
-          const float m_new = grow ? mx : mrun;                // finite: the block holds at least one real key
-          const float alpha = grow ? __builtin_amdgcn_exp2f((mrun - m_new) * c2) : 1.f;
-          lrun *= alpha;
-          mrun = m_new;
+          const float m_new = grow ? mx : mrun[b];             // finite: the block holds at least one real key
+          const float alpha = grow ? __builtin_amdgcn_exp2f((mrun[b] - m_new) * c2) : 1.f;
+          lrun[b] *= alpha;
+          mrun[b] = m_new;
+          if (!o_zero) {                                       // (the first block a wave works on always grows: O is still 0)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[i][e] *= alpha;
+              for (int e = 0; e < 16; ++e) o[b][i][e] *= alpha;
+          }
         }
-        const float mc = (mrun == -INFINITY ? 0.f : mrun) * c2;   // nothing visible so far: p = exp2(-inf) = 0
+        const float mc = (mrun[b] == -INFINITY ? 0.f : mrun[b]) * c2;   // nothing visible so far: p = exp2(-inf) = 0
         float rs = 0.f;
-        uint32_t pk[8];
 #pragma unroll
         for (int e = 0; e < 16; e += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(st[e] * c2 - mc);
-          const float p1 = __builtin_amdgcn_exp2f(st[e + 1] * c2 - mc);
+          const float p0 = __builtin_amdgcn_exp2f(sb[e] * c2 - mc);
+          const float p1 = __builtin_amdgcn_exp2f(sb[e + 1] * c2 - mc);
           rs += p0 + p1;
-          pk[e >> 1] = cvt_pk(p0, p1);
+          pk[b][e >> 1] = cvt_pk(p0, p1);
         }
         rs = half_pair_sum(rs);
-        lrun += rs;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the V fragments
+        lrun[b] += rs;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the V fragments
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) asm volatile("" : "+v"(vf[t][cb].s.x), "+v"(vf[t][cb].s.y));
+        for (int cb = 0; cb < 4; ++cb) asm volatile("" : "+v"(vf[t][cb].s.x), "+v"(vf[t][cb].s.y));
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int b = 0; b < NQB; ++b) {
           union { uint32_t u[4]; bf16x8_t v; } pf;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) pf.u[i] = pk[4 * t + i];
+          for (int i = 0; i < 4; ++i) pf.u[i] = pk[b][4 * t + i];
 #pragma unroll
           for (int cb = 0; cb < 4; ++cb)
-            o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb].v, pf.v, o[cb], 0, 0, 0);
+            o[b][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][cb].v, pf.v, o[b][cb], 0, 0, 0);
         }
-        if constexpr (NQB == 1) {
-          __builtin_amdgcn_sched_barrier(0);
-          if (refill) fetch_own_half(cur, step + 2, 1);        // ... and the wave's V rows, behind the P V MFMAs
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      } else if (NQB == 1 && refill) {
-        fetch_own(cur, step + 2);                              // keeps every wave's request count the same
-      }
+      o_zero = false;
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) fetch_own_half(SI, step + 2, 1);             // ... and the wave's V rows, behind the P V MFMAs
+      __builtin_amdgcn_sched_barrier(0);
+    } else if (refill) {
+      fetch_own(SI, step + 2);                                 // keeps every wave's request count the same
     }
   };
 
-  if constexpr (NQB == 1) {
-    // Two stages.  Before step s the wave's rows of s must have landed: the only younger requests are those of
-    // step s + 1 (issued during step s - 1).  With up to 8 queries the first two steps were requested across
-    // waves, hence the one barrier before step 1.
+  // Two stages.  Before step s the wave's rows of s must have landed: the only younger requests are those of
+  // step s + 1 (issued during step s - 1).  With up to 8 queries the first two steps were requested across
+  // waves, hence the one barrier before step 1.
 #pragma unroll 1
-    for (int step = 0; step < nsteps; step += 2) {
-      if (step > 0) {
-        if (step + 1 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-      }
-      step_compute(stage0, step, step + 2 < nsteps);
-      if (step + 1 < nsteps) {
-        if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-        if (shared_first_steps && step == 0) lds_barrier();
-        step_compute(stage1, step + 1, step + 3 < nsteps);
-      }
+  for (int step = 0; step < nsteps; step += 2) {
+    if (step > 0) {
+      if (step + 1 < nsteps) wait_vmem_n<16>(); else wait_vmem();
     }
-  } else {
-    // two stages, both complete at this point; a stage is refilled as soon as every wave is done with it, and the
-    // refill stays in flight while the other stage is worked on (barriers without a fence: a fence would wait for it)
-#pragma unroll 1
-    for (int step = 0; step < nsteps; step += 2) {
-      step_compute(stage0, step, false);
-      lds_barrier();                                          // all waves done with stage0
-      if (step + 2 < nsteps) fetch(stage0, step + 2);
-      if (step + 1 < nsteps) {
-        // stage1's loads (step + 1) are older than the refill just issued
-        if (step > 0) { if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem(); lds_barrier(); }
-        step_compute(stage1, step + 1, false);
-        lds_barrier();
-        if (step + 3 < nsteps) fetch(stage1, step + 3);
-        if (step + 2 < nsteps) {
-          if (step + 3 < nsteps) wait_vmem_n<16>(); else wait_vmem();
-          lds_barrier();
-        }
-      }
+    step_compute(int_c<0>{}, step, step + 2 < nsteps);
+    if (step + 1 < nsteps) {
+      if (step + 2 < nsteps) wait_vmem_n<16>(); else wait_vmem();
+      if (shared_first_steps && step == 0) lds_barrier();
+      step_compute(int_c<1>{}, step + 1, step + 3 < nsteps);
     }
   }
 
   // ---- merge the waves' partials of each query block (fixed order) and write this key range's partial.
-  // Buffer: [4 waves][32 queries][128 channels] floats = one stage; a float4 of query q sits 4 q floats further
-  // round its row, so that neither the per-query writes nor the per-channel reads conflict.
+  // Buffer of block b (64 KB of the stages): [4 waves][32 queries][128 channels] floats; a float4 of query q sits 4 q floats
+  // further round its row, so that neither the per-query writes nor the per-channel reads conflict.
   __syncthreads();
-  float* ob = (float*)stage0;
-  static_assert(4 * 32 * HD * sizeof(float) <= sizeof(stage0), "merge buffer must fit in one stage");
+  static_assert(NQB * 4 * 32 * HD * sizeof(float) <= sizeof(kvt), "the merge buffers must fit in the stages");
   const int64_t pbase = ((int64_t)h * a.R + r) * a.Mpad + m0;
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
+  for (int b = 0; b < NQB; ++b) {
+    float* ob = (float*)kvt + b * 4 * 32 * HD;
 #pragma unroll
-    for (int e4 = 0; e4 < 4; ++e4) {
-      const int c = 32 * cb + 8 * e4 + 4 * hf;
-      const float4 v = {o[cb][4 * e4], o[cb][4 * e4 + 1], o[cb][4 * e4 + 2], o[cb][4 * e4 + 3]};
-      *(float4*)(ob + (wave * 32 + ql) * HD + ((c + 4 * ql) & (HD - 1))) = v;
-    }
-  if (hf == 0) { s_ml[wave][0][ql] = mrun; s_ml[wave][1][ql] = lrun; }
+    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const int c = 32 * cb + 8 * e4 + 4 * hf;
+        const float4 v = {o[b][cb][4 * e4], o[b][cb][4 * e4 + 1], o[b][cb][4 * e4 + 2], o[b][cb][4 * e4 + 3]};
+        *(float4*)(ob + (wave * 32 + ql) * HD + ((c + 4 * ql) & (HD - 1))) = v;
+      }
+    if (hf == 0) { s_ml[wave][b][0][ql] = mrun[b]; s_ml[wave][b][1][ql] = lrun[b]; }
+  }
   __syncthreads();
   if (tid < 32 * NQB) {                                       // per query: the merged (max, sum) and each wave's weight
-    const int qb = tid >> 5, q = tid & 31, w0 = qb * WPB;
+    const int qb = tid >> 5, q = tid & 31;
     float mm = -INFINITY;
 #pragma unroll
-    for (int wv = 0; wv < WPB; ++wv) mm = fmaxf(mm, s_ml[w0 + wv][0][q]);
+    for (int wv = 0; wv < 4; ++wv) mm = fmaxf(mm, s_ml[wv][qb][0][q]);
     float lt = 0.f;
 #pragma unroll
-    for (int wv = 0; wv < WPB; ++wv) {
-      const float mw = s_ml[w0 + wv][0][q];
+    for (int wv = 0; wv < 4; ++wv) {
+      const float mw = s_ml[wv][qb][0][q];
       const float sc = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mw - mm) * c2);
-      s_sc[w0 + wv][q] = sc;
-      lt += s_ml[w0 + wv][1][q] * sc;
+      s_sc[wv][qb][q] = sc;
+      lt += s_ml[wv][qb][1][q] * sc;
     }
     s_mm[qb][0][q] = mm; s_mm[qb][1][q] = lt;
   }
   __syncthreads();
   for (int i = tid; i < mtot * 32; i += 256) {                 // padding rows are never read
-    const int c4 = i & 31, qq = i >> 5, qb = qq >> 5, q = qq & 31, w0 = qb * WPB;
+    const int c4 = i & 31, qq = i >> 5, qb = qq >> 5, q = qq & 31;
+    const float* ob = (const float*)kvt + qb * 4 * 32 * HD;
     float4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int wv = 0; wv < WPB; ++wv) {
-      const float sc = s_sc[w0 + wv][q];
-      const float4 v = *(const float4*)(ob + ((w0 + wv) * 32 + q) * HD + ((4 * c4 + 4 * q) & (HD - 1)));
+    for (int wv = 0; wv < 4; ++wv) {
+      const float sc = s_sc[wv][qb][q];
+      const float4 v = *(const float4*)(ob + (wv * 32 + q) * HD + ((4 * c4 + 4 * q) & (HD - 1)));
       acc.x += v.x * sc; acc.y += v.y * sc; acc.z += v.z * sc; acc.w += v.w * sc;
     }
     *(float4*)(a.opart + (pbase + qq) * HD + 4 * c4) = acc;
