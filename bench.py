@@ -101,6 +101,9 @@ def kernel_flops(cfg, fl, need_dxkv=True):
     return {
         "proj_qkv": p["q"] + p["k"] + p["v"], "proj_out": p["o"], "bwd_dout": p["o"], "bwd_dwo": p["o"],
         "bwd_dx": p["q"] + ((p["k"] + p["v"]) if need_dxkv else 0), "bwd_dw": p["q"] + p["k"] + p["v"],
+        # grouped-query shapes whose three weight gradients would leave a half-empty last round: dWq alone, dWk and dWv as
+        # halves of the contraction (+ a pass that adds the halves, bwd_dwkv_sum: no algorithmic FLOPs)
+        "bwd_dwq": p["q"], "bwd_dwkv": p["k"] + p["v"],
         "attn_fwd_bf16": fl["attn_fwd"],
         # the backward's five contractions (10 d flops per visible pair): S, dP, dQ are credited to the dQ
         # kernel, dK and dV to the dK/dV kernel; the S and dP that the latter recomputes are not counted

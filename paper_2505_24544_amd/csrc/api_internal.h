@@ -26,10 +26,11 @@ struct Dims {
   bool kv_f16;             // the key/value source states arrive as IEEE half
 };
 
-struct BwdWs { size_t dO, dQ, dK, dV, delta, attn, total; };
+struct BwdWs { size_t dO, dQ, dK, dV, delta, dwpart, attn, total; };   // dwpart: see split_kv_wgrad
 
 beagle_status check_desc(const beagle_xattn_desc* c, bool draft, Dims* out);
 BwdWs bwd_layout(const Dims& d);
+bool split_kv_wgrad(const Dims& d);
 AttnArgs attn_args(const Dims& d);
 // C[M,N] = A[M,K] B with B stored [K,N]; ... = A W^T with W stored [N,K]; ... = X^T Y with X [K,M], Y [K,N]
 GemmArgs gemm_nn(const void* A, const void* W, void* C, int64_t M, int64_t N, int64_t K);

@@ -58,6 +58,10 @@ void launch_gemm_f32(const GemmGroup& g, hipStream_t s, const char* name);
 void launch_gemm_bf16(const GemmGroup& g, hipStream_t s, const char* name);
 // whether the MFMA kernel covers the group (storage orders, k granularity, 32-bit operand extents)
 bool gemm_bf16_supported(const GemmGroup& g);
+// out[i] = a[i] + b[i] for up to two (a, b, out) triples of n floats each in one launch (n % 4 == 0); out is bf16 or
+// float.  The two halves of a GEMM whose contraction was split over two problems of a group.
+struct SumPairArgs { const float* a[2]; const float* b[2]; void* out[2]; int32_t count; };
+void launch_sum_pairs(const SumPairArgs& p, int64_t n, bool out_f32, hipStream_t s, const char* name);
 
 // ---- draft block around the attention (section 4.1, Eq. 1): streaming kernels ----
 constexpr int RMS_BWD_MAX_PARTS = 1024;      // workgroups (= column-partial rows) of the RMSNorm backward

@@ -444,4 +444,24 @@ void launch_gemm_bf16(const GemmGroup& grp, hipStream_t s, const char* name) {
   else launch_tiles<2, 2>(grp, s);
 }
 
+template <bool F32OUT>
+__global__ __launch_bounds__(256) void sum_pairs_kernel(SumPairArgs p, int64_t n4) {
+  const int t = blockIdx.y;
+  const float4* a = (const float4*)p.a[t];
+  const float4* b = (const float4*)p.b[t];
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    const float4 x = a[i], y = b[i];
+    const float4 v = {x.x + y.x, x.y + y.y, x.z + y.z, x.w + y.w};
+    if (F32OUT) ((float4*)p.out[t])[i] = v;
+    else ((uint2*)p.out[t])[i] = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+  }
+}
+void launch_sum_pairs(const SumPairArgs& p, int64_t n, bool out_f32, hipStream_t s, const char* name) {
+  ProfScope ps(name, s);
+  const int64_t n4 = n / 4;
+  const dim3 grid((unsigned)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048), p.count);
+  if (out_f32) hipLaunchKernelGGL(sum_pairs_kernel<true>, grid, dim3(256), 0, s, p, n4);
+  else hipLaunchKernelGGL(sum_pairs_kernel<false>, grid, dim3(256), 0, s, p, n4);
+}
+
 }  // namespace beagle

@@ -89,3 +89,28 @@ def test_fullsize_structure_properties_c5():
     assert torch.equal(y1, dev2["y"])
     for n in snap:
         assert torch.equal(snap[n], g2[n]), n
+
+
+def test_c3_key_value_weight_gradients_in_float_round_to_the_bf16_results():
+    """At c3 (H 32 / G 8) dWk and dWv are computed as two halves of the contraction plus a pass that adds them (their
+    tiles alone would leave half of the chip idle); that pass writes bf16 or, with BEAGLE_FLAG_WGRAD_F32, float.  Both
+    come from the same float sums: the float results, rounded, are the bf16 results bit for bit; dWq (one launch
+    either way) likewise.  The values themselves are checked against the oracle in test_fullsize_sampled_parity[c3]."""
+    cfg = synth.CONFIGS["c3"]
+    # the workspace says whether the split applies: 4 float partials of D x G d on top of the c2-like layout
+    extra = 4 * cfg.hidden * cfg.n_kv_heads * cfg.head_dim * 4
+    d3 = gh.desc_of(cfg, bx.BEAGLE_FLAG_NEED_DXKV)
+    d_mha = gh.desc_of(cfg.with_(n_kv_heads=cfg.n_q_heads), bx.BEAGLE_FLAG_NEED_DXKV)
+    base = lambda c: (2 * c.batch * c.seq_q * c.n_q_heads * c.head_dim * 2 + 2 * c.batch * c.seq_kv * c.n_kv_heads * c.head_dim * 2
+                      + 2 * c.batch * c.n_q_heads * c.seq_q * 4)
+    assert bx.beagle_xattn_workspace_bytes(d3, bx.BEAGLE_WS_BWD) >= base(cfg) + extra
+    assert bx.beagle_xattn_workspace_bytes(d_mha, bx.BEAGLE_WS_BWD) < base(cfg.with_(n_kv_heads=cfg.n_q_heads)) + extra
+    inp = synth.make_inputs(cfg)
+    dev, _ = gh.run_fwd_device(cfg, inp)
+    g16 = gh.run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV)
+    g32 = gh.run_bwd_device(cfg, inp, dev, flags=bx.BEAGLE_FLAG_NEED_DXKV | bx.BEAGLE_FLAG_WGRAD_F32)
+    for n in ("dwq", "dwk", "dwv", "dwo"):
+        assert g32[n].dtype == torch.float32 and g16[n].dtype == torch.bfloat16, n
+        assert torch.equal(g32[n].to(torch.bfloat16), g16[n]), n
+    for n in ("dxq", "dxkv"):
+        assert torch.equal(g32[n], g16[n]), n
