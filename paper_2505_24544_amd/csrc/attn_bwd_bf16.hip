@@ -183,16 +183,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   }
   if (jt < ntiles) tile_step(stage0, stage1, jt);
 
-  if (q_ok) {
-    bf16_t* dQg = (bf16_t*)a.dq + qrow;
+  // ---- dQ rows out, through LDS (the stages are free: the last step, or the prologue, ended with a barrier)
+  {
+    uint2 pq[16];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        uint2 v = {cvt_pk(dq[cb][4 * qd] * a.scale, dq[cb][4 * qd + 1] * a.scale),
-                   cvt_pk(dq[cb][4 * qd + 2] * a.scale, dq[cb][4 * qd + 3] * a.scale)};
-        *(uint2*)(dQg + 32 * cb + 8 * qd + 4 * hf) = v;
-      }
+      for (int qd = 0; qd < 4; ++qd)
+        pq[4 * cb + qd] = make_uint2(cvt_pk(dq[cb][4 * qd] * a.scale, dq[cb][4 * qd + 1] * a.scale),
+                                     cvt_pk(dq[cb][4 * qd + 2] * a.scale, dq[cb][4 * qd + 3] * a.scale));
+    store_rows_via_lds(stage0 + wave * 32 * HD, pq, lane, (bf16_t*)a.dq + ((sv.q0 + qw0) * a.H + h) * HD, (int64_t)a.H * HD,
+                       sv.S - qw0);
   }
 }
 
@@ -387,19 +388,21 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   }
   if (it < iters) tile_step(stage0, stat0, stage1, stat1);
 
-  if (j_ok) {
-    bf16_t* dKg = (bf16_t*)a.dk + kvrow;
-    bf16_t* dVg = (bf16_t*)a.dv + kvrow;
+  // ---- dK, dV rows out, through LDS (both stages are free: the last step ended with the requests landed and a barrier)
+  {
+    uint2 pk[16], pv[16];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
-        uint2 v = {cvt_pk(dk[cb][4 * qd] * a.scale, dk[cb][4 * qd + 1] * a.scale),
-                   cvt_pk(dk[cb][4 * qd + 2] * a.scale, dk[cb][4 * qd + 3] * a.scale)};
-        uint2 w = {cvt_pk(dv[cb][4 * qd], dv[cb][4 * qd + 1]), cvt_pk(dv[cb][4 * qd + 2], dv[cb][4 * qd + 3])};
-        *(uint2*)(dKg + 32 * cb + 8 * qd + 4 * hf) = v;
-        *(uint2*)(dVg + 32 * cb + 8 * qd + 4 * hf) = w;
+        pk[4 * cb + qd] = make_uint2(cvt_pk(dk[cb][4 * qd] * a.scale, dk[cb][4 * qd + 1] * a.scale),
+                                     cvt_pk(dk[cb][4 * qd + 2] * a.scale, dk[cb][4 * qd + 3] * a.scale));
+        pv[4 * cb + qd] = make_uint2(cvt_pk(dv[cb][4 * qd], dv[cb][4 * qd + 1]), cvt_pk(dv[cb][4 * qd + 2], dv[cb][4 * qd + 3]));
       }
+    const int64_t wrow = ((sv.kv0 + jw0) * a.G + g) * HD;               // row of the wave's first key
+    const int64_t kvs = (int64_t)a.G * HD;
+    store_rows_via_lds(stage0 + wave * 32 * HD, pk, lane, (bf16_t*)a.dk + wrow, kvs, sv.L - jw0);
+    store_rows_via_lds(stage1 + wave * 32 * HD, pv, lane, (bf16_t*)a.dv + wrow, kvs, sv.L - jw0);
   }
 }
 

@@ -190,18 +190,19 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   if (jt < ntiles) tile_step(stage0, stage1, jt);
 
   // ---- normalise and store: register e of block cb is channel 32 cb + 8 (e/4) + 4 hf + e%4
-  if (q_ok) {
+  // The rows go out through LDS (the stages are free: the last step, or the prologue, ended with a barrier).
+  {
     const float inv = l > 0.f ? 1.f / l : 0.f;
-    bf16_t* Og = (bf16_t*)a.o + ((sv.q0 + q) * a.H + h) * HD;
+    uint2 po[16];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
-        uint2 v = {cvt_pk(o[cb][4 * qd] * inv, o[cb][4 * qd + 1] * inv),
-                   cvt_pk(o[cb][4 * qd + 2] * inv, o[cb][4 * qd + 3] * inv)};
-        *(uint2*)(Og + 32 * cb + 8 * qd + 4 * hf) = v;
-      }
-    if (hf == 0)
+      for (int qd = 0; qd < 4; ++qd)
+        po[4 * cb + qd] = make_uint2(cvt_pk(o[cb][4 * qd] * inv, o[cb][4 * qd + 1] * inv),
+                                     cvt_pk(o[cb][4 * qd + 2] * inv, o[cb][4 * qd + 3] * inv));
+    store_rows_via_lds(stage0 + wave * 32 * HD, po, lane, (bf16_t*)a.o + ((sv.q0 + qw0) * a.H + h) * HD, (int64_t)a.H * HD,
+                       sv.S - qw0);
+    if (q_ok && hf == 0)
       a.lse[sv.lse0 + h * sv.lse_hs + q] = l > 0.f ? m * a.scale + __logf(l) : -INFINITY;
   }
 }

@@ -172,6 +172,26 @@ __device__ __forceinline__ void pipeline_reads_mfma_valu() {
   }
 }
 
+// A wave's 32 rows x 128 channels from the accumulator layout of a transposed 32x32 MFMA block row (lane = row
+// lane % 32; its registers are groups of four consecutive channels, piece 4 cb + qd = channels 32 cb + 8 qd + 4 hf ..)
+// out as whole rows of a bf16 tensor.  Stored from the registers, every instruction would write 16 bytes into each of
+// 32 rows; through 8 KB of LDS private to the wave instead: 8-byte pieces in, with 16-byte chunk c of row r at chunk
+// c ^ (r % 16) so that the rows of an instruction spread over the banks, then whole 256-byte rows out, four rows per
+// instruction.  Rows from rows_ok on are not stored.  The caller sees to it that nobody else uses the region.
+__device__ __forceinline__ void store_rows_via_lds(bf16_t* region, const uint2 (&pieces)[16], int lane, bf16_t* row0,
+                                                   int64_t stride, int rows_ok) {
+  const int ql = lane & 31, hf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) *(uint2*)(region + ql * HD + ((i ^ (ql & 15)) << 3) + 4 * hf) = pieces[i];
+  const int rr = lane >> 4, p = lane & 15;
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = 4 * it + rr, c = p ^ (r & 15);
+    const uint4 v = *(const uint4*)(region + r * HD + 8 * p);
+    if (r < rows_ok) *(uint4*)(row0 + r * stride + 8 * c) = v;
+  }
+}
+
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).  Memory loads complete in
 // order, so vmcnt(N) means "all but the N youngest loads have landed".
