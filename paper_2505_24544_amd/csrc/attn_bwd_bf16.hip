@@ -51,6 +51,7 @@ constexpr int TILE = BJ * HD;            // one K or V tile
 
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_bf16_kernel(AttnArgs a) {
   using namespace dqk;
+  args_at_hand(a);
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hf = lane >> 5, ql = lane & 31;
@@ -207,6 +208,7 @@ constexpr int TILE = BQ * HD;            // one Q or dO tile
 
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_bf16_kernel(AttnArgs a) {
   using namespace dkv;
+  args_at_hand(a);
   __shared__ __attribute__((aligned(1024))) bf16_t stage0[2 * TILE];
   __shared__ __attribute__((aligned(1024))) bf16_t stage1[2 * TILE];
   // [-log2(e) lse 64 | delta 64] of the stage's queries; waves 2 and 3 repeat the two requests into the second half,
