@@ -295,7 +295,10 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
   if (blockIdx.z == 1) { part = part_z1; y = y_z1; res = nullptr; }
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
-  // eight slices are loaded before any is added (one round trip to memory, not eight); the order of the sum is fixed
+  // eight slices (and the residual) are loaded before any is added (one round trip to memory, not eight or nine); the
+  // order of the sum is fixed
+  uint2 r = {0u, 0u};
+  if (res) r = *(const uint2*)(res + i);
   float4 s = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = 0; k0 < KS; k0 += 8) {
     float4 t[8];
@@ -306,7 +309,6 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
       if (k0 + k < KS) { s.x += t[k].x; s.y += t[k].y; s.z += t[k].z; s.w += t[k].w; }
   }
   if (res) {                                  // residual connection of Eq. 1
-    const uint2 r = *(const uint2*)(res + i);
     s.x += __uint_as_float(r.x << 16); s.y += __uint_as_float(r.x & 0xffff0000u);
     s.z += __uint_as_float(r.y << 16); s.w += __uint_as_float(r.y & 0xffff0000u);
   }
@@ -1205,10 +1207,23 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
   const int m = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   const float c2 = scale * LOG2E;
   const int64_t p0 = (int64_t)h * R * Mpad + m;              // range s sits at p0 + s * Mpad
-  // eight ranges are loaded at a time before any is used (one round trip to memory instead of eight); a batch
-  // that reaches past the last range repeats it, which changes neither the maximum nor (weight 0) the sums
+  // Eight ranges are loaded at a time before any is used, maxima, sums and outputs together: with up to eight ranges
+  // the whole merge is one round trip to memory (the kernel is nothing but round trips: a pass over the maxima first
+  // and the rest behind it cost a second one).  A batch that reaches past the last range repeats it, which changes
+  // neither the maximum nor (weight 0) the sums.
+  float ms[8], ls[8], ov[8];
+  auto load_batch = [&](int s0) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int64_t pb = p0 + (int64_t)min(s0 + k, R - 1) * Mpad;
+      ms[k] = mlpart[pb * 2]; ls[k] = mlpart[pb * 2 + 1]; ov[k] = opart[pb * HD + c];
+    }
+  };
+  load_batch(0);
   float mm = -INFINITY;
-  for (int s0 = 0; s0 < R; s0 += 8) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k) mm = fmaxf(mm, ms[k]);
+  for (int s0 = 8; s0 < R; s0 += 8) {                          // more than eight ranges: the remaining maxima first
     float t[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) t[k] = mlpart[(p0 + (int64_t)min(s0 + k, R - 1) * Mpad) * 2];
@@ -1217,12 +1232,7 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
   }
   float acc = 0.f, lt = 0.f;
   for (int s0 = 0; s0 < R; s0 += 8) {
-    float ms[8], ls[8], ov[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int64_t pb = p0 + (int64_t)min(s0 + k, R - 1) * Mpad;
-      ms[k] = mlpart[pb * 2]; ls[k] = mlpart[pb * 2 + 1]; ov[k] = opart[pb * HD + c];
-    }
+    if (s0 > 0) load_batch(s0);
 #pragma unroll
     for (int k = 0; k < 8; ++k) {                              // fixed order
       const float sc = (s0 + k < R && ms[k] > -INFINITY) ? __builtin_amdgcn_exp2f((ms[k] - mm) * c2) : 0.f;
