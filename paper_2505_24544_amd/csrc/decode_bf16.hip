@@ -292,18 +292,20 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
 __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ part, bf16_t* __restrict__ y,
                                                          int64_t MN, int KS, const float* __restrict__ part_z1,
                                                          bf16_t* __restrict__ y_z1, const bf16_t* __restrict__ res) {
+  // (all arguments at hand after one trip to the constant cache: placed where each is first used, they made three)
+  asm volatile("" :: "s"(part), "s"(y), "s"(MN), "s"(KS), "s"(part_z1), "s"(y_z1), "s"(res));
   if (blockIdx.z == 1) { part = part_z1; y = y_z1; res = nullptr; }
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
   // eight slices (and the residual) are loaded before any is added (one round trip to memory, not eight or nine); the
   // order of the sum is fixed
   uint2 r = {0u, 0u};
-  if (res) r = *(const uint2*)(res + i);
   float4 s = {0.f, 0.f, 0.f, 0.f};
   for (int k0 = 0; k0 < KS; k0 += 8) {
     float4 t[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) t[k] = *(const float4*)(part + (int64_t)min(k0 + k, KS - 1) * MN + i);
+    if (k0 == 0 && res) r = *(const uint2*)(res + i);       // behind the first batch's requests, ahead of their use
 #pragma unroll
     for (int k = 0; k < 8; ++k)
       if (k0 + k < KS) { s.x += t[k].x; s.y += t[k].y; s.z += t[k].z; s.w += t[k].w; }
@@ -319,6 +321,7 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict
 // m[i] = silu(sum_ks upart[ks][i]) * sum_ks wpart[ks][i]  -> bf16   (gate of the feed-forward layer, Eq. 1)
 __global__ __launch_bounds__(256) void sum_gate_kernel(const float* __restrict__ upart, const float* __restrict__ wpart,
                                                        bf16_t* __restrict__ m, int64_t MN, int KS) {
+  asm volatile("" :: "s"(upart), "s"(wpart), "s"(m), "s"(MN), "s"(KS));
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= MN) return;
   float4 u = {0.f, 0.f, 0.f, 0.f}, w = {0.f, 0.f, 0.f, 0.f};
@@ -385,6 +388,8 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void strip_gemm_kernel(const
                                                             int M, int N, int K, CombineArgs cb, int out_f32,
                                                             float norm_eps) {
   using namespace dec;
+  asm volatile("" :: "s"(a), "s"(Wt), "s"(Wt2), "s"(yout), "s"(yout2), "s"(res), "s"(M), "s"(N), "s"(K), "s"(out_f32), "s"(norm_eps),
+               "s"(cb.opart), "s"(cb.mlpart), "s"(cb.lse), "s"(cb.lse_stride), "s"(cb.Mpad), "s"(cb.R), "s"(cb.scale));
   constexpr int ROWS = ROWS16 ? 16 : 8;             // activation rows kept per macro-step
   constexpr int ST_CH = ROWS16 ? 2 : 4;             // macro-steps per activation chunk
   constexpr int LPS = ROWS / 4;                     // loads per macro-step (1 KB = 4 rows each)
@@ -700,7 +705,12 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
   const int h = blockIdx.x, r = blockIdx.y;
   const int m0 = 32 * NQB * blockIdx.z;                      // first query of the workgroup
   const int mtot = min(32 * NQB, a.M - m0);                  // its queries
-  const int g = h / (a.H / a.G);
+  // every field at hand after one trip to the constant cache (the compiler otherwise fetches them where they are first
+  // used, two dependent trips before the first K/V request); no division for the common one head per group
+  asm volatile("" :: "s"(a.qpart), "s"(a.KSq), "s"(a.kc), "s"(a.vc), "s"(a.opart), "s"(a.mlpart), "s"(a.M), "s"(a.Mpad), "s"(a.L),
+               "s"(a.H), "s"(a.G), "s"(a.R), "s"(a.range), "s"(a.scale), "s"(a.tree), "s"(a.n_true), "s"(a.tree_words),
+               "s"(a.rope_tab));
+  const int g = a.H == a.G ? h : h / (a.H / a.G);
   const int HDt = a.H * HD;
   const int j_begin = r * a.range, j_end = min(j_begin + a.range, a.L);
   const int nsteps = j_end > j_begin ? (j_end - j_begin + KSTEP - 1) / KSTEP : 0;
@@ -1204,6 +1214,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
 __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
                                                              bf16_t* __restrict__ o, float* __restrict__ lse,
                                                              int lse_stride, int Mpad, int H, int R, float scale) {
+  asm volatile("" :: "s"(opart), "s"(mlpart), "s"(o), "s"(lse), "s"(lse_stride), "s"(Mpad), "s"(H), "s"(R), "s"(scale));
   const int m = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   const float c2 = scale * LOG2E;
   const int64_t p0 = (int64_t)h * R * Mpad + m;              // range s sits at p0 + s * Mpad
