@@ -74,7 +74,8 @@ typedef unsigned int xload_t __attribute__((ext_vector_type(4)));
 template <bool COMBINE>
 __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
                                                              float* __restrict__ part, int M, int N, int K, CombineArgs cb,
-                                                             const bf16_t* __restrict__ W_z1, float* __restrict__ part_z1) {
+                                                             const bf16_t* __restrict__ W_z1, float* __restrict__ part_z1,
+                                                             int x_chunked) {
   using namespace dec;
   if (blockIdx.z == 1) { W = W_z1; part = part_z1; }        // second weight matrix of the launch (same x)
   // The 64 KB tile as four quarters of 128 k-rows, one LDS variable each: requests land in the order they were
@@ -112,7 +113,10 @@ __global__ __launch_bounds__(256, 2) void skinny_gemm_kernel(const bf16_t* __res
         for (int st = 0; st < 8; ++st) {
           const int m = 32 * mb + (lane & 31), k = k0 + (st >> 1) * SG_KQ + wave * 32 + (st & 1) * 16 + 8 * hf;
           union { xload_t u; bf16x8_t v; } t;
-          t.u = __builtin_amdgcn_raw_buffer_load_b128(xrs, (m < M && k < K) ? (m * K + k) * 2 : (int)0x80000000, 0, 0);
+          // x_chunked: x is stored [K / 8][M][8] -- the 32 rows of a fragment are 512 contiguous bytes, where the row-major
+          // layout has 32 bytes of each of 32 rows (the range merge writes its output that way for this kernel)
+          const int off = x_chunked ? ((k >> 3) * M + m) * 16 : (m * K + k) * 2;
+          t.u = __builtin_amdgcn_raw_buffer_load_b128(xrs, (m < M && k < K) ? off : (int)0x80000000, 0, 0);
           xf[mb][st] = t.v;
         }
       }
@@ -1213,8 +1217,9 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecAttnArgs a) {
 // ---- (C) merge the key ranges (fixed order): o (bf16) and LSE ------------------
 __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
                                                              bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                             int lse_stride, int Mpad, int H, int R, float scale) {
-  asm volatile("" :: "s"(opart), "s"(mlpart), "s"(o), "s"(lse), "s"(lse_stride), "s"(Mpad), "s"(H), "s"(R), "s"(scale));
+                                                             int lse_stride, int Mpad, int H, int R, float scale,
+                                                             int chunked_rows) {
+  asm volatile("" :: "s"(opart), "s"(mlpart), "s"(o), "s"(lse), "s"(lse_stride), "s"(Mpad), "s"(H), "s"(R), "s"(scale), "s"(chunked_rows));
   const int m = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
   const float c2 = scale * LOG2E;
   const int64_t p0 = (int64_t)h * R * Mpad + m;              // range s sits at p0 + s * Mpad
@@ -1251,7 +1256,9 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(const float* __rest
       lt += ls[k] * sc;
     }
   }
-  o[((int64_t)m * H + h) * HD + c] = f32_to_bf16(lt > 0.f ? acc / lt : 0.f);
+  // chunked_rows (the split-k projection reads the merged rows): o as [H d / 8][rows][8], rows = chunked_rows; else [rows][H d]
+  const int64_t oi = chunked_rows ? ((int64_t)((h * HD + c) >> 3) * chunked_rows + m) * 8 + (c & 7) : ((int64_t)m * H + h) * HD + c;
+  o[oi] = f32_to_bf16(lt > 0.f ? acc / lt : 0.f);
   if (c == 0) lse[(int64_t)h * lse_stride + m] = lt > 0.f ? mm * scale + logf(lt) : -INFINITY;
 }
 
@@ -1384,7 +1391,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
     } else {
       ProfScope ps("draft_proj_q", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(HDt / SG_N, w.KSq), dim3(256), 0, s, x, (const bf16_t*)a.wq, qpart,
-                         Mp, HDt, a.D, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
+                         Mp, HDt, a.D, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr, 0);
     }
     {
       DecAttnArgs t;
@@ -1412,7 +1419,7 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
         {
           ProfScope ps("draft_combine", s);
           hipLaunchKernelGGL(decode_combine_kernel, dim3(Mp, a.H), dim3(128), 0, s, opart, mlpart, o, a.lse + m0, a.M,
-                             w.Mpad, a.H, w.R, a.scale);
+                             w.Mpad, a.H, w.R, a.scale, 0);
         }
         ProfScope ps("draft_proj_out", s);
         launch_strip_gemm(o, (const bf16_t*)a.wo_pk, nullptr, yo, nullptr, yr, Mp, a.D, HDt, nullptr, false, -1.f, s);
@@ -1426,16 +1433,16 @@ void launch_decode_bf16(const DecodeArgs& a, hipStream_t s) {
       cb.scale = a.scale;
       ProfScope ps("draft_proj_out", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<true>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)nullptr,
-                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, cb, (const bf16_t*)nullptr, (float*)nullptr);
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, cb, (const bf16_t*)nullptr, (float*)nullptr, 0);
     } else {
       {
         ProfScope ps("draft_combine", s);
         hipLaunchKernelGGL(decode_combine_kernel, dim3(Mp, a.H), dim3(128), 0, s, opart, mlpart, o, a.lse + m0, a.M,
-                           w.Mpad, a.H, w.R, a.scale);
+                           w.Mpad, a.H, w.R, a.scale, Mp);
       }
       ProfScope ps("draft_proj_out", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(a.D / SG_N, w.KSo), dim3(256), 0, s, (const bf16_t*)o,
-                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
+                         (const bf16_t*)a.wo, ypart, Mp, a.D, HDt, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr, 1);
     }
     {
       ProfScope ps("draft_sum_out", s);
@@ -1465,7 +1472,7 @@ void launch_kv_append_bf16(const void* x, const void* wk, const void* wv, void* 
   {
     ProfScope ps("kv_append_proj", s);
     hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(N / SG_N, KS, 2), dim3(256), 0, s, (const bf16_t*)x,
-                       (const bf16_t*)wk, kpart, n, N, K, CombineArgs{}, (const bf16_t*)wv, vpart);
+                       (const bf16_t*)wk, kpart, n, N, K, CombineArgs{}, (const bf16_t*)wv, vpart, 0);
   }
   {
     ProfScope ps("kv_append_sum", s);
@@ -1515,7 +1522,7 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
     {
       ProfScope ps("draft_mlp_gate_up", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(F / SG_N, w.KSg, 2), dim3(256), 0, s, zr, (const bf16_t*)w_gate,
-                         upart, Mp, F, D, CombineArgs{}, (const bf16_t*)w_up, wpart);
+                         upart, Mp, F, D, CombineArgs{}, (const bf16_t*)w_up, wpart, 0);
     }
     {
       ProfScope ps("draft_mlp_gate", s);
@@ -1525,7 +1532,7 @@ void launch_block_mlp_bf16(const void* z, const void* w_gate, const void* w_up, 
     {
       ProfScope ps("draft_mlp_down", s);
       hipLaunchKernelGGL(skinny_gemm_kernel<false>, dim3(D / SG_N, w.KSd), dim3(256), 0, s, (const bf16_t*)mbuf,
-                         (const bf16_t*)w_down, dpart, Mp, D, F, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr);
+                         (const bf16_t*)w_down, dpart, Mp, D, F, CombineArgs{}, (const bf16_t*)nullptr, (float*)nullptr, 0);
     }
     {
       ProfScope ps("draft_mlp_sum", s);
