@@ -60,6 +60,20 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   const __amdgpu_buffer_rsrc_t krs = rows_rsrc((const bf16_t*)a.k + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
   const __amdgpu_buffer_rsrc_t vrs = rows_rsrc((const bf16_t*)a.v + (sv.kv0 * a.G + g) * HD, sv.L, kvs);
 
+  // The first K/V tile and this lane's Q row are requested before the mask's arithmetic (several integer divisions):
+  // the trip to memory and the arithmetic run side by side.  Tile 0 exists unless no query of the workgroup sees any
+  // key; then its rows are fetched for nothing (they are inside the tensors either way).
+  auto fetch = [&](bf16_t* st, int jt) {
+    load_rows<BJ>(st, krs, kvs, jt * BJ, tid);
+    load_rows<BJ>(st + TILE, vrs, kvs, jt * BJ, tid);
+  };
+  fetch(stage0, 0);
+  // Q fragments: B operand, lane holds Q[q][16*s + 8*hf .. +7]
+  bf16x8_t qf[HD / 16];
+#pragma unroll
+  for (int s = 0; s < HD / 16; ++s) qf[s] = *(const bf16x8_t*)(Qg + 16 * s + 8 * hf);
+  __builtin_amdgcn_sched_barrier(0);
+
   const MaskParams mk = sample_mask(a, b);
   const int lim = q_ok ? row_limit(q, mk) : 0;                     // keys visible to this lane's query
   const int q_last = min(q0 + BQ, sv.S) - 1;
@@ -69,11 +83,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   const int wave_lo = qw0 < sv.S ? row_limit(qw0, mk) : 0;      // smallest
   const int ntiles = (wg_lim + BJ - 1) / BJ;
 
-  // Q fragments: B operand, lane holds Q[q][16*s + 8*hf .. +7]
-  bf16x8_t qf[HD / 16];
-#pragma unroll
-  for (int s = 0; s < HD / 16; ++s) qf[s] = *(const bf16x8_t*)(Qg + 16 * s + 8 * hf);
-
   f32x16_t o[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -82,11 +91,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
   float m = -INFINITY, l = 0.f;
   const float c2 = a.scale * LOG2E;               // scores are kept raw; exp2((s - m) * c2)
   const FragOffs fo = make_frag_offs(lane);
-
-  auto fetch = [&](bf16_t* st, int jt) {
-    load_rows<BJ>(st, krs, kvs, jt * BJ, tid);
-    load_rows<BJ>(st + TILE, vrs, kvs, jt * BJ, tid);
-  };
 
   auto tile_step = [&](const bf16_t* cur, bf16_t* nxt, int jt) {
     const int j0 = jt * BJ;
@@ -177,10 +181,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_bf16_kernel(AttnArgs a) {
     __syncthreads();
   };
 
-  if (ntiles > 0) {
-    fetch(stage0, 0);
-    wait_vmem();
-  }
+  wait_vmem();
   __syncthreads();
   int jt = 0;
 #pragma unroll 1
